@@ -1,0 +1,8 @@
+"""Seeded synthetic inputs shared by the CPU oracle's tests and the GPU path's tests.
+
+This package only draws random vectors; it contains none of the method's
+arithmetic (no quantiser, no lookup table, no distance).
+"""
+from .gmm import GaussianMixture, CONFIGS, WorkloadConfig, get_config
+
+__all__ = ["GaussianMixture", "CONFIGS", "WorkloadConfig", "get_config"]
