@@ -1,0 +1,200 @@
+/*
+ * etf.h -- C ABI of the E-Tree / E-Forest asymmetric-distance library for MI355X (gfx950).
+ *
+ * The library computes, for a batch of uncompressed float32 queries, the
+ * asymmetric distances (ADC) to a database of product-quantised vectors
+ * (M one-byte codes per vector, K <= 256 codewords per group), either flat
+ * (paper: Related Work, Eq. 1 and the paragraph after it: "M table lookups and
+ * M-1 additions") or through an Encoding Tree / Encoding Forest (paper:
+ * sections "Encoding Tree", "Constructing Encoding Tree", "Distance Computation
+ * with Hierarchical Memory Structure", "Encoding Forests"), in which the partial
+ * sum of a shared code prefix is computed once.
+ *
+ * Conventions
+ *   - Every function returns ETF_OK (0) or a negative ETF_E* code; nothing
+ *     throws or aborts across this boundary.  etf_last_error() gives a text for
+ *     the most recent failure on a context.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device
+ *     memory of the context's GPU (for example torch tensor data_ptr()).  The
+ *     caller owns every buffer.  The library keeps no reference to a buffer
+ *     after a call returns, with one exception: the index buffer given to
+ *     etf_index_upload() must stay alive and unmodified until etf_destroy() or
+ *     the next etf_index_upload().
+ *   - Device entry points enqueue their work on the context's stream and return
+ *     without synchronising; results are ready when the stream is.  They
+ *     validate arguments on the host first and launch nothing on error.
+ *   - Distances are squared Euclidean distances.  Codes are 0-based bytes.
+ *     Arrays are row-major, dense, in the index order written in the comments.
+ *   - Limits: 1 <= M <= ETF_MAX_M, d % M == 0, 1 <= K <= 256, 1 <= N < 2^31,
+ *     1 <= T <= M, 1 <= k <= ETF_MAX_TOPK.
+ */
+#ifndef ETF_H
+#define ETF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ETF_MAX_M 16       /* code chunks per vector */
+#define ETF_MAX_TOPK 1024  /* largest k of etf_search */
+
+enum {
+    ETF_OK = 0,
+    ETF_EINVAL = -1, /* bad argument (null pointer, shape, range)             */
+    ETF_ESTATE = -2, /* call order: e.g. search before index upload           */
+    ETF_ENOMEM = -3, /* host allocation failed, or caller's buffer too small  */
+    ETF_EHIP = -4,   /* a HIP runtime call failed                             */
+    ETF_ENOGPU = -5  /* device entry point called on a host-only context      */
+};
+
+/* How distances are evaluated (results agree up to float32 summation order). */
+enum {
+    ETF_MODE_FLAT = 0,   /* every encoding: M lookups (the paper's ADC baseline)            */
+    ETF_MODE_TREE = 1,   /* single Encoding Tree; the index must have been built with T = 1 */
+    ETF_MODE_FOREST = 2  /* Encoding Forest: T per-tree partial results summed per encoding */
+};
+
+typedef struct etf_ctx etf_ctx; /* opaque */
+
+/* Tree statistics (paper: "Statistics of Encoding Tree").  Levels are 1-based in
+ * the text and stored 0-based here: entry [t][l] is level l+1 of tree t. */
+typedef struct etf_stats {
+    int32_t M, K, T;
+    int32_t chunk_begin[ETF_MAX_M + 1];    /* tree t covers chunks [chunk_begin[t], chunk_begin[t+1]) */
+    int64_t N;                             /* database vectors                                          */
+    int64_t n_distinct;                    /* distinct full encodings                                   */
+    int64_t max_dup;                       /* most vectors sharing one full encoding                    */
+    int64_t nI[ETF_MAX_M][ETF_MAX_M];      /* internal nodes per level                                  */
+    int64_t nL[ETF_MAX_M][ETF_MAX_M];      /* leaves whose own chunk is at that level                   */
+    int64_t L1[ETF_MAX_M];                 /* internal nodes per tree                                   */
+    int64_t L2[ETF_MAX_M];                 /* leaves per tree (= distinct sub-encodings)                */
+    int64_t sumP[ETF_MAX_M];               /* total postfix length over the leaves                      */
+    int64_t lookups[ETF_MAX_M];            /* table lookups of one traversal: L1 + L2 + sumP            */
+    int64_t paper_bytes[ETF_MAX_M];        /* 4N + 2(L1+L2) + sumP (Hierarchical Memory Structure)      */
+    int64_t device_bytes;                  /* size of the level-ordered device image                    */
+} etf_stats;
+
+/* ---- context ------------------------------------------------------------ */
+
+/* Creates a context.  device >= 0 selects the HIP device that all device entry
+ * points of this context use; device < 0 makes a host-only context (PQ
+ * training, encoding, index build and statistics work; device entry points
+ * return ETF_ENOGPU).  hip_stream is a hipStream_t (NULL = the default stream);
+ * it is borrowed, not owned. */
+int etf_create(etf_ctx **out, int device, void *hip_stream);
+void etf_destroy(etf_ctx *ctx);
+int etf_set_stream(etf_ctx *ctx, void *hip_stream);
+const char *etf_strerror(int code);
+const char *etf_last_error(const etf_ctx *ctx);
+
+/* Tunables, by name.  Known names:
+ *   "ws_cap_bytes"    upper bound the library aims at for the workspace (it
+ *                     processes queries in batches to stay below it)
+ *   "force_fallback"  1: etf_search answers every query with the exact
+ *                     whole-database selection kernel (testing)
+ *   "sample_min" / "sample_div"   threshold-sample size = max(sample_min, n/sample_div)
+ *   "cand_cap"        per-query candidate capacity (0 = derived from k)
+ * Returns ETF_EINVAL for an unknown name or a value out of range. */
+int etf_set_option(etf_ctx *ctx, const char *name, int64_t value);
+
+/* ---- product quantiser, host side (paper: Introduction, Related Work) ---- */
+
+/* Lloyd k-means per dimension group on x [n][d] (host): K codewords of d/M
+ * dimensions per group, `iters` iterations, initial codewords drawn from the
+ * training rows with a generator seeded by `seed`.  Replaces any codebooks and
+ * any index held by the context. */
+int etf_pq_train(etf_ctx *ctx, const float *x, int64_t n, int d, int M, int K, int iters, uint64_t seed);
+/* Installs codebooks cb [M][K][d/M] (host) trained elsewhere. */
+int etf_pq_set_codebooks(etf_ctx *ctx, const float *cb, int d, int M, int K);
+/* Copies the codebooks to cb_out [M][K][d/M] (host). */
+int etf_pq_get_codebooks(const etf_ctx *ctx, float *cb_out);
+/* codes_out[i][m] = index of the codeword of group m nearest to x[i]'s group-m
+ * sub-vector (lowest index on ties).  x [n][d] host, codes_out [n][M] host. */
+int etf_pq_encode(const etf_ctx *ctx, const float *x, int64_t n, uint8_t *codes_out);
+
+/* ---- index build, host side (paper: Algorithm 1, Hierarchical Memory Structure) ---- */
+
+/* Sorts the encodings lexicographically and builds T encoding trees.
+ *   codes        [N][M] host, every byte < K
+ *   ids          [N] host, non-negative, or NULL for ids 0..N-1.  Reported by etf_search.
+ *   T            number of trees (1 = Encoding Tree, >1 = Encoding Forest)
+ *   chunk_begin  [T+1] host, strictly increasing from 0 to M; NULL = equal
+ *                contiguous groups (T must divide M)
+ * In each tree a node below which a single distinct (sub-)encoding remains is a
+ * leaf carrying the rest of that encoding as postfix; vectors with equal
+ * encodings share one leaf.  Requires codebooks (for M and K). */
+int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, const int32_t *ids, int T,
+                    const int32_t *chunk_begin);
+int etf_index_stats(const etf_ctx *ctx, etf_stats *out);
+/* Bytes of device memory the built index needs. */
+int64_t etf_index_device_bytes(const etf_ctx *ctx);
+/* Copies the index (and the codebooks) into dev_buf (device, 256-byte aligned,
+ * at least etf_index_device_bytes()).  Synchronises the stream before returning. */
+int etf_index_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes);
+
+/* Where each array of the device image starts (byte offsets into the buffer of
+ * etf_index_upload / etf_index_export; -1 = array not present).  Entry [t][l] is
+ * level l+1 of tree t.
+ *   codebooks   float [M][K][d/M]
+ *   codes       u8  [N][M]       encodings in input order (flat mode)
+ *   ids_in      i32 [N]          ids in input order
+ *   ids_sorted  i32 [N]          ids ordered by (encoding, id)
+ *   ebegin      u32 [n_distinct+1]  range of ids_sorted held by every distinct encoding
+ *   enc_of_pos  u32 [N]          distinct-encoding number of the n-th input vector
+ *   ecodes      u8  [n_distinct][M]  distinct encodings in lexicographic order
+ *   sample_enc  u32 [n_sample_enc]   distinct encodings used to bound the k-th distance
+ *   sample_pos  u32 [n_sample_pos]   input positions used for the same purpose in flat mode
+ *   leaf_of[t]  u32 [n_distinct] leaf (row of tree t's result table) of every distinct
+ *                                encoding; absent when T = 1 (the identity)
+ *   icode / iparent [t][l]   internal nodes of a level in lexicographic (= breadth-first)
+ *                            order: chunk value (u8) and index of the parent in level l (u32;
+ *                            0xFFFFFFFF at level 1)
+ *   lcodes / lparent / lrow [t][l]   leaves whose own chunk is at this level: records of
+ *                            lstride bytes (own chunk, postfix, zero padding), parent index
+ *                            in the internal level above, and result-table row            */
+typedef struct etf_layout {
+    int64_t total;
+    int64_t codebooks, codes, ids_in, ids_sorted, ebegin, enc_of_pos, ecodes, sample_enc, sample_pos;
+    int64_t n_sample_enc, n_sample_pos;
+    int64_t leaf_of[ETF_MAX_M];
+    int64_t icode[ETF_MAX_M][ETF_MAX_M], iparent[ETF_MAX_M][ETF_MAX_M];
+    int64_t lcodes[ETF_MAX_M][ETF_MAX_M], lparent[ETF_MAX_M][ETF_MAX_M], lrow[ETF_MAX_M][ETF_MAX_M];
+    int32_t lstride[ETF_MAX_M][ETF_MAX_M];
+} etf_layout;
+int etf_index_layout(const etf_ctx *ctx, etf_layout *out);
+/* Writes the device image to host memory (at least etf_index_device_bytes()): the
+ * same bytes etf_index_upload copies to the GPU.  For saving or inspecting an index. */
+int etf_index_export(const etf_ctx *ctx, void *host_buf, int64_t bytes);
+
+/* ---- device side -------------------------------------------------------- */
+
+/* Workspace (device bytes) that etf_adc / etf_search need for Q queries in the
+ * given mode (k is ignored by etf_adc: pass 0).  Negative = error code. */
+int64_t etf_workspace_bytes(const etf_ctx *ctx, int64_t Q, int k, int mode);
+
+/* Precomputed distance tables (paper: Eq. 1, first term, on each group's own
+ * dimensions): lut[q][m][c] = || queries[q] group m  -  codeword c of group m ||^2.
+ *   queries [Q][d] device, lut [Q][M][K] device. */
+int etf_lut_build(etf_ctx *ctx, const float *queries, int64_t Q, float *lut);
+
+/* All-pairs ADC: dist[q][n] = distance between query q and the n-th vector given
+ * to etf_index_build (input order, not id value).
+ *   queries [Q][d] device, dist [Q][N] device, ws device workspace of ws_bytes. */
+int etf_adc(etf_ctx *ctx, const float *queries, int64_t Q, int mode, float *dist, void *ws, int64_t ws_bytes);
+
+/* k nearest encodings per query: out_ids [Q][k] (the ids given at build),
+ * out_dist [Q][k], ascending by (distance, id).  k <= N. */
+int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, int mode, int32_t *out_ids,
+               float *out_dist, void *ws, int64_t ws_bytes);
+
+/* Number of queries of the most recent etf_search on this context that were
+ * answered by the exact whole-database selection kernel instead of the
+ * threshold-filtered path (diagnostic).  Synchronises the stream. */
+int etf_last_fallback_count(etf_ctx *ctx, int64_t *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ETF_H */

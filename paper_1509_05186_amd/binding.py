@@ -1,0 +1,289 @@
+"""ctypes binding of include/etf.h.  Method names are the C entry points without the prefix."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+ETF_MAX_M = 16
+ETF_MAX_TOPK = 1024
+ETF_MODE_FLAT, ETF_MODE_TREE, ETF_MODE_FOREST = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "lib", "libetf.so")
+_lib = None
+
+EXPORTS = [
+    "etf_create", "etf_destroy", "etf_set_stream", "etf_strerror", "etf_last_error", "etf_set_option",
+    "etf_pq_train", "etf_pq_set_codebooks", "etf_pq_get_codebooks", "etf_pq_encode",
+    "etf_index_build", "etf_index_stats", "etf_index_device_bytes", "etf_index_upload",
+    "etf_index_layout", "etf_index_export",
+    "etf_workspace_bytes", "etf_lut_build", "etf_adc", "etf_search", "etf_last_fallback_count",
+]
+
+
+class EtfStats(ctypes.Structure):
+    _fields_ = [
+        ("M", ctypes.c_int32), ("K", ctypes.c_int32), ("T", ctypes.c_int32),
+        ("chunk_begin", ctypes.c_int32 * (ETF_MAX_M + 1)),
+        ("N", ctypes.c_int64), ("n_distinct", ctypes.c_int64), ("max_dup", ctypes.c_int64),
+        ("nI", (ctypes.c_int64 * ETF_MAX_M) * ETF_MAX_M),
+        ("nL", (ctypes.c_int64 * ETF_MAX_M) * ETF_MAX_M),
+        ("L1", ctypes.c_int64 * ETF_MAX_M), ("L2", ctypes.c_int64 * ETF_MAX_M),
+        ("sumP", ctypes.c_int64 * ETF_MAX_M), ("lookups", ctypes.c_int64 * ETF_MAX_M),
+        ("paper_bytes", ctypes.c_int64 * ETF_MAX_M),
+        ("device_bytes", ctypes.c_int64),
+    ]
+
+    def as_dict(self) -> dict:
+        T = self.T
+        cb = [int(self.chunk_begin[t]) for t in range(T + 1)]
+        trees = []
+        for t in range(T):
+            D = cb[t + 1] - cb[t]
+            trees.append({
+                "chunks": (cb[t], cb[t + 1]), "D": D,
+                "nI": [int(self.nI[t][l]) for l in range(D)], "nL": [int(self.nL[t][l]) for l in range(D)],
+                "L1": int(self.L1[t]), "L2": int(self.L2[t]), "sumP": int(self.sumP[t]),
+                "lookups": int(self.lookups[t]), "paper_bytes": int(self.paper_bytes[t]),
+            })
+        return {"M": self.M, "K": self.K, "T": T, "N": int(self.N), "n_distinct": int(self.n_distinct),
+                "max_dup": int(self.max_dup), "device_bytes": int(self.device_bytes), "trees": trees}
+
+
+_Grid64 = (ctypes.c_int64 * ETF_MAX_M) * ETF_MAX_M
+_Grid32 = (ctypes.c_int32 * ETF_MAX_M) * ETF_MAX_M
+
+
+class EtfLayout(ctypes.Structure):
+    _fields_ = [
+        ("total", ctypes.c_int64),
+        ("codebooks", ctypes.c_int64), ("codes", ctypes.c_int64), ("ids_in", ctypes.c_int64),
+        ("ids_sorted", ctypes.c_int64), ("ebegin", ctypes.c_int64), ("enc_of_pos", ctypes.c_int64),
+        ("ecodes", ctypes.c_int64), ("sample_enc", ctypes.c_int64), ("sample_pos", ctypes.c_int64),
+        ("n_sample_enc", ctypes.c_int64), ("n_sample_pos", ctypes.c_int64),
+        ("leaf_of", ctypes.c_int64 * ETF_MAX_M),
+        ("icode", _Grid64), ("iparent", _Grid64), ("lcodes", _Grid64), ("lparent", _Grid64), ("lrow", _Grid64),
+        ("lstride", _Grid32),
+    ]
+
+
+class EtfError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__("etf error %d: %s" % (code, message))
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads lib/libetf.so.  Raises if it has not been built: there is no other implementation."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("HIP library %s is missing: run `python -m paper_1509_05186_amd.build`" % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    P, I, L = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    sig = {
+        "etf_create": (I, [ctypes.POINTER(P), I, P]),
+        "etf_destroy": (None, [P]),
+        "etf_set_stream": (I, [P, P]),
+        "etf_strerror": (ctypes.c_char_p, [I]),
+        "etf_last_error": (ctypes.c_char_p, [P]),
+        "etf_set_option": (I, [P, ctypes.c_char_p, L]),
+        "etf_pq_train": (I, [P, P, L, I, I, I, I, ctypes.c_uint64]),
+        "etf_pq_set_codebooks": (I, [P, P, I, I, I]),
+        "etf_pq_get_codebooks": (I, [P, P]),
+        "etf_pq_encode": (I, [P, P, L, P]),
+        "etf_index_build": (I, [P, P, L, P, I, P]),
+        "etf_index_stats": (I, [P, ctypes.POINTER(EtfStats)]),
+        "etf_index_device_bytes": (L, [P]),
+        "etf_index_upload": (I, [P, P, L]),
+        "etf_index_layout": (I, [P, ctypes.POINTER(EtfLayout)]),
+        "etf_index_export": (I, [P, P, L]),
+        "etf_workspace_bytes": (L, [P, L, I, I]),
+        "etf_lut_build": (I, [P, P, L, P]),
+        "etf_adc": (I, [P, P, L, I, P, P, L]),
+        "etf_search": (I, [P, P, L, I, I, P, P, P, L]),
+        "etf_last_fallback_count": (I, [P, ctypes.POINTER(L)]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def _host(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dev(t) -> int:
+    """Device pointer of a torch tensor (contiguous, on the GPU)."""
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous GPU tensor")
+    return t.data_ptr()
+
+
+class Context:
+    """One etf_ctx.  device=None makes a host-only context (train / encode / build / stats)."""
+
+    def __init__(self, device: Optional[int] = 0, stream: Optional[int] = None):
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        rc = self._lib.etf_create(ctypes.byref(self._h), -1 if device is None else int(device), stream)
+        if rc != 0:
+            raise EtfError(rc, self._lib.etf_strerror(rc).decode())
+        self._keep = {}     # device buffers the library refers to (index image)
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            self._lib.etf_destroy(self._h)
+            self._h = ctypes.c_void_p()
+            self._keep = {}
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _ck(self, rc: int):
+        if rc < 0:
+            raise EtfError(int(rc), self._lib.etf_last_error(self._h).decode())
+        return rc
+
+    # ---- context
+    def set_stream(self, stream: Optional[int]):
+        self._ck(self._lib.etf_set_stream(self._h, stream))
+
+    def set_option(self, name: str, value: int):
+        self._ck(self._lib.etf_set_option(self._h, name.encode(), int(value)))
+
+    # ---- product quantiser (host)
+    def pq_train(self, x: np.ndarray, M: int, K: int, iters: int, seed: int):
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        self._ck(self._lib.etf_pq_train(self._h, _host(x), x.shape[0], x.shape[1], M, K, iters, seed))
+        self._shape = (x.shape[1], M, K)
+
+    def pq_set_codebooks(self, cb: np.ndarray):
+        cb = np.ascontiguousarray(cb, dtype=np.float32)
+        M, K, ds = cb.shape
+        self._ck(self._lib.etf_pq_set_codebooks(self._h, _host(cb), M * ds, M, K))
+        self._shape = (M * ds, M, K)
+
+    def pq_get_codebooks(self) -> np.ndarray:
+        d, M, K = self._shape
+        cb = np.zeros((M, K, d // M), dtype=np.float32)
+        self._ck(self._lib.etf_pq_get_codebooks(self._h, _host(cb)))
+        return cb
+
+    def pq_encode(self, x: np.ndarray) -> np.ndarray:
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        d, M, K = self._shape
+        if x.ndim != 2 or x.shape[1] != d:
+            raise ValueError("expected [n][%d] vectors" % d)
+        codes = np.zeros((x.shape[0], M), dtype=np.uint8)
+        self._ck(self._lib.etf_pq_encode(self._h, _host(x), x.shape[0], _host(codes)))
+        return codes
+
+    # ---- index (host)
+    def index_build(self, codes: np.ndarray, ids: Optional[np.ndarray] = None, T: int = 1,
+                    chunk_begin: Optional[Sequence[int]] = None):
+        codes = np.ascontiguousarray(codes, dtype=np.uint8)
+        d, M, K = self._shape
+        if codes.ndim != 2 or codes.shape[1] != M:
+            raise ValueError("expected [N][%d] codes" % M)
+        ids_a = None if ids is None else np.ascontiguousarray(ids, dtype=np.int32)
+        cb = None if chunk_begin is None else np.ascontiguousarray(chunk_begin, dtype=np.int32)
+        if cb is not None and cb.shape != (T + 1,):
+            raise ValueError("chunk_begin must have T+1 entries")
+        self._ck(self._lib.etf_index_build(self._h, _host(codes), codes.shape[0], _host(ids_a), T, _host(cb)))
+        self._N = codes.shape[0]
+
+    def index_stats(self) -> dict:
+        st = EtfStats()
+        self._ck(self._lib.etf_index_stats(self._h, ctypes.byref(st)))
+        return st.as_dict()
+
+    def index_device_bytes(self) -> int:
+        return self._ck(self._lib.etf_index_device_bytes(self._h))
+
+    def index_layout(self) -> EtfLayout:
+        lay = EtfLayout()
+        self._ck(self._lib.etf_index_layout(self._h, ctypes.byref(lay)))
+        return lay
+
+    def index_export(self) -> np.ndarray:
+        """The device image as a host byte array (what index_upload copies to the GPU)."""
+        buf = np.zeros(self.index_device_bytes(), dtype=np.uint8)
+        self._ck(self._lib.etf_index_export(self._h, _host(buf), buf.size))
+        return buf
+
+    def index_upload(self, dev_buf=None):
+        """Uploads the index into dev_buf (uint8 GPU tensor); allocates one with torch if None."""
+        import torch
+        n = self.index_device_bytes()
+        if dev_buf is None:
+            dev_buf = torch.empty(n + 256, dtype=torch.uint8, device="cuda")
+        off = (-dev_buf.data_ptr()) % 256
+        self._ck(self._lib.etf_index_upload(self._h, dev_buf.data_ptr() + off, dev_buf.numel() - off))
+        self._keep["index"] = dev_buf
+        return dev_buf
+
+    # ---- device
+    def workspace_bytes(self, Q: int, k: int, mode: int) -> int:
+        return self._ck(self._lib.etf_workspace_bytes(self._h, Q, k, mode))
+
+    def alloc_workspace(self, Q: int, k: int, mode: int):
+        import torch
+        n = self.workspace_bytes(Q, k, mode)
+        return torch.empty(n + 256, dtype=torch.uint8, device="cuda")
+
+    @staticmethod
+    def _ws(ws):
+        off = (-ws.data_ptr()) % 256
+        return ws.data_ptr() + off, ws.numel() - off
+
+    def lut_build(self, queries, lut=None):
+        import torch
+        d, M, K = self._shape
+        Q = queries.shape[0]
+        if lut is None:
+            lut = torch.empty((Q, M, K), dtype=torch.float32, device=queries.device)
+        self._ck(self._lib.etf_lut_build(self._h, _dev(queries), Q, _dev(lut)))
+        return lut
+
+    def adc(self, queries, mode: int, dist=None, ws=None):
+        import torch
+        Q = queries.shape[0]
+        if dist is None:
+            dist = torch.empty((Q, self._N), dtype=torch.float32, device=queries.device)
+        if ws is None:
+            ws = self.alloc_workspace(Q, 0, mode)
+        p, n = self._ws(ws)
+        self._ck(self._lib.etf_adc(self._h, _dev(queries), Q, mode, _dev(dist), p, n))
+        return dist
+
+    def search(self, queries, k: int, mode: int, out_ids=None, out_dist=None, ws=None):
+        import torch
+        Q = queries.shape[0]
+        if out_ids is None:
+            out_ids = torch.empty((Q, k), dtype=torch.int32, device=queries.device)
+        if out_dist is None:
+            out_dist = torch.empty((Q, k), dtype=torch.float32, device=queries.device)
+        if ws is None:
+            ws = self.alloc_workspace(Q, k, mode)
+        p, n = self._ws(ws)
+        self._ck(self._lib.etf_search(self._h, _dev(queries), Q, k, mode, _dev(out_ids), _dev(out_dist), p, n))
+        return out_ids, out_dist
+
+    def last_fallback_count(self) -> int:
+        v = ctypes.c_int64(0)
+        self._ck(self._lib.etf_last_fallback_count(self._h, ctypes.byref(v)))
+        return int(v.value)

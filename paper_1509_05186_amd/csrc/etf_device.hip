@@ -1,0 +1,570 @@
+// Device half of the library: index upload, workspace planning, kernel launches.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <functional>
+
+#include "etf_internal.h"
+#include "etf_kernels.hip.h"
+
+using namespace etf;
+
+#define HIP_TRY(ctx, call)                                                                            \
+    do {                                                                                              \
+        hipError_t e_ = (call);                                                                       \
+        if (e_ != hipSuccess) return fail(ctx, ETF_EHIP, "%s: %s", #call, hipGetErrorString(e_));     \
+    } while (0)
+
+#define LAUNCH_CHECK(ctx, name)                                                                       \
+    do {                                                                                              \
+        hipError_t e_ = hipGetLastError();                                                            \
+        if (e_ != hipSuccess) return fail(ctx, ETF_EHIP, "launch of %s: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+static constexpr int64_t LDS_BUDGET = 128 * 1024;  // bytes of table slices a workgroup may stage
+
+// =============================================================================================
+// context
+// =============================================================================================
+extern "C" int etf_create(etf_ctx **out, int device, void *hip_stream)
+{
+    if (!out) return ETF_EINVAL;
+    *out = nullptr;
+    if (device >= 0) {
+        int n = 0;
+        if (hipGetDeviceCount(&n) != hipSuccess || device >= n) return ETF_ENOGPU;
+    }
+    etf_ctx *c = new (std::nothrow) etf_ctx();
+    if (!c) return ETF_ENOMEM;
+    c->device = device;
+    c->stream = hip_stream;
+    *out = c;
+    return ETF_OK;
+}
+
+extern "C" void etf_destroy(etf_ctx *ctx) { delete ctx; }
+
+extern "C" int etf_set_stream(etf_ctx *ctx, void *hip_stream)
+{
+    if (!ctx) return ETF_EINVAL;
+    ctx->stream = hip_stream;
+    return ETF_OK;
+}
+
+static int need_device(const etf_ctx *ctx)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (ctx->device < 0) return fail(ctx, ETF_ENOGPU, "host-only context");
+    return ETF_OK;
+}
+
+// =============================================================================================
+// index upload
+// =============================================================================================
+extern "C" int etf_index_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes)
+{
+    int rc = need_device(ctx);
+    if (rc) return rc;
+    if (!ctx->idx.built) return fail(ctx, ETF_ESTATE, "no index: call etf_index_build first");
+    if (!dev_buf) return fail(ctx, ETF_EINVAL, "device buffer is null");
+    if (((uintptr_t)dev_buf & 255) != 0) return fail(ctx, ETF_EINVAL, "device buffer must be 256-byte aligned");
+    if (bytes < ctx->lay.total) return fail(ctx, ETF_ENOMEM, "device buffer too small: %lld < %lld", (long long)bytes, (long long)ctx->lay.total);
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    hipStream_t st = (hipStream_t)ctx->stream;
+    char *base = (char *)dev_buf;
+    hipError_t first = hipSuccess;
+    for_each_image_array(ctx, [&](int64_t off, const void *src, size_t n) {
+        if (n == 0 || first != hipSuccess) return;
+        first = hipMemcpyAsync(base + off, src, n, hipMemcpyHostToDevice, st);
+    });
+    HIP_TRY(ctx, first);
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    ctx->dev_base = base;
+    return ETF_OK;
+}
+
+// =============================================================================================
+// workspace plan
+// =============================================================================================
+namespace {
+
+struct Plan {
+    int mode = 0;
+    bool search = false;
+    int k = 0;
+    int64_t tiles_total = 0;  // ceil(Q / 64)
+    int64_t NT = 0;           // tiles per batch
+    int64_t items = 0;        // candidates per query: N (flat) or distinct encodings
+    int64_t S = 0;            // threshold sample size
+    uint32_t C = 0;           // candidate capacity per query
+    bool use_tau = false;
+    int64_t o_counter = 0, o_lutT = 0, o_sdist = 0, o_tau = 0, o_cnt = 0, o_flag = 0, o_cand = 0;
+    int64_t o_part[ETF_MAX_M][ETF_MAX_M];
+    int64_t o_leafp[ETF_MAX_M];
+    int64_t total = 0;
+};
+
+int64_t al256(int64_t x) { return (x + 255) & ~(int64_t)255; }
+
+int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan &P)
+{
+    const HostIndex &ix = ctx->idx;
+    if (!ix.built) return fail(ctx, ETF_ESTATE, "no index: call etf_index_build first");
+    if (Q <= 0) return fail(ctx, ETF_EINVAL, "Q must be positive");
+    if (mode != ETF_MODE_FLAT && mode != ETF_MODE_TREE && mode != ETF_MODE_FOREST)
+        return fail(ctx, ETF_EINVAL, "unknown mode %d", mode);
+    if (mode == ETF_MODE_TREE && ix.T != 1) return fail(ctx, ETF_ESTATE, "ETF_MODE_TREE needs an index built with T = 1 (it has T = %d)", ix.T);
+    if (search && (k < 1 || k > ETF_MAX_TOPK || k > ix.N)) return fail(ctx, ETF_EINVAL, "need 1 <= k <= min(N, %d) (k=%d)", ETF_MAX_TOPK, k);
+    P.mode = mode;
+    P.search = search;
+    P.k = k;
+    P.tiles_total = (Q + QT - 1) / QT;
+    const int M = ix.M, K = ix.K;
+    P.items = mode == ETF_MODE_FLAT ? ix.N : ix.Nd;
+    P.S = mode == ETF_MODE_FLAT ? (int64_t)ix.sample_pos.size() : (int64_t)ix.sample_enc.size();
+    if (search) {
+        int64_t C = ctx->opt.cand_cap;
+        if (C == 0) {
+            const int64_t expect = (int64_t)((double)k * (double)P.items / (double)std::max<int64_t>(P.S, 1));
+            C = 4096;
+            while (C < 3 * expect + 2048 && C < (1 << 17)) C <<= 1;
+        }
+        if (P.items <= C || P.S < k) {  // few enough encodings: every one is a candidate, no bound needed
+            P.use_tau = false;
+            if (P.items > C) C = P.items;  // cannot bound without a large enough sample
+        } else {
+            P.use_tau = true;
+        }
+        P.C = (uint32_t)C;
+    }
+    // bytes per tile of 64 queries
+    int64_t per_tile = (int64_t)M * K * QT * 4;
+    if (mode != ETF_MODE_FLAT)
+        for (int t = 0; t < ix.T; ++t) {
+            const HostTree &tr = ix.tree[t];
+            for (int l = 0; l + 1 < tr.D; ++l) per_tile += al256((int64_t)tr.level[l].code.size() * QT * 4);
+            per_tile += al256(tr.U * QT * 4);
+        }
+    if (search) {
+        if (P.use_tau) per_tile += al256(P.S * QT * 4);
+        per_tile += (int64_t)QT * (12 + (int64_t)P.C * 8);
+    }
+    int64_t nt = ctx->opt.ws_cap_bytes / std::max<int64_t>(per_tile, 1);
+    P.NT = std::max<int64_t>(1, std::min<int64_t>(nt, P.tiles_total));
+    // offsets
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) {
+        int64_t o = off;
+        off = al256(off + bytes);
+        return o;
+    };
+    P.o_counter = take(256);
+    P.o_lutT = take(P.NT * M * K * QT * 4);
+    if (mode != ETF_MODE_FLAT)
+        for (int t = 0; t < ix.T; ++t) {
+            const HostTree &tr = ix.tree[t];
+            for (int l = 0; l + 1 < tr.D; ++l) P.o_part[t][l] = take(P.NT * (int64_t)tr.level[l].code.size() * QT * 4);
+            P.o_leafp[t] = take(P.NT * tr.U * QT * 4);
+        }
+    if (search) {
+        if (P.use_tau) P.o_sdist = take(P.NT * P.S * QT * 4);
+        P.o_tau = take(P.NT * QT * 4);
+        P.o_cnt = take(P.NT * QT * 4);
+        P.o_flag = take(P.NT * QT * 4);
+        P.o_cand = take(P.NT * QT * (int64_t)P.C * 8);
+    }
+    P.total = off;
+    return ETF_OK;
+}
+
+// choose the number of workgroups along x so that a launch has a few thousand workgroups in total
+int64_t blocks_for(int64_t n, int64_t min_items_per_block, int64_t other_dims)
+{
+    int64_t want = std::max<int64_t>(1, 4096 / std::max<int64_t>(other_dims, 1));
+    int64_t b = (n + min_items_per_block - 1) / min_items_per_block;
+    return std::max<int64_t>(1, std::min<int64_t>(b, want));
+}
+
+int pick_G(int width, int K)
+{
+    int G = 1;
+    while (G < 16 && (int64_t)width * K * (WAVE / G) * 4 > LDS_BUDGET) G <<= 1;
+    return G;
+}
+
+template <class F>
+int set_lds(const etf_ctx *ctx, F kernel, size_t bytes)
+{
+    if (bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) return fail(ctx, ETF_EHIP, "hipFuncSetAttribute(%zu bytes of LDS): %s", bytes, hipGetErrorString(e));
+    }
+    return ETF_OK;
+}
+
+// ---- launch helpers --------------------------------------------------------------------------
+
+int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_t tiles, float *lutT, float *lut_public)
+{
+    const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
+    dim3 grid((unsigned)tiles, (unsigned)ctx->M);
+    hipLaunchKernelGGL(k_lut_direct, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M,
+                       ctx->K, cb, lutT, lut_public);
+    LAUNCH_CHECK(ctx, "k_lut_direct");
+    return ETF_OK;
+}
+
+template <int G>
+int launch_leaf_g(etf_ctx *ctx, int ndw, dim3 grid, dim3 block, size_t lds, const uint8_t *lcodes, int width,
+                  const uint32_t *lparent, const uint32_t *lrow, int64_t n, const float *prev, int64_t nprev, float *out,
+                  int64_t U, const float *lutT, int m0, int per_block)
+{
+    hipStream_t st = (hipStream_t)ctx->stream;
+    const int M = ctx->M, K = ctx->K;
+#define LEAF_CASE(NDW)                                                                                         \
+    case NDW: {                                                                                                \
+        int rc = set_lds(ctx, k_leaf<G, NDW>, lds);                                                            \
+        if (rc) return rc;                                                                                     \
+        hipLaunchKernelGGL((k_leaf<G, NDW>), grid, block, lds, st, lcodes, width, lparent, lrow, n, prev, nprev, \
+                           out, U, lutT, M, K, m0, per_block);                                                 \
+        break;                                                                                                 \
+    }
+    switch (ndw) {
+        LEAF_CASE(1)
+        LEAF_CASE(2)
+        LEAF_CASE(3)
+        LEAF_CASE(4)
+        default: return fail(ctx, ETF_EINVAL, "leaf record of %d words", ndw);
+    }
+#undef LEAF_CASE
+    LAUNCH_CHECK(ctx, "k_leaf");
+    return ETF_OK;
+}
+
+// all levels and leaf buckets of every tree for `tiles` tiles: fills the per-tree result tables
+int launch_trees(etf_ctx *ctx, const Plan &P, char *ws, int64_t tiles)
+{
+    const HostIndex &ix = ctx->idx;
+    const DevLayout &L = ctx->lay;
+    hipStream_t st = (hipStream_t)ctx->stream;
+    const float *lutT = reinterpret_cast<const float *>(ws + P.o_lutT);
+    const int M = ix.M, K = ix.K;
+    for (int t = 0; t < ix.T; ++t) {
+        const HostTree &tr = ix.tree[t];
+        const DevTreeLayout &TL = L.tree[t];
+        // internal levels, top down
+        for (int l = 0; l + 1 < tr.D; ++l) {
+            const int64_t n = (int64_t)tr.level[l].code.size();
+            if (n == 0) break;  // no internal node at this level: none below either
+            const int64_t bx = blocks_for(n, 4 * 32, tiles);
+            const int per_wave = (int)((n + bx * 4 - 1) / (bx * 4));
+            const float *prev = l > 0 ? reinterpret_cast<const float *>(ws + P.o_part[t][l - 1]) : nullptr;
+            const int64_t nprev = l > 0 ? (int64_t)tr.level[l - 1].code.size() : 0;
+            hipLaunchKernelGGL(k_level, dim3((unsigned)bx, (unsigned)tiles), dim3(256), 0, st,
+                               reinterpret_cast<const uint8_t *>(ctx->dev_base + TL.icode[l]),
+                               reinterpret_cast<const uint32_t *>(ctx->dev_base + TL.iparent[l]), n, prev, nprev,
+                               reinterpret_cast<float *>(ws + P.o_part[t][l]), lutT, M, K, tr.c0 + l, per_wave);
+            LAUNCH_CHECK(ctx, "k_level");
+        }
+        // leaf buckets
+        for (int l = 0; l < tr.D; ++l) {
+            const HostBucket &B = tr.bucket[l];
+            const int64_t n = (int64_t)B.size();
+            if (n == 0) continue;
+            const int G = pick_G(B.width, K);
+            const size_t lds = (size_t)B.width * K * (WAVE / G) * 4;
+            const int64_t bx = blocks_for(n, 2048, tiles * G);
+            const int per_block = (int)((n + bx - 1) / bx);
+            const float *prev = l > 0 ? reinterpret_cast<const float *>(ws + P.o_part[t][l - 1]) : nullptr;
+            const int64_t nprev = l > 0 ? (int64_t)tr.level[l - 1].code.size() : 0;
+            dim3 grid((unsigned)bx, (unsigned)G, (unsigned)tiles), block(512);
+            const uint8_t *lc = reinterpret_cast<const uint8_t *>(ctx->dev_base + TL.lcodes[l]);
+            const uint32_t *lp = reinterpret_cast<const uint32_t *>(ctx->dev_base + TL.lparent[l]);
+            const uint32_t *lr = reinterpret_cast<const uint32_t *>(ctx->dev_base + TL.lrow[l]);
+            float *out = reinterpret_cast<float *>(ws + P.o_leafp[t]);
+            int rc;
+            switch (G) {
+                case 1: rc = launch_leaf_g<1>(ctx, B.stride / 4, grid, block, lds, lc, B.width, lp, lr, n, prev, nprev, out, tr.U, lutT, tr.c0 + l, per_block); break;
+                case 2: rc = launch_leaf_g<2>(ctx, B.stride / 4, grid, block, lds, lc, B.width, lp, lr, n, prev, nprev, out, tr.U, lutT, tr.c0 + l, per_block); break;
+                case 4: rc = launch_leaf_g<4>(ctx, B.stride / 4, grid, block, lds, lc, B.width, lp, lr, n, prev, nprev, out, tr.U, lutT, tr.c0 + l, per_block); break;
+                case 8: rc = launch_leaf_g<8>(ctx, B.stride / 4, grid, block, lds, lc, B.width, lp, lr, n, prev, nprev, out, tr.U, lutT, tr.c0 + l, per_block); break;
+                default: rc = fail(ctx, ETF_EINVAL, "no kernel for %d leaves per wave", G);
+            }
+            if (rc) return rc;
+        }
+    }
+    return ETF_OK;
+}
+
+void fill_reduce_args(const etf_ctx *ctx, const Plan &P, char *ws, ReduceArgs &r)
+{
+    const HostIndex &ix = ctx->idx;
+    memset(&r, 0, sizeof r);
+    r.T = ix.T;
+    for (int t = 0; t < ix.T; ++t) {
+        r.leafp[t] = reinterpret_cast<const float *>(ws + P.o_leafp[t]);
+        r.leaf_of[t] = ctx->lay.tree[t].leaf_of >= 0 ? reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.tree[t].leaf_of) : nullptr;
+        r.U[t] = ix.tree[t].U;
+    }
+}
+
+template <int MODE>
+int launch_reduce(etf_ctx *ctx, const ReduceArgs &r, int64_t nitems, const uint32_t *map, int64_t tiles, const OutArgs &o)
+{
+    if (nitems == 0) return ETF_OK;
+    const int64_t bx = blocks_for(nitems, 4 * 64, tiles);
+    int per_wave = (int)((nitems + bx * 4 - 1) / (bx * 4));
+    if (MODE == OUT_ALLPAIRS) per_wave = (per_wave + 63) & ~63;  // whole 64-wide output segments per wave
+    const int64_t bx2 = (nitems + (int64_t)per_wave * 4 - 1) / ((int64_t)per_wave * 4);
+    hipLaunchKernelGGL((k_reduce<MODE>), dim3((unsigned)bx2, (unsigned)tiles), dim3(256), 0, (hipStream_t)ctx->stream, r,
+                       nitems, map, per_wave, o);
+    LAUNCH_CHECK(ctx, "k_reduce");
+    return ETF_OK;
+}
+
+template <int MODE>
+int launch_flat(etf_ctx *ctx, const Plan &P, char *ws, int64_t nitems, const uint32_t *sample, int64_t tiles, const OutArgs &o)
+{
+    if (nitems == 0) return ETF_OK;
+    const int M = ctx->M, K = ctx->K;
+    const int G = pick_G(M, K);
+    const size_t lds = (size_t)M * K * (WAVE / G) * 4;
+    const int64_t bx = blocks_for(nitems, 4096, tiles * G);
+    const int per_block = (int)((nitems + bx - 1) / bx);
+    dim3 grid((unsigned)bx, (unsigned)G, (unsigned)tiles), block(512);
+    hipStream_t st = (hipStream_t)ctx->stream;
+    const uint8_t *codes = reinterpret_cast<const uint8_t *>(ctx->dev_base + ctx->lay.codes);
+    const float *lutT = reinterpret_cast<const float *>(ws + P.o_lutT);
+#define FLAT_CASE(GG)                                                                                        \
+    case GG: {                                                                                               \
+        int rc = set_lds(ctx, k_flat<GG, MODE>, lds);                                                        \
+        if (rc) return rc;                                                                                   \
+        hipLaunchKernelGGL((k_flat<GG, MODE>), grid, block, lds, st, codes, nitems, sample, lutT, M, K, per_block, o); \
+        break;                                                                                               \
+    }
+    switch (G) {
+        FLAT_CASE(1)
+        FLAT_CASE(2)
+        FLAT_CASE(4)
+        FLAT_CASE(8)
+        default: return fail(ctx, ETF_EINVAL, "no kernel for %d encodings per wave", G);
+    }
+#undef FLAT_CASE
+    LAUNCH_CHECK(ctx, "k_flat");
+    return ETF_OK;
+}
+
+int check_ready(etf_ctx *ctx, const void *queries, const void *ws)
+{
+    int rc = need_device(ctx);
+    if (rc) return rc;
+    if (!ctx->idx.built) return fail(ctx, ETF_ESTATE, "no index: call etf_index_build first");
+    if (!ctx->dev_base) return fail(ctx, ETF_ESTATE, "index not on the device: call etf_index_upload first");
+    if (!queries) return fail(ctx, ETF_EINVAL, "queries pointer is null");
+    if (!ws) return fail(ctx, ETF_EINVAL, "workspace pointer is null");
+    if (((uintptr_t)ws & 255) != 0) return fail(ctx, ETF_EINVAL, "workspace must be 256-byte aligned");
+    return ETF_OK;
+}
+
+}  // namespace
+
+extern "C" int64_t etf_workspace_bytes(const etf_ctx *ctx, int64_t Q, int k, int mode)
+{
+    if (!ctx) return ETF_EINVAL;
+    Plan P;
+    int rc = make_plan(ctx, Q, k, mode, k > 0, P);
+    if (rc) return rc;
+    return P.total;
+}
+
+// =============================================================================================
+// S1 as an entry point
+// =============================================================================================
+extern "C" int etf_lut_build(etf_ctx *ctx, const float *queries, int64_t Q, float *lut)
+{
+    int rc = need_device(ctx);
+    if (rc) return rc;
+    if (ctx->codebooks.empty()) return fail(ctx, ETF_ESTATE, "no codebooks");
+    if (!ctx->dev_base) return fail(ctx, ETF_ESTATE, "codebooks not on the device: call etf_index_upload first");
+    if (!queries || !lut) return fail(ctx, ETF_EINVAL, "null pointer");
+    if (Q <= 0) return fail(ctx, ETF_EINVAL, "Q must be positive");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    const int64_t tiles = (Q + QT - 1) / QT;
+    for (int64_t t0 = 0; t0 < tiles; t0 += 32768) {
+        const int64_t nt = std::min<int64_t>(32768, tiles - t0);
+        rc = launch_lut(ctx, queries, Q, t0 * QT, nt, nullptr, lut);
+        if (rc) return rc;
+    }
+    return ETF_OK;
+}
+
+// =============================================================================================
+// all-pairs ADC
+// =============================================================================================
+extern "C" int etf_adc(etf_ctx *ctx, const float *queries, int64_t Q, int mode, float *dist, void *ws, int64_t ws_bytes)
+{
+    int rc = check_ready(ctx, queries, ws);
+    if (rc) return rc;
+    if (!dist) return fail(ctx, ETF_EINVAL, "dist pointer is null");
+    Plan P;
+    rc = make_plan(ctx, Q, 0, mode, false, P);
+    if (rc) return rc;
+    if (ws_bytes < P.total) return fail(ctx, ETF_ENOMEM, "workspace too small: %lld < %lld", (long long)ws_bytes, (long long)P.total);
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    const HostIndex &ix = ctx->idx;
+    char *w = (char *)ws;
+    for (int64_t t0 = 0; t0 < P.tiles_total; t0 += P.NT) {
+        const int64_t tiles = std::min<int64_t>(P.NT, P.tiles_total - t0);
+        const int64_t q0 = t0 * QT;
+        rc = launch_lut(ctx, queries, Q, q0, tiles, reinterpret_cast<float *>(w + P.o_lutT), nullptr);
+        if (rc) return rc;
+        OutArgs o;
+        memset(&o, 0, sizeof o);
+        o.dist = dist + q0 * ix.N;
+        o.N = ix.N;
+        o.nq = std::min<int64_t>(tiles * QT, Q - q0);
+        if (mode == ETF_MODE_FLAT) {
+            rc = launch_flat<OUT_ALLPAIRS>(ctx, P, w, ix.N, nullptr, tiles, o);
+            if (rc) return rc;
+        } else {
+            rc = launch_trees(ctx, P, w, tiles);
+            if (rc) return rc;
+            ReduceArgs r;
+            fill_reduce_args(ctx, P, w, r);
+            rc = launch_reduce<OUT_ALLPAIRS>(ctx, r, ix.N, reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.enc_of_pos), tiles, o);
+            if (rc) return rc;
+        }
+    }
+    return ETF_OK;
+}
+
+// =============================================================================================
+// top-k search
+// =============================================================================================
+extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, int mode, int32_t *out_ids,
+                          float *out_dist, void *ws, int64_t ws_bytes)
+{
+    int rc = check_ready(ctx, queries, ws);
+    if (rc) return rc;
+    if (!out_ids || !out_dist) return fail(ctx, ETF_EINVAL, "output pointer is null");
+    Plan P;
+    rc = make_plan(ctx, Q, k, mode, true, P);
+    if (rc) return rc;
+    if (ws_bytes < P.total) return fail(ctx, ETF_ENOMEM, "workspace too small: %lld < %lld", (long long)ws_bytes, (long long)P.total);
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    hipStream_t st = (hipStream_t)ctx->stream;
+    const HostIndex &ix = ctx->idx;
+    const DevLayout &L = ctx->lay;
+    char *w = (char *)ws;
+    const bool flat = mode == ETF_MODE_FLAT;
+    uint32_t *counter = reinterpret_cast<uint32_t *>(w + P.o_counter);
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, counter, (int64_t)64, 0u);
+    LAUNCH_CHECK(ctx, "k_fill_u32");
+    ctx->last_flag_count = counter;
+    for (int64_t t0 = 0; t0 < P.tiles_total; t0 += P.NT) {
+        const int64_t tiles = std::min<int64_t>(P.NT, P.tiles_total - t0);
+        const int64_t q0 = t0 * QT;
+        const int64_t nq = std::min<int64_t>(tiles * QT, Q - q0);
+        const int64_t nql = tiles * QT;
+        float *lutT = reinterpret_cast<float *>(w + P.o_lutT);
+        float *tau = reinterpret_cast<float *>(w + P.o_tau);
+        uint32_t *cnt = reinterpret_cast<uint32_t *>(w + P.o_cnt);
+        uint32_t *flag = reinterpret_cast<uint32_t *>(w + P.o_flag);
+        uint64_t *cand = reinterpret_cast<uint64_t *>(w + P.o_cand);
+        rc = launch_lut(ctx, queries, Q, q0, tiles, lutT, nullptr);
+        if (rc) return rc;
+        const unsigned fb = (unsigned)((nql + 255) / 256);
+        hipLaunchKernelGGL(k_fill_u32, dim3(fb), dim3(256), 0, st, cnt, nql, 0u);
+        hipLaunchKernelGGL(k_fill_u32, dim3(fb), dim3(256), 0, st, flag, nql, ctx->opt.force_fallback ? 1u : 0u);
+        LAUNCH_CHECK(ctx, "k_fill_u32");
+        OutArgs o;
+        memset(&o, 0, sizeof o);
+        o.sdist = P.use_tau ? reinterpret_cast<float *>(w + P.o_sdist) : nullptr;
+        o.S = P.S;
+        o.tau = tau;
+        o.cnt = cnt;
+        o.cand = cand;
+        o.C = P.C;
+        o.nq = nq;
+        ReduceArgs r;
+        if (!flat) {
+            rc = launch_trees(ctx, P, w, tiles);
+            if (rc) return rc;
+            fill_reduce_args(ctx, P, w, r);
+        }
+        if (!ctx->opt.force_fallback) {
+            if (P.use_tau) {
+                if (flat)
+                    rc = launch_flat<OUT_SAMPLE>(ctx, P, w, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_pos), tiles, o);
+                else
+                    rc = launch_reduce<OUT_SAMPLE>(ctx, r, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_enc), tiles, o);
+                if (rc) return rc;
+                hipLaunchKernelGGL(k_tau, dim3((unsigned)tiles), dim3(1024), 0, st, o.sdist, P.S, k, 3, nq, tau);
+                LAUNCH_CHECK(ctx, "k_tau");
+            } else {
+                hipLaunchKernelGGL(k_fill_f32, dim3(fb), dim3(256), 0, st, tau, nql, nq, __builtin_inff(), -1.f);
+                LAUNCH_CHECK(ctx, "k_fill_f32");
+            }
+            if (flat)
+                rc = launch_flat<OUT_FILTER>(ctx, P, w, ix.N, nullptr, tiles, o);
+            else
+                rc = launch_reduce<OUT_FILTER>(ctx, r, ix.Nd, nullptr, tiles, o);
+            if (rc) return rc;
+        }
+        SelectArgs sa;
+        sa.cnt = cnt;
+        sa.cand = cand;
+        sa.C = P.C;
+        sa.ebegin = flat ? nullptr : reinterpret_cast<const uint32_t *>(ctx->dev_base + L.ebegin);
+        sa.ids = reinterpret_cast<const int32_t *>(ctx->dev_base + (flat ? L.ids_in : L.ids_sorted));
+        sa.k = k;
+        sa.out_ids = out_ids + q0 * k;
+        sa.out_dist = out_dist + q0 * k;
+        sa.flag = flag;
+        hipLaunchKernelGGL(k_select, dim3((unsigned)nq), dim3(256), 0, st, sa);
+        LAUNCH_CHECK(ctx, "k_select");
+        ExactArgs ea;
+        memset(&ea, 0, sizeof ea);
+        ea.flag = flag;
+        ea.nflag = counter;
+        ea.lutT = lutT;
+        ea.M = ix.M;
+        ea.K = ix.K;
+        if (flat) {
+            ea.T = 1;
+            ea.chunk_begin[0] = 0;
+            ea.chunk_begin[1] = ix.M;
+            ea.codes = reinterpret_cast<const uint8_t *>(ctx->dev_base + L.codes);
+            ea.rows = ix.N;
+            ea.ebegin = nullptr;
+        } else {
+            ea.T = ix.T;
+            for (int t = 0; t <= ix.T; ++t) ea.chunk_begin[t] = ix.chunk_begin[t];
+            ea.codes = reinterpret_cast<const uint8_t *>(ctx->dev_base + L.ecodes);
+            ea.rows = ix.Nd;
+            ea.ebegin = sa.ebegin;
+        }
+        ea.ids = sa.ids;
+        ea.k = k;
+        ea.out_ids = sa.out_ids;
+        ea.out_dist = sa.out_dist;
+        hipLaunchKernelGGL(k_exact, dim3((unsigned)nq), dim3(256), 0, st, ea);
+        LAUNCH_CHECK(ctx, "k_exact");
+    }
+    return ETF_OK;
+}
+
+extern "C" int etf_last_fallback_count(etf_ctx *ctx, int64_t *out)
+{
+    int rc = need_device(ctx);
+    if (rc) return rc;
+    if (!out) return fail(ctx, ETF_EINVAL, "output pointer is null");
+    if (!ctx->last_flag_count) return fail(ctx, ETF_ESTATE, "no search has run on this context");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    HIP_TRY(ctx, hipStreamSynchronize((hipStream_t)ctx->stream));
+    uint32_t v = 0;
+    HIP_TRY(ctx, hipMemcpy(&v, ctx->last_flag_count, sizeof v, hipMemcpyDeviceToHost));
+    *out = v;
+    return ETF_OK;
+}

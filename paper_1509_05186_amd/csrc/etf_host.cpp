@@ -1,0 +1,656 @@
+// Host half of the library: context, product quantiser (train / encode), index build, statistics.
+//
+// The index build follows the paper's "Constructing Encoding Tree": sort the encodings
+// lexicographically, then grow the tree in one linear, append-only pass driven by the longest
+// common prefix of neighbouring encodings (Algorithm 1).  What differs from the paper is the
+// serialisation: instead of one depth-first byte stream (Hierarchical Memory Structure) the nodes
+// are appended to one array per level.  Because the input is sorted, each of these arrays is in
+// breadth-first order, the children of a node are adjacent, and the leaves in sorted order are the
+// paper's depth-first leaf order.
+#include <algorithm>
+#include <atomic>
+#include <cfloat>
+#include <cmath>
+#include <cstdarg>
+#include <cstring>
+#include <functional>
+#include <thread>
+
+#include "etf_internal.h"
+
+namespace etf {
+
+int fail(const etf_ctx *ctx, int code, const char *fmt, ...)
+{
+    if (ctx) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        ctx->err = buf;
+    }
+    return code;
+}
+
+int host_threads()
+{
+    unsigned hc = std::thread::hardware_concurrency();
+    int t = hc ? (int)hc : 4;
+    if (const char *e = getenv("OMP_NUM_THREADS")) {
+        int v = atoi(e);
+        if (v > 0) t = std::min(t, v);
+    }
+    return std::max(1, std::min(t, 64));
+}
+
+void parallel_slices(int64_t n, int threads, const std::function<void(int, int64_t, int64_t)> &fn)
+{
+    if (n <= 0) return;
+    threads = (int)std::max<int64_t>(1, std::min<int64_t>(threads, n));
+    if (threads == 1) {
+        fn(0, 0, n);
+        return;
+    }
+    std::vector<std::thread> th;
+    th.reserve(threads);
+    for (int t = 0; t < threads; ++t) {
+        int64_t b = n * t / threads, e = n * (t + 1) / threads;
+        th.emplace_back([&fn, t, b, e] { fn(t, b, e); });
+    }
+    for (auto &x : th) x.join();
+}
+
+// splitmix64: the library's own seeded generator (initial codewords, threshold sample)
+static inline uint64_t splitmix64(uint64_t &s)
+{
+    uint64_t z = (s += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Stable LSD radix sort of fixed-size records by a list of key bytes (least significant first).
+// ---------------------------------------------------------------------------------------------
+template <class Rec, class ByteOf>
+static void radix_sort_records(std::vector<Rec> &a, int nbytes, ByteOf byte_of)
+{
+    const int64_t n = (int64_t)a.size();
+    if (n < 2) return;
+    std::vector<Rec> b(a.size());
+    Rec *src = a.data(), *dst = b.data();
+    const int threads = n > (1 << 16) ? host_threads() : 1;
+    std::vector<int64_t> hist((size_t)threads * 256);
+    for (int p = 0; p < nbytes; ++p) {
+        std::fill(hist.begin(), hist.end(), 0);
+        parallel_slices(n, threads, [&](int t, int64_t lo, int64_t hi) {
+            int64_t *h = hist.data() + (size_t)t * 256;
+            for (int64_t i = lo; i < hi; ++i) h[byte_of(src[i], p)]++;
+        });
+        // a pass in which every record has the same digit moves nothing
+        bool trivial = false;
+        for (int v = 0; v < 256 && !trivial; ++v) {
+            int64_t c = 0;
+            for (int t = 0; t < threads; ++t) c += hist[(size_t)t * 256 + v];
+            if (c == n) trivial = true;
+        }
+        if (trivial) continue;
+        int64_t run = 0;
+        for (int v = 0; v < 256; ++v)
+            for (int t = 0; t < threads; ++t) {
+                int64_t c = hist[(size_t)t * 256 + v];
+                hist[(size_t)t * 256 + v] = run;
+                run += c;
+            }
+        parallel_slices(n, threads, [&](int t, int64_t lo, int64_t hi) {
+            int64_t *h = hist.data() + (size_t)t * 256;
+            for (int64_t i = lo; i < hi; ++i) dst[h[byte_of(src[i], p)]++] = src[i];
+        });
+        std::swap(src, dst);
+    }
+    if (src != a.data()) a.swap(b);
+}
+
+struct KeyRec {
+    uint64_t k[2];   // code bytes packed big-endian: integer order == lexicographic order
+    uint32_t pos;    // payload: input position or distinct-encoding number
+    int32_t id;      // secondary key
+};
+
+static inline void pack_key(const uint8_t *code, int c0, int c1, uint64_t k[2])
+{
+    k[0] = k[1] = 0;
+    for (int m = c0; m < c1; ++m) {
+        int j = m - c0;
+        k[j >> 3] |= (uint64_t)code[m] << (56 - 8 * (j & 7));
+    }
+}
+
+static inline int key_byte(const uint64_t k[2], int j) { return (int)((k[j >> 3] >> (56 - 8 * (j & 7))) & 255); }
+
+// longest common prefix, in chunks, of two packed keys of D chunks
+static inline int key_lcp(const uint64_t a[2], const uint64_t b[2], int D)
+{
+    for (int w = 0; w < 2; ++w) {
+        uint64_t x = a[w] ^ b[w];
+        if (x) return std::min(D, w * 8 + (__builtin_clzll(x) >> 3));
+    }
+    return D;
+}
+
+// ---------------------------------------------------------------------------------------------
+// One tree over sorted distinct sub-encodings (Algorithm 1, level-ordered output).
+// ---------------------------------------------------------------------------------------------
+static void build_tree(const std::vector<KeyRec> &sub /* sorted, distinct keys */, int D, HostTree &tr)
+{
+    const int64_t U = (int64_t)sub.size();
+    tr.U = U;
+    tr.level.assign(D, HostLevel());
+    tr.bucket.assign(D, HostBucket());
+    for (int l = 0; l < D; ++l) {
+        tr.bucket[l].width = D - l;                       // own chunk + postfix of D-(l+1)
+        tr.bucket[l].stride = (tr.bucket[l].width + 3) & ~3;
+    }
+    // cur[l] = internal node of level l (1-based) that the current path runs through, or NO_PARENT
+    uint32_t cur[ETF_MAX_M + 1];
+    for (int l = 0; l <= D; ++l) cur[l] = NO_PARENT;
+    int lcp_prev = 0;  // common prefix with the previous encoding
+    for (int64_t i = 0; i < U; ++i) {
+        const int lcp_next = (i + 1 < U) ? key_lcp(sub[i].k, sub[i + 1].k, D) : 0;
+        // the path diverges from the previous one after lcp_prev chunks: every level below that starts
+        // a new prefix group; it is an internal node iff the next encoding still shares it
+        for (int l = lcp_prev + 1; l <= D - 1; ++l) {
+            if (lcp_next >= l) {
+                HostLevel &L = tr.level[l - 1];
+                L.code.push_back((uint8_t)key_byte(sub[i].k, l - 1));
+                L.parent.push_back(l > 1 ? cur[l - 1] : NO_PARENT);
+                cur[l] = (uint32_t)(L.code.size() - 1);
+            } else {
+                cur[l] = NO_PARENT;
+            }
+        }
+        // the first level at which this encoding is alone in its prefix group: its leaf
+        const int lev = 1 + std::max(lcp_prev, lcp_next);
+        HostBucket &B = tr.bucket[lev - 1];
+        const size_t at = B.codes.size();
+        B.codes.resize(at + B.stride, 0);
+        for (int j = 0; j < B.width; ++j) B.codes[at + j] = (uint8_t)key_byte(sub[i].k, lev - 1 + j);
+        B.parent.push_back(lev > 1 ? cur[lev - 1] : NO_PARENT);
+        B.row.push_back((uint32_t)i);
+        lcp_prev = lcp_next;
+    }
+}
+
+static int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
+
+void compute_layout(etf_ctx *ctx)
+{
+    const HostIndex &ix = ctx->idx;
+    DevLayout &L = ctx->lay;
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) {
+        int64_t o = off;
+        off = align256(off + std::max<int64_t>(bytes, 4));
+        return o;
+    };
+    L.codebooks = take((int64_t)ctx->codebooks.size() * 4);
+    L.codes = take((int64_t)ix.codes.size());
+    L.ids_in = take(ix.N * 4);
+    L.ids_sorted = take(ix.N * 4);
+    L.ebegin = take((ix.Nd + 1) * 4);
+    L.enc_of_pos = take(ix.N * 4);
+    L.ecodes = take((int64_t)ix.ecodes.size());
+    L.sample_enc = take((int64_t)ix.sample_enc.size() * 4);
+    L.sample_pos = take((int64_t)ix.sample_pos.size() * 4);
+    L.tree.assign(ix.T, DevTreeLayout());
+    for (int t = 0; t < ix.T; ++t) {
+        const HostTree &tr = ix.tree[t];
+        DevTreeLayout &TL = L.tree[t];
+        TL.leaf_of = tr.leaf_of.empty() ? -1 : take((int64_t)tr.leaf_of.size() * 4);
+        for (int l = 0; l < tr.D; ++l) {
+            TL.icode[l] = take((int64_t)tr.level[l].code.size());
+            TL.iparent[l] = take((int64_t)tr.level[l].parent.size() * 4);
+            TL.lcodes[l] = take((int64_t)tr.bucket[l].codes.size());
+            TL.lparent[l] = take((int64_t)tr.bucket[l].parent.size() * 4);
+            TL.lrow[l] = take((int64_t)tr.bucket[l].row.size() * 4);
+        }
+    }
+    L.total = off;
+}
+
+void for_each_image_array(const etf_ctx *ctx, const std::function<void(int64_t, const void *, size_t)> &put)
+{
+    const HostIndex &ix = ctx->idx;
+    const DevLayout &L = ctx->lay;
+    put(L.codebooks, ctx->codebooks.data(), ctx->codebooks.size() * 4);
+    put(L.codes, ix.codes.data(), ix.codes.size());
+    put(L.ids_in, ix.ids_in.data(), ix.ids_in.size() * 4);
+    put(L.ids_sorted, ix.ids_sorted.data(), ix.ids_sorted.size() * 4);
+    put(L.ebegin, ix.ebegin.data(), ix.ebegin.size() * 4);
+    put(L.enc_of_pos, ix.enc_of_pos.data(), ix.enc_of_pos.size() * 4);
+    put(L.ecodes, ix.ecodes.data(), ix.ecodes.size());
+    put(L.sample_enc, ix.sample_enc.data(), ix.sample_enc.size() * 4);
+    put(L.sample_pos, ix.sample_pos.data(), ix.sample_pos.size() * 4);
+    for (int t = 0; t < ix.T; ++t) {
+        const HostTree &tr = ix.tree[t];
+        const DevTreeLayout &TL = L.tree[t];
+        if (TL.leaf_of >= 0) put(TL.leaf_of, tr.leaf_of.data(), tr.leaf_of.size() * 4);
+        for (int l = 0; l < tr.D; ++l) {
+            put(TL.icode[l], tr.level[l].code.data(), tr.level[l].code.size());
+            put(TL.iparent[l], tr.level[l].parent.data(), tr.level[l].parent.size() * 4);
+            put(TL.lcodes[l], tr.bucket[l].codes.data(), tr.bucket[l].codes.size());
+            put(TL.lparent[l], tr.bucket[l].parent.data(), tr.bucket[l].parent.size() * 4);
+            put(TL.lrow[l], tr.bucket[l].row.data(), tr.bucket[l].row.size() * 4);
+        }
+    }
+}
+
+}  // namespace etf
+
+using namespace etf;
+
+// =============================================================================================
+// context
+// =============================================================================================
+extern "C" const char *etf_strerror(int code)
+{
+    switch (code) {
+        case ETF_OK: return "ok";
+        case ETF_EINVAL: return "invalid argument";
+        case ETF_ESTATE: return "call not valid in this state";
+        case ETF_ENOMEM: return "out of memory or buffer too small";
+        case ETF_EHIP: return "HIP runtime error";
+        case ETF_ENOGPU: return "context has no device";
+        default: return "unknown error code";
+    }
+}
+
+extern "C" const char *etf_last_error(const etf_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+extern "C" int etf_set_option(etf_ctx *ctx, const char *name, int64_t value)
+{
+    if (!ctx || !name) return ETF_EINVAL;
+    std::string n(name);
+    if (n == "ws_cap_bytes") {
+        if (value < ((int64_t)1 << 20)) return fail(ctx, ETF_EINVAL, "ws_cap_bytes must be at least 1 MiB");
+        ctx->opt.ws_cap_bytes = value;
+    } else if (n == "force_fallback") {
+        if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "force_fallback must be 0 or 1");
+        ctx->opt.force_fallback = value;
+    } else if (n == "sample_min") {
+        if (value < 1) return fail(ctx, ETF_EINVAL, "sample_min must be positive");
+        ctx->opt.sample_min = value;
+    } else if (n == "sample_div") {
+        if (value < 1) return fail(ctx, ETF_EINVAL, "sample_div must be positive");
+        ctx->opt.sample_div = value;
+    } else if (n == "cand_cap") {
+        if (value < 0 || value > (1 << 20)) return fail(ctx, ETF_EINVAL, "cand_cap out of range");
+        ctx->opt.cand_cap = value;
+    } else {
+        return fail(ctx, ETF_EINVAL, "unknown option '%s'", name);
+    }
+    return ETF_OK;
+}
+
+// =============================================================================================
+// product quantiser (paper: Introduction / Related Work)
+// =============================================================================================
+static int check_pq_shape(etf_ctx *ctx, int d, int M, int K)
+{
+    if (d <= 0 || M <= 0 || M > ETF_MAX_M || K <= 0 || K > 256)
+        return fail(ctx, ETF_EINVAL, "need d > 0, 1 <= M <= %d, 1 <= K <= 256 (got d=%d M=%d K=%d)", ETF_MAX_M, d, M, K);
+    if (d % M != 0) return fail(ctx, ETF_EINVAL, "d=%d is not a multiple of M=%d", d, M);
+    return ETF_OK;
+}
+
+static void drop_index(etf_ctx *ctx)
+{
+    ctx->idx = HostIndex();
+    ctx->lay = DevLayout();
+    ctx->dev_base = nullptr;
+}
+
+// nearest codeword of one sub-vector; float32 arithmetic, direct (a-b)^2 form, lowest index on ties
+static inline int nearest_codeword(const float *x, const float *cb, int K, int ds, float *best_out)
+{
+    int best = 0;
+    float bestd = FLT_MAX;
+    for (int k = 0; k < K; ++k) {
+        const float *c = cb + (size_t)k * ds;
+        float s = 0.f;
+        for (int j = 0; j < ds; ++j) {
+            float t = x[j] - c[j];
+            s += t * t;
+        }
+        if (s < bestd) {
+            bestd = s;
+            best = k;
+        }
+    }
+    if (best_out) *best_out = bestd;
+    return best;
+}
+
+extern "C" int etf_pq_set_codebooks(etf_ctx *ctx, const float *cb, int d, int M, int K)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (!cb) return fail(ctx, ETF_EINVAL, "codebooks pointer is null");
+    int rc = check_pq_shape(ctx, d, M, K);
+    if (rc) return rc;
+    drop_index(ctx);
+    ctx->d = d; ctx->M = M; ctx->K = K; ctx->ds = d / M;
+    try {
+        ctx->codebooks.assign(cb, cb + (size_t)M * K * ctx->ds);
+    } catch (const std::bad_alloc &) {
+        return fail(ctx, ETF_ENOMEM, "out of host memory");
+    }
+    return ETF_OK;
+}
+
+extern "C" int etf_pq_get_codebooks(const etf_ctx *ctx, float *cb_out)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (!cb_out) return fail(ctx, ETF_EINVAL, "output pointer is null");
+    if (ctx->codebooks.empty()) return fail(ctx, ETF_ESTATE, "no codebooks: call etf_pq_train or etf_pq_set_codebooks first");
+    memcpy(cb_out, ctx->codebooks.data(), ctx->codebooks.size() * sizeof(float));
+    return ETF_OK;
+}
+
+extern "C" int etf_pq_train(etf_ctx *ctx, const float *x, int64_t n, int d, int M, int K, int iters, uint64_t seed)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (!x || n <= 0) return fail(ctx, ETF_EINVAL, "training set is empty or null");
+    if (iters < 0) return fail(ctx, ETF_EINVAL, "iters must be >= 0");
+    int rc = check_pq_shape(ctx, d, M, K);
+    if (rc) return rc;
+    const int ds = d / M;
+    try {
+        std::vector<float> cb((size_t)M * K * ds);
+        std::vector<int> assign((size_t)n);
+        const int threads = host_threads();
+        for (int m = 0; m < M; ++m) {
+            float *c = cb.data() + (size_t)m * K * ds;
+            // initial codewords: the first K rows of a seeded Fisher-Yates shuffle (with replacement if n < K)
+            uint64_t s = seed * 0x9E3779B97F4A7C15ull + (uint64_t)m + 1;
+            std::vector<int64_t> pick(K);
+            if (n >= K) {
+                std::vector<int64_t> perm((size_t)n);
+                for (int64_t i = 0; i < n; ++i) perm[i] = i;
+                for (int k = 0; k < K; ++k) {
+                    int64_t j = k + (int64_t)(splitmix64(s) % (uint64_t)(n - k));
+                    std::swap(perm[k], perm[j]);
+                    pick[k] = perm[k];
+                }
+            } else {
+                for (int k = 0; k < K; ++k) pick[k] = (int64_t)(splitmix64(s) % (uint64_t)n);
+            }
+            for (int k = 0; k < K; ++k)
+                memcpy(c + (size_t)k * ds, x + (size_t)pick[k] * d + (size_t)m * ds, sizeof(float) * ds);
+            for (int it = 0; it < iters; ++it) {
+                parallel_slices(n, threads, [&](int, int64_t lo, int64_t hi) {
+                    for (int64_t i = lo; i < hi; ++i)
+                        assign[i] = nearest_codeword(x + (size_t)i * d + (size_t)m * ds, c, K, ds, nullptr);
+                });
+                std::vector<double> sum((size_t)K * ds, 0.0);
+                std::vector<int64_t> cnt(K, 0);
+                for (int64_t i = 0; i < n; ++i) {
+                    const float *xi = x + (size_t)i * d + (size_t)m * ds;
+                    double *sk = sum.data() + (size_t)assign[i] * ds;
+                    cnt[assign[i]]++;
+                    for (int j = 0; j < ds; ++j) sk[j] += xi[j];
+                }
+                for (int k = 0; k < K; ++k)
+                    if (cnt[k])  // an empty cluster keeps its previous codeword
+                        for (int j = 0; j < ds; ++j) c[(size_t)k * ds + j] = (float)(sum[(size_t)k * ds + j] / (double)cnt[k]);
+            }
+        }
+        drop_index(ctx);
+        ctx->d = d; ctx->M = M; ctx->K = K; ctx->ds = ds;
+        ctx->codebooks.swap(cb);
+    } catch (const std::bad_alloc &) {
+        return fail(ctx, ETF_ENOMEM, "out of host memory");
+    }
+    return ETF_OK;
+}
+
+extern "C" int etf_pq_encode(const etf_ctx *ctx, const float *x, int64_t n, uint8_t *codes_out)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (ctx->codebooks.empty()) return fail(ctx, ETF_ESTATE, "no codebooks: call etf_pq_train or etf_pq_set_codebooks first");
+    if (n < 0 || (n > 0 && (!x || !codes_out))) return fail(ctx, ETF_EINVAL, "null input or output with n=%lld", (long long)n);
+    const int d = ctx->d, M = ctx->M, K = ctx->K, ds = ctx->ds;
+    const float *cb = ctx->codebooks.data();
+    parallel_slices(n, host_threads(), [&](int, int64_t lo, int64_t hi) {
+        for (int64_t i = lo; i < hi; ++i)
+            for (int m = 0; m < M; ++m)
+                codes_out[(size_t)i * M + m] =
+                    (uint8_t)nearest_codeword(x + (size_t)i * d + (size_t)m * ds, cb + (size_t)m * K * ds, K, ds, nullptr);
+    });
+    return ETF_OK;
+}
+
+// =============================================================================================
+// index build
+// =============================================================================================
+extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, const int32_t *ids, int T,
+                               const int32_t *chunk_begin)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (ctx->codebooks.empty()) return fail(ctx, ETF_ESTATE, "no codebooks: M and K are unknown");
+    const int M = ctx->M, K = ctx->K;
+    if (!codes || N <= 0) return fail(ctx, ETF_EINVAL, "codes is null or N <= 0");
+    if (N >= ((int64_t)1 << 31)) return fail(ctx, ETF_EINVAL, "N must be below 2^31");
+    if (T < 1 || T > M) return fail(ctx, ETF_EINVAL, "need 1 <= T <= M (T=%d, M=%d)", T, M);
+    std::vector<int32_t> cb(T + 1);
+    if (chunk_begin) {
+        for (int t = 0; t <= T; ++t) cb[t] = chunk_begin[t];
+        if (cb[0] != 0 || cb[T] != M) return fail(ctx, ETF_EINVAL, "chunk_begin must run from 0 to M");
+        for (int t = 0; t < T; ++t)
+            if (cb[t + 1] <= cb[t]) return fail(ctx, ETF_EINVAL, "chunk_begin must be strictly increasing");
+    } else {
+        if (M % T != 0) return fail(ctx, ETF_EINVAL, "T=%d does not divide M=%d and no chunk_begin was given", T, M);
+        for (int t = 0; t <= T; ++t) cb[t] = t * (M / T);
+    }
+    {
+        std::atomic<int> bad(0);
+        parallel_slices(N, host_threads(), [&](int, int64_t lo, int64_t hi) {
+            for (int64_t i = lo * M; i < hi * M; ++i)
+                if (codes[i] >= K) { bad = 1; break; }
+            if (ids)
+                for (int64_t i = lo; i < hi; ++i)
+                    if (ids[i] < 0) { bad = 2; break; }
+        });
+        if (bad == 1) return fail(ctx, ETF_EINVAL, "a code byte is >= K=%d", K);
+        if (bad == 2) return fail(ctx, ETF_EINVAL, "ids must be non-negative");
+    }
+    try {
+        HostIndex ix;
+        ix.M = M; ix.K = K; ix.T = T; ix.N = N;
+        ix.chunk_begin = cb;
+        ix.codes.assign(codes, codes + (size_t)N * M);
+        ix.ids_in.resize(N);
+        for (int64_t i = 0; i < N; ++i) ix.ids_in[i] = ids ? ids[i] : (int32_t)i;
+
+        // 1. lexicographic sort of (encoding, id)  -- "in place sort of the encoded dataset"
+        std::vector<KeyRec> rec((size_t)N);
+        parallel_slices(N, host_threads(), [&](int, int64_t lo, int64_t hi) {
+            for (int64_t i = lo; i < hi; ++i) {
+                pack_key(codes + (size_t)i * M, 0, M, rec[i].k);
+                rec[i].pos = (uint32_t)i;
+                rec[i].id = ix.ids_in[i];
+            }
+        });
+        const int idbytes = ids ? 4 : 0;  // positions are already ascending when ids are implicit
+        radix_sort_records(rec, idbytes + M, [idbytes, M](const KeyRec &r, int p) -> int {
+            if (p < idbytes) return (int)(((uint32_t)r.id >> (8 * p)) & 255);
+            return key_byte(r.k, M - 1 - (p - idbytes));
+        });
+
+        // 2. distinct encodings and their id ranges
+        ix.ids_sorted.resize(N);
+        ix.enc_of_pos.resize(N);
+        ix.ebegin.clear();
+        std::vector<KeyRec> distinct;  // key + pos = distinct number
+        for (int64_t i = 0; i < N; ++i) {
+            if (i == 0 || rec[i].k[0] != rec[i - 1].k[0] || rec[i].k[1] != rec[i - 1].k[1]) {
+                ix.ebegin.push_back((uint32_t)i);
+                KeyRec r = rec[i];
+                r.pos = (uint32_t)distinct.size();
+                distinct.push_back(r);
+            }
+            ix.ids_sorted[i] = rec[i].id;
+            ix.enc_of_pos[rec[i].pos] = (uint32_t)(distinct.size() - 1);
+        }
+        ix.ebegin.push_back((uint32_t)N);
+        ix.Nd = (int64_t)distinct.size();
+        ix.max_dup = 0;
+        for (int64_t e = 0; e < ix.Nd; ++e) ix.max_dup = std::max<int64_t>(ix.max_dup, ix.ebegin[e + 1] - ix.ebegin[e]);
+        ix.ecodes.resize((size_t)ix.Nd * M);
+        for (int64_t e = 0; e < ix.Nd; ++e)
+            for (int m = 0; m < M; ++m) ix.ecodes[(size_t)e * M + m] = (uint8_t)key_byte(distinct[e].k, m);
+        { std::vector<KeyRec>().swap(rec); }
+
+        // 3. one tree per chunk group
+        ix.tree.assign(T, HostTree());
+        for (int t = 0; t < T; ++t) {
+            HostTree &tr = ix.tree[t];
+            tr.c0 = cb[t];
+            tr.D = cb[t + 1] - cb[t];
+            if (T == 1) {
+                build_tree(distinct, tr.D, tr);
+                continue;
+            }
+            std::vector<KeyRec> sub((size_t)ix.Nd);
+            for (int64_t e = 0; e < ix.Nd; ++e) {
+                pack_key(ix.ecodes.data() + (size_t)e * M, tr.c0, tr.c0 + tr.D, sub[e].k);
+                sub[e].pos = (uint32_t)e;
+                sub[e].id = 0;
+            }
+            if (t > 0) {  // tree 0 covers a prefix of the full encoding: already in order
+                const int D = tr.D;
+                radix_sort_records(sub, D, [D](const KeyRec &r, int p) -> int { return key_byte(r.k, D - 1 - p); });
+            }
+            tr.leaf_of.resize(ix.Nd);
+            std::vector<KeyRec> uniq;
+            for (int64_t i = 0; i < ix.Nd; ++i) {
+                if (i == 0 || sub[i].k[0] != sub[i - 1].k[0] || sub[i].k[1] != sub[i - 1].k[1]) uniq.push_back(sub[i]);
+                tr.leaf_of[sub[i].pos] = (uint32_t)(uniq.size() - 1);
+            }
+            { std::vector<KeyRec>().swap(sub); }
+            build_tree(uniq, tr.D, tr);
+        }
+
+        // 4. threshold samples: a seeded random subset of the vectors (as encodings, and as positions)
+        {
+            uint64_t s = 0x1509051860ull ^ (uint64_t)N;
+            int64_t want = std::max<int64_t>(ctx->opt.sample_min, ix.Nd / ctx->opt.sample_div);
+            int64_t S = std::min<int64_t>(ix.Nd, want);
+            if (S == ix.Nd) {
+                ix.sample_enc.resize(S);
+                for (int64_t i = 0; i < S; ++i) ix.sample_enc[i] = (uint32_t)i;
+            } else {
+                std::vector<uint32_t> v((size_t)S);
+                for (int64_t i = 0; i < S; ++i) v[i] = ix.enc_of_pos[splitmix64(s) % (uint64_t)N];
+                std::sort(v.begin(), v.end());
+                v.erase(std::unique(v.begin(), v.end()), v.end());
+                ix.sample_enc.swap(v);
+            }
+            want = std::max<int64_t>(ctx->opt.sample_min, N / ctx->opt.sample_div);
+            S = std::min<int64_t>(N, want);
+            if (S == N) {
+                ix.sample_pos.resize(S);
+                for (int64_t i = 0; i < S; ++i) ix.sample_pos[i] = (uint32_t)i;
+            } else {
+                std::vector<uint32_t> v((size_t)S);
+                for (int64_t i = 0; i < S; ++i) v[i] = (uint32_t)(splitmix64(s) % (uint64_t)N);
+                std::sort(v.begin(), v.end());
+                v.erase(std::unique(v.begin(), v.end()), v.end());
+                ix.sample_pos.swap(v);
+            }
+        }
+        ix.built = true;
+        ctx->idx = std::move(ix);
+        ctx->dev_base = nullptr;
+        compute_layout(ctx);
+    } catch (const std::bad_alloc &) {
+        drop_index(ctx);
+        return fail(ctx, ETF_ENOMEM, "out of host memory while building the index");
+    }
+    return ETF_OK;
+}
+
+extern "C" int etf_index_stats(const etf_ctx *ctx, etf_stats *out)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (!out) return fail(ctx, ETF_EINVAL, "output pointer is null");
+    if (!ctx->idx.built) return fail(ctx, ETF_ESTATE, "no index: call etf_index_build first");
+    const HostIndex &ix = ctx->idx;
+    memset(out, 0, sizeof *out);
+    out->M = ix.M; out->K = ix.K; out->T = ix.T;
+    for (int t = 0; t <= ix.T; ++t) out->chunk_begin[t] = ix.chunk_begin[t];
+    out->N = ix.N; out->n_distinct = ix.Nd; out->max_dup = ix.max_dup;
+    for (int t = 0; t < ix.T; ++t) {
+        const HostTree &tr = ix.tree[t];
+        for (int l = 0; l < tr.D; ++l) {
+            out->nI[t][l] = (int64_t)tr.level[l].code.size();
+            out->nL[t][l] = (int64_t)tr.bucket[l].size();
+            out->L1[t] += out->nI[t][l];
+            out->L2[t] += out->nL[t][l];
+            out->sumP[t] += out->nL[t][l] * (tr.D - (l + 1));
+        }
+        out->lookups[t] = out->L1[t] + out->L2[t] + out->sumP[t];
+        out->paper_bytes[t] = 4 * ix.N + 2 * (out->L1[t] + out->L2[t]) + out->sumP[t];
+    }
+    out->device_bytes = ctx->lay.total;
+    return ETF_OK;
+}
+
+extern "C" int64_t etf_index_device_bytes(const etf_ctx *ctx)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (!ctx->idx.built) return fail(ctx, ETF_ESTATE, "no index: call etf_index_build first");
+    return ctx->lay.total;
+}
+
+extern "C" int etf_index_layout(const etf_ctx *ctx, etf_layout *out)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (!out) return fail(ctx, ETF_EINVAL, "output pointer is null");
+    if (!ctx->idx.built) return fail(ctx, ETF_ESTATE, "no index: call etf_index_build first");
+    const HostIndex &ix = ctx->idx;
+    const DevLayout &L = ctx->lay;
+    memset(out, 0xFF, sizeof *out);  // every offset -1 unless set below
+    out->total = L.total;
+    out->codebooks = L.codebooks; out->codes = L.codes; out->ids_in = L.ids_in; out->ids_sorted = L.ids_sorted;
+    out->ebegin = L.ebegin; out->enc_of_pos = L.enc_of_pos; out->ecodes = L.ecodes;
+    out->sample_enc = L.sample_enc; out->sample_pos = L.sample_pos;
+    out->n_sample_enc = (int64_t)ix.sample_enc.size();
+    out->n_sample_pos = (int64_t)ix.sample_pos.size();
+    for (int t = 0; t < ix.T; ++t) {
+        out->leaf_of[t] = L.tree[t].leaf_of;
+        for (int l = 0; l < ix.tree[t].D; ++l) {
+            out->icode[t][l] = L.tree[t].icode[l];
+            out->iparent[t][l] = L.tree[t].iparent[l];
+            out->lcodes[t][l] = L.tree[t].lcodes[l];
+            out->lparent[t][l] = L.tree[t].lparent[l];
+            out->lrow[t][l] = L.tree[t].lrow[l];
+            out->lstride[t][l] = ix.tree[t].bucket[l].stride;
+        }
+    }
+    return ETF_OK;
+}
+
+extern "C" int etf_index_export(const etf_ctx *ctx, void *host_buf, int64_t bytes)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (!host_buf) return fail(ctx, ETF_EINVAL, "output pointer is null");
+    if (!ctx->idx.built) return fail(ctx, ETF_ESTATE, "no index: call etf_index_build first");
+    if (bytes < ctx->lay.total) return fail(ctx, ETF_ENOMEM, "buffer too small: %lld < %lld", (long long)bytes, (long long)ctx->lay.total);
+    memset(host_buf, 0, (size_t)ctx->lay.total);
+    char *base = (char *)host_buf;
+    for_each_image_array(ctx, [base](int64_t off, const void *src, size_t n) {
+        if (n) memcpy(base + off, src, n);
+    });
+    return ETF_OK;
+}

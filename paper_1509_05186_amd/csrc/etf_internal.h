@@ -1,0 +1,108 @@
+// Internal declarations shared by the host and device halves of the library.
+#pragma once
+
+#include <cstdint>
+#include <cstdio>
+#include <functional>
+#include <string>
+#include <vector>
+
+#include "etf.h"
+
+namespace etf {
+
+constexpr int QT = 64;            // queries per tile: one partial-sum row is QT floats (256 bytes)
+constexpr uint32_t NO_PARENT = 0xFFFFFFFFu;
+
+// One internal level of one tree, in sorted (= breadth-first) order.
+struct HostLevel {
+    std::vector<uint8_t> code;     // chunk value of the node
+    std::vector<uint32_t> parent;  // index into the previous level (NO_PARENT at level 1)
+};
+
+// All leaves of one tree whose own chunk is at the same level: equal record width.
+struct HostBucket {
+    int width = 0;                 // 1 + postfix length
+    int stride = 0;                // record stride in bytes (width rounded up to 4)
+    std::vector<uint8_t> codes;    // [n][stride], own chunk first, then the postfix, zero padded
+    std::vector<uint32_t> parent;  // index into internal level (level-1), NO_PARENT for level 1
+    std::vector<uint32_t> row;     // leaf number in sorted order = row of the tree's result table
+    size_t size() const { return parent.size(); }
+};
+
+struct HostTree {
+    int c0 = 0, D = 0;                      // covers chunks [c0, c0 + D)
+    int64_t U = 0;                          // distinct sub-encodings = leaves
+    std::vector<HostLevel> level;           // [D]   (entry l = level l+1; the last one is always empty)
+    std::vector<HostBucket> bucket;         // [D]   (entry l = leaves at level l+1)
+    std::vector<uint32_t> leaf_of;          // [n_distinct] leaf row of every distinct full encoding (empty if T == 1)
+};
+
+struct HostIndex {
+    bool built = false;
+    int M = 0, K = 0, T = 0;
+    int64_t N = 0, Nd = 0, max_dup = 0;
+    std::vector<int32_t> chunk_begin;       // [T+1]
+    std::vector<uint8_t> codes;             // [N][M] input order
+    std::vector<int32_t> ids_in;            // [N] ids in input order
+    std::vector<int32_t> ids_sorted;        // [N] ids in (encoding, id) order
+    std::vector<uint32_t> ebegin;           // [Nd+1] range of ids_sorted of every distinct encoding
+    std::vector<uint32_t> enc_of_pos;       // [N] distinct-encoding number of the n-th input vector
+    std::vector<uint8_t> ecodes;            // [Nd][M] distinct encodings in sorted order
+    std::vector<uint32_t> sample_enc;       // sorted distinct-encoding numbers of the threshold sample
+    std::vector<uint32_t> sample_pos;       // input positions of the flat-mode threshold sample
+    std::vector<HostTree> tree;
+};
+
+// Device image: offsets (bytes) into the uploaded buffer.
+struct DevTreeLayout {
+    int64_t leaf_of = -1;
+    int64_t icode[ETF_MAX_M], iparent[ETF_MAX_M];
+    int64_t lcodes[ETF_MAX_M], lparent[ETF_MAX_M], lrow[ETF_MAX_M];
+};
+
+struct DevLayout {
+    int64_t total = 0;
+    int64_t codebooks = 0, codes = 0, ids_in = 0, ids_sorted = 0, ebegin = 0, enc_of_pos = 0, ecodes = 0,
+            sample_enc = 0, sample_pos = 0;
+    std::vector<DevTreeLayout> tree;
+};
+
+struct Options {
+    int64_t ws_cap_bytes = (int64_t)8 << 30;
+    int64_t force_fallback = 0;
+    int64_t sample_min = 32768;
+    int64_t sample_div = 32;
+    int64_t cand_cap = 0;
+};
+
+}  // namespace etf
+
+struct etf_ctx {
+    int device = -1;
+    void *stream = nullptr;
+    mutable std::string err;
+    // quantiser
+    int d = 0, M = 0, K = 0, ds = 0;
+    std::vector<float> codebooks;           // [M][K][ds]
+    // index
+    etf::HostIndex idx;
+    etf::DevLayout lay;
+    char *dev_base = nullptr;               // caller-owned buffer holding the device image
+    etf::Options opt;
+    // diagnostics of the most recent search (device address inside the caller's workspace)
+    void *last_flag_count = nullptr;
+};
+
+namespace etf {
+
+int fail(const etf_ctx *ctx, int code, const char *fmt, ...);
+void compute_layout(etf_ctx *ctx);
+// calls put(offset, pointer, bytes) for every array of the device image
+void for_each_image_array(const etf_ctx *ctx, const std::function<void(int64_t, const void *, size_t)> &put);
+
+// parallel for over [0, n) in contiguous slices, on up to `threads` std::threads
+void parallel_slices(int64_t n, int threads, const std::function<void(int, int64_t, int64_t)> &fn);
+int host_threads();
+
+}  // namespace etf

@@ -1,0 +1,678 @@
+// HIP kernels for gfx950 (wave64).  Included only by etf_device.hip.
+//
+// Data layout shared by all kernels.  Queries are processed in tiles of QT = 64: lane q of a wave
+// owns query q of the tile.  Every per-node quantity is a *row* of 64 floats (256 bytes), so a wave
+// reads or writes one row with one fully coalesced instruction:
+//   lutT   [tile][M][K][64]    transposed lookup tables: row (m, c) holds LUT[q][m][c] for the 64 queries
+//   part   [tile][nodes][64]   partial sums of the internal nodes of one tree level
+//   leafp  [tile][leaves][64]  per-tree result table: one row per leaf (distinct sub-encoding)
+// Kernels that keep several table slices in LDS split a tile into G sub-tiles of Qs = 64 / G queries;
+// a wave then works on G nodes at a time (lane = g * Qs + q).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "etf_internal.h"
+
+namespace etf {
+
+constexpr int WAVE = 64;
+
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+__device__ __forceinline__ int64_t uniform64(int64_t v)
+{
+    uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// ------------------------------------------------------------------------------------------------
+// S1  lookup tables (paper Eq. 1, first term on each group's own dimensions), plain float32 form.
+//     grid (tiles, M), block 256: wave w computes codewords [64w, 64w+64) for the tile's 64 queries.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_lut_direct(const float *__restrict__ queries, int64_t Q, int64_t q0, int d,
+                                                    int M, int K, const float *__restrict__ codebooks,
+                                                    float *__restrict__ lutT, float *__restrict__ lut_public)
+{
+    const int tile = blockIdx.x, m = blockIdx.y;
+    const int lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6);
+    const int ds = d / M;
+    const int64_t q = q0 + (int64_t)tile * QT + lane;
+    const bool live = q < Q;
+    const float *qv = queries + (live ? q : 0) * d + (int64_t)m * ds;
+    const int kbase = w * 64;
+    float acc[64];
+#pragma unroll
+    for (int i = 0; i < 64; ++i) acc[i] = 0.f;
+    for (int j0 = 0; j0 < ds; j0 += 4) {
+        float x[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) x[jj] = (live && j0 + jj < ds) ? qv[j0 + jj] : 0.f;
+        const int nj = min(4, ds - j0);
+#pragma unroll
+        for (int i = 0; i < 64; ++i) {
+            const int k = kbase + i;
+            if (k < K) {
+                const float *c = codebooks + ((int64_t)m * K + k) * ds + j0;
+                for (int jj = 0; jj < nj; ++jj) {
+                    float t = x[jj] - c[jj];
+                    acc[i] = fmaf(t, t, acc[i]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 64; ++i) {
+        const int k = kbase + i;
+        if (k < K) {
+            if (lutT) lutT[(((int64_t)tile * M + m) * K + k) * QT + lane] = acc[i];
+            if (lut_public && live) lut_public[(q * M + m) * K + k] = acc[i];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// S2  one internal level of one tree:  part[l][i] = part[l-1][parent[i]] + LUT row (m, code[i]).
+//     grid (blocks, tiles), block 256; every wave takes `per_wave` consecutive nodes.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_level(const uint8_t *__restrict__ icode, const uint32_t *__restrict__ iparent,
+                                               int64_t n, const float *__restrict__ prev, int64_t nprev,
+                                               float *__restrict__ out, const float *__restrict__ lutT, int M, int K,
+                                               int m, int per_wave)
+{
+    const int tile = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int64_t wv = (int64_t)blockIdx.x * 4 + uniform(threadIdx.x >> 6);
+    const int64_t lo = wv * per_wave;
+    const int64_t hi = min(n, lo + per_wave);
+    const float *lrow = lutT + ((int64_t)tile * M + m) * K * QT + lane;
+    const float *prow = prev ? prev + (int64_t)tile * nprev * QT + lane : nullptr;
+    float *orow = out + (int64_t)tile * n * QT + lane;
+#pragma unroll 4
+    for (int64_t i = lo; i < hi; ++i) {
+        const int code = icode[i];
+        float v = lrow[(int64_t)code * QT];
+        if (prow) v = prow[(int64_t)iparent[i] * QT] + v;
+        orow[i * QT] = v;
+    }
+}
+
+// Stage `width` consecutive table slices (chunks m0 .. m0+width-1) of sub-tile g into LDS as [c][K][Qs].
+template <int G>
+__device__ __forceinline__ void stage_slices(float *lds, const float *__restrict__ lutT, int tile, int g, int M, int K,
+                                             int m0, int width)
+{
+    constexpr int Qs = WAVE / G;
+    const int total = width * K * Qs;
+    const float *src = lutT + ((int64_t)tile * M + m0) * K * QT + g * Qs;
+    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+        const int row = idx / Qs, qq = idx % Qs;  // row = c * K + k
+        lds[idx] = src[(int64_t)row * QT + qq];
+    }
+    __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------------
+// S3  one leaf bucket of one tree (all leaves whose own chunk is at the same level, so with the same
+//     postfix length):  leafp[row] = part[level-1][parent] + LUT(own chunk) + LUT(postfix chunks ...),
+//     added left to right.  The bucket's `width` table slices live in LDS; lane = g*Qs + q handles
+//     leaf (step*G + g) for query q of the sub-tile.
+//     grid (blocks, G, tiles), block 256..1024, dynamic LDS = width*K*Qs*4 bytes.
+// ------------------------------------------------------------------------------------------------
+template <int G, int NDW>
+__global__ void k_leaf(const uint8_t *__restrict__ lcodes, int width, const uint32_t *__restrict__ lparent,
+                       const uint32_t *__restrict__ lrow, int64_t n, const float *__restrict__ prev, int64_t nprev,
+                       float *__restrict__ out, int64_t U, const float *__restrict__ lutT, int M, int K, int m0,
+                       int per_block)
+{
+    constexpr int Qs = WAVE / G;
+    extern __shared__ float lds[];
+    const int tile = blockIdx.z, sub = blockIdx.y;
+    stage_slices<G>(lds, lutT, tile, sub, M, K, m0, width);
+    const int lane = threadIdx.x & 63;
+    const int lg = lane / Qs, qq = lane % Qs;
+    const int w = uniform(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    const int64_t blo = (int64_t)blockIdx.x * per_block;
+    const int64_t bhi = min(n, blo + per_block);
+    const int col = sub * Qs + qq;
+    const float *prow = prev ? prev + (int64_t)tile * nprev * QT + col : nullptr;
+    float *orow = out + (int64_t)tile * U * QT + col;
+    const uint32_t *rec = reinterpret_cast<const uint32_t *>(lcodes);
+    for (int64_t j = blo + (int64_t)w * G + lg; j < bhi; j += (int64_t)nw * G) {
+        uint32_t dw[NDW];
+#pragma unroll
+        for (int i = 0; i < NDW; ++i) dw[i] = rec[j * NDW + i];
+        float acc = prow ? prow[(int64_t)lparent[j] * QT] : 0.f;
+#pragma unroll
+        for (int i = 0; i < NDW; ++i) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int c = i * 4 + b;
+                if (c < width) {
+                    const int code = (dw[i] >> (8 * b)) & 255;
+                    acc += lds[(c * K + code) * Qs + qq];
+                }
+            }
+        }
+        orow[(int64_t)lrow[j] * QT] = acc;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Consumers of a finished distance.  One distance belongs to (item, query lane).
+// ------------------------------------------------------------------------------------------------
+enum { OUT_ALLPAIRS = 0, OUT_SAMPLE = 1, OUT_FILTER = 2 };
+
+struct OutArgs {
+    // OUT_ALLPAIRS
+    float *dist;        // [Q][N], rows q0.. of this batch
+    int64_t N;          // row length
+    int64_t nq;         // live queries of this batch (rows beyond are not written)
+    // OUT_SAMPLE
+    float *sdist;       // [tile][S][64]
+    int64_t S;
+    // OUT_FILTER
+    const float *tau;   // [tiles*64]
+    uint32_t *cnt;      // [tiles*64]
+    uint64_t *cand;     // [tiles*64][C]
+    uint32_t C;
+};
+
+__device__ __forceinline__ void emit_filter(const OutArgs &o, int tile, int col, float tauv, float d, uint32_t item)
+{
+    if (d <= tauv) {
+        const int64_t ql = (int64_t)tile * QT + col;
+        const uint32_t pos = atomicAdd(&o.cnt[ql], 1u);
+        if (pos < o.C) o.cand[ql * o.C + pos] = ((uint64_t)__float_as_uint(d) << 32) | item;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// B0  flat ADC: every encoding costs M lookups.  All M slices in LDS, lane = g*Qs + q.
+//     items: ALLPAIRS -> n in [0,N) (input order); SAMPLE -> sample_pos[i]; FILTER -> n in [0,N).
+//     grid (blocks, G, tiles).
+// ------------------------------------------------------------------------------------------------
+template <int G, int MODE>
+__global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const uint32_t *__restrict__ sample,
+                       const float *__restrict__ lutT, int M, int K, int per_block, OutArgs o)
+{
+    constexpr int Qs = WAVE / G;
+    extern __shared__ float lds[];
+    const int tile = blockIdx.z, sub = blockIdx.y;
+    stage_slices<G>(lds, lutT, tile, sub, M, K, 0, M);
+    const int lane = threadIdx.x & 63;
+    const int lg = lane / Qs, qq = lane % Qs;
+    const int w = uniform(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    const int64_t blo = (int64_t)blockIdx.x * per_block;
+    const int64_t bhi = min(nitems, blo + per_block);
+    const int col = sub * Qs + qq;
+    float tauv = 0.f;
+    if (MODE == OUT_FILTER) tauv = o.tau[(int64_t)tile * QT + col];
+    for (int64_t j = blo + (int64_t)w * G + lg; j < bhi; j += (int64_t)nw * G) {
+        const int64_t n = (MODE == OUT_SAMPLE) ? (int64_t)sample[j] : j;
+        const uint8_t *c = codes + n * M;
+        float acc = 0.f;
+        if ((M & 3) == 0) {
+            const uint32_t *c4 = reinterpret_cast<const uint32_t *>(c);
+            for (int i = 0; i < (M >> 2); ++i) {
+                const uint32_t dw = c4[i];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc += lds[((i * 4 + b) * K + ((dw >> (8 * b)) & 255)) * Qs + qq];
+            }
+        } else {
+            for (int m = 0; m < M; ++m) acc += lds[(m * K + c[m]) * Qs + qq];
+        }
+        if (MODE == OUT_ALLPAIRS) {
+            const int64_t ql = (int64_t)tile * QT + col;
+            if (ql < o.nq) o.dist[ql * o.N + n] = acc;
+        } else if (MODE == OUT_SAMPLE) {
+            o.sdist[((int64_t)tile * o.S + j) * QT + col] = acc;
+        } else {
+            emit_filter(o, tile, col, tauv, acc, (uint32_t)n);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// S4  forest reduction (paper "Encoding Forests": per-tree result arrays summed per vector):
+//     dist(e) = leafp[0][leaf_of[0][e]] + leafp[1][leaf_of[1][e]] + ...   (tree order).
+//     Lane = query; a wave walks consecutive items, each item is T coalesced row reads.
+//     items: FILTER -> distinct encodings e; SAMPLE -> sample_enc[i]; ALLPAIRS -> input positions n
+//     (e = enc_of_pos[n]), written transposed through LDS so that dist[q][n..n+63] is one store.
+//     grid (blocks, tiles), block 256.
+// ------------------------------------------------------------------------------------------------
+struct ReduceArgs {
+    const float *leafp[ETF_MAX_M];
+    const uint32_t *leaf_of[ETF_MAX_M];  // nullptr: identity (single tree)
+    int64_t U[ETF_MAX_M];
+    int T;
+};
+
+__device__ __forceinline__ float reduce_one(const ReduceArgs &r, int tile, int lane, uint32_t e)
+{
+    float d = 0.f;
+    for (int t = 0; t < r.T; ++t) {
+        const uint32_t row = r.leaf_of[t] ? r.leaf_of[t][e] : e;
+        const float v = r.leafp[t][((int64_t)tile * r.U[t] + row) * QT + lane];
+        d = (t == 0) ? v : d + v;
+    }
+    return d;
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void k_reduce(ReduceArgs r, int64_t nitems, const uint32_t *__restrict__ map,
+                                                int per_wave, OutArgs o)
+{
+    const int tile = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int w = uniform(threadIdx.x >> 6);
+    const int64_t wv = (int64_t)blockIdx.x * 4 + w;
+    const int64_t lo = wv * per_wave;
+    const int64_t hi = min(nitems, lo + per_wave);
+    if (MODE == OUT_ALLPAIRS) {
+        __shared__ float tbuf[4][64][65];
+        for (int64_t n0 = lo; n0 < hi; n0 += 64) {
+            const int cntn = (int)min<int64_t>(64, hi - n0);
+            for (int jj = 0; jj < cntn; ++jj) tbuf[w][jj][lane] = reduce_one(r, tile, lane, map[n0 + jj]);
+            __builtin_amdgcn_wave_barrier();
+            for (int qq = 0; qq < 64; ++qq) {
+                const int64_t ql = (int64_t)tile * QT + qq;
+                if (ql < o.nq && lane < cntn) o.dist[ql * o.N + n0 + lane] = tbuf[w][lane][qq];
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    } else if (MODE == OUT_SAMPLE) {
+        for (int64_t i = lo; i < hi; ++i)
+            o.sdist[((int64_t)tile * o.S + i) * QT + lane] = reduce_one(r, tile, lane, map[i]);
+    } else {
+        const float tauv = o.tau[(int64_t)tile * QT + lane];
+#pragma unroll 2
+        for (int64_t e = lo; e < hi; ++e) emit_filter(o, tile, lane, tauv, reduce_one(r, tile, lane, (uint32_t)e), (uint32_t)e);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// S5a  per-query threshold from the sample: an upper bound of the k-th smallest sample distance, found
+//      by a most-significant-digit radix select on the float bit patterns (distances are >= 0, so the
+//      patterns order like the values).  `passes` digits of 8 bits are resolved; the bound is the top
+//      of the remaining bucket.  Any subset of the database gives a valid bound: at least k database
+//      encodings are at or below it.
+//      grid (tiles), block 1024, LDS hist[256][64].
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void k_tau(const float *__restrict__ sdist, int64_t S, int k, int passes,
+                                              int64_t nq, float *__restrict__ tau)
+{
+    __shared__ uint32_t hist[256][64];
+    __shared__ uint32_t s_prefix[64], s_rank[64];
+    const int tile = blockIdx.x;
+    const int lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    const int64_t ql = (int64_t)tile * QT + lane;
+    if (threadIdx.x < 64) {
+        s_prefix[lane] = 0;
+        s_rank[lane] = (uint32_t)k;
+    }
+    if (S < k) {  // too few samples: no bound
+        if (threadIdx.x < 64) tau[ql] = (ql < nq) ? __uint_as_float(0x7F800000u) : -1.f;
+        return;
+    }
+    const float *col = sdist + (int64_t)tile * S * QT + lane;
+    int shift = 24;
+    for (int p = 0; p < passes; ++p, shift -= 8) {
+        for (int i = threadIdx.x; i < 256 * 64; i += blockDim.x) (&hist[0][0])[i] = 0;
+        __syncthreads();
+        const uint32_t prefix = s_prefix[lane];
+        for (int64_t s = w; s < S; s += nw) {
+            const uint32_t v = __float_as_uint(col[s * QT]);
+            const bool match = (p == 0) || ((v >> (shift + 8)) == (prefix >> (shift + 8)));
+            if (match) atomicAdd(&hist[(v >> shift) & 255][lane], 1u);
+        }
+        __syncthreads();
+        if (threadIdx.x < 64) {
+            uint32_t rank = s_rank[lane], below = 0;
+            int b = 0;
+            for (; b < 255; ++b) {
+                const uint32_t h = hist[b][lane];
+                if (below + h >= rank) break;
+                below += h;
+            }
+            s_prefix[lane] = prefix | ((uint32_t)b << shift);
+            s_rank[lane] = rank - below;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x < 64) {
+        const uint32_t top = s_prefix[lane] | ((shift + 8 > 0) ? ((1u << (shift + 8)) - 1u) : 0u);
+        tau[ql] = (ql < nq) ? __uint_as_float(top) : -1.f;
+    }
+}
+
+__global__ void k_fill_u32(uint32_t *p, int64_t n, uint32_t v)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__global__ void k_fill_f32(float *p, int64_t n, int64_t nlive, float v, float vdead)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = i < nlive ? v : vdead;
+}
+
+// ------------------------------------------------------------------------------------------------
+// block-level helpers (256 threads)
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void bitonic_sort_u64(uint64_t *a, int n)
+{
+    for (int k = 2; k <= n; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = threadIdx.x; i < n; i += blockDim.x) {
+                const int ixj = i ^ j;
+                if (ixj > i) {
+                    const bool up = (i & k) == 0;
+                    const uint64_t x = a[i], y = a[ixj];
+                    if ((x > y) == up) {
+                        a[i] = y;
+                        a[ixj] = x;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+}
+
+// in-place inclusive scan of v[0..n) (n <= 256 * ipt), 256 threads, `tmp` has 256 entries
+__device__ __forceinline__ void block_inclusive_scan(uint32_t *v, int n, uint32_t *tmp)
+{
+    const int ipt = (n + 255) / 256;
+    const int lo = threadIdx.x * ipt, hi = min(n, lo + ipt);
+    uint32_t s = 0;
+    for (int i = lo; i < hi; ++i) s += v[i];
+    tmp[threadIdx.x] = s;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+        uint32_t add = (threadIdx.x >= off) ? tmp[threadIdx.x - off] : 0;
+        __syncthreads();
+        tmp[threadIdx.x] += add;
+        __syncthreads();
+    }
+    uint32_t run = tmp[threadIdx.x] - s;
+    for (int i = lo; i < hi; ++i) {
+        run += v[i];
+        v[i] = run;
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ int pow2_at_least(int n)
+{
+    int p = 1;
+    while (p < n) p <<= 1;
+    return p;
+}
+
+// ------------------------------------------------------------------------------------------------
+// S5b  final selection of one query from its candidate list (all encodings at or below the bound).
+//      Only the k closest candidate encodings can contribute; they are sorted, expanded into their
+//      vector ids (each encoding at most as many as are still needed), sorted by (distance, id), and
+//      the first k are written.  Anything that does not fit the fixed LDS buffers (candidate overflow,
+//      huge groups of exactly equal distances) is flagged for the exact whole-database kernel.
+//      grid (queries of the batch), block 256.
+// ------------------------------------------------------------------------------------------------
+constexpr int KEPT_CAP = 2048;
+constexpr int EXP_CAP = 4096;
+
+struct SelectArgs {
+    const uint32_t *cnt;     // [nq]
+    const uint64_t *cand;    // [nq][C]
+    uint32_t C;
+    const uint32_t *ebegin;  // id range of every item, or nullptr: one id per item
+    const int32_t *ids;      // ids_sorted (with ebegin) or ids in item order
+    int k;
+    int32_t *out_ids;        // [nq][k]
+    float *out_dist;         // [nq][k]
+    uint32_t *flag;          // [nq]  set to 1 when the query needs the exact kernel
+};
+
+__global__ __launch_bounds__(256) void k_select(SelectArgs a)
+{
+    __shared__ uint64_t kept[KEPT_CAP];
+    __shared__ uint64_t xkeys[EXP_CAP];
+    __shared__ uint32_t sc[KEPT_CAP];
+    __shared__ uint32_t tmp[256];
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_a, s_b, s_c, s_d;
+    const int64_t ql = blockIdx.x;
+    if (a.flag[ql]) return;  // already routed to the exact kernel
+    const uint32_t craw = a.cnt[ql];
+    if (craw > a.C) {
+        if (threadIdx.x == 0) a.flag[ql] = 1;
+        return;
+    }
+    const int c = (int)craw;
+    const uint64_t *cand = a.cand + ql * a.C;
+    const int k = a.k;
+    // 1. the value of the min(k, c)-th closest candidate
+    uint32_t vstar = 0xFFFFFFFFu;
+    if (c > KEPT_CAP) {
+        uint32_t prefix = 0, rank = (uint32_t)min(k, c);
+        for (int p = 0, shift = 24; p < 4; ++p, shift -= 8) {
+            hist[threadIdx.x] = 0;
+            __syncthreads();
+            for (int i = threadIdx.x; i < c; i += 256) {
+                const uint32_t v = (uint32_t)(cand[i] >> 32);
+                if (p == 0 || (v >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(v >> shift) & 255], 1u);
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                uint32_t below = 0;
+                int b = 0;
+                for (; b < 255; ++b) {
+                    if (below + hist[b] >= rank) break;
+                    below += hist[b];
+                }
+                s_a = prefix | ((uint32_t)b << shift);
+                s_b = rank - below;
+            }
+            __syncthreads();
+            prefix = s_a;
+            rank = s_b;
+            __syncthreads();
+        }
+        vstar = prefix;
+    }
+    // 2. keep the candidates at or below it, sorted by (distance bits, item)
+    if (threadIdx.x == 0) s_c = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < c; i += 256) {
+        const uint64_t key = cand[i];
+        if ((uint32_t)(key >> 32) <= vstar) {
+            const uint32_t pos = atomicAdd(&s_c, 1u);
+            if (pos < KEPT_CAP) kept[pos] = key;
+        }
+    }
+    __syncthreads();
+    const int nk = (int)s_c;
+    if (nk > KEPT_CAP || nk == 0) {
+        if (threadIdx.x == 0) a.flag[ql] = 1;
+        return;
+    }
+    const int nk2 = pow2_at_least(nk);
+    for (int i = nk + threadIdx.x; i < nk2; i += 256) kept[i] = ~0ull;
+    __syncthreads();
+    bitonic_sort_u64(kept, nk2);
+    // 3. how many vectors each kept encoding holds (never more than k matter)
+    for (int i = threadIdx.x; i < nk; i += 256) {
+        const uint32_t e = (uint32_t)kept[i];
+        const uint32_t mult = a.ebegin ? a.ebegin[e + 1] - a.ebegin[e] : 1u;
+        sc[i] = min(mult, (uint32_t)k);
+    }
+    __syncthreads();
+    block_inclusive_scan(sc, nk, tmp);
+    if (sc[nk - 1] < (uint32_t)k) {  // the bound was not valid: cannot happen with a sample of the database
+        if (threadIdx.x == 0) a.flag[ql] = 1;
+        return;
+    }
+    // first position whose running count reaches k, and the run of equal distances around it
+    for (int i = threadIdx.x; i < nk; i += 256)
+        if (sc[i] >= (uint32_t)k && (i == 0 || sc[i - 1] < (uint32_t)k)) s_a = (uint32_t)i;
+    __syncthreads();
+    const uint32_t dstar = (uint32_t)(kept[s_a] >> 32);
+    for (int i = threadIdx.x; i < nk; i += 256) {
+        const uint32_t v = (uint32_t)(kept[i] >> 32);
+        if (v == dstar && (i == 0 || (uint32_t)(kept[i - 1] >> 32) != dstar)) s_b = (uint32_t)i;          // run start
+        if (v == dstar && (i == nk - 1 || (uint32_t)(kept[i + 1] >> 32) != dstar)) s_d = (uint32_t)i + 1;  // run end
+    }
+    __syncthreads();
+    const int ta = (int)s_b, tb = (int)s_d;
+    const uint32_t before = ta > 0 ? sc[ta - 1] : 0;  // vectors strictly closer than dstar (< k)
+    const uint32_t need = (uint32_t)k - before;        // still to take from the run of equal distances
+    __syncthreads();
+    // 4. contribution of every kept encoding, exclusive offsets, expansion into (distance, id) keys
+    for (int i = threadIdx.x; i < nk; i += 256) {
+        const uint32_t e = (uint32_t)kept[i];
+        const uint32_t mult = a.ebegin ? a.ebegin[e + 1] - a.ebegin[e] : 1u;
+        sc[i] = i < ta ? mult : (i < tb ? min(mult, need) : 0u);
+    }
+    __syncthreads();
+    block_inclusive_scan(sc, nk, tmp);
+    const uint32_t xtotal = sc[nk - 1];
+    if (xtotal > EXP_CAP) {
+        if (threadIdx.x == 0) a.flag[ql] = 1;
+        return;
+    }
+    for (int i = threadIdx.x; i < tb; i += 256) {
+        const uint32_t end = sc[i], beg = i > 0 ? sc[i - 1] : 0;
+        const uint32_t e = (uint32_t)kept[i];
+        const uint64_t hi = kept[i] & 0xFFFFFFFF00000000ull;
+        const uint32_t first = a.ebegin ? a.ebegin[e] : e;
+        for (uint32_t j = 0; j < end - beg; ++j) xkeys[beg + j] = hi | (uint32_t)a.ids[first + j];
+    }
+    const int nx2 = pow2_at_least((int)xtotal);
+    for (int i = (int)xtotal + threadIdx.x; i < nx2; i += 256) xkeys[i] = ~0ull;
+    __syncthreads();
+    bitonic_sort_u64(xkeys, nx2);
+    for (int i = threadIdx.x; i < k; i += 256) {
+        a.out_ids[ql * k + i] = (int32_t)(uint32_t)xkeys[i];
+        a.out_dist[ql * k + i] = __uint_as_float((uint32_t)(xkeys[i] >> 32));
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// S5c  exact selection over the whole database for one query, without any buffer that depends on the
+//      data: a most-significant-digit radix select on the 64-bit key (distance bits, id), 8 passes of
+//      8 bits, each pass recomputing the distances from the codes, then one collecting pass.  The sum
+//      is associated exactly as in the mode's main path (left to right inside a chunk group, groups in
+//      order), so both paths produce the same float32 values.
+//      grid (queries of the batch), block 256; only flagged queries do any work.
+// ------------------------------------------------------------------------------------------------
+struct ExactArgs {
+    const uint32_t *flag;     // [nq]
+    uint32_t *nflag;          // running count of queries answered here
+    const float *lutT;        // [tiles][M][K][64]
+    int M, K, T;
+    int32_t chunk_begin[ETF_MAX_M + 1];
+    const uint8_t *codes;     // [rows][M]
+    int64_t rows;
+    const uint32_t *ebegin;   // id ranges per row or nullptr (one id per row)
+    const int32_t *ids;
+    int k;
+    int32_t *out_ids;
+    float *out_dist;
+};
+
+__device__ __forceinline__ float exact_distance(const ExactArgs &a, const float *lut, const uint8_t *c)
+{
+    float d = 0.f;
+    for (int t = 0; t < a.T; ++t) {
+        float s = 0.f;
+        for (int m = a.chunk_begin[t]; m < a.chunk_begin[t + 1]; ++m) {
+            const float v = lut[m * a.K + c[m]];
+            s = (m == a.chunk_begin[t]) ? v : s + v;
+        }
+        d = (t == 0) ? s : d + s;
+    }
+    return d;
+}
+
+__global__ __launch_bounds__(256) void k_exact(ExactArgs a)
+{
+    __shared__ float lut[ETF_MAX_M * 256];
+    __shared__ uint32_t hist[256];
+    __shared__ uint64_t okeys[ETF_MAX_TOPK];
+    __shared__ uint32_t s_digit, s_rank, s_n;
+    const int64_t ql = blockIdx.x;
+    if (!a.flag[ql]) return;
+    if (threadIdx.x == 0) atomicAdd(a.nflag, 1u);
+    const int tile = (int)(ql / QT), col = (int)(ql % QT);
+    for (int i = threadIdx.x; i < a.M * a.K; i += 256) lut[i] = a.lutT[((int64_t)tile * a.M * a.K + i) * QT + col];
+    __syncthreads();
+    const uint32_t k = (uint32_t)a.k;
+    uint64_t prefix = 0;
+    uint32_t rank = k;
+    for (int p = 0, shift = 56; p < 8; ++p, shift -= 8) {
+        hist[threadIdx.x] = 0;
+        __syncthreads();
+        for (int64_t e = threadIdx.x; e < a.rows; e += 256) {
+            const uint32_t v = __float_as_uint(exact_distance(a, lut, a.codes + e * a.M));
+            const uint32_t first = a.ebegin ? a.ebegin[e] : (uint32_t)e;
+            const uint32_t mult = min(a.ebegin ? a.ebegin[e + 1] - first : 1u, k);
+            if (p < 4) {
+                const int sh = shift - 32;  // digit position inside the distance bits
+                if (p == 0 || (v >> (sh + 8)) == ((uint32_t)(prefix >> 32) >> (sh + 8)))
+                    atomicAdd(&hist[(v >> sh) & 255], mult);
+            } else if (v == (uint32_t)(prefix >> 32)) {
+                for (uint32_t j = 0; j < mult; ++j) {
+                    const uint32_t id = (uint32_t)a.ids[first + j];
+                    if (p == 4 || (id >> (shift + 8)) == ((uint32_t)prefix >> (shift + 8)))
+                        atomicAdd(&hist[(id >> shift) & 255], 1u);
+                }
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t below = 0;
+            int b = 0;
+            for (; b < 255; ++b) {
+                if (below + hist[b] >= rank) break;
+                below += hist[b];
+            }
+            s_digit = (uint32_t)b;
+            s_rank = rank - below;
+        }
+        __syncthreads();
+        prefix |= (uint64_t)s_digit << shift;
+        rank = s_rank;
+        __syncthreads();
+    }
+    // collect every (distance, id) key at or below the k-th: exactly k of them
+    if (threadIdx.x == 0) s_n = 0;
+    __syncthreads();
+    const uint32_t vk = (uint32_t)(prefix >> 32), idk = (uint32_t)prefix;
+    for (int64_t e = threadIdx.x; e < a.rows; e += 256) {
+        const uint32_t v = __float_as_uint(exact_distance(a, lut, a.codes + e * a.M));
+        if (v > vk) continue;
+        const uint32_t first = a.ebegin ? a.ebegin[e] : (uint32_t)e;
+        const uint32_t mult = min(a.ebegin ? a.ebegin[e + 1] - first : 1u, k);
+        for (uint32_t j = 0; j < mult; ++j) {
+            const uint32_t id = (uint32_t)a.ids[first + j];
+            if (v < vk || id <= idk) {
+                const uint32_t pos = atomicAdd(&s_n, 1u);
+                if (pos < ETF_MAX_TOPK) okeys[pos] = ((uint64_t)v << 32) | id;
+            }
+        }
+    }
+    __syncthreads();
+    const int n = (int)min(s_n, (uint32_t)ETF_MAX_TOPK);
+    const int n2 = pow2_at_least(max(n, 1));
+    for (int i = n + threadIdx.x; i < n2; i += 256) okeys[i] = ~0ull;
+    __syncthreads();
+    bitonic_sort_u64(okeys, n2);
+    for (int i = threadIdx.x; i < a.k; i += 256) {
+        a.out_ids[ql * a.k + i] = (int32_t)(uint32_t)okeys[i];
+        a.out_dist[ql * a.k + i] = __uint_as_float((uint32_t)(okeys[i] >> 32));
+    }
+}
+
+}  // namespace etf

@@ -1,0 +1,64 @@
+"""Comparison helpers shared by the GPU parity tests, the smoke check and the benchmark."""
+import numpy as np
+
+REL_TOL = 1e-5          # relative tolerance on float32 distances against the float64 oracle
+
+
+def dist_tol(ref):
+    """|gpu - oracle| <= 1e-5 * |oracle|, with an absolute floor tied to the typical distance of the
+    query for the degenerate case of an oracle distance of (almost) zero."""
+    ref = np.asarray(ref, dtype=np.float64)
+    floor = 1e-8 * np.median(np.abs(ref)) if ref.size else 0.0
+    return REL_TOL * np.abs(ref) + floor
+
+
+def assert_distances_close(gpu, ref, what=""):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
+    err = np.abs(gpu - ref)
+    tol = REL_TOL * np.abs(ref) + 1e-8 * np.median(np.abs(ref), axis=-1, keepdims=True)
+    bad = err > tol
+    assert not bad.any(), "%s: %d of %d distances off, worst relative error %.3g" % (
+        what, int(bad.sum()), bad.size, float((err / np.maximum(np.abs(ref), 1e-300)).max()))
+
+
+def assert_topk_matches(gpu_ids, gpu_dist, ref_all, ids, k, what=""):
+    """Tie-aware check of one query's top-k against the oracle's distances to every vector.
+
+    ref_all[n] is the oracle distance of input position n, ids[n] its id.  Required:
+      - k distinct, valid ids, ordered ascending by (returned distance, id);
+      - each returned distance agrees with the oracle distance of the returned id;
+      - the returned distances agree, position by position, with the oracle's sorted top-k;
+      - nothing left out is closer (beyond the tolerance) than the last one returned;
+      - outside the tolerance band around the k-th distance the id lists are identical.
+    """
+    gpu_ids = np.asarray(gpu_ids).astype(np.int64)
+    gpu_dist = np.asarray(gpu_dist, dtype=np.float64)
+    ref_all = np.asarray(ref_all, dtype=np.float64)
+    ids = np.asarray(ids).astype(np.int64)
+    assert gpu_ids.shape == (k,) and gpu_dist.shape == (k,), what
+    assert len(set(gpu_ids.tolist())) == k, what + ": duplicate ids"
+    pos_of = {int(v): i for i, v in enumerate(ids)}
+    assert all(int(i) in pos_of for i in gpu_ids), what + ": unknown id"
+    # ordering by (distance, id)
+    for a in range(k - 1):
+        assert (gpu_dist[a], gpu_ids[a]) < (gpu_dist[a + 1], gpu_ids[a + 1]), what + ": order at %d" % a
+    tol_all = dist_tol(ref_all)
+    pos = np.array([pos_of[int(i)] for i in gpu_ids])
+    assert np.all(np.abs(gpu_dist - ref_all[pos]) <= tol_all[pos]), what + ": returned distance vs oracle"
+    order = np.lexsort((ids, ref_all))
+    ref_top = ref_all[order[:k]]
+    assert np.all(np.abs(gpu_dist - ref_top) <= dist_tol(ref_all)[order[:k]] + 1e-300), what + ": sorted distances"
+    kth = ref_top[-1]
+    band = REL_TOL * abs(kth) * 2 + 1e-8 * np.median(np.abs(ref_all))
+    left_out = np.ones(len(ids), dtype=bool)
+    left_out[pos] = False
+    assert not np.any(ref_all[left_out] < kth - band), what + ": a closer vector was left out"
+    # identical ids where the order is unambiguous
+    sure = np.abs(ref_top - kth) > band
+    for a in np.flatnonzero(sure):
+        lo, hi = ref_top[a] - band, ref_top[a] + band
+        clash = np.count_nonzero((ref_all >= lo) & (ref_all <= hi)) > 1
+        if not clash:
+            assert gpu_ids[a] == ids[order[a]], what + ": id at rank %d" % a

@@ -1,0 +1,192 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+import oracle
+from workload import GaussianMixture
+from parity import assert_distances_close, assert_topk_matches
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import paper_1509_05186_amd as etf  # noqa: E402
+
+FLAT, TREE, FOREST = etf.ETF_MODE_FLAT, etf.ETF_MODE_TREE, etf.ETF_MODE_FOREST
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+class Problem:
+    def __init__(self, d, M, K, N, Q, ntrain, seed, comps=16, iters=4, dup_factor=1):
+        gm = GaussianMixture(d, comps, 1.1, (0.2, 1.0), (-4.0, 4.0), seed=seed)
+        xt = gm.sample(ntrain, 1)
+        self.xb = gm.sample(N // dup_factor, 2)
+        if dup_factor > 1:
+            self.xb = np.repeat(self.xb, dup_factor, axis=0)[np.random.default_rng(seed).permutation(N)]
+        self.q = gm.sample(Q, 3)
+        self.cb, _ = oracle.kmeans(xt, M, K, iters, oracle.kmeans_init_rows(ntrain, M, K, seed))
+        self.codes = oracle.encode(self.xb, self.cb)
+        self.d, self.M, self.K, self.N, self.Q = d, M, K, N, Q
+        self._all = None
+
+    @property
+    def ref_all(self):
+        if self._all is None:
+            self._all = oracle.adc_all(self.q, self.cb, self.codes)
+        return self._all
+
+    def ctx(self, T=1, ids=None, chunk_begin=None, **opts):
+        c = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+        for name, v in opts.items():
+            c.set_option(name, v)
+        c.pq_set_codebooks(self.cb)
+        c.index_build(self.codes, ids=ids, T=T, chunk_begin=chunk_begin)
+        c.index_upload()
+        return c
+
+
+@pytest.fixture(scope="module")
+def small():
+    # several tiles of queries with a ragged tail (150 = 64 + 64 + 22), K = 256, 8 chunks
+    return Problem(d=32, M=8, K=256, N=20000, Q=150, ntrain=4000, seed=11)
+
+
+@pytest.fixture(scope="module")
+def dups():
+    # few codewords => many identical encodings and exact distance ties
+    return Problem(d=16, M=4, K=4, N=6000, Q=70, ntrain=500, seed=12, dup_factor=3)
+
+
+def qdev(p):
+    return torch.from_numpy(p.q).cuda()
+
+
+def test_lut_build(small):
+    say("lut_build small")
+    c = small.ctx()
+    lut = c.lut_build(qdev(small)).cpu().numpy()
+    ref = np.stack([oracle.lut(q, small.cb) for q in small.q])
+    assert_distances_close(lut.reshape(small.Q, -1), ref.reshape(small.Q, -1), "lut")
+
+
+@pytest.mark.parametrize("mode,T", [(FLAT, 1), (TREE, 1), (FOREST, 1), (FOREST, 2), (FOREST, 4), (FOREST, 8)])
+def test_adc_all_pairs(small, mode, T):
+    say("adc all pairs mode", mode, "T", T)
+    c = small.ctx(T=T)
+    dist = c.adc(qdev(small), mode)
+    torch.cuda.synchronize()
+    assert_distances_close(dist.cpu().numpy(), small.ref_all, "adc mode %d T %d" % (mode, T))
+
+
+def test_tree_equals_flat_bitwise(small):
+    say("tree == flat bitwise")
+    c = small.ctx(T=1)
+    a = c.adc(qdev(small), FLAT)
+    b = c.adc(qdev(small), TREE)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)       # same left-to-right float32 sum, shared prefixes added once
+
+
+def test_adc_unequal_groups_and_batches(small):
+    say("adc unequal chunk groups, tiny workspace cap => several query batches")
+    c = small.ctx(T=3, chunk_begin=[0, 1, 4, 8], ws_cap_bytes=1 << 20)
+    dist = c.adc(qdev(small), FOREST)
+    torch.cuda.synchronize()
+    assert_distances_close(dist.cpu().numpy(), small.ref_all, "adc T=3")
+
+
+def check_search(p, c, mode, k, ids=None, what=""):
+    oi, od = c.search(qdev(p), k, mode)
+    torch.cuda.synchronize()
+    oi, od = oi.cpu().numpy(), od.cpu().numpy()
+    idv = np.arange(p.N) if ids is None else ids
+    for j in range(p.Q):
+        assert_topk_matches(oi[j], od[j], p.ref_all[j], idv, k, "%s q%d" % (what, j))
+    return oi, od
+
+
+@pytest.mark.parametrize("mode,T", [(FLAT, 1), (TREE, 1), (FOREST, 2), (FOREST, 4)])
+@pytest.mark.parametrize("k", [1, 10, 100])
+def test_search(small, mode, T, k):
+    say("search mode", mode, "T", T, "k", k)
+    c = small.ctx(T=T, sample_min=2048)          # small sample so that the threshold path is exercised
+    check_search(small, c, mode, k, what="search m%d T%d k%d" % (mode, T, k))
+    assert c.last_fallback_count() == 0
+
+
+def test_search_matches_oracle_lists_exactly(small):
+    say("search ids identical to the oracle's (no near-ties expected at this size)")
+    c = small.ctx(T=2, sample_min=2048)
+    oi, od = c.search(qdev(small), 20, FOREST)
+    torch.cuda.synchronize()
+    ri, rd = oracle.search(small.q, small.cb, small.codes, 20)
+    same = (oi.cpu().numpy() == ri).all(axis=1).mean()
+    assert same > 0.9, same
+
+
+@pytest.mark.parametrize("mode,T", [(FLAT, 1), (TREE, 1), (FOREST, 2)])
+def test_search_exact_kernel(small, mode, T):
+    say("search through the exact whole-database kernel, mode", mode)
+    c = small.ctx(T=T, force_fallback=1)
+    a_i, a_d = check_search(small, c, mode, 50, what="exact m%d" % mode)
+    assert c.last_fallback_count() == small.Q
+    c2 = small.ctx(T=T, sample_min=2048)
+    b_i, b_d = c2.search(qdev(small), 50, mode)
+    torch.cuda.synchronize()
+    assert np.array_equal(a_i, b_i.cpu().numpy()) and np.array_equal(a_d, b_d.cpu().numpy())
+
+
+@pytest.mark.parametrize("mode,T", [(FLAT, 1), (TREE, 1), (FOREST, 2)])
+def test_search_with_duplicates_and_custom_ids(dups, mode, T):
+    say("search on heavily duplicated encodings, custom ids, mode", mode)
+    ids = (np.random.default_rng(0).permutation(dups.N) * 7 + 3).astype(np.int32)
+    c = dups.ctx(T=T, ids=ids, sample_min=512)
+    st = c.index_stats()
+    assert st["max_dup"] >= 3 and st["n_distinct"] <= 256
+    for k in (1, 5, 100, 1000):
+        oi, od = check_search(dups, c, mode, k, ids=ids, what="dups m%d k%d" % (mode, k))
+        ri, rd = oracle.search(dups.q, dups.cb, dups.codes, k, ids)
+        # both sides order exact ties by id, so the lists agree wherever float32 and float64 agree on ties
+        agree = (oi == ri).all(axis=1).mean()
+        assert agree > 0.8, (k, agree)
+
+
+def test_search_small_database():
+    say("search with N below one tile and k == N")
+    p = Problem(d=8, M=2, K=8, N=40, Q=5, ntrain=100, seed=13)
+    for mode, T in [(FLAT, 1), (TREE, 1), (FOREST, 2)]:
+        c = p.ctx(T=T)
+        check_search(p, c, mode, 40, what="tiny m%d" % mode)
+        d = c.adc(qdev(p), mode)
+        torch.cuda.synchronize()
+        assert_distances_close(d.cpu().numpy(), p.ref_all, "tiny adc")
+
+
+def test_search_several_batches(small):
+    say("search with a workspace cap that forces several query batches")
+    c = small.ctx(T=2, sample_min=2048, ws_cap_bytes=8 << 20)
+    assert c.workspace_bytes(small.Q, 10, FOREST) <= 16 << 20
+    check_search(small, c, FOREST, 10, what="batched")
+
+
+def test_device_error_paths(small):
+    say("device entry points reject bad arguments before launching")
+    lib = etf.load_library()
+    c = small.ctx(T=2)
+    q = qdev(small)
+    ws = c.alloc_workspace(small.Q, 10, FOREST)
+    oi = torch.empty((small.Q, 10), dtype=torch.int32, device="cuda")
+    od = torch.empty((small.Q, 10), dtype=torch.float32, device="cuda")
+    p, n = c._ws(ws)
+    assert lib.etf_search(c._h, q.data_ptr(), small.Q, 10, TREE, oi.data_ptr(), od.data_ptr(), p, n) == -2
+    assert lib.etf_search(c._h, q.data_ptr(), small.Q, 10, FOREST, oi.data_ptr(), od.data_ptr(), p, 1024) == -3
+    assert lib.etf_search(c._h, q.data_ptr(), small.Q, 0, FOREST, oi.data_ptr(), od.data_ptr(), p, n) == -1
+    assert lib.etf_search(c._h, None, small.Q, 10, FOREST, oi.data_ptr(), od.data_ptr(), p, n) == -1
+    assert lib.etf_search(c._h, q.data_ptr(), small.Q, 10, FOREST, oi.data_ptr(), od.data_ptr(), p + 4, n - 4) == -1
+    c2 = etf.Context(device=0)
+    c2.pq_set_codebooks(small.cb)
+    c2.index_build(small.codes)
+    assert lib.etf_search(c2._h, q.data_ptr(), small.Q, 10, FLAT, oi.data_ptr(), od.data_ptr(), p, n) == -2  # no upload
+    torch.cuda.synchronize()

@@ -1,0 +1,212 @@
+"""Host side of the library (no GPU): C-ABI symbols, error paths, quantiser, index builder."""
+import ctypes
+import re
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle.trie import EncodingTree
+import paper_1509_05186_amd as etf
+from paper_1509_05186_amd import binding
+from workload import GaussianMixture
+from imagewalk import walk_image, arr
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def host_ctx(cb):
+    c = etf.Context(device=None)
+    c.pq_set_codebooks(cb)
+    return c
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "etf.h")).read()
+    declared = set(re.findall(r"\b(etf_[a-z_]+)\s*\(", hdr))
+    assert declared == set(binding.EXPORTS)
+    lib = ctypes.CDLL(etf.library_path())
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_error_paths_without_gpu():
+    lib = etf.load_library()
+    c = etf.Context(device=None)
+    cb = np.zeros((2, 4, 3), dtype=np.float32)
+    codes = np.zeros((5, 2), dtype=np.uint8)
+    with pytest.raises(etf.EtfError) as e:          # build before codebooks
+        c._ck(lib.etf_index_build(c._h, codes.ctypes.data, 5, None, 1, None))
+    assert e.value.code == -2
+    for d, M, K in [(7, 2, 4), (6, 0, 4), (6, 2, 257), (6, 17, 4), (0, 1, 1)]:
+        assert lib.etf_pq_set_codebooks(c._h, cb.ctypes.data, d, M, K) == -1
+    assert lib.etf_pq_set_codebooks(c._h, None, 6, 2, 4) == -1
+    c.pq_set_codebooks(cb)
+    assert lib.etf_index_build(c._h, None, 5, None, 1, None) == -1
+    assert lib.etf_index_build(c._h, codes.ctypes.data, 0, None, 1, None) == -1
+    assert lib.etf_index_build(c._h, codes.ctypes.data, 5, None, 3, None) == -1      # T > M
+    bad = codes.copy(); bad[3, 1] = 4                                                # byte >= K
+    assert lib.etf_index_build(c._h, bad.ctypes.data, 5, None, 1, None) == -1
+    neg = np.array([0, 1, -2, 3, 4], dtype=np.int32)
+    assert lib.etf_index_build(c._h, codes.ctypes.data, 5, neg.ctypes.data, 1, None) == -1
+    cbeg = np.array([0, 0, 2], dtype=np.int32)
+    assert lib.etf_index_build(c._h, codes.ctypes.data, 5, None, 2, cbeg.ctypes.data) == -1
+    assert lib.etf_index_device_bytes(c._h) == -2                                    # nothing built
+    assert b"no index" in lib.etf_last_error(c._h)
+    c.index_build(codes)
+    assert c.index_device_bytes() > 0
+    assert lib.etf_workspace_bytes(c._h, 10, 6, etf.ETF_MODE_FLAT) == -1             # k > N
+    assert lib.etf_workspace_bytes(c._h, 0, 1, etf.ETF_MODE_FLAT) == -1
+    assert lib.etf_workspace_bytes(c._h, 10, 1, 7) == -1
+    c.index_build(codes, T=2)
+    assert lib.etf_workspace_bytes(c._h, 10, 1, etf.ETF_MODE_TREE) == -2             # tree mode needs T=1
+    assert lib.etf_workspace_bytes(c._h, 10, 1, etf.ETF_MODE_FOREST) > 0
+    # device entry points on a host-only context
+    assert lib.etf_lut_build(c._h, 1, 1, 1) == -5
+    assert lib.etf_search(c._h, 1, 1, 1, 0, 1, 1, 1, 1) == -5
+    assert lib.etf_set_option(c._h, b"nonsense", 1) == -1
+    assert lib.etf_set_option(c._h, b"force_fallback", 2) == -1
+    assert lib.etf_strerror(-3) == b"out of memory or buffer too small"
+
+
+def test_encode_matches_oracle_and_train_quality():
+    gm = GaussianMixture(32, 16, 1.1, (0.2, 1.0), (-4, 4), seed=5)
+    xt, xb = gm.sample(4000, 1), gm.sample(3000, 2)
+    M, K = 4, 32
+    ocb, oobj = oracle.kmeans(xt, M, K, 10, oracle.kmeans_init_rows(4000, M, K, 3))
+    c = host_ctx(ocb)
+    mine, ref = c.pq_encode(xb), oracle.encode(xb, ocb)
+    diff = np.argwhere(mine != ref)
+    # float32 vs float64 argmin may differ only where two codewords are (nearly) equally near
+    for i, m in diff:
+        sub = xb[i, m * 8:(m + 1) * 8].astype(np.float64)
+        da = ((sub - ocb[m, mine[i, m]]) ** 2).sum()
+        db = ((sub - ocb[m, ref[i, m]]) ** 2).sum()
+        assert abs(da - db) <= 1e-5 * max(da, db)
+    assert len(diff) <= 3
+    assert np.array_equal(c.pq_get_codebooks(), ocb)
+    # the library's own training: quantisation error close to the oracle's k-means on the same data
+    t = etf.Context(device=None)
+    t.pq_train(xt, M, K, 10, seed=7)
+    tcb = t.pq_get_codebooks()
+    err_t = ((xb - oracle.decode(t.pq_encode(xb), tcb)) ** 2).sum(1).mean()
+    err_o = ((xb - oracle.decode(ref, ocb)) ** 2).sum(1).mean()
+    assert err_t < 1.15 * err_o
+    # more iterations never make the training error worse (same seed => same start)
+    errs = []
+    for it in (0, 1, 3, 6):
+        t.pq_train(xt, M, K, it, seed=7)
+        errs.append(((xt - oracle.decode(t.pq_encode(xt), t.pq_get_codebooks())) ** 2).sum(1).mean())
+    assert all(b <= a * (1 + 1e-6) for a, b in zip(errs, errs[1:]))
+
+
+CASES = [
+    # (N, M, K, T, chunk_begin, seed)
+    (300, 6, 3, 1, None, 0),
+    (300, 6, 3, 2, None, 1),
+    (300, 6, 3, 6, None, 2),          # one chunk per tree: forest == flat regrouped
+    (500, 8, 4, 2, [0, 3, 8], 3),     # unequal groups
+    (1, 4, 5, 1, None, 4),            # single vector
+    (64, 1, 7, 1, None, 5),           # M = 1
+    (2000, 16, 2, 4, None, 6),        # 16-byte codes, two key words
+    (1000, 12, 256, 3, None, 7),      # full byte range, three-word-wide records
+    (700, 5, 3, 1, None, 8),          # odd M: padded records
+]
+
+
+@pytest.mark.parametrize("N,M,K,T,cbeg,seed", CASES)
+def test_builder_against_pointer_trie(N, M, K, T, cbeg, seed):
+    rng = np.random.default_rng(seed)
+    codes = rng.integers(0, K, size=(N, M)).astype(np.uint8)
+    if K == 256:                       # make prefixes collide although the alphabet is large
+        codes[:, :M // 2] = rng.integers(0, 3, size=(N, M // 2)) * 100
+    c = host_ctx(np.zeros((M, K, 1), dtype=np.float32))
+    c.index_build(codes, T=T, chunk_begin=cbeg)
+    st = c.index_stats()
+    cb = cbeg or [t * (M // T) for t in range(T + 1)]
+    assert st["n_distinct"] == len(np.unique(codes, axis=0))
+    for t in range(T):
+        ref = EncodingTree(codes, cb[t], cb[t + 1]).stats()
+        got = st["trees"][t]
+        for key in ("nI", "nL", "L1", "L2", "sumP", "lookups", "paper_bytes"):
+            assert got[key] == ref[key], (t, key)
+    lut = rng.random((M, K)) * 10
+    dist, lookups = walk_image(c, lut)
+    flat = oracle.adc_flat(lut, codes)
+    assert np.allclose(dist, flat, rtol=1e-13)
+    assert lookups == sum(tr["lookups"] for tr in st["trees"])
+
+
+def test_builder_degenerate_inputs():
+    M, K = 6, 4
+    c = host_ctx(np.zeros((M, K, 1), dtype=np.float32))
+    lut = np.random.default_rng(0).random((M, K))
+    # all encodings equal: one level-1 leaf holding every id
+    codes = np.full((1000, M), 2, dtype=np.uint8)
+    c.index_build(codes)
+    st = c.index_stats()
+    assert (st["n_distinct"], st["max_dup"]) == (1, 1000)
+    assert st["trees"][0]["nL"] == [1, 0, 0, 0, 0, 0] and st["trees"][0]["L1"] == 0 and st["trees"][0]["sumP"] == M - 1
+    assert np.allclose(walk_image(c, lut)[0], oracle.adc_flat(lut, codes))
+    # all first chunks distinct
+    codes = np.random.default_rng(1).integers(0, K, size=(4, M)).astype(np.uint8)
+    codes[:, 0] = np.arange(4)
+    c.index_build(codes)
+    st = c.index_stats()["trees"][0]
+    assert st["L1"] == 0 and st["nL"][0] == 4 and st["lookups"] == 4 * M
+    # full enumeration K^D
+    K2, D = 3, 4
+    grid = np.array(np.meshgrid(*[np.arange(K2)] * D, indexing="ij")).reshape(D, -1).T.astype(np.uint8)
+    c2 = host_ctx(np.zeros((D, K2, 1), dtype=np.float32))
+    c2.index_build(grid[np.random.default_rng(2).permutation(len(grid))])
+    st = c2.index_stats()["trees"][0]
+    assert st["nI"] == [3, 9, 27, 0] and st["nL"] == [0, 0, 0, 81]
+
+
+def test_builder_ids_and_ranges():
+    rng = np.random.default_rng(3)
+    N, M, K = 400, 4, 2
+    codes = rng.integers(0, K, size=(N, M)).astype(np.uint8)       # 16 distinct codes, many duplicates
+    ids = rng.permutation(10 * N)[:N].astype(np.int32)
+    c = host_ctx(np.zeros((M, K, 1), dtype=np.float32))
+    c.index_build(codes, ids=ids, T=2)
+    st, lay, buf = c.index_stats(), c.index_layout(), c.index_export()
+    Nd = st["n_distinct"]
+    ebegin = arr(buf, lay.ebegin, Nd + 1, np.uint32)
+    ids_sorted = arr(buf, lay.ids_sorted, N, np.int32)
+    ecodes = arr(buf, lay.ecodes, Nd * M, np.uint8).reshape(Nd, M)
+    enc_of_pos = arr(buf, lay.enc_of_pos, N, np.uint32)
+    assert np.array_equal(arr(buf, lay.ids_in, N, np.int32), ids)
+    assert np.array_equal(arr(buf, lay.codes, N * M, np.uint8).reshape(N, M), codes)
+    assert ebegin[0] == 0 and ebegin[-1] == N and np.all(np.diff(ebegin.astype(np.int64)) > 0)
+    assert np.array_equal(ecodes, np.unique(codes, axis=0))          # lexicographic, distinct
+    assert np.array_equal(ecodes[enc_of_pos], codes)
+    for e in range(Nd):
+        mine = ids_sorted[ebegin[e]:ebegin[e + 1]]
+        ref = np.sort(ids[np.all(codes == ecodes[e], axis=1)])
+        assert np.array_equal(mine, ref)                               # ascending ids inside a leaf
+    assert sorted(ids_sorted.tolist()) == sorted(ids.tolist())
+    # samples are valid, distinct, sorted references
+    se = arr(buf, lay.sample_enc, lay.n_sample_enc, np.uint32)
+    sp = arr(buf, lay.sample_pos, lay.n_sample_pos, np.uint32)
+    assert len(se) == Nd and len(sp) == N and np.all(np.diff(se.astype(np.int64)) > 0)
+
+
+def test_builder_sampling_on_larger_input():
+    rng = np.random.default_rng(4)
+    N, M, K = 300000, 8, 16
+    codes = rng.integers(0, K, size=(N, M)).astype(np.uint8)
+    codes[:, :3] //= 4
+    c = host_ctx(np.zeros((M, K, 1), dtype=np.float32))
+    c.set_option("sample_min", 1000)
+    c.index_build(codes, T=2)
+    st, lay, buf = c.index_stats(), c.index_layout(), c.index_export()
+    se = arr(buf, lay.sample_enc, lay.n_sample_enc, np.uint32)
+    sp = arr(buf, lay.sample_pos, lay.n_sample_pos, np.uint32)
+    assert 0.9 * st["n_distinct"] / 32 <= len(se) <= st["n_distinct"] / 32 + 1 and se.max() < st["n_distinct"]
+    assert 0.9 * N / 32 <= len(sp) <= N / 32 + 1 and sp.max() < N
+    assert np.all(np.diff(se.astype(np.int64)) > 0) and np.all(np.diff(sp.astype(np.int64)) > 0)
+    lut = rng.random((M, K))
+    dist, _ = walk_image(c, lut)
+    assert np.allclose(dist, oracle.adc_flat(lut, codes), rtol=1e-13)
