@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the E-Forest ADC hot path on one MI355X.
+
+One step = one pass of the whole hot path over the workload's query batch: lookup tables ->
+tree levels and leaf buckets of every tree -> forest reduction with the per-query bound ->
+top-k selection.  Inputs (queries, index image, codebooks) are resident in HBM before the timed
+region.  Prints one JSON line (the last line of stdout); progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+PAPER_CONTEXT = {              # the paper's own numbers: one Core i7 at 3.6 GHz, one query at a time, SIFT1M, M=8, K=256
+    "hardware": "Intel Core i7 3.6 GHz (paper, section Experiments)",
+    "ms_per_query": {"flat_adc": 2.678, "e_tree": 1.760, "e_forest_2": 1.265},
+    "distances_per_s": {"flat_adc": 1e6 / 2.678e-3, "e_tree": 1e6 / 1.760e-3, "e_forest_2": 1e6 / 1.265e-3},
+}
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def make_inputs(cfg, etf, scale_n=None, scale_q=None):
+    """Synthetic workload: library-trained codebooks, library-encoded database, queries."""
+    from workload import GaussianMixture, SEED_TRAIN, SEED_DATABASE, SEED_QUERIES
+    gm = GaussianMixture.from_config(cfg)
+    N = scale_n or cfg.N
+    Q = scale_q or cfg.Q
+    host = etf.Context(device=None)
+    t0 = time.time()
+    host.pq_train(gm.sample(cfg.n_train, SEED_TRAIN), cfg.M, cfg.K, cfg.kmeans_iters, seed=SEED_TRAIN)
+    log("k-means (%d x %d, %d iters): %.1f s" % (cfg.n_train, cfg.d, cfg.kmeans_iters, time.time() - t0))
+    t0 = time.time()
+    codes = np.empty((N, cfg.M), dtype=np.uint8)
+    done = 0
+    for chunk in gm.chunks(N, SEED_DATABASE):
+        codes[done:done + len(chunk)] = host.pq_encode(chunk)
+        done += len(chunk)
+    log("generate + encode %d vectors: %.1f s" % (N, time.time() - t0))
+    queries = gm.sample(Q, SEED_QUERIES)
+    return host.pq_get_codebooks(), codes, queries
+
+
+def algorithmic_bytes(stats, mode, S, tiles):
+    """Bytes each kernel class has to move for `tiles` tiles of 64 queries, from the index statistics:
+    every partial-sum / result row is 256 bytes per tile and is counted once where consecutive
+    nodes share it (children of one parent, encodings of one tree-0 leaf)."""
+    M, K, T, N, Nd = stats["M"], stats["K"], stats["T"], stats["N"], stats["n_distinct"]
+    row = 256
+    out = {"lut": tiles * M * K * row}
+    if mode == "flat":
+        G = 1
+        while M * K * (64 // G) * 4 > 128 * 1024:
+            G *= 2
+        out["flat"] = tiles * (G * N * M + M * K * row)
+        out["sample"] = tiles * (S * (4 + M * G) + S * row + M * K * row)
+        return out
+    level = leaf = 0
+    for tr in stats["trees"]:
+        D = tr["D"]
+        for l in range(D):
+            nI, nL = tr["nI"][l], tr["nL"][l]
+            prev = tr["nI"][l - 1] if l > 0 else 0
+            if nI:
+                level += nI * 5 + nI * row + min(nI, prev) * row + K * row
+            if nL:
+                stride = (D - l + 3) // 4 * 4
+                leaf += nL * (stride + 8) + nL * row + min(nL, prev) * row + (D - l) * K * row
+    out["level"] = tiles * level
+    out["leaf"] = tiles * leaf
+    U0 = stats["trees"][0]["L2"]
+    gather = (U0 + (T - 1) * Nd) * row if T > 1 else Nd * row
+    out["reduce"] = tiles * (gather + (Nd * 4 * T if T > 1 else 0))
+    out["sample"] = tiles * (S * 4 * (1 + (T if T > 1 else 0)) + S * T * row + S * row)
+    return out
+
+
+def time_search(ctx, qd, k, mode, warmup, steps, torch, ws, out_ids, out_dist):
+    for _ in range(warmup):
+        ctx.search(qd, k, mode, out_ids, out_dist, ws)
+    torch.cuda.synchronize()
+    ctx.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ctx.search(qd, k, mode, out_ids, out_dist, ws)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return dt, ctx.profile_read()
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--scale-n", type=int, default=0, help="override N (debugging only; invalidates the metric)")
+    ap.add_argument("--scale-q", type=int, default=0, help="override Q (debugging only; invalidates the metric)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline and the parity spot check")
+    ap.add_argument("--no-others", action="store_true", help="skip the flat and single-tree legs")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus %d is not supported); "
+              "the path shards by query tile or by database range, see DESIGN.md" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_1509_05186_amd as etf
+    from workload import get_config
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    etf.load_library()          # raises if the HIP library is missing: there is no fallback
+
+    cfg = get_config(args.config)
+    k = cfg.topk or 100
+    cb, codes, queries = make_inputs(cfg, etf, args.scale_n or None, args.scale_q or None)
+    N, Q = codes.shape[0], queries.shape[0]
+    stream = torch.cuda.current_stream().cuda_stream
+    qd = torch.from_numpy(queries).cuda()
+    out_ids = torch.empty((Q, k), dtype=torch.int32, device="cuda")
+    out_dist = torch.empty((Q, k), dtype=torch.float32, device="cuda")
+
+    def make_ctx(T):
+        c = etf.Context(device=0, stream=stream)
+        c.pq_set_codebooks(cb)
+        t0 = time.time()
+        c.index_build(codes, T=T)
+        c.index_upload()
+        log("index T=%d: build + upload %.1f s, %.1f MB on device" % (T, time.time() - t0, c.index_device_bytes() / 1e6))
+        c.profile_enable(not args.no_profile)
+        return c
+
+    T = max(cfg.trees, 1)
+    forest = make_ctx(T)
+    stats = forest.index_stats()
+    mode = etf.ETF_MODE_FOREST
+    ws = forest.alloc_workspace(Q, k, mode)
+    log("workspace %.2f GB" % (ws.numel() / 1e9))
+    dt, prof = time_search(forest, qd, k, mode, args.warmup, args.steps, torch, ws, out_ids, out_dist)
+    ms_step = dt / args.steps * 1e3
+    value = N * Q * args.steps / dt
+    fallbacks = forest.last_fallback_count()
+    log("E-Forest(T=%d) top-%d: %.2f ms/step, %.3e distances/s, %d queries via the exact kernel" % (T, k, ms_step, value, fallbacks))
+    got_ids, got_dist = out_ids.cpu().numpy(), out_dist.cpu().numpy()
+
+    # ---- roofline of the dominant kernel class
+    tiles = (Q + 63) // 64
+    S = forest.index_layout().n_sample_enc
+    alg = algorithmic_bytes(stats, "forest", S, tiles)
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        if cnt:
+            kernels[name] = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps,
+                             "alg_GB_per_step": alg.get(name, 0) / 1e9,
+                             "alg_GBps": (alg.get(name, 0) / 1e9) / (ms / args.steps / 1e3) if ms > 0 and name in alg else None}
+    roofline = None
+    if kernels:
+        dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+        kd = kernels[dom]
+        lps = kd["launches_per_step"]
+        achieved = kd["alg_GBps"] or 0.0
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "alg_bytes_per_launch": alg.get(dom, 0) / lps if lps else None,
+                    "avg_launch_ms": kd["ms_per_step"] / lps if lps else None,
+                    "launches_per_step": lps}
+        # the traversal as a whole (levels + leaves + reduction), the north-star's bandwidth figure
+        trav = [n for n in ("level", "leaf", "reduce", "sample") if n in kernels]
+        tms = sum(kernels[n]["ms_per_step"] for n in trav)
+        tgb = sum(kernels[n]["alg_GB_per_step"] for n in trav)
+        roofline["traversal"] = {"kernels": trav, "ms_per_step": tms, "alg_GB_per_step": tgb,
+                                 "alg_GBps": tgb / (tms / 1e3) if tms > 0 else None,
+                                 "frac": (tgb / (tms / 1e3)) / HBM_PEAK_GBS if tms > 0 else None}
+
+    # ---- the same workload through the flat kernel and a single E-Tree, same run
+    others = {}
+    if not args.no_others:
+        osteps = max(2, min(args.steps, 3))
+        tree = make_ctx(1)
+        for name, ctx, m in (("flat_gpu", tree, etf.ETF_MODE_FLAT), ("e_tree_gpu", tree, etf.ETF_MODE_TREE)):
+            w2 = ctx.alloc_workspace(Q, k, m)
+            d2, p2 = time_search(ctx, qd, k, m, 1, osteps, torch, w2, out_ids, out_dist)
+            others[name] = {"value": N * Q * osteps / d2, "ms_per_step": d2 / osteps * 1e3,
+                            "kernels_ms_per_step": {n: v[0] / osteps for n, v in p2.items() if v[1]}}
+            log("%s: %.2f ms/step, %.3e distances/s" % (name, others[name]["ms_per_step"], others[name]["value"]))
+            del w2
+        others["e_tree_stats"] = tree.index_stats()["trees"]
+        del tree
+
+    # ---- CPU oracle on a bounded sample of the same workload, and parity of the timed output on it
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        from parity import assert_topk_matches
+        nq = min(Q, 16)
+        t0 = time.perf_counter()
+        oracle.search(queries[:nq], cb, codes, k)
+        t1 = time.perf_counter() - t0
+        nq2 = int(min(Q, max(nq, min(512, nq * 12.0 / max(t1, 1e-3)))))
+        t0 = time.perf_counter()
+        oracle.search(queries[:nq2], cb, codes, k)
+        t2 = time.perf_counter() - t0
+        cpu = {"value": N * nq2 / t2, "unit": "encoding-distances/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "first %d of %d queries against all %d encodings (float64 flat ADC + full-sort top-%d), %.1f s"
+                         % (nq2, Q, N, k, t2)}
+        log("CPU oracle: %.3e distances/s on %d threads (%s)" % (cpu["value"], cpu["cores"], cpu["sample"]))
+        npar = min(Q, 24)
+        ref = oracle.adc_all(queries[:npar], cb, codes)
+        for j in range(npar):
+            assert_topk_matches(got_ids[j], got_dist[j], ref[j], np.arange(N), k, "bench q%d" % j)
+        # plus a spread of queries from the rest of the batch (other tiles, the ragged last tile)
+        rest = np.unique(np.linspace(npar, Q - 1, 8).astype(int)) if Q > npar else []
+        for j in rest:
+            r = oracle.adc_all(queries[j:j + 1], cb, codes)[0]
+            assert_topk_matches(got_ids[j], got_dist[j], r, np.arange(N), k, "bench q%d" % j)
+        log("parity of the timed output against the oracle: ok on %d queries" % (npar + len(rest)))
+
+    line = {
+        "metric": "encoding-distances/sec (batched queries), E-Forest ADC + top-k, 1 GPU",
+        "value": value, "unit": "encoding-distances/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: d=%d N=%d Q=%d PQ M=%d K=%d, E-Forest T=%d, top-%d, seeded %d-component Gaussian mixture"
+                               % (cfg.name, cfg.d, N, Q, cfg.M, cfg.K, T, k, cfg.components),
+                   "valid": not (args.scale_n or args.scale_q)},
+        "roofline": roofline, "cpu_baseline": cpu,
+        "kernels": kernels, "others": others, "fallback_queries": fallbacks,
+        "index": {"n_distinct": stats["n_distinct"], "max_dup": stats["max_dup"], "device_MB": stats["device_bytes"] / 1e6,
+                  "trees": stats["trees"], "sample": int(S)},
+        "paper_context": PAPER_CONTEXT,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -144,7 +144,7 @@ int etf_index_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes);
  *   ebegin      u32 [n_distinct+1]  range of ids_sorted held by every distinct encoding
  *   enc_of_pos  u32 [N]          distinct-encoding number of the n-th input vector
  *   ecodes      u8  [n_distinct][M]  distinct encodings in lexicographic order
- *   sample_enc  u32 [n_sample_enc]   distinct encodings used to bound the k-th distance
+ *   sample_enc  u32 [n_sample_enc]   distinct encodings used to bound the k-th distance (random order)
  *   sample_pos  u32 [n_sample_pos]   input positions used for the same purpose in flat mode
  *   leaf_of[t]  u32 [n_distinct] leaf (row of tree t's result table) of every distinct
  *                                encoding; absent when T = 1 (the identity)
@@ -193,6 +193,29 @@ int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, int mode, i
  * answered by the exact whole-database selection kernel instead of the
  * threshold-filtered path (diagnostic).  Synchronises the stream. */
 int etf_last_fallback_count(etf_ctx *ctx, int64_t *out);
+
+/* ---- per-kernel timing (for benchmarks) ---------------------------------- */
+
+/* Kernel classes of the hot path, in launch order. */
+enum {
+    ETF_K_LUT = 0,      /* lookup-table build                                 */
+    ETF_K_LEVEL = 1,    /* internal tree levels                               */
+    ETF_K_LEAF = 2,     /* leaf buckets                                       */
+    ETF_K_FLAT = 3,     /* flat ADC (filter or all-pairs output)              */
+    ETF_K_REDUCE = 4,   /* forest reduction (filter or all-pairs output)      */
+    ETF_K_TAU = 5,      /* per-query bound from the sample                    */
+    ETF_K_SELECT = 6,   /* final top-k selection                              */
+    ETF_K_EXACT = 7,    /* exact whole-database selection                     */
+    ETF_K_SAMPLE = 8,   /* distances of the bound's sample (flat or reduction) */
+    ETF_K_COUNT = 9
+};
+/* on != 0: every later kernel launch of this context is bracketed by a pair of
+ * HIP events on the context's stream. */
+int etf_profile_enable(etf_ctx *ctx, int on);
+/* Synchronises the stream, then returns per class the summed kernel time in
+ * milliseconds (ms[ETF_K_COUNT]) and the number of launches
+ * (launches[ETF_K_COUNT]) since the last read, and resets both. */
+int etf_profile_read(etf_ctx *ctx, double *ms, int64_t *launches);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,9 @@ EXPORTS = [
     "etf_index_build", "etf_index_stats", "etf_index_device_bytes", "etf_index_upload",
     "etf_index_layout", "etf_index_export",
     "etf_workspace_bytes", "etf_lut_build", "etf_adc", "etf_search", "etf_last_fallback_count",
+    "etf_profile_enable", "etf_profile_read",
 ]
+KERNEL_CLASSES = ["lut", "level", "leaf", "flat", "reduce", "tau", "select", "exact", "sample"]
 
 
 class EtfStats(ctypes.Structure):
@@ -111,6 +113,8 @@ def load_library():
         "etf_adc": (I, [P, P, L, I, P, P, L]),
         "etf_search": (I, [P, P, L, I, I, P, P, P, L]),
         "etf_last_fallback_count": (I, [P, ctypes.POINTER(L)]),
+        "etf_profile_enable": (I, [P, I]),
+        "etf_profile_read": (I, [P, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(L)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -287,3 +291,14 @@ class Context:
         v = ctypes.c_int64(0)
         self._ck(self._lib.etf_last_fallback_count(self._h, ctypes.byref(v)))
         return int(v.value)
+
+    def profile_enable(self, on: bool):
+        self._ck(self._lib.etf_profile_enable(self._h, 1 if on else 0))
+
+    def profile_read(self) -> dict:
+        """{kernel class: (milliseconds, launches)} since the last read."""
+        n = len(KERNEL_CLASSES)
+        ms = (ctypes.c_double * n)()
+        cnt = (ctypes.c_int64 * n)()
+        self._ck(self._lib.etf_profile_read(self._h, ms, cnt))
+        return {name: (float(ms[i]), int(cnt[i])) for i, name in enumerate(KERNEL_CLASSES)}

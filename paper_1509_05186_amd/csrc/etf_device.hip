@@ -22,6 +22,36 @@ using namespace etf;
         if (e_ != hipSuccess) return fail(ctx, ETF_EHIP, "launch of %s: %s", name, hipGetErrorString(e_)); \
     } while (0)
 
+// Brackets the launches made during its lifetime with a pair of events when profiling is on.
+struct ProfScope {
+    etf_ctx *ctx;
+    etf_ctx::Stamp st{nullptr, nullptr, 0};
+    bool live = false;
+    ProfScope(etf_ctx *c, int cls) : ctx(c)
+    {
+        if (!c->profile_on) return;
+        if (!c->stamp_pool.empty()) {
+            st = c->stamp_pool.back();
+            c->stamp_pool.pop_back();
+        } else {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess) return;
+            if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+            st.start = a;
+            st.stop = b;
+        }
+        st.cls = cls;
+        live = hipEventRecord((hipEvent_t)st.start, (hipStream_t)c->stream) == hipSuccess;
+        if (!live) c->stamp_pool.push_back(st);
+    }
+    ~ProfScope()
+    {
+        if (!live) return;
+        (void)hipEventRecord((hipEvent_t)st.stop, (hipStream_t)ctx->stream);
+        ctx->stamps.push_back(st);
+    }
+};
+
 static constexpr int64_t LDS_BUDGET = 128 * 1024;  // bytes of table slices a workgroup may stage
 
 // =============================================================================================
@@ -43,7 +73,46 @@ extern "C" int etf_create(etf_ctx **out, int device, void *hip_stream)
     return ETF_OK;
 }
 
-extern "C" void etf_destroy(etf_ctx *ctx) { delete ctx; }
+extern "C" void etf_destroy(etf_ctx *ctx)
+{
+    if (!ctx) return;
+    for (auto *v : {&ctx->stamps, &ctx->stamp_pool})
+        for (auto &s : *v) {
+            (void)hipEventDestroy((hipEvent_t)s.start);
+            (void)hipEventDestroy((hipEvent_t)s.stop);
+        }
+    delete ctx;
+}
+
+extern "C" int etf_profile_enable(etf_ctx *ctx, int on)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (ctx->device < 0) return fail(ctx, ETF_ENOGPU, "host-only context");
+    ctx->profile_on = on != 0;
+    return ETF_OK;
+}
+
+extern "C" int etf_profile_read(etf_ctx *ctx, double *ms, int64_t *launches)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (ctx->device < 0) return fail(ctx, ETF_ENOGPU, "host-only context");
+    if (!ms || !launches) return fail(ctx, ETF_EINVAL, "output pointer is null");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    HIP_TRY(ctx, hipStreamSynchronize((hipStream_t)ctx->stream));
+    for (int i = 0; i < ETF_K_COUNT; ++i) {
+        ms[i] = 0.0;
+        launches[i] = 0;
+    }
+    for (auto &s : ctx->stamps) {
+        float t = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&t, (hipEvent_t)s.start, (hipEvent_t)s.stop));
+        ms[s.cls] += t;
+        launches[s.cls] += 1;
+        ctx->stamp_pool.push_back(s);
+    }
+    ctx->stamps.clear();
+    return ETF_OK;
+}
 
 extern "C" int etf_set_stream(etf_ctx *ctx, void *hip_stream)
 {
@@ -97,9 +166,11 @@ struct Plan {
     int64_t NT = 0;           // tiles per batch
     int64_t items = 0;        // candidates per query: N (flat) or distinct encodings
     int64_t S = 0;            // threshold sample size
+    int gsize = 1;            // sample entries per group (only group minima are kept)
+    int64_t ngroups = 0;      // ceil(S / gsize)
     uint32_t C = 0;           // candidate capacity per query
     bool use_tau = false;
-    int64_t o_counter = 0, o_lutT = 0, o_sdist = 0, o_tau = 0, o_cnt = 0, o_flag = 0, o_cand = 0;
+    int64_t o_counter = 0, o_lutT = 0, o_gmin = 0, o_tau = 0, o_cnt = 0, o_flag = 0, o_cand = 0;
     int64_t o_part[ETF_MAX_M][ETF_MAX_M];
     int64_t o_leafp[ETF_MAX_M];
     int64_t total = 0;
@@ -124,13 +195,19 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     P.items = mode == ETF_MODE_FLAT ? ix.N : ix.Nd;
     P.S = mode == ETF_MODE_FLAT ? (int64_t)ix.sample_pos.size() : (int64_t)ix.sample_enc.size();
     if (search) {
+        // The sample is cut into about 2.5 k groups; the bound is the k-th smallest group minimum, which
+        // lets through about 1.3 k items/S candidates per query.
+        int64_t groups = 256;
+        while (groups < (int64_t)(2.5 * k) && groups < 4096) groups <<= 1;
+        P.gsize = (int)std::max<int64_t>(1, P.S / groups);
+        P.ngroups = (P.S + P.gsize - 1) / P.gsize;
         int64_t C = ctx->opt.cand_cap;
         if (C == 0) {
-            const int64_t expect = (int64_t)((double)k * (double)P.items / (double)std::max<int64_t>(P.S, 1));
+            const int64_t expect = (int64_t)(1.3 * (double)k * (double)P.items / (double)std::max<int64_t>(P.S, 1));
             C = 4096;
             while (C < 3 * expect + 2048 && C < (1 << 17)) C <<= 1;
         }
-        if (P.items <= C || P.S < k) {  // few enough encodings: every one is a candidate, no bound needed
+        if (P.items <= C || P.ngroups < k) {  // few enough encodings: every one is a candidate, no bound needed
             P.use_tau = false;
             if (P.items > C) C = P.items;  // cannot bound without a large enough sample
         } else {
@@ -147,7 +224,7 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
             per_tile += al256(tr.U * QT * 4);
         }
     if (search) {
-        if (P.use_tau) per_tile += al256(P.S * QT * 4);
+        if (P.use_tau) per_tile += al256(P.ngroups * QT * 4);
         per_tile += (int64_t)QT * (12 + (int64_t)P.C * 8);
     }
     int64_t nt = ctx->opt.ws_cap_bytes / std::max<int64_t>(per_tile, 1);
@@ -168,7 +245,7 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
             P.o_leafp[t] = take(P.NT * tr.U * QT * 4);
         }
     if (search) {
-        if (P.use_tau) P.o_sdist = take(P.NT * P.S * QT * 4);
+        if (P.use_tau) P.o_gmin = take(P.NT * P.ngroups * QT * 4);
         P.o_tau = take(P.NT * QT * 4);
         P.o_cnt = take(P.NT * QT * 4);
         P.o_flag = take(P.NT * QT * 4);
@@ -209,6 +286,7 @@ int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_
 {
     const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
     dim3 grid((unsigned)tiles, (unsigned)ctx->M);
+    ProfScope prof(ctx, ETF_K_LUT);
     hipLaunchKernelGGL(k_lut_direct, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M,
                        ctx->K, cb, lutT, lut_public);
     LAUNCH_CHECK(ctx, "k_lut_direct");
@@ -222,6 +300,7 @@ int launch_leaf_g(etf_ctx *ctx, int ndw, dim3 grid, dim3 block, size_t lds, cons
 {
     hipStream_t st = (hipStream_t)ctx->stream;
     const int M = ctx->M, K = ctx->K;
+    ProfScope prof(ctx, ETF_K_LEAF);
 #define LEAF_CASE(NDW)                                                                                         \
     case NDW: {                                                                                                \
         int rc = set_lds(ctx, k_leaf<G, NDW>, lds);                                                            \
@@ -261,6 +340,7 @@ int launch_trees(etf_ctx *ctx, const Plan &P, char *ws, int64_t tiles)
             const int per_wave = (int)((n + bx * 4 - 1) / (bx * 4));
             const float *prev = l > 0 ? reinterpret_cast<const float *>(ws + P.o_part[t][l - 1]) : nullptr;
             const int64_t nprev = l > 0 ? (int64_t)tr.level[l - 1].code.size() : 0;
+            ProfScope prof(ctx, ETF_K_LEVEL);
             hipLaunchKernelGGL(k_level, dim3((unsigned)bx, (unsigned)tiles), dim3(256), 0, st,
                                reinterpret_cast<const uint8_t *>(ctx->dev_base + TL.icode[l]),
                                reinterpret_cast<const uint32_t *>(ctx->dev_base + TL.iparent[l]), n, prev, nprev,
@@ -313,12 +393,23 @@ template <int MODE>
 int launch_reduce(etf_ctx *ctx, const ReduceArgs &r, int64_t nitems, const uint32_t *map, int64_t tiles, const OutArgs &o)
 {
     if (nitems == 0) return ETF_OK;
-    const int64_t bx = blocks_for(nitems, 4 * 64, tiles);
-    int per_wave = (int)((nitems + bx * 4 - 1) / (bx * 4));
-    if (MODE == OUT_ALLPAIRS) per_wave = (per_wave + 63) & ~63;  // whole 64-wide output segments per wave
+    int per_wave;
+    if (MODE == OUT_SAMPLE) {
+        per_wave = o.gsize;  // one sample group per wave
+    } else {
+        const int64_t bx = blocks_for(nitems, 4 * 64, tiles);
+        per_wave = (int)((nitems + bx * 4 - 1) / (bx * 4));
+        per_wave = (per_wave + 63) & ~63;  // whole 64-item chunks per wave
+    }
     const int64_t bx2 = (nitems + (int64_t)per_wave * 4 - 1) / ((int64_t)per_wave * 4);
-    hipLaunchKernelGGL((k_reduce<MODE>), dim3((unsigned)bx2, (unsigned)tiles), dim3(256), 0, (hipStream_t)ctx->stream, r,
-                       nitems, map, per_wave, o);
+    const dim3 grid((unsigned)bx2, (unsigned)tiles), block(256);
+    hipStream_t st = (hipStream_t)ctx->stream;
+    ProfScope prof(ctx, MODE == OUT_SAMPLE ? ETF_K_SAMPLE : ETF_K_REDUCE);
+    if (r.T <= 1) hipLaunchKernelGGL((k_reduce<MODE, 1>), grid, block, 0, st, r, nitems, map, per_wave, o);
+    else if (r.T <= 2) hipLaunchKernelGGL((k_reduce<MODE, 2>), grid, block, 0, st, r, nitems, map, per_wave, o);
+    else if (r.T <= 4) hipLaunchKernelGGL((k_reduce<MODE, 4>), grid, block, 0, st, r, nitems, map, per_wave, o);
+    else if (r.T <= 8) hipLaunchKernelGGL((k_reduce<MODE, 8>), grid, block, 0, st, r, nitems, map, per_wave, o);
+    else hipLaunchKernelGGL((k_reduce<MODE, 16>), grid, block, 0, st, r, nitems, map, per_wave, o);
     LAUNCH_CHECK(ctx, "k_reduce");
     return ETF_OK;
 }
@@ -330,12 +421,14 @@ int launch_flat(etf_ctx *ctx, const Plan &P, char *ws, int64_t nitems, const uin
     const int M = ctx->M, K = ctx->K;
     const int G = pick_G(M, K);
     const size_t lds = (size_t)M * K * (WAVE / G) * 4;
-    const int64_t bx = blocks_for(nitems, 4096, tiles * G);
+    // sample mode: every (wave, lane group) of the 8-wave block owns whole sample groups
+    const int64_t bx = MODE == OUT_SAMPLE ? blocks_for(o.ngroups, 8 * G, tiles * G) : blocks_for(nitems, 4096, tiles * G);
     const int per_block = (int)((nitems + bx - 1) / bx);
     dim3 grid((unsigned)bx, (unsigned)G, (unsigned)tiles), block(512);
     hipStream_t st = (hipStream_t)ctx->stream;
     const uint8_t *codes = reinterpret_cast<const uint8_t *>(ctx->dev_base + ctx->lay.codes);
     const float *lutT = reinterpret_cast<const float *>(ws + P.o_lutT);
+    ProfScope prof(ctx, MODE == OUT_SAMPLE ? ETF_K_SAMPLE : ETF_K_FLAT);
 #define FLAT_CASE(GG)                                                                                        \
     case GG: {                                                                                               \
         int rc = set_lds(ctx, k_flat<GG, MODE>, lds);                                                        \
@@ -480,8 +573,9 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
         LAUNCH_CHECK(ctx, "k_fill_u32");
         OutArgs o;
         memset(&o, 0, sizeof o);
-        o.sdist = P.use_tau ? reinterpret_cast<float *>(w + P.o_sdist) : nullptr;
-        o.S = P.S;
+        o.gmin = P.use_tau ? reinterpret_cast<float *>(w + P.o_gmin) : nullptr;
+        o.ngroups = P.ngroups;
+        o.gsize = P.gsize;
         o.tau = tau;
         o.cnt = cnt;
         o.cand = cand;
@@ -500,7 +594,10 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
                 else
                     rc = launch_reduce<OUT_SAMPLE>(ctx, r, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_enc), tiles, o);
                 if (rc) return rc;
-                hipLaunchKernelGGL(k_tau, dim3((unsigned)tiles), dim3(1024), 0, st, o.sdist, P.S, k, 3, nq, tau);
+                {
+                    ProfScope prof(ctx, ETF_K_TAU);
+                    hipLaunchKernelGGL(k_tau, dim3((unsigned)tiles), dim3(1024), 0, st, o.gmin, P.ngroups, k, 4, nq, tau);
+                }
                 LAUNCH_CHECK(ctx, "k_tau");
             } else {
                 hipLaunchKernelGGL(k_fill_f32, dim3(fb), dim3(256), 0, st, tau, nql, nq, __builtin_inff(), -1.f);
@@ -522,7 +619,10 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
         sa.out_ids = out_ids + q0 * k;
         sa.out_dist = out_dist + q0 * k;
         sa.flag = flag;
-        hipLaunchKernelGGL(k_select, dim3((unsigned)nq), dim3(256), 0, st, sa);
+        {
+            ProfScope prof(ctx, ETF_K_SELECT);
+            hipLaunchKernelGGL(k_select, dim3((unsigned)nq), dim3(256), 0, st, sa);
+        }
         LAUNCH_CHECK(ctx, "k_select");
         ExactArgs ea;
         memset(&ea, 0, sizeof ea);
@@ -549,7 +649,10 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
         ea.k = k;
         ea.out_ids = sa.out_ids;
         ea.out_dist = sa.out_dist;
-        hipLaunchKernelGGL(k_exact, dim3((unsigned)nq), dim3(256), 0, st, ea);
+        {
+            ProfScope prof(ctx, ETF_K_EXACT);
+            hipLaunchKernelGGL(k_exact, dim3((unsigned)nq), dim3(256), 0, st, ea);
+        }
         LAUNCH_CHECK(ctx, "k_exact");
     }
     return ETF_OK;

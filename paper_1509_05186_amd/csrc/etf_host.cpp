@@ -546,6 +546,11 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
             uint64_t s = 0x1509051860ull ^ (uint64_t)N;
             int64_t want = std::max<int64_t>(ctx->opt.sample_min, ix.Nd / ctx->opt.sample_div);
             int64_t S = std::min<int64_t>(ix.Nd, want);
+            // The sample is stored in random order: consecutive runs of it are the sample groups whose
+            // minima bound the k-th distance, and a group must not be a cluster of similar encodings.
+            auto shuffle = [&s](std::vector<uint32_t> &v) {
+                for (size_t i = v.size(); i > 1; --i) std::swap(v[i - 1], v[splitmix64(s) % i]);
+            };
             if (S == ix.Nd) {
                 ix.sample_enc.resize(S);
                 for (int64_t i = 0; i < S; ++i) ix.sample_enc[i] = (uint32_t)i;
@@ -556,6 +561,7 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
                 v.erase(std::unique(v.begin(), v.end()), v.end());
                 ix.sample_enc.swap(v);
             }
+            shuffle(ix.sample_enc);
             want = std::max<int64_t>(ctx->opt.sample_min, N / ctx->opt.sample_div);
             S = std::min<int64_t>(N, want);
             if (S == N) {
@@ -568,6 +574,7 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
                 v.erase(std::unique(v.begin(), v.end()), v.end());
                 ix.sample_pos.swap(v);
             }
+            shuffle(ix.sample_pos);
         }
         ix.built = true;
         ctx->idx = std::move(ix);

@@ -92,6 +92,11 @@ struct etf_ctx {
     etf::Options opt;
     // diagnostics of the most recent search (device address inside the caller's workspace)
     void *last_flag_count = nullptr;
+    // per-kernel timing: pairs of hipEvent_t (stored untyped so that host-only code need not see HIP)
+    bool profile_on = false;
+    struct Stamp { void *start, *stop; int cls; };
+    std::vector<Stamp> stamps;      // recorded since the last read
+    std::vector<Stamp> stamp_pool;  // events ready for reuse
 };
 
 namespace etf {

@@ -18,6 +18,7 @@
 namespace etf {
 
 constexpr int WAVE = 64;
+constexpr int UB = 8;  // rows a wave keeps in flight
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -90,12 +91,24 @@ __global__ __launch_bounds__(256) void k_level(const uint8_t *__restrict__ icode
     const float *lrow = lutT + ((int64_t)tile * M + m) * K * QT + lane;
     const float *prow = prev ? prev + (int64_t)tile * nprev * QT + lane : nullptr;
     float *orow = out + (int64_t)tile * n * QT + lane;
-#pragma unroll 4
-    for (int64_t i = lo; i < hi; ++i) {
-        const int code = icode[i];
-        float v = lrow[(int64_t)code * QT];
-        if (prow) v = prow[(int64_t)iparent[i] * QT] + v;
-        orow[i * QT] = v;
+    // 64 nodes at a time: lane i fetches the record of node base+i, then the wave walks the nodes with
+    // the record broadcast from that lane, UB row loads in flight before the first store
+    for (int64_t base = lo; base < hi; base += 64) {
+        const int cnt = (int)min<int64_t>(64, hi - base);
+        const int my_code = lane < cnt ? (int)icode[base + lane] : 0;
+        const int my_par = (prow && lane < cnt) ? (int)iparent[base + lane] : 0;
+        for (int s0 = 0; s0 < cnt; s0 += UB) {
+            float a[UB], b[UB];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int sidx = min(s0 + u, cnt - 1);
+                a[u] = lrow[(int64_t)__builtin_amdgcn_readlane(my_code, sidx) * QT];
+                b[u] = prow ? prow[(int64_t)(uint32_t)__builtin_amdgcn_readlane(my_par, sidx) * QT] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < UB; ++u)
+                if (s0 + u < cnt) orow[(base + s0 + u) * QT] = prow ? b[u] + a[u] : a[u];
+        }
     }
 }
 
@@ -140,23 +153,51 @@ __global__ void k_leaf(const uint8_t *__restrict__ lcodes, int width, const uint
     const float *prow = prev ? prev + (int64_t)tile * nprev * QT + col : nullptr;
     float *orow = out + (int64_t)tile * U * QT + col;
     const uint32_t *rec = reinterpret_cast<const uint32_t *>(lcodes);
-    for (int64_t j = blo + (int64_t)w * G + lg; j < bhi; j += (int64_t)nw * G) {
-        uint32_t dw[NDW];
+    // 64 leaves at a time: lane i fetches the record of leaf base+i; then every step handles G leaves
+    // (lane group lg takes leaf s+lg), with UB parent rows in flight before the lookups start
+    for (int64_t base = blo + (int64_t)w * 64; base < bhi; base += (int64_t)nw * 64) {
+        const int cnt = (int)min<int64_t>(64, bhi - base);
+        uint32_t my_dw[NDW];
 #pragma unroll
-        for (int i = 0; i < NDW; ++i) dw[i] = rec[j * NDW + i];
-        float acc = prow ? prow[(int64_t)lparent[j] * QT] : 0.f;
+        for (int i = 0; i < NDW; ++i) my_dw[i] = lane < cnt ? rec[(base + lane) * NDW + i] : 0u;
+        const uint32_t my_par = (prow && lane < cnt) ? lparent[base + lane] : 0u;
+        const uint32_t my_row = lane < cnt ? lrow[base + lane] : 0u;
+        for (int s0 = 0; s0 < cnt; s0 += UB * G) {
+            float acc[UB];
+            uint32_t row[UB];
+            uint32_t dw[UB][NDW];
 #pragma unroll
-        for (int i = 0; i < NDW; ++i) {
+            for (int u = 0; u < UB; ++u) {
+                const int src = min(s0 + u * G + lg, cnt - 1);
+                uint32_t par;
+                if (G == 1) {
+                    par = (uint32_t)__builtin_amdgcn_readlane((int)my_par, src);
+                    row[u] = (uint32_t)__builtin_amdgcn_readlane((int)my_row, src);
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int c = i * 4 + b;
-                if (c < width) {
-                    const int code = (dw[i] >> (8 * b)) & 255;
-                    acc += lds[(c * K + code) * Qs + qq];
+                    for (int i = 0; i < NDW; ++i) dw[u][i] = (uint32_t)__builtin_amdgcn_readlane((int)my_dw[i], src);
+                } else {
+                    par = (uint32_t)__shfl((int)my_par, src);
+                    row[u] = (uint32_t)__shfl((int)my_row, src);
+#pragma unroll
+                    for (int i = 0; i < NDW; ++i) dw[u][i] = (uint32_t)__shfl((int)my_dw[i], src);
+                }
+                acc[u] = prow ? prow[(int64_t)par * QT] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+#pragma unroll
+                for (int i = 0; i < NDW; ++i) {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int c = i * 4 + b;
+                        if (c < width) acc[u] += lds[(c * K + ((dw[u][i] >> (8 * b)) & 255)) * Qs + qq];
+                    }
                 }
             }
+#pragma unroll
+            for (int u = 0; u < UB; ++u)
+                if (s0 + u * G + lg < cnt) orow[(int64_t)row[u] * QT] = acc[u];
         }
-        orow[(int64_t)lrow[j] * QT] = acc;
     }
 }
 
@@ -170,9 +211,11 @@ struct OutArgs {
     float *dist;        // [Q][N], rows q0.. of this batch
     int64_t N;          // row length
     int64_t nq;         // live queries of this batch (rows beyond are not written)
-    // OUT_SAMPLE
-    float *sdist;       // [tile][S][64]
-    int64_t S;
+    // OUT_SAMPLE: the sample is cut into groups of `gsize` consecutive entries; only the minimum of
+    // every group is kept
+    float *gmin;        // [tile][ngroups][64]
+    int64_t ngroups;
+    int gsize;
     // OUT_FILTER
     const float *tau;   // [tiles*64]
     uint32_t *cnt;      // [tiles*64]
@@ -194,6 +237,24 @@ __device__ __forceinline__ void emit_filter(const OutArgs &o, int tile, int col,
 //     items: ALLPAIRS -> n in [0,N) (input order); SAMPLE -> sample_pos[i]; FILTER -> n in [0,N).
 //     grid (blocks, G, tiles).
 // ------------------------------------------------------------------------------------------------
+template <int G>
+__device__ __forceinline__ float flat_one(const float *lds, const uint8_t *__restrict__ c, int M, int K, int qq)
+{
+    constexpr int Qs = WAVE / G;
+    float acc = 0.f;
+    if ((M & 3) == 0) {
+        const uint32_t *c4 = reinterpret_cast<const uint32_t *>(c);
+        for (int i = 0; i < (M >> 2); ++i) {
+            const uint32_t dw = c4[i];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) acc += lds[((i * 4 + b) * K + ((dw >> (8 * b)) & 255)) * Qs + qq];
+        }
+    } else {
+        for (int m = 0; m < M; ++m) acc += lds[(m * K + c[m]) * Qs + qq];
+    }
+    return acc;
+}
+
 template <int G, int MODE>
 __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const uint32_t *__restrict__ sample,
                        const float *__restrict__ lutT, int M, int K, int per_block, OutArgs o)
@@ -205,32 +266,28 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
     const int lane = threadIdx.x & 63;
     const int lg = lane / Qs, qq = lane % Qs;
     const int w = uniform(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    const int col = sub * Qs + qq;
+    if (MODE == OUT_SAMPLE) {
+        // every (wave, lane group) owns whole sample groups
+        for (int64_t g = ((int64_t)blockIdx.x * nw + w) * G + lg; g < o.ngroups; g += (int64_t)gridDim.x * nw * G) {
+            const int64_t lo = g * o.gsize, hi = min(nitems, lo + o.gsize);
+            float best = __uint_as_float(0x7F800000u);
+            for (int64_t j = lo; j < hi; ++j) best = fminf(best, flat_one<G>(lds, codes + (int64_t)sample[j] * M, M, K, qq));
+            o.gmin[((int64_t)tile * o.ngroups + g) * QT + col] = best;
+        }
+        return;
+    }
     const int64_t blo = (int64_t)blockIdx.x * per_block;
     const int64_t bhi = min(nitems, blo + per_block);
-    const int col = sub * Qs + qq;
     float tauv = 0.f;
     if (MODE == OUT_FILTER) tauv = o.tau[(int64_t)tile * QT + col];
     for (int64_t j = blo + (int64_t)w * G + lg; j < bhi; j += (int64_t)nw * G) {
-        const int64_t n = (MODE == OUT_SAMPLE) ? (int64_t)sample[j] : j;
-        const uint8_t *c = codes + n * M;
-        float acc = 0.f;
-        if ((M & 3) == 0) {
-            const uint32_t *c4 = reinterpret_cast<const uint32_t *>(c);
-            for (int i = 0; i < (M >> 2); ++i) {
-                const uint32_t dw = c4[i];
-#pragma unroll
-                for (int b = 0; b < 4; ++b) acc += lds[((i * 4 + b) * K + ((dw >> (8 * b)) & 255)) * Qs + qq];
-            }
-        } else {
-            for (int m = 0; m < M; ++m) acc += lds[(m * K + c[m]) * Qs + qq];
-        }
+        const float acc = flat_one<G>(lds, codes + j * M, M, K, qq);
         if (MODE == OUT_ALLPAIRS) {
             const int64_t ql = (int64_t)tile * QT + col;
-            if (ql < o.nq) o.dist[ql * o.N + n] = acc;
-        } else if (MODE == OUT_SAMPLE) {
-            o.sdist[((int64_t)tile * o.S + j) * QT + col] = acc;
+            if (ql < o.nq) o.dist[ql * o.N + j] = acc;
         } else {
-            emit_filter(o, tile, col, tauv, acc, (uint32_t)n);
+            emit_filter(o, tile, col, tauv, acc, (uint32_t)j);
         }
     }
 }
@@ -250,18 +307,42 @@ struct ReduceArgs {
     int T;
 };
 
-__device__ __forceinline__ float reduce_one(const ReduceArgs &r, int tile, int lane, uint32_t e)
+// rows of one item in every tree, fetched by the lane that owns the item in a 64-item chunk
+template <int TMAX>
+__device__ __forceinline__ void reduce_rows(const ReduceArgs &r, uint32_t e, bool live, uint32_t rows[TMAX])
 {
-    float d = 0.f;
-    for (int t = 0; t < r.T; ++t) {
-        const uint32_t row = r.leaf_of[t] ? r.leaf_of[t][e] : e;
-        const float v = r.leafp[t][((int64_t)tile * r.U[t] + row) * QT + lane];
-        d = (t == 0) ? v : d + v;
-    }
-    return d;
+#pragma unroll
+    for (int t = 0; t < TMAX; ++t)
+        rows[t] = (t < r.T && live) ? (r.leaf_of[t] ? r.leaf_of[t][e] : e) : 0u;
 }
 
-template <int MODE>
+// UB distances at a time for items s0 .. s0+UB-1 of the chunk: all T*UB row loads are issued before
+// the first add; trees are added in order
+template <int TMAX>
+__device__ __forceinline__ void reduce_batch(const ReduceArgs &r, int tile, int lane, const uint32_t my_rows[TMAX],
+                                             int s0, int cnt, float d[UB])
+{
+    float v[UB][TMAX];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+        const int src = min(s0 + u, cnt - 1);
+#pragma unroll
+        for (int t = 0; t < TMAX; ++t)
+            if (t < r.T) {
+                const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)my_rows[t], src);
+                v[u][t] = r.leafp[t][((int64_t)tile * r.U[t] + row) * QT + lane];
+            }
+    }
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+        d[u] = v[u][0];
+#pragma unroll
+        for (int t = 1; t < TMAX; ++t)
+            if (t < r.T) d[u] += v[u][t];
+    }
+}
+
+template <int MODE, int TMAX>
 __global__ __launch_bounds__(256) void k_reduce(ReduceArgs r, int64_t nitems, const uint32_t *__restrict__ map,
                                                 int per_wave, OutArgs o)
 {
@@ -271,37 +352,48 @@ __global__ __launch_bounds__(256) void k_reduce(ReduceArgs r, int64_t nitems, co
     const int64_t wv = (int64_t)blockIdx.x * 4 + w;
     const int64_t lo = wv * per_wave;
     const int64_t hi = min(nitems, lo + per_wave);
-    if (MODE == OUT_ALLPAIRS) {
-        __shared__ float tbuf[4][64][65];
-        for (int64_t n0 = lo; n0 < hi; n0 += 64) {
-            const int cntn = (int)min<int64_t>(64, hi - n0);
-            for (int jj = 0; jj < cntn; ++jj) tbuf[w][jj][lane] = reduce_one(r, tile, lane, map[n0 + jj]);
+    __shared__ float tbuf[MODE == OUT_ALLPAIRS ? 4 : 1][MODE == OUT_ALLPAIRS ? 64 : 1][65];
+    float tauv = 0.f, best = __uint_as_float(0x7F800000u);
+    if (MODE == OUT_FILTER) tauv = o.tau[(int64_t)tile * QT + lane];
+    for (int64_t base = lo; base < hi; base += 64) {
+        const int cnt = (int)min<int64_t>(64, hi - base);
+        const bool live = lane < cnt;
+        const uint32_t e = live ? (MODE == OUT_FILTER ? (uint32_t)(base + lane) : map[base + lane]) : 0u;
+        uint32_t my_rows[TMAX];
+        reduce_rows<TMAX>(r, e, live, my_rows);
+        for (int s0 = 0; s0 < cnt; s0 += UB) {
+            float d[UB];
+            reduce_batch<TMAX>(r, tile, lane, my_rows, s0, cnt, d);
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                if (s0 + u >= cnt) break;
+                if (MODE == OUT_ALLPAIRS) tbuf[w][s0 + u][lane] = d[u];
+                else if (MODE == OUT_SAMPLE) best = fminf(best, d[u]);
+                else emit_filter(o, tile, lane, tauv, d[u], (uint32_t)(base + s0 + u));
+            }
+        }
+        if (MODE == OUT_ALLPAIRS) {
             __builtin_amdgcn_wave_barrier();
             for (int qq = 0; qq < 64; ++qq) {
                 const int64_t ql = (int64_t)tile * QT + qq;
-                if (ql < o.nq && lane < cntn) o.dist[ql * o.N + n0 + lane] = tbuf[w][lane][qq];
+                if (ql < o.nq && lane < cnt) o.dist[ql * o.N + base + lane] = tbuf[w][lane][qq];
             }
             __builtin_amdgcn_wave_barrier();
         }
-    } else if (MODE == OUT_SAMPLE) {
-        for (int64_t i = lo; i < hi; ++i)
-            o.sdist[((int64_t)tile * o.S + i) * QT + lane] = reduce_one(r, tile, lane, map[i]);
-    } else {
-        const float tauv = o.tau[(int64_t)tile * QT + lane];
-#pragma unroll 2
-        for (int64_t e = lo; e < hi; ++e) emit_filter(o, tile, lane, tauv, reduce_one(r, tile, lane, (uint32_t)e), (uint32_t)e);
     }
+    // OUT_SAMPLE: a wave's items are one sample group (per_wave == gsize); keep its minimum
+    if (MODE == OUT_SAMPLE && lo < hi) o.gmin[((int64_t)tile * o.ngroups + wv) * QT + lane] = best;
 }
 
 // ------------------------------------------------------------------------------------------------
-// S5a  per-query threshold from the sample: an upper bound of the k-th smallest sample distance, found
-//      by a most-significant-digit radix select on the float bit patterns (distances are >= 0, so the
-//      patterns order like the values).  `passes` digits of 8 bits are resolved; the bound is the top
-//      of the remaining bucket.  Any subset of the database gives a valid bound: at least k database
-//      encodings are at or below it.
+// S5a  per-query bound from the sample.  Input: the minimum distance of each of S sample groups.  The
+//      k-th smallest group minimum is an upper bound of the k-th smallest database distance, because k
+//      different encodings (one per group) are at or below it.  Found by a most-significant-digit radix
+//      select on the float bit patterns (distances are >= 0, so the patterns order like the values);
+//      `passes` digits of 8 bits are resolved and the bound is the top of the remaining bucket.
 //      grid (tiles), block 1024, LDS hist[256][64].
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_tau(const float *__restrict__ sdist, int64_t S, int k, int passes,
+__global__ __launch_bounds__(1024) void k_tau(const float *__restrict__ gmin, int64_t S, int k, int passes,
                                               int64_t nq, float *__restrict__ tau)
 {
     __shared__ uint32_t hist[256][64];
@@ -317,7 +409,7 @@ __global__ __launch_bounds__(1024) void k_tau(const float *__restrict__ sdist, i
         if (threadIdx.x < 64) tau[ql] = (ql < nq) ? __uint_as_float(0x7F800000u) : -1.f;
         return;
     }
-    const float *col = sdist + (int64_t)tile * S * QT + lane;
+    const float *col = gmin + (int64_t)tile * S * QT + lane;
     int shift = 24;
     for (int p = 0; p < passes; ++p, shift -= 8) {
         for (int i = threadIdx.x; i < 256 * 64; i += blockDim.x) (&hist[0][0])[i] = 0;
@@ -405,6 +497,44 @@ __device__ __forceinline__ void block_inclusive_scan(uint32_t *v, int n, uint32_
     __syncthreads();
 }
 
+// Smallest 32-bit value v such that at least `rank` of the participating keys are <= v (block of 256
+// threads, most significant digit first, 4 passes of 8 bits).  key(i, v) returns false for entries
+// that do not take part.  Also returns how many keys equal v and how many of those the rank needs.
+// hist: 256 words of LDS, sh: 3 words of LDS.
+template <class KeyFn>
+__device__ __forceinline__ void block_radix_select(int n, uint32_t rank, KeyFn key, uint32_t *hist, uint32_t *sh,
+                                                   uint32_t &value, uint32_t &rank_in_ties, uint32_t &n_ties)
+{
+    uint32_t prefix = 0;
+    for (int p = 0, shift = 24; p < 4; ++p, shift -= 8) {
+        hist[threadIdx.x] = 0;
+        __syncthreads();
+        for (int i = threadIdx.x; i < n; i += 256) {
+            uint32_t v;
+            if (key(i, v) && (p == 0 || (v >> (shift + 8)) == (prefix >> (shift + 8)))) atomicAdd(&hist[(v >> shift) & 255], 1u);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t below = 0;
+            int b = 0;
+            for (; b < 255; ++b) {
+                if (below + hist[b] >= rank) break;
+                below += hist[b];
+            }
+            sh[0] = prefix | ((uint32_t)b << shift);
+            sh[1] = rank - below;
+            sh[2] = hist[b];
+        }
+        __syncthreads();
+        prefix = sh[0];
+        rank = sh[1];
+        n_ties = sh[2];
+        __syncthreads();
+    }
+    value = prefix;
+    rank_in_ties = rank;
+}
+
 __device__ __forceinline__ int pow2_at_least(int n)
 {
     int p = 1;
@@ -443,6 +573,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     __shared__ uint32_t tmp[256];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_a, s_b, s_c, s_d;
+    __shared__ uint32_t sel_sh[4];
     const int64_t ql = blockIdx.x;
     if (a.flag[ql]) return;  // already routed to the exact kernel
     const uint32_t craw = a.cnt[ql];
@@ -453,41 +584,37 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     const int c = (int)craw;
     const uint64_t *cand = a.cand + ql * a.C;
     const int k = a.k;
-    // 1. the value of the min(k, c)-th closest candidate
-    uint32_t vstar = 0xFFFFFFFFu;
+    // 1. the value of the min(k, c)-th closest candidate.  If more candidates tie with it exactly than
+    //    fit, only those with the smallest first ids can matter (ids inside an encoding ascend, so the r
+    //    smallest ids of a set of encodings lie in the r encodings with the smallest first id).
+    auto first_id = [&](uint32_t e) -> uint32_t { return (uint32_t)a.ids[a.ebegin ? a.ebegin[e] : e]; };
+    uint32_t vstar = 0xFFFFFFFFu, idstar = 0xFFFFFFFFu;
     if (c > KEPT_CAP) {
-        uint32_t prefix = 0, rank = (uint32_t)min(k, c);
-        for (int p = 0, shift = 24; p < 4; ++p, shift -= 8) {
-            hist[threadIdx.x] = 0;
-            __syncthreads();
-            for (int i = threadIdx.x; i < c; i += 256) {
-                const uint32_t v = (uint32_t)(cand[i] >> 32);
-                if (p == 0 || (v >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(v >> shift) & 255], 1u);
-            }
-            __syncthreads();
-            if (threadIdx.x == 0) {
-                uint32_t below = 0;
-                int b = 0;
-                for (; b < 255; ++b) {
-                    if (below + hist[b] >= rank) break;
-                    below += hist[b];
-                }
-                s_a = prefix | ((uint32_t)b << shift);
-                s_b = rank - below;
-            }
-            __syncthreads();
-            prefix = s_a;
-            rank = s_b;
-            __syncthreads();
+        const uint32_t rank = (uint32_t)min(k, c);
+        uint32_t rank_in_ties, n_ties;
+        block_radix_select(
+            c, rank, [&](int i, uint32_t &v) { v = (uint32_t)(cand[i] >> 32); return true; }, hist, sel_sh, vstar,
+            rank_in_ties, n_ties);
+        if (rank - rank_in_ties + n_ties > KEPT_CAP) {
+            uint32_t r2, n2;
+            block_radix_select(
+                c, rank_in_ties,
+                [&](int i, uint32_t &v) {
+                    const uint64_t key = cand[i];
+                    if ((uint32_t)(key >> 32) != vstar) return false;
+                    v = first_id((uint32_t)key);
+                    return true;
+                },
+                hist, sel_sh, idstar, r2, n2);
         }
-        vstar = prefix;
     }
     // 2. keep the candidates at or below it, sorted by (distance bits, item)
     if (threadIdx.x == 0) s_c = 0;
     __syncthreads();
     for (int i = threadIdx.x; i < c; i += 256) {
         const uint64_t key = cand[i];
-        if ((uint32_t)(key >> 32) <= vstar) {
+        const uint32_t v = (uint32_t)(key >> 32);
+        if (v < vstar || (v == vstar && (idstar == 0xFFFFFFFFu || first_id((uint32_t)key) <= idstar))) {
             const uint32_t pos = atomicAdd(&s_c, 1u);
             if (pos < KEPT_CAP) kept[pos] = key;
         }

@@ -190,7 +190,7 @@ def test_builder_ids_and_ranges():
     # samples are valid, distinct, sorted references
     se = arr(buf, lay.sample_enc, lay.n_sample_enc, np.uint32)
     sp = arr(buf, lay.sample_pos, lay.n_sample_pos, np.uint32)
-    assert len(se) == Nd and len(sp) == N and np.all(np.diff(se.astype(np.int64)) > 0)
+    assert sorted(se.tolist()) == list(range(Nd)) and sorted(sp.tolist()) == list(range(N))
 
 
 def test_builder_sampling_on_larger_input():
@@ -206,7 +206,8 @@ def test_builder_sampling_on_larger_input():
     sp = arr(buf, lay.sample_pos, lay.n_sample_pos, np.uint32)
     assert 0.9 * st["n_distinct"] / 32 <= len(se) <= st["n_distinct"] / 32 + 1 and se.max() < st["n_distinct"]
     assert 0.9 * N / 32 <= len(sp) <= N / 32 + 1 and sp.max() < N
-    assert np.all(np.diff(se.astype(np.int64)) > 0) and np.all(np.diff(sp.astype(np.int64)) > 0)
+    assert len(np.unique(se)) == len(se) and len(np.unique(sp)) == len(sp)
+    assert not np.all(np.diff(se.astype(np.int64)) > 0)       # stored in random order
     lut = rng.random((M, K))
     dist, _ = walk_image(c, lut)
     assert np.allclose(dist, oracle.adc_flat(lut, codes), rtol=1e-13)
