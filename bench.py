@@ -112,6 +112,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline and the parity spot check")
     ap.add_argument("--no-others", action="store_true", help="skip the flat and single-tree legs")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    ap.add_argument("--no-copy", action="store_true", help="skip the 1 GiB device copy (bandwidth ceiling / counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus %d is not supported); "
@@ -187,6 +188,27 @@ def main():
                                  "alg_GBps": tgb / (tms / 1e3) if tms > 0 else None,
                                  "frac": (tgb / (tms / 1e3)) / HBM_PEAK_GBS if tms > 0 else None}
 
+    # ---- a plain device copy of known size: achievable-bandwidth ceiling, and the reference dispatch
+    #      against which the HBM byte counters are scaled
+    copy = None
+    if not args.no_copy:
+        nbytes = 1 << 30
+        src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        copy = {"bytes_read": nbytes, "bytes_written": nbytes, "ms": ms, "GBps": 2 * nbytes / 1e9 / (ms / 1e3)}
+        log("device copy of 1 GiB: %.3f ms, %.0f GB/s (read + write)" % (ms, copy["GBps"]))
+        del src, dst
+
     # ---- the same workload through the flat kernel and a single E-Tree, same run
     others = {}
     if not args.no_others:
@@ -239,7 +261,7 @@ def main():
                                % (cfg.name, cfg.d, N, Q, cfg.M, cfg.K, T, k, cfg.components),
                    "valid": not (args.scale_n or args.scale_q)},
         "roofline": roofline, "cpu_baseline": cpu,
-        "kernels": kernels, "others": others, "fallback_queries": fallbacks,
+        "kernels": kernels, "others": others, "fallback_queries": fallbacks, "device_copy": copy,
         "index": {"n_distinct": stats["n_distinct"], "max_dup": stats["max_dup"], "device_MB": stats["device_bytes"] / 1e6,
                   "trees": stats["trees"], "sample": int(S)},
         "paper_context": PAPER_CONTEXT,

@@ -352,17 +352,32 @@ int launch_trees(etf_ctx *ctx, const Plan &P, char *ws, int64_t tiles)
             const HostBucket &B = tr.bucket[l];
             const int64_t n = (int64_t)B.size();
             if (n == 0) continue;
-            const int G = pick_G(B.width, K);
-            const size_t lds = (size_t)B.width * K * (WAVE / G) * 4;
-            const int64_t bx = blocks_for(n, 2048, tiles * G);
-            const int per_block = (int)((n + bx - 1) / bx);
             const float *prev = l > 0 ? reinterpret_cast<const float *>(ws + P.o_part[t][l - 1]) : nullptr;
             const int64_t nprev = l > 0 ? (int64_t)tr.level[l - 1].code.size() : 0;
-            dim3 grid((unsigned)bx, (unsigned)G, (unsigned)tiles), block(512);
             const uint8_t *lc = reinterpret_cast<const uint8_t *>(ctx->dev_base + TL.lcodes[l]);
             const uint32_t *lp = reinterpret_cast<const uint32_t *>(ctx->dev_base + TL.lparent[l]);
             const uint32_t *lr = reinterpret_cast<const uint32_t *>(ctx->dev_base + TL.lrow[l]);
             float *out = reinterpret_cast<float *>(ws + P.o_leafp[t]);
+            if (B.width <= 2) {  // short leaves: table rows straight from L2, no LDS staging
+                const int64_t bx = blocks_for(n, 4 * 64, tiles);
+                int per_wave = (int)((n + bx * 4 - 1) / (bx * 4));
+                per_wave = (per_wave + 63) & ~63;
+                const int64_t bx2 = (n + (int64_t)per_wave * 4 - 1) / ((int64_t)per_wave * 4);
+                ProfScope prof(ctx, ETF_K_LEAF);
+                if (B.width == 1)
+                    hipLaunchKernelGGL((k_leaf_short<1>), dim3((unsigned)bx2, (unsigned)tiles), dim3(256), 0, st, lc, lp, lr, n,
+                                       prev, nprev, out, tr.U, lutT, M, K, tr.c0 + l, per_wave);
+                else
+                    hipLaunchKernelGGL((k_leaf_short<2>), dim3((unsigned)bx2, (unsigned)tiles), dim3(256), 0, st, lc, lp, lr, n,
+                                       prev, nprev, out, tr.U, lutT, M, K, tr.c0 + l, per_wave);
+                LAUNCH_CHECK(ctx, "k_leaf_short");
+                continue;
+            }
+            const int G = pick_G(B.width, K);
+            const size_t lds = (size_t)B.width * K * (WAVE / G) * 4;
+            const int64_t bx = blocks_for(n, 2048, tiles * G);
+            const int per_block = (int)((n + bx - 1) / bx);
+            dim3 grid((unsigned)bx, (unsigned)G, (unsigned)tiles), block(512);
             int rc;
             switch (G) {
                 case 1: rc = launch_leaf_g<1>(ctx, B.stride / 4, grid, block, lds, lc, B.width, lp, lr, n, prev, nprev, out, tr.U, lutT, tr.c0 + l, per_block); break;
@@ -386,6 +401,12 @@ void fill_reduce_args(const etf_ctx *ctx, const Plan &P, char *ws, ReduceArgs &r
         r.leafp[t] = reinterpret_cast<const float *>(ws + P.o_leafp[t]);
         r.leaf_of[t] = ctx->lay.tree[t].leaf_of >= 0 ? reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.tree[t].leaf_of) : nullptr;
         r.U[t] = ix.tree[t].U;
+    }
+    // padding slots up to the kernel's compile-time tree count: valid, cached, and not added
+    for (int t = ix.T; t < ETF_MAX_M; ++t) {
+        r.leafp[t] = r.leafp[0];
+        r.leaf_of[t] = r.leaf_of[0];
+        r.U[t] = r.U[0];
     }
 }
 

@@ -202,6 +202,56 @@ __global__ void k_leaf(const uint8_t *__restrict__ lcodes, int width, const uint
 }
 
 // ------------------------------------------------------------------------------------------------
+// S3 for short leaves (own chunk plus at most one postfix chunk, W = 1 or 2): the same sum, but the
+//     table rows are read straight from the transposed tables in global memory (a 64 KB slice per tile
+//     and chunk, resident in L2) instead of being staged in LDS, so the kernel needs no LDS, runs at
+//     full occupancy and has no staging phase.  Lane = query, one leaf per step, UB leaves in flight.
+//     grid (blocks, tiles), block 256; every wave takes `per_wave` consecutive leaves.
+// ------------------------------------------------------------------------------------------------
+template <int W>
+__global__ __launch_bounds__(256) void k_leaf_short(const uint8_t *__restrict__ lcodes, const uint32_t *__restrict__ lparent,
+                                                    const uint32_t *__restrict__ lrow, int64_t n,
+                                                    const float *__restrict__ prev, int64_t nprev, float *__restrict__ out,
+                                                    int64_t U, const float *__restrict__ lutT, int M, int K, int m0,
+                                                    int per_wave)
+{
+    const int tile = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int64_t wv = (int64_t)blockIdx.x * 4 + uniform(threadIdx.x >> 6);
+    const int64_t lo = wv * per_wave;
+    const int64_t hi = min(n, lo + per_wave);
+    const float *lut0 = lutT + ((int64_t)tile * M + m0) * K * QT + lane;
+    const float *prow = prev ? prev + (int64_t)tile * nprev * QT + lane : nullptr;
+    float *orow = out + (int64_t)tile * U * QT + lane;
+    const uint32_t *rec = reinterpret_cast<const uint32_t *>(lcodes);  // one 4-byte record per leaf
+    for (int64_t base = lo; base < hi; base += 64) {
+        const int cnt = (int)min<int64_t>(64, hi - base);
+        const int my_dw = lane < cnt ? (int)rec[base + lane] : 0;
+        const int my_par = (prow && lane < cnt) ? (int)lparent[base + lane] : 0;
+        const int my_row = lane < cnt ? (int)lrow[base + lane] : 0;
+        for (int s0 = 0; s0 < cnt; s0 += UB) {
+            float p[UB], v[UB][W];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int src = min(s0 + u, cnt - 1);
+                const uint32_t dw = (uint32_t)__builtin_amdgcn_readlane(my_dw, src);
+                p[u] = prow ? prow[(int64_t)(uint32_t)__builtin_amdgcn_readlane(my_par, src) * QT] : 0.f;
+#pragma unroll
+                for (int c = 0; c < W; ++c) v[u][c] = lut0[((int64_t)c * K + ((dw >> (8 * c)) & 255)) * QT];
+            }
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                if (s0 + u >= cnt) break;
+                float acc = p[u];
+#pragma unroll
+                for (int c = 0; c < W; ++c) acc += v[u][c];
+                orow[(int64_t)(uint32_t)__builtin_amdgcn_readlane(my_row, s0 + u) * QT] = acc;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Consumers of a finished distance.  One distance belongs to (item, query lane).
 // ------------------------------------------------------------------------------------------------
 enum { OUT_ALLPAIRS = 0, OUT_SAMPLE = 1, OUT_FILTER = 2 };
@@ -307,17 +357,19 @@ struct ReduceArgs {
     int T;
 };
 
-// rows of one item in every tree, fetched by the lane that owns the item in a 64-item chunk
+// rows of one item in every tree, fetched by the lane that owns the item in a 64-item chunk.
+// The host fills the entries t >= T of ReduceArgs with copies of tree 0, so that every one of the TMAX
+// slots is a valid load and the loops below contain no branch (a branch between the row loads makes the
+// compiler wait for each load before issuing the next).
 template <int TMAX>
 __device__ __forceinline__ void reduce_rows(const ReduceArgs &r, uint32_t e, bool live, uint32_t rows[TMAX])
 {
 #pragma unroll
-    for (int t = 0; t < TMAX; ++t)
-        rows[t] = (t < r.T && live) ? (r.leaf_of[t] ? r.leaf_of[t][e] : e) : 0u;
+    for (int t = 0; t < TMAX; ++t) rows[t] = live ? (r.leaf_of[t] ? r.leaf_of[t][e] : e) : 0u;
 }
 
-// UB distances at a time for items s0 .. s0+UB-1 of the chunk: all T*UB row loads are issued before
-// the first add; trees are added in order
+// UB distances at a time for items s0 .. s0+UB-1 of the chunk: all TMAX*UB row loads are issued before
+// the first add; trees are added in order (padding slots add +0, which leaves a sum of squares unchanged)
 template <int TMAX>
 __device__ __forceinline__ void reduce_batch(const ReduceArgs &r, int tile, int lane, const uint32_t my_rows[TMAX],
                                              int s0, int cnt, float d[UB])
@@ -327,18 +379,16 @@ __device__ __forceinline__ void reduce_batch(const ReduceArgs &r, int tile, int 
     for (int u = 0; u < UB; ++u) {
         const int src = min(s0 + u, cnt - 1);
 #pragma unroll
-        for (int t = 0; t < TMAX; ++t)
-            if (t < r.T) {
-                const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)my_rows[t], src);
-                v[u][t] = r.leafp[t][((int64_t)tile * r.U[t] + row) * QT + lane];
-            }
+        for (int t = 0; t < TMAX; ++t) {
+            const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)my_rows[t], src);
+            v[u][t] = r.leafp[t][((int64_t)tile * r.U[t] + row) * QT + lane];
+        }
     }
 #pragma unroll
     for (int u = 0; u < UB; ++u) {
         d[u] = v[u][0];
 #pragma unroll
-        for (int t = 1; t < TMAX; ++t)
-            if (t < r.T) d[u] += v[u][t];
+        for (int t = 1; t < TMAX; ++t) d[u] += (t < r.T) ? v[u][t] : 0.f;
     }
 }
 
@@ -353,8 +403,20 @@ __global__ __launch_bounds__(256) void k_reduce(ReduceArgs r, int64_t nitems, co
     const int64_t lo = wv * per_wave;
     const int64_t hi = min(nitems, lo + per_wave);
     __shared__ float tbuf[MODE == OUT_ALLPAIRS ? 4 : 1][MODE == OUT_ALLPAIRS ? 64 : 1][65];
+    // OUT_FILTER: passing candidates are parked in LDS (STG per lane and wave) and appended to the
+    // query's list in one reservation, so the row loads are not interleaved with atomic round trips
+    constexpr int STG = 8;
+    __shared__ uint64_t stage[MODE == OUT_FILTER ? 4 : 1][MODE == OUT_FILTER ? STG : 1][64];
+    int nloc = 0;
+    const int64_t ql = (int64_t)tile * QT + lane;
+    auto flush = [&]() {
+        const uint32_t pos = atomicAdd(&o.cnt[ql], (uint32_t)nloc);
+        for (int i = 0; i < nloc; ++i)
+            if (pos + i < o.C) o.cand[ql * o.C + pos + i] = stage[w][i][lane];
+        nloc = 0;
+    };
     float tauv = 0.f, best = __uint_as_float(0x7F800000u);
-    if (MODE == OUT_FILTER) tauv = o.tau[(int64_t)tile * QT + lane];
+    if (MODE == OUT_FILTER) tauv = o.tau[ql];
     for (int64_t base = lo; base < hi; base += 64) {
         const int cnt = (int)min<int64_t>(64, hi - base);
         const bool live = lane < cnt;
@@ -369,7 +431,10 @@ __global__ __launch_bounds__(256) void k_reduce(ReduceArgs r, int64_t nitems, co
                 if (s0 + u >= cnt) break;
                 if (MODE == OUT_ALLPAIRS) tbuf[w][s0 + u][lane] = d[u];
                 else if (MODE == OUT_SAMPLE) best = fminf(best, d[u]);
-                else emit_filter(o, tile, lane, tauv, d[u], (uint32_t)(base + s0 + u));
+                else if (d[u] <= tauv) {
+                    stage[w][nloc][lane] = ((uint64_t)__float_as_uint(d[u]) << 32) | (uint32_t)(base + s0 + u);
+                    if (++nloc == STG) flush();
+                }
             }
         }
         if (MODE == OUT_ALLPAIRS) {
@@ -381,6 +446,7 @@ __global__ __launch_bounds__(256) void k_reduce(ReduceArgs r, int64_t nitems, co
             __builtin_amdgcn_wave_barrier();
         }
     }
+    if (MODE == OUT_FILTER && nloc > 0) flush();
     // OUT_SAMPLE: a wave's items are one sample group (per_wave == gsize); keep its minimum
     if (MODE == OUT_SAMPLE && lo < hi) o.gmin[((int64_t)tile * o.ngroups + wv) * QT + lane] = best;
 }
