@@ -96,6 +96,9 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     whole-database selection kernel (testing)
  *   "sample_min" / "sample_div"   threshold-sample size = max(sample_min, n/sample_div)
  *   "cand_cap"        per-query candidate capacity (0 = derived from k)
+ *   "traversal"       0 (default): trees are walked in depth-first leaf order with the distance
+ *                     context in registers; 1: level-synchronous kernels over the level arrays
+ *                     (partial sums of internal nodes in device memory)
  * Returns ETF_EINVAL for an unknown name or a value out of range. */
 int etf_set_option(etf_ctx *ctx, const char *name, int64_t value);
 
@@ -148,6 +151,9 @@ int etf_index_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes);
  *   sample_pos  u32 [n_sample_pos]   input positions used for the same purpose in flat mode
  *   leaf_of[t]  u32 [n_distinct] leaf (row of tree t's result table) of every distinct
  *                                encoding; absent when T = 1 (the identity)
+ *   rec0 / trec[t]   the sorted distinct (sub-)encodings again as zero-padded records of 4, 8 or
+ *                            16 bytes: the depth-first leaf sequence of each tree, walked by the
+ *                            kernels that keep the distance context in registers
  *   icode / iparent [t][l]   internal nodes of a level in lexicographic (= breadth-first)
  *                            order: chunk value (u8) and index of the parent in level l (u32;
  *                            0xFFFFFFFF at level 1)
@@ -162,6 +168,10 @@ typedef struct etf_layout {
     int64_t icode[ETF_MAX_M][ETF_MAX_M], iparent[ETF_MAX_M][ETF_MAX_M];
     int64_t lcodes[ETF_MAX_M][ETF_MAX_M], lparent[ETF_MAX_M][ETF_MAX_M], lrow[ETF_MAX_M][ETF_MAX_M];
     int32_t lstride[ETF_MAX_M][ETF_MAX_M];
+    int64_t rec0;                  /* u8 [n_distinct][rec0_stride]: tree 0's chunks of every distinct encoding */
+    int32_t rec0_stride;
+    int64_t trec[ETF_MAX_M];       /* u8 [L2 of tree t][trec_stride[t]]: the tree's leaves as plain records     */
+    int32_t trec_stride[ETF_MAX_M];
 } etf_layout;
 int etf_index_layout(const etf_ctx *ctx, etf_layout *out);
 /* Writes the device image to host memory (at least etf_index_device_bytes()): the

@@ -69,6 +69,8 @@ class EtfLayout(ctypes.Structure):
         ("leaf_of", ctypes.c_int64 * ETF_MAX_M),
         ("icode", _Grid64), ("iparent", _Grid64), ("lcodes", _Grid64), ("lparent", _Grid64), ("lrow", _Grid64),
         ("lstride", _Grid32),
+        ("rec0", ctypes.c_int64), ("rec0_stride", ctypes.c_int32),
+        ("trec", ctypes.c_int64 * ETF_MAX_M), ("trec_stride", ctypes.c_int32 * ETF_MAX_M),
     ]
 
 

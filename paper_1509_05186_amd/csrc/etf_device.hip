@@ -7,6 +7,7 @@
 
 #include "etf_internal.h"
 #include "etf_kernels.hip.h"
+#include "etf_ctx_kernels.hip.h"
 
 using namespace etf;
 
@@ -170,6 +171,7 @@ struct Plan {
     int64_t ngroups = 0;      // ceil(S / gsize)
     uint32_t C = 0;           // candidate capacity per query
     bool use_tau = false;
+    bool ctx_path = false;    // trees walked with the distance context in registers (no partial-sum tables)
     int64_t o_counter = 0, o_lutT = 0, o_gmin = 0, o_tau = 0, o_cnt = 0, o_flag = 0, o_cand = 0;
     int64_t o_part[ETF_MAX_M][ETF_MAX_M];
     int64_t o_leafp[ETF_MAX_M];
@@ -177,6 +179,7 @@ struct Plan {
 };
 
 int64_t al256(int64_t x) { return (x + 255) & ~(int64_t)255; }
+int tmax_class(int T);
 
 int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan &P)
 {
@@ -217,10 +220,12 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     }
     // bytes per tile of 64 queries
     int64_t per_tile = (int64_t)M * K * QT * 4;
+    P.ctx_path = tmax_class(ix.T) != 0 && mode != ETF_MODE_FLAT && ctx->opt.traversal == 0;
     if (mode != ETF_MODE_FLAT)
-        for (int t = 0; t < ix.T; ++t) {
+        for (int t = P.ctx_path ? 1 : 0; t < ix.T; ++t) {
             const HostTree &tr = ix.tree[t];
-            for (int l = 0; l + 1 < tr.D; ++l) per_tile += al256((int64_t)tr.level[l].code.size() * QT * 4);
+            if (!P.ctx_path)
+                for (int l = 0; l + 1 < tr.D; ++l) per_tile += al256((int64_t)tr.level[l].code.size() * QT * 4);
             per_tile += al256(tr.U * QT * 4);
         }
     if (search) {
@@ -239,9 +244,10 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     P.o_counter = take(256);
     P.o_lutT = take(P.NT * M * K * QT * 4);
     if (mode != ETF_MODE_FLAT)
-        for (int t = 0; t < ix.T; ++t) {
+        for (int t = P.ctx_path ? 1 : 0; t < ix.T; ++t) {
             const HostTree &tr = ix.tree[t];
-            for (int l = 0; l + 1 < tr.D; ++l) P.o_part[t][l] = take(P.NT * (int64_t)tr.level[l].code.size() * QT * 4);
+            if (!P.ctx_path)
+                for (int l = 0; l + 1 < tr.D; ++l) P.o_part[t][l] = take(P.NT * (int64_t)tr.level[l].code.size() * QT * 4);
             P.o_leafp[t] = take(P.NT * tr.U * QT * 4);
         }
     if (search) {
@@ -410,6 +416,111 @@ void fill_reduce_args(const etf_ctx *ctx, const Plan &P, char *ws, ReduceArgs &r
     }
 }
 
+// ---- register-context traversal ----------------------------------------------------------------
+
+int tmax_class(int T) { return T <= 1 ? 1 : T <= 2 ? 2 : T <= 4 ? 4 : 0; }
+
+// The fused tree-0 kernel is instantiated for up to 4 trees; other shapes (and the explicit option) use
+// the level-synchronous kernels.
+
+// result tables of trees 1 .. T-1 (tree 0 is evaluated inside the fused kernel)
+int launch_trees_ctx(etf_ctx *ctx, const Plan &P, char *ws, int64_t tiles)
+{
+    const HostIndex &ix = ctx->idx;
+    hipStream_t st = (hipStream_t)ctx->stream;
+    const float *lutT = reinterpret_cast<const float *>(ws + P.o_lutT);
+    for (int t = 1; t < ix.T; ++t) {
+        const HostTree &tr = ix.tree[t];
+        const uint32_t *codes = reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.tree[t].rec);
+        float *out = reinterpret_cast<float *>(ws + P.o_leafp[t]);
+        const int64_t bx = blocks_for(tr.U, 4 * 64, tiles);
+        int per_wave = (int)((tr.U + bx * 4 - 1) / (bx * 4));
+        per_wave = (per_wave + 63) & ~63;
+        const int64_t bx2 = (tr.U + (int64_t)per_wave * 4 - 1) / ((int64_t)per_wave * 4);
+        const dim3 grid((unsigned)bx2, (unsigned)tiles), block(256);
+        ProfScope prof(ctx, ETF_K_LEAF);
+#define TREE_CASE(DT, NDW)                                                                                       \
+    case DT:                                                                                                     \
+        hipLaunchKernelGGL((k_tree_ctx<DT, NDW>), grid, block, 0, st, codes, tr.U, out, lutT, ix.M, ix.K, tr.c0, \
+                           tr.D, per_wave);                                                                      \
+        break;
+        switch (depth_class(tr.D)) {
+            TREE_CASE(1, 1)
+            TREE_CASE(2, 1)
+            TREE_CASE(4, 1)
+            TREE_CASE(8, 2)
+            TREE_CASE(16, 4)
+            default: return fail(ctx, ETF_EINVAL, "tree depth %d", tr.D);
+        }
+#undef TREE_CASE
+        LAUNCH_CHECK(ctx, "k_tree_ctx");
+    }
+    return ETF_OK;
+}
+
+void fill_fused_args(const etf_ctx *ctx, const Plan &P, char *ws, ReduceArgs &r)
+{
+    const HostIndex &ix = ctx->idx;
+    memset(&r, 0, sizeof r);
+    r.T = ix.T;
+    for (int t = 1; t < ix.T; ++t) {
+        r.leafp[t] = reinterpret_cast<const float *>(ws + P.o_leafp[t]);
+        r.leaf_of[t] = reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.tree[t].leaf_of);
+        r.U[t] = ix.tree[t].U;
+    }
+    // padding slots up to the kernel's compile-time tree count: valid, cached, and not added
+    for (int t = std::max(ix.T, 2); t < ETF_MAX_M; ++t) {
+        r.leafp[t] = r.leafp[1];
+        r.leaf_of[t] = r.leaf_of[1];
+        r.U[t] = r.U[1];
+    }
+}
+
+template <int MODE, int DT, int NDW>
+int launch_fused_d(etf_ctx *ctx, const Plan &P, char *ws, const ReduceArgs &r, int64_t nitems, const uint32_t *map,
+                   int64_t tiles, const OutArgs &o, dim3 grid, int per_wave)
+{
+    const HostIndex &ix = ctx->idx;
+    hipStream_t st = (hipStream_t)ctx->stream;
+    const float *lutT = reinterpret_cast<const float *>(ws + P.o_lutT);
+    const uint32_t *codes0 = reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.rec0);
+    const int D0 = ix.tree[0].D;
+    switch (tmax_class(ix.T)) {
+        case 1: hipLaunchKernelGGL((k_fused<MODE, DT, NDW, 1>), grid, dim3(256), 0, st, codes0, D0, lutT, ix.M, ix.K, r, nitems, map, per_wave, o); break;
+        case 2: hipLaunchKernelGGL((k_fused<MODE, DT, NDW, 2>), grid, dim3(256), 0, st, codes0, D0, lutT, ix.M, ix.K, r, nitems, map, per_wave, o); break;
+        case 4: hipLaunchKernelGGL((k_fused<MODE, DT, NDW, 4>), grid, dim3(256), 0, st, codes0, D0, lutT, ix.M, ix.K, r, nitems, map, per_wave, o); break;
+        default: return fail(ctx, ETF_EINVAL, "no fused kernel for %d trees", ix.T);
+    }
+    LAUNCH_CHECK(ctx, "k_fused");
+    return ETF_OK;
+}
+
+template <int MODE>
+int launch_fused(etf_ctx *ctx, const Plan &P, char *ws, const ReduceArgs &r, int64_t nitems, const uint32_t *map,
+                 int64_t tiles, const OutArgs &o)
+{
+    if (nitems == 0) return ETF_OK;
+    int per_wave;
+    if (MODE == OUT_SAMPLE) {
+        per_wave = o.gsize;  // one sample group per wave
+    } else {
+        const int64_t bx = blocks_for(nitems, 4 * 64, tiles);
+        per_wave = (int)((nitems + bx * 4 - 1) / (bx * 4));
+        per_wave = (per_wave + 63) & ~63;
+    }
+    const int64_t bx2 = (nitems + (int64_t)per_wave * 4 - 1) / ((int64_t)per_wave * 4);
+    const dim3 grid((unsigned)bx2, (unsigned)tiles);
+    ProfScope prof(ctx, MODE == OUT_SAMPLE ? ETF_K_SAMPLE : ETF_K_REDUCE);
+    switch (depth_class(ctx->idx.tree[0].D)) {
+        case 1: return launch_fused_d<MODE, 1, 1>(ctx, P, ws, r, nitems, map, tiles, o, grid, per_wave);
+        case 2: return launch_fused_d<MODE, 2, 1>(ctx, P, ws, r, nitems, map, tiles, o, grid, per_wave);
+        case 4: return launch_fused_d<MODE, 4, 1>(ctx, P, ws, r, nitems, map, tiles, o, grid, per_wave);
+        case 8: return launch_fused_d<MODE, 8, 2>(ctx, P, ws, r, nitems, map, tiles, o, grid, per_wave);
+        case 16: return launch_fused_d<MODE, 16, 4>(ctx, P, ws, r, nitems, map, tiles, o, grid, per_wave);
+        default: return fail(ctx, ETF_EINVAL, "tree depth %d", ctx->idx.tree[0].D);
+    }
+}
+
 template <int MODE>
 int launch_reduce(etf_ctx *ctx, const ReduceArgs &r, int64_t nitems, const uint32_t *map, int64_t tiles, const OutArgs &o)
 {
@@ -542,11 +653,19 @@ extern "C" int etf_adc(etf_ctx *ctx, const float *queries, int64_t Q, int mode, 
             rc = launch_flat<OUT_ALLPAIRS>(ctx, P, w, ix.N, nullptr, tiles, o);
             if (rc) return rc;
         } else {
-            rc = launch_trees(ctx, P, w, tiles);
-            if (rc) return rc;
+            const uint32_t *enc_of_pos = reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.enc_of_pos);
             ReduceArgs r;
-            fill_reduce_args(ctx, P, w, r);
-            rc = launch_reduce<OUT_ALLPAIRS>(ctx, r, ix.N, reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.enc_of_pos), tiles, o);
+            if (P.ctx_path) {
+                rc = launch_trees_ctx(ctx, P, w, tiles);
+                if (rc) return rc;
+                fill_fused_args(ctx, P, w, r);
+                rc = launch_fused<OUT_ALLPAIRS>(ctx, P, w, r, ix.N, enc_of_pos, tiles, o);
+            } else {
+                rc = launch_trees(ctx, P, w, tiles);
+                if (rc) return rc;
+                fill_reduce_args(ctx, P, w, r);
+                rc = launch_reduce<OUT_ALLPAIRS>(ctx, r, ix.N, enc_of_pos, tiles, o);
+            }
             if (rc) return rc;
         }
     }
@@ -604,16 +723,18 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
         o.nq = nq;
         ReduceArgs r;
         if (!flat) {
-            rc = launch_trees(ctx, P, w, tiles);
+            rc = P.ctx_path ? launch_trees_ctx(ctx, P, w, tiles) : launch_trees(ctx, P, w, tiles);
             if (rc) return rc;
-            fill_reduce_args(ctx, P, w, r);
+            if (P.ctx_path) fill_fused_args(ctx, P, w, r);
+            else fill_reduce_args(ctx, P, w, r);
         }
         if (!ctx->opt.force_fallback) {
             if (P.use_tau) {
                 if (flat)
                     rc = launch_flat<OUT_SAMPLE>(ctx, P, w, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_pos), tiles, o);
                 else
-                    rc = launch_reduce<OUT_SAMPLE>(ctx, r, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_enc), tiles, o);
+                    rc = P.ctx_path ? launch_fused<OUT_SAMPLE>(ctx, P, w, r, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_enc), tiles, o)
+                                    : launch_reduce<OUT_SAMPLE>(ctx, r, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_enc), tiles, o);
                 if (rc) return rc;
                 {
                     ProfScope prof(ctx, ETF_K_TAU);
@@ -627,7 +748,8 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
             if (flat)
                 rc = launch_flat<OUT_FILTER>(ctx, P, w, ix.N, nullptr, tiles, o);
             else
-                rc = launch_reduce<OUT_FILTER>(ctx, r, ix.Nd, nullptr, tiles, o);
+                rc = P.ctx_path ? launch_fused<OUT_FILTER>(ctx, P, w, r, ix.Nd, nullptr, tiles, o)
+                                : launch_reduce<OUT_FILTER>(ctx, r, ix.Nd, nullptr, tiles, o);
             if (rc) return rc;
         }
         SelectArgs sa;

@@ -180,6 +180,11 @@ static void build_tree(const std::vector<KeyRec> &sub /* sorted, distinct keys *
         B.row.push_back((uint32_t)i);
         lcp_prev = lcp_next;
     }
+    // the same leaves as plain padded records in lexicographic order (register-context traversal)
+    tr.rstride = std::max(4, depth_class(D));
+    tr.rec.assign((size_t)U * tr.rstride, 0);
+    for (int64_t i = 0; i < U; ++i)
+        for (int j = 0; j < D; ++j) tr.rec[(size_t)i * tr.rstride + j] = (uint8_t)key_byte(sub[i].k, j);
 }
 
 static int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
@@ -203,11 +208,13 @@ void compute_layout(etf_ctx *ctx)
     L.ecodes = take((int64_t)ix.ecodes.size());
     L.sample_enc = take((int64_t)ix.sample_enc.size() * 4);
     L.sample_pos = take((int64_t)ix.sample_pos.size() * 4);
+    L.rec0 = take((int64_t)ix.rec0.size());
     L.tree.assign(ix.T, DevTreeLayout());
     for (int t = 0; t < ix.T; ++t) {
         const HostTree &tr = ix.tree[t];
         DevTreeLayout &TL = L.tree[t];
         TL.leaf_of = tr.leaf_of.empty() ? -1 : take((int64_t)tr.leaf_of.size() * 4);
+        TL.rec = take((int64_t)tr.rec.size());
         for (int l = 0; l < tr.D; ++l) {
             TL.icode[l] = take((int64_t)tr.level[l].code.size());
             TL.iparent[l] = take((int64_t)tr.level[l].parent.size() * 4);
@@ -232,10 +239,12 @@ void for_each_image_array(const etf_ctx *ctx, const std::function<void(int64_t, 
     put(L.ecodes, ix.ecodes.data(), ix.ecodes.size());
     put(L.sample_enc, ix.sample_enc.data(), ix.sample_enc.size() * 4);
     put(L.sample_pos, ix.sample_pos.data(), ix.sample_pos.size() * 4);
+    put(L.rec0, ix.rec0.data(), ix.rec0.size());
     for (int t = 0; t < ix.T; ++t) {
         const HostTree &tr = ix.tree[t];
         const DevTreeLayout &TL = L.tree[t];
         if (TL.leaf_of >= 0) put(TL.leaf_of, tr.leaf_of.data(), tr.leaf_of.size() * 4);
+        put(TL.rec, tr.rec.data(), tr.rec.size());
         for (int l = 0; l < tr.D; ++l) {
             put(TL.icode[l], tr.level[l].code.data(), tr.level[l].code.size());
             put(TL.iparent[l], tr.level[l].parent.data(), tr.level[l].parent.size() * 4);
@@ -284,6 +293,9 @@ extern "C" int etf_set_option(etf_ctx *ctx, const char *name, int64_t value)
     } else if (n == "sample_div") {
         if (value < 1) return fail(ctx, ETF_EINVAL, "sample_div must be positive");
         ctx->opt.sample_div = value;
+    } else if (n == "traversal") {
+        if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "traversal must be 0 (register context) or 1 (level-synchronous)");
+        ctx->opt.traversal = value;
     } else if (n == "cand_cap") {
         if (value < 0 || value > (1 << 20)) return fail(ctx, ETF_EINVAL, "cand_cap out of range");
         ctx->opt.cand_cap = value;
@@ -541,6 +553,15 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
             build_tree(uniq, tr.D, tr);
         }
 
+        // tree 0's chunks of every distinct encoding, as padded records (fused tree-0 / reduction kernel)
+        {
+            const int D0 = ix.tree[0].D;
+            ix.rstride0 = std::max(4, depth_class(D0));
+            ix.rec0.assign((size_t)ix.Nd * ix.rstride0, 0);
+            for (int64_t e = 0; e < ix.Nd; ++e)
+                memcpy(ix.rec0.data() + (size_t)e * ix.rstride0, ix.ecodes.data() + (size_t)e * M, (size_t)D0);
+        }
+
         // 4. threshold samples: a seeded random subset of the vectors (as encodings, and as positions)
         {
             uint64_t s = 0x1509051860ull ^ (uint64_t)N;
@@ -632,10 +653,14 @@ extern "C" int etf_index_layout(const etf_ctx *ctx, etf_layout *out)
     out->codebooks = L.codebooks; out->codes = L.codes; out->ids_in = L.ids_in; out->ids_sorted = L.ids_sorted;
     out->ebegin = L.ebegin; out->enc_of_pos = L.enc_of_pos; out->ecodes = L.ecodes;
     out->sample_enc = L.sample_enc; out->sample_pos = L.sample_pos;
+    out->rec0 = L.rec0;
+    out->rec0_stride = ix.rstride0;
     out->n_sample_enc = (int64_t)ix.sample_enc.size();
     out->n_sample_pos = (int64_t)ix.sample_pos.size();
     for (int t = 0; t < ix.T; ++t) {
         out->leaf_of[t] = L.tree[t].leaf_of;
+        out->trec[t] = L.tree[t].rec;
+        out->trec_stride[t] = ix.tree[t].rstride;
         for (int l = 0; l < ix.tree[t].D; ++l) {
             out->icode[t][l] = L.tree[t].icode[l];
             out->iparent[t][l] = L.tree[t].iparent[l];

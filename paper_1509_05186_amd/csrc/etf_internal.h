@@ -36,7 +36,17 @@ struct HostTree {
     std::vector<HostLevel> level;           // [D]   (entry l = level l+1; the last one is always empty)
     std::vector<HostBucket> bucket;         // [D]   (entry l = leaves at level l+1)
     std::vector<uint32_t> leaf_of;          // [n_distinct] leaf row of every distinct full encoding (empty if T == 1)
+    int rstride = 0;                        // bytes per record of `rec`: D rounded up to 1, 2, 4, 8 or 16, at least 4
+    std::vector<uint8_t> rec;               // [U][rstride] the distinct sub-encodings in lexicographic order, zero padded
 };
+
+// smallest of 1, 2, 4, 8, 16 that is >= D: the unrolled depth of the register-context kernels
+inline int depth_class(int D)
+{
+    int c = 1;
+    while (c < D) c <<= 1;
+    return c;
+}
 
 struct HostIndex {
     bool built = false;
@@ -51,12 +61,15 @@ struct HostIndex {
     std::vector<uint8_t> ecodes;            // [Nd][M] distinct encodings in sorted order
     std::vector<uint32_t> sample_enc;       // sorted distinct-encoding numbers of the threshold sample
     std::vector<uint32_t> sample_pos;       // input positions of the flat-mode threshold sample
+    int rstride0 = 0;
+    std::vector<uint8_t> rec0;              // [Nd][rstride0] tree 0's chunks of every distinct encoding, zero padded
     std::vector<HostTree> tree;
 };
 
 // Device image: offsets (bytes) into the uploaded buffer.
 struct DevTreeLayout {
     int64_t leaf_of = -1;
+    int64_t rec = 0;
     int64_t icode[ETF_MAX_M], iparent[ETF_MAX_M];
     int64_t lcodes[ETF_MAX_M], lparent[ETF_MAX_M], lrow[ETF_MAX_M];
 };
@@ -64,7 +77,7 @@ struct DevTreeLayout {
 struct DevLayout {
     int64_t total = 0;
     int64_t codebooks = 0, codes = 0, ids_in = 0, ids_sorted = 0, ebegin = 0, enc_of_pos = 0, ecodes = 0,
-            sample_enc = 0, sample_pos = 0;
+            sample_enc = 0, sample_pos = 0, rec0 = 0;
     std::vector<DevTreeLayout> tree;
 };
 
@@ -74,6 +87,7 @@ struct Options {
     int64_t sample_min = 32768;
     int64_t sample_div = 32;
     int64_t cand_cap = 0;
+    int64_t traversal = 0;  // 0: distance context in registers, 1: level-synchronous kernels
 };
 
 }  // namespace etf

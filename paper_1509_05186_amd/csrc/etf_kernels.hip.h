@@ -18,7 +18,10 @@
 namespace etf {
 
 constexpr int WAVE = 64;
-constexpr int UB = 8;  // rows a wave keeps in flight
+#ifndef ETF_UB
+#define ETF_UB 8
+#endif
+constexpr int UB = ETF_UB;  // rows a wave keeps in flight
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -27,6 +30,27 @@ __device__ __forceinline__ int64_t uniform64(int64_t v)
     uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
     uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
     return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// Runs of equal row indices.  Consecutive nodes usually share their parent row (siblings are adjacent in
+// every level array), and a second load of a row that is still in flight is not served by the L1 but
+// travels to the L2 again, which costs about as much as a fresh row.  So only the first entry of a run
+// loads its row; the others load row 0 of the same table (resident in L1 after its first use) and take
+// the value of their predecessor.  Everything is arithmetic on masks: a select or a branch between the
+// loads would make the compiler split the batch and wait for each load before issuing the next.
+// Lane i of a 64-entry chunk holds index my_idx; the result is 0 where entry i repeats entry i-1 (entry
+// 0 is compared with the last index of the previous chunk) and ~0 where it starts a new run.
+__device__ __forceinline__ uint32_t run_mask(uint32_t my_idx, int lane, int cnt, uint32_t carry_idx)
+{
+    const uint32_t up = (uint32_t)__shfl_up((int)my_idx, 1);
+    const uint32_t before = lane == 0 ? carry_idx : up;
+    return (lane < cnt && my_idx != before) ? 0xFFFFFFFFu : 0u;
+}
+
+// value of entry u: its own load where it starts a run (m = ~0), else the predecessor's value
+__device__ __forceinline__ float run_pick(float loaded, float before, uint32_t m)
+{
+    return __uint_as_float((__float_as_uint(loaded) & m) | (__float_as_uint(before) & ~m));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -93,18 +117,30 @@ __global__ __launch_bounds__(256) void k_level(const uint8_t *__restrict__ icode
     float *orow = out + (int64_t)tile * n * QT + lane;
     // 64 nodes at a time: lane i fetches the record of node base+i, then the wave walks the nodes with
     // the record broadcast from that lane, UB row loads in flight before the first store
+    float carry = 0.f;
+    uint32_t carry_idx = NO_PARENT;
     for (int64_t base = lo; base < hi; base += 64) {
         const int cnt = (int)min<int64_t>(64, hi - base);
         const int my_code = lane < cnt ? (int)icode[base + lane] : 0;
-        const int my_par = (prow && lane < cnt) ? (int)iparent[base + lane] : 0;
+        const uint32_t my_par = (prow && lane < cnt) ? iparent[base + lane] : 0u;
+        const uint32_t my_m = prow ? run_mask(my_par, lane, cnt, carry_idx) : 0u;
+        const uint32_t my_eff = my_par & my_m;
+        carry_idx = (uint32_t)__builtin_amdgcn_readlane((int)my_par, cnt - 1);
         for (int s0 = 0; s0 < cnt; s0 += UB) {
             float a[UB], b[UB];
 #pragma unroll
             for (int u = 0; u < UB; ++u) {
                 const int sidx = min(s0 + u, cnt - 1);
                 a[u] = lrow[(int64_t)__builtin_amdgcn_readlane(my_code, sidx) * QT];
-                b[u] = prow ? prow[(int64_t)(uint32_t)__builtin_amdgcn_readlane(my_par, sidx) * QT] : 0.f;
+                b[u] = prow ? prow[(int64_t)(uint32_t)__builtin_amdgcn_readlane((int)my_eff, sidx) * QT] : 0.f;
             }
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int sidx = min(s0 + u, cnt - 1);
+                const uint32_t m = (s0 + u < cnt) ? (uint32_t)__builtin_amdgcn_readlane((int)my_m, sidx) : 0u;
+                b[u] = run_pick(b[u], u == 0 ? carry : b[u - 1], m);
+            }
+            carry = b[UB - 1];
 #pragma unroll
             for (int u = 0; u < UB; ++u)
                 if (s0 + u < cnt) orow[(base + s0 + u) * QT] = prow ? b[u] + a[u] : a[u];
@@ -224,25 +260,37 @@ __global__ __launch_bounds__(256) void k_leaf_short(const uint8_t *__restrict__ 
     const float *prow = prev ? prev + (int64_t)tile * nprev * QT + lane : nullptr;
     float *orow = out + (int64_t)tile * U * QT + lane;
     const uint32_t *rec = reinterpret_cast<const uint32_t *>(lcodes);  // one 4-byte record per leaf
+    float carry = 0.f;
+    uint32_t carry_idx = NO_PARENT;
     for (int64_t base = lo; base < hi; base += 64) {
         const int cnt = (int)min<int64_t>(64, hi - base);
         const int my_dw = lane < cnt ? (int)rec[base + lane] : 0;
-        const int my_par = (prow && lane < cnt) ? (int)lparent[base + lane] : 0;
+        const uint32_t my_par = (prow && lane < cnt) ? lparent[base + lane] : 0u;
         const int my_row = lane < cnt ? (int)lrow[base + lane] : 0;
+        const uint32_t my_m = prow ? run_mask(my_par, lane, cnt, carry_idx) : 0u;
+        const uint32_t my_eff = my_par & my_m;
+        carry_idx = (uint32_t)__builtin_amdgcn_readlane((int)my_par, cnt - 1);
         for (int s0 = 0; s0 < cnt; s0 += UB) {
             float p[UB], v[UB][W];
 #pragma unroll
             for (int u = 0; u < UB; ++u) {
                 const int src = min(s0 + u, cnt - 1);
                 const uint32_t dw = (uint32_t)__builtin_amdgcn_readlane(my_dw, src);
-                p[u] = prow ? prow[(int64_t)(uint32_t)__builtin_amdgcn_readlane(my_par, src) * QT] : 0.f;
+                p[u] = prow ? prow[(int64_t)(uint32_t)__builtin_amdgcn_readlane((int)my_eff, src) * QT] : 0.f;
 #pragma unroll
                 for (int c = 0; c < W; ++c) v[u][c] = lut0[((int64_t)c * K + ((dw >> (8 * c)) & 255)) * QT];
             }
 #pragma unroll
             for (int u = 0; u < UB; ++u) {
+                const int src = min(s0 + u, cnt - 1);
+                const uint32_t m = (s0 + u < cnt) ? (uint32_t)__builtin_amdgcn_readlane((int)my_m, src) : 0u;
+                p[u] = run_pick(p[u], u == 0 ? carry : p[u - 1], m);
+            }
+            carry = p[UB - 1];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
                 if (s0 + u >= cnt) break;
-                float acc = p[u];
+                float acc = prow ? p[u] : 0.f;
 #pragma unroll
                 for (int c = 0; c < W; ++c) acc += v[u][c];
                 orow[(int64_t)(uint32_t)__builtin_amdgcn_readlane(my_row, s0 + u) * QT] = acc;

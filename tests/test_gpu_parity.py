@@ -71,27 +71,35 @@ def test_lut_build(small):
     assert_distances_close(lut.reshape(small.Q, -1), ref.reshape(small.Q, -1), "lut")
 
 
+TRAVERSALS = [0, 1]      # 0: distance context in registers, 1: level-synchronous kernels
+
+
+@pytest.mark.parametrize("trav", TRAVERSALS)
 @pytest.mark.parametrize("mode,T", [(FLAT, 1), (TREE, 1), (FOREST, 1), (FOREST, 2), (FOREST, 4), (FOREST, 8)])
-def test_adc_all_pairs(small, mode, T):
-    say("adc all pairs mode", mode, "T", T)
-    c = small.ctx(T=T)
+def test_adc_all_pairs(small, mode, T, trav):
+    if mode == FLAT and trav == 1:
+        pytest.skip("flat mode has no tree traversal")
+    say("adc all pairs mode", mode, "T", T, "traversal", trav)
+    c = small.ctx(T=T, traversal=trav)
     dist = c.adc(qdev(small), mode)
     torch.cuda.synchronize()
     assert_distances_close(dist.cpu().numpy(), small.ref_all, "adc mode %d T %d" % (mode, T))
 
 
-def test_tree_equals_flat_bitwise(small):
-    say("tree == flat bitwise")
-    c = small.ctx(T=1)
+@pytest.mark.parametrize("trav", TRAVERSALS)
+def test_tree_equals_flat_bitwise(small, trav):
+    say("tree == flat bitwise, traversal", trav)
+    c = small.ctx(T=1, traversal=trav)
     a = c.adc(qdev(small), FLAT)
     b = c.adc(qdev(small), TREE)
     torch.cuda.synchronize()
     assert torch.equal(a, b)       # same left-to-right float32 sum, shared prefixes added once
 
 
-def test_adc_unequal_groups_and_batches(small):
-    say("adc unequal chunk groups, tiny workspace cap => several query batches")
-    c = small.ctx(T=3, chunk_begin=[0, 1, 4, 8], ws_cap_bytes=1 << 20)
+@pytest.mark.parametrize("trav", TRAVERSALS)
+def test_adc_unequal_groups_and_batches(small, trav):
+    say("adc unequal chunk groups, tiny workspace cap => several query batches, traversal", trav)
+    c = small.ctx(T=3, chunk_begin=[0, 1, 4, 8], ws_cap_bytes=1 << 20, traversal=trav)
     dist = c.adc(qdev(small), FOREST)
     torch.cuda.synchronize()
     assert_distances_close(dist.cpu().numpy(), small.ref_all, "adc T=3")
@@ -107,11 +115,14 @@ def check_search(p, c, mode, k, ids=None, what=""):
     return oi, od
 
 
+@pytest.mark.parametrize("trav", TRAVERSALS)
 @pytest.mark.parametrize("mode,T", [(FLAT, 1), (TREE, 1), (FOREST, 2), (FOREST, 4)])
 @pytest.mark.parametrize("k", [1, 10, 100])
-def test_search(small, mode, T, k):
-    say("search mode", mode, "T", T, "k", k)
-    c = small.ctx(T=T, sample_min=2048)          # small sample so that the threshold path is exercised
+def test_search(small, mode, T, k, trav):
+    if mode == FLAT and trav == 1:
+        pytest.skip("flat mode has no tree traversal")
+    say("search mode", mode, "T", T, "k", k, "traversal", trav)
+    c = small.ctx(T=T, sample_min=2048, traversal=trav)   # small sample so that the threshold path is exercised
     check_search(small, c, mode, k, what="search m%d T%d k%d" % (mode, T, k))
     assert c.last_fallback_count() == 0
 
@@ -132,17 +143,21 @@ def test_search_exact_kernel(small, mode, T):
     c = small.ctx(T=T, force_fallback=1)
     a_i, a_d = check_search(small, c, mode, 50, what="exact m%d" % mode)
     assert c.last_fallback_count() == small.Q
-    c2 = small.ctx(T=T, sample_min=2048)
-    b_i, b_d = c2.search(qdev(small), 50, mode)
-    torch.cuda.synchronize()
-    assert np.array_equal(a_i, b_i.cpu().numpy()) and np.array_equal(a_d, b_d.cpu().numpy())
+    for trav in TRAVERSALS:      # the same float32 values whichever way the trees are walked
+        c2 = small.ctx(T=T, sample_min=2048, traversal=trav)
+        b_i, b_d = c2.search(qdev(small), 50, mode)
+        torch.cuda.synchronize()
+        assert np.array_equal(a_i, b_i.cpu().numpy()) and np.array_equal(a_d, b_d.cpu().numpy())
 
 
+@pytest.mark.parametrize("trav", TRAVERSALS)
 @pytest.mark.parametrize("mode,T", [(FLAT, 1), (TREE, 1), (FOREST, 2)])
-def test_search_with_duplicates_and_custom_ids(dups, mode, T):
-    say("search on heavily duplicated encodings, custom ids, mode", mode)
+def test_search_with_duplicates_and_custom_ids(dups, mode, T, trav):
+    if mode == FLAT and trav == 1:
+        pytest.skip("flat mode has no tree traversal")
+    say("search on heavily duplicated encodings, custom ids, mode", mode, "traversal", trav)
     ids = (np.random.default_rng(0).permutation(dups.N) * 7 + 3).astype(np.int32)
-    c = dups.ctx(T=T, ids=ids, sample_min=512)
+    c = dups.ctx(T=T, ids=ids, sample_min=512, traversal=trav)
     st = c.index_stats()
     assert st["max_dup"] >= 3 and st["n_distinct"] <= 256
     for k in (1, 5, 100, 1000):
@@ -151,6 +166,26 @@ def test_search_with_duplicates_and_custom_ids(dups, mode, T):
         # both sides order exact ties by id, so the lists agree wherever float32 and float64 agree on ties
         agree = (oi == ri).all(axis=1).mean()
         assert agree > 0.8, (k, agree)
+
+
+@pytest.fixture(scope="module")
+def wide():
+    # 16 chunks: two-word records, depth classes 16 (single tree), 8 and 4
+    return Problem(d=32, M=16, K=64, N=12000, Q=70, ntrain=3000, seed=14)
+
+
+@pytest.mark.parametrize("trav", TRAVERSALS)
+@pytest.mark.parametrize("mode,T,cbeg", [(TREE, 1, None), (FOREST, 2, None), (FOREST, 4, None), (FOREST, 3, [0, 5, 10, 16]),
+                                        (FOREST, 2, [0, 3, 16]), (FLAT, 1, None)])
+def test_sixteen_chunks(wide, mode, T, cbeg, trav):
+    if mode == FLAT and trav == 1:
+        pytest.skip("flat mode has no tree traversal")
+    say("M=16 mode", mode, "T", T, "chunks", cbeg, "traversal", trav)
+    c = wide.ctx(T=T, chunk_begin=cbeg, sample_min=1024, traversal=trav)
+    d = c.adc(qdev(wide), mode)
+    torch.cuda.synchronize()
+    assert_distances_close(d.cpu().numpy(), wide.ref_all, "M16 adc")
+    check_search(wide, c, mode, 20, what="M16 search")
 
 
 def test_search_small_database():
