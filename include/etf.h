@@ -151,9 +151,11 @@ int etf_index_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes);
  *   sample_pos  u32 [n_sample_pos]   input positions used for the same purpose in flat mode
  *   leaf_of[t]  u32 [n_distinct] leaf (row of tree t's result table) of every distinct
  *                                encoding; absent when T = 1 (the identity)
- *   rec0 / trec[t]   the sorted distinct (sub-)encodings again as zero-padded records of 4, 8 or
- *                            16 bytes: the depth-first leaf sequence of each tree, walked by the
- *                            kernels that keep the distance context in registers
+ *   rec0 / trec[t]   the sorted distinct (sub-)encodings again as records of 4, 8 or 16 bytes:
+ *                            the depth-first leaf sequence of each tree, walked by the kernels that
+ *                            keep the distance context in registers.  A tree of D chunks uses the
+ *                            last D of the first P bytes of a record, P = D rounded up to 1, 2, 4, 8
+ *                            or 16; all other bytes are zero
  *   icode / iparent [t][l]   internal nodes of a level in lexicographic (= breadth-first)
  *                            order: chunk value (u8) and index of the parent in level l (u32;
  *                            0xFFFFFFFF at level 1)

@@ -221,6 +221,8 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     // bytes per tile of 64 queries
     int64_t per_tile = (int64_t)M * K * QT * 4;
     P.ctx_path = tmax_class(ix.T) != 0 && mode != ETF_MODE_FLAT && ctx->opt.traversal == 0;
+    for (int t = 1; t < ix.T; ++t)  // the register-context kernels address a tree's result table with 32-bit offsets
+        if (ix.tree[t].U >= ((int64_t)1 << 24)) P.ctx_path = false;
     if (mode != ETF_MODE_FLAT)
         for (int t = P.ctx_path ? 1 : 0; t < ix.T; ++t) {
             const HostTree &tr = ix.tree[t];
@@ -433,23 +435,28 @@ int launch_trees_ctx(etf_ctx *ctx, const Plan &P, char *ws, int64_t tiles)
         const HostTree &tr = ix.tree[t];
         const uint32_t *codes = reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.tree[t].rec);
         float *out = reinterpret_cast<float *>(ws + P.o_leafp[t]);
-        const int64_t bx = blocks_for(tr.U, 4 * 64, tiles);
-        int per_wave = (int)((tr.U + bx * 4 - 1) / (bx * 4));
+        // 16 waves per workgroup share the staged slices; about 2048 workgroups per launch
+        const int64_t bx = blocks_for(tr.U, 16 * 64 * 4, tiles * 2);
+        int per_wave = (int)((tr.U + bx * 16 - 1) / (bx * 16));
         per_wave = (per_wave + 63) & ~63;
-        const int64_t bx2 = (tr.U + (int64_t)per_wave * 4 - 1) / ((int64_t)per_wave * 4);
-        const dim3 grid((unsigned)bx2, (unsigned)tiles), block(256);
+        const int64_t bx2 = (tr.U + (int64_t)per_wave * 16 - 1) / ((int64_t)per_wave * 16);
+        const dim3 grid((unsigned)bx2, (unsigned)tiles), block(1024);
         ProfScope prof(ctx, ETF_K_LEAF);
-#define TREE_CASE(DT, NDW)                                                                                       \
-    case DT:                                                                                                     \
-        hipLaunchKernelGGL((k_tree_ctx<DT, NDW>), grid, block, 0, st, codes, tr.U, out, lutT, ix.M, ix.K, tr.c0, \
-                           tr.D, per_wave);                                                                      \
-        break;
+#define TREE_CASE(DT, NDW, NL)                                                                                   \
+    case DT: {                                                                                                   \
+        const size_t lds = (size_t)NL * ix.K * QT * 4;                                                           \
+        int rc = set_lds(ctx, k_tree_ctx<DT, NDW, NL, UB>, lds);                                                     \
+        if (rc) return rc;                                                                                       \
+        hipLaunchKernelGGL((k_tree_ctx<DT, NDW, NL, UB>), grid, block, lds, st, codes, tr.U, out, lutT, ix.M, ix.K,  \
+                           tr.c0, tr.D, per_wave);                                                               \
+        break;                                                                                                   \
+    }
         switch (depth_class(tr.D)) {
-            TREE_CASE(1, 1)
-            TREE_CASE(2, 1)
-            TREE_CASE(4, 1)
-            TREE_CASE(8, 2)
-            TREE_CASE(16, 4)
+            TREE_CASE(1, 1, 1)
+            TREE_CASE(2, 1, 2)
+            TREE_CASE(4, 1, 2)
+            TREE_CASE(8, 2, 2)
+            TREE_CASE(16, 4, 2)
             default: return fail(ctx, ETF_EINVAL, "tree depth %d", tr.D);
         }
 #undef TREE_CASE
@@ -478,19 +485,30 @@ void fill_fused_args(const etf_ctx *ctx, const Plan &P, char *ws, ReduceArgs &r)
 
 template <int MODE, int DT, int NDW>
 int launch_fused_d(etf_ctx *ctx, const Plan &P, char *ws, const ReduceArgs &r, int64_t nitems, const uint32_t *map,
-                   int64_t tiles, const OutArgs &o, dim3 grid, int per_wave)
+                   const OutArgs &o, dim3 grid, dim3 block, int per_wave)
 {
+    constexpr int NL = MODE == OUT_ALLPAIRS ? 0 : (DT >= 2 ? 2 : 1);
     const HostIndex &ix = ctx->idx;
     hipStream_t st = (hipStream_t)ctx->stream;
     const float *lutT = reinterpret_cast<const float *>(ws + P.o_lutT);
     const uint32_t *codes0 = reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.rec0);
     const int D0 = ix.tree[0].D;
+    const size_t lds = (size_t)NL * ix.K * QT * 4;
+#define FUSED_CASE(TM)                                                                                              \
+    case TM: {                                                                                                      \
+        int rc = set_lds(ctx, k_fused<MODE, DT, NDW, TM, NL, UB>, lds);                                                 \
+        if (rc) return rc;                                                                                          \
+        hipLaunchKernelGGL((k_fused<MODE, DT, NDW, TM, NL, UB>), grid, block, lds, st, codes0, D0, lutT, ix.M, ix.K, r, \
+                           nitems, map, per_wave, o);                                                               \
+        break;                                                                                                      \
+    }
     switch (tmax_class(ix.T)) {
-        case 1: hipLaunchKernelGGL((k_fused<MODE, DT, NDW, 1>), grid, dim3(256), 0, st, codes0, D0, lutT, ix.M, ix.K, r, nitems, map, per_wave, o); break;
-        case 2: hipLaunchKernelGGL((k_fused<MODE, DT, NDW, 2>), grid, dim3(256), 0, st, codes0, D0, lutT, ix.M, ix.K, r, nitems, map, per_wave, o); break;
-        case 4: hipLaunchKernelGGL((k_fused<MODE, DT, NDW, 4>), grid, dim3(256), 0, st, codes0, D0, lutT, ix.M, ix.K, r, nitems, map, per_wave, o); break;
+        FUSED_CASE(1)
+        FUSED_CASE(2)
+        FUSED_CASE(4)
         default: return fail(ctx, ETF_EINVAL, "no fused kernel for %d trees", ix.T);
     }
+#undef FUSED_CASE
     LAUNCH_CHECK(ctx, "k_fused");
     return ETF_OK;
 }
@@ -500,23 +518,25 @@ int launch_fused(etf_ctx *ctx, const Plan &P, char *ws, const ReduceArgs &r, int
                  int64_t tiles, const OutArgs &o)
 {
     if (nitems == 0) return ETF_OK;
+    // all-pairs output is transposed through a per-wave LDS tile: 4 waves per workgroup there, 16 elsewhere
+    const int wpb = MODE == OUT_ALLPAIRS ? 4 : 16;
     int per_wave;
     if (MODE == OUT_SAMPLE) {
         per_wave = o.gsize;  // one sample group per wave
     } else {
-        const int64_t bx = blocks_for(nitems, 4 * 64, tiles);
-        per_wave = (int)((nitems + bx * 4 - 1) / (bx * 4));
+        const int64_t bx = blocks_for(nitems, wpb * 64 * 4, tiles * (MODE == OUT_ALLPAIRS ? 1 : 2));
+        per_wave = (int)((nitems + bx * wpb - 1) / (bx * wpb));
         per_wave = (per_wave + 63) & ~63;
     }
-    const int64_t bx2 = (nitems + (int64_t)per_wave * 4 - 1) / ((int64_t)per_wave * 4);
-    const dim3 grid((unsigned)bx2, (unsigned)tiles);
+    const int64_t bx2 = (nitems + (int64_t)per_wave * wpb - 1) / ((int64_t)per_wave * wpb);
+    const dim3 grid((unsigned)bx2, (unsigned)tiles), block(wpb * 64);
     ProfScope prof(ctx, MODE == OUT_SAMPLE ? ETF_K_SAMPLE : ETF_K_REDUCE);
     switch (depth_class(ctx->idx.tree[0].D)) {
-        case 1: return launch_fused_d<MODE, 1, 1>(ctx, P, ws, r, nitems, map, tiles, o, grid, per_wave);
-        case 2: return launch_fused_d<MODE, 2, 1>(ctx, P, ws, r, nitems, map, tiles, o, grid, per_wave);
-        case 4: return launch_fused_d<MODE, 4, 1>(ctx, P, ws, r, nitems, map, tiles, o, grid, per_wave);
-        case 8: return launch_fused_d<MODE, 8, 2>(ctx, P, ws, r, nitems, map, tiles, o, grid, per_wave);
-        case 16: return launch_fused_d<MODE, 16, 4>(ctx, P, ws, r, nitems, map, tiles, o, grid, per_wave);
+        case 1: return launch_fused_d<MODE, 1, 1>(ctx, P, ws, r, nitems, map, o, grid, block, per_wave);
+        case 2: return launch_fused_d<MODE, 2, 1>(ctx, P, ws, r, nitems, map, o, grid, block, per_wave);
+        case 4: return launch_fused_d<MODE, 4, 1>(ctx, P, ws, r, nitems, map, o, grid, block, per_wave);
+        case 8: return launch_fused_d<MODE, 8, 2>(ctx, P, ws, r, nitems, map, o, grid, block, per_wave);
+        case 16: return launch_fused_d<MODE, 16, 4>(ctx, P, ws, r, nitems, map, o, grid, block, per_wave);
         default: return fail(ctx, ETF_EINVAL, "tree depth %d", ctx->idx.tree[0].D);
     }
 }

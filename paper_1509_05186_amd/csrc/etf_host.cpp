@@ -181,10 +181,12 @@ static void build_tree(const std::vector<KeyRec> &sub /* sorted, distinct keys *
         lcp_prev = lcp_next;
     }
     // the same leaves as plain padded records in lexicographic order (register-context traversal)
+    // (padded at the front to the unrolled depth, so that the deepest level is always the last slot)
     tr.rstride = std::max(4, depth_class(D));
     tr.rec.assign((size_t)U * tr.rstride, 0);
+    const int pad = depth_class(D) - D;
     for (int64_t i = 0; i < U; ++i)
-        for (int j = 0; j < D; ++j) tr.rec[(size_t)i * tr.rstride + j] = (uint8_t)key_byte(sub[i].k, j);
+        for (int j = 0; j < D; ++j) tr.rec[(size_t)i * tr.rstride + pad + j] = (uint8_t)key_byte(sub[i].k, j);
 }
 
 static int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
@@ -558,8 +560,9 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
             const int D0 = ix.tree[0].D;
             ix.rstride0 = std::max(4, depth_class(D0));
             ix.rec0.assign((size_t)ix.Nd * ix.rstride0, 0);
+            const int pad = depth_class(D0) - D0;
             for (int64_t e = 0; e < ix.Nd; ++e)
-                memcpy(ix.rec0.data() + (size_t)e * ix.rstride0, ix.ecodes.data() + (size_t)e * M, (size_t)D0);
+                memcpy(ix.rec0.data() + (size_t)e * ix.rstride0 + pad, ix.ecodes.data() + (size_t)e * M, (size_t)D0);
         }
 
         // 4. threshold samples: a seeded random subset of the vectors (as encodings, and as positions)
