@@ -68,6 +68,17 @@ def algorithmic_bytes(stats, mode, S, tiles):
         out["flat"] = tiles * (G * N * M + M * K * row)
         out["sample"] = tiles * (S * (4 + M * G) + S * row + M * K * row)
         return out
+    if mode == "forest_ctx":
+        # register-context traversal: trees 1..T-1 each write one result row per leaf (reading a 4..16 byte
+        # record per leaf and their table slices); the fused kernel reads, per distinct encoding, one row
+        # of each of those tables, their leaf numbers and its tree-0 record, plus tree 0's table slices
+        rec = lambda D: max(4, 1 << max(D - 1, 0).bit_length())
+        trees = stats["trees"]
+        out["leaf"] = tiles * sum(tr["L2"] * (row + rec(tr["D"])) + tr["D"] * K * row for tr in trees[1:])
+        per_enc = (T - 1) * (row + 4) + rec(trees[0]["D"])
+        out["reduce"] = tiles * (Nd * per_enc + trees[0]["D"] * K * row)
+        out["sample"] = tiles * (S * (per_enc + 4) + trees[0]["D"] * K * row)
+        return out
     level = leaf = 0
     for tr in stats["trees"]:
         D = tr["D"]
@@ -112,6 +123,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline and the parity spot check")
     ap.add_argument("--no-others", action="store_true", help="skip the flat and single-tree legs")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    ap.add_argument("--levels", action="store_true",
+                    help="time the level-synchronous traversal (partial sums of internal nodes in HBM) instead of the default "
+                         "register-context traversal")
     ap.add_argument("--no-copy", action="store_true", help="skip the 1 GiB device copy (bandwidth ceiling / counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -138,6 +152,7 @@ def main():
 
     def make_ctx(T):
         c = etf.Context(device=0, stream=stream)
+        c.set_option("traversal", 1 if args.levels else 0)
         c.pq_set_codebooks(cb)
         t0 = time.time()
         c.index_build(codes, T=T)
@@ -162,7 +177,8 @@ def main():
     # ---- roofline of the dominant kernel class
     tiles = (Q + 63) // 64
     S = forest.index_layout().n_sample_enc
-    alg = algorithmic_bytes(stats, "forest", S, tiles)
+    ctx_path = not args.levels and T <= 4
+    alg = algorithmic_bytes(stats, "forest_ctx" if ctx_path else "forest", S, tiles)
     kernels = {}
     for name, (ms, cnt) in prof.items():
         if cnt:
@@ -259,6 +275,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: d=%d N=%d Q=%d PQ M=%d K=%d, E-Forest T=%d, top-%d, seeded %d-component Gaussian mixture"
                                % (cfg.name, cfg.d, N, Q, cfg.M, cfg.K, T, k, cfg.components),
+                   "traversal": "level-synchronous" if args.levels else "register-context",
                    "valid": not (args.scale_n or args.scale_q)},
         "roofline": roofline, "cpu_baseline": cpu,
         "kernels": kernels, "others": others, "fallback_queries": fallbacks, "device_copy": copy,

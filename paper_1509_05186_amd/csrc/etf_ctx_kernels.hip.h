@@ -275,7 +275,10 @@ __global__ __launch_bounds__(1024) void k_fused(const uint32_t *__restrict__ cod
                                                 const uint32_t *__restrict__ map, int per_wave, OutArgs o)
 {
     constexpr int NG1 = TMAX - 1;                              // tables gathered per item
-    constexpr int GP = NG1 == 1 ? 16 : UBT;                    // items per gather group (GP * NG1 rows in flight)
+#ifndef ETF_GP
+#define ETF_GP 16
+#endif
+    constexpr int GP = NG1 == 1 ? ETF_GP : UBT;                // items per gather group (GP * NG1 rows in flight)
     constexpr int NGRP = 64 / GP, NBAT = GP / UBT;
     constexpr int NV = NG1 > 0 ? NG1 : 1;
     constexpr int R = 4;                                       // parked candidates per lane

@@ -54,6 +54,7 @@ struct ProfScope {
 };
 
 static constexpr int64_t LDS_BUDGET = 128 * 1024;  // bytes of table slices a workgroup may stage
+static constexpr int CUB = 4;                       // items per batch of the register-context kernels (measured best)
 
 // =============================================================================================
 // context
@@ -445,9 +446,9 @@ int launch_trees_ctx(etf_ctx *ctx, const Plan &P, char *ws, int64_t tiles)
 #define TREE_CASE(DT, NDW, NL)                                                                                   \
     case DT: {                                                                                                   \
         const size_t lds = (size_t)NL * ix.K * QT * 4;                                                           \
-        int rc = set_lds(ctx, k_tree_ctx<DT, NDW, NL, UB>, lds);                                                     \
+        int rc = set_lds(ctx, k_tree_ctx<DT, NDW, NL, CUB>, lds);                                                     \
         if (rc) return rc;                                                                                       \
-        hipLaunchKernelGGL((k_tree_ctx<DT, NDW, NL, UB>), grid, block, lds, st, codes, tr.U, out, lutT, ix.M, ix.K,  \
+        hipLaunchKernelGGL((k_tree_ctx<DT, NDW, NL, CUB>), grid, block, lds, st, codes, tr.U, out, lutT, ix.M, ix.K,  \
                            tr.c0, tr.D, per_wave);                                                               \
         break;                                                                                                   \
     }
@@ -496,9 +497,9 @@ int launch_fused_d(etf_ctx *ctx, const Plan &P, char *ws, const ReduceArgs &r, i
     const size_t lds = (size_t)NL * ix.K * QT * 4;
 #define FUSED_CASE(TM)                                                                                              \
     case TM: {                                                                                                      \
-        int rc = set_lds(ctx, k_fused<MODE, DT, NDW, TM, NL, UB>, lds);                                                 \
+        int rc = set_lds(ctx, k_fused<MODE, DT, NDW, TM, NL, CUB>, lds);                                                 \
         if (rc) return rc;                                                                                          \
-        hipLaunchKernelGGL((k_fused<MODE, DT, NDW, TM, NL, UB>), grid, block, lds, st, codes0, D0, lutT, ix.M, ix.K, r, \
+        hipLaunchKernelGGL((k_fused<MODE, DT, NDW, TM, NL, CUB>), grid, block, lds, st, codes0, D0, lutT, ix.M, ix.K, r, \
                            nitems, map, per_wave, o);                                                               \
         break;                                                                                                      \
     }
