@@ -22,6 +22,10 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
 import numpy as np
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+# HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised
+# under profiles/ (counters scaled by what a 1 GiB copy in the same run reads).  Keyed by (workload, kernel class,
+# traversal); reported only for the exact configuration that was profiled.
+MEASURED_TRAFFIC_BYTES = {("cfg2", "reduce", "register-context"): 9.556e9}
 PAPER_CONTEXT = {              # the paper's own numbers: one Core i7 at 3.6 GHz, one query at a time, SIFT1M, M=8, K=256
     "hardware": "Intel Core i7 3.6 GHz (paper, section Experiments)",
     "ms_per_query": {"flat_adc": 2.678, "e_tree": 1.760, "e_forest_2": 1.265},
@@ -191,8 +195,10 @@ def main():
         kd = kernels[dom]
         lps = kd["launches_per_step"]
         achieved = kd["alg_GBps"] or 0.0
+        trav_name = "level-synchronous" if args.levels else "register-context"
+        traffic = None if (args.scale_n or args.scale_q) else MEASURED_TRAFFIC_BYTES.get((cfg.name, dom, trav_name))
         roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                     "alg_bytes_per_launch": alg.get(dom, 0) / lps if lps else None,
                     "avg_launch_ms": kd["ms_per_step"] / lps if lps else None,
                     "launches_per_step": lps}
