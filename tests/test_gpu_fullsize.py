@@ -1,0 +1,118 @@
+"""GPU parity at the sizes of the benchmark configurations, in the launch configuration bench.py times.
+
+The oracle cannot produce all N x Q distances of these sizes in a test, so a spread of queries (first tile,
+middle tiles, the ragged last tile) is checked completely: the oracle computes their distances to every
+encoding, and the tie-aware comparison of tests/parity.py is applied to the returned top-k."""
+import numpy as np
+import pytest
+
+import oracle
+from workload import GaussianMixture, get_config, SEED_TRAIN, SEED_DATABASE, SEED_QUERIES
+from parity import assert_distances_close, assert_topk_matches
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import paper_1509_05186_amd as etf  # noqa: E402
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def build_inputs(cfg, N=None, Q=None):
+    gm = GaussianMixture.from_config(cfg)
+    N, Q = N or cfg.N, Q or cfg.Q
+    host = etf.Context(device=None)
+    host.pq_train(gm.sample(cfg.n_train, SEED_TRAIN), cfg.M, cfg.K, cfg.kmeans_iters, seed=SEED_TRAIN)
+    codes = np.empty((N, cfg.M), dtype=np.uint8)
+    done = 0
+    for chunk in gm.chunks(N, SEED_DATABASE):
+        codes[done:done + len(chunk)] = host.pq_encode(chunk)
+        done += len(chunk)
+    return host.pq_get_codebooks(), codes, gm.sample(Q, SEED_QUERIES)
+
+
+def make_ctx(cb, codes, T, **opts):
+    c = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+    for name, v in opts.items():
+        c.set_option(name, v)
+    c.pq_set_codebooks(cb)
+    c.index_build(codes, T=T)
+    c.index_upload()
+    return c
+
+
+def check_sampled_queries(cb, codes, queries, ids, dist, k, nsample, what):
+    Q, N = queries.shape[0], codes.shape[0]
+    picks = np.unique(np.concatenate([np.arange(min(4, Q)), np.linspace(0, Q - 1, nsample).astype(int), [Q - 1]]))
+    for j in picks:
+        ref = oracle.adc_all(queries[j:j + 1], cb, codes)[0]
+        assert_topk_matches(ids[j], dist[j], ref, np.arange(N), k, "%s q%d" % (what, j))
+    return len(picks)
+
+
+def test_cfg2_forest_search_full_size():
+    cfg = get_config("cfg2")
+    say("cfg2 full size: building inputs")
+    cb, codes, queries = build_inputs(cfg)
+    qd = torch.from_numpy(queries).cuda()
+    for trav in (0, 1):
+        say("cfg2 E-Forest T=2 top-100, traversal", trav)
+        c = make_ctx(cb, codes, cfg.trees, traversal=trav)
+        ids, dist = c.search(qd, cfg.topk, etf.ETF_MODE_FOREST)
+        torch.cuda.synchronize()
+        assert c.last_fallback_count() == 0
+        n = check_sampled_queries(cb, codes, queries, ids.cpu().numpy(), dist.cpu().numpy(), cfg.topk, 12, "cfg2 trav%d" % trav)
+        say("  checked", n, "queries against the oracle")
+        if trav == 0:
+            first = (ids.clone(), dist.clone())
+        else:   # both traversals add the same float32 values in the same order
+            assert torch.equal(first[0], ids) and torch.equal(first[1], dist)
+    say("cfg2 single E-Tree and flat, same queries")
+    c = make_ctx(cb, codes, 1)
+    for mode in (etf.ETF_MODE_TREE, etf.ETF_MODE_FLAT):
+        ids, dist = c.search(qd, cfg.topk, mode)
+        torch.cuda.synchronize()
+        check_sampled_queries(cb, codes, queries, ids.cpu().numpy(), dist.cpu().numpy(), cfg.topk, 6, "cfg2 mode%d" % mode)
+
+
+def test_cfg1_all_pairs_full_size():
+    cfg = get_config("cfg1")
+    say("cfg1 full size: all pairs, single E-Tree")
+    cb, codes, queries = build_inputs(cfg)
+    ref = oracle.adc_all(queries, cb, codes)
+    qd = torch.from_numpy(queries).cuda()
+    c = make_ctx(cb, codes, 1)
+    for mode in (etf.ETF_MODE_TREE, etf.ETF_MODE_FLAT):
+        d = c.adc(qd, mode)
+        torch.cuda.synchronize()
+        assert_distances_close(d.cpu().numpy(), ref, "cfg1 mode %d" % mode)
+    c = make_ctx(cb, codes, 1, traversal=1)
+    d = c.adc(qd, etf.ETF_MODE_TREE)
+    torch.cuda.synchronize()
+    assert_distances_close(d.cpu().numpy(), ref, "cfg1 level-synchronous")
+
+
+@pytest.mark.parametrize("name,N,Q", [("cfg3", 150_000, 200), ("cfg4", 400_000, 300), ("cfg5", 600_000, 256)])
+def test_other_configurations_scaled(name, N, Q):
+    """Shapes of the remaining configurations (960-d vectors; 16-byte codes in 4 trees; 96-d, query batches of 256)
+    at a database size the oracle can cover completely."""
+    cfg = get_config(name)
+    say(name, "scaled to N =", N, "Q =", Q)
+    cb, codes, queries = build_inputs(cfg, N, Q)
+    qd = torch.from_numpy(queries).cuda()
+    ref = oracle.adc_all(queries[:40], cb, codes)
+    forest = make_ctx(cb, codes, cfg.trees, sample_min=4096)
+    ids, dist = forest.search(qd, cfg.topk, etf.ETF_MODE_FOREST)
+    torch.cuda.synchronize()
+    ids, dist = ids.cpu().numpy(), dist.cpu().numpy()
+    for j in range(40):
+        assert_topk_matches(ids[j], dist[j], ref[j], np.arange(N), cfg.topk, "%s forest q%d" % (name, j))
+    if name == "cfg3":      # this configuration also times a single tree
+        tree = make_ctx(cb, codes, 1, sample_min=4096)
+        ids, dist = tree.search(qd, cfg.topk, etf.ETF_MODE_TREE)
+        torch.cuda.synchronize()
+        ids, dist = ids.cpu().numpy(), dist.cpu().numpy()
+        for j in range(40):
+            assert_topk_matches(ids[j], dist[j], ref[j], np.arange(N), cfg.topk, "cfg3 tree q%d" % j)
