@@ -96,6 +96,10 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     whole-database selection kernel (testing)
  *   "sample_min" / "sample_div"   threshold-sample size = max(sample_min, n/sample_div)
  *   "cand_cap"        per-query candidate capacity (0 = derived from k)
+ *   "lut_kernel"      0 (default): lookup tables on the matrix cores, as ||q'||^2 - 2 q'.c' + ||c'||^2
+ *                     on vectors shifted by the group's mean codeword; entries below a quarter of
+ *                     ||q'||^2 + ||c'||^2, where that form cancels, are recomputed as plain sums.
+ *                     1: every entry as a plain float32 sum of (q - c)^2
  *   "traversal"       0 (default): trees are walked in depth-first leaf order with the distance
  *                     context in registers; 1: level-synchronous kernels over the level arrays
  *                     (partial sums of internal nodes in device memory)
@@ -174,6 +178,10 @@ typedef struct etf_layout {
     int32_t rec0_stride;
     int64_t trec[ETF_MAX_M];       /* u8 [L2 of tree t][trec_stride[t]]: the tree's leaves as plain records     */
     int32_t trec_stride[ETF_MAX_M];
+    int64_t cb_centered;           /* float [M][K][cb_row]: codewords minus their group's mean codeword, zero padded */
+    int64_t cb_norm;               /* float [M][K]: squared norms of those                                            */
+    int64_t cb_mean;               /* float [M][d/M]: the mean codeword of every group                                */
+    int32_t cb_row;
 } etf_layout;
 int etf_index_layout(const etf_ctx *ctx, etf_layout *out);
 /* Writes the device image to host memory (at least etf_index_device_bytes()): the

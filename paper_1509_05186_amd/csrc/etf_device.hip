@@ -293,12 +293,22 @@ int set_lds(const etf_ctx *ctx, F kernel, size_t bytes)
 
 int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_t tiles, float *lutT, float *lut_public)
 {
-    const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
     dim3 grid((unsigned)tiles, (unsigned)ctx->M);
     ProfScope prof(ctx, ETF_K_LUT);
-    hipLaunchKernelGGL(k_lut_direct, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M,
-                       ctx->K, cb, lutT, lut_public);
-    LAUNCH_CHECK(ctx, "k_lut_direct");
+    if (ctx->opt.lut_kernel == 0) {
+        const float *cbc = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_centered);
+        const float *cbn = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_norm);
+        const float *cbm = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_mean);
+        const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
+        hipLaunchKernelGGL(k_lut_mfma, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
+                           cb, cbc, cbn, cbm, ctx->dsp, lutT, lut_public);
+        LAUNCH_CHECK(ctx, "k_lut_mfma");
+    } else {
+        const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
+        hipLaunchKernelGGL(k_lut_direct, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M,
+                           ctx->K, cb, lutT, lut_public);
+        LAUNCH_CHECK(ctx, "k_lut_direct");
+    }
     return ETF_OK;
 }
 

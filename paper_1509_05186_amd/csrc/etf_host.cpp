@@ -191,6 +191,34 @@ static void build_tree(const std::vector<KeyRec> &sub /* sorted, distinct keys *
 
 static int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 
+// Operands of the matrix-core table build.  ||q - c||^2 = ||q'||^2 - 2 q'.c' + ||c'||^2 holds for any common
+// shift q' = q - mu, c' = c - mu; the group's mean codeword as mu keeps the three terms small, so the
+// cancellation in float32 stays well inside the distance tolerance.  Norms are summed in double.
+void prepare_centered(etf_ctx *ctx)
+{
+    const int M = ctx->M, K = ctx->K, ds = ctx->ds;
+    ctx->dsp = (ds + 1) & ~1;
+    ctx->cb_mean.assign((size_t)M * ds, 0.f);
+    ctx->cb_centered.assign((size_t)M * K * ctx->dsp, 0.f);
+    ctx->cb_norm.assign((size_t)M * K, 0.f);
+    for (int m = 0; m < M; ++m) {
+        for (int j = 0; j < ds; ++j) {
+            double s = 0.0;
+            for (int k = 0; k < K; ++k) s += ctx->codebooks[((size_t)m * K + k) * ds + j];
+            ctx->cb_mean[(size_t)m * ds + j] = (float)(s / K);
+        }
+        for (int k = 0; k < K; ++k) {
+            double nn = 0.0;
+            for (int j = 0; j < ds; ++j) {
+                const float c = ctx->codebooks[((size_t)m * K + k) * ds + j] - ctx->cb_mean[(size_t)m * ds + j];
+                ctx->cb_centered[((size_t)m * K + k) * ctx->dsp + j] = c;
+                nn += (double)c * (double)c;
+            }
+            ctx->cb_norm[(size_t)m * K + k] = (float)nn;
+        }
+    }
+}
+
 void compute_layout(etf_ctx *ctx)
 {
     const HostIndex &ix = ctx->idx;
@@ -202,6 +230,9 @@ void compute_layout(etf_ctx *ctx)
         return o;
     };
     L.codebooks = take((int64_t)ctx->codebooks.size() * 4);
+    L.cb_centered = take((int64_t)ctx->cb_centered.size() * 4);
+    L.cb_norm = take((int64_t)ctx->cb_norm.size() * 4);
+    L.cb_mean = take((int64_t)ctx->cb_mean.size() * 4);
     L.codes = take((int64_t)ix.codes.size());
     L.ids_in = take(ix.N * 4);
     L.ids_sorted = take(ix.N * 4);
@@ -233,6 +264,9 @@ void for_each_image_array(const etf_ctx *ctx, const std::function<void(int64_t, 
     const HostIndex &ix = ctx->idx;
     const DevLayout &L = ctx->lay;
     put(L.codebooks, ctx->codebooks.data(), ctx->codebooks.size() * 4);
+    put(L.cb_centered, ctx->cb_centered.data(), ctx->cb_centered.size() * 4);
+    put(L.cb_norm, ctx->cb_norm.data(), ctx->cb_norm.size() * 4);
+    put(L.cb_mean, ctx->cb_mean.data(), ctx->cb_mean.size() * 4);
     put(L.codes, ix.codes.data(), ix.codes.size());
     put(L.ids_in, ix.ids_in.data(), ix.ids_in.size() * 4);
     put(L.ids_sorted, ix.ids_sorted.data(), ix.ids_sorted.size() * 4);
@@ -298,6 +332,9 @@ extern "C" int etf_set_option(etf_ctx *ctx, const char *name, int64_t value)
     } else if (n == "traversal") {
         if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "traversal must be 0 (register context) or 1 (level-synchronous)");
         ctx->opt.traversal = value;
+    } else if (n == "lut_kernel") {
+        if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "lut_kernel must be 0 (matrix cores) or 1 (plain sums)");
+        ctx->opt.lut_kernel = value;
     } else if (n == "cand_cap") {
         if (value < 0 || value > (1 << 20)) return fail(ctx, ETF_EINVAL, "cand_cap out of range");
         ctx->opt.cand_cap = value;
@@ -356,6 +393,7 @@ extern "C" int etf_pq_set_codebooks(etf_ctx *ctx, const float *cb, int d, int M,
     ctx->d = d; ctx->M = M; ctx->K = K; ctx->ds = d / M;
     try {
         ctx->codebooks.assign(cb, cb + (size_t)M * K * ctx->ds);
+        prepare_centered(ctx);
     } catch (const std::bad_alloc &) {
         return fail(ctx, ETF_ENOMEM, "out of host memory");
     }
@@ -422,6 +460,7 @@ extern "C" int etf_pq_train(etf_ctx *ctx, const float *x, int64_t n, int d, int 
         drop_index(ctx);
         ctx->d = d; ctx->M = M; ctx->K = K; ctx->ds = ds;
         ctx->codebooks.swap(cb);
+        prepare_centered(ctx);
     } catch (const std::bad_alloc &) {
         return fail(ctx, ETF_ENOMEM, "out of host memory");
     }
@@ -657,6 +696,8 @@ extern "C" int etf_index_layout(const etf_ctx *ctx, etf_layout *out)
     out->ebegin = L.ebegin; out->enc_of_pos = L.enc_of_pos; out->ecodes = L.ecodes;
     out->sample_enc = L.sample_enc; out->sample_pos = L.sample_pos;
     out->rec0 = L.rec0;
+    out->cb_centered = L.cb_centered; out->cb_norm = L.cb_norm; out->cb_mean = L.cb_mean;
+    out->cb_row = ctx->dsp;
     out->rec0_stride = ix.rstride0;
     out->n_sample_enc = (int64_t)ix.sample_enc.size();
     out->n_sample_pos = (int64_t)ix.sample_pos.size();

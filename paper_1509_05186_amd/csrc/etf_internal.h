@@ -77,7 +77,7 @@ struct DevTreeLayout {
 struct DevLayout {
     int64_t total = 0;
     int64_t codebooks = 0, codes = 0, ids_in = 0, ids_sorted = 0, ebegin = 0, enc_of_pos = 0, ecodes = 0,
-            sample_enc = 0, sample_pos = 0, rec0 = 0;
+            sample_enc = 0, sample_pos = 0, rec0 = 0, cb_centered = 0, cb_norm = 0, cb_mean = 0;
     std::vector<DevTreeLayout> tree;
 };
 
@@ -88,6 +88,7 @@ struct Options {
     int64_t sample_div = 32;
     int64_t cand_cap = 0;
     int64_t traversal = 0;  // 0: distance context in registers, 1: level-synchronous kernels
+    int64_t lut_kernel = 0; // 0: matrix cores (expanded form on centred vectors, small entries recomputed), 1: plain (a-b)^2 sums
 };
 
 }  // namespace etf
@@ -99,6 +100,12 @@ struct etf_ctx {
     // quantiser
     int d = 0, M = 0, K = 0, ds = 0;
     std::vector<float> codebooks;           // [M][K][ds]
+    // for the matrix-core table build: codewords minus the group's mean codeword, rows padded to an even
+    // length dsp; their squared norms; the means
+    int dsp = 0;
+    std::vector<float> cb_centered;         // [M][K][dsp]
+    std::vector<float> cb_norm;             // [M][K]
+    std::vector<float> cb_mean;             // [M][ds]
     // index
     etf::HostIndex idx;
     etf::DevLayout lay;
@@ -117,6 +124,7 @@ namespace etf {
 
 int fail(const etf_ctx *ctx, int code, const char *fmt, ...);
 void compute_layout(etf_ctx *ctx);
+void prepare_centered(etf_ctx *ctx);
 // calls put(offset, pointer, bytes) for every array of the device image
 void for_each_image_array(const etf_ctx *ctx, const std::function<void(int64_t, const void *, size_t)> &put);
 

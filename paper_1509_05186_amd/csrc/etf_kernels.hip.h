@@ -99,6 +99,123 @@ __global__ __launch_bounds__(256) void k_lut_direct(const float *__restrict__ qu
 }
 
 // ------------------------------------------------------------------------------------------------
+// S1 on the matrix cores.  The table of one (tile, group) is a 256 x 64 block of squared distances
+//     between K codewords and 64 queries over ds dimensions:  ||q' - c'||^2 = ||q'||^2 + ||c'||^2 - 2 c'.q'
+//     with both sides shifted by the group's mean codeword.  The cross term is the dense contraction:
+//     v_mfma_f32_32x32x2_f32 with A = codewords (32 rows) and B = queries (32 columns), float32 in,
+//     float32 accumulate.  A wave owns 64 codewords x 64 queries = 2 x 2 accumulator blocks.
+//     Operand layout of the instruction (lane l): A[i = l % 32][k = l / 32], B[k = l / 32][j = l % 32];
+//     accumulator register r of lane l is D[i = 8 * (r / 4) + 4 * (l / 32) + r % 4][j = l % 32], so for a
+//     fixed r the lanes 0..31 hold 32 consecutive queries of one codeword: a 128-byte piece of a table row.
+//     Entries that are small against the norms are recomputed exactly (see below).
+//     grid (tiles, M), block 256 (wave w: codewords 64w .. 64w+63).
+// ------------------------------------------------------------------------------------------------
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ queries, int64_t Q, int64_t q0, int d, int M,
+                                                  int K, const float *__restrict__ cb, const float *__restrict__ cbc,
+                                                  const float *__restrict__ cbnorm, const float *__restrict__ cbmean,
+                                                  int dsp, float *__restrict__ lutT,
+                                                  float *__restrict__ lut_public)
+{
+    const int tile = blockIdx.x, m = blockIdx.y;
+    const int lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6);
+    const int ds = d / M;
+    const int col = lane & 31, half = lane >> 5;
+    const int kbase = w * 64;
+    // B operand: the two queries this lane feeds (columns col and col + 32 of the tile)
+    const float *qrow[2];
+    bool qlive[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const int64_t q = q0 + (int64_t)tile * QT + cb * 32 + col;
+        qlive[cb] = q < Q;
+        qrow[cb] = queries + (qlive[cb] ? q : 0) * d + (int64_t)m * ds;
+    }
+    // A operand: the two codewords this lane feeds (rows col and col + 32 of the wave's 64)
+    const float *crow[2];
+    bool clive[2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        const int k = kbase + rb * 32 + col;
+        clive[rb] = k < K;
+        crow[rb] = cbc + ((int64_t)m * K + (clive[rb] ? k : 0)) * dsp;
+    }
+    const float *mean = cbmean + (int64_t)m * ds;
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
+    float qq[2] = {0.f, 0.f};
+    for (int j0 = 0; j0 < dsp; j0 += 2) {
+        const int j = j0 + half;
+        float a[2], b[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) a[rb] = clive[rb] ? crow[rb][j] : 0.f;
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            b[cb] = (qlive[cb] && j < ds) ? qrow[cb][j] - mean[j] : 0.f;
+            qq[cb] = fmaf(b[cb], b[cb], qq[cb]);
+        }
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rb], b[cb], acc[rb][cb], 0, 0, 0);
+    }
+    // the two halves of the wave summed the even and the odd dimensions of the same query
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) qq[cb] += __shfl_xor(qq[cb], 32);
+    // The expanded form loses about 2^-23 (||q'||^2 + ||c'||^2) absolutely, which is too much for an entry
+    // that is small against the norms (a codeword next to the query).  Such entries are not written here but
+    // queued, and recomputed below as plain sums of (q - c)^2 by all threads of the workgroup.
+    __shared__ uint16_t fix[QT * 256];
+    __shared__ int nfix;
+    if (threadIdx.x == 0) nfix = 0;
+    __syncthreads();
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int k = kbase + rb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+            if (k < K) {
+                const float cc = cbnorm[(int64_t)m * K + k];
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) {
+                    const float nn = qq[cb] + cc;
+                    const float v = nn - 2.f * acc[rb][cb][r];
+                    const int ql = cb * 32 + col;
+                    if (v < 0.25f * nn) {
+                        fix[atomicAdd(&nfix, 1)] = (uint16_t)((ql << 8) | k);
+                    } else {
+                        if (lutT) lutT[(((int64_t)tile * M + m) * K + k) * QT + ql] = v;
+                        const int64_t q = q0 + (int64_t)tile * QT + ql;
+                        if (lut_public && q < Q) lut_public[(q * M + m) * K + k] = v;
+                    }
+                }
+            }
+        }
+    __syncthreads();
+    const int todo = nfix;
+    for (int i = threadIdx.x; i < todo; i += blockDim.x) {
+        const int ql = fix[i] >> 8, k = fix[i] & 255;
+        const int64_t q = q0 + (int64_t)tile * QT + ql;
+        const bool live = q < Q;
+        const float *x = queries + (live ? q : 0) * d + (int64_t)m * ds;
+        const float *c = cb + ((int64_t)m * K + k) * ds;
+        float sum = 0.f;
+        for (int j = 0; j < ds; ++j) {
+            const float t = (live ? x[j] : 0.f) - c[j];
+            sum = fmaf(t, t, sum);
+        }
+        if (lutT) lutT[(((int64_t)tile * M + m) * K + k) * QT + ql] = sum;
+        if (lut_public && live) lut_public[(q * M + m) * K + k] = sum;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // S2  one internal level of one tree:  part[l][i] = part[l-1][parent[i]] + LUT row (m, code[i]).
 //     grid (blocks, tiles), block 256; every wave takes `per_wave` consecutive nodes.
 // ------------------------------------------------------------------------------------------------

@@ -63,12 +63,28 @@ def qdev(p):
     return torch.from_numpy(p.q).cuda()
 
 
-def test_lut_build(small):
-    say("lut_build small")
-    c = small.ctx()
+@pytest.mark.parametrize("lut_kernel", [0, 1])   # 0: matrix cores (+ exact recomputation of small entries), 1: plain sums
+def test_lut_build(small, lut_kernel):
+    say("lut_build small, kernel", lut_kernel)
+    c = small.ctx(lut_kernel=lut_kernel)
     lut = c.lut_build(qdev(small)).cpu().numpy()
     ref = np.stack([oracle.lut(q, small.cb) for q in small.q])
-    assert_distances_close(lut.reshape(small.Q, -1), ref.reshape(small.Q, -1), "lut")
+    assert lut.min() >= 0.0
+    assert_distances_close(lut.reshape(small.Q, -1), ref.reshape(small.Q, -1), "lut kernel %d" % lut_kernel)
+    say("  worst relative error of an entry: %.3g" % float((np.abs(lut - ref) / np.maximum(ref, 1e-30)).max()))
+
+
+def test_lut_kernels_on_wide_subspaces():
+    say("lut_build with 120-dimensional groups (odd sizes, padding), both kernels")
+    p = Problem(d=7 * 17, M=7, K=50, N=500, Q=70, ntrain=600, seed=15)         # ds = 17: padded to 18 for the matrix cores
+    ref = np.stack([oracle.lut(q, p.cb) for q in p.q])
+    for lk in (0, 1):
+        c = p.ctx(lut_kernel=lk)
+        lut = c.lut_build(qdev(p)).cpu().numpy()
+        assert_distances_close(lut.reshape(p.Q, -1), ref.reshape(p.Q, -1), "lut kernel %d" % lk)
+        d = c.adc(qdev(p), TREE)
+        torch.cuda.synchronize()
+        assert_distances_close(d.cpu().numpy(), p.ref_all, "adc with lut kernel %d" % lk)
 
 
 TRAVERSALS = [0, 1]      # 0: distance context in registers, 1: level-synchronous kernels
