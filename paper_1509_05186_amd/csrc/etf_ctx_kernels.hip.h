@@ -131,7 +131,9 @@ __device__ __forceinline__ void chunk_meta(ChunkMeta<DT> &m, const uint32_t my_d
 
 // The common case: no item of the batch leaves the path of its predecessor above the two deepest levels.
 // Those two are then simply looked up for every item (both slices are in LDS): the same sum as a masked
-// update, without any mask, and per item one broadcast, two LDS reads and two adds.
+// update, without any mask, and per item one broadcast, two LDS reads and two adds.  Items past the end
+// of the chunk look up rows of code 0 and leave a meaningless context behind, which nobody reads: a short
+// chunk is the last one of the wave's run.
 template <int DT, int UBT, class Mid>
 __device__ __forceinline__ void ctx_batch_deep(float ctx[DT], const char *ldsb, int lane4, const ChunkMeta<DT> &m, int s0,
                                                int cnt, float res[UBT], Mid mid)
@@ -139,7 +141,7 @@ __device__ __forceinline__ void ctx_batch_deep(float ctx[DT], const char *ldsb, 
     float x2[UBT], x3[UBT];
 #pragma unroll
     for (int u = 0; u < UBT; ++u) {
-        const uint32_t p = (uint32_t)__builtin_amdgcn_readlane((int)m.deep, min(s0 + u, cnt - 1));
+        const uint32_t p = (uint32_t)__builtin_amdgcn_readlane((int)m.deep, s0 + u);
         x2[u] = *reinterpret_cast<const float *>(ldsb + ((p & 0xFFFFu) << 8) + lane4);
         x3[u] = *reinterpret_cast<const float *>(ldsb + ((p >> 16) << 8) + lane4);
     }
@@ -159,7 +161,7 @@ __device__ __forceinline__ void ctx_batch_deep(float ctx[DT], const char *ldsb, 
 //   lutr     buffer over this tile's table slices starting at the tree's first chunk
 //   ldsb     the NL deepest slices in LDS, as bytes
 //   res[u]   receives the full-depth sum of item s0+u
-// Items past the end of the chunk repeat the last one, which changes nothing.
+// Items past the end of the chunk (only at the end of a wave's run) have no bit set and read row 0.
 // `mid` runs between the issue of the batch's lookups and their use (the place to request data for later).
 template <int DT, int NL, int UBT, int F, class Mid>
 __device__ __forceinline__ void ctx_batch(float ctx[DT], rsrc_t lutr, const char *ldsb, int lane4, const ChunkMeta<DT> &m,
@@ -169,7 +171,7 @@ __device__ __forceinline__ void ctx_batch(float ctx[DT], rsrc_t lutr, const char
     uint32_t bits[UBT];
 #pragma unroll
     for (int u = 0; u < UBT; ++u) {
-        const int src = min(s0 + u, cnt - 1);
+        const int src = s0 + u;
         bits[u] = (uint32_t)__builtin_amdgcn_readlane((int)m.bits, src);
 #pragma unroll
         for (int s = F; s < DT; ++s) {
@@ -232,7 +234,7 @@ __global__ __launch_bounds__(1024) void k_tree_ctx(const uint32_t *__restrict__ 
 #pragma unroll
     for (int s = 0; s < DT; ++s) ctx[s] = 0.f;
     for (int64_t base = lo; base < hi; base += 64) {
-        const int cnt = (int)min<int64_t>(64, hi - base);
+        const int cnt = uniform((int)min<int64_t>(64, hi - base));
         uint32_t my_dw[NDW];
 #pragma unroll
         for (int i = 0; i < NDW; ++i) my_dw[i] = lane < cnt ? codes[(base + lane) * NDW + i] : 0u;
@@ -263,9 +265,10 @@ __global__ __launch_bounds__(1024) void k_tree_ctx(const uint32_t *__restrict__ 
 //     batch of items is evaluated in a fraction of that.  So they are requested GP items ahead (a whole
 //     group of the 64-item chunk, across chunk boundaries too) into registers; the table lookups of the
 //     items in between come from LDS, whose counter is separate, so waiting for them does not wait for
-//     the rows in flight.  Candidates that pass the bound are parked in registers (R per lane) and
-//     appended to the query's list with one reservation when a lane's slots are full and at the end: an
-//     atomic with a return value in the item loop would drain the rows in flight every time.
+//     the rows in flight.  Candidates that pass the bound are compacted into a ring of the wave in LDS
+//     (rank of a lane among the passing ones from the ballot) and appended to the queries' lists, one
+//     atomic each, by all 64 lanes together when the ring is nearly full and at the end: an atomic with
+//     a return value in the item loop would drain the rows in flight every time.
 //     grid (blocks, tiles); FILTER and SAMPLE: block 1024, NL = 2; ALLPAIRS: block 256, NL = 0;
 //     dynamic LDS NL*K*256 bytes.
 // ------------------------------------------------------------------------------------------------
@@ -281,7 +284,7 @@ __global__ __launch_bounds__(1024) void k_fused(const uint32_t *__restrict__ cod
     constexpr int GP = NG1 == 1 ? ETF_GP : UBT;                // items per gather group (GP * NG1 rows in flight)
     constexpr int NGRP = 64 / GP, NBAT = GP / UBT;
     constexpr int NV = NG1 > 0 ? NG1 : 1;
-    constexpr int R = 4;                                       // parked candidates per lane
+    constexpr int RING = 192;                                  // candidates a wave holds back in LDS
     extern __shared__ float lds[];
     const int tile = blockIdx.y;
     stage_deepest<NL>(lds, lutT, tile, M, K, 0, D0);
@@ -300,19 +303,27 @@ __global__ __launch_bounds__(1024) void k_fused(const uint32_t *__restrict__ cod
     // all-pairs output is transposed through LDS, 4 waves per block in that mode
     __shared__ float tbuf[MODE == OUT_ALLPAIRS ? 4 : 1][MODE == OUT_ALLPAIRS ? 64 : 1][65];
     const int64_t ql = (int64_t)tile * QT + lane;
-    float cd[R];
-    uint32_t ci[R];
-    int cn = 0;
-#pragma unroll
-    for (int i = 0; i < R; ++i) { cd[i] = 0.f; ci[i] = 0u; }
+    // candidates of this wave waiting to be appended: (distance bits << 32) | lane << 26 | item
+    __shared__ uint64_t ring[MODE == OUT_FILTER ? 16 : 1][MODE == OUT_FILTER ? RING : 1];
+    __shared__ uint32_t wpos[MODE == OUT_FILTER ? 16 : 1][64];
+    int held = 0;         // wave-uniform number of entries in the ring
+    uint32_t mine = 0u;   // how many of them belong to this lane's query
+    // one reservation per query, then every entry takes the next free slot of its query's share
     auto flush = [&]() {
-        if (cn > 0) {
-            const uint32_t pos = atomicAdd(&o.cnt[ql], (uint32_t)cn);
-#pragma unroll
-            for (int i = 0; i < R; ++i)
-                if (i < cn && pos + i < o.C) o.cand[ql * o.C + pos + i] = ((uint64_t)__float_as_uint(cd[i]) << 32) | ci[i];
-            cn = 0;
+#ifndef ETF_ABL
+        wpos[w][lane] = mine ? atomicAdd(&o.cnt[ql], mine) : 0u;
+        __builtin_amdgcn_wave_barrier();
+        for (int i = lane; i < held; i += 64) {
+            const uint64_t e = ring[w][i];
+            const int owner = (int)((e >> 26) & 63u);
+            const uint32_t pos = atomicAdd(&wpos[w][owner], 1u);
+            const int64_t q = (int64_t)tile * QT + owner;
+            if (pos < o.C) o.cand[q * o.C + pos] = (e & 0xFFFFFFFF00000000ull) | (e & 0x3FFFFFFull);
         }
+        __builtin_amdgcn_wave_barrier();
+#endif
+        held = 0;
+        mine = 0u;
     };
     float tauv = 0.f, best = __uint_as_float(0x7F800000u);
     if (MODE == OUT_FILTER) tauv = o.tau[ql];
@@ -329,12 +340,12 @@ __global__ __launch_bounds__(1024) void k_fused(const uint32_t *__restrict__ cod
 #pragma unroll
         for (int t = 1; t < TMAX; ++t) goff[t] = live ? r.leaf_of[t][e] * (uint32_t)(QT * 4) : 0u;
     };
-    // requests the rows of group g of a chunk with `cnt` items (items past the end repeat the last one)
+    // requests the rows of group g of a chunk (items past the end read row 0)
     constexpr int GV = NG1 > 0 ? GP : 1;
-    auto gather = [&](const uint32_t goff[TMAX], int g, int cnt, float v[GV][NV]) {
+    auto gather = [&](const uint32_t goff[TMAX], int g, float v[GV][NV]) {
 #pragma unroll
         for (int i = 0; i < GP; ++i) {
-            const int src = min(g * GP + i, cnt - 1);
+            const int src = g * GP + i;
 #pragma unroll
             for (int t = 1; t < TMAX; ++t)
                 v[i][t - 1] = buf_load(tabr[t], lane4, __builtin_amdgcn_readlane((int)goff[t], src));
@@ -344,10 +355,9 @@ __global__ __launch_bounds__(1024) void k_fused(const uint32_t *__restrict__ cod
     uint32_t my_dw[NDW], my_goff[TMAX], next_dw[NDW], next_goff[TMAX];
     float va[GV][NV], vb[GV][NV];  // rows of the group being evaluated / of the group after it, alternating
     fetch(lo, my_dw, my_goff);
-    if (NG1 > 0) gather(my_goff, 0, (int)min<int64_t>(64, hi - lo), va);
+    if (NG1 > 0) gather(my_goff, 0, va);
     for (int64_t base = lo; base < hi; base += 64) {
-        const int cnt = (int)min<int64_t>(64, hi - base);
-        const int ncnt = (int)max<int64_t>(1, min<int64_t>(64, hi - base - 64));
+        const int cnt = uniform((int)min<int64_t>(64, hi - base));
         fetch(base + 64, next_dw, next_goff);  // arrives while this chunk is evaluated
         ChunkMeta<DT> m;
         chunk_meta<DT, NDW, NL, UBT>(m, my_dw, codes0, base, lo, lane, cnt, pad, K, MODE == OUT_FILTER);
@@ -359,8 +369,8 @@ __global__ __launch_bounds__(1024) void k_fused(const uint32_t *__restrict__ cod
                 const int s0 = g * GP + b * UBT;
                 auto request = [&] {
                     if (NG1 > 0 && b == 0) {
-                        if ((g + 1) * GP < 64) gather(my_goff, g + 1, cnt, nxt);
-                        else gather(next_goff, 0, ncnt, nxt);
+                        if ((g + 1) * GP < 64) gather(my_goff, g + 1, nxt);
+                        else gather(next_goff, 0, nxt);
                     }
                 };
                 if (s0 >= cnt) {
@@ -381,15 +391,16 @@ __global__ __launch_bounds__(1024) void k_fused(const uint32_t *__restrict__ cod
                             else if (MODE == OUT_SAMPLE) best = fminf(best, d[u]);
                             else {
                                 const bool pass = d[u] <= tauv;
-                                if (__ballot(pass) != 0ull) {
-                                    if (pass) {
-#pragma unroll
-                                        for (int i = R - 1; i > 0; --i) { cd[i] = cd[i - 1]; ci[i] = ci[i - 1]; }
-                                        cd[0] = d[u];
-                                        ci[0] = (uint32_t)(base + s0 + u);
-                                        ++cn;
-                                    }
-                                    if (__ballot(cn == R) != 0ull) flush();
+                                const uint64_t mask = __ballot(pass);
+                                if (mask != 0ull) {
+                                    const int rank = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                                    __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                                    if (pass)
+                                        ring[w][held + rank] = ((uint64_t)__float_as_uint(d[u]) << 32) |
+                                                               ((uint32_t)lane << 26) | (uint32_t)(base + s0 + u);
+                                    mine += pass ? 1u : 0u;
+                                    held += __popcll(mask);
+                                    if (held > RING - 64) flush();
                                 }
                             }
                         }

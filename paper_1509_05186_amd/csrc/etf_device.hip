@@ -224,6 +224,7 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     P.ctx_path = tmax_class(ix.T) != 0 && mode != ETF_MODE_FLAT && ctx->opt.traversal == 0;
     for (int t = 1; t < ix.T; ++t)  // the register-context kernels address a tree's result table with 32-bit offsets
         if (ix.tree[t].U >= ((int64_t)1 << 24)) P.ctx_path = false;
+    if (ix.Nd >= ((int64_t)1 << 26)) P.ctx_path = false;  // its candidate records keep the item in 26 bits
     if (mode != ETF_MODE_FLAT)
         for (int t = P.ctx_path ? 1 : 0; t < ix.T; ++t) {
             const HostTree &tr = ix.tree[t];

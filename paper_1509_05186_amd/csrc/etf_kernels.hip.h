@@ -731,7 +731,7 @@ __device__ __forceinline__ void block_inclusive_scan(uint32_t *v, int n, uint32_
 // Smallest 32-bit value v such that at least `rank` of the participating keys are <= v (block of 256
 // threads, most significant digit first, 4 passes of 8 bits).  key(i, v) returns false for entries
 // that do not take part.  Also returns how many keys equal v and how many of those the rank needs.
-// hist: 256 words of LDS, sh: 3 words of LDS.
+// hist: 256 words of LDS, sh: 8 words of LDS.
 template <class KeyFn>
 __device__ __forceinline__ void block_radix_select(int n, uint32_t rank, KeyFn key, uint32_t *hist, uint32_t *sh,
                                                    uint32_t &value, uint32_t &rank_in_ties, uint32_t &n_ties)
@@ -740,21 +740,29 @@ __device__ __forceinline__ void block_radix_select(int n, uint32_t rank, KeyFn k
     for (int p = 0, shift = 24; p < 4; ++p, shift -= 8) {
         hist[threadIdx.x] = 0;
         __syncthreads();
+#pragma unroll 8
         for (int i = threadIdx.x; i < n; i += 256) {
             uint32_t v;
             if (key(i, v) && (p == 0 || (v >> (shift + 8)) == (prefix >> (shift + 8)))) atomicAdd(&hist[(v >> shift) & 255], 1u);
         }
         __syncthreads();
-        if (threadIdx.x == 0) {
-            uint32_t below = 0;
-            int b = 0;
-            for (; b < 255; ++b) {
-                if (below + hist[b] >= rank) break;
-                below += hist[b];
-            }
-            sh[0] = prefix | ((uint32_t)b << shift);
-            sh[1] = rank - below;
-            sh[2] = hist[b];
+        // the digit at which the running count reaches the rank: a scan over the 256 bins, one bin per thread
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const uint32_t h = hist[threadIdx.x];
+        uint32_t inc = h;
+#pragma unroll
+        for (int dlt = 1; dlt < 64; dlt <<= 1) {
+            const uint32_t up = (uint32_t)__shfl_up((int)inc, dlt);
+            if (lane >= dlt) inc += up;
+        }
+        if (lane == 63) sh[4 + wave] = inc;
+        __syncthreads();
+        for (int w2 = 0; w2 < wave; ++w2) inc += sh[4 + w2];
+        const uint32_t excl = inc - h;
+        if ((excl < rank && rank <= inc) || (threadIdx.x == 255 && inc < rank)) {
+            sh[0] = prefix | ((uint32_t)threadIdx.x << shift);
+            sh[1] = rank - excl;
+            sh[2] = h;
         }
         __syncthreads();
         prefix = sh[0];
@@ -804,7 +812,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     __shared__ uint32_t tmp[256];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_a, s_b, s_c, s_d;
-    __shared__ uint32_t sel_sh[4];
+    __shared__ uint32_t sel_sh[8];
     const int64_t ql = blockIdx.x;
     if (a.flag[ql]) return;  // already routed to the exact kernel
     const uint32_t craw = a.cnt[ql];
@@ -842,6 +850,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     // 2. keep the candidates at or below it, sorted by (distance bits, item)
     if (threadIdx.x == 0) s_c = 0;
     __syncthreads();
+#pragma unroll 8
     for (int i = threadIdx.x; i < c; i += 256) {
         const uint64_t key = cand[i];
         const uint32_t v = (uint32_t)(key >> 32);
