@@ -796,7 +796,7 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
         sa.flag = flag;
         {
             ProfScope prof(ctx, ETF_K_SELECT);
-            hipLaunchKernelGGL(k_select, dim3((unsigned)nq), dim3(256), 0, st, sa);
+            hipLaunchKernelGGL(k_select, dim3((unsigned)nq), dim3(256), select_lds_bytes(k), st, sa);
         }
         LAUNCH_CHECK(ctx, "k_select");
         ExactArgs ea;

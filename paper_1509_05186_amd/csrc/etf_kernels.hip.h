@@ -705,22 +705,24 @@ __device__ __forceinline__ void bitonic_sort_u64(uint64_t *a, int n)
         }
 }
 
-// in-place inclusive scan of v[0..n) (n <= 256 * ipt), 256 threads, `tmp` has 256 entries
+// in-place inclusive scan of v[0..n) (n <= 256 * ipt), 256 threads, `tmp` has 4 entries
 __device__ __forceinline__ void block_inclusive_scan(uint32_t *v, int n, uint32_t *tmp)
 {
     const int ipt = (n + 255) / 256;
     const int lo = threadIdx.x * ipt, hi = min(n, lo + ipt);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t s = 0;
     for (int i = lo; i < hi; ++i) s += v[i];
-    tmp[threadIdx.x] = s;
-    __syncthreads();
-    for (int off = 1; off < 256; off <<= 1) {
-        uint32_t add = (threadIdx.x >= off) ? tmp[threadIdx.x - off] : 0;
-        __syncthreads();
-        tmp[threadIdx.x] += add;
-        __syncthreads();
+    uint32_t inc = s;
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_up((int)inc, dlt);
+        if (lane >= dlt) inc += up;
     }
-    uint32_t run = tmp[threadIdx.x] - s;
+    if (lane == 63) tmp[wave] = inc;
+    __syncthreads();
+    for (int w2 = 0; w2 < wave; ++w2) inc += tmp[w2];
+    uint32_t run = inc - s;
     for (int i = lo; i < hi; ++i) {
         run += v[i];
         v[i] = run;
@@ -787,10 +789,17 @@ __device__ __forceinline__ int pow2_at_least(int n)
 //      vector ids (each encoding at most as many as are still needed), sorted by (distance, id), and
 //      the first k are written.  Anything that does not fit the fixed LDS buffers (candidate overflow,
 //      huge groups of exactly equal distances) is flagged for the exact whole-database kernel.
-//      grid (queries of the batch), block 256.
+//      grid (queries of the batch), block 256, dynamic LDS select_lds_bytes(k).
 // ------------------------------------------------------------------------------------------------
-constexpr int KEPT_CAP = 2048;
-constexpr int EXP_CAP = 4096;
+// capacity of the kept list and of the expanded list: twice k rounded up to a power of two, at least 256
+// (room for the k closest plus a run of exactly equal distances); 16 bytes of dynamic LDS per entry plus 4
+__host__ __device__ inline int select_cap(int k)
+{
+    int c = 256;
+    while (c < 2 * k) c <<= 1;
+    return c;
+}
+inline size_t select_lds_bytes(int k) { return (size_t)select_cap(k) * 20; }
 
 struct SelectArgs {
     const uint32_t *cnt;     // [nq]
@@ -806,10 +815,12 @@ struct SelectArgs {
 
 __global__ __launch_bounds__(256) void k_select(SelectArgs a)
 {
-    __shared__ uint64_t kept[KEPT_CAP];
-    __shared__ uint64_t xkeys[EXP_CAP];
-    __shared__ uint32_t sc[KEPT_CAP];
-    __shared__ uint32_t tmp[256];
+    extern __shared__ uint64_t sel_lds[];
+    const int KEPT_CAP = select_cap(a.k), EXP_CAP = KEPT_CAP;
+    uint64_t *kept = sel_lds;                                         // [KEPT_CAP]
+    uint64_t *xkeys = sel_lds + KEPT_CAP;                             // [EXP_CAP]
+    uint32_t *sc = reinterpret_cast<uint32_t *>(sel_lds + 2 * KEPT_CAP);  // [KEPT_CAP]
+    __shared__ uint32_t tmp[4];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_a, s_b, s_c, s_d;
     __shared__ uint32_t sel_sh[8];
@@ -828,13 +839,13 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     //    smallest ids of a set of encodings lie in the r encodings with the smallest first id).
     auto first_id = [&](uint32_t e) -> uint32_t { return (uint32_t)a.ids[a.ebegin ? a.ebegin[e] : e]; };
     uint32_t vstar = 0xFFFFFFFFu, idstar = 0xFFFFFFFFu;
-    if (c > KEPT_CAP) {
+    if (c > 256) {  // more than the sort below should see: cut at the k-th closest first
         const uint32_t rank = (uint32_t)min(k, c);
         uint32_t rank_in_ties, n_ties;
         block_radix_select(
             c, rank, [&](int i, uint32_t &v) { v = (uint32_t)(cand[i] >> 32); return true; }, hist, sel_sh, vstar,
             rank_in_ties, n_ties);
-        if (rank - rank_in_ties + n_ties > KEPT_CAP) {
+        if (rank - rank_in_ties + n_ties > (uint32_t)KEPT_CAP) {
             uint32_t r2, n2;
             block_radix_select(
                 c, rank_in_ties,
@@ -856,7 +867,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
         const uint32_t v = (uint32_t)(key >> 32);
         if (v < vstar || (v == vstar && (idstar == 0xFFFFFFFFu || first_id((uint32_t)key) <= idstar))) {
             const uint32_t pos = atomicAdd(&s_c, 1u);
-            if (pos < KEPT_CAP) kept[pos] = key;
+            if (pos < (uint32_t)KEPT_CAP) kept[pos] = key;
         }
     }
     __syncthreads();
@@ -905,7 +916,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     __syncthreads();
     block_inclusive_scan(sc, nk, tmp);
     const uint32_t xtotal = sc[nk - 1];
-    if (xtotal > EXP_CAP) {
+    if (xtotal > (uint32_t)EXP_CAP) {
         if (threadIdx.x == 0) a.flag[ql] = 1;
         return;
     }
