@@ -143,6 +143,15 @@ def test_search(small, mode, T, k, trav):
     assert c.last_fallback_count() == 0
 
 
+@pytest.mark.parametrize("mode,T", [(FLAT, 1), (FOREST, 2)])
+def test_search_large_k(small, mode, T):
+    say("search with k near the maximum (largest selection buffers), mode", mode)
+    c = small.ctx(T=T, sample_min=2048)
+    check_search(small, c, mode, 1000, what="large k m%d" % mode)
+    check_search(small, c, mode, 1024, what="max k m%d" % mode)
+    assert c.last_fallback_count() == 0
+
+
 def test_search_matches_oracle_lists_exactly(small):
     say("search ids identical to the oracle's (no near-ties expected at this size)")
     c = small.ctx(T=2, sample_min=2048)
