@@ -130,8 +130,11 @@ def main():
     ap.add_argument("--levels", action="store_true",
                     help="time the level-synchronous traversal (partial sums of internal nodes in HBM) instead of the default "
                          "register-context traversal")
+    ap.add_argument("--traversal", type=int, default=0, help="0 register context (default), 1 level-synchronous, 2 tables in LDS")
     ap.add_argument("--no-copy", action="store_true", help="skip the 1 GiB device copy (bandwidth ceiling / counter calibration)")
     args = ap.parse_args()
+    if args.levels:
+        args.traversal = 1
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus %d is not supported); "
               "the path shards by query tile or by database range, see DESIGN.md" % args.gpus, file=sys.stderr)
@@ -156,7 +159,7 @@ def main():
 
     def make_ctx(T):
         c = etf.Context(device=0, stream=stream)
-        c.set_option("traversal", 1 if args.levels else 0)
+        c.set_option("traversal", args.traversal)
         c.pq_set_codebooks(cb)
         t0 = time.time()
         c.index_build(codes, T=T)

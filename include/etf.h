@@ -102,7 +102,11 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     1: every entry as a plain float32 sum of (q - c)^2
  *   "traversal"       0 (default): trees are walked in depth-first leaf order with the distance
  *                     context in registers; 1: level-synchronous kernels over the level arrays
- *                     (partial sums of internal nodes in device memory)
+ *                     (partial sums of internal nodes in device memory); 2: searches keep every
+ *                     table slice of a group of queries in LDS and walk the sorted encodings
+ *                     with a short distance context per lane group, no per-tree result tables
+ *                     (M in {4, 8, 16}, 1, 2 or 4 equal trees; anything else, and etf_adc, runs
+ *                     as traversal 0)
  * Returns ETF_EINVAL for an unknown name or a value out of range. */
 int etf_set_option(etf_ctx *ctx, const char *name, int64_t value);
 
@@ -227,7 +231,8 @@ enum {
     ETF_K_SELECT = 6,   /* final top-k selection                              */
     ETF_K_EXACT = 7,    /* exact whole-database selection                     */
     ETF_K_SAMPLE = 8,   /* distances of the bound's sample (flat or reduction) */
-    ETF_K_COUNT = 9
+    ETF_K_LDS = 9,      /* tree / forest search with every table slice in LDS  */
+    ETF_K_COUNT = 10
 };
 /* on != 0: every later kernel launch of this context is bracketed by a pair of
  * HIP events on the context's stream. */

@@ -23,7 +23,7 @@ EXPORTS = [
     "etf_workspace_bytes", "etf_lut_build", "etf_adc", "etf_search", "etf_last_fallback_count",
     "etf_profile_enable", "etf_profile_read",
 ]
-KERNEL_CLASSES = ["lut", "level", "leaf", "flat", "reduce", "tau", "select", "exact", "sample"]
+KERNEL_CLASSES = ["lut", "level", "leaf", "flat", "reduce", "tau", "select", "exact", "sample", "lds"]
 
 
 class EtfStats(ctypes.Structure):

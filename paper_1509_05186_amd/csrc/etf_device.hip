@@ -173,6 +173,7 @@ struct Plan {
     uint32_t C = 0;           // candidate capacity per query
     bool use_tau = false;
     bool ctx_path = false;    // trees walked with the distance context in registers (no partial-sum tables)
+    bool lds_path = false;    // search with every table slice in LDS: no result tables at all
     int64_t o_counter = 0, o_lutT = 0, o_gmin = 0, o_tau = 0, o_cnt = 0, o_flag = 0, o_cand = 0;
     int64_t o_part[ETF_MAX_M][ETF_MAX_M];
     int64_t o_leafp[ETF_MAX_M];
@@ -181,6 +182,7 @@ struct Plan {
 
 int64_t al256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 int tmax_class(int T);
+bool lds_eligible(int M, int K, int T, const int32_t *chunk_begin);
 
 int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan &P)
 {
@@ -221,11 +223,14 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     }
     // bytes per tile of 64 queries
     int64_t per_tile = (int64_t)M * K * QT * 4;
-    P.ctx_path = tmax_class(ix.T) != 0 && mode != ETF_MODE_FLAT && ctx->opt.traversal == 0;
+    // traversal 2 = every table slice in LDS, for searches on the shapes that kernel is built for; otherwise
+    // it means the register-context kernels, like traversal 0
+    P.lds_path = search && mode != ETF_MODE_FLAT && ctx->opt.traversal == 2 && lds_eligible(M, K, ix.T, ix.chunk_begin.data());
+    P.ctx_path = !P.lds_path && tmax_class(ix.T) != 0 && mode != ETF_MODE_FLAT && ctx->opt.traversal != 1;
     for (int t = 1; t < ix.T; ++t)  // the register-context kernels address a tree's result table with 32-bit offsets
         if (ix.tree[t].U >= ((int64_t)1 << 24)) P.ctx_path = false;
     if (ix.Nd >= ((int64_t)1 << 26)) P.ctx_path = false;  // its candidate records keep the item in 26 bits
-    if (mode != ETF_MODE_FLAT)
+    if (mode != ETF_MODE_FLAT && !P.lds_path)
         for (int t = P.ctx_path ? 1 : 0; t < ix.T; ++t) {
             const HostTree &tr = ix.tree[t];
             if (!P.ctx_path)
@@ -247,7 +252,7 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     };
     P.o_counter = take(256);
     P.o_lutT = take(P.NT * M * K * QT * 4);
-    if (mode != ETF_MODE_FLAT)
+    if (mode != ETF_MODE_FLAT && !P.lds_path)
         for (int t = P.ctx_path ? 1 : 0; t < ix.T; ++t) {
             const HostTree &tr = ix.tree[t];
             if (!P.ctx_path)
@@ -578,6 +583,62 @@ int launch_reduce(etf_ctx *ctx, const ReduceArgs &r, int64_t nitems, const uint3
     return ETF_OK;
 }
 
+// Every table slice of a sub-tile in LDS: which shapes the kernel is built for.  Trees must be T equal
+// groups of chunks (chunk_begin == nullptr: a single group).
+bool lds_eligible(int M, int K, int T, const int32_t *chunk_begin)
+{
+    if (M != 4 && M != 8 && M != 16) return false;
+    if (T != 1 && T != 2 && T != 4) return false;
+    if (M % T != 0) return false;
+    if (chunk_begin)
+        for (int t = 0; t <= T; ++t)
+            if (chunk_begin[t] != t * (M / T)) return false;
+    return std::max(2, pick_G(M, K)) <= 8;
+}
+
+template <int MODE, bool CTX>
+int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64_t nitems, const uint32_t *map, int T,
+               int64_t tiles, const OutArgs &o, int cls)
+{
+    if (nitems == 0) return ETF_OK;
+    const int M = ctx->M, K = ctx->K;
+    const int G = std::max(2, pick_G(M, K));
+    const size_t lds = (size_t)M * K * (WAVE / G) * 4;
+    const int IPS = 2 * G;  // items per wave step
+    int64_t bx;
+    int per_block = 0;
+    if (MODE == OUT_SAMPLE) {
+        bx = blocks_for(o.ngroups, 16 * IPS, tiles * G);
+    } else {
+        // item numbers inside a workgroup's share travel in 26 bits
+        bx = std::max(blocks_for(nitems, 16384, tiles * G), (nitems >> 25) + 1);
+        per_block = (int)((nitems + bx - 1) / bx);
+    }
+    dim3 grid((unsigned)bx, (unsigned)G, (unsigned)tiles);
+    hipStream_t st = (hipStream_t)ctx->stream;
+    const float *lutT = reinterpret_cast<const float *>(ws + P.o_lutT);
+    ProfScope prof(ctx, cls);
+    bool done = false;
+#define LDS_CASE(GG, MM4, TT)                                                                                  \
+    if constexpr (CTX || MODE == OUT_SAMPLE || TT == 1) {                                                      \
+        if (!done && G == GG && M == 4 * MM4 && T == TT) {                                                     \
+            int rc = set_lds(ctx, k_lds<GG, MM4, TT, MODE, CTX>, lds);                                         \
+            if (rc) return rc;                                                                                 \
+            hipLaunchKernelGGL((k_lds<GG, MM4, TT, MODE, CTX>), grid, dim3(1024), lds, st, rec, nitems, map, lutT, K, \
+                               per_block, o);                                                                  \
+            done = true;                                                                                       \
+        }                                                                                                      \
+    }
+#define LDS_CASES(GG) LDS_CASE(GG, 1, 1) LDS_CASE(GG, 1, 2) LDS_CASE(GG, 1, 4) LDS_CASE(GG, 2, 1) LDS_CASE(GG, 2, 2) \
+    LDS_CASE(GG, 2, 4) LDS_CASE(GG, 4, 1) LDS_CASE(GG, 4, 2) LDS_CASE(GG, 4, 4)
+    LDS_CASES(2) LDS_CASES(4) LDS_CASES(8)
+#undef LDS_CASES
+#undef LDS_CASE
+    if (!done) return fail(ctx, ETF_EINVAL, "no LDS-resident kernel for M=%d K=%d T=%d", M, K, T);
+    LAUNCH_CHECK(ctx, "k_lds");
+    return ETF_OK;
+}
+
 template <int MODE>
 int launch_flat(etf_ctx *ctx, const Plan &P, char *ws, int64_t nitems, const uint32_t *sample, int64_t tiles, const OutArgs &o)
 {
@@ -592,8 +653,12 @@ int launch_flat(etf_ctx *ctx, const Plan &P, char *ws, int64_t nitems, const uin
     hipStream_t st = (hipStream_t)ctx->stream;
     const uint8_t *codes = reinterpret_cast<const uint8_t *>(ctx->dev_base + ctx->lay.codes);
     const float *lutT = reinterpret_cast<const float *>(ws + P.o_lutT);
+    if constexpr (MODE != OUT_ALLPAIRS)
+        if (lds_eligible(M, K, 1, nullptr))
+            return launch_lds<MODE, false>(ctx, P, ws, reinterpret_cast<const uint32_t *>(codes), nitems, sample, 1, tiles, o,
+                                       MODE == OUT_SAMPLE ? ETF_K_SAMPLE : ETF_K_FLAT);
     ProfScope prof(ctx, MODE == OUT_SAMPLE ? ETF_K_SAMPLE : ETF_K_FLAT);
-#define FLAT_CASE(GG)                                                                                        \
+#define FLAT_CASE(GG)                                                                                     \
     case GG: {                                                                                               \
         int rc = set_lds(ctx, k_flat<GG, MODE>, lds);                                                        \
         if (rc) return rc;                                                                                   \
@@ -754,7 +819,8 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
         o.C = P.C;
         o.nq = nq;
         ReduceArgs r;
-        if (!flat) {
+        const uint32_t *ecodes = reinterpret_cast<const uint32_t *>(ctx->dev_base + L.ecodes);
+        if (!flat && !P.lds_path) {
             rc = P.ctx_path ? launch_trees_ctx(ctx, P, w, tiles) : launch_trees(ctx, P, w, tiles);
             if (rc) return rc;
             if (P.ctx_path) fill_fused_args(ctx, P, w, r);
@@ -764,6 +830,9 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
             if (P.use_tau) {
                 if (flat)
                     rc = launch_flat<OUT_SAMPLE>(ctx, P, w, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_pos), tiles, o);
+                else if (P.lds_path)
+                    rc = launch_lds<OUT_SAMPLE, false>(ctx, P, w, ecodes, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_enc),
+                                                       ix.T, tiles, o, ETF_K_SAMPLE);
                 else
                     rc = P.ctx_path ? launch_fused<OUT_SAMPLE>(ctx, P, w, r, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_enc), tiles, o)
                                     : launch_reduce<OUT_SAMPLE>(ctx, r, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_enc), tiles, o);
@@ -779,6 +848,8 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
             }
             if (flat)
                 rc = launch_flat<OUT_FILTER>(ctx, P, w, ix.N, nullptr, tiles, o);
+            else if (P.lds_path)
+                rc = launch_lds<OUT_FILTER, true>(ctx, P, w, ecodes, ix.Nd, nullptr, ix.T, tiles, o, ETF_K_LDS);
             else
                 rc = P.ctx_path ? launch_fused<OUT_FILTER>(ctx, P, w, r, ix.Nd, nullptr, tiles, o)
                                 : launch_reduce<OUT_FILTER>(ctx, r, ix.Nd, nullptr, tiles, o);

@@ -330,7 +330,8 @@ extern "C" int etf_set_option(etf_ctx *ctx, const char *name, int64_t value)
         if (value < 1) return fail(ctx, ETF_EINVAL, "sample_div must be positive");
         ctx->opt.sample_div = value;
     } else if (n == "traversal") {
-        if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "traversal must be 0 (register context) or 1 (level-synchronous)");
+        if (value < 0 || value > 2)
+            return fail(ctx, ETF_EINVAL, "traversal must be 0 (register context), 1 (level-synchronous) or 2 (tables in LDS)");
         ctx->opt.traversal = value;
     } else if (n == "lut_kernel") {
         if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "lut_kernel must be 0 (matrix cores) or 1 (plain sums)");

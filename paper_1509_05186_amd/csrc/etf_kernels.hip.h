@@ -508,6 +508,197 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
 }
 
 // ------------------------------------------------------------------------------------------------
+// Search with every table slice in LDS (flat ADC, and the trees walked per lane group).
+//     All M = 4*M4 slices of a sub-tile of Qs = 64/G queries are staged in LDS; a lane owns V = 2
+//     adjacent queries of one item, so one address and one 8-byte LDS read serve two distances: Qs/2
+//     lanes per item, IPS = 2G items per wave step.  Nothing but the item records is read from HBM.
+//     The sum of an item is formed as everywhere else: chunks left to right inside a tree, the T trees
+//     (equal groups of D = M/T chunks) in order.
+//
+//     OUT_FILTER: a workgroup takes per_block consecutive items and cuts them into one run per lane
+//     group.  With CTX the items are the sorted distinct encodings and every lane group walks its run
+//     depth first with a Distance Context (paper, "Distance Computation with Hierarchical Memory
+//     Structure") reduced to the first S levels of tree 0: as long as no lane group of the wave leaves
+//     the S-chunk prefix of its previous item, the sum over those levels is kept and only the deeper
+//     chunks are looked up; otherwise the whole wave recomputes it (which changes nothing for the lane
+//     groups that did not need to).  Deeper levels are not shared: the lane groups of a wave diverge
+//     there almost every step, and a lookup costs the same whether or not every group needs it.
+//     Candidates at or below the bound go to a ring of the wave in LDS (slot = rank among the passing
+//     lanes) and are appended to the queries' lists by the whole wave when the ring is nearly full: one
+//     global reservation per query, then LDS atomics hand out the slots.
+//     OUT_SAMPLE: items map[i]; every lane group owns whole sample groups and keeps their minima.
+//     rec [n][M4] dwords: the codes of an item, chunk 0 in the lowest byte.
+//     grid (blocks, G, tiles), block 1024, dynamic LDS M*K*Qs*4 bytes; per_block < 2^26.
+// ------------------------------------------------------------------------------------------------
+typedef float vec2f __attribute__((ext_vector_type(2)));
+
+// FROM = 0: every chunk is looked up and `top` (the sum over the first S chunks) is refreshed;
+// FROM = S > 0: `top` is reused.  look(m) returns the two queries' entries of chunk m.
+template <int M4, int T, int S, int FROM, class Look>
+__device__ __forceinline__ vec2f lds_item_sum(Look look, vec2f &top)
+{
+    constexpr int M = 4 * M4, D = M / T;
+    vec2f s = 0.f, d = 0.f;
+    if (S > 0) {
+        if (FROM == 0) {
+            s = look(0);
+#pragma unroll
+            for (int m = 1; m < S; ++m) s += look(m);
+            top = s;
+        } else {
+            s = top;
+        }
+    }
+#pragma unroll
+    for (int m = S; m < M; ++m) {
+        const vec2f x = look(m);
+        if (m % D == 0) {
+            if (m > 0) d = (m == D) ? s : d + s;
+            s = x;
+        } else {
+            s += x;
+        }
+    }
+    return T == 1 ? s : d + s;
+}
+
+template <int G, int M4, int T, int MODE, bool CTX>
+__global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, int64_t nitems,
+                                              const uint32_t *__restrict__ map, const float *__restrict__ lutT, int K,
+                                              int per_block, OutArgs o)
+{
+    constexpr int Qs = WAVE / G, V = 2, LPI = Qs / V, IPS = WAVE / LPI, M = 4 * M4, D = M / T;
+    constexpr int S = CTX ? (D >= 3 ? 2 : D - 1) : 0;
+    constexpr int U = M4 >= 4 ? 2 : 4;
+    constexpr int RING = 160;
+    constexpr bool FILTER = MODE == OUT_FILTER;
+    extern __shared__ float lds[];
+    __shared__ uint64_t ring[FILTER ? 16 : 1][FILTER ? RING : 1];
+    __shared__ uint32_t wcount[FILTER ? 16 : 1][64];
+    __shared__ uint32_t wpos[FILTER ? 16 : 1][64];
+    const int tile = blockIdx.z, sub = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int w = uniform(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    if (FILTER) wcount[w][lane] = 0u;
+    stage_slices<G>(lds, lutT, tile, sub, M, K, 0, M);
+    const int lg = lane / LPI, lq = lane % LPI;
+    const int col = sub * Qs + lq * V;  // first of this lane's two queries inside the tile
+    const char *ldsb = reinterpret_cast<const char *>(lds) + lq * (V * 4);
+    const uint32_t rowB = Qs * 4, sliceB = (uint32_t)K * rowB;
+    auto sum_of = [&](const uint32_t dw[M4], bool fast, vec2f &top) -> vec2f {
+        auto look = [&](int m) -> vec2f {
+            const uint32_t code = (dw[m >> 2] >> (8 * (m & 3))) & 255u;
+            return *reinterpret_cast<const vec2f *>(ldsb + (uint32_t)m * sliceB + code * rowB);
+        };
+        if (S > 0 && fast) return lds_item_sum<M4, T, S, S>(look, top);
+        return lds_item_sum<M4, T, S, 0>(look, top);
+    };
+
+    if (MODE == OUT_SAMPLE) {
+        const int64_t stride = (int64_t)gridDim.x * nw * IPS;
+        for (int64_t g0 = ((int64_t)blockIdx.x * nw + w) * IPS; g0 < o.ngroups; g0 += stride) {
+            const int64_t g = g0 + lg;
+            const bool glive = g < o.ngroups;
+            vec2f best = __uint_as_float(0x7F800000u);
+            for (int jj = 0; jj < o.gsize; jj += U) {
+                uint32_t dw[U][M4];
+                bool live[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t idx = g * o.gsize + jj + u;
+                    live[u] = glive && jj + u < o.gsize && idx < nitems;
+                    const int64_t e = live[u] ? (int64_t)map[idx] : 0;
+#pragma unroll
+                    for (int i = 0; i < M4; ++i) dw[u][i] = rec[e * M4 + i];
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    vec2f top = 0.f;
+                    const vec2f d = sum_of(dw[u], false, top);
+                    if (live[u]) {
+                        best.x = fminf(best.x, d.x);
+                        best.y = fminf(best.y, d.y);
+                    }
+                }
+            }
+            if (glive) {
+                float *dst = o.gmin + ((int64_t)tile * o.ngroups + g) * QT + col;
+                dst[0] = best.x;
+                dst[1] = best.y;
+            }
+        }
+        return;
+    }
+
+    const int64_t blo = (int64_t)blockIdx.x * per_block;
+    const int64_t bhi = min(nitems, blo + per_block);
+    const float tau0 = o.tau[(int64_t)tile * QT + col], tau1 = o.tau[(int64_t)tile * QT + col + 1];
+    int held = 0;
+    auto flush = [&]() {
+        const uint32_t c = wcount[w][lane];
+        wpos[w][lane] = c ? atomicAdd(&o.cnt[(int64_t)tile * QT + lane], c) : 0u;
+        wcount[w][lane] = 0u;
+        __builtin_amdgcn_wave_barrier();
+        for (int i = lane; i < held; i += 64) {
+            const uint64_t e = ring[w][i];
+            const int owner = (int)((e >> 26) & 63u);
+            const uint32_t pos = atomicAdd(&wpos[w][owner], 1u);
+            const int64_t q = (int64_t)tile * QT + owner;
+            if (pos < o.C)
+                o.cand[q * o.C + pos] = (e & 0xFFFFFFFF00000000ull) | (uint32_t)(blo + (int64_t)(e & 0x3FFFFFFull));
+        }
+        __builtin_amdgcn_wave_barrier();
+        held = 0;
+    };
+    auto emit = [&](bool pass, float d, int c, uint32_t rel) {
+        const uint64_t mask = __ballot(pass);
+        if (mask != 0ull) {
+            const int rank = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            if (pass) {
+                ring[w][held + rank] = ((uint64_t)__float_as_uint(d) << 32) | ((uint32_t)c << 26) | rel;
+                atomicAdd(&wcount[w][c], 1u);
+            }
+            held += __popcll(mask);
+            if (held > RING - 64) flush();
+        }
+    };
+    // one run of consecutive items per lane group
+    const int nruns = nw * IPS;
+    const int64_t RL = (per_block + nruns - 1) / nruns;
+    const int64_t rlo = blo + (int64_t)(w * IPS + lg) * RL;
+    const int64_t rhi = min(bhi, rlo + RL);
+    uint32_t prev0 = 0u;
+    vec2f top = 0.f;
+    for (int64_t i = 0; i < RL; i += U) {
+        uint32_t dw[U][M4];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t j = min(rlo + i + u, nitems - 1);
+#pragma unroll
+            for (int k2 = 0; k2 < M4; ++k2) dw[u][k2] = rec[j * M4 + k2];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t j = rlo + i + u;
+            const bool live = j < rhi;
+            bool fast = false;
+            if (S > 0) {
+                // a lane group may keep its context if its item has the S-chunk prefix of the previous one
+                const uint32_t smask = S == 1 ? 0xFFu : 0xFFFFu;
+                const bool keep = !live || ((((dw[u][0] ^ prev0) & smask) == 0u) && (i + u) > 0);
+                fast = __ballot(!keep) == 0ull;
+                prev0 = dw[u][0];
+            }
+            const vec2f d = sum_of(dw[u], fast, top);
+            const uint32_t rel = (uint32_t)(j - blo);
+            emit(live && d.x <= tau0, d.x, col, rel);
+            emit(live && d.y <= tau1, d.y, col + 1, rel);
+        }
+    }
+    flush();
+}
+
+// ------------------------------------------------------------------------------------------------
 // S4  forest reduction (paper "Encoding Forests": per-tree result arrays summed per vector):
 //     dist(e) = leafp[0][leaf_of[0][e]] + leafp[1][leaf_of[1][e]] + ...   (tree order).
 //     Lane = query; a wave walks consecutive items, each item is T coalesced row reads.

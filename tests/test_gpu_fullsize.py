@@ -57,7 +57,7 @@ def test_cfg2_forest_search_full_size():
     say("cfg2 full size: building inputs")
     cb, codes, queries = build_inputs(cfg)
     qd = torch.from_numpy(queries).cuda()
-    for trav in (0, 1):
+    for trav in (0, 1, 2):
         say("cfg2 E-Forest T=2 top-100, traversal", trav)
         c = make_ctx(cb, codes, cfg.trees, traversal=trav)
         ids, dist = c.search(qd, cfg.topk, etf.ETF_MODE_FOREST)
@@ -67,7 +67,7 @@ def test_cfg2_forest_search_full_size():
         say("  checked", n, "queries against the oracle")
         if trav == 0:
             first = (ids.clone(), dist.clone())
-        else:   # both traversals add the same float32 values in the same order
+        else:   # every traversal adds the same float32 values in the same order
             assert torch.equal(first[0], ids) and torch.equal(first[1], dist)
     say("cfg2 single E-Tree and flat, same queries")
     c = make_ctx(cb, codes, 1)

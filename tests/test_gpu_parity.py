@@ -87,10 +87,11 @@ def test_lut_kernels_on_wide_subspaces():
         assert_distances_close(d.cpu().numpy(), p.ref_all, "adc with lut kernel %d" % lk)
 
 
-TRAVERSALS = [0, 1]      # 0: distance context in registers, 1: level-synchronous kernels
+TRAVERSALS = [0, 1, 2]   # 0: distance context in registers, 1: level-synchronous kernels, 2: searches with all tables in LDS
+ADC_TRAVERSALS = [0, 1]  # all-pairs output has no LDS-resident variant (2 runs as 0 there)
 
 
-@pytest.mark.parametrize("trav", TRAVERSALS)
+@pytest.mark.parametrize("trav", ADC_TRAVERSALS)
 @pytest.mark.parametrize("mode,T", [(FLAT, 1), (TREE, 1), (FOREST, 1), (FOREST, 2), (FOREST, 4), (FOREST, 8)])
 def test_adc_all_pairs(small, mode, T, trav):
     if mode == FLAT and trav == 1:
@@ -102,7 +103,7 @@ def test_adc_all_pairs(small, mode, T, trav):
     assert_distances_close(dist.cpu().numpy(), small.ref_all, "adc mode %d T %d" % (mode, T))
 
 
-@pytest.mark.parametrize("trav", TRAVERSALS)
+@pytest.mark.parametrize("trav", ADC_TRAVERSALS)
 def test_tree_equals_flat_bitwise(small, trav):
     say("tree == flat bitwise, traversal", trav)
     c = small.ctx(T=1, traversal=trav)
@@ -112,7 +113,7 @@ def test_tree_equals_flat_bitwise(small, trav):
     assert torch.equal(a, b)       # same left-to-right float32 sum, shared prefixes added once
 
 
-@pytest.mark.parametrize("trav", TRAVERSALS)
+@pytest.mark.parametrize("trav", ADC_TRAVERSALS)
 def test_adc_unequal_groups_and_batches(small, trav):
     say("adc unequal chunk groups, tiny workspace cap => several query batches, traversal", trav)
     c = small.ctx(T=3, chunk_begin=[0, 1, 4, 8], ws_cap_bytes=1 << 20, traversal=trav)
