@@ -24,23 +24,6 @@
 
 namespace etf {
 
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-
-// raw buffer over `bytes` bytes at p (gfx9 family descriptor word 3: 32-bit data format); loads beyond
-// the end return zero instead of faulting
-__device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), (short)0, (int)bytes, 0x00020000);
-}
-__device__ __forceinline__ float buf_load(rsrc_t r, int voff, int soff)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
-}
-__device__ __forceinline__ void buf_store(float v, rsrc_t r, int voff, int soff)
-{
-    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), r, voff, soff, 0);
-}
-
 // (a & m) | (b & ~m)
 __device__ __forceinline__ float bit_select(uint32_t m, float a, float b)
 {

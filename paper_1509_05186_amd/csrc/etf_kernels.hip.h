@@ -10,6 +10,8 @@
 // a wave then works on G nodes at a time (lane = g * Qs + q).
 #pragma once
 
+#include <type_traits>
+
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -24,6 +26,24 @@ constexpr int WAVE = 64;
 constexpr int UB = ETF_UB;  // rows a wave keeps in flight
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+// raw buffer over `bytes` bytes at p (gfx9 family descriptor word 3: 32-bit data format); loads beyond
+// the end return zero instead of faulting
+__device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), (short)0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ float buf_load(rsrc_t r, int voff, int soff)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+}
+__device__ __forceinline__ void buf_store(float v, rsrc_t r, int voff, int soff)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), r, voff, soff, 0);
+}
+
 
 __device__ __forceinline__ int64_t uniform64(int64_t v)
 {
@@ -587,7 +607,7 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     const uint32_t rowB = Qs * 4, sliceB = (uint32_t)K * rowB;
     auto sum_of = [&](const uint32_t dw[M4], bool fast, vec2f &top) -> vec2f {
         auto look = [&](int m) -> vec2f {
-            const uint32_t code = (dw[m >> 2] >> (8 * (m & 3))) & 255u;
+            const uint32_t code = __builtin_amdgcn_ubfe(dw[m >> 2], 8 * (m & 3), 8);
             return *reinterpret_cast<const vec2f *>(ldsb + (uint32_t)m * sliceB + code * rowB);
         };
         if (S > 0 && fast) return lds_item_sum<M4, T, S, S>(look, top);
@@ -662,39 +682,56 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
             if (held > RING - 64) flush();
         }
     };
-    // one run of consecutive items per lane group
+    // one run of consecutive items per lane group; records come through a buffer over the workgroup's share,
+    // the step number in the scalar offset
+    if (blo >= bhi) return;
     const int nruns = nw * IPS;
-    const int64_t RL = (per_block + nruns - 1) / nruns;
+    const int RL = (per_block + nruns - 1) / nruns;
     const int64_t rlo = blo + (int64_t)(w * IPS + lg) * RL;
-    const int64_t rhi = min(bhi, rlo + RL);
+    const int len = (int)max<int64_t>(0, min<int64_t>(bhi - rlo, RL));  // items of this lane group's run
+    int minlen = len;
+#pragma unroll
+    for (int dlt = LPI; dlt < WAVE; dlt <<= 1) minlen = min(minlen, __shfl_xor(minlen, dlt));
+    minlen = uniform(minlen);
+    const rsrc_t rr = make_rsrc(rec + blo * M4, (uint32_t)((bhi - blo) * (M4 * 4)));
+    const uint32_t voff = len > 0 ? (uint32_t)((rlo - blo) * (M4 * 4)) : 0u;
     uint32_t prev0 = 0u;
     vec2f top = 0.f;
-    for (int64_t i = 0; i < RL; i += U) {
+    // U steps from step i on; CHECK: some lane groups may be past the end of their run
+    auto steps = [&](int i, auto check) {
+        constexpr bool CHECK = decltype(check)::value;
         uint32_t dw[U][M4];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t j = min(rlo + i + u, nitems - 1);
+            uint32_t vo = voff;
+            int so = (i + u) * (M4 * 4);
+            if (CHECK) {
+                vo += (uint32_t)max(0, min(i + u, len - 1)) * (M4 * 4);
+                so = 0;
+            }
 #pragma unroll
-            for (int k2 = 0; k2 < M4; ++k2) dw[u][k2] = rec[j * M4 + k2];
+            for (int k2 = 0; k2 < M4; ++k2) dw[u][k2] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rr, (int)vo + 4 * k2, so, 0);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t j = rlo + i + u;
-            const bool live = j < rhi;
+            const bool live = !CHECK || i + u < len;
             bool fast = false;
             if (S > 0) {
                 // a lane group may keep its context if its item has the S-chunk prefix of the previous one
                 const uint32_t smask = S == 1 ? 0xFFu : 0xFFFFu;
-                const bool keep = !live || ((((dw[u][0] ^ prev0) & smask) == 0u) && (i + u) > 0);
-                fast = __ballot(!keep) == 0ull;
+                const bool differs = live && ((dw[u][0] ^ prev0) & smask) != 0u;
+                fast = __ballot(differs) == 0ull && i + u != 0;
                 prev0 = dw[u][0];
             }
             const vec2f d = sum_of(dw[u], fast, top);
-            const uint32_t rel = (uint32_t)(j - blo);
+            const uint32_t rel = (uint32_t)(rlo - blo) + (uint32_t)(i + u);
             emit(live && d.x <= tau0, d.x, col, rel);
             emit(live && d.y <= tau1, d.y, col + 1, rel);
         }
-    }
+    };
+    int i = 0;
+    for (; i + U <= minlen; i += U) steps(i, std::false_type{});
+    for (; i < RL; i += U) steps(i, std::true_type{});
     flush();
 }
 
