@@ -26,6 +26,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # under profiles/ (counters scaled by what a 1 GiB copy in the same run reads).  Keyed by (workload, kernel class,
 # traversal); reported only for the exact configuration that was profiled.
 MEASURED_TRAFFIC_BYTES = {("cfg2", "reduce", "register-context"): 9.357e9}
+# LDS read bandwidth of the chip: 256 compute units x 256 bytes per clock x 2.4 GHz (a conflict-free 16-byte-per-lane
+# wave read, 1 KiB, occupies the LDS pipe for 4 clocks: SQ_LDS_IDX_ACTIVE minus SQ_LDS_BANK_CONFLICT per read)
+LDS_PEAK_GBS = 256 * 256 * 2.4
+TRAVERSAL_NAMES = {0: "register-context", 1: "level-synchronous", 2: "lds-resident"}
 PAPER_CONTEXT = {              # the paper's own numbers: one Core i7 at 3.6 GHz, one query at a time, SIFT1M, M=8, K=256
     "hardware": "Intel Core i7 3.6 GHz (paper, section Experiments)",
     "ms_per_query": {"flat_adc": 2.678, "e_tree": 1.760, "e_forest_2": 1.265},
@@ -71,6 +75,20 @@ def algorithmic_bytes(stats, mode, S, tiles):
             G *= 2
         out["flat"] = tiles * (G * N * M + M * K * row)
         out["sample"] = tiles * (S * (4 + M * G) + S * row + M * K * row)
+        return out
+    if mode == "forest_lds":
+        # every table slice in LDS: per query and distinct encoding, one 4-byte LDS read per chunk below the
+        # S-chunk prefix kept in the context, plus the S upper ones for the first encoding of every prefix
+        tr0 = stats["trees"][0]
+        D0 = tr0["D"]
+        Sl = 2 if D0 >= 3 else D0 - 1
+        prefixes = (tr0["nI"][Sl - 1] + sum(tr0["nL"][:Sl])) if Sl > 0 else 0
+        out["lds"] = tiles * 64 * 4 * (Nd * (M - Sl) + Sl * prefixes)
+        out["sample"] = tiles * 64 * 4 * S * M
+        G = 2
+        while M * K * (64 // G) * 4 > 128 * 1024:
+            G *= 2
+        out["lds_hbm"] = tiles * (M * K * row + G * Nd * M)   # what the same kernel has to read from HBM
         return out
     if mode == "forest_ctx":
         # register-context traversal: trees 1..T-1 each write one result row per leaf (reading a 4..16 byte
@@ -128,9 +146,9 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the flat and single-tree legs")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
     ap.add_argument("--levels", action="store_true",
-                    help="time the level-synchronous traversal (partial sums of internal nodes in HBM) instead of the default "
-                         "register-context traversal")
-    ap.add_argument("--traversal", type=int, default=0, help="0 register context (default), 1 level-synchronous, 2 tables in LDS")
+                    help="same as --traversal 1: the level-synchronous traversal (partial sums of internal nodes in HBM)")
+    ap.add_argument("--traversal", type=int, default=2, choices=[0, 1, 2],
+                    help="2 every table slice in LDS (default), 0 distance context in registers + result tables, 1 level-synchronous")
     ap.add_argument("--no-copy", action="store_true", help="skip the 1 GiB device copy (bandwidth ceiling / counter calibration)")
     args = ap.parse_args()
     if args.levels:
@@ -157,9 +175,9 @@ def main():
     out_ids = torch.empty((Q, k), dtype=torch.int32, device="cuda")
     out_dist = torch.empty((Q, k), dtype=torch.float32, device="cuda")
 
-    def make_ctx(T):
+    def make_ctx(T, traversal=None):
         c = etf.Context(device=0, stream=stream)
-        c.set_option("traversal", args.traversal)
+        c.set_option("traversal", args.traversal if traversal is None else traversal)
         c.pq_set_codebooks(cb)
         t0 = time.time()
         c.index_build(codes, T=T)
@@ -169,49 +187,64 @@ def main():
         return c
 
     T = max(cfg.trees, 1)
-    forest = make_ctx(T)
-    stats = forest.index_stats()
-    mode = etf.ETF_MODE_FOREST
-    ws = forest.alloc_workspace(Q, k, mode)
-    log("workspace %.2f GB" % (ws.numel() / 1e9))
-    dt, prof = time_search(forest, qd, k, mode, args.warmup, args.steps, torch, ws, out_ids, out_dist)
-    ms_step = dt / args.steps * 1e3
-    value = N * Q * args.steps / dt
-    fallbacks = forest.last_fallback_count()
-    log("E-Forest(T=%d) top-%d: %.2f ms/step, %.3e distances/s, %d queries via the exact kernel" % (T, k, ms_step, value, fallbacks))
-    got_ids, got_dist = out_ids.cpu().numpy(), out_dist.cpu().numpy()
-
-    # ---- roofline of the dominant kernel class
     tiles = (Q + 63) // 64
-    S = forest.index_layout().n_sample_enc
-    ctx_path = not args.levels and T <= 4
-    alg = algorithmic_bytes(stats, "forest_ctx" if ctx_path else "forest", S, tiles)
-    kernels = {}
-    for name, (ms, cnt) in prof.items():
-        if cnt:
-            kernels[name] = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps,
-                             "alg_GB_per_step": alg.get(name, 0) / 1e9,
-                             "alg_GBps": (alg.get(name, 0) / 1e9) / (ms / args.steps / 1e3) if ms > 0 and name in alg else None}
-    roofline = None
-    if kernels:
-        dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
-        kd = kernels[dom]
-        lps = kd["launches_per_step"]
-        achieved = kd["alg_GBps"] or 0.0
-        trav_name = "level-synchronous" if args.levels else "register-context"
-        traffic = None if (args.scale_n or args.scale_q) else MEASURED_TRAFFIC_BYTES.get((cfg.name, dom, trav_name))
-        roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                    "alg_bytes_per_launch": alg.get(dom, 0) / lps if lps else None,
-                    "avg_launch_ms": kd["ms_per_step"] / lps if lps else None,
-                    "launches_per_step": lps}
-        # the traversal as a whole (levels + leaves + reduction), the north-star's bandwidth figure
-        trav = [n for n in ("level", "leaf", "reduce", "sample") if n in kernels]
-        tms = sum(kernels[n]["ms_per_step"] for n in trav)
-        tgb = sum(kernels[n]["alg_GB_per_step"] for n in trav)
-        roofline["traversal"] = {"kernels": trav, "ms_per_step": tms, "alg_GB_per_step": tgb,
-                                 "alg_GBps": tgb / (tms / 1e3) if tms > 0 else None,
-                                 "frac": (tgb / (tms / 1e3)) / HBM_PEAK_GBS if tms > 0 else None}
+    mode = etf.ETF_MODE_FOREST
+
+    def measure_forest(traversal, steps, warmup):
+        """Times the E-Forest search with one traversal; returns the numbers of the JSON line."""
+        forest = make_ctx(T, traversal)
+        stats = forest.index_stats()
+        ws = forest.alloc_workspace(Q, k, mode)
+        log("traversal %s: workspace %.2f GB" % (TRAVERSAL_NAMES[traversal], ws.numel() / 1e9))
+        dt, prof = time_search(forest, qd, k, mode, warmup, steps, torch, ws, out_ids, out_dist)
+        ms_step = dt / steps * 1e3
+        value = N * Q * steps / dt
+        fallbacks = forest.last_fallback_count()
+        log("E-Forest(T=%d) top-%d, %s: %.2f ms/step, %.3e distances/s, %d queries via the exact kernel"
+            % (T, k, TRAVERSAL_NAMES[traversal], ms_step, value, fallbacks))
+        S = forest.index_layout().n_sample_enc
+        lds_path = "lds" in prof and prof["lds"][1] > 0
+        ctx_path = traversal != 1 and T <= 4
+        alg = algorithmic_bytes(stats, "forest_lds" if lds_path else "forest_ctx" if ctx_path else "forest", S, tiles)
+        kernels = {}
+        for name, (ms, cnt) in prof.items():
+            if cnt:
+                kernels[name] = {"ms_per_step": ms / steps, "launches_per_step": cnt / steps,
+                                 "alg_GB_per_step": alg.get(name, 0) / 1e9,
+                                 "alg_GBps": (alg.get(name, 0) / 1e9) / (ms / steps / 1e3) if ms > 0 and name in alg else None}
+        roofline = None
+        if kernels:
+            dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+            kd = kernels[dom]
+            lps = kd["launches_per_step"]
+            achieved = kd["alg_GBps"] or 0.0
+            traffic = None if (args.scale_n or args.scale_q) else MEASURED_TRAFFIC_BYTES.get((cfg.name, dom, TRAVERSAL_NAMES[traversal]))
+            if dom == "lds":
+                # bound by the LDS pipe: algorithmic bytes are the 4-byte table entries the method reads per query
+                roofline = {"bound": "alu", "resource": "LDS read bandwidth", "kernel": dom, "achieved": achieved,
+                            "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": achieved / LDS_PEAK_GBS, "traffic": traffic}
+            else:
+                roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic}
+            roofline.update({"alg_bytes_per_launch": alg.get(dom, 0) / lps if lps else None,
+                             "avg_launch_ms": kd["ms_per_step"] / lps if lps else None, "launches_per_step": lps})
+            if dom != "lds":
+                # the traversal as a whole (levels + leaves + reduction): the bandwidth figure of the table-based paths
+                trav = [n for n in ("level", "leaf", "reduce", "sample") if n in kernels]
+                tms = sum(kernels[n]["ms_per_step"] for n in trav)
+                tgb = sum(kernels[n]["alg_GB_per_step"] for n in trav)
+                roofline["traversal"] = {"kernels": trav, "ms_per_step": tms, "alg_GB_per_step": tgb,
+                                         "alg_GBps": tgb / (tms / 1e3) if tms > 0 else None,
+                                         "frac": (tgb / (tms / 1e3)) / HBM_PEAK_GBS if tms > 0 else None}
+        res = {"ms_per_step": ms_step, "value": value, "fallbacks": fallbacks, "kernels": kernels, "roofline": roofline,
+               "stats": stats, "S": int(S), "traversal": TRAVERSAL_NAMES[traversal]}
+        del ws
+        return res
+
+    main_res = measure_forest(args.traversal, args.steps, args.warmup)
+    got_ids, got_dist = out_ids.cpu().numpy(), out_dist.cpu().numpy()
+    ms_step, value, fallbacks = main_res["ms_per_step"], main_res["value"], main_res["fallbacks"]
+    kernels, roofline, stats, S = main_res["kernels"], main_res["roofline"], main_res["stats"], main_res["S"]
 
     # ---- a plain device copy of known size: achievable-bandwidth ceiling, and the reference dispatch
     #      against which the HBM byte counters are scaled
@@ -238,6 +271,10 @@ def main():
     others = {}
     if not args.no_others:
         osteps = max(2, min(args.steps, 3))
+        if args.traversal == 2:
+            # the same E-Forest search through the table-based traversal (per-tree result tables in HBM)
+            r0 = measure_forest(0, osteps, 1)
+            others["e_forest_register_context"] = {k2: r0[k2] for k2 in ("value", "ms_per_step", "kernels", "roofline")}
         tree = make_ctx(1)
         for name, ctx, m in (("flat_gpu", tree, etf.ETF_MODE_FLAT), ("e_tree_gpu", tree, etf.ETF_MODE_TREE)):
             w2 = ctx.alloc_workspace(Q, k, m)
@@ -284,7 +321,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: d=%d N=%d Q=%d PQ M=%d K=%d, E-Forest T=%d, top-%d, seeded %d-component Gaussian mixture"
                                % (cfg.name, cfg.d, N, Q, cfg.M, cfg.K, T, k, cfg.components),
-                   "traversal": "level-synchronous" if args.levels else "register-context",
+                   "traversal": TRAVERSAL_NAMES[args.traversal],
                    "valid": not (args.scale_n or args.scale_q)},
         "roofline": roofline, "cpu_baseline": cpu,
         "kernels": kernels, "others": others, "fallback_queries": fallbacks, "device_copy": copy,

@@ -100,13 +100,16 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     on vectors shifted by the group's mean codeword; entries below a quarter of
  *                     ||q'||^2 + ||c'||^2, where that form cancels, are recomputed as plain sums.
  *                     1: every entry as a plain float32 sum of (q - c)^2
- *   "traversal"       0 (default): trees are walked in depth-first leaf order with the distance
- *                     context in registers; 1: level-synchronous kernels over the level arrays
- *                     (partial sums of internal nodes in device memory); 2: searches keep every
- *                     table slice of a group of queries in LDS and walk the sorted encodings
- *                     with a short distance context per lane group, no per-tree result tables
- *                     (M in {4, 8, 16}, 1, 2 or 4 equal trees; anything else, and etf_adc, runs
- *                     as traversal 0)
+ *   "traversal"       how trees are walked.
+ *                     0: depth-first leaf order with the distance context in registers, per-tree
+ *                     result tables in device memory for trees 1 .. T-1;
+ *                     1: level-synchronous kernels over the level arrays (partial sums of internal
+ *                     nodes in device memory);
+ *                     2 (default): searches keep every table slice of a group of queries in LDS and
+ *                     walk the sorted encodings with a short distance context per lane group, no
+ *                     result tables at all (built for M in {4, 8, 16} and 1, 2 or 4 equal trees);
+ *                     every other shape, and etf_adc, runs as 0.
+ *                     All three add the same float32 values in the same order.
  * Returns ETF_EINVAL for an unknown name or a value out of range. */
 int etf_set_option(etf_ctx *ctx, const char *name, int64_t value);
 

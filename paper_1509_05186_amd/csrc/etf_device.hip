@@ -604,7 +604,7 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
     const int M = ctx->M, K = ctx->K;
     const int G = std::max(2, pick_G(M, K));
     const size_t lds = (size_t)M * K * (WAVE / G) * 4;
-    const int IPS = 2 * G;  // items per wave step
+    const int IPS = LDS_V * G;  // items per wave step
     int64_t bx;
     int per_block = 0;
     if (MODE == OUT_SAMPLE) {

@@ -529,9 +529,9 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
 
 // ------------------------------------------------------------------------------------------------
 // Search with every table slice in LDS (flat ADC, and the trees walked per lane group).
-//     All M = 4*M4 slices of a sub-tile of Qs = 64/G queries are staged in LDS; a lane owns V = 2
-//     adjacent queries of one item, so one address and one 8-byte LDS read serve two distances: Qs/2
-//     lanes per item, IPS = 2G items per wave step.  Nothing but the item records is read from HBM.
+//     All M = 4*M4 slices of a sub-tile of Qs = 64/G queries are staged in LDS; a lane owns V = 4
+//     adjacent queries of one item, so one address and one 16-byte LDS read serve four distances: Qs/4
+//     lanes per item, IPS = 4G items per wave step (measured on cfg2: V = 1, 2, 4, 8 -> 12.2, 4.2, 3.5, 4.8 ms).  Nothing but the item records is read from HBM.
 //     The sum of an item is formed as everywhere else: chunks left to right inside a tree, the T trees
 //     (equal groups of D = M/T chunks) in order.
 //
@@ -550,15 +550,16 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
 //     rec [n][M4] dwords: the codes of an item, chunk 0 in the lowest byte.
 //     grid (blocks, G, tiles), block 1024, dynamic LDS M*K*Qs*4 bytes; per_block < 2^26.
 // ------------------------------------------------------------------------------------------------
-typedef float vec2f __attribute__((ext_vector_type(2)));
+constexpr int LDS_V = 4;  // queries per lane (one 16-byte LDS read per lookup)
+typedef float vecq __attribute__((ext_vector_type(LDS_V)));
 
 // FROM = 0: every chunk is looked up and `top` (the sum over the first S chunks) is refreshed;
-// FROM = S > 0: `top` is reused.  look(m) returns the two queries' entries of chunk m.
+// FROM = S > 0: `top` is reused.  look(m) returns the lane's queries' entries of chunk m.
 template <int M4, int T, int S, int FROM, class Look>
-__device__ __forceinline__ vec2f lds_item_sum(Look look, vec2f &top)
+__device__ __forceinline__ vecq lds_item_sum(Look look, vecq &top)
 {
     constexpr int M = 4 * M4, D = M / T;
-    vec2f s = 0.f, d = 0.f;
+    vecq s = 0.f, d = 0.f;
     if (S > 0) {
         if (FROM == 0) {
             s = look(0);
@@ -571,7 +572,7 @@ __device__ __forceinline__ vec2f lds_item_sum(Look look, vec2f &top)
     }
 #pragma unroll
     for (int m = S; m < M; ++m) {
-        const vec2f x = look(m);
+        const vecq x = look(m);
         if (m % D == 0) {
             if (m > 0) d = (m == D) ? s : d + s;
             s = x;
@@ -587,7 +588,7 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
                                               const uint32_t *__restrict__ map, const float *__restrict__ lutT, int K,
                                               int per_block, OutArgs o)
 {
-    constexpr int Qs = WAVE / G, V = 2, LPI = Qs / V, IPS = WAVE / LPI, M = 4 * M4, D = M / T;
+    constexpr int Qs = WAVE / G, V = LDS_V, LPI = Qs / V, IPS = WAVE / LPI, M = 4 * M4, D = M / T;
     constexpr int S = CTX ? (D >= 3 ? 2 : D - 1) : 0;
     constexpr int U = M4 >= 4 ? 2 : 4;
     constexpr int RING = 160;
@@ -602,13 +603,13 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     if (FILTER) wcount[w][lane] = 0u;
     stage_slices<G>(lds, lutT, tile, sub, M, K, 0, M);
     const int lg = lane / LPI, lq = lane % LPI;
-    const int col = sub * Qs + lq * V;  // first of this lane's two queries inside the tile
+    const int col = sub * Qs + lq * V;  // first of this lane's queries inside the tile
     const char *ldsb = reinterpret_cast<const char *>(lds) + lq * (V * 4);
     const uint32_t rowB = Qs * 4, sliceB = (uint32_t)K * rowB;
-    auto sum_of = [&](const uint32_t dw[M4], bool fast, vec2f &top) -> vec2f {
-        auto look = [&](int m) -> vec2f {
+    auto sum_of = [&](const uint32_t dw[M4], bool fast, vecq &top) -> vecq {
+        auto look = [&](int m) -> vecq {
             const uint32_t code = __builtin_amdgcn_ubfe(dw[m >> 2], 8 * (m & 3), 8);
-            return *reinterpret_cast<const vec2f *>(ldsb + (uint32_t)m * sliceB + code * rowB);
+            return *reinterpret_cast<const vecq *>(ldsb + (uint32_t)m * sliceB + code * rowB);
         };
         if (S > 0 && fast) return lds_item_sum<M4, T, S, S>(look, top);
         return lds_item_sum<M4, T, S, 0>(look, top);
@@ -619,7 +620,7 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
         for (int64_t g0 = ((int64_t)blockIdx.x * nw + w) * IPS; g0 < o.ngroups; g0 += stride) {
             const int64_t g = g0 + lg;
             const bool glive = g < o.ngroups;
-            vec2f best = __uint_as_float(0x7F800000u);
+            vecq best = __uint_as_float(0x7F800000u);
             for (int jj = 0; jj < o.gsize; jj += U) {
                 uint32_t dw[U][M4];
                 bool live[U];
@@ -633,18 +634,18 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    vec2f top = 0.f;
-                    const vec2f d = sum_of(dw[u], false, top);
+                    vecq top = 0.f;
+                    const vecq d = sum_of(dw[u], false, top);
                     if (live[u]) {
-                        best.x = fminf(best.x, d.x);
-                        best.y = fminf(best.y, d.y);
+#pragma unroll
+                        for (int v = 0; v < V; ++v) best[v] = fminf(best[v], d[v]);
                     }
                 }
             }
             if (glive) {
                 float *dst = o.gmin + ((int64_t)tile * o.ngroups + g) * QT + col;
-                dst[0] = best.x;
-                dst[1] = best.y;
+#pragma unroll
+                for (int v = 0; v < V; ++v) dst[v] = best[v];
             }
         }
         return;
@@ -652,7 +653,9 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
 
     const int64_t blo = (int64_t)blockIdx.x * per_block;
     const int64_t bhi = min(nitems, blo + per_block);
-    const float tau0 = o.tau[(int64_t)tile * QT + col], tau1 = o.tau[(int64_t)tile * QT + col + 1];
+    float tau[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) tau[v] = o.tau[(int64_t)tile * QT + col + v];
     int held = 0;
     auto flush = [&]() {
         const uint32_t c = wcount[w][lane];
@@ -696,7 +699,7 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     const rsrc_t rr = make_rsrc(rec + blo * M4, (uint32_t)((bhi - blo) * (M4 * 4)));
     const uint32_t voff = len > 0 ? (uint32_t)((rlo - blo) * (M4 * 4)) : 0u;
     uint32_t prev0 = 0u;
-    vec2f top = 0.f;
+    vecq top = 0.f;
     // U steps from step i on; CHECK: some lane groups may be past the end of their run
     auto steps = [&](int i, auto check) {
         constexpr bool CHECK = decltype(check)::value;
@@ -723,10 +726,10 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
                 fast = __ballot(differs) == 0ull && i + u != 0;
                 prev0 = dw[u][0];
             }
-            const vec2f d = sum_of(dw[u], fast, top);
+            const vecq d = sum_of(dw[u], fast, top);
             const uint32_t rel = (uint32_t)(rlo - blo) + (uint32_t)(i + u);
-            emit(live && d.x <= tau0, d.x, col, rel);
-            emit(live && d.y <= tau1, d.y, col + 1, rel);
+#pragma unroll
+            for (int v = 0; v < V; ++v) emit(live && d[v] <= tau[v], d[v], col + v, rel);
         }
     };
     int i = 0;
