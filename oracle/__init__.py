@@ -41,6 +41,7 @@ def _load():
         lib.orc_num_threads.restype = c_int
         lib.orc_kmeans.argtypes = [P, c_i64, c_int, c_int, c_int, c_int, P, P, P]
         lib.orc_encode.argtypes = [P, c_i64, c_int, c_int, c_int, P, P]
+        lib.orc_encode_f32.argtypes = [P, c_i64, c_int, c_int, c_int, P, P]
         lib.orc_decode.argtypes = [P, c_i64, c_int, c_int, c_int, P, P]
         lib.orc_brute.argtypes = [P, P, c_i64, c_int, P]
         lib.orc_lut.argtypes = [P, c_int, c_int, c_int, P, P]
@@ -48,7 +49,7 @@ def _load():
         lib.orc_topk.argtypes = [P, P, c_i64, c_int, P, P]
         lib.orc_adc_all.argtypes = [P, c_i64, c_int, c_int, c_int, P, P, c_i64, P]
         lib.orc_search.argtypes = [P, c_i64, c_int, c_int, c_int, P, P, P, c_i64, c_int, P, P]
-        for f in ("orc_kmeans", "orc_encode", "orc_decode", "orc_brute", "orc_lut", "orc_adc_flat",
+        for f in ("orc_kmeans", "orc_encode", "orc_encode_f32", "orc_decode", "orc_brute", "orc_lut", "orc_adc_flat",
                   "orc_topk", "orc_adc_all", "orc_search"):
             getattr(lib, f).restype = c_int
         _lib = lib
@@ -102,6 +103,18 @@ def encode(x, codebooks) -> np.ndarray:
     assert d == M * ds
     codes = np.zeros((n, M), dtype=np.uint8)
     _check(_load().orc_encode(_p(x), n, d, M, K, _p(cb), _p(codes)), "encode")
+    return codes
+
+
+def encode_f32(x, codebooks) -> np.ndarray:
+    """The nearest-codeword assignment decided in float32 (sequential sums, one rounding per operation)."""
+    x = _f32(x)
+    cb = _f32(codebooks)
+    M, K, ds = cb.shape
+    n, d = x.shape
+    assert d == M * ds
+    codes = np.zeros((n, M), dtype=np.uint8)
+    _check(_load().orc_encode_f32(_p(x), n, d, M, K, _p(cb), _p(codes)), "encode_f32")
     return codes
 
 

@@ -191,6 +191,45 @@ int orc_encode(const float *x, int64_t n, int d, int M, int K,
 }
 
 /*
+ * The same quantiser decided in single precision: every squared distance is
+ * the float32 sum of float32 products, terms added in index order, each
+ * operation rounded on its own (no fused multiply-add), lowest index on ties.
+ * This is the arithmetic a float32 encoder can reproduce bit for bit; it is
+ * the reference for encoders that work in float32 (the paper fixes no
+ * precision for the assignment step).
+ */
+int orc_encode_f32(const float *x, int64_t n, int d, int M, int K,
+                   const float *codebooks, uint8_t *codes)
+{
+    int rc = check_shape(d, M, K);
+    if (rc) return rc;
+    if ((!x && n > 0) || !codebooks || (!codes && n > 0) || n < 0) return ORC_EINVAL;
+    const int ds = d / M;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t i = 0; i < n; ++i) {
+        for (int m = 0; m < M; ++m) {
+            const float *xi = x + (size_t)i * d + (size_t)m * ds;
+            int best = 0;
+            float bestd = FLT_MAX;
+            for (int k = 0; k < K; ++k) {
+                const float *c = codebooks + ((size_t)m * K + k) * ds;
+                volatile float s = 0.0f;     /* volatile: one rounding per operation, no contraction */
+                for (int j = 0; j < ds; ++j) {
+                    volatile float t = xi[j] - c[j];
+                    volatile float t2 = t * t;
+                    s = s + t2;
+                }
+                if (s < bestd) { bestd = s; best = k; }
+            }
+            codes[(size_t)i * M + m] = (uint8_t)best;
+        }
+    }
+    return ORC_OK;
+}
+
+/*
  * Reconstruction (Introduction: "approximated by the concatenation of M
  * codewords assigned"): xhat[i] = [c_1(i_1) | c_2(i_2) | ... | c_M(i_M)].
  */

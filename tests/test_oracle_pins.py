@@ -228,3 +228,46 @@ def test_tree_lookups_never_exceed_flat_on_distinct():
         assert st["L2"] == distinct
         assert st["lookups"] <= M * distinct
         assert st["paper_bytes"] == 4 * n + 2 * (st["L1"] + st["L2"]) + st["sumP"]
+
+
+# ---- float32 assignment (the reference of encoders that decide in float32) -------------------------
+
+def test_encode_f32_agrees_with_float64_outside_rounding_ties():
+    gm = GaussianMixture(24, 8, 1.1, (0.2, 1.0), (-4, 4), seed=21)
+    xt, xb = gm.sample(1500, 1), gm.sample(4000, 2)
+    M, K = 3, 64
+    cb, _ = oracle.kmeans(xt, M, K, 5, oracle.kmeans_init_rows(1500, M, K, 4))
+    a, b = oracle.encode(xb, cb), oracle.encode_f32(xb, cb)
+    diff = np.argwhere(a != b)
+    assert len(diff) <= 4          # float32 and float64 disagree only on near-ties
+    for i, m in diff:
+        sub = xb[i, m * 8:(m + 1) * 8].astype(np.float64)
+        da = ((sub - cb[m, a[i, m]]) ** 2).sum()
+        db = ((sub - cb[m, b[i, m]]) ** 2).sum()
+        assert abs(da - db) <= 1e-6 * max(da, db)
+
+
+def test_encode_f32_rounds_every_operation_and_breaks_ties_low():
+    # one query at the origin, two dimensions.  Codeword 0 = (1, 2^-13): its squared distance 1 + 2^-26 rounds to 1
+    # in float32; codeword 1 = (1, 0) is at exactly 1.  Float64 prefers codeword 1, float32 sees a tie -> index 0.
+    cb = np.array([[[1.0, 2.0 ** -13], [1.0, 0.0], [2.0, 0.0]]], dtype=np.float32)
+    x = np.zeros((1, 2), dtype=np.float32)
+    assert oracle.encode(x, cb)[0, 0] == 1
+    assert oracle.encode_f32(x, cb)[0, 0] == 0
+    # identical codewords: the lower index wins in both
+    cb2 = np.array([[[3.0, 3.0], [0.5, 0.5], [0.5, 0.5]]], dtype=np.float32)
+    assert oracle.encode_f32(x, cb2)[0, 0] == 1 and oracle.encode(x, cb2)[0, 0] == 1
+
+
+def test_encode_f32_equals_numpy_float32_definition():
+    rng = np.random.default_rng(5)
+    x = rng.normal(size=(300, 12)).astype(np.float32)
+    cb = rng.normal(size=(2, 20, 6)).astype(np.float32)
+    want = np.zeros((300, 2), dtype=np.uint8)
+    for m in range(2):
+        s = np.zeros((300, 20), dtype=np.float32)
+        for j in range(6):                   # terms in index order, every operation rounded to float32
+            d = (x[:, None, m * 6 + j] - cb[m][None, :, j]).astype(np.float32)
+            s = (s + (d * d).astype(np.float32)).astype(np.float32)
+        want[:, m] = s.argmin(axis=1)        # argmin returns the first minimum
+    assert np.array_equal(oracle.encode_f32(x, cb), want)
