@@ -197,6 +197,17 @@ int etf_index_export(const etf_ctx *ctx, void *host_buf, int64_t bytes);
 
 /* ---- device side -------------------------------------------------------- */
 
+/* Device encoder (paper: Introduction, product quantisation; complexity O(dKN) in
+ * "Efficient Encoding Tree Construction").  Same result definition as
+ * etf_pq_encode, decided in float32: every squared distance is the sum of its
+ * (x - c)^2 terms in dimension order, one rounding per operation, lowest index on
+ * ties.  x [n][d] device, codes_out [n][M] device; ws is device scratch of at least
+ * etf_encode_workspace_bytes() bytes (256-byte aligned) that receives the codebooks;
+ * the copy is enqueued on the context's stream from the context's host copy.
+ * Needs d/M <= 128; ETF_EINVAL otherwise.  n = 0 is allowed. */
+int64_t etf_encode_workspace_bytes(const etf_ctx *ctx);
+int etf_pq_encode_device(etf_ctx *ctx, const float *x, int64_t n, uint8_t *codes_out, void *ws, int64_t ws_bytes);
+
 /* Workspace (device bytes) that etf_adc / etf_search need for Q queries in the
  * given mode (k is ignored by etf_adc: pass 0).  Negative = error code. */
 int64_t etf_workspace_bytes(const etf_ctx *ctx, int64_t Q, int k, int mode);
@@ -235,7 +246,8 @@ enum {
     ETF_K_EXACT = 7,    /* exact whole-database selection                     */
     ETF_K_SAMPLE = 8,   /* distances of the bound's sample (flat or reduction) */
     ETF_K_LDS = 9,      /* tree / forest search with every table slice in LDS  */
-    ETF_K_COUNT = 10
+    ETF_K_ENCODE = 10,  /* device encoder                                      */
+    ETF_K_COUNT = 11
 };
 /* on != 0: every later kernel launch of this context is bracketed by a pair of
  * HIP events on the context's stream. */

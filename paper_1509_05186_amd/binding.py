@@ -20,10 +20,11 @@ EXPORTS = [
     "etf_pq_train", "etf_pq_set_codebooks", "etf_pq_get_codebooks", "etf_pq_encode",
     "etf_index_build", "etf_index_stats", "etf_index_device_bytes", "etf_index_upload",
     "etf_index_layout", "etf_index_export",
+    "etf_encode_workspace_bytes", "etf_pq_encode_device",
     "etf_workspace_bytes", "etf_lut_build", "etf_adc", "etf_search", "etf_last_fallback_count",
     "etf_profile_enable", "etf_profile_read",
 ]
-KERNEL_CLASSES = ["lut", "level", "leaf", "flat", "reduce", "tau", "select", "exact", "sample", "lds"]
+KERNEL_CLASSES = ["lut", "level", "leaf", "flat", "reduce", "tau", "select", "exact", "sample", "lds", "encode"]
 
 
 class EtfStats(ctypes.Structure):
@@ -112,6 +113,8 @@ def load_library():
         "etf_index_upload": (I, [P, P, L]),
         "etf_index_layout": (I, [P, ctypes.POINTER(EtfLayout)]),
         "etf_index_export": (I, [P, P, L]),
+        "etf_encode_workspace_bytes": (L, [P]),
+        "etf_pq_encode_device": (I, [P, P, L, P, P, L]),
         "etf_workspace_bytes": (L, [P, L, I, I]),
         "etf_lut_build": (I, [P, P, L, P]),
         "etf_adc": (I, [P, P, L, I, P, P, L]),
@@ -257,6 +260,24 @@ class Context:
     def _ws(ws):
         off = (-ws.data_ptr()) % 256
         return ws.data_ptr() + off, ws.numel() - off
+
+    def encode_workspace_bytes(self) -> int:
+        return self._ck(self._lib.etf_encode_workspace_bytes(self._h))
+
+    def pq_encode_device(self, x, codes=None, ws=None):
+        """x: float32 device tensor [n][d]; returns uint8 device tensor [n][M]."""
+        import torch
+        d, M, K = self._shape
+        if x.dim() != 2 or x.shape[1] != d or x.dtype != torch.float32 or not x.is_contiguous():
+            raise ValueError("expected a contiguous float32 tensor [n][%d]" % d)
+        n = x.shape[0]
+        if codes is None:
+            codes = torch.empty((n, M), dtype=torch.uint8, device=x.device)
+        if ws is None:
+            ws = torch.empty(self.encode_workspace_bytes() + 256, dtype=torch.uint8, device=x.device)
+        p, nb = self._ws(ws)
+        self._ck(self._lib.etf_pq_encode_device(self._h, _dev(x) if n else None, n, _dev(codes) if n else None, p, nb))
+        return codes
 
     def lut_build(self, queries, lut=None):
         import torch

@@ -770,6 +770,60 @@ extern "C" int etf_adc(etf_ctx *ctx, const float *queries, int64_t Q, int mode, 
 }
 
 // =============================================================================================
+// device encoder
+// =============================================================================================
+extern "C" int64_t etf_encode_workspace_bytes(const etf_ctx *ctx)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (ctx->codebooks.empty()) return fail(ctx, ETF_ESTATE, "no codebooks: call etf_pq_train or etf_pq_set_codebooks first");
+    return (int64_t)((ctx->codebooks.size() * sizeof(float) + 255) & ~(size_t)255);
+}
+
+extern "C" int etf_pq_encode_device(etf_ctx *ctx, const float *x, int64_t n, uint8_t *codes_out, void *ws, int64_t ws_bytes)
+{
+    int rc = need_device(ctx);
+    if (rc) return rc;
+    if (ctx->codebooks.empty()) return fail(ctx, ETF_ESTATE, "no codebooks: call etf_pq_train or etf_pq_set_codebooks first");
+    if (n < 0 || (n > 0 && (!x || !codes_out))) return fail(ctx, ETF_EINVAL, "null input or output with n=%lld", (long long)n);
+    if (!ws || ((uintptr_t)ws & 255) != 0) return fail(ctx, ETF_EINVAL, "workspace is null or not 256-byte aligned");
+    const int64_t need = etf_encode_workspace_bytes(ctx);
+    if (ws_bytes < need) return fail(ctx, ETF_ENOMEM, "workspace too small: %lld < %lld", (long long)ws_bytes, (long long)need);
+    const int d = ctx->d, M = ctx->M, K = ctx->K, ds = ctx->ds;
+    if (ds > 128) return fail(ctx, ETF_EINVAL, "the device encoder handles at most 128 dimensions per group (d/M = %d)", ds);
+    if (n == 0) return ETF_OK;
+    if ((n + 255) / 256 > 0x7FFFFFFF) return fail(ctx, ETF_EINVAL, "n too large for one launch");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    hipStream_t st = (hipStream_t)ctx->stream;
+    HIP_TRY(ctx, hipMemcpyAsync(ws, ctx->codebooks.data(), ctx->codebooks.size() * sizeof(float), hipMemcpyHostToDevice, st));
+    const float *cb = reinterpret_cast<const float *>(ws);
+    int dsp = 4;
+    while (dsp < ds) dsp <<= 1;
+    const int KC = (int)std::min<int64_t>(K, LDS_BUDGET / (dsp * 4));
+    const size_t lds = (size_t)KC * dsp * 4;
+    dim3 grid((unsigned)((n + 255) / 256), (unsigned)M);
+    ProfScope prof(ctx, ETF_K_ENCODE);
+#define ENC_CASE(DSP)                                                                                     \
+    case DSP: {                                                                                           \
+        int rc2 = set_lds(ctx, k_encode<DSP>, lds);                                                       \
+        if (rc2) return rc2;                                                                              \
+        hipLaunchKernelGGL(k_encode<DSP>, grid, dim3(256), lds, st, x, n, d, ds, K, M, cb, codes_out, KC); \
+        break;                                                                                            \
+    }
+    switch (dsp) {
+        ENC_CASE(4)
+        ENC_CASE(8)
+        ENC_CASE(16)
+        ENC_CASE(32)
+        ENC_CASE(64)
+        ENC_CASE(128)
+        default: return fail(ctx, ETF_EINVAL, "no encoder for %d dimensions per group", ds);
+    }
+#undef ENC_CASE
+    LAUNCH_CHECK(ctx, "k_encode");
+    return ETF_OK;
+}
+
+// =============================================================================================
 // top-k search
 // =============================================================================================
 extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, int mode, int32_t *out_ids,

@@ -437,6 +437,56 @@ __global__ __launch_bounds__(256) void k_leaf_short(const uint8_t *__restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------------
+// PQ encoding on the device (paper, Introduction: every dimension group is quantised separately to its nearest
+//     codeword): codes[i][m] = argmin_c || x[i] group m - codeword c of group m ||^2, lowest c on ties.
+//     Float32, every squared distance the sum of its terms in dimension order with one rounding per
+//     operation (no fused multiply-add), so that a float32 reference can reproduce every decision.
+//     One thread per vector and group, the sub-vector in registers (DSP = ds rounded up to 4, 8, ..., 128,
+//     padded with zeros against zero-padded codewords, which adds exact zeros); the group's codewords in
+//     LDS, KC at a time, read as broadcasts.
+//     grid (ceil(n / 256), M), block 256, dynamic LDS KC*DSP*4 bytes.
+// ------------------------------------------------------------------------------------------------
+template <int DSP>
+__global__ __launch_bounds__(256) void k_encode(const float *__restrict__ x, int64_t n, int d, int ds, int K, int M,
+                                                const float *__restrict__ cb, uint8_t *__restrict__ codes, int KC)
+{
+    extern __shared__ float lds[];  // [KC][DSP]
+    const int m = blockIdx.y;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    float xv[DSP];
+    {
+        const float *xi = x + (i < n ? i : 0) * d + (int64_t)m * ds;
+#pragma unroll
+        for (int j = 0; j < DSP; ++j) xv[j] = (j < ds && i < n) ? xi[j] : 0.f;
+    }
+    float bestd = 3.402823466e+38f;
+    int best = 0;
+    for (int k0 = 0; k0 < K; k0 += KC) {
+        const int kc = min(KC, K - k0);
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < kc * DSP; idx += 256) {
+            const int k = idx / DSP, j = idx % DSP;
+            lds[idx] = j < ds ? cb[((int64_t)m * K + k0 + k) * ds + j] : 0.f;
+        }
+        __syncthreads();
+        for (int k = 0; k < kc; ++k) {
+            const float *c = lds + k * DSP;
+            float s = 0.f;
+#pragma unroll
+            for (int j = 0; j < DSP; ++j) {
+                const float t = __fsub_rn(xv[j], c[j]);
+                s = __fadd_rn(s, __fmul_rn(t, t));
+            }
+            if (s < bestd) {
+                bestd = s;
+                best = k0 + k;
+            }
+        }
+    }
+    if (i < n) codes[i * M + m] = (uint8_t)best;
+}
+
+// ------------------------------------------------------------------------------------------------
 // Consumers of a finished distance.  One distance belongs to (item, query lane).
 // ------------------------------------------------------------------------------------------------
 enum { OUT_ALLPAIRS = 0, OUT_SAMPLE = 1, OUT_FILTER = 2 };
