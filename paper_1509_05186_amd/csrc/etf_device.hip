@@ -210,8 +210,10 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
         int64_t C = ctx->opt.cand_cap;
         if (C == 0) {
             const int64_t expect = (int64_t)(1.3 * (double)k * (double)P.items / (double)std::max<int64_t>(P.S, 1));
+            // the flat scan lists every copy of an encoding at or below the bound
+            const int64_t copies = mode == ETF_MODE_FLAT ? 2 * ix.max_dup : 0;
             C = 4096;
-            while (C < 3 * expect + 2048 && C < (1 << 17)) C <<= 1;
+            while (C < 3 * expect + 2048 + copies && C < (1 << 17)) C <<= 1;
         }
         if (P.items <= C || P.ngroups < k) {  // few enough encodings: every one is a candidate, no bound needed
             P.use_tau = false;
