@@ -133,14 +133,23 @@ def algorithmic_bytes(stats, mode, S, tiles):
     return out
 
 
-def time_search(ctx, qd, k, mode, warmup, steps, torch, ws, out_ids, out_dist):
+def time_search(ctx, qd, k, mode, warmup, steps, torch, ws, out_ids, out_dist, batch=0):
+    """One step = the whole query set; `batch` > 0 sends it in consecutive calls of that many queries (a
+    workload defined with batched queries), all inside the timed region."""
+    Q = qd.shape[0]
+    cuts = [(0, Q)] if not batch or batch >= Q else [(a, min(Q, a + batch)) for a in range(0, Q, batch)]
+
+    def step():
+        for a, b in cuts:
+            ctx.search(qd[a:b], k, mode, out_ids[a:b], out_dist[a:b], ws)
+
     for _ in range(warmup):
-        ctx.search(qd, k, mode, out_ids, out_dist, ws)
+        step()
     torch.cuda.synchronize()
     ctx.profile_read()
     t0 = time.perf_counter()
     for _ in range(steps):
-        ctx.search(qd, k, mode, out_ids, out_dist, ws)
+        step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     return dt, ctx.profile_read()
@@ -208,7 +217,7 @@ def main():
         stats = forest.index_stats()
         ws = forest.alloc_workspace(Q, k, mode)
         log("traversal %s: workspace %.2f GB" % (TRAVERSAL_NAMES[traversal], ws.numel() / 1e9))
-        dt, prof = time_search(forest, qd, k, mode, warmup, steps, torch, ws, out_ids, out_dist)
+        dt, prof = time_search(forest, qd, k, mode, warmup, steps, torch, ws, out_ids, out_dist, cfg.query_batch)
         ms_step = dt / steps * 1e3
         value = N * Q * steps / dt
         fallbacks = forest.last_fallback_count()
@@ -290,13 +299,38 @@ def main():
         tree = make_ctx(1)
         for name, ctx, m in (("flat_gpu", tree, etf.ETF_MODE_FLAT), ("e_tree_gpu", tree, etf.ETF_MODE_TREE)):
             w2 = ctx.alloc_workspace(Q, k, m)
-            d2, p2 = time_search(ctx, qd, k, m, 1, osteps, torch, w2, out_ids, out_dist)
+            d2, p2 = time_search(ctx, qd, k, m, 1, osteps, torch, w2, out_ids, out_dist, cfg.query_batch)
             others[name] = {"value": N * Q * osteps / d2, "ms_per_step": d2 / osteps * 1e3,
                             "kernels_ms_per_step": {n: v[0] / osteps for n, v in p2.items() if v[1]}}
             log("%s: %.2f ms/step, %.3e distances/s" % (name, others[name]["ms_per_step"], others[name]["value"]))
             del w2
         others["e_tree_stats"] = tree.index_stats()["trees"]
         del tree
+        if cfg.name == "cfg2" and not (args.scale_n or args.scale_q):
+            # the all-pairs output row of the path: configuration 1 (single E-Tree, every distance written in
+            # input order), its own inputs
+            c1 = get_config("cfg1")
+            cb1, codes1, q1, _ = make_inputs(c1, etf, torch)
+            t1 = etf.Context(device=0, stream=stream)
+            t1.pq_set_codebooks(cb1)
+            t1.index_build(codes1, T=1)
+            t1.index_upload()
+            q1d = torch.from_numpy(q1).cuda()
+            dist1 = torch.empty((q1.shape[0], codes1.shape[0]), dtype=torch.float32, device="cuda")
+            w1 = t1.alloc_workspace(q1.shape[0], 0, etf.ETF_MODE_TREE)
+            for _ in range(3):
+                t1.adc(q1d, etf.ETF_MODE_TREE, dist1, w1)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(20):
+                t1.adc(q1d, etf.ETF_MODE_TREE, dist1, w1)
+            torch.cuda.synchronize()
+            ms1 = (time.perf_counter() - t0) / 20 * 1e3
+            nd1 = codes1.shape[0] * q1.shape[0]
+            others["all_pairs_cfg1"] = {"ms_per_step": ms1, "value": nd1 / (ms1 / 1e3), "output_GBps": nd1 * 4 / 1e9 / (ms1 / 1e3),
+                                        "workload": "cfg1: N=%d Q=%d, single E-Tree, all pairs in input order" % (codes1.shape[0], q1.shape[0])}
+            log("all pairs (cfg1): %.3f ms/step, %.3e distances/s, %.0f GB/s of output" % (ms1, others["all_pairs_cfg1"]["value"], others["all_pairs_cfg1"]["output_GBps"]))
+            del t1, dist1, w1
 
     # ---- CPU oracle on a bounded sample of the same workload, and parity of the timed output on it
     cpu = None
@@ -333,9 +367,12 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: d=%d N=%d Q=%d PQ M=%d K=%d, E-Forest T=%d, top-%d, seeded %d-component Gaussian mixture"
                                % (cfg.name, cfg.d, N, Q, cfg.M, cfg.K, T, k, cfg.components),
-                   "traversal": TRAVERSAL_NAMES[args.traversal],
+                   "traversal": TRAVERSAL_NAMES[args.traversal], "query_batch": cfg.query_batch or Q,
                    "valid": not (args.scale_n or args.scale_q)},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline,
+        # the table-based E-Forest traversal of the same run (per-tree result tables in HBM): the HBM-bandwidth figure
+        "roofline_hbm_traversal": (others.get("e_forest_register_context") or {}).get("roofline"),
+        "cpu_baseline": cpu,
         "kernels": kernels, "others": others, "encode_gpu": encode_info, "fallback_queries": fallbacks, "device_copy": copy,
         "index": {"n_distinct": stats["n_distinct"], "max_dup": stats["max_dup"], "device_MB": stats["device_bytes"] / 1e6,
                   "trees": stats["trees"], "sample": int(S)},
