@@ -177,7 +177,7 @@ def test_search_exact_kernel(small, mode, T):
 
 
 @pytest.mark.parametrize("trav", TRAVERSALS)
-@pytest.mark.parametrize("mode,T", [(FLAT, 1), (TREE, 1), (FOREST, 2)])
+@pytest.mark.parametrize("mode,T", [(FLAT, 1), (TREE, 1), (FOREST, 2), (FOREST, 4)])
 def test_search_with_duplicates_and_custom_ids(dups, mode, T, trav):
     if mode == FLAT and trav == 1:
         pytest.skip("flat mode has no tree traversal")
@@ -251,3 +251,29 @@ def test_device_error_paths(small):
     c2.index_build(small.codes)
     assert lib.etf_search(c2._h, q.data_ptr(), small.Q, 10, FLAT, oi.data_ptr(), od.data_ptr(), p, n) == -2  # no upload
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("seed", [101, 102, 103, 104, 105, 106])
+def test_search_random_shapes_all_traversals_agree(seed):
+    """Random shapes around the limits of the LDS-resident kernel (M in {4, 8, 16}, T in {1, 2, 4}, any K): every
+    traversal returns the same float32 lists, and they match the oracle."""
+    rng = np.random.default_rng(seed)
+    M = int(rng.choice([4, 8, 16]))
+    T = int(rng.choice([t for t in (1, 2, 4) if t <= M]))
+    K = int(rng.choice([2, 5, 16, 64, 200, 256]))
+    ds = int(rng.choice([1, 2, 3]))
+    N = int(rng.integers(300, 9000))
+    Q = int(rng.integers(1, 140))
+    k = int(rng.integers(1, min(N, 120)))
+    dup = int(rng.choice([1, 1, 4]))
+    say("random shape seed", seed, "M", M, "T", T, "K", K, "ds", ds, "N", N, "Q", Q, "k", k, "dup", dup)
+    p = Problem(d=M * ds, M=M, K=K, N=N - N % dup, Q=Q, ntrain=max(4 * K, 300), seed=seed, iters=2, dup_factor=dup)
+    lists = []
+    for trav in TRAVERSALS:
+        c = p.ctx(T=T, sample_min=256, traversal=trav)
+        oi, od = check_search(p, c, FOREST, k, what="random seed %d trav %d" % (seed, trav))
+        lists.append((oi, od))
+    for oi, od in lists[1:]:
+        assert np.array_equal(lists[0][0], oi) and np.array_equal(lists[0][1], od)
+    c = p.ctx(T=1, sample_min=256)
+    check_search(p, c, FLAT, k, what="random seed %d flat" % seed)
