@@ -170,6 +170,7 @@ def main():
                     help="same as --traversal 1: the level-synchronous traversal (partial sums of internal nodes in HBM)")
     ap.add_argument("--traversal", type=int, default=2, choices=[0, 1, 2],
                     help="2 every table slice in LDS (default), 0 distance context in registers + result tables, 1 level-synchronous")
+    ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE", help="library option for every context (tuning)")
     ap.add_argument("--no-copy", action="store_true", help="skip the 1 GiB device copy (bandwidth ceiling / counter calibration)")
     args = ap.parse_args()
     if args.levels:
@@ -199,6 +200,9 @@ def main():
     def make_ctx(T, traversal=None):
         c = etf.Context(device=0, stream=stream)
         c.set_option("traversal", args.traversal if traversal is None else traversal)
+        for nv in args.opt:
+            name, val = nv.split("=")
+            c.set_option(name, int(val))
         c.pq_set_codebooks(cb)
         t0 = time.time()
         c.index_build(codes, T=T)

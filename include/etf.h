@@ -94,7 +94,9 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     processes queries in batches to stay below it)
  *   "force_fallback"  1: etf_search answers every query with the exact
  *                     whole-database selection kernel (testing)
- *   "sample_min" / "sample_div"   threshold-sample size = max(sample_min, n/sample_div)
+ *   "sample_min" / "sample_scale"   size of the sample that bounds the k-th distance (drawn by
+ *                     etf_index_build): max(sample_min, sample_scale * sqrt(n)), n = number of distinct
+ *                     encodings (of vectors in flat mode); defaults 32768 and 60
  *   "cand_cap"        per-query candidate capacity (0 = derived from k)
  *   "lut_kernel"      0 (default): lookup tables on the matrix cores, as ||q'||^2 - 2 q'.c' + ||c'||^2
  *                     on vectors shifted by the group's mean codeword; entries below a quarter of
@@ -160,6 +162,7 @@ int etf_index_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes);
  *   ecodes      u8  [n_distinct][M]  distinct encodings in lexicographic order
  *   sample_enc  u32 [n_sample_enc]   distinct encodings used to bound the k-th distance (random order)
  *   sample_pos  u32 [n_sample_pos]   input positions used for the same purpose in flat mode
+ *   sample_enc_codes / sample_pos_codes  u8 [n_sample_*][M]  the encodings of those samples, in sample order
  *   leaf_of[t]  u32 [n_distinct] leaf (row of tree t's result table) of every distinct
  *                                encoding; absent when T = 1 (the identity)
  *   rec0 / trec[t]   the sorted distinct (sub-)encodings again as records of 4, 8 or 16 bytes:
@@ -188,6 +191,8 @@ typedef struct etf_layout {
     int64_t cb_centered;           /* float [M][K][cb_row]: codewords minus their group's mean codeword, zero padded */
     int64_t cb_norm;               /* float [M][K]: squared norms of those                                            */
     int64_t cb_mean;               /* float [M][d/M]: the mean codeword of every group                                */
+    int64_t sample_enc_codes;      /* u8 [n_sample_enc][M]: ecodes rows of sample_enc, in sample order               */
+    int64_t sample_pos_codes;      /* u8 [n_sample_pos][M]: codes rows of sample_pos, in sample order                */
     int32_t cb_row;
 } etf_layout;
 int etf_index_layout(const etf_ctx *ctx, etf_layout *out);

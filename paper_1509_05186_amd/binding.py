@@ -73,6 +73,7 @@ class EtfLayout(ctypes.Structure):
         ("rec0", ctypes.c_int64), ("rec0_stride", ctypes.c_int32),
         ("trec", ctypes.c_int64 * ETF_MAX_M), ("trec_stride", ctypes.c_int32 * ETF_MAX_M),
         ("cb_centered", ctypes.c_int64), ("cb_norm", ctypes.c_int64), ("cb_mean", ctypes.c_int64),
+        ("sample_enc_codes", ctypes.c_int64), ("sample_pos_codes", ctypes.c_int64),
         ("cb_row", ctypes.c_int32),
     ]
 

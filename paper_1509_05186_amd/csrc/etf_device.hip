@@ -201,9 +201,13 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     P.items = mode == ETF_MODE_FLAT ? ix.N : ix.Nd;
     P.S = mode == ETF_MODE_FLAT ? (int64_t)ix.sample_pos.size() : (int64_t)ix.sample_enc.size();
     if (search) {
-        // The sample is cut into about 2.5 k groups; the bound is the k-th smallest group minimum, which
-        // lets through about 1.3 k items/S candidates per query.
-        int64_t groups = 256;
+        // The sample is cut into at least 1024 (256) and at least 2.5 k groups; the bound is the k-th smallest group
+        // minimum, which lets through 1.05 to 1.3 times k items/S candidates per query (the more groups, the
+        // closer the bound is to the k-th smallest sample; small groups also spread the sample pass over more waves).
+        // (The table-based kernels take one group per wave: they keep 256.)
+        const bool lds_kernels = mode == ETF_MODE_FLAT ? lds_eligible(M, K, 1, nullptr)
+                                                       : (ctx->opt.traversal == 2 && lds_eligible(M, K, ix.T, ix.chunk_begin.data()));
+        int64_t groups = lds_kernels ? 1024 : 256;
         while (groups < (int64_t)(2.5 * k) && groups < 4096) groups <<= 1;
         P.gsize = (int)std::max<int64_t>(1, P.S / groups);
         P.ngroups = (P.S + P.gsize - 1) / P.gsize;
@@ -610,7 +614,8 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
     int64_t bx;
     int per_block = 0;
     if (MODE == OUT_SAMPLE) {
-        bx = blocks_for(o.ngroups, 16 * IPS, tiles * G);
+        // every workgroup stages the whole table set: give each lane group at least two sample groups
+        bx = blocks_for(o.ngroups, 2 * 16 * IPS, tiles * G);
     } else {
         // item numbers inside a workgroup's share travel in 26 bits
         bx = std::max(blocks_for(nitems, 16384, tiles * G), (nitems >> 25) + 1);
@@ -656,9 +661,12 @@ int launch_flat(etf_ctx *ctx, const Plan &P, char *ws, int64_t nitems, const uin
     const uint8_t *codes = reinterpret_cast<const uint8_t *>(ctx->dev_base + ctx->lay.codes);
     const float *lutT = reinterpret_cast<const float *>(ws + P.o_lutT);
     if constexpr (MODE != OUT_ALLPAIRS)
-        if (lds_eligible(M, K, 1, nullptr))
-            return launch_lds<MODE, false>(ctx, P, ws, reinterpret_cast<const uint32_t *>(codes), nitems, sample, 1, tiles, o,
-                                       MODE == OUT_SAMPLE ? ETF_K_SAMPLE : ETF_K_FLAT);
+        if (lds_eligible(M, K, 1, nullptr)) {
+            // the sample's codes are stored side by side in sample order: no indirection
+            const uint8_t *rec = MODE == OUT_SAMPLE ? reinterpret_cast<const uint8_t *>(ctx->dev_base + ctx->lay.sample_pos_codes) : codes;
+            return launch_lds<MODE, false>(ctx, P, ws, reinterpret_cast<const uint32_t *>(rec), nitems, nullptr, 1, tiles, o,
+                                           MODE == OUT_SAMPLE ? ETF_K_SAMPLE : ETF_K_FLAT);
+        }
     ProfScope prof(ctx, MODE == OUT_SAMPLE ? ETF_K_SAMPLE : ETF_K_FLAT);
 #define FLAT_CASE(GG)                                                                                     \
     case GG: {                                                                                               \
@@ -887,8 +895,8 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
                 if (flat)
                     rc = launch_flat<OUT_SAMPLE>(ctx, P, w, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_pos), tiles, o);
                 else if (P.lds_path)
-                    rc = launch_lds<OUT_SAMPLE, false>(ctx, P, w, ecodes, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_enc),
-                                                       ix.T, tiles, o, ETF_K_SAMPLE);
+                    rc = launch_lds<OUT_SAMPLE, false>(ctx, P, w, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_enc_codes), P.S,
+                                                       nullptr, ix.T, tiles, o, ETF_K_SAMPLE);
                 else
                     rc = P.ctx_path ? launch_fused<OUT_SAMPLE>(ctx, P, w, r, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_enc), tiles, o)
                                     : launch_reduce<OUT_SAMPLE>(ctx, r, P.S, reinterpret_cast<const uint32_t *>(ctx->dev_base + L.sample_enc), tiles, o);

@@ -61,6 +61,8 @@ struct HostIndex {
     std::vector<uint8_t> ecodes;            // [Nd][M] distinct encodings in sorted order
     std::vector<uint32_t> sample_enc;       // sorted distinct-encoding numbers of the threshold sample
     std::vector<uint32_t> sample_pos;       // input positions of the flat-mode threshold sample
+    std::vector<uint8_t> sample_enc_codes;  // [n_sample_enc][M] the sampled encodings themselves, in sample order
+    std::vector<uint8_t> sample_pos_codes;  // [n_sample_pos][M] likewise for the flat-mode sample
     int rstride0 = 0;
     std::vector<uint8_t> rec0;              // [Nd][rstride0] tree 0's chunks of every distinct encoding, zero padded
     std::vector<HostTree> tree;
@@ -77,7 +79,8 @@ struct DevTreeLayout {
 struct DevLayout {
     int64_t total = 0;
     int64_t codebooks = 0, codes = 0, ids_in = 0, ids_sorted = 0, ebegin = 0, enc_of_pos = 0, ecodes = 0,
-            sample_enc = 0, sample_pos = 0, rec0 = 0, cb_centered = 0, cb_norm = 0, cb_mean = 0;
+            sample_enc = 0, sample_pos = 0, rec0 = 0, cb_centered = 0, cb_norm = 0, cb_mean = 0, sample_enc_codes = 0,
+            sample_pos_codes = 0;
     std::vector<DevTreeLayout> tree;
 };
 
@@ -85,7 +88,7 @@ struct Options {
     int64_t ws_cap_bytes = (int64_t)8 << 30;
     int64_t force_fallback = 0;
     int64_t sample_min = 32768;
-    int64_t sample_div = 32;
+    int64_t sample_scale = 60;  // sample size = max(sample_min, sample_scale * sqrt(n))
     int64_t cand_cap = 0;
     int64_t traversal = 2;  // 0: distance context in registers, 1: level-synchronous kernels, 2: searches with all tables in LDS
     int64_t lut_kernel = 0; // 0: matrix cores (expanded form on centred vectors, small entries recomputed), 1: plain (a-b)^2 sums

@@ -596,7 +596,8 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
 //     Candidates at or below the bound go to a ring of the wave in LDS (slot = rank among the passing
 //     lanes) and are appended to the queries' lists by the whole wave when the ring is nearly full: one
 //     global reservation per query, then LDS atomics hand out the slots.
-//     OUT_SAMPLE: items map[i]; every lane group owns whole sample groups and keeps their minima.
+//     OUT_SAMPLE: items map[i] (or i itself without a map: the sample's records stored side by side); every
+//     lane group owns whole sample groups and keeps their minima.
 //     rec [n][M4] dwords: the codes of an item, chunk 0 in the lowest byte.
 //     grid (blocks, G, tiles), block 1024, dynamic LDS M*K*Qs*4 bytes; per_block < 2^26.
 // ------------------------------------------------------------------------------------------------
@@ -678,7 +679,7 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
                 for (int u = 0; u < U; ++u) {
                     const int64_t idx = g * o.gsize + jj + u;
                     live[u] = glive && jj + u < o.gsize && idx < nitems;
-                    const int64_t e = live[u] ? (int64_t)map[idx] : 0;
+                    const int64_t e = live[u] ? (map ? (int64_t)map[idx] : idx) : 0;
 #pragma unroll
                     for (int i = 0; i < M4; ++i) dw[u][i] = rec[e * M4 + i];
                 }

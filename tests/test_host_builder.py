@@ -191,6 +191,10 @@ def test_builder_ids_and_ranges():
     se = arr(buf, lay.sample_enc, lay.n_sample_enc, np.uint32)
     sp = arr(buf, lay.sample_pos, lay.n_sample_pos, np.uint32)
     assert sorted(se.tolist()) == list(range(Nd)) and sorted(sp.tolist()) == list(range(N))
+    # and their encodings are stored once more side by side, in sample order
+    sec = arr(buf, lay.sample_enc_codes, lay.n_sample_enc * M, np.uint8).reshape(-1, M)
+    spc = arr(buf, lay.sample_pos_codes, lay.n_sample_pos * M, np.uint8).reshape(-1, M)
+    assert np.array_equal(sec, ecodes[se]) and np.array_equal(spc, codes[sp])
 
 
 def test_builder_sampling_on_larger_input():
@@ -204,8 +208,9 @@ def test_builder_sampling_on_larger_input():
     st, lay, buf = c.index_stats(), c.index_layout(), c.index_export()
     se = arr(buf, lay.sample_enc, lay.n_sample_enc, np.uint32)
     sp = arr(buf, lay.sample_pos, lay.n_sample_pos, np.uint32)
-    assert 0.9 * st["n_distinct"] / 32 <= len(se) <= st["n_distinct"] / 32 + 1 and se.max() < st["n_distinct"]
-    assert 0.9 * N / 32 <= len(sp) <= N / 32 + 1 and sp.max() < N
+    want_e, want_p = 60 * np.sqrt(st["n_distinct"]), 60 * np.sqrt(N)         # sample_scale * sqrt(n), duplicates of the draw removed
+    assert 0.9 * want_e <= len(se) <= want_e + 1 and se.max() < st["n_distinct"]
+    assert 0.9 * want_p <= len(sp) <= want_p + 1 and sp.max() < N
     assert len(np.unique(se)) == len(se) and len(np.unique(sp)) == len(sp)
     assert not np.all(np.diff(se.astype(np.int64)) > 0)       # stored in random order
     lut = rng.random((M, K))
