@@ -107,10 +107,10 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     result tables in device memory for trees 1 .. T-1;
  *                     1: level-synchronous kernels over the level arrays (partial sums of internal
  *                     nodes in device memory);
- *                     2 (default): searches keep every table slice of a group of queries in LDS and
- *                     walk the sorted encodings with a short distance context per lane group, no
- *                     result tables at all (built for M in {4, 8, 16} and 1, 2 or 4 equal trees);
- *                     every other shape, and etf_adc, runs as 0.
+ *                     2 (default): every table slice of a group of queries is kept in LDS; searches
+ *                     walk the sorted encodings with a short distance context per lane group,
+ *                     etf_adc evaluates the input positions in order; no result tables at all (built
+ *                     for M in {4, 8, 16} and 1, 2 or 4 equal trees); every other shape runs as 0.
  *                     All three add the same float32 values in the same order.
  * Returns ETF_EINVAL for an unknown name or a value out of range. */
 int etf_set_option(etf_ctx *ctx, const char *name, int64_t value);

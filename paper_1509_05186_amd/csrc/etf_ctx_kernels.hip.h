@@ -49,8 +49,8 @@ __device__ __forceinline__ int common_prefix(const uint32_t a[NDW], const uint32
 // the deepest level is always slot DT-1.  That makes the split below a compile-time one: the table slices
 // of the NL deepest levels (where almost all lookups of a tree fall: own chunks and postfixes of the
 // leaves) are staged in LDS, the lookups of the levels above read the transposed tables in global memory
-// (L2).  NL = 2 where LDS has nothing else to hold, 1 next to the candidate staging buffer, 0 next to the
-// transpose buffer of the all-pairs output.
+// (L2).  NL = 2 (128 KB, next to the candidate ring) except for the all-pairs output, whose transpose
+// buffer takes the room: NL = 0 there.
 
 // copies the NL deepest slices of a tree (chunks m0+D-NL .. m0+D-1, adjacent rows of lutT) into LDS
 template <int NL>

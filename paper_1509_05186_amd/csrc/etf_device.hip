@@ -231,7 +231,7 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     int64_t per_tile = (int64_t)M * K * QT * 4;
     // traversal 2 = every table slice in LDS, for searches on the shapes that kernel is built for; otherwise
     // it means the register-context kernels, like traversal 0
-    P.lds_path = search && mode != ETF_MODE_FLAT && ctx->opt.traversal == 2 && lds_eligible(M, K, ix.T, ix.chunk_begin.data());
+    P.lds_path = mode != ETF_MODE_FLAT && ctx->opt.traversal == 2 && lds_eligible(M, K, ix.T, ix.chunk_begin.data());
     P.ctx_path = !P.lds_path && tmax_class(ix.T) != 0 && mode != ETF_MODE_FLAT && ctx->opt.traversal != 1;
     for (int t = 1; t < ix.T; ++t)  // the register-context kernels address a tree's result table with 32-bit offsets
         if (ix.tree[t].U >= ((int64_t)1 << 24)) P.ctx_path = false;
@@ -627,7 +627,7 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
     ProfScope prof(ctx, cls);
     bool done = false;
 #define LDS_CASE(GG, MM4, TT)                                                                                  \
-    if constexpr (CTX || MODE == OUT_SAMPLE || TT == 1) {                                                      \
+    if constexpr (CTX || MODE != OUT_FILTER || TT == 1) {                                                      \
         if (!done && G == GG && M == 4 * MM4 && T == TT) {                                                     \
             int rc = set_lds(ctx, k_lds<GG, MM4, TT, MODE, CTX>, lds);                                         \
             if (rc) return rc;                                                                                 \
@@ -756,8 +756,16 @@ extern "C" int etf_adc(etf_ctx *ctx, const float *queries, int64_t Q, int mode, 
         o.dist = dist + q0 * ix.N;
         o.N = ix.N;
         o.nq = std::min<int64_t>(tiles * QT, Q - q0);
-        if (mode == ETF_MODE_FLAT) {
+        const uint32_t *codes_in = reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.codes);
+        if (mode == ETF_MODE_FLAT && lds_eligible(ix.M, ix.K, 1, nullptr)) {
+            rc = launch_lds<OUT_ALLPAIRS, false>(ctx, P, w, codes_in, ix.N, nullptr, 1, tiles, o, ETF_K_FLAT);
+            if (rc) return rc;
+        } else if (mode == ETF_MODE_FLAT) {
             rc = launch_flat<OUT_ALLPAIRS>(ctx, P, w, ix.N, nullptr, tiles, o);
+            if (rc) return rc;
+        } else if (P.lds_path) {
+            // every distance in input order: the sums of the trees, chunk by chunk from LDS
+            rc = launch_lds<OUT_ALLPAIRS, false>(ctx, P, w, codes_in, ix.N, nullptr, ix.T, tiles, o, ETF_K_LDS);
             if (rc) return rc;
         } else {
             const uint32_t *enc_of_pos = reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.enc_of_pos);

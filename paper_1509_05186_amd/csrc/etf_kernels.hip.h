@@ -598,6 +598,8 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
 //     global reservation per query, then LDS atomics hand out the slots.
 //     OUT_SAMPLE: items map[i] (or i itself without a map: the sample's records stored side by side); every
 //     lane group owns whole sample groups and keeps their minima.
+//     OUT_ALLPAIRS: items are input positions (rec = the codes in input order, no context); dist[q][n] written
+//     as 64-byte pieces (16 consecutive n of one query per wave step).
 //     rec [n][M4] dwords: the codes of an item, chunk 0 in the lowest byte.
 //     grid (blocks, G, tiles), block 1024, dynamic LDS M*K*Qs*4 bytes; per_block < 2^26.
 // ------------------------------------------------------------------------------------------------
@@ -697,6 +699,36 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
                 float *dst = o.gmin + ((int64_t)tile * o.ngroups + g) * QT + col;
 #pragma unroll
                 for (int v = 0; v < V; ++v) dst[v] = best[v];
+            }
+        }
+        return;
+    }
+
+    if (MODE == OUT_ALLPAIRS) {
+        // items are the N input positions, U * IPS consecutive ones per wave and round: for one query the lane
+        // groups of a step write IPS consecutive floats of its row, the U steps adjacent pieces of it
+        // (the workgroups of a sub-tile take turns along the rows, so that what is written at any time is close)
+        const int64_t bhi = nitems;
+        for (int64_t j0 = ((int64_t)blockIdx.x * nw + w) * (IPS * U); j0 < bhi; j0 += (int64_t)gridDim.x * nw * (IPS * U)) {
+            uint32_t dw[U][M4];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t j = min(j0 + u * IPS + lg, nitems - 1);
+#pragma unroll
+                for (int k2 = 0; k2 < M4; ++k2) dw[u][k2] = rec[j * M4 + k2];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t j = j0 + u * IPS + lg;
+                vecq top = 0.f;
+                const vecq d = sum_of(dw[u], false, top);
+                if (j < bhi) {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        const int64_t ql = (int64_t)tile * QT + col + v;
+                        if (ql < o.nq) __builtin_nontemporal_store(d[v], &o.dist[ql * o.N + j]);  // written once, never read here
+                    }
+                }
             }
         }
         return;

@@ -88,7 +88,7 @@ def test_lut_kernels_on_wide_subspaces():
 
 
 TRAVERSALS = [0, 1, 2]   # 0: distance context in registers, 1: level-synchronous kernels, 2: searches with all tables in LDS
-ADC_TRAVERSALS = [0, 1]  # all-pairs output has no LDS-resident variant (2 runs as 0 there)
+ADC_TRAVERSALS = TRAVERSALS
 
 
 @pytest.mark.parametrize("trav", ADC_TRAVERSALS)
