@@ -943,6 +943,7 @@ __global__ __launch_bounds__(1024) void k_tau(const float *__restrict__ gmin, in
 {
     __shared__ uint32_t hist[256][64];
     __shared__ uint32_t s_prefix[64], s_rank[64];
+    __shared__ uint32_t s_part[16][64];
     const int tile = blockIdx.x;
     const int lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6), nw = blockDim.x >> 6;
     const int64_t ql = (int64_t)tile * QT + lane;
@@ -966,16 +967,29 @@ __global__ __launch_bounds__(1024) void k_tau(const float *__restrict__ gmin, in
             if (match) atomicAdd(&hist[(v >> shift) & 255][lane], 1u);
         }
         __syncthreads();
-        if (threadIdx.x < 64) {
-            uint32_t rank = s_rank[lane], below = 0;
-            int b = 0;
-            for (; b < 255; ++b) {
-                const uint32_t h = hist[b][lane];
-                if (below + h >= rank) break;
-                below += h;
+        // the bin in which the running count of a query reaches its rank: wave w sums bins 16w .. 16w+15 of
+        // every query, then the wave whose stretch holds the crossing walks its 16 bins (blockDim.x = 1024)
+        {
+            uint32_t part = 0;
+#pragma unroll
+            for (int b = 0; b < 16; ++b) part += hist[w * 16 + b][lane];
+            s_part[w][lane] = part;
+            __syncthreads();
+            uint32_t below = 0;
+            for (int w2 = 0; w2 < w; ++w2) below += s_part[w2][lane];
+            const uint32_t rank = s_rank[lane];
+            const bool last = w == nw - 1;
+            __syncthreads();
+            if (below < rank && (rank <= below + part || last)) {
+                int b = w * 16;
+                for (; b < w * 16 + 15; ++b) {
+                    const uint32_t h = hist[b][lane];
+                    if (below + h >= rank) break;
+                    below += h;
+                }
+                s_prefix[lane] = prefix | ((uint32_t)b << shift);
+                s_rank[lane] = rank - below;
             }
-            s_prefix[lane] = prefix | ((uint32_t)b << shift);
-            s_rank[lane] = rank - below;
         }
         __syncthreads();
     }
