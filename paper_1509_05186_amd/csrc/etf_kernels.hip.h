@@ -226,7 +226,8 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
         const float *x = queries + (live ? q : 0) * d + (int64_t)m * ds;
         const float *c = cb + ((int64_t)m * K + k) * ds;
         float sum = 0.f;
-        for (int j = 0; j < ds; ++j) {
+#pragma unroll 8
+        for (int j = 0; j < ds; ++j) {  // unrolled so that the loads of several terms are in flight together
             const float t = (live ? x[j] : 0.f) - c[j];
             sum = fmaf(t, t, sum);
         }
