@@ -174,6 +174,7 @@ struct Plan {
     bool use_tau = false;
     bool ctx_path = false;    // trees walked with the distance context in registers (no partial-sum tables)
     bool lds_path = false;    // search with every table slice in LDS: no result tables at all
+    bool flat_lds = false;    // flat mode through the same kernels
     int64_t o_counter = 0, o_lutT = 0, o_gmin = 0, o_tau = 0, o_cnt = 0, o_flag = 0, o_cand = 0;
     int64_t o_part[ETF_MAX_M][ETF_MAX_M];
     int64_t o_leafp[ETF_MAX_M];
@@ -205,8 +206,8 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
         // minimum, which lets through 1.05 to 1.3 times k items/S candidates per query (the more groups, the
         // closer the bound is to the k-th smallest sample; small groups also spread the sample pass over more waves).
         // (The table-based kernels take one group per wave: they keep 256.)
-        const bool lds_kernels = mode == ETF_MODE_FLAT ? lds_eligible(M, K, 1, nullptr)
-                                                       : (ctx->opt.traversal == 2 && lds_eligible(M, K, ix.T, ix.chunk_begin.data()));
+        const bool lds_kernels = ctx->opt.traversal == 2 &&
+                                 (mode == ETF_MODE_FLAT ? lds_eligible(M, K, 1, nullptr) : lds_eligible(M, K, ix.T, ix.chunk_begin.data()));
         int64_t groups = lds_kernels ? 1024 : 256;
         while (groups < (int64_t)(2.5 * k) && groups < 4096) groups <<= 1;
         P.gsize = (int)std::max<int64_t>(1, P.S / groups);
@@ -232,6 +233,7 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     // traversal 2 = every table slice in LDS, for searches on the shapes that kernel is built for; otherwise
     // it means the register-context kernels, like traversal 0
     P.lds_path = mode != ETF_MODE_FLAT && ctx->opt.traversal == 2 && lds_eligible(M, K, ix.T, ix.chunk_begin.data());
+    P.flat_lds = mode == ETF_MODE_FLAT && ctx->opt.traversal == 2 && lds_eligible(M, K, 1, nullptr);
     P.ctx_path = !P.lds_path && tmax_class(ix.T) != 0 && mode != ETF_MODE_FLAT && ctx->opt.traversal != 1;
     for (int t = 1; t < ix.T; ++t)  // the register-context kernels address a tree's result table with 32-bit offsets
         if (ix.tree[t].U >= ((int64_t)1 << 24)) P.ctx_path = false;
@@ -661,7 +663,7 @@ int launch_flat(etf_ctx *ctx, const Plan &P, char *ws, int64_t nitems, const uin
     const uint8_t *codes = reinterpret_cast<const uint8_t *>(ctx->dev_base + ctx->lay.codes);
     const float *lutT = reinterpret_cast<const float *>(ws + P.o_lutT);
     if constexpr (MODE != OUT_ALLPAIRS)
-        if (lds_eligible(M, K, 1, nullptr)) {
+        if (P.flat_lds) {
             // the sample's codes are stored side by side in sample order: no indirection
             const uint8_t *rec = MODE == OUT_SAMPLE ? reinterpret_cast<const uint8_t *>(ctx->dev_base + ctx->lay.sample_pos_codes) : codes;
             return launch_lds<MODE, false>(ctx, P, ws, reinterpret_cast<const uint32_t *>(rec), nitems, nullptr, 1, tiles, o,
@@ -757,7 +759,7 @@ extern "C" int etf_adc(etf_ctx *ctx, const float *queries, int64_t Q, int mode, 
         o.N = ix.N;
         o.nq = std::min<int64_t>(tiles * QT, Q - q0);
         const uint32_t *codes_in = reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.codes);
-        if (mode == ETF_MODE_FLAT && lds_eligible(ix.M, ix.K, 1, nullptr)) {
+        if (P.flat_lds) {
             rc = launch_lds<OUT_ALLPAIRS, false>(ctx, P, w, codes_in, ix.N, nullptr, 1, tiles, o, ETF_K_FLAT);
             if (rc) return rc;
         } else if (mode == ETF_MODE_FLAT) {
@@ -949,6 +951,7 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
         ea.lutT = lutT;
         ea.M = ix.M;
         ea.K = ix.K;
+        ea.grouped = (P.lds_path || P.flat_lds) ? 1 : 0;
         if (flat) {
             ea.T = 1;
             ea.chunk_begin[0] = 0;

@@ -607,34 +607,59 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
 constexpr int LDS_V = 4;  // queries per lane (one 16-byte LDS read per lookup)
 typedef float vecq __attribute__((ext_vector_type(LDS_V)));
 
-// FROM = 0: every chunk is looked up and `top` (the sum over the first S chunks) is refreshed;
-// FROM = S > 0: `top` is reused.  look(m) returns the lane's queries' entries of chunk m.
-template <int M4, int T, int S, int FROM, class Look>
-__device__ __forceinline__ vecq lds_item_sum(Look look, vecq &top)
+// Sum of one item.  The chunks are taken in groups of four, a group as (x0 + x1) + (x2 + x3), where x0 .. x3
+// are the group's four entries in the order the lane read them.  That order differs from lane group to lane
+// group (see k_lds), but only by permutations that swap the members of a pair and/or the two pairs, and
+// float addition is commutative: every lane forms exactly (c0 + c1) + (c2 + c3).  A tree's sum is the sum of its
+// groups in order (a tree of fewer than four chunks lives inside one group), the trees are added in order.
+// CTX: `top` is the first pair of group 0, c0 + c1; with fast it is reused instead of read.
+template <int M4, int T, bool CTX, class Look>
+__device__ __forceinline__ vecq lds_item_sum(Look look, bool fast, vecq &top)
 {
-    constexpr int M = 4 * M4, D = M / T;
-    vecq s = 0.f, d = 0.f;
-    if (S > 0) {
-        if (FROM == 0) {
-            s = look(0);
+    constexpr int D = 4 * M4 / T;
+    constexpr int GPT = D >= 4 ? D / 4 : 1;  // groups per tree
+    vecq P[M4];
 #pragma unroll
-            for (int m = 1; m < S; ++m) s += look(m);
-            top = s;
+    for (int g = 0; g < M4; ++g) {
+        vecq a;
+        if (CTX && g == 0) {
+            if (fast) {
+                a = top;
+            } else {
+                a = look(g, 0) + look(g, 1);
+                top = a;
+            }
         } else {
-            s = top;
+            a = look(g, 0) + look(g, 1);
         }
+        P[g] = a + (look(g, 2) + look(g, 3));
     }
+    vecq d = 0.f;
 #pragma unroll
-    for (int m = S; m < M; ++m) {
-        const vecq x = look(m);
-        if (m % D == 0) {
-            if (m > 0) d = (m == D) ? s : d + s;
-            s = x;
-        } else {
-            s += x;
-        }
+    for (int t0 = 0; t0 < M4; t0 += GPT) {
+        vecq s = P[t0];
+#pragma unroll
+        for (int i = 1; i < GPT; ++i) s += P[t0 + i];
+        d = t0 == 0 ? s : d + s;
     }
-    return T == 1 ? s : d + s;
+    return d;
+}
+
+// Stages all M slices of sub-tile g as lines: the four rows (m = 4i .. 4i+3, same codeword number) of a chunk
+// group side by side, [M/4][K][4][Qs].  A row of Qs = 16 queries is 64 bytes, a line 256 bytes = all LDS banks,
+// so the row of chunk m always sits in bank quarter m % 4, whatever the codeword.
+template <int G>
+__device__ __forceinline__ void stage_lines(float *lds, const float *__restrict__ lutT, int tile, int g, int M, int K)
+{
+    constexpr int Qs = WAVE / G;
+    const int total = M * K * Qs;
+    const float *src = lutT + (int64_t)tile * M * K * QT + g * Qs;
+    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+        const int row = idx / Qs, qq = idx % Qs;  // row = m * K + k
+        const int m = row / K, k = row - m * K;
+        lds[((((m >> 2) * K + k) << 2) + (m & 3)) * Qs + qq] = src[(int64_t)row * QT + qq];
+    }
+    __syncthreads();
 }
 
 template <int G, int M4, int T, int MODE, bool CTX>
@@ -642,8 +667,8 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
                                               const uint32_t *__restrict__ map, const float *__restrict__ lutT, int K,
                                               int per_block, OutArgs o)
 {
-    constexpr int Qs = WAVE / G, V = LDS_V, LPI = Qs / V, IPS = WAVE / LPI, M = 4 * M4, D = M / T;
-    constexpr int S = CTX ? (D >= 3 ? 2 : D - 1) : 0;
+    constexpr int Qs = WAVE / G, V = LDS_V, LPI = Qs / V, IPS = WAVE / LPI, M = 4 * M4;
+    constexpr int S = CTX ? 2 : 0;  // chunks kept in the context: the first pair
     constexpr int U = M4 >= 4 ? 2 : 4;
     constexpr int RING = 160;
     constexpr bool FILTER = MODE == OUT_FILTER;
@@ -655,18 +680,37 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     const int lane = threadIdx.x & 63;
     const int w = uniform(threadIdx.x >> 6), nw = blockDim.x >> 6;
     if (FILTER) wcount[w][lane] = 0u;
-    stage_slices<G>(lds, lutT, tile, sub, M, K, 0, M);
+    stage_lines<G>(lds, lutT, tile, sub, M, K);
     const int lg = lane / LPI, lq = lane % LPI;
     const int col = sub * Qs + lq * V;  // first of this lane's queries inside the tile
-    const char *ldsb = reinterpret_cast<const char *>(lds) + lq * (V * 4);
-    const uint32_t rowB = Qs * 4, sliceB = (uint32_t)K * rowB;
+    const uint32_t rowB = Qs * 4, lineB = 4 * rowB;
+    // Which chunk of a group this lane reads t-th: t ^ j with j = the lane group's number mod 4.  The four lane
+    // groups that share a pass of the LDS pipe (16 lanes x 16 bytes) then read four different chunks at any
+    // time, i.e. four different bank quarters: no bank conflicts, whatever the codes.  Group 0 of a walk with
+    // context only swaps inside its pairs (j & 1), so that the first two reads are chunks 0 and 1 in every lane
+    // and can be skipped together.
+    const int j4 = lg & 3;
+    uint32_t sh[2][4];                         // shift of the code byte; [0]: group 0, [1]: the other groups
+    uint32_t pb[M4][4];                        // byte address of row 0 of that chunk for this lane
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int c0 = CTX ? (t ^ (j4 & 1)) : (t ^ j4);
+        const int c1 = t ^ j4;
+        sh[0][t] = 8u * (uint32_t)c0;
+        sh[1][t] = 8u * (uint32_t)c1;
+#pragma unroll
+        for (int g = 0; g < M4; ++g) {
+            const int c = g == 0 ? c0 : c1;
+            pb[g][t] = (uint32_t)(lq * (V * 4)) + (uint32_t)g * (uint32_t)K * lineB + (uint32_t)c * rowB;
+        }
+    }
+    const char *lds0 = reinterpret_cast<const char *>(lds);
     auto sum_of = [&](const uint32_t dw[M4], bool fast, vecq &top) -> vecq {
-        auto look = [&](int m) -> vecq {
-            const uint32_t code = __builtin_amdgcn_ubfe(dw[m >> 2], 8 * (m & 3), 8);
-            return *reinterpret_cast<const vecq *>(ldsb + (uint32_t)m * sliceB + code * rowB);
+        auto look = [&](int g, int t) -> vecq {
+            const uint32_t code = __builtin_amdgcn_ubfe(dw[g], sh[g == 0 ? 0 : 1][t], 8);
+            return *reinterpret_cast<const vecq *>(lds0 + pb[g][t] + code * lineB);
         };
-        if (S > 0 && fast) return lds_item_sum<M4, T, S, S>(look, top);
-        return lds_item_sum<M4, T, S, 0>(look, top);
+        return lds_item_sum<M4, T, CTX>(look, CTX && fast, top);
     };
 
     if (MODE == OUT_SAMPLE) {
@@ -1279,6 +1323,7 @@ struct ExactArgs {
     uint32_t *nflag;          // running count of queries answered here
     const float *lutT;        // [tiles][M][K][64]
     int M, K, T;
+    int grouped;              // 1: sums associated as the LDS-resident kernels do (see exact_distance)
     int32_t chunk_begin[ETF_MAX_M + 1];
     const uint8_t *codes;     // [rows][M]
     int64_t rows;
@@ -1291,6 +1336,23 @@ struct ExactArgs {
 
 __device__ __forceinline__ float exact_distance(const ExactArgs &a, const float *lut, const uint8_t *c)
 {
+    if (a.grouped) {
+        // the association of the LDS-resident kernels: chunks in groups of four as (c0 + c1) + (c2 + c3), a
+        // tree the sum of its groups in order (trees are equal there; shorter ones live inside one group)
+        const int M4 = a.M >> 2, D = a.M / a.T, gpt = D >= 4 ? D >> 2 : 1;
+        float d = 0.f;
+        for (int t0 = 0; t0 < M4; t0 += gpt) {
+            float s = 0.f;
+            for (int i = 0; i < gpt; ++i) {
+                const int m = 4 * (t0 + i);
+                const float P = (lut[m * a.K + c[m]] + lut[(m + 1) * a.K + c[m + 1]]) +
+                                (lut[(m + 2) * a.K + c[m + 2]] + lut[(m + 3) * a.K + c[m + 3]]);
+                s = i == 0 ? P : s + P;
+            }
+            d = t0 == 0 ? s : d + s;
+        }
+        return d;
+    }
     float d = 0.f;
     for (int t = 0; t < a.T; ++t) {
         float s = 0.f;

@@ -110,7 +110,7 @@ def test_tree_equals_flat_bitwise(small, trav):
     a = c.adc(qdev(small), FLAT)
     b = c.adc(qdev(small), TREE)
     torch.cuda.synchronize()
-    assert torch.equal(a, b)       # same left-to-right float32 sum, shared prefixes added once
+    assert torch.equal(a, b)       # the same float32 sum, associated the same way, shared prefixes added once
 
 
 @pytest.mark.parametrize("trav", ADC_TRAVERSALS)
@@ -120,6 +120,22 @@ def test_adc_unequal_groups_and_batches(small, trav):
     dist = c.adc(qdev(small), FOREST)
     torch.cuda.synchronize()
     assert_distances_close(dist.cpu().numpy(), small.ref_all, "adc T=3")
+
+
+def assert_lists_agree(a, b, what):
+    """Two traversals that associate the float32 sums differently (left to right / in pairs): the distance lists
+    agree to rounding, and the id lists wherever the neighbouring distances are not within rounding of each other."""
+    (ai, ad), (bi, bd) = a, b
+    assert np.allclose(ad, bd, rtol=2e-6, atol=0.0), what
+    differ = ai != bi
+    if differ.any():
+        gap_next = np.abs(np.diff(ad, axis=1, append=ad[:, -1:] * 2 + 1))
+        gap_prev = np.abs(np.diff(ad, axis=1, prepend=ad[:, :1] * 0 - 1))
+        near_tie = np.minimum(gap_next, gap_prev) <= 4e-6 * np.abs(ad)
+        last = np.zeros_like(differ)
+        last[:, -1] = True                      # the k-th place can trade with the (k+1)-th, which the list does not show
+        assert (near_tie | last)[differ].all(), what
+        assert differ.mean() < 0.01, what
 
 
 def check_search(p, c, mode, k, ids=None, what=""):
@@ -166,10 +182,10 @@ def test_search_matches_oracle_lists_exactly(small):
 @pytest.mark.parametrize("mode,T", [(FLAT, 1), (TREE, 1), (FOREST, 2)])
 def test_search_exact_kernel(small, mode, T):
     say("search through the exact whole-database kernel, mode", mode)
-    c = small.ctx(T=T, force_fallback=1)
-    a_i, a_d = check_search(small, c, mode, 50, what="exact m%d" % mode)
-    assert c.last_fallback_count() == small.Q
-    for trav in TRAVERSALS:      # the same float32 values whichever way the trees are walked
+    for trav in TRAVERSALS:      # the exact kernel associates the sums as the traversal it stands in for
+        c = small.ctx(T=T, force_fallback=1, traversal=trav)
+        a_i, a_d = check_search(small, c, mode, 50, what="exact m%d" % mode)
+        assert c.last_fallback_count() == small.Q
         c2 = small.ctx(T=T, sample_min=2048, traversal=trav)
         b_i, b_d = c2.search(qdev(small), 50, mode)
         torch.cuda.synchronize()
@@ -256,7 +272,7 @@ def test_device_error_paths(small):
 @pytest.mark.parametrize("seed", [101, 102, 103, 104, 105, 106])
 def test_search_random_shapes_all_traversals_agree(seed):
     """Random shapes around the limits of the LDS-resident kernel (M in {4, 8, 16}, T in {1, 2, 4}, any K): every
-    traversal returns the same float32 lists, and they match the oracle."""
+    traversal matches the oracle, and they agree with one another (to the bit where the sums are associated alike)."""
     rng = np.random.default_rng(seed)
     M = int(rng.choice([4, 8, 16]))
     T = int(rng.choice([t for t in (1, 2, 4) if t <= M]))
@@ -273,7 +289,8 @@ def test_search_random_shapes_all_traversals_agree(seed):
         c = p.ctx(T=T, sample_min=256, traversal=trav)
         oi, od = check_search(p, c, FOREST, k, what="random seed %d trav %d" % (seed, trav))
         lists.append((oi, od))
-    for oi, od in lists[1:]:
-        assert np.array_equal(lists[0][0], oi) and np.array_equal(lists[0][1], od)
+    # traversals 0 and 1 add left to right: identical bits; traversal 2 adds the chunks of a group in pairs
+    assert np.array_equal(lists[0][0], lists[1][0]) and np.array_equal(lists[0][1], lists[1][1])
+    assert_lists_agree(lists[0], lists[2], "random seed %d: traversal 2 against 0" % seed)
     c = p.ctx(T=1, sample_min=256)
     check_search(p, c, FLAT, k, what="random seed %d flat" % seed)
