@@ -611,7 +611,7 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
     if (nitems == 0) return ETF_OK;
     const int M = ctx->M, K = ctx->K;
     const int G = std::max(2, pick_G(M, K));
-    const size_t lds = (size_t)M * K * (WAVE / G) * 4;
+    const size_t lds = lds_table_bytes(G, M, K) + lds_aux_bytes(MODE == OUT_FILTER);
     const int IPS = LDS_V * G;  // items per wave step
     int64_t bx;
     int per_block = 0;

@@ -648,8 +648,9 @@ __device__ __forceinline__ vecq lds_item_sum(Look look, bool fast, vecq &top)
 // Stages all M slices of sub-tile g as lines: the four rows (m = 4i .. 4i+3, same codeword number) of a chunk
 // group side by side, [M/4][K][4][Qs].  A row of Qs = 16 queries is 64 bytes, a line 256 bytes = all LDS banks,
 // so the row of chunk m always sits in bank quarter m % 4, whatever the codeword.
+// KP >= K is the number of lines reserved per group.
 template <int G>
-__device__ __forceinline__ void stage_lines(float *lds, const float *__restrict__ lutT, int tile, int g, int M, int K)
+__device__ __forceinline__ void stage_lines(float *lds, const float *__restrict__ lutT, int tile, int g, int M, int K, int KP)
 {
     constexpr int Qs = WAVE / G;
     const int total = M * K * Qs;
@@ -657,10 +658,21 @@ __device__ __forceinline__ void stage_lines(float *lds, const float *__restrict_
     for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
         const int row = idx / Qs, qq = idx % Qs;  // row = m * K + k
         const int m = row / K, k = row - m * K;
-        lds[((((m >> 2) * K + k) << 2) + (m & 3)) * Qs + qq] = src[(int64_t)row * QT + qq];
+        lds[((((m >> 2) * KP + k) << 2) + (m & 3)) * Qs + qq] = src[(int64_t)row * QT + qq];
     }
     __syncthreads();
 }
+
+// bytes of LDS k_lds needs: the table lines, and behind them the candidate ring and its counters in filter mode
+constexpr int LDS_RING = 160;
+__host__ __device__ inline int lds_lines_per_group(int G, int K) { return G == 4 ? 256 : K; }
+__host__ __device__ inline size_t lds_table_bytes(int G, int M, int K)
+{
+    return (size_t)(M / 4) * lds_lines_per_group(G, K) * (size_t)(4 * (WAVE / G) * 4);
+}
+__host__ __device__ inline size_t lds_aux_bytes(bool filter) { return filter ? (size_t)16 * LDS_RING * 8 + 2 * 16 * 64 * 4 : 0; }
+
+typedef __attribute__((address_space(3))) const vecq lds_vecq_t;
 
 template <int G, int M4, int T, int MODE, bool CTX>
 __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, int64_t nitems,
@@ -670,45 +682,59 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     constexpr int Qs = WAVE / G, V = LDS_V, LPI = Qs / V, IPS = WAVE / LPI, M = 4 * M4;
     constexpr int S = CTX ? 2 : 0;  // chunks kept in the context: the first pair
     constexpr int U = M4 >= 4 ? 2 : 4;
-    constexpr int RING = 160;
+    constexpr int RING = LDS_RING;
     constexpr bool FILTER = MODE == OUT_FILTER;
+    // With rows of 64 bytes a line is 256 bytes, and with 256 lines per group the byte address of an entry is
+    // (group << 16) | (code << 8) | (chunk << 6) | (lane's piece << 4): one v_perm_b32 drops the code byte of the
+    // record into byte 1 of a per-lane constant, instead of a bit-field extract and a shift-add.  That needs the
+    // tables at LDS address 0: this kernel has no static LDS, ring and counters live behind the tables.
+    constexpr bool PERM = Qs == 16;
     extern __shared__ float lds[];
-    __shared__ uint64_t ring[FILTER ? 16 : 1][FILTER ? RING : 1];
-    __shared__ uint32_t wcount[FILTER ? 16 : 1][64];
-    __shared__ uint32_t wpos[FILTER ? 16 : 1][64];
+    const int KP = PERM ? 256 : K;
+    const uint32_t rowB = Qs * 4, lineB = 4 * rowB;
+    char *aux = reinterpret_cast<char *>(lds) + (size_t)M4 * KP * lineB;
+    uint64_t(*ring)[RING] = reinterpret_cast<uint64_t(*)[RING]>(aux);
+    uint32_t(*wcount)[64] = reinterpret_cast<uint32_t(*)[64]>(aux + 16 * RING * 8);
+    uint32_t(*wpos)[64] = reinterpret_cast<uint32_t(*)[64]>(aux + 16 * RING * 8 + 16 * 64 * 4);
     const int tile = blockIdx.z, sub = blockIdx.y;
     const int lane = threadIdx.x & 63;
     const int w = uniform(threadIdx.x >> 6), nw = blockDim.x >> 6;
     if (FILTER) wcount[w][lane] = 0u;
-    stage_lines<G>(lds, lutT, tile, sub, M, K);
+    stage_lines<G>(lds, lutT, tile, sub, M, K, KP);
     const int lg = lane / LPI, lq = lane % LPI;
     const int col = sub * Qs + lq * V;  // first of this lane's queries inside the tile
-    const uint32_t rowB = Qs * 4, lineB = 4 * rowB;
     // Which chunk of a group this lane reads t-th: t ^ j with j = the lane group's number mod 4.  The four lane
     // groups that share a pass of the LDS pipe (16 lanes x 16 bytes) then read four different chunks at any
     // time, i.e. four different bank quarters: no bank conflicts, whatever the codes.  Group 0 of a walk with
     // context only swaps inside its pairs (j & 1), so that the first two reads are chunks 0 and 1 in every lane
     // and can be skipped together.
     const int j4 = lg & 3;
-    uint32_t sh[2][4];                         // shift of the code byte; [0]: group 0, [1]: the other groups
-    uint32_t pb[M4][4];                        // byte address of row 0 of that chunk for this lane
+    const uint32_t base = (uint32_t)(uintptr_t)lds;  // LDS address of the tables (0 when PERM)
+    uint32_t sh[2][4];   // PERM: selector of v_perm_b32; else shift of the code byte.  [0]: group 0, [1]: the others
+    uint32_t pb[M4][4];  // LDS address of line 0 of that chunk for this lane
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int c0 = CTX ? (t ^ (j4 & 1)) : (t ^ j4);
         const int c1 = t ^ j4;
-        sh[0][t] = 8u * (uint32_t)c0;
-        sh[1][t] = 8u * (uint32_t)c1;
+        sh[0][t] = PERM ? (0x03020000u | ((4u + (uint32_t)c0) << 8)) : 8u * (uint32_t)c0;
+        sh[1][t] = PERM ? (0x03020000u | ((4u + (uint32_t)c1) << 8)) : 8u * (uint32_t)c1;
 #pragma unroll
         for (int g = 0; g < M4; ++g) {
             const int c = g == 0 ? c0 : c1;
-            pb[g][t] = (uint32_t)(lq * (V * 4)) + (uint32_t)g * (uint32_t)K * lineB + (uint32_t)c * rowB;
+            pb[g][t] = base + (uint32_t)(lq * (V * 4)) + (uint32_t)g * (uint32_t)KP * lineB + (uint32_t)c * rowB;
         }
     }
-    const char *lds0 = reinterpret_cast<const char *>(lds);
     auto sum_of = [&](const uint32_t dw[M4], bool fast, vecq &top) -> vecq {
         auto look = [&](int g, int t) -> vecq {
-            const uint32_t code = __builtin_amdgcn_ubfe(dw[g], sh[g == 0 ? 0 : 1][t], 8);
-            return *reinterpret_cast<const vecq *>(lds0 + pb[g][t] + code * lineB);
+            uint32_t addr;
+            if (PERM) {
+                // bytes 0, 2, 3 from pb (byte 1 of pb is zero), byte 1 = the code: selector bytes 0..3 pick from
+                // the second operand, 4..7 from the first
+                addr = __builtin_amdgcn_perm(dw[g], pb[g][t], sh[g == 0 ? 0 : 1][t]);
+            } else {
+                addr = pb[g][t] + __builtin_amdgcn_ubfe(dw[g], sh[g == 0 ? 0 : 1][t], 8) * lineB;
+            }
+            return *reinterpret_cast<lds_vecq_t *>(addr);
         };
         return lds_item_sum<M4, T, CTX>(look, CTX && fast, top);
     };
