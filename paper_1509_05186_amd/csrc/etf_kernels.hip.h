@@ -207,9 +207,18 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
                     const float nn = qq[cb] + cc;
                     const float v = nn - 2.f * acc[rb][cb][r];
                     const int ql = cb * 32 + col;
-                    if (v < 0.25f * nn) {
-                        fix[atomicAdd(&nfix, 1)] = (uint16_t)((ql << 8) | k);
-                    } else {
+                    const bool small = v < 0.25f * nn;
+                    // append the wave's small entries with one reservation (rank among them from the ballot)
+                    const uint64_t smask = __ballot(small);
+                    if (smask != 0ull) {
+                        int slot0 = 0;
+                        if (lane == __ffsll((unsigned long long)smask) - 1) slot0 = atomicAdd(&nfix, __popcll(smask));
+                        slot0 = __builtin_amdgcn_readlane(slot0, __ffsll((unsigned long long)smask) - 1);
+                        if (small)
+                            fix[slot0 + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(smask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)smask, 0u))] =
+                                (uint16_t)((ql << 8) | k);
+                    }
+                    if (!small) {
                         if (lutT) lutT[(((int64_t)tile * M + m) * K + k) * QT + ql] = v;
                         const int64_t q = q0 + (int64_t)tile * QT + ql;
                         if (lut_public && q < Q) lut_public[(q * M + m) * K + k] = v;
@@ -226,10 +235,28 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
         const float *x = queries + (live ? q : 0) * d + (int64_t)m * ds;
         const float *c = cb + ((int64_t)m * K + k) * ds;
         float sum = 0.f;
+        if ((ds & 3) == 0 && (d & 3) == 0) {  // rows of both arrays are 16-byte aligned: four terms per load
+            const float4 *x4 = reinterpret_cast<const float4 *>(x), *c4 = reinterpret_cast<const float4 *>(c);
+#pragma unroll 4
+            for (int j = 0; j < (ds >> 2); ++j) {
+                float4 xv = x4[j];
+                const float4 cv = c4[j];
+                if (!live) xv = make_float4(0.f, 0.f, 0.f, 0.f);
+                float t = xv.x - cv.x;
+                sum = fmaf(t, t, sum);
+                t = xv.y - cv.y;
+                sum = fmaf(t, t, sum);
+                t = xv.z - cv.z;
+                sum = fmaf(t, t, sum);
+                t = xv.w - cv.w;
+                sum = fmaf(t, t, sum);
+            }
+        } else {
 #pragma unroll 8
-        for (int j = 0; j < ds; ++j) {  // unrolled so that the loads of several terms are in flight together
-            const float t = (live ? x[j] : 0.f) - c[j];
-            sum = fmaf(t, t, sum);
+            for (int j = 0; j < ds; ++j) {  // unrolled so that the loads of several terms are in flight together
+                const float t = (live ? x[j] : 0.f) - c[j];
+                sum = fmaf(t, t, sum);
+            }
         }
         if (lutT) lutT[(((int64_t)tile * M + m) * K + k) * QT + ql] = sum;
         if (lut_public && live) lut_public[(q * M + m) * K + k] = sum;
