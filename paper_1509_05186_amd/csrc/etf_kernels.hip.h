@@ -1059,10 +1059,19 @@ __global__ __launch_bounds__(1024) void k_tau(const float *__restrict__ gmin, in
         for (int i = threadIdx.x; i < 256 * 64; i += blockDim.x) (&hist[0][0])[i] = 0;
         __syncthreads();
         const uint32_t prefix = s_prefix[lane];
-        for (int64_t s = w; s < S; s += nw) {
-            const uint32_t v = __float_as_uint(col[s * QT]);
-            const bool match = (p == 0) || ((v >> (shift + 8)) == (prefix >> (shift + 8)));
-            if (match) atomicAdd(&hist[(v >> shift) & 255][lane], 1u);
+        // eight rows in flight per wave: one load at a time would make the pass a chain of memory latencies
+        for (int64_t s0 = w; s0 < S; s0 += 8 * nw) {
+            uint32_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t s = s0 + (int64_t)u * nw;
+                v[u] = s < S ? __float_as_uint(col[s * QT]) : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const bool match = s0 + (int64_t)u * nw < S && ((p == 0) || ((v[u] >> (shift + 8)) == (prefix >> (shift + 8))));
+                if (match) atomicAdd(&hist[(v[u] >> shift) & 255][lane], 1u);
+            }
         }
         __syncthreads();
         // the bin in which the running count of a query reaches its rank: wave w sums bins 16w .. 16w+15 of
