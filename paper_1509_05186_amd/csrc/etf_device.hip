@@ -601,7 +601,9 @@ bool lds_eligible(int M, int K, int T, const int32_t *chunk_begin)
     if (chunk_begin)
         for (int t = 0; t <= T; ++t)
             if (chunk_begin[t] != t * (M / T)) return false;
-    return std::max(2, pick_G(M, K)) <= 8;
+    const int G = std::max(2, pick_G(M, K));
+    if (G > 8) return false;
+    return M % lds_chunks_per_line(G) == 0;  // whole lines of 4 (8 at eight queries per sub-tile) chunks
 }
 
 template <int MODE, bool CTX>
@@ -629,7 +631,7 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
     ProfScope prof(ctx, cls);
     bool done = false;
 #define LDS_CASE(GG, MM4, TT)                                                                                  \
-    if constexpr (CTX || MODE != OUT_FILTER || TT == 1) {                                                      \
+    if constexpr ((CTX || MODE != OUT_FILTER || TT == 1) && (4 * MM4) % lds_chunks_per_line(GG) == 0) {                                                      \
         if (!done && G == GG && M == 4 * MM4 && T == TT) {                                                     \
             int rc = set_lds(ctx, k_lds<GG, MM4, TT, MODE, CTX>, lds);                                         \
             if (rc) return rc;                                                                                 \
@@ -951,7 +953,7 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
         ea.lutT = lutT;
         ea.M = ix.M;
         ea.K = ix.K;
-        ea.grouped = (P.lds_path || P.flat_lds) ? 1 : 0;
+        ea.grouped = (P.lds_path || P.flat_lds) ? lds_chunks_per_line(std::max(2, pick_G(ix.M, ix.K))) : 0;
         if (flat) {
             ea.T = 1;
             ea.chunk_begin[0] = 0;

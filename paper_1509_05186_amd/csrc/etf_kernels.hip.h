@@ -634,20 +634,23 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
 constexpr int LDS_V = 4;  // queries per lane (one 16-byte LDS read per lookup)
 typedef float vecq __attribute__((ext_vector_type(LDS_V)));
 
-// Sum of one item.  The chunks are taken in groups of four, a group as (x0 + x1) + (x2 + x3), where x0 .. x3
-// are the group's four entries in the order the lane read them.  That order differs from lane group to lane
-// group (see k_lds), but only by permutations that swap the members of a pair and/or the two pairs, and
-// float addition is commutative: every lane forms exactly (c0 + c1) + (c2 + c3).  A tree's sum is the sum of its
-// groups in order (a tree of fewer than four chunks lives inside one group), the trees are added in order.
+// Sum of one item.  The chunks are taken in groups of CPL = 4 or 8 (the chunks of one LDS line), a group as a
+// balanced tree, (x0 + x1) + (x2 + x3) or ((x0 + x1) + (x2 + x3)) + ((x4 + x5) + (x6 + x7)), where x0 .. are the
+// group's entries in the order the lane read them.  That order differs from lane group to lane group (see
+// k_lds), but only by exchanging the two halves of subtrees of that tree (read order = t XOR j), and float
+// addition is commutative: every lane forms exactly the tree over c0 .. c(CPL-1), bit for bit.  With CPL = 4 a
+// tree's sum is the sum of its groups in order (a tree of fewer than four chunks lives inside one group) and
+// the trees are added in order; with CPL = 8 the groups are added in order.
 // CTX: `top` is the first pair of group 0, c0 + c1; with fast it is reused instead of read.
-template <int M4, int T, bool CTX, class Look>
+template <int M4, int T, int CPL, bool CTX, class Look>
 __device__ __forceinline__ vecq lds_item_sum(Look look, bool fast, vecq &top)
 {
+    constexpr int NG = 4 * M4 / CPL;
     constexpr int D = 4 * M4 / T;
-    constexpr int GPT = D >= 4 ? D / 4 : 1;  // groups per tree
-    vecq P[M4];
+    constexpr int GPT = CPL == 8 ? NG : (D >= 4 ? D / 4 : 1);  // groups per tree
+    vecq P[NG];
 #pragma unroll
-    for (int g = 0; g < M4; ++g) {
+    for (int g = 0; g < NG; ++g) {
         vecq a;
         if (CTX && g == 0) {
             if (fast) {
@@ -660,10 +663,11 @@ __device__ __forceinline__ vecq lds_item_sum(Look look, bool fast, vecq &top)
             a = look(g, 0) + look(g, 1);
         }
         P[g] = a + (look(g, 2) + look(g, 3));
+        if (CPL == 8) P[g] = P[g] + ((look(g, 4) + look(g, 5)) + (look(g, 6) + look(g, 7)));
     }
     vecq d = 0.f;
 #pragma unroll
-    for (int t0 = 0; t0 < M4; t0 += GPT) {
+    for (int t0 = 0; t0 < NG; t0 += GPT) {
         vecq s = P[t0];
 #pragma unroll
         for (int i = 1; i < GPT; ++i) s += P[t0 + i];
@@ -672,30 +676,34 @@ __device__ __forceinline__ vecq lds_item_sum(Look look, bool fast, vecq &top)
     return d;
 }
 
-// Stages all M slices of sub-tile g as lines: the four rows (m = 4i .. 4i+3, same codeword number) of a chunk
-// group side by side, [M/4][K][4][Qs].  A row of Qs = 16 queries is 64 bytes, a line 256 bytes = all LDS banks,
-// so the row of chunk m always sits in bank quarter m % 4, whatever the codeword.
+// chunks per LDS line of the LDS-resident kernels: a line is at least 256 bytes (all banks)
+__host__ __device__ constexpr int lds_chunks_per_line(int G) { return G == 8 ? 8 : 4; }
+
+// Stages all M slices of sub-tile g as lines: the rows of the CPL chunks of a group (same codeword number) side
+// by side, [M/CPL][KP][CPL][Qs].  With rows of 64 (32) bytes and CPL = 4 (8) a line is 256 bytes = all LDS
+// banks, so the row of chunk m always sits in the same bank quarter (eighth) m % CPL, whatever the codeword.
 // KP >= K is the number of lines reserved per group.
 template <int G>
 __device__ __forceinline__ void stage_lines(float *lds, const float *__restrict__ lutT, int tile, int g, int M, int K, int KP)
 {
-    constexpr int Qs = WAVE / G;
+    constexpr int Qs = WAVE / G, CPL = lds_chunks_per_line(G);
     const int total = M * K * Qs;
     const float *src = lutT + (int64_t)tile * M * K * QT + g * Qs;
     for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
         const int row = idx / Qs, qq = idx % Qs;  // row = m * K + k
         const int m = row / K, k = row - m * K;
-        lds[((((m >> 2) * KP + k) << 2) + (m & 3)) * Qs + qq] = src[(int64_t)row * QT + qq];
+        lds[(((m / CPL) * KP + k) * CPL + (m % CPL)) * Qs + qq] = src[(int64_t)row * QT + qq];
     }
     __syncthreads();
 }
 
 // bytes of LDS k_lds needs: the table lines, and behind them the candidate ring and its counters in filter mode
 constexpr int LDS_RING = 160;
-__host__ __device__ inline int lds_lines_per_group(int G, int K) { return G == 4 ? 256 : K; }
+__host__ __device__ inline int lds_lines_per_group(int G, int K) { return (G == 4 || G == 8) ? 256 : K; }
 __host__ __device__ inline size_t lds_table_bytes(int G, int M, int K)
 {
-    return (size_t)(M / 4) * lds_lines_per_group(G, K) * (size_t)(4 * (WAVE / G) * 4);
+    const int CPL = lds_chunks_per_line(G);
+    return (size_t)(M / CPL) * lds_lines_per_group(G, K) * (size_t)(CPL * (WAVE / G) * 4);
 }
 __host__ __device__ inline size_t lds_aux_bytes(bool filter) { return filter ? (size_t)16 * LDS_RING * 8 + 2 * 16 * 64 * 4 : 0; }
 
@@ -715,11 +723,12 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     // (group << 16) | (code << 8) | (chunk << 6) | (lane's piece << 4): one v_perm_b32 drops the code byte of the
     // record into byte 1 of a per-lane constant, instead of a bit-field extract and a shift-add.  That needs the
     // tables at LDS address 0: this kernel has no static LDS, ring and counters live behind the tables.
-    constexpr bool PERM = Qs == 16;
+    constexpr int CPL = lds_chunks_per_line(G), NG = M / CPL;
+    constexpr bool PERM = CPL * Qs * 4 == 256;
     extern __shared__ float lds[];
     const int KP = PERM ? 256 : K;
-    const uint32_t rowB = Qs * 4, lineB = 4 * rowB;
-    char *aux = reinterpret_cast<char *>(lds) + (size_t)M4 * KP * lineB;
+    const uint32_t rowB = Qs * 4, lineB = CPL * rowB;
+    char *aux = reinterpret_cast<char *>(lds) + (size_t)NG * KP * lineB;
     uint64_t(*ring)[RING] = reinterpret_cast<uint64_t(*)[RING]>(aux);
     uint32_t(*wcount)[64] = reinterpret_cast<uint32_t(*)[64]>(aux + 16 * RING * 8);
     uint32_t(*wpos)[64] = reinterpret_cast<uint32_t(*)[64]>(aux + 16 * RING * 8 + 16 * 64 * 4);
@@ -730,40 +739,50 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     stage_lines<G>(lds, lutT, tile, sub, M, K, KP);
     const int lg = lane / LPI, lq = lane % LPI;
     const int col = sub * Qs + lq * V;  // first of this lane's queries inside the tile
-    // Which chunk of a group this lane reads t-th: t ^ j with j = the lane group's number mod 4.  The four lane
-    // groups that share a pass of the LDS pipe (16 lanes x 16 bytes) then read four different chunks at any
-    // time, i.e. four different bank quarters: no bank conflicts, whatever the codes.  Group 0 of a walk with
-    // context only swaps inside its pairs (j & 1), so that the first two reads are chunks 0 and 1 in every lane
-    // and can be skipped together.
-    const int j4 = lg & 3;
+    // Which chunk of a group this lane reads t-th: t ^ j with j = the lane group's number mod CPL.  The CPL lane
+    // groups that share a pass of the LDS pipe (16 lanes x 16 bytes) then read CPL different chunks at any time,
+    // i.e. different bank quarters (eighths): no bank conflicts, whatever the codes.  Group 0 of a walk with
+    // context only swaps inside its pairs (and, with CPL = 8, rotates chunks 4 .. 7 among themselves), so that the
+    // first two reads are chunks 0 and 1 in every lane and can be skipped together.
+    const int jr = lg & (CPL - 1);
     const uint32_t base = (uint32_t)(uintptr_t)lds;  // LDS address of the tables (0 when PERM)
-    uint32_t sh[2][4];   // PERM: selector of v_perm_b32; else shift of the code byte.  [0]: group 0, [1]: the others
-    uint32_t pb[M4][4];  // LDS address of line 0 of that chunk for this lane
+    uint32_t sh[2][CPL];   // PERM: selector of v_perm_b32; else shift of the code byte.  [0]: group 0, [1]: the others
+    uint32_t pb[NG][CPL];  // LDS address of line 0 of that chunk for this lane
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int c0 = CTX ? (t ^ (j4 & 1)) : (t ^ j4);
-        const int c1 = t ^ j4;
-        sh[0][t] = PERM ? (0x03020000u | ((4u + (uint32_t)c0) << 8)) : 8u * (uint32_t)c0;
-        sh[1][t] = PERM ? (0x03020000u | ((4u + (uint32_t)c1) << 8)) : 8u * (uint32_t)c1;
+    for (int t = 0; t < CPL; ++t) {
+        int c0 = t ^ jr;
+        if (CTX) c0 = t < 4 ? (t ^ (jr & 1)) : 4 + ((t - 4) ^ (jr & 3));
+        const int c1 = t ^ jr;
+        sh[0][t] = PERM ? (0x03020000u | ((4u + (uint32_t)(c0 & 3)) << 8)) : 8u * (uint32_t)(c0 & 3);
+        sh[1][t] = PERM ? (0x03020000u | ((4u + (uint32_t)(c1 & 3)) << 8)) : 8u * (uint32_t)(c1 & 3);
 #pragma unroll
-        for (int g = 0; g < M4; ++g) {
+        for (int g = 0; g < NG; ++g) {
             const int c = g == 0 ? c0 : c1;
             pb[g][t] = base + (uint32_t)(lq * (V * 4)) + (uint32_t)g * (uint32_t)KP * lineB + (uint32_t)c * rowB;
         }
     }
+    // CPL = 8: the two record dwords of a group; a lane whose rotation exchanges the halves reads them crosswise
+    const bool cross = CPL == 8 && (jr & 4) != 0;
     auto sum_of = [&](const uint32_t dw[M4], bool fast, vecq &top) -> vecq {
         auto look = [&](int g, int t) -> vecq {
+            uint32_t src;
+            if (CPL == 4) {
+                src = dw[g];
+            } else {
+                const bool second = (CTX && g == 0) ? t >= 4 : ((t >= 4) != cross);
+                src = second ? dw[2 * g + 1] : dw[2 * g];
+            }
             uint32_t addr;
             if (PERM) {
                 // bytes 0, 2, 3 from pb (byte 1 of pb is zero), byte 1 = the code: selector bytes 0..3 pick from
                 // the second operand, 4..7 from the first
-                addr = __builtin_amdgcn_perm(dw[g], pb[g][t], sh[g == 0 ? 0 : 1][t]);
+                addr = __builtin_amdgcn_perm(src, pb[g][t], sh[g == 0 ? 0 : 1][t]);
             } else {
-                addr = pb[g][t] + __builtin_amdgcn_ubfe(dw[g], sh[g == 0 ? 0 : 1][t], 8) * lineB;
+                addr = pb[g][t] + __builtin_amdgcn_ubfe(src, sh[g == 0 ? 0 : 1][t], 8) * lineB;
             }
             return *reinterpret_cast<lds_vecq_t *>(addr);
         };
-        return lds_item_sum<M4, T, CTX>(look, CTX && fast, top);
+        return lds_item_sum<M4, T, CPL, CTX>(look, CTX && fast, top);
     };
 
     if (MODE == OUT_SAMPLE) {
@@ -866,19 +885,28 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
             if (held > RING - 64) flush();
         }
     };
-    // one run of consecutive items per lane group; records come through a buffer over the workgroup's share,
-    // the step number in the scalar offset
+    // A wave walks one run of consecutive items, its IPS lane groups taking the items in turn (lane group g:
+    // items g, g + IPS, ...): a step reads IPS consecutive records, one coalesced load, and a CU follows 16
+    // record streams.  (One run per lane group means 256 to 512 streams per CU; at 32 items per step they
+    // overflow the 32 KB vector cache and every record load goes to L2: cfg4 72 -> 37 ms.)  The context of a lane
+    // group then refers to the item IPS places back.  Records come through a buffer over the workgroup's
+    // share, the step number in the scalar offset.
+    constexpr int RF = IPS;  // lane groups per run
     if (blo >= bhi) return;
-    const int nruns = nw * IPS;
-    const int RL = (per_block + nruns - 1) / nruns;
-    const int64_t rlo = blo + (int64_t)(w * IPS + lg) * RL;
-    const int len = (int)max<int64_t>(0, min<int64_t>(bhi - rlo, RL));  // items of this lane group's run
+    const int nruns = nw * IPS / RF;
+    const int RLr = (per_block + nruns - 1) / nruns;         // items per run
+    const int RL = (RLr + RF - 1) / RF;                      // steps per run
+    const int ph = lg % RF;
+    const int64_t rlo = blo + (int64_t)((w * IPS + lg) / RF) * RLr;
+    const int runlen = (int)max<int64_t>(0, min<int64_t>(bhi - rlo, RLr));
+    const int len = runlen > ph ? (runlen - ph + RF - 1) / RF : 0;  // items of this lane group
     int minlen = len;
 #pragma unroll
     for (int dlt = LPI; dlt < WAVE; dlt <<= 1) minlen = min(minlen, __shfl_xor(minlen, dlt));
     minlen = uniform(minlen);
     const rsrc_t rr = make_rsrc(rec + blo * M4, (uint32_t)((bhi - blo) * (M4 * 4)));
-    const uint32_t voff = len > 0 ? (uint32_t)((rlo - blo) * (M4 * 4)) : 0u;
+    const uint32_t first = (uint32_t)(rlo - blo) + (uint32_t)ph;   // this lane group's first item, relative to blo
+    const uint32_t voff = len > 0 ? first * (M4 * 4) : 0u;
     uint32_t prev0 = 0u;
     vecq top = 0.f;
     // U steps from step i on; CHECK: some lane groups may be past the end of their run
@@ -888,9 +916,9 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             uint32_t vo = voff;
-            int so = (i + u) * (M4 * 4);
+            int so = (i + u) * (RF * M4 * 4);
             if (CHECK) {
-                vo += (uint32_t)max(0, min(i + u, len - 1)) * (M4 * 4);
+                vo += (uint32_t)max(0, min(i + u, len - 1)) * (RF * M4 * 4);
                 so = 0;
             }
 #pragma unroll
@@ -901,14 +929,14 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
             const bool live = !CHECK || i + u < len;
             bool fast = false;
             if (S > 0) {
-                // a lane group may keep its context if its item has the S-chunk prefix of the previous one
+                // a lane group may keep its context if its item has the S-chunk prefix of its previous one
                 const uint32_t smask = S == 1 ? 0xFFu : 0xFFFFu;
                 const bool differs = live && ((dw[u][0] ^ prev0) & smask) != 0u;
                 fast = __ballot(differs) == 0ull && i + u != 0;
                 prev0 = dw[u][0];
             }
             const vecq d = sum_of(dw[u], fast, top);
-            const uint32_t rel = (uint32_t)(rlo - blo) + (uint32_t)(i + u);
+            const uint32_t rel = first + (uint32_t)(i + u) * RF;
 #pragma unroll
             for (int v = 0; v < V; ++v) emit(live && d[v] <= tau[v], d[v], col + v, rel);
         }
@@ -1385,7 +1413,7 @@ struct ExactArgs {
     uint32_t *nflag;          // running count of queries answered here
     const float *lutT;        // [tiles][M][K][64]
     int M, K, T;
-    int grouped;              // 1: sums associated as the LDS-resident kernels do (see exact_distance)
+    int grouped;              // 4 or 8: sums associated as the LDS-resident kernels do (see exact_distance), 0: left to right
     int32_t chunk_begin[ETF_MAX_M + 1];
     const uint8_t *codes;     // [rows][M]
     int64_t rows;
@@ -1398,7 +1426,7 @@ struct ExactArgs {
 
 __device__ __forceinline__ float exact_distance(const ExactArgs &a, const float *lut, const uint8_t *c)
 {
-    if (a.grouped) {
+    if (a.grouped == 4) {
         // the association of the LDS-resident kernels: chunks in groups of four as (c0 + c1) + (c2 + c3), a
         // tree the sum of its groups in order (trees are equal there; shorter ones live inside one group)
         const int M4 = a.M >> 2, D = a.M / a.T, gpt = D >= 4 ? D >> 2 : 1;
@@ -1412,6 +1440,18 @@ __device__ __forceinline__ float exact_distance(const ExactArgs &a, const float 
                 s = i == 0 ? P : s + P;
             }
             d = t0 == 0 ? s : d + s;
+        }
+        return d;
+    }
+    if (a.grouped == 8) {
+        // groups of eight as a balanced tree, the groups added in order
+        float d = 0.f;
+        for (int m = 0; m < a.M; m += 8) {
+            const float lo = (lut[m * a.K + c[m]] + lut[(m + 1) * a.K + c[m + 1]]) +
+                             (lut[(m + 2) * a.K + c[m + 2]] + lut[(m + 3) * a.K + c[m + 3]]);
+            const float hi = (lut[(m + 4) * a.K + c[m + 4]] + lut[(m + 5) * a.K + c[m + 5]]) +
+                             (lut[(m + 6) * a.K + c[m + 6]] + lut[(m + 7) * a.K + c[m + 7]]);
+            d = m == 0 ? lo + hi : d + (lo + hi);
         }
         return d;
     }
