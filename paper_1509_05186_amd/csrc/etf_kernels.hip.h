@@ -606,21 +606,23 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
 }
 
 // ------------------------------------------------------------------------------------------------
-// Search with every table slice in LDS (flat ADC, and the trees walked per lane group).
-//     All M = 4*M4 slices of a sub-tile of Qs = 64/G queries are staged in LDS; a lane owns V = 4
-//     adjacent queries of one item, so one address and one 16-byte LDS read serve four distances: Qs/4
-//     lanes per item, IPS = 4G items per wave step (measured on cfg2: V = 1, 2, 4, 8 -> 12.2, 4.2, 3.5, 4.8 ms).  Nothing but the item records is read from HBM.
-//     The sum of an item is formed as everywhere else: chunks left to right inside a tree, the T trees
-//     (equal groups of D = M/T chunks) in order.
+// Search and all-pairs output with every table slice in LDS (flat ADC, and the trees walked by the waves).
+//     All M = 4*M4 slices of a sub-tile of Qs = 64/G queries are staged in LDS (as lines, see stage_lines);
+//     a lane owns V = 4 adjacent queries of one item, so one address and one 16-byte LDS read serve four
+//     distances: Qs/4 lanes per item (a lane group), IPS = 4G items per wave step (measured on cfg2:
+//     V = 1, 2, 4, 8 -> 12.2, 4.2, 3.5, 4.8 ms).  Nothing but the item records is read from HBM.
+//     The sum of an item: see lds_item_sum (chunks in pairs inside the groups of a line, groups and trees in
+//     order).
 //
-//     OUT_FILTER: a workgroup takes per_block consecutive items and cuts them into one run per lane
-//     group.  With CTX the items are the sorted distinct encodings and every lane group walks its run
-//     depth first with a Distance Context (paper, "Distance Computation with Hierarchical Memory
-//     Structure") reduced to the first S levels of tree 0: as long as no lane group of the wave leaves
-//     the S-chunk prefix of its previous item, the sum over those levels is kept and only the deeper
-//     chunks are looked up; otherwise the whole wave recomputes it (which changes nothing for the lane
-//     groups that did not need to).  Deeper levels are not shared: the lane groups of a wave diverge
-//     there almost every step, and a lookup costs the same whether or not every group needs it.
+//     OUT_FILTER: a workgroup takes per_block consecutive items and cuts them into one run per wave; the
+//     wave's lane groups take the run's items in turn.  With CTX the items are the sorted distinct
+//     encodings and every lane group carries a Distance Context (paper, "Distance Computation with
+//     Hierarchical Memory Structure") over the items it sees, reduced to the first two levels of tree 0: as
+//     long as no lane group of the wave leaves the 2-chunk prefix of its previous item, the sum over those
+//     levels is kept and only the deeper chunks are looked up; otherwise the whole wave recomputes it
+//     (which changes nothing for the lane groups that did not need to).  Deeper levels are not shared: the
+//     lane groups of a wave diverge there almost every step, and a lookup costs the same whether or not
+//     every group needs it.
 //     Candidates at or below the bound go to a ring of the wave in LDS (slot = rank among the passing
 //     lanes) and are appended to the queries' lists by the whole wave when the ring is nearly full: one
 //     global reservation per query, then LDS atomics hand out the slots.
@@ -629,7 +631,8 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
 //     OUT_ALLPAIRS: items are input positions (rec = the codes in input order, no context); dist[q][n] written
 //     as 64-byte pieces (16 consecutive n of one query per wave step).
 //     rec [n][M4] dwords: the codes of an item, chunk 0 in the lowest byte.
-//     grid (blocks, G, tiles), block 1024, dynamic LDS M*K*Qs*4 bytes; per_block < 2^26.
+//     grid (blocks, G, tiles), block 1024, dynamic LDS lds_table_bytes + lds_aux_bytes, no static LDS;
+//     per_block < 2^26.
 // ------------------------------------------------------------------------------------------------
 constexpr int LDS_V = 4;  // queries per lane (one 16-byte LDS read per lookup)
 typedef float vecq __attribute__((ext_vector_type(LDS_V)));
