@@ -241,6 +241,19 @@ def test_search_small_database():
         assert_distances_close(d.cpu().numpy(), p.ref_all, "tiny adc")
 
 
+@pytest.mark.parametrize("M,K,N,Q", [(4, 8, 17, 3), (8, 256, 1, 1), (16, 200, 33, 70), (8, 16, 64, 64)])
+def test_search_tiny_databases_through_the_lds_kernels(M, K, N, Q):
+    say("tiny database through the LDS-resident kernels: M", M, "K", K, "N", N, "Q", Q)
+    p = Problem(d=M * 2, M=M, K=K, N=N, Q=Q, ntrain=max(2 * K, 100), seed=31 + M, iters=2)
+    for mode, T in [(FLAT, 1), (TREE, 1), (FOREST, 2), (FOREST, 4)]:
+        c = p.ctx(T=T)
+        for k in sorted({1, min(N, 7), N}):
+            check_search(p, c, mode, k, what="tiny lds m%d T%d k%d" % (mode, T, k))
+        d = c.adc(qdev(p), mode)
+        torch.cuda.synchronize()
+        assert_distances_close(d.cpu().numpy(), p.ref_all, "tiny lds adc")
+
+
 def test_search_several_batches(small):
     say("search with a workspace cap that forces several query batches")
     c = small.ctx(T=2, sample_min=2048, ws_cap_bytes=8 << 20)
