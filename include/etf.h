@@ -96,7 +96,7 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     whole-database selection kernel (testing)
  *   "sample_min" / "sample_scale"   size of the sample that bounds the k-th distance (drawn by
  *                     etf_index_build): max(sample_min, sample_scale * sqrt(n)), n = number of distinct
- *                     encodings (of vectors in flat mode); defaults 32768 and 60
+ *                     encodings (of vectors in flat mode); defaults 32768 and 90
  *   "cand_cap"        per-query candidate capacity (0 = derived from k)
  *   "lut_kernel"      0 (default): lookup tables on the matrix cores, as ||q'||^2 - 2 q'.c' + ||c'||^2
  *                     on vectors shifted by the group's mean codeword; entries below a quarter of

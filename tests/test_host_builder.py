@@ -208,7 +208,7 @@ def test_builder_sampling_on_larger_input():
     st, lay, buf = c.index_stats(), c.index_layout(), c.index_export()
     se = arr(buf, lay.sample_enc, lay.n_sample_enc, np.uint32)
     sp = arr(buf, lay.sample_pos, lay.n_sample_pos, np.uint32)
-    want_e, want_p = 60 * np.sqrt(st["n_distinct"]), 60 * np.sqrt(N)         # sample_scale * sqrt(n), duplicates of the draw removed
+    want_e, want_p = 90 * np.sqrt(st["n_distinct"]), 90 * np.sqrt(N)         # sample_scale * sqrt(n), duplicates of the draw removed
     assert 0.9 * want_e <= len(se) <= want_e + 1 and se.max() < st["n_distinct"]
     assert 0.9 * want_p <= len(sp) <= want_p + 1 and sp.max() < N
     assert len(np.unique(se)) == len(se) and len(np.unique(sp)) == len(sp)
