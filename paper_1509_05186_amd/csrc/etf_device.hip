@@ -618,7 +618,7 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
     int64_t bx;
     int per_block = 0;
     if (MODE == OUT_SAMPLE) {
-        // every workgroup stages the whole table set: give each lane group at least two sample groups
+        // every workgroup stages the whole table set: give each wave at least two stretches of IPS sample groups
         bx = blocks_for(o.ngroups, 2 * 16 * IPS, tiles * G);
     } else {
         // item numbers inside a workgroup's share travel in 26 bits

@@ -626,8 +626,8 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
 //     Candidates at or below the bound go to a ring of the wave in LDS (slot = rank among the passing
 //     lanes) and are appended to the queries' lists by the whole wave when the ring is nearly full: one
 //     global reservation per query, then LDS atomics hand out the slots.
-//     OUT_SAMPLE: items map[i] (or i itself without a map: the sample's records stored side by side); every
-//     lane group owns whole sample groups and keeps their minima.
+//     OUT_SAMPLE: items map[i] (or i itself without a map: the sample's records stored side by side); a wave
+//     walks a stretch of the sample, every lane group's share of it is one sample group, whose minimum it keeps.
 //     OUT_ALLPAIRS: items are input positions (rec = the codes in input order, no context); dist[q][n] written
 //     as 64-byte pieces (16 consecutive n of one query per wave step).
 //     rec [n][M4] dwords: the codes of an item, chunk 0 in the lowest byte.
@@ -789,19 +789,24 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     };
 
     if (MODE == OUT_SAMPLE) {
-        const int64_t stride = (int64_t)gridDim.x * nw * IPS;
-        for (int64_t g0 = ((int64_t)blockIdx.x * nw + w) * IPS; g0 < o.ngroups; g0 += stride) {
-            const int64_t g = g0 + lg;
-            const bool glive = g < o.ngroups;
+        // The sample is cut into one stretch per IPS sample groups; a wave walks a stretch, its lane groups
+        // taking the items in turn (coalesced record loads), and every lane group's share is one sample group.
+        // (Any partition of the sample into ngroups disjoint sets serves the bound; the sample is in random
+        // order.)
+        const int64_t nwr = (o.ngroups + IPS - 1) / IPS;
+        const int64_t per = ((nitems + nwr - 1) / nwr + IPS - 1) / IPS * IPS;  // items per stretch
+        for (int64_t wr = (int64_t)blockIdx.x * nw + w; wr < nwr; wr += (int64_t)gridDim.x * nw) {
+            const int64_t lo = wr * per, hi = min(nitems, lo + per);
             vecq best = __uint_as_float(0x7F800000u);
-            for (int jj = 0; jj < o.gsize; jj += U) {
+            for (int64_t j0 = lo; j0 < hi; j0 += IPS * U) {
                 uint32_t dw[U][M4];
                 bool live[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const int64_t idx = g * o.gsize + jj + u;
-                    live[u] = glive && jj + u < o.gsize && idx < nitems;
-                    const int64_t e = live[u] ? (map ? (int64_t)map[idx] : idx) : 0;
+                    const int64_t idx = j0 + u * IPS + lg;
+                    live[u] = idx < hi;
+                    const int64_t ic = min(idx, nitems - 1);
+                    const int64_t e = map ? (int64_t)map[ic] : ic;
 #pragma unroll
                     for (int i = 0; i < M4; ++i) dw[u][i] = rec[e * M4 + i];
                 }
@@ -815,7 +820,8 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
                     }
                 }
             }
-            if (glive) {
+            const int64_t g = wr * IPS + lg;
+            if (g < o.ngroups) {
                 float *dst = o.gmin + ((int64_t)tile * o.ngroups + g) * QT + col;
 #pragma unroll
                 for (int v = 0; v < V; ++v) dst[v] = best[v];
