@@ -214,6 +214,37 @@ int etf_index_export(const etf_ctx *ctx, void *host_buf, int64_t bytes);
 int64_t etf_encode_workspace_bytes(const etf_ctx *ctx);
 int etf_pq_encode_device(etf_ctx *ctx, const float *x, int64_t n, uint8_t *codes_out, void *ws, int64_t ws_bytes);
 
+/* Index build on the device (paper: "Efficient Encoding Tree Construction": the
+ * in-place lexicographic sort of the encoded dataset that Algorithm 1 starts from
+ * and the merge of repeated encodings, built in parallel as the closing remark of
+ * that section suggests).  Same arguments as etf_index_build, except:
+ *   codes   [N][M] u8, DEVICE (for example the output of etf_pq_encode_device)
+ *   ids     [N] non-negative, DEVICE, or NULL for ids = position
+ *   chunk_begin  host, as in etf_index_build
+ *   image   device, 256-byte aligned, at least *image_bytes of
+ *           etf_index_build_device_bytes(); receives the index and becomes the
+ *           resident index of the context: no etf_index_upload, and the buffer
+ *           must stay alive and unmodified like the one given to etf_index_upload
+ *   workspace  device scratch, 256-byte aligned, at least *workspace_bytes; free
+ *           to reuse when the call returns
+ * The image holds the arrays of etf_layout up to sample_pos_codes with the same
+ * meaning (codes, ids_in, ids_sorted, ebegin, enc_of_pos, ecodes, the two samples
+ * as numbers and as rows, the quantiser tables), each array at the offset its
+ * largest possible size needs; the per-tree level arrays are absent (-1 in
+ * etf_layout, zero counts in etf_stats).  Searches and all-pairs calls on such an
+ * index therefore need option traversal = 2 and a shape the LDS-resident kernels
+ * are built for (M in {4, 8, 16}, T in {1, 2, 4} equal trees); any other returns
+ * ETF_ESTATE.  etf_index_export and etf_index_upload return ETF_ESTATE.
+ * Order of vectors with equal encodings: ascending id, as in etf_index_build.  The
+ * threshold samples are drawn differently from the host build's (one row from each
+ * of n_sample equal strata), which changes no result.
+ * Synchronises the stream (the number of distinct encodings comes back to the
+ * host).  On any error the context holds no index. */
+int etf_index_build_device_bytes(const etf_ctx *ctx, int64_t N, int64_t *image_bytes, int64_t *workspace_bytes);
+int etf_index_build_device(etf_ctx *ctx, const uint8_t *codes, int64_t N, const int32_t *ids, int T,
+                           const int32_t *chunk_begin, void *image, int64_t image_bytes, void *workspace,
+                           int64_t workspace_bytes);
+
 /* Workspace (device bytes) that etf_adc / etf_search need for Q queries in the
  * given mode (k is ignored by etf_adc: pass 0).  Negative = error code. */
 int64_t etf_workspace_bytes(const etf_ctx *ctx, int64_t Q, int k, int mode);

@@ -21,6 +21,7 @@ EXPORTS = [
     "etf_index_build", "etf_index_stats", "etf_index_device_bytes", "etf_index_upload",
     "etf_index_layout", "etf_index_export",
     "etf_encode_workspace_bytes", "etf_pq_encode_device",
+    "etf_index_build_device_bytes", "etf_index_build_device",
     "etf_workspace_bytes", "etf_lut_build", "etf_adc", "etf_search", "etf_last_fallback_count",
     "etf_profile_enable", "etf_profile_read",
 ]
@@ -116,6 +117,8 @@ def load_library():
         "etf_index_export": (I, [P, P, L]),
         "etf_encode_workspace_bytes": (L, [P]),
         "etf_pq_encode_device": (I, [P, P, L, P, P, L]),
+        "etf_index_build_device_bytes": (I, [P, L, ctypes.POINTER(L), ctypes.POINTER(L)]),
+        "etf_index_build_device": (I, [P, P, L, P, I, P, P, L, P, L]),
         "etf_workspace_bytes": (L, [P, L, I, I]),
         "etf_lut_build": (I, [P, P, L, P]),
         "etf_adc": (I, [P, P, L, I, P, P, L]),
@@ -279,6 +282,38 @@ class Context:
         p, nb = self._ws(ws)
         self._ck(self._lib.etf_pq_encode_device(self._h, _dev(x) if n else None, n, _dev(codes) if n else None, p, nb))
         return codes
+
+    def index_build_device_bytes(self, N: int):
+        """(image bytes, workspace bytes) of a device-side build of N vectors."""
+        a, b = ctypes.c_int64(0), ctypes.c_int64(0)
+        self._ck(self._lib.etf_index_build_device_bytes(self._h, N, ctypes.byref(a), ctypes.byref(b)))
+        return int(a.value), int(b.value)
+
+    def index_build_device(self, codes, ids=None, T: int = 1, chunk_begin: Optional[Sequence[int]] = None,
+                           image=None, ws=None):
+        """codes: uint8 device tensor [N][M]; ids: int32 device tensor [N] or None.  Returns the image tensor."""
+        import torch
+        d, M, K = self._shape
+        if codes.dim() != 2 or codes.shape[1] != M or codes.dtype != torch.uint8 or not codes.is_contiguous():
+            raise ValueError("expected a contiguous uint8 tensor [N][%d]" % M)
+        N = codes.shape[0]
+        if ids is not None and (ids.dtype != torch.int32 or ids.shape != (N,) or not ids.is_contiguous()):
+            raise ValueError("expected a contiguous int32 tensor [N]")
+        cb = None if chunk_begin is None else np.ascontiguousarray(chunk_begin, dtype=np.int32)
+        if cb is not None and cb.shape != (T + 1,):
+            raise ValueError("chunk_begin must have T+1 entries")
+        nimg, nws = self.index_build_device_bytes(N)
+        if image is None:
+            image = torch.empty(nimg + 256, dtype=torch.uint8, device=codes.device)
+        if ws is None:
+            ws = torch.empty(nws + 256, dtype=torch.uint8, device=codes.device)
+        pi, ni = self._ws(image)
+        pw, nw = self._ws(ws)
+        self._ck(self._lib.etf_index_build_device(self._h, _dev(codes), N, None if ids is None else _dev(ids), T,
+                                                  _host(cb), pi, ni, pw, nw))
+        self._keep["index"] = image
+        self._N = N
+        return image
 
     def lut_build(self, queries, lut=None):
         import torch

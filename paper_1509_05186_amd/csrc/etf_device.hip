@@ -138,6 +138,7 @@ extern "C" int etf_index_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes)
     int rc = need_device(ctx);
     if (rc) return rc;
     if (!ctx->idx.built) return fail(ctx, ETF_ESTATE, "no index: call etf_index_build first");
+    if (ctx->idx.lean) return fail(ctx, ETF_ESTATE, "the index was built on the device and is resident already");
     if (!dev_buf) return fail(ctx, ETF_EINVAL, "device buffer is null");
     if (((uintptr_t)dev_buf & 255) != 0) return fail(ctx, ETF_EINVAL, "device buffer must be 256-byte aligned");
     if (bytes < ctx->lay.total) return fail(ctx, ETF_ENOMEM, "device buffer too small: %lld < %lld", (long long)bytes, (long long)ctx->lay.total);
@@ -200,7 +201,7 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     P.tiles_total = (Q + QT - 1) / QT;
     const int M = ix.M, K = ix.K;
     P.items = mode == ETF_MODE_FLAT ? ix.N : ix.Nd;
-    P.S = mode == ETF_MODE_FLAT ? (int64_t)ix.sample_pos.size() : (int64_t)ix.sample_enc.size();
+    P.S = mode == ETF_MODE_FLAT ? ix.n_sample_pos : ix.n_sample_enc;
     if (search) {
         // The sample is cut into at least 1024 (256) and at least 2.5 k groups; the bound is the k-th smallest group
         // minimum, which lets through 1.05 to 1.3 times k items/S candidates per query (the more groups, the
@@ -234,6 +235,10 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     // it means the register-context kernels, like traversal 0
     P.lds_path = mode != ETF_MODE_FLAT && ctx->opt.traversal == 2 && lds_eligible(M, K, ix.T, ix.chunk_begin.data());
     P.flat_lds = mode == ETF_MODE_FLAT && ctx->opt.traversal == 2 && lds_eligible(M, K, 1, nullptr);
+    if (ix.lean && !(mode == ETF_MODE_FLAT ? P.flat_lds : P.lds_path))
+        return fail(ctx, ETF_ESTATE, "an index built on the device holds no per-tree level arrays: it serves option traversal = 2 "
+                                     "on the shapes the LDS-resident kernels are built for (M = %d, K = %d, T = %d is %s)",
+                    M, K, ix.T, lds_eligible(M, K, mode == ETF_MODE_FLAT ? 1 : ix.T, mode == ETF_MODE_FLAT ? nullptr : ix.chunk_begin.data()) ? "one of them" : "not one of them");
     P.ctx_path = !P.lds_path && tmax_class(ix.T) != 0 && mode != ETF_MODE_FLAT && ctx->opt.traversal != 1;
     for (int t = 1; t < ix.T; ++t)  // the register-context kernels address a tree's result table with 32-bit offsets
         if (ix.tree[t].U >= ((int64_t)1 << 24)) P.ctx_path = false;

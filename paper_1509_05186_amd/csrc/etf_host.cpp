@@ -219,6 +219,40 @@ void prepare_centered(etf_ctx *ctx)
     }
 }
 
+int64_t sample_size(const Options &opt, int64_t n)
+{
+    return std::max<int64_t>(opt.sample_min, (int64_t)((double)opt.sample_scale * std::sqrt((double)n)));
+}
+
+void lean_layout(const etf_ctx *ctx, int64_t N, DevLayout &L)
+{
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) {
+        int64_t o = off;
+        off = align256(off + std::max<int64_t>(bytes, 4));
+        return o;
+    };
+    const int M = ctx->M;
+    const int64_t S = std::min(N, sample_size(ctx->opt, N));
+    L = DevLayout();
+    L.codebooks = take((int64_t)ctx->codebooks.size() * 4);
+    L.cb_centered = take((int64_t)ctx->cb_centered.size() * 4);
+    L.cb_norm = take((int64_t)ctx->cb_norm.size() * 4);
+    L.cb_mean = take((int64_t)ctx->cb_mean.size() * 4);
+    L.codes = take(N * M);
+    L.ids_in = take(N * 4);
+    L.ids_sorted = take(N * 4);
+    L.ebegin = take((N + 1) * 4);
+    L.enc_of_pos = take(N * 4);
+    L.ecodes = take(N * M);
+    L.sample_enc = take(S * 4);
+    L.sample_pos = take(S * 4);
+    L.sample_enc_codes = take(S * M);
+    L.sample_pos_codes = take(S * M);
+    L.rec0 = take(0);
+    L.total = off;
+}
+
 void compute_layout(etf_ctx *ctx)
 {
     const HostIndex &ix = ctx->idx;
@@ -360,12 +394,14 @@ static int check_pq_shape(etf_ctx *ctx, int d, int M, int K)
     return ETF_OK;
 }
 
-static void drop_index(etf_ctx *ctx)
+namespace etf {
+void drop_index(etf_ctx *ctx)
 {
     ctx->idx = HostIndex();
     ctx->lay = DevLayout();
     ctx->dev_base = nullptr;
 }
+}  // namespace etf
 
 // nearest codeword of one sub-vector; float32 arithmetic, direct (a-b)^2 form, lowest index on ties
 static inline int nearest_codeword(const float *x, const float *cb, int K, int ds, float *best_out)
@@ -612,12 +648,7 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
         // 4. threshold samples: a seeded random subset of the vectors (as encodings, and as positions)
         {
             uint64_t s = 0x1509051860ull ^ (uint64_t)N;
-            // The sample pass costs time in proportion to the sample, the candidates it lets through in inverse
-            // proportion: the best size grows like the square root of the database (measured optimum 55 000 draws
-            // for 700 000 distinct encodings at k = 100).
-            auto sample_size = [&](int64_t n) {
-                return std::max<int64_t>(ctx->opt.sample_min, (int64_t)((double)ctx->opt.sample_scale * std::sqrt((double)n)));
-            };
+            auto sample_size = [&](int64_t n) { return etf::sample_size(ctx->opt, n); };
             int64_t want = sample_size(ix.Nd);
             int64_t S = std::min<int64_t>(ix.Nd, want);
             // The sample is stored in random order: consecutive runs of it are the sample groups whose
@@ -657,6 +688,8 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
             for (size_t i = 0; i < ix.sample_pos.size(); ++i)
                 memcpy(ix.sample_pos_codes.data() + i * M, ix.codes.data() + (size_t)ix.sample_pos[i] * M, (size_t)M);
         }
+        ix.n_sample_enc = (int64_t)ix.sample_enc.size();
+        ix.n_sample_pos = (int64_t)ix.sample_pos.size();
         ix.built = true;
         ctx->idx = std::move(ix);
         ctx->dev_base = nullptr;
@@ -678,7 +711,7 @@ extern "C" int etf_index_stats(const etf_ctx *ctx, etf_stats *out)
     out->M = ix.M; out->K = ix.K; out->T = ix.T;
     for (int t = 0; t <= ix.T; ++t) out->chunk_begin[t] = ix.chunk_begin[t];
     out->N = ix.N; out->n_distinct = ix.Nd; out->max_dup = ix.max_dup;
-    for (int t = 0; t < ix.T; ++t) {
+    for (int t = 0; t < ix.T && !ix.lean; ++t) {
         const HostTree &tr = ix.tree[t];
         for (int l = 0; l < tr.D; ++l) {
             out->nI[t][l] = (int64_t)tr.level[l].code.size();
@@ -718,9 +751,9 @@ extern "C" int etf_index_layout(const etf_ctx *ctx, etf_layout *out)
     out->cb_centered = L.cb_centered; out->cb_norm = L.cb_norm; out->cb_mean = L.cb_mean;
     out->cb_row = ctx->dsp;
     out->rec0_stride = ix.rstride0;
-    out->n_sample_enc = (int64_t)ix.sample_enc.size();
-    out->n_sample_pos = (int64_t)ix.sample_pos.size();
-    for (int t = 0; t < ix.T; ++t) {
+    out->n_sample_enc = ix.n_sample_enc;
+    out->n_sample_pos = ix.n_sample_pos;
+    for (int t = 0; t < ix.T && !ix.lean; ++t) {
         out->leaf_of[t] = L.tree[t].leaf_of;
         out->trec[t] = L.tree[t].rec;
         out->trec_stride[t] = ix.tree[t].rstride;
@@ -741,6 +774,7 @@ extern "C" int etf_index_export(const etf_ctx *ctx, void *host_buf, int64_t byte
     if (!ctx) return ETF_EINVAL;
     if (!host_buf) return fail(ctx, ETF_EINVAL, "output pointer is null");
     if (!ctx->idx.built) return fail(ctx, ETF_ESTATE, "no index: call etf_index_build first");
+    if (ctx->idx.lean) return fail(ctx, ETF_ESTATE, "the index was built on the device: the host holds no copy of it");
     if (bytes < ctx->lay.total) return fail(ctx, ETF_ENOMEM, "buffer too small: %lld < %lld", (long long)bytes, (long long)ctx->lay.total);
     memset(host_buf, 0, (size_t)ctx->lay.total);
     char *base = (char *)host_buf;

@@ -50,6 +50,10 @@ inline int depth_class(int D)
 
 struct HostIndex {
     bool built = false;
+    // Built on the device: the host holds the shape and the counts only, the image is already resident and holds
+    // the arrays the LDS-resident kernels, the flat scan and the exact kernel read (no per-tree level arrays).
+    bool lean = false;
+    int64_t n_sample_enc = 0, n_sample_pos = 0;  // entries of the two threshold samples
     int M = 0, K = 0, T = 0;
     int64_t N = 0, Nd = 0, max_dup = 0;
     std::vector<int32_t> chunk_begin;       // [T+1]
@@ -94,6 +98,10 @@ struct Options {
     int64_t lut_kernel = 0; // 0: matrix cores (expanded form on centred vectors, small entries recomputed), 1: plain (a-b)^2 sums
 };
 
+// entries of the threshold sample for n candidates: the sample pass costs time in proportion to the sample, the
+// candidates it lets through in inverse proportion, so the best size grows like the square root of n
+int64_t sample_size(const Options &opt, int64_t n);
+
 }  // namespace etf
 
 struct etf_ctx {
@@ -127,6 +135,9 @@ namespace etf {
 
 int fail(const etf_ctx *ctx, int code, const char *fmt, ...);
 void compute_layout(etf_ctx *ctx);
+// layout of the image a device-side build of N vectors writes (every array at its largest possible size)
+void lean_layout(const etf_ctx *ctx, int64_t N, DevLayout &L);
+void drop_index(etf_ctx *ctx);
 void prepare_centered(etf_ctx *ctx);
 // calls put(offset, pointer, bytes) for every array of the device image
 void for_each_image_array(const etf_ctx *ctx, const std::function<void(int64_t, const void *, size_t)> &put);

@@ -1,0 +1,190 @@
+"""Index build on the device: the arrays against their definition (sorted distinct encodings, id ranges), and
+searches / all-pairs distances on a device-built index against the oracle and against the host-built index."""
+import numpy as np
+import pytest
+
+import oracle
+from parity import assert_distances_close, assert_topk_matches
+from test_gpu_parity import Problem, qdev, say, FLAT, TREE, FOREST
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import paper_1509_05186_amd as etf  # noqa: E402
+
+
+def dev_ctx(cb, codes, ids=None, T=1, chunk_begin=None, **opts):
+    c = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+    for name, v in opts.items():
+        c.set_option(name, v)
+    c.pq_set_codebooks(cb)
+    img = c.index_build_device(torch.from_numpy(codes).cuda(), None if ids is None else torch.from_numpy(ids).cuda(),
+                               T=T, chunk_begin=chunk_begin)
+    torch.cuda.synchronize()
+    return c, img
+
+
+def arr(img, lay_off, count, dtype):
+    base = (-img.data_ptr()) % 256
+    nbytes = count * np.dtype(dtype).itemsize
+    return img[base + lay_off: base + lay_off + nbytes].cpu().numpy().view(dtype)
+
+
+def check_image(c, img, codes, ids):
+    N, M = codes.shape
+    st, lay = c.index_stats(), c.index_layout()
+    Nd = st["n_distinct"]
+    want_ecodes, inverse, counts = np.unique(codes, axis=0, return_inverse=True, return_counts=True)   # lexicographic
+    assert Nd == len(want_ecodes) and st["N"] == N and st["max_dup"] == counts.max()
+    idv = np.arange(N, dtype=np.int32) if ids is None else ids
+    assert np.array_equal(arr(img, lay.codes, N * M, np.uint8).reshape(N, M), codes)
+    assert np.array_equal(arr(img, lay.ids_in, N, np.int32), idv)
+    assert np.array_equal(arr(img, lay.ecodes, Nd * M, np.uint8).reshape(Nd, M), want_ecodes)
+    assert np.array_equal(arr(img, lay.enc_of_pos, N, np.uint32), inverse.reshape(-1).astype(np.uint32))
+    assert np.array_equal(arr(img, lay.ebegin, Nd + 1, np.uint32), np.concatenate([[0], np.cumsum(counts)]).astype(np.uint32))
+    order = np.lexsort((idv, inverse.reshape(-1)))                      # by encoding, then ascending id
+    assert np.array_equal(arr(img, lay.ids_sorted, N, np.int32), idv[order])
+    # the samples: distinct rows, stored once more as encodings in sample order
+    se = arr(img, lay.sample_enc, lay.n_sample_enc, np.uint32)
+    sp = arr(img, lay.sample_pos, lay.n_sample_pos, np.uint32)
+    assert len(np.unique(se)) == len(se) and se.max() < Nd and len(np.unique(sp)) == len(sp) and sp.max() < N
+    assert np.array_equal(arr(img, lay.sample_enc_codes, len(se) * M, np.uint8).reshape(-1, M), want_ecodes[se])
+    assert np.array_equal(arr(img, lay.sample_pos_codes, len(sp) * M, np.uint8).reshape(-1, M), codes[sp])
+    return st, lay, se, sp
+
+
+@pytest.mark.parametrize("N,M,K,with_ids,seed", [
+    (20000, 8, 256, False, 1),      # the benchmark's code width
+    (5000, 8, 4, True, 2),          # few codewords: many repeated encodings, explicit ids decide their order
+    (3000, 16, 256, False, 3),      # sixteen chunks: two sort passes
+    (3000, 16, 2, True, 4),         # ... with repeats and explicit ids: three
+    (4097, 4, 7, True, 5),          # four chunks, K not a power of two
+    (1, 8, 256, False, 6),          # a single vector
+    (700, 3, 5, True, 7),           # an odd number of chunks (the image is built; no kernel serves the shape)
+])
+def test_device_built_arrays(N, M, K, with_ids, seed):
+    say("device build arrays N", N, "M", M, "K", K, "ids", with_ids)
+    rng = np.random.default_rng(seed)
+    codes = rng.integers(0, K, size=(N, M)).astype(np.uint8)
+    if K > 16:
+        codes[:, : M // 2] //= 64                                          # shared prefixes and some repeats
+        codes[rng.integers(0, N, N // 10)] = codes[rng.integers(0, N, N // 10)]
+    ids = rng.permutation(10 * N + 5)[:N].astype(np.int32) if with_ids else None
+    c, img = dev_ctx(np.zeros((M, K, 1), dtype=np.float32), codes, ids, T=1, sample_min=256)
+    st, lay, se, sp = check_image(c, img, codes, ids)
+    assert lay.rec0 >= 0 and lay.icode[0][0] == -1 and st["trees"][0]["nI"] == [0] * M
+
+
+def test_device_build_sample_sizes_and_spread():
+    say("device build: sample sizes and spread on 300000 vectors")
+    rng = np.random.default_rng(4)
+    N, M, K = 300000, 8, 16
+    codes = rng.integers(0, K, size=(N, M)).astype(np.uint8)
+    codes[:, :3] //= 4
+    c, img = dev_ctx(np.zeros((M, K, 1), dtype=np.float32), codes, None, T=2, sample_min=1000)
+    st, lay, se, sp = check_image(c, img, codes, None)
+    Nd = st["n_distinct"]
+    assert len(se) == int(90 * np.sqrt(Nd)) and len(sp) == int(90 * np.sqrt(N))
+    # one draw from each of len(se) equal strata of the sorted encodings, in scattered order
+    srt, s = np.sort(se.astype(np.int64)), np.arange(len(se), dtype=np.int64)
+    assert np.all(srt >= s * Nd // len(se)) and np.all(srt < (s + 1) * Nd // len(se))
+    assert np.abs(np.diff(se.astype(np.int64))).min() > Nd // (4 * len(se))
+
+
+@pytest.fixture(scope="module")
+def small():
+    return Problem(d=32, M=8, K=256, N=20000, Q=150, ntrain=4000, seed=11)
+
+
+@pytest.mark.parametrize("mode,T", [(FLAT, 1), (TREE, 1), (FOREST, 2), (FOREST, 4)])
+def test_search_on_device_built_index(small, mode, T):
+    say("search on a device-built index, mode", mode, "T", T)
+    p = small
+    c, img = dev_ctx(p.cb, p.codes, None, T=T, sample_min=2048)
+    h = p.ctx(T=T, sample_min=2048)
+    for k in (1, 100):
+        oi, od = c.search(qdev(p), k, mode)
+        hi, hd = h.search(qdev(p), k, mode)
+        torch.cuda.synchronize()
+        oi, od = oi.cpu().numpy(), od.cpu().numpy()
+        for j in range(p.Q):
+            assert_topk_matches(oi[j], od[j], p.ref_all[j], np.arange(p.N), k, "device-built m%d T%d q%d" % (mode, T, j))
+        # same kernels, same arithmetic, another sample: identical lists
+        assert np.array_equal(od, hd.cpu().numpy()) and np.array_equal(oi, hi.cpu().numpy())
+        assert c.last_fallback_count() == 0
+    dist = c.adc(qdev(p), mode)
+    torch.cuda.synchronize()
+    assert_distances_close(dist.cpu().numpy(), p.ref_all, "all pairs on a device-built index")
+    assert torch.equal(dist, h.adc(qdev(p), mode))
+
+
+def test_search_device_built_duplicates_ids_sixteen_chunks():
+    say("device-built index: repeated encodings with explicit ids (M = 4), and M = 16")
+    p = Problem(d=16, M=4, K=4, N=6000, Q=70, ntrain=500, seed=12, dup_factor=3)
+    ids = np.random.default_rng(5).permutation(3 * p.N)[: p.N].astype(np.int32)
+    for mode, T in [(FLAT, 1), (TREE, 1), (FOREST, 2)]:
+        c, _ = dev_ctx(p.cb, p.codes, ids, T=T)
+        oi, od = c.search(qdev(p), 50, mode)
+        torch.cuda.synchronize()
+        for j in range(p.Q):
+            assert_topk_matches(oi[j].cpu().numpy(), od[j].cpu().numpy(), p.ref_all[j], ids, 50, "dups m%d q%d" % (mode, j))
+    w = Problem(d=64, M=16, K=256, N=12000, Q=70, ntrain=3000, seed=13)
+    c, _ = dev_ctx(w.cb, w.codes, None, T=4, sample_min=1024)
+    oi, od = c.search(qdev(w), 20, FOREST)
+    torch.cuda.synchronize()
+    for j in range(w.Q):
+        assert_topk_matches(oi[j].cpu().numpy(), od[j].cpu().numpy(), w.ref_all[j], np.arange(w.N), 20, "M16 q%d" % j)
+
+
+def test_encode_then_build_then_search_all_on_the_device(small):
+    say("vectors -> device encoder -> device build -> search, nothing through the host")
+    p = small
+    c = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+    c.pq_set_codebooks(p.cb)
+    codes = c.pq_encode_device(torch.from_numpy(p.xb).cuda())
+    c.index_build_device(codes, T=2)
+    oi, od = c.search(qdev(p), 10, FOREST)
+    torch.cuda.synchronize()
+    ref = oracle.adc_all(p.q, p.cb, codes.cpu().numpy())      # the float32 encoder may differ from the float64 one on near-ties
+    for j in range(p.Q):
+        assert_topk_matches(oi[j].cpu().numpy(), od[j].cpu().numpy(), ref[j], np.arange(p.N), 10, "all-device q%d" % j)
+
+
+def test_device_build_error_paths(small):
+    say("device build: error paths")
+    p = small
+    c = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+    with pytest.raises(etf.EtfError):
+        c._ck(c._lib.etf_index_build_device_bytes(c._h, 10, None, None))         # no codebooks
+    c.pq_set_codebooks(p.cb)
+    codes = torch.from_numpy(p.codes).cuda()
+    nimg, nws = c.index_build_device_bytes(p.N)
+    with pytest.raises(etf.EtfError):
+        c.index_build_device(codes, T=3)                                          # 3 does not divide 8
+    with pytest.raises(etf.EtfError):
+        c.index_build_device(codes, image=torch.empty(nimg // 2, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(etf.EtfError):
+        c.index_build_device(codes, ws=torch.empty(nws // 2, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(etf.EtfError):
+        c.index_build_device(codes, ids=torch.full((p.N,), -1, dtype=torch.int32, device="cuda"))
+    with pytest.raises(etf.EtfError):
+        c.search(qdev(p), 5, TREE)                                                # every failed build left no index
+    # code bytes beyond K
+    c2 = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+    c2.pq_set_codebooks(np.zeros((8, 5, 1), dtype=np.float32))
+    with pytest.raises(etf.EtfError):
+        c2.index_build_device(torch.full((100, 8), 5, dtype=torch.uint8, device="cuda"))
+    # a device-built index serves the LDS-resident kernels only, and has no host copy
+    c.index_build_device(codes, T=2)
+    with pytest.raises(etf.EtfError):
+        c.index_export()
+    with pytest.raises(etf.EtfError):
+        c.index_upload()
+    c.set_option("traversal", 0)
+    with pytest.raises(etf.EtfError):
+        c.search(qdev(p), 5, FOREST)
+    c.set_option("traversal", 2)
+    c.search(qdev(p), 5, FOREST)
+    c3, _ = dev_ctx(p.cb, p.codes, None, T=3, chunk_begin=[0, 3, 5, 8])
+    with pytest.raises(etf.EtfError):
+        c3.search(qdev(p), 5, FOREST)                                             # unequal trees: no LDS-resident kernel
