@@ -96,6 +96,12 @@ def load_library():
         return _lib
     if not os.path.exists(_LIB_PATH):
         raise ImportError("HIP library %s is missing: run `python -m paper_1509_05186_amd.build`" % _LIB_PATH)
+    try:
+        # torch first: the library must bind to the HIP runtime torch brings along (whichever of the two is
+        # loaded first decides), or its calls see no device in a process where torch holds the GPU
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(_LIB_PATH)
     P, I, L = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
     sig = {
