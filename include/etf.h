@@ -214,33 +214,34 @@ int etf_index_export(const etf_ctx *ctx, void *host_buf, int64_t bytes);
 int64_t etf_encode_workspace_bytes(const etf_ctx *ctx);
 int etf_pq_encode_device(etf_ctx *ctx, const float *x, int64_t n, uint8_t *codes_out, void *ws, int64_t ws_bytes);
 
-/* Index build on the device (paper: "Efficient Encoding Tree Construction": the
- * in-place lexicographic sort of the encoded dataset that Algorithm 1 starts from
- * and the merge of repeated encodings, built in parallel as the closing remark of
- * that section suggests).  Same arguments as etf_index_build, except:
+/* Index build on the device (paper: "Efficient Encoding Tree Construction":
+ * Algorithm 1 — the in-place lexicographic sort of the encoded dataset and the
+ * tree from the common prefixes of consecutive sorted encodings — built in
+ * parallel, as the closing remark of that section suggests: radix sort, then per
+ * level one flag pass over the neighbours' common prefix lengths, a prefix sum that
+ * numbers the nodes, and a scatter).  Same arguments and the same index as
+ * etf_index_build, except:
  *   codes   [N][M] u8, DEVICE (for example the output of etf_pq_encode_device)
  *   ids     [N] non-negative, DEVICE, or NULL for ids = position
  *   chunk_begin  host, as in etf_index_build
- *   image   device, 256-byte aligned, at least *image_bytes of
- *           etf_index_build_device_bytes(); receives the index and becomes the
- *           resident index of the context: no etf_index_upload, and the buffer
- *           must stay alive and unmodified like the one given to etf_index_upload
+ *   image   device, 256-byte aligned; receives the index and becomes the resident
+ *           index of the context: no etf_index_upload, and the buffer must stay
+ *           alive and unmodified like the one given to etf_index_upload.
+ *           *image_bytes of etf_index_build_device_bytes() always suffices (every
+ *           array at its largest: as many distinct encodings as vectors); the
+ *           build uses etf_index_device_bytes() of it, known afterwards, and
+ *           returns ETF_ENOMEM as soon as an array does not fit a smaller buffer
  *   workspace  device scratch, 256-byte aligned, at least *workspace_bytes; free
  *           to reuse when the call returns
- * The image holds the arrays of etf_layout up to sample_pos_codes with the same
- * meaning (codes, ids_in, ids_sorted, ebegin, enc_of_pos, ecodes, the two samples
- * as numbers and as rows, the quantiser tables), each array at the offset its
- * largest possible size needs; the per-tree level arrays are absent (-1 in
- * etf_layout, zero counts in etf_stats).  Searches and all-pairs calls on such an
- * index therefore need option traversal = 2 and a shape the LDS-resident kernels
- * are built for (M in {4, 8, 16}, T in {1, 2, 4} equal trees); any other returns
- * ETF_ESTATE.  etf_index_export and etf_index_upload return ETF_ESTATE.
- * Order of vectors with equal encodings: ascending id, as in etf_index_build.  The
- * threshold samples are drawn differently from the host build's (one row from each
- * of n_sample equal strata), which changes no result.
- * Synchronises the stream (the number of distinct encodings comes back to the
- * host).  On any error the context holds no index. */
-int etf_index_build_device_bytes(const etf_ctx *ctx, int64_t N, int64_t *image_bytes, int64_t *workspace_bytes);
+ * The image has the layout of etf_index_layout, array for array what
+ * etf_index_build + etf_index_upload produce, except the two threshold samples
+ * (one row from each of n_sample equal strata here; which rows are sampled
+ * changes no result).  etf_index_export and etf_index_upload return ETF_ESTATE:
+ * the host holds no copy.
+ * Synchronises the stream several times (the counts that size the arrays come
+ * back to the host).  On any error the context holds no index. */
+int etf_index_build_device_bytes(const etf_ctx *ctx, int64_t N, int T, const int32_t *chunk_begin,
+                                 int64_t *image_bytes, int64_t *workspace_bytes);
 int etf_index_build_device(etf_ctx *ctx, const uint8_t *codes, int64_t N, const int32_t *ids, int T,
                            const int32_t *chunk_begin, void *image, int64_t image_bytes, void *workspace,
                            int64_t workspace_bytes);

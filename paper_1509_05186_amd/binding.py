@@ -123,7 +123,7 @@ def load_library():
         "etf_index_export": (I, [P, P, L]),
         "etf_encode_workspace_bytes": (L, [P]),
         "etf_pq_encode_device": (I, [P, P, L, P, P, L]),
-        "etf_index_build_device_bytes": (I, [P, L, ctypes.POINTER(L), ctypes.POINTER(L)]),
+        "etf_index_build_device_bytes": (I, [P, L, I, P, ctypes.POINTER(L), ctypes.POINTER(L)]),
         "etf_index_build_device": (I, [P, P, L, P, I, P, P, L, P, L]),
         "etf_workspace_bytes": (L, [P, L, I, I]),
         "etf_lut_build": (I, [P, P, L, P]),
@@ -289,10 +289,13 @@ class Context:
         self._ck(self._lib.etf_pq_encode_device(self._h, _dev(x) if n else None, n, _dev(codes) if n else None, p, nb))
         return codes
 
-    def index_build_device_bytes(self, N: int):
-        """(image bytes, workspace bytes) of a device-side build of N vectors."""
+    def index_build_device_bytes(self, N: int, T: int = 1, chunk_begin: Optional[Sequence[int]] = None):
+        """(image bytes that always suffice, workspace bytes) of a device-side build of N vectors."""
         a, b = ctypes.c_int64(0), ctypes.c_int64(0)
-        self._ck(self._lib.etf_index_build_device_bytes(self._h, N, ctypes.byref(a), ctypes.byref(b)))
+        cb = None if chunk_begin is None else np.ascontiguousarray(chunk_begin, dtype=np.int32)
+        if cb is not None and cb.shape != (T + 1,):
+            raise ValueError("chunk_begin must have T+1 entries")
+        self._ck(self._lib.etf_index_build_device_bytes(self._h, N, T, _host(cb), ctypes.byref(a), ctypes.byref(b)))
         return int(a.value), int(b.value)
 
     def index_build_device(self, codes, ids=None, T: int = 1, chunk_begin: Optional[Sequence[int]] = None,
@@ -308,7 +311,7 @@ class Context:
         cb = None if chunk_begin is None else np.ascontiguousarray(chunk_begin, dtype=np.int32)
         if cb is not None and cb.shape != (T + 1,):
             raise ValueError("chunk_begin must have T+1 entries")
-        nimg, nws = self.index_build_device_bytes(N)
+        nimg, nws = self.index_build_device_bytes(N, T, chunk_begin)
         if image is None:
             image = torch.empty(nimg + 256, dtype=torch.uint8, device=codes.device)
         if ws is None:

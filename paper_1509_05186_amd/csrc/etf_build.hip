@@ -1,8 +1,9 @@
-// Index build on the device (Algorithm 1's first half; Section 3.2's remark on building in parallel): the
-// lexicographic sort of the encodings, the merge of repeated encodings into id ranges, and the threshold samples.
-// The sort and the prefix sum are rocPRIM's device-wide radix sort and scan; everything around them is kernels of
-// this file.  The image written here holds what the LDS-resident kernels, the flat scan and the exact kernel read:
-// no per-tree level arrays (those kernels take an encoding's shared prefix from its sorted neighbour instead).
+// Index build on the device (Algorithm 1; the remark on building in parallel that closes "Efficient Encoding Tree
+// Construction"): the lexicographic sort of the encodings, the merge of repeated encodings into id ranges, every
+// tree's level arrays from the longest common prefixes of neighbouring sorted (sub-)encodings, and the threshold
+// samples.  The sorts and the prefix sums are rocPRIM's device-wide radix sort and scan; everything around them is
+// kernels of this file.  The image has the layout the host builder's has (the same layout function, fed with the
+// counts as they come back from the device), so the two are interchangeable byte for byte, samples aside.
 #include <cstring>
 
 #include <hip/hip_runtime.h>
@@ -51,35 +52,41 @@ __global__ void __launch_bounds__(BT) k_build_init(const uint8_t *codes, const i
     if (bad) atomicOr(&scal[2], bad);
 }
 
-// Sort key of the vector at position pos[i].  part 0: its id; part 1: chunks 8.. of its encoding; part 2: chunks
-// 0..7.  Chunks go most significant first, so that integer order is lexicographic order; a part of n chunks
-// fills the low 8 n bits (the sort then leaves out the empty high bits).
-__global__ void __launch_bounds__(BT) k_build_keys(const uint8_t *codes, const int32_t *ids_in, const uint32_t *pos,
-                                                   int64_t N, int M, int part, uint64_t *keys)
+// Sort key of row pos[i]: chunks [c0, c1) of it (at most eight), most significant first, so that integer order is
+// lexicographic order, in the low 8 (c1 - c0) bits (the sort then leaves out the empty high bits); c0 == c1 asks
+// for the row's id instead.
+__global__ void __launch_bounds__(BT) k_build_keys(const uint8_t *rows, int M, const int32_t *ids_in, const uint32_t *pos,
+                                                   int64_t N, int c0, int c1, uint64_t *keys)
 {
     const int64_t i = (int64_t)blockIdx.x * BT + threadIdx.x;
     if (i >= N) return;
     const int64_t p = pos[i];
     uint64_t k = 0;
-    if (part == 0) {
+    if (c0 == c1) {
         k = (uint64_t)(uint32_t)ids_in[p];
     } else {
-        const int c0 = part == 1 ? 8 : 0, c1 = part == 1 ? M : min(M, 8);
-        for (int c = c0; c < c1; ++c) k |= (uint64_t)codes[p * M + c] << (8 * (c1 - 1 - c));
+        for (int c = c0; c < c1; ++c) k |= (uint64_t)rows[p * M + c] << (8 * (c1 - 1 - c));
     }
     keys[i] = k;
 }
 
-// head[i] = 1 where the i-th vector in sorted order starts a new encoding
-__global__ void __launch_bounds__(BT) k_build_heads(const uint8_t *codes, const uint32_t *pos, int64_t N, int M, uint32_t *head)
+__global__ void __launch_bounds__(BT) k_build_iota(uint32_t *pos, int64_t N)
+{
+    const int64_t i = (int64_t)blockIdx.x * BT + threadIdx.x;
+    if (i < N) pos[i] = (uint32_t)i;
+}
+
+// head[i] = 1 where the i-th row in sorted order differs from its predecessor in chunks [c0, c0 + D)
+__global__ void __launch_bounds__(BT) k_build_heads(const uint8_t *rows, const uint32_t *pos, int64_t N, int M, int c0, int D,
+                                                    uint32_t *head)
 {
     const int64_t i = (int64_t)blockIdx.x * BT + threadIdx.x;
     if (i >= N) return;
     uint32_t h = 1;
     if (i > 0) {
-        const uint8_t *a = codes + (int64_t)pos[i] * M, *b = codes + (int64_t)pos[i - 1] * M;
+        const uint8_t *a = rows + (int64_t)pos[i] * M + c0, *b = rows + (int64_t)pos[i - 1] * M + c0;
         h = 0;
-        for (int m = 0; m < M; ++m) h |= a[m] != b[m];
+        for (int m = 0; m < D; ++m) h |= a[m] != b[m];
     }
     head[i] = h;
 }
@@ -112,6 +119,84 @@ __global__ void __launch_bounds__(BT) k_build_maxdup(const uint32_t *ebegin, uin
     uint32_t n = e < (int64_t)scal[0] ? ebegin[e + 1] - ebegin[e] : 0;
     for (int o = 32; o > 0; o >>= 1) n = max(n, (uint32_t)__shfl_xor((int)n, o));
     if ((threadIdx.x & 63) == 0 && n) atomicMax(&scal[1], n);
+}
+
+// ---- one tree over chunks [c0, c0 + D) of the distinct encodings -------------------------------------------------
+// eord: the distinct encodings in the order of their sub-encoding; head/rank as above over that order.  Writes the
+// leaf number of every distinct encoding and the distinct sub-encodings as records padded at the front.
+__global__ void __launch_bounds__(BT) k_tree_records(const uint8_t *ecodes, int M, int c0, int D, const uint32_t *eord,
+                                                     const uint32_t *head, const uint32_t *rank, int64_t Nd,
+                                                     uint32_t *leaf_of, uint8_t *rec, int rstride, int pad)
+{
+    const int64_t i = (int64_t)blockIdx.x * BT + threadIdx.x;
+    if (i >= Nd) return;
+    const int64_t e = eord[i];
+    const uint32_t u = rank[i] - 1;
+    if (leaf_of) leaf_of[e] = u;
+    if (head[i]) {
+        uint8_t *r = rec + (int64_t)u * rstride;
+        for (int j = 0; j < rstride; ++j) r[j] = (j >= pad && j < pad + D) ? ecodes[e * M + c0 + j - pad] : (uint8_t)0;
+    }
+}
+
+// lcp[u] = chunks the u-th sorted sub-encoding shares with its predecessor; lcp[0] = lcp[U] = 0
+__global__ void __launch_bounds__(BT) k_tree_lcp(const uint8_t *rec, int rstride, int pad, int D, int64_t U, uint8_t *lcp)
+{
+    const int64_t u = (int64_t)blockIdx.x * BT + threadIdx.x;
+    if (u > U) return;
+    int n = 0;
+    if (u > 0 && u < U) {
+        const uint8_t *a = rec + u * rstride + pad, *b = a - rstride;
+        while (n < D && a[n] == b[n]) ++n;
+    }
+    lcp[u] = (uint8_t)n;
+}
+
+// Level l (1-based): a prefix group of length l starts at u where lcp[u] < l; it is an internal node when the next
+// sub-encoding still shares it (lcp[u + 1] >= l; only below the last level); u is a leaf of the level at which
+// it is alone in its group, 1 + max(lcp[u], lcp[u + 1]).  flags = internal | leaf << 32: one scan numbers both.
+__global__ void __launch_bounds__(BT) k_tree_flags(const uint8_t *lcp, int64_t U, int l, int D, uint64_t *flags)
+{
+    const int64_t u = (int64_t)blockIdx.x * BT + threadIdx.x;
+    if (u >= U) return;
+    const int a = lcp[u], b = lcp[u + 1];
+    const uint64_t internal = (l < D && a < l && b >= l) ? 1u : 0u;
+    const uint64_t leaf = (1 + max(a, b) == l) ? 1u : 0u;
+    flags[u] = internal | (leaf << 32);
+}
+
+// cur / prev: inclusive scans of this level's and the previous level's flags.  The parent of a node that starts
+// at u is the last internal node of the previous level that starts at or before u (u's own group there: it holds
+// at least two sub-encodings, or u would be a leaf higher up).
+__global__ void __launch_bounds__(BT) k_tree_level(const uint8_t *rec, int rstride, int pad, int D, const uint8_t *lcp,
+                                                   const uint64_t *cur, const uint64_t *prev, int64_t U, int l,
+                                                   uint8_t *icode, uint32_t *iparent, uint8_t *lcodes, int lstride,
+                                                   uint32_t *lparent, uint32_t *lrow)
+{
+    const int64_t u = (int64_t)blockIdx.x * BT + threadIdx.x;
+    if (u >= U) return;
+    const int a = lcp[u], b = lcp[u + 1];
+    const uint32_t parent = l > 1 ? (uint32_t)(prev[u] & 0xFFFFFFFFu) - 1u : 0xFFFFFFFFu;
+    const uint8_t *r = rec + u * rstride + pad;
+    if (l < D && a < l && b >= l) {
+        const uint32_t n = (uint32_t)(cur[u] & 0xFFFFFFFFu) - 1u;
+        icode[n] = r[l - 1];
+        iparent[n] = parent;
+    }
+    if (1 + max(a, b) == l) {
+        const uint32_t n = (uint32_t)(cur[u] >> 32) - 1u;
+        for (int j = 0; j < lstride; ++j) lcodes[(int64_t)n * lstride + j] = j < D - l + 1 ? r[l - 1 + j] : (uint8_t)0;
+        lparent[n] = parent;
+        lrow[n] = (uint32_t)u;
+    }
+}
+
+// tree 0's chunks of every distinct encoding as records padded at the front
+__global__ void __launch_bounds__(BT) k_build_rec0(const uint8_t *ecodes, int M, int D0, int64_t Nd, uint8_t *rec0, int rstride, int pad)
+{
+    const int64_t e = (int64_t)blockIdx.x * BT + threadIdx.x;
+    if (e >= Nd) return;
+    for (int j = 0; j < rstride; ++j) rec0[e * rstride + j] = (j >= pad && j < pad + D0) ? ecodes[e * M + j - pad] : (uint8_t)0;
 }
 
 __device__ inline uint64_t mix64(uint64_t z)
@@ -149,17 +234,20 @@ uint64_t spread_multiplier(int64_t S)
 }
 
 struct BuildWs {
-    int64_t keys[2], pos[2], head, rank, scal, temp, temp_bytes, total;
+    int64_t keys[2], pos[2], head, rank, scal, lcp, flags, scan[2], temp, temp_bytes, total;
 };
 
 int plan_ws(const etf_ctx *ctx, int64_t N, BuildWs &W)
 {
-    size_t t_sort = 0, t_scan = 0;
+    size_t t_sort = 0, t_scan = 0, t_scan64 = 0;
     // size queries: no launch, no device memory touched
     hipError_t e = rocprim::radix_sort_pairs(nullptr, t_sort, (uint64_t *)nullptr, (uint64_t *)nullptr, (uint32_t *)nullptr,
                                              (uint32_t *)nullptr, (size_t)N, 0u, 64u, (hipStream_t)ctx->stream);
     if (e != hipSuccess) return fail(ctx, ETF_EHIP, "radix sort size query: %s", hipGetErrorString(e));
     e = rocprim::inclusive_scan(nullptr, t_scan, (uint32_t *)nullptr, (uint32_t *)nullptr, (size_t)N, rocprim::plus<uint32_t>(),
+                                (hipStream_t)ctx->stream);
+    if (e != hipSuccess) return fail(ctx, ETF_EHIP, "scan size query: %s", hipGetErrorString(e));
+    e = rocprim::inclusive_scan(nullptr, t_scan64, (uint64_t *)nullptr, (uint64_t *)nullptr, (size_t)N, rocprim::plus<uint64_t>(),
                                 (hipStream_t)ctx->stream);
     if (e != hipSuccess) return fail(ctx, ETF_EHIP, "scan size query: %s", hipGetErrorString(e));
     int64_t off = 0;
@@ -175,7 +263,11 @@ int plan_ws(const etf_ctx *ctx, int64_t N, BuildWs &W)
     W.head = take(N * 4);
     W.rank = take(N * 4);
     W.scal = take(16);
-    W.temp_bytes = (int64_t)std::max(t_sort, t_scan);
+    W.lcp = take(N + 1);
+    W.flags = take(N * 8);
+    W.scan[0] = take(N * 8);
+    W.scan[1] = take(N * 8);
+    W.temp_bytes = (int64_t)std::max(std::max(t_sort, t_scan), t_scan64);
     W.temp = take(W.temp_bytes);
     W.total = off;
     return ETF_OK;
@@ -191,34 +283,11 @@ int check_args(const etf_ctx *ctx, int64_t N)
     return ETF_OK;
 }
 
-}  // namespace
-
-extern "C" int etf_index_build_device_bytes(const etf_ctx *ctx, int64_t N, int64_t *image_bytes, int64_t *workspace_bytes)
+int check_trees(const etf_ctx *ctx, int T, const int32_t *chunk_begin, std::vector<int32_t> &cb)
 {
-    int rc = check_args(ctx, N);
-    if (rc) return rc;
-    if (!image_bytes || !workspace_bytes) return fail(ctx, ETF_EINVAL, "output pointer is null");
-    HIP_TRY(ctx, hipSetDevice(ctx->device));
-    DevLayout L;
-    lean_layout(ctx, N, L);
-    BuildWs W;
-    rc = plan_ws(ctx, N, W);
-    if (rc) return rc;
-    *image_bytes = L.total;
-    *workspace_bytes = W.total;
-    return ETF_OK;
-}
-
-extern "C" int etf_index_build_device(etf_ctx *ctx, const uint8_t *codes, int64_t N, const int32_t *ids, int T,
-                                      const int32_t *chunk_begin, void *image, int64_t image_bytes, void *workspace,
-                                      int64_t workspace_bytes)
-{
-    int rc = check_args(ctx, N);
-    if (rc) return rc;
-    const int M = ctx->M, K = ctx->K;
-    if (!codes) return fail(ctx, ETF_EINVAL, "codes is null");
+    const int M = ctx->M;
     if (T < 1 || T > M) return fail(ctx, ETF_EINVAL, "need 1 <= T <= M (T=%d, M=%d)", T, M);
-    std::vector<int32_t> cb(T + 1);
+    cb.resize(T + 1);
     if (chunk_begin) {
         for (int t = 0; t <= T; ++t) cb[t] = chunk_begin[t];
         if (cb[0] != 0 || cb[T] != M) return fail(ctx, ETF_EINVAL, "chunk_begin must run from 0 to M");
@@ -228,21 +297,63 @@ extern "C" int etf_index_build_device(etf_ctx *ctx, const uint8_t *codes, int64_
         if (M % T != 0) return fail(ctx, ETF_EINVAL, "T=%d does not divide M=%d and no chunk_begin was given", T, M);
         for (int t = 0; t <= T; ++t) cb[t] = t * (M / T);
     }
-    if (!image || !workspace) return fail(ctx, ETF_EINVAL, "image or workspace is null");
-    if ((((uintptr_t)image | (uintptr_t)workspace) & 255) != 0) return fail(ctx, ETF_EINVAL, "image and workspace must be 256-byte aligned");
-    HIP_TRY(ctx, hipSetDevice(ctx->device));
-    DevLayout L;
-    lean_layout(ctx, N, L);
-    BuildWs W;
-    rc = plan_ws(ctx, N, W);
-    if (rc) return rc;
-    if (image_bytes < L.total) return fail(ctx, ETF_ENOMEM, "image buffer too small: %lld < %lld", (long long)image_bytes, (long long)L.total);
-    if (workspace_bytes < W.total) return fail(ctx, ETF_ENOMEM, "workspace too small: %lld < %lld", (long long)workspace_bytes, (long long)W.total);
+    return ETF_OK;
+}
 
-    drop_index(ctx);
+// stable sort of (keys gathered through pos[cur]) with the positions as payload; flips cur
+int sort_pass(etf_ctx *ctx, const BuildWs &W, char *ws, const uint8_t *rows, int M, const int32_t *ids_in, int64_t n, int c0,
+              int c1, int &cur)
+{
     hipStream_t st = (hipStream_t)ctx->stream;
-    char *img = (char *)image, *ws = (char *)workspace;
     uint64_t *keys[2] = {(uint64_t *)(ws + W.keys[0]), (uint64_t *)(ws + W.keys[1])};
+    uint32_t *pos[2] = {(uint32_t *)(ws + W.pos[0]), (uint32_t *)(ws + W.pos[1])};
+    hipLaunchKernelGGL(k_build_keys, dim3(blocks(n)), dim3(BT), 0, st, rows, M, ids_in, pos[cur], n, c0, c1, keys[0]);
+    HIP_TRY(ctx, hipGetLastError());
+    const unsigned bits = c0 == c1 ? 32u : (unsigned)(8 * (c1 - c0));
+    size_t tb = 0;
+    HIP_TRY(ctx, rocprim::radix_sort_pairs(nullptr, tb, keys[0], keys[1], pos[cur], pos[cur ^ 1], (size_t)n, 0u, bits, st));
+    if ((int64_t)tb > W.temp_bytes) return fail(ctx, ETF_ENOMEM, "radix sort scratch: %lld > %lld", (long long)tb, (long long)W.temp_bytes);
+    tb = (size_t)W.temp_bytes;
+    HIP_TRY(ctx, rocprim::radix_sort_pairs(ws + W.temp, tb, keys[0], keys[1], pos[cur], pos[cur ^ 1], (size_t)n, 0u, bits, st));
+    cur ^= 1;
+    return ETF_OK;
+}
+
+int build_impl(etf_ctx *ctx, const uint8_t *codes, int64_t N, const int32_t *ids, int T, const std::vector<int32_t> &cb,
+               char *img, int64_t image_bytes, char *ws, const BuildWs &W)
+{
+    const int M = ctx->M, K = ctx->K;
+    hipStream_t st = (hipStream_t)ctx->stream;
+    HostIndex &ix = ctx->idx;
+    ix.M = M; ix.K = K; ix.T = T; ix.N = N;
+    ix.chunk_begin = cb;
+    ix.device_built = true;
+    ix.rstride0 = std::max(4, depth_class(cb[1] - cb[0]));
+    ix.tree.assign(T, HostTree());
+    for (int t = 0; t < T; ++t) {
+        HostTree &tr = ix.tree[t];
+        tr.c0 = cb[t];
+        tr.D = cb[t + 1] - cb[t];
+        tr.rstride = std::max(4, depth_class(tr.D));
+        tr.level.assign(tr.D, HostLevel());
+        tr.bucket.assign(tr.D, HostBucket());
+        tr.nI.assign(tr.D, 0);
+        tr.nL.assign(tr.D, 0);
+        for (int l = 0; l < tr.D; ++l) {
+            tr.bucket[l].width = tr.D - l;
+            tr.bucket[l].stride = (tr.bucket[l].width + 3) & ~3;
+        }
+    }
+    // The layout grows with the counts: arrays whose sizes are known keep their offsets when later counts arrive.
+    const DevLayout &L = ctx->lay;
+    auto fits = [&](int64_t upto, const char *what) -> int {
+        if (upto > image_bytes) return fail(ctx, ETF_ENOMEM, "image buffer too small for %s: %lld > %lld", what, (long long)upto, (long long)image_bytes);
+        return ETF_OK;
+    };
+    compute_layout(ctx);
+    int rc = fits(L.ebegin, "the input codes and ids");   // codes, ids_in, ids_sorted end where ebegin starts
+    if (rc) return rc;
+
     uint32_t *pos[2] = {(uint32_t *)(ws + W.pos[0]), (uint32_t *)(ws + W.pos[1])};
     uint32_t *head = (uint32_t *)(ws + W.head), *rank = (uint32_t *)(ws + W.rank), *scal = (uint32_t *)(ws + W.scal);
     uint8_t *d_codes = (uint8_t *)(img + L.codes);
@@ -266,27 +377,32 @@ extern "C" int etf_index_build_device(etf_ctx *ctx, const uint8_t *codes, int64_
     // (encoding, id) order by stable least-significant-part-first passes: id (only when ids are given: positions
     // ascend already), chunks 8.. (only when there are any), chunks 0..7
     int cur = 0;
-    for (int part = ids ? 0 : 1; part <= 2; ++part) {
-        if (part == 1 && M <= 8) continue;
-        const int nchunks = part == 1 ? M - 8 : std::min(M, 8);
-        const unsigned b0 = 0u, b1 = part == 0 ? 32u : (unsigned)(8 * nchunks);
-        hipLaunchKernelGGL(k_build_keys, dim3(nb), dim3(BT), 0, st, d_codes, d_ids_in, pos[cur], N, M, part, keys[0]);
-        HIP_TRY(ctx, hipGetLastError());
-        size_t tb = 0;
-        HIP_TRY(ctx, rocprim::radix_sort_pairs(nullptr, tb, keys[0], keys[1], pos[cur], pos[cur ^ 1], (size_t)N, b0, b1, st));
-        if ((int64_t)tb > W.temp_bytes) return fail(ctx, ETF_ENOMEM, "radix sort scratch: %lld > %lld", (long long)tb, (long long)W.temp_bytes);
-        tb = (size_t)W.temp_bytes;
-        HIP_TRY(ctx, rocprim::radix_sort_pairs(ws + W.temp, tb, keys[0], keys[1], pos[cur], pos[cur ^ 1], (size_t)N, b0, b1, st));
-        cur ^= 1;
-    }
+    if (ids && (rc = sort_pass(ctx, W, ws, d_codes, M, d_ids_in, N, 0, 0, cur))) return rc;
+    if (M > 8 && (rc = sort_pass(ctx, W, ws, d_codes, M, d_ids_in, N, 8, M, cur))) return rc;
+    if ((rc = sort_pass(ctx, W, ws, d_codes, M, d_ids_in, N, 0, std::min(M, 8), cur))) return rc;
     const uint32_t *spos = pos[cur];
 
-    hipLaunchKernelGGL(k_build_heads, dim3(nb), dim3(BT), 0, st, d_codes, spos, N, M, head);
+    hipLaunchKernelGGL(k_build_heads, dim3(nb), dim3(BT), 0, st, d_codes, spos, N, M, 0, M, head);
     HIP_TRY(ctx, hipGetLastError());
     {
         size_t tb = (size_t)W.temp_bytes;
         HIP_TRY(ctx, rocprim::inclusive_scan(ws + W.temp, tb, head, rank, (size_t)N, rocprim::plus<uint32_t>(), st));
     }
+    uint32_t h_scal[4] = {0, 0, 0, 0};
+    HIP_TRY(ctx, hipMemcpyAsync(&h_scal[0], rank + (N - 1), 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipMemcpyAsync(&h_scal[2], scal + 2, 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    if (h_scal[2] & 1u) return fail(ctx, ETF_EINVAL, "a code byte is >= K=%d", K);
+    if (h_scal[2] & 2u) return fail(ctx, ETF_EINVAL, "ids must be non-negative");
+    const int64_t Nd = h_scal[0];
+    if (Nd < 1 || Nd > N) return fail(ctx, ETF_EHIP, "device build returned %lld distinct encodings for %lld vectors", (long long)Nd, (long long)N);
+    ix.Nd = Nd;
+    ix.n_sample_enc = std::min(Nd, sample_size(ctx->opt, Nd));
+    ix.n_sample_pos = std::min(N, sample_size(ctx->opt, N));
+    compute_layout(ctx);
+    rc = fits(L.tree[0].leaf_of >= 0 ? L.tree[0].leaf_of : L.tree[0].rec, "the sorted encodings");
+    if (rc) return rc;
+
     uint32_t *d_ebegin = (uint32_t *)(img + L.ebegin);
     uint8_t *d_ecodes = (uint8_t *)(img + L.ecodes);
     hipLaunchKernelGGL(k_build_scatter, dim3(nb), dim3(BT), 0, st, d_codes, d_ids_in, spos, head, rank, N, M,
@@ -294,17 +410,10 @@ extern "C" int etf_index_build_device(etf_ctx *ctx, const uint8_t *codes, int64_
     HIP_TRY(ctx, hipGetLastError());
     hipLaunchKernelGGL(k_build_maxdup, dim3(nb), dim3(BT), 0, st, d_ebegin, scal);
     HIP_TRY(ctx, hipGetLastError());
-
-    uint32_t h_scal[4] = {0, 0, 0, 0};
-    HIP_TRY(ctx, hipMemcpyAsync(h_scal, scal, 16, hipMemcpyDeviceToHost, st));
-    HIP_TRY(ctx, hipStreamSynchronize(st));
-    if (h_scal[2] & 1u) return fail(ctx, ETF_EINVAL, "a code byte is >= K=%d", K);
-    if (h_scal[2] & 2u) return fail(ctx, ETF_EINVAL, "ids must be non-negative");
-    const int64_t Nd = h_scal[0], max_dup = h_scal[1];
-    if (Nd < 1 || Nd > N || max_dup < 1) return fail(ctx, ETF_EHIP, "device build returned %lld distinct encodings for %lld vectors", (long long)Nd, (long long)N);
+    HIP_TRY(ctx, hipMemcpyAsync(&h_scal[1], scal + 1, 4, hipMemcpyDeviceToHost, st));  // read at the next synchronisation
 
     // threshold samples (of the distinct encodings for the tree modes, of the input positions for the flat scan)
-    const int64_t S_enc = std::min(Nd, sample_size(ctx->opt, Nd)), S_pos = std::min(N, sample_size(ctx->opt, N));
+    const int64_t S_enc = ix.n_sample_enc, S_pos = ix.n_sample_pos;
     const uint64_t seed = 0x1509051860ull ^ (uint64_t)N;
     hipLaunchKernelGGL(k_build_sample, dim3(blocks(S_enc)), dim3(BT), 0, st, d_ecodes, Nd, M, S_enc, spread_multiplier(S_enc),
                        (uint64_t)(S_enc / 3), seed, (uint32_t *)(img + L.sample_enc), (uint8_t *)(img + L.sample_enc_codes));
@@ -312,22 +421,129 @@ extern "C" int etf_index_build_device(etf_ctx *ctx, const uint8_t *codes, int64_
     hipLaunchKernelGGL(k_build_sample, dim3(blocks(S_pos)), dim3(BT), 0, st, d_codes, N, M, S_pos, spread_multiplier(S_pos),
                        (uint64_t)(S_pos / 3), seed ^ 0x5DEECE66Dull, (uint32_t *)(img + L.sample_pos), (uint8_t *)(img + L.sample_pos_codes));
     HIP_TRY(ctx, hipGetLastError());
-    HIP_TRY(ctx, hipStreamSynchronize(st));
+    hipLaunchKernelGGL(k_build_rec0, dim3(blocks(Nd)), dim3(BT), 0, st, d_ecodes, M, cb[1] - cb[0], Nd, (uint8_t *)(img + L.rec0),
+                       ix.rstride0, depth_class(cb[1] - cb[0]) - (cb[1] - cb[0]));
+    HIP_TRY(ctx, hipGetLastError());
 
-    HostIndex &ix = ctx->idx;
-    ix.M = M; ix.K = K; ix.T = T; ix.N = N; ix.Nd = Nd; ix.max_dup = max_dup;
-    ix.chunk_begin = cb;
-    ix.n_sample_enc = S_enc;
-    ix.n_sample_pos = S_pos;
-    ix.tree.assign(T, HostTree());
+    // ---- the trees
+    uint8_t *lcp = (uint8_t *)(ws + W.lcp);
+    uint64_t *flags = (uint64_t *)(ws + W.flags);
+    uint64_t *scan[2] = {(uint64_t *)(ws + W.scan[0]), (uint64_t *)(ws + W.scan[1])};
+    const unsigned nbd = blocks(Nd);
     for (int t = 0; t < T; ++t) {
-        ix.tree[t].c0 = cb[t];
-        ix.tree[t].D = cb[t + 1] - cb[t];
+        HostTree &tr = ix.tree[t];
+        const int c0 = tr.c0, D = tr.D, pad = depth_class(D) - D;
+        // the distinct encodings in the order of this tree's chunks (tree 0's are a prefix: sorted already)
+        cur = 0;
+        hipLaunchKernelGGL(k_build_iota, dim3(nbd), dim3(BT), 0, st, pos[0], Nd);
+        HIP_TRY(ctx, hipGetLastError());
+        if (t > 0) {
+            if (D > 8 && (rc = sort_pass(ctx, W, ws, d_ecodes, M, nullptr, Nd, c0 + 8, c0 + D, cur))) return rc;
+            if ((rc = sort_pass(ctx, W, ws, d_ecodes, M, nullptr, Nd, c0, c0 + std::min(D, 8), cur))) return rc;
+        }
+        const uint32_t *eord = pos[cur];
+        hipLaunchKernelGGL(k_build_heads, dim3(nbd), dim3(BT), 0, st, d_ecodes, eord, Nd, M, c0, D, head);
+        HIP_TRY(ctx, hipGetLastError());
+        {
+            size_t tb = (size_t)W.temp_bytes;
+            HIP_TRY(ctx, rocprim::inclusive_scan(ws + W.temp, tb, head, rank, (size_t)Nd, rocprim::plus<uint32_t>(), st));
+        }
+        uint32_t h_U = 0;
+        HIP_TRY(ctx, hipMemcpyAsync(&h_U, rank + (Nd - 1), 4, hipMemcpyDeviceToHost, st));
+        HIP_TRY(ctx, hipStreamSynchronize(st));
+        const int64_t U = h_U;
+        if (U < 1 || U > Nd || (T == 1 && U != Nd)) return fail(ctx, ETF_EHIP, "device build: tree %d has %lld leaves for %lld encodings", t, (long long)U, (long long)Nd);
+        tr.U = U;
+        compute_layout(ctx);
+        const DevTreeLayout TL = L.tree[t];
+        rc = fits(TL.icode[0], "a tree's records");   // leaf_of and rec end where the first level starts
+        if (rc) return rc;
+        uint8_t *rec = (uint8_t *)(img + TL.rec);
+        hipLaunchKernelGGL(k_tree_records, dim3(nbd), dim3(BT), 0, st, d_ecodes, M, c0, D, eord, head, rank, Nd,
+                           TL.leaf_of >= 0 ? (uint32_t *)(img + TL.leaf_of) : nullptr, rec, tr.rstride, pad);
+        HIP_TRY(ctx, hipGetLastError());
+        hipLaunchKernelGGL(k_tree_lcp, dim3(blocks(U + 1)), dim3(BT), 0, st, rec, tr.rstride, pad, D, U, lcp);
+        HIP_TRY(ctx, hipGetLastError());
+        const unsigned nbu = blocks(U);
+        int sc = 0;
+        for (int l = 1; l <= D; ++l) {
+            hipLaunchKernelGGL(k_tree_flags, dim3(nbu), dim3(BT), 0, st, lcp, U, l, D, flags);
+            HIP_TRY(ctx, hipGetLastError());
+            size_t tb = (size_t)W.temp_bytes;
+            HIP_TRY(ctx, rocprim::inclusive_scan(ws + W.temp, tb, flags, scan[sc], (size_t)U, rocprim::plus<uint64_t>(), st));
+            uint64_t tot = 0;
+            HIP_TRY(ctx, hipMemcpyAsync(&tot, scan[sc] + (U - 1), 8, hipMemcpyDeviceToHost, st));
+            HIP_TRY(ctx, hipStreamSynchronize(st));
+            tr.nI[l - 1] = (int64_t)(tot & 0xFFFFFFFFu);
+            tr.nL[l - 1] = (int64_t)(tot >> 32);
+            compute_layout(ctx);
+            const DevTreeLayout TL2 = L.tree[t];
+            rc = fits(TL2.lrow[l - 1] + tr.nL[l - 1] * 4, "a tree level");
+            if (rc) return rc;
+            hipLaunchKernelGGL(k_tree_level, dim3(nbu), dim3(BT), 0, st, rec, tr.rstride, pad, D, lcp, scan[sc], scan[sc ^ 1], U, l,
+                               (uint8_t *)(img + TL2.icode[l - 1]), (uint32_t *)(img + TL2.iparent[l - 1]),
+                               (uint8_t *)(img + TL2.lcodes[l - 1]), tr.bucket[l - 1].stride,
+                               (uint32_t *)(img + TL2.lparent[l - 1]), (uint32_t *)(img + TL2.lrow[l - 1]));
+            HIP_TRY(ctx, hipGetLastError());
+            sc ^= 1;
+        }
+        int64_t leaves = 0;
+        for (int l = 0; l < D; ++l) leaves += tr.nL[l];
+        if (leaves != U) return fail(ctx, ETF_EHIP, "device build: tree %d has %lld leaves in its levels, %lld sub-encodings", t, (long long)leaves, (long long)U);
     }
-    ix.lean = true;
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    compute_layout(ctx);
+    rc = fits(L.total, "the index");
+    if (rc) return rc;
+    ix.max_dup = h_scal[1];
+    if (ix.max_dup < 1) return fail(ctx, ETF_EHIP, "device build: no id range");
     ix.built = true;
-    L.tree.assign(T, DevTreeLayout());
-    ctx->lay = L;
     ctx->dev_base = img;
     return ETF_OK;
+}
+
+}  // namespace
+
+extern "C" int etf_index_build_device_bytes(const etf_ctx *ctx, int64_t N, int T, const int32_t *chunk_begin,
+                                            int64_t *image_bytes, int64_t *workspace_bytes)
+{
+    int rc = check_args(ctx, N);
+    if (rc) return rc;
+    if (!image_bytes || !workspace_bytes) return fail(ctx, ETF_EINVAL, "output pointer is null");
+    std::vector<int32_t> cb;
+    rc = check_trees(ctx, T, chunk_begin, cb);
+    if (rc) return rc;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    BuildWs W;
+    rc = plan_ws(ctx, N, W);
+    if (rc) return rc;
+    *image_bytes = image_bytes_bound(ctx, N, T, cb.data());
+    *workspace_bytes = W.total;
+    return ETF_OK;
+}
+
+extern "C" int etf_index_build_device(etf_ctx *ctx, const uint8_t *codes, int64_t N, const int32_t *ids, int T,
+                                      const int32_t *chunk_begin, void *image, int64_t image_bytes, void *workspace,
+                                      int64_t workspace_bytes)
+{
+    int rc = check_args(ctx, N);
+    if (rc) return rc;
+    if (!codes) return fail(ctx, ETF_EINVAL, "codes is null");
+    std::vector<int32_t> cb;
+    rc = check_trees(ctx, T, chunk_begin, cb);
+    if (rc) return rc;
+    if (!image || !workspace) return fail(ctx, ETF_EINVAL, "image or workspace is null");
+    if ((((uintptr_t)image | (uintptr_t)workspace) & 255) != 0) return fail(ctx, ETF_EINVAL, "image and workspace must be 256-byte aligned");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    BuildWs W;
+    rc = plan_ws(ctx, N, W);
+    if (rc) return rc;
+    if (workspace_bytes < W.total) return fail(ctx, ETF_ENOMEM, "workspace too small: %lld < %lld", (long long)workspace_bytes, (long long)W.total);
+    drop_index(ctx);
+    rc = build_impl(ctx, codes, N, ids, T, cb, (char *)image, image_bytes, (char *)workspace, W);
+    if (rc) {
+        (void)hipStreamSynchronize((hipStream_t)ctx->stream);  // nothing of a failed build may still be running in the buffers
+        drop_index(ctx);
+    }
+    return rc;
 }

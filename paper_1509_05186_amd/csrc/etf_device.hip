@@ -138,7 +138,7 @@ extern "C" int etf_index_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes)
     int rc = need_device(ctx);
     if (rc) return rc;
     if (!ctx->idx.built) return fail(ctx, ETF_ESTATE, "no index: call etf_index_build first");
-    if (ctx->idx.lean) return fail(ctx, ETF_ESTATE, "the index was built on the device and is resident already");
+    if (ctx->idx.device_built) return fail(ctx, ETF_ESTATE, "the index was built on the device and is resident already");
     if (!dev_buf) return fail(ctx, ETF_EINVAL, "device buffer is null");
     if (((uintptr_t)dev_buf & 255) != 0) return fail(ctx, ETF_EINVAL, "device buffer must be 256-byte aligned");
     if (bytes < ctx->lay.total) return fail(ctx, ETF_ENOMEM, "device buffer too small: %lld < %lld", (long long)bytes, (long long)ctx->lay.total);
@@ -235,10 +235,6 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     // it means the register-context kernels, like traversal 0
     P.lds_path = mode != ETF_MODE_FLAT && ctx->opt.traversal == 2 && lds_eligible(M, K, ix.T, ix.chunk_begin.data());
     P.flat_lds = mode == ETF_MODE_FLAT && ctx->opt.traversal == 2 && lds_eligible(M, K, 1, nullptr);
-    if (ix.lean && !(mode == ETF_MODE_FLAT ? P.flat_lds : P.lds_path))
-        return fail(ctx, ETF_ESTATE, "an index built on the device holds no per-tree level arrays: it serves option traversal = 2 "
-                                     "on the shapes the LDS-resident kernels are built for (M = %d, K = %d, T = %d is %s)",
-                    M, K, ix.T, lds_eligible(M, K, mode == ETF_MODE_FLAT ? 1 : ix.T, mode == ETF_MODE_FLAT ? nullptr : ix.chunk_begin.data()) ? "one of them" : "not one of them");
     P.ctx_path = !P.lds_path && tmax_class(ix.T) != 0 && mode != ETF_MODE_FLAT && ctx->opt.traversal != 1;
     for (int t = 1; t < ix.T; ++t)  // the register-context kernels address a tree's result table with 32-bit offsets
         if (ix.tree[t].U >= ((int64_t)1 << 24)) P.ctx_path = false;
@@ -247,7 +243,7 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
         for (int t = P.ctx_path ? 1 : 0; t < ix.T; ++t) {
             const HostTree &tr = ix.tree[t];
             if (!P.ctx_path)
-                for (int l = 0; l + 1 < tr.D; ++l) per_tile += al256((int64_t)tr.level[l].code.size() * QT * 4);
+                for (int l = 0; l + 1 < tr.D; ++l) per_tile += al256(tr.nI[l] * QT * 4);
             per_tile += al256(tr.U * QT * 4);
         }
     if (search) {
@@ -269,7 +265,7 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
         for (int t = P.ctx_path ? 1 : 0; t < ix.T; ++t) {
             const HostTree &tr = ix.tree[t];
             if (!P.ctx_path)
-                for (int l = 0; l + 1 < tr.D; ++l) P.o_part[t][l] = take(P.NT * (int64_t)tr.level[l].code.size() * QT * 4);
+                for (int l = 0; l + 1 < tr.D; ++l) P.o_part[t][l] = take(P.NT * tr.nI[l] * QT * 4);
             P.o_leafp[t] = take(P.NT * tr.U * QT * 4);
         }
     if (search) {
@@ -372,12 +368,12 @@ int launch_trees(etf_ctx *ctx, const Plan &P, char *ws, int64_t tiles)
         const DevTreeLayout &TL = L.tree[t];
         // internal levels, top down
         for (int l = 0; l + 1 < tr.D; ++l) {
-            const int64_t n = (int64_t)tr.level[l].code.size();
+            const int64_t n = tr.nI[l];
             if (n == 0) break;  // no internal node at this level: none below either
             const int64_t bx = blocks_for(n, 4 * 32, tiles);
             const int per_wave = (int)((n + bx * 4 - 1) / (bx * 4));
             const float *prev = l > 0 ? reinterpret_cast<const float *>(ws + P.o_part[t][l - 1]) : nullptr;
-            const int64_t nprev = l > 0 ? (int64_t)tr.level[l - 1].code.size() : 0;
+            const int64_t nprev = l > 0 ? tr.nI[l - 1] : 0;
             ProfScope prof(ctx, ETF_K_LEVEL);
             hipLaunchKernelGGL(k_level, dim3((unsigned)bx, (unsigned)tiles), dim3(256), 0, st,
                                reinterpret_cast<const uint8_t *>(ctx->dev_base + TL.icode[l]),
@@ -388,10 +384,10 @@ int launch_trees(etf_ctx *ctx, const Plan &P, char *ws, int64_t tiles)
         // leaf buckets
         for (int l = 0; l < tr.D; ++l) {
             const HostBucket &B = tr.bucket[l];
-            const int64_t n = (int64_t)B.size();
+            const int64_t n = tr.nL[l];
             if (n == 0) continue;
             const float *prev = l > 0 ? reinterpret_cast<const float *>(ws + P.o_part[t][l - 1]) : nullptr;
-            const int64_t nprev = l > 0 ? (int64_t)tr.level[l - 1].code.size() : 0;
+            const int64_t nprev = l > 0 ? tr.nI[l - 1] : 0;
             const uint8_t *lc = reinterpret_cast<const uint8_t *>(ctx->dev_base + TL.lcodes[l]);
             const uint32_t *lp = reinterpret_cast<const uint32_t *>(ctx->dev_base + TL.lparent[l]);
             const uint32_t *lr = reinterpret_cast<const uint32_t *>(ctx->dev_base + TL.lrow[l]);

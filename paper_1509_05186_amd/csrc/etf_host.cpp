@@ -180,6 +180,12 @@ static void build_tree(const std::vector<KeyRec> &sub /* sorted, distinct keys *
         B.row.push_back((uint32_t)i);
         lcp_prev = lcp_next;
     }
+    tr.nI.resize(D);
+    tr.nL.resize(D);
+    for (int l = 0; l < D; ++l) {
+        tr.nI[l] = (int64_t)tr.level[l].code.size();
+        tr.nL[l] = (int64_t)tr.bucket[l].size();
+    }
     // the same leaves as plain padded records in lexicographic order (register-context traversal)
     // (padded at the front to the unrolled depth, so that the deepest level is always the last slot)
     tr.rstride = std::max(4, depth_class(D));
@@ -224,33 +230,33 @@ int64_t sample_size(const Options &opt, int64_t n)
     return std::max<int64_t>(opt.sample_min, (int64_t)((double)opt.sample_scale * std::sqrt((double)n)));
 }
 
-void lean_layout(const etf_ctx *ctx, int64_t N, DevLayout &L)
+// Every array at its largest: as many distinct encodings as vectors, every tree with as many leaves, every
+// internal level with half as many nodes (an internal node has at least two encodings below it).
+int64_t image_bytes_bound(const etf_ctx *ctx, int64_t N, int T, const int32_t *chunk_begin)
 {
-    int64_t off = 0;
-    auto take = [&](int64_t bytes) {
-        int64_t o = off;
-        off = align256(off + std::max<int64_t>(bytes, 4));
-        return o;
-    };
     const int M = ctx->M;
     const int64_t S = std::min(N, sample_size(ctx->opt, N));
-    L = DevLayout();
-    L.codebooks = take((int64_t)ctx->codebooks.size() * 4);
-    L.cb_centered = take((int64_t)ctx->cb_centered.size() * 4);
-    L.cb_norm = take((int64_t)ctx->cb_norm.size() * 4);
-    L.cb_mean = take((int64_t)ctx->cb_mean.size() * 4);
-    L.codes = take(N * M);
-    L.ids_in = take(N * 4);
-    L.ids_sorted = take(N * 4);
-    L.ebegin = take((N + 1) * 4);
-    L.enc_of_pos = take(N * 4);
-    L.ecodes = take(N * M);
-    L.sample_enc = take(S * 4);
-    L.sample_pos = take(S * 4);
-    L.sample_enc_codes = take(S * M);
-    L.sample_pos_codes = take(S * M);
-    L.rec0 = take(0);
-    L.total = off;
+    int64_t tot = 0;
+    auto take = [&](int64_t bytes) { tot = align256(tot + std::max<int64_t>(bytes, 4)); };
+    take((int64_t)ctx->codebooks.size() * 4);
+    take((int64_t)ctx->cb_centered.size() * 4);
+    take((int64_t)ctx->cb_norm.size() * 4);
+    take((int64_t)ctx->cb_mean.size() * 4);
+    take(N * M); take(N * 4); take(N * 4); take((N + 1) * 4); take(N * 4); take(N * M);
+    take(S * 4); take(S * 4); take(S * M); take(S * M);
+    take(N * std::max(4, depth_class(chunk_begin[1] - chunk_begin[0])));
+    for (int t = 0; t < T; ++t) {
+        const int D = chunk_begin[t + 1] - chunk_begin[t];
+        if (T > 1) take(N * 4);
+        take(N * std::max(4, depth_class(D)));
+        for (int l = 0; l < D; ++l) {
+            take(l + 1 < D ? N / 2 : 0);
+            take(l + 1 < D ? N / 2 * 4 : 0);
+        }
+        // the leaves of all levels together are N; every level's arrays may round up to the next 256 bytes
+        tot += N * ((D + 3) & ~3) + N * 4 + N * 4 + (int64_t)D * 3 * 256;
+    }
+    return tot;
 }
 
 void compute_layout(etf_ctx *ctx)
@@ -267,29 +273,30 @@ void compute_layout(etf_ctx *ctx)
     L.cb_centered = take((int64_t)ctx->cb_centered.size() * 4);
     L.cb_norm = take((int64_t)ctx->cb_norm.size() * 4);
     L.cb_mean = take((int64_t)ctx->cb_mean.size() * 4);
-    L.codes = take((int64_t)ix.codes.size());
+    const int M = ix.M;
+    L.codes = take(ix.N * M);
     L.ids_in = take(ix.N * 4);
     L.ids_sorted = take(ix.N * 4);
     L.ebegin = take((ix.Nd + 1) * 4);
     L.enc_of_pos = take(ix.N * 4);
-    L.ecodes = take((int64_t)ix.ecodes.size());
-    L.sample_enc = take((int64_t)ix.sample_enc.size() * 4);
-    L.sample_pos = take((int64_t)ix.sample_pos.size() * 4);
-    L.sample_enc_codes = take((int64_t)ix.sample_enc_codes.size());
-    L.sample_pos_codes = take((int64_t)ix.sample_pos_codes.size());
-    L.rec0 = take((int64_t)ix.rec0.size());
+    L.ecodes = take(ix.Nd * M);
+    L.sample_enc = take(ix.n_sample_enc * 4);
+    L.sample_pos = take(ix.n_sample_pos * 4);
+    L.sample_enc_codes = take(ix.n_sample_enc * M);
+    L.sample_pos_codes = take(ix.n_sample_pos * M);
+    L.rec0 = take(ix.Nd * ix.rstride0);
     L.tree.assign(ix.T, DevTreeLayout());
     for (int t = 0; t < ix.T; ++t) {
         const HostTree &tr = ix.tree[t];
         DevTreeLayout &TL = L.tree[t];
-        TL.leaf_of = tr.leaf_of.empty() ? -1 : take((int64_t)tr.leaf_of.size() * 4);
-        TL.rec = take((int64_t)tr.rec.size());
+        TL.leaf_of = ix.T == 1 ? -1 : take(ix.Nd * 4);
+        TL.rec = take(tr.U * tr.rstride);
         for (int l = 0; l < tr.D; ++l) {
-            TL.icode[l] = take((int64_t)tr.level[l].code.size());
-            TL.iparent[l] = take((int64_t)tr.level[l].parent.size() * 4);
-            TL.lcodes[l] = take((int64_t)tr.bucket[l].codes.size());
-            TL.lparent[l] = take((int64_t)tr.bucket[l].parent.size() * 4);
-            TL.lrow[l] = take((int64_t)tr.bucket[l].row.size() * 4);
+            TL.icode[l] = take(tr.nI[l]);
+            TL.iparent[l] = take(tr.nI[l] * 4);
+            TL.lcodes[l] = take(tr.nL[l] * tr.bucket[l].stride);
+            TL.lparent[l] = take(tr.nL[l] * 4);
+            TL.lrow[l] = take(tr.nL[l] * 4);
         }
     }
     L.total = off;
@@ -711,11 +718,11 @@ extern "C" int etf_index_stats(const etf_ctx *ctx, etf_stats *out)
     out->M = ix.M; out->K = ix.K; out->T = ix.T;
     for (int t = 0; t <= ix.T; ++t) out->chunk_begin[t] = ix.chunk_begin[t];
     out->N = ix.N; out->n_distinct = ix.Nd; out->max_dup = ix.max_dup;
-    for (int t = 0; t < ix.T && !ix.lean; ++t) {
+    for (int t = 0; t < ix.T; ++t) {
         const HostTree &tr = ix.tree[t];
         for (int l = 0; l < tr.D; ++l) {
-            out->nI[t][l] = (int64_t)tr.level[l].code.size();
-            out->nL[t][l] = (int64_t)tr.bucket[l].size();
+            out->nI[t][l] = tr.nI[l];
+            out->nL[t][l] = tr.nL[l];
             out->L1[t] += out->nI[t][l];
             out->L2[t] += out->nL[t][l];
             out->sumP[t] += out->nL[t][l] * (tr.D - (l + 1));
@@ -753,7 +760,7 @@ extern "C" int etf_index_layout(const etf_ctx *ctx, etf_layout *out)
     out->rec0_stride = ix.rstride0;
     out->n_sample_enc = ix.n_sample_enc;
     out->n_sample_pos = ix.n_sample_pos;
-    for (int t = 0; t < ix.T && !ix.lean; ++t) {
+    for (int t = 0; t < ix.T; ++t) {
         out->leaf_of[t] = L.tree[t].leaf_of;
         out->trec[t] = L.tree[t].rec;
         out->trec_stride[t] = ix.tree[t].rstride;
@@ -774,7 +781,7 @@ extern "C" int etf_index_export(const etf_ctx *ctx, void *host_buf, int64_t byte
     if (!ctx) return ETF_EINVAL;
     if (!host_buf) return fail(ctx, ETF_EINVAL, "output pointer is null");
     if (!ctx->idx.built) return fail(ctx, ETF_ESTATE, "no index: call etf_index_build first");
-    if (ctx->idx.lean) return fail(ctx, ETF_ESTATE, "the index was built on the device: the host holds no copy of it");
+    if (ctx->idx.device_built) return fail(ctx, ETF_ESTATE, "the index was built on the device: the host holds no copy of it");
     if (bytes < ctx->lay.total) return fail(ctx, ETF_ENOMEM, "buffer too small: %lld < %lld", (long long)bytes, (long long)ctx->lay.total);
     memset(host_buf, 0, (size_t)ctx->lay.total);
     char *base = (char *)host_buf;

@@ -35,6 +35,8 @@ struct HostTree {
     int64_t U = 0;                          // distinct sub-encodings = leaves
     std::vector<HostLevel> level;           // [D]   (entry l = level l+1; the last one is always empty)
     std::vector<HostBucket> bucket;         // [D]   (entry l = leaves at level l+1)
+    std::vector<int64_t> nI, nL;            // [D]   internal nodes / leaves of level l+1 (the arrays above are empty
+                                            //       when the index was built on the device)
     std::vector<uint32_t> leaf_of;          // [n_distinct] leaf row of every distinct full encoding (empty if T == 1)
     int rstride = 0;                        // bytes per record of `rec`: D rounded up to 1, 2, 4, 8 or 16, at least 4
     std::vector<uint8_t> rec;               // [U][rstride] the distinct sub-encodings in lexicographic order, zero padded
@@ -50,9 +52,8 @@ inline int depth_class(int D)
 
 struct HostIndex {
     bool built = false;
-    // Built on the device: the host holds the shape and the counts only, the image is already resident and holds
-    // the arrays the LDS-resident kernels, the flat scan and the exact kernel read (no per-tree level arrays).
-    bool lean = false;
+    // Built on the device: the host holds the shape and the counts only, the image is already resident.
+    bool device_built = false;
     int64_t n_sample_enc = 0, n_sample_pos = 0;  // entries of the two threshold samples
     int M = 0, K = 0, T = 0;
     int64_t N = 0, Nd = 0, max_dup = 0;
@@ -135,8 +136,8 @@ namespace etf {
 
 int fail(const etf_ctx *ctx, int code, const char *fmt, ...);
 void compute_layout(etf_ctx *ctx);
-// layout of the image a device-side build of N vectors writes (every array at its largest possible size)
-void lean_layout(const etf_ctx *ctx, int64_t N, DevLayout &L);
+// upper bound of the image bytes of an index over N vectors in T trees
+int64_t image_bytes_bound(const etf_ctx *ctx, int64_t N, int T, const int32_t *chunk_begin);
 void drop_index(etf_ctx *ctx);
 void prepare_centered(etf_ctx *ctx);
 // calls put(offset, pointer, bytes) for every array of the device image

@@ -1,5 +1,6 @@
-"""Index build on the device: the arrays against their definition (sorted distinct encodings, id ranges), and
-searches / all-pairs distances on a device-built index against the oracle and against the host-built index."""
+"""Index build on the device: the arrays against their definition (sorted distinct encodings, id ranges) and, level
+arrays included, against the host builder's image (itself checked against the oracle's pointer trie), and searches /
+all-pairs distances on a device-built index against the oracle and against the host-built index."""
 import numpy as np
 import pytest
 
@@ -53,26 +54,71 @@ def check_image(c, img, codes, ids):
     return st, lay, se, sp
 
 
-@pytest.mark.parametrize("N,M,K,with_ids,seed", [
-    (20000, 8, 256, False, 1),      # the benchmark's code width
-    (5000, 8, 4, True, 2),          # few codewords: many repeated encodings, explicit ids decide their order
-    (3000, 16, 256, False, 3),      # sixteen chunks: two sort passes
-    (3000, 16, 2, True, 4),         # ... with repeats and explicit ids: three
-    (4097, 4, 7, True, 5),          # four chunks, K not a power of two
-    (1, 8, 256, False, 6),          # a single vector
-    (700, 3, 5, True, 7),           # an odd number of chunks (the image is built; no kernel serves the shape)
+def image_arrays(lay, st, M):
+    """(name, offset, bytes) of every array of an index image except the threshold samples."""
+    N, Nd, T = st["N"], st["n_distinct"], st["T"]
+    out = [("codes", lay.codes, N * M), ("ids_in", lay.ids_in, 4 * N), ("ids_sorted", lay.ids_sorted, 4 * N),
+           ("ebegin", lay.ebegin, 4 * (Nd + 1)), ("enc_of_pos", lay.enc_of_pos, 4 * N), ("ecodes", lay.ecodes, Nd * M),
+           ("rec0", lay.rec0, Nd * lay.rec0_stride)]
+    for t, tr in enumerate(st["trees"]):
+        U = sum(tr["nL"])
+        if T > 1:
+            out.append(("leaf_of%d" % t, lay.leaf_of[t], 4 * Nd))
+        out.append(("rec%d" % t, lay.trec[t], U * lay.trec_stride[t]))
+        for l in range(tr["D"]):
+            nI, nL = tr["nI"][l], tr["nL"][l]
+            out += [("icode%d.%d" % (t, l), lay.icode[t][l], nI), ("iparent%d.%d" % (t, l), lay.iparent[t][l], 4 * nI),
+                    ("lcodes%d.%d" % (t, l), lay.lcodes[t][l], nL * lay.lstride[t][l]),
+                    ("lparent%d.%d" % (t, l), lay.lparent[t][l], 4 * nL), ("lrow%d.%d" % (t, l), lay.lrow[t][l], 4 * nL)]
+    return out
+
+
+def assert_same_as_host_build(c, img, cb, codes, ids, T, chunk_begin, **opts):
+    """Every array of the device-built image equals the host builder's, at the same offset."""
+    h = etf.Context(device=None)
+    for name, v in opts.items():
+        h.set_option(name, v)
+    h.pq_set_codebooks(cb)
+    h.index_build(codes, ids=ids, T=T, chunk_begin=chunk_begin)
+    hs, hl, hbuf = h.index_stats(), h.index_layout(), h.index_export()
+    ds, dl = c.index_stats(), c.index_layout()
+    # (the host's samples are draws with repeats removed, the device's one row per stratum: their sizes differ, and
+    # with them the offsets of the arrays behind them and the total)
+    assert {k: v for k, v in ds.items() if k != "device_bytes"} == {k: v for k, v in hs.items() if k != "device_bytes"}
+    dbuf = arr(img, 0, c.index_device_bytes(), np.uint8)
+    ha, da = image_arrays(hl, hs, codes.shape[1]), image_arrays(dl, ds, codes.shape[1])
+    assert [(n, b) for n, o, b in ha] == [(n, b) for n, o, b in da]
+    ends = sorted(o + b for n, o, b in da)
+    assert all(o >= 0 and o % 256 == 0 for n, o, b in da) and ends[-1] <= c.index_device_bytes()
+    for (name, hoff, nbytes), (_, doff, _) in zip(ha, da):
+        assert np.array_equal(dbuf[doff:doff + nbytes], hbuf[hoff:hoff + nbytes]), name
+
+
+@pytest.mark.parametrize("N,M,K,with_ids,T,cbeg,seed", [
+    (20000, 8, 256, False, 1, None, 1),          # the benchmark's code width, a single tree
+    (20000, 8, 256, False, 2, None, 11),         # ... the benchmark's forest
+    (5000, 8, 4, True, 4, None, 2),              # few codewords: many repeated encodings, explicit ids decide their order
+    (3000, 16, 256, False, 4, None, 3),          # sixteen chunks: two sort passes
+    (3000, 16, 2, True, 1, None, 4),             # ... with repeats and explicit ids: three; one tree sixteen levels deep
+    (3000, 16, 3, False, 2, [0, 1, 16], 8),      # a tree of fifteen chunks: its own order takes two passes as well
+    (4097, 4, 7, True, 2, None, 5),              # four chunks, K not a power of two
+    (6000, 8, 5, False, 3, [0, 3, 5, 8], 9),     # unequal trees
+    (1, 8, 256, False, 2, None, 6),              # a single vector
+    (700, 3, 5, True, 1, None, 7),               # an odd number of chunks
+    (500, 2, 9, False, 2, None, 10),             # trees of a single chunk: leaves only
 ])
-def test_device_built_arrays(N, M, K, with_ids, seed):
-    say("device build arrays N", N, "M", M, "K", K, "ids", with_ids)
+def test_device_built_arrays(N, M, K, with_ids, T, cbeg, seed):
+    say("device build arrays N", N, "M", M, "K", K, "ids", with_ids, "T", T, cbeg)
     rng = np.random.default_rng(seed)
     codes = rng.integers(0, K, size=(N, M)).astype(np.uint8)
     if K > 16:
         codes[:, : M // 2] //= 64                                          # shared prefixes and some repeats
         codes[rng.integers(0, N, N // 10)] = codes[rng.integers(0, N, N // 10)]
     ids = rng.permutation(10 * N + 5)[:N].astype(np.int32) if with_ids else None
-    c, img = dev_ctx(np.zeros((M, K, 1), dtype=np.float32), codes, ids, T=1, sample_min=256)
-    st, lay, se, sp = check_image(c, img, codes, ids)
-    assert lay.rec0 >= 0 and lay.icode[0][0] == -1 and st["trees"][0]["nI"] == [0] * M
+    cb = np.zeros((M, K, 1), dtype=np.float32)
+    c, img = dev_ctx(cb, codes, ids, T=T, chunk_begin=cbeg, sample_min=256)
+    check_image(c, img, codes, ids)
+    assert_same_as_host_build(c, img, cb, codes, ids, T, cbeg, sample_min=256)
 
 
 def test_device_build_sample_sizes_and_spread():
@@ -96,12 +142,15 @@ def small():
     return Problem(d=32, M=8, K=256, N=20000, Q=150, ntrain=4000, seed=11)
 
 
+@pytest.mark.parametrize("trav", [0, 1, 2])
 @pytest.mark.parametrize("mode,T", [(FLAT, 1), (TREE, 1), (FOREST, 2), (FOREST, 4)])
-def test_search_on_device_built_index(small, mode, T):
-    say("search on a device-built index, mode", mode, "T", T)
+def test_search_on_device_built_index(small, mode, T, trav):
+    if mode == FLAT and trav == 1:
+        pytest.skip("flat mode has no tree traversal")
+    say("search on a device-built index, mode", mode, "T", T, "traversal", trav)
     p = small
-    c, img = dev_ctx(p.cb, p.codes, None, T=T, sample_min=2048)
-    h = p.ctx(T=T, sample_min=2048)
+    c, img = dev_ctx(p.cb, p.codes, None, T=T, sample_min=2048, traversal=trav)
+    h = p.ctx(T=T, sample_min=2048, traversal=trav)
     for k in (1, 100):
         oi, od = c.search(qdev(p), k, mode)
         hi, hd = h.search(qdev(p), k, mode)
@@ -155,14 +204,16 @@ def test_device_build_error_paths(small):
     p = small
     c = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
     with pytest.raises(etf.EtfError):
-        c._ck(c._lib.etf_index_build_device_bytes(c._h, 10, None, None))         # no codebooks
+        c.index_build_device_bytes(10)                                            # no codebooks
     c.pq_set_codebooks(p.cb)
     codes = torch.from_numpy(p.codes).cuda()
     nimg, nws = c.index_build_device_bytes(p.N)
     with pytest.raises(etf.EtfError):
         c.index_build_device(codes, T=3)                                          # 3 does not divide 8
     with pytest.raises(etf.EtfError):
-        c.index_build_device(codes, image=torch.empty(nimg // 2, dtype=torch.uint8, device="cuda"))
+        c.index_build_device_bytes(p.N, 3)
+    with pytest.raises(etf.EtfError):
+        c.index_build_device(codes, image=torch.empty(nimg // 16, dtype=torch.uint8, device="cuda"))   # fails at the first arrays
     with pytest.raises(etf.EtfError):
         c.index_build_device(codes, ws=torch.empty(nws // 2, dtype=torch.uint8, device="cuda"))
     with pytest.raises(etf.EtfError):
@@ -174,17 +225,19 @@ def test_device_build_error_paths(small):
     c2.pq_set_codebooks(np.zeros((8, 5, 1), dtype=np.float32))
     with pytest.raises(etf.EtfError):
         c2.index_build_device(torch.full((100, 8), 5, dtype=torch.uint8, device="cuda"))
-    # a device-built index serves the LDS-resident kernels only, and has no host copy
+    # the image the build needs is known afterwards: a buffer of exactly that size serves, one byte less fails late
+    c.index_build_device(codes, T=2)
+    need = c.index_device_bytes()
+    assert need <= c.index_build_device_bytes(p.N, 2)[0]
+    exact = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+    off = (-exact.data_ptr()) % 256
+    c.index_build_device(codes, T=2, image=exact[off:off + need])
+    c.search(qdev(p), 5, FOREST)
+    with pytest.raises(etf.EtfError):
+        c.index_build_device(codes, T=2, image=exact[off:off + need - 256])
+    # a device-built index has no host copy
     c.index_build_device(codes, T=2)
     with pytest.raises(etf.EtfError):
         c.index_export()
     with pytest.raises(etf.EtfError):
         c.index_upload()
-    c.set_option("traversal", 0)
-    with pytest.raises(etf.EtfError):
-        c.search(qdev(p), 5, FOREST)
-    c.set_option("traversal", 2)
-    c.search(qdev(p), 5, FOREST)
-    c3, _ = dev_ctx(p.cb, p.codes, None, T=3, chunk_begin=[0, 3, 5, 8])
-    with pytest.raises(etf.EtfError):
-        c3.search(qdev(p), 5, FOREST)                                             # unequal trees: no LDS-resident kernel
