@@ -119,3 +119,25 @@ def test_other_configurations_scaled(name, N, Q):
         ids, dist = ids.cpu().numpy(), dist.cpu().numpy()
         for j in range(40):
             assert_topk_matches(ids[j], dist[j], ref[j], np.arange(N), cfg.topk, "cfg3 tree q%d" % j)
+
+
+@pytest.mark.parametrize("name,N", [("cfg2", None), ("cfg4", 2_000_000)])
+def test_device_built_index_full_size(name, N):
+    """The index build on the device at the benchmark's size (cfg2) and at two million 16-byte codes in four trees
+    (cfg4's shape): every array equal to the host builder's, and the same search results."""
+    from test_gpu_build import assert_same_as_host_build
+    cfg = get_config(name)
+    say(name, "device-built index, N =", N or cfg.N)
+    cb, codes, queries = build_inputs(cfg, N, 512)
+    dev = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+    dev.pq_set_codebooks(cb)
+    img = dev.index_build_device(torch.from_numpy(codes).cuda(), T=cfg.trees)
+    torch.cuda.synchronize()
+    assert_same_as_host_build(dev, img, cb, codes, None, cfg.trees, None)
+    host = make_ctx(cb, codes, cfg.trees)
+    qd = torch.from_numpy(queries).cuda()
+    a, b = dev.search(qd, cfg.topk, etf.ETF_MODE_FOREST), host.search(qd, cfg.topk, etf.ETF_MODE_FOREST)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    assert dev.last_fallback_count() == 0
+    check_sampled_queries(cb, codes, queries, a[0].cpu().numpy(), a[1].cpu().numpy(), cfg.topk, 4, name + " device-built")
