@@ -98,6 +98,15 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     etf_index_build): max(sample_min, sample_scale * sqrt(n)), n = number of distinct
  *                     encodings (of vectors in flat mode); defaults 32768 and 90
  *   "cand_cap"        per-query candidate capacity (0 = derived from k)
+ *   "metric"          0 (default): squared Euclidean distance.  1: scalar product (the paper notes, after
+ *                     Eq. 1 and in its conclusion, that tables of scalar products serve the same
+ *                     machinery): etf_lut_build gives lut[q][m][c] = <queries[q] group m, codeword c>,
+ *                     etf_adc gives dist[q][n] = <q, reconstruction of vector n> as the plain sum of the
+ *                     table entries, etf_search returns the k LARGEST scalar products, descending, ties by
+ *                     ascending id, out_dist holding the products.  Searches order candidates as
+ *                     B(q) - <q, x> with B(q) the sum of every group's largest table entry, so a returned
+ *                     product carries a rounding error of a few units in the last place of B(q), not of
+ *                     the product itself.  Takes effect on the next call; the index does not depend on it
  *   "lut_kernel"      0 (default): lookup tables on the matrix cores, as ||q'||^2 - 2 q'.c' + ||c'||^2
  *                     on vectors shifted by the group's mean codeword; entries below a quarter of
  *                     ||q'||^2 + ||c'||^2, where that form cancels, are recomputed as plain sums.

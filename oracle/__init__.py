@@ -191,3 +191,34 @@ def search(queries, codebooks, codes, k: int, ids=None) -> Tuple[np.ndarray, np.
     _check(_load().orc_search(_p(queries), Q, M * ds, M, K, _p(cb), _p(codes), _p(ids_a), N, k,
                               _p(oi), _p(od)), "search")
     return oi, od
+
+
+# ---- scalar-product tables (the paper's remark that ADC tables may hold scalar products instead of distances):
+# ---- the definition written out in float64 with numpy
+
+def lut_ip(q, codebooks) -> np.ndarray:
+    """lut[m][k] = <q restricted to group m, codeword k of group m>, float64."""
+    q = np.asarray(_f32(q), dtype=np.float64)
+    cb = np.asarray(_f32(codebooks), dtype=np.float64)
+    M, K, ds = cb.shape
+    out = np.zeros((M, K), dtype=np.float64)
+    for m in range(M):
+        out[m] = cb[m] @ q[m * ds:(m + 1) * ds]
+    return out
+
+
+def adc_all_ip(queries, codebooks, codes) -> np.ndarray:
+    """ip[Q][N] float64: scalar product of every query with every reconstructed vector, as the sum of table entries."""
+    queries = _f32(queries)
+    return np.stack([adc_flat(lut_ip(q, codebooks), codes) for q in queries])
+
+
+def search_ip(queries, codebooks, codes, k: int, ids=None) -> Tuple[np.ndarray, np.ndarray]:
+    """(ids int32 [Q][k], ip float64 [Q][k]): the k largest scalar products, descending, ties by ascending id."""
+    allp = adc_all_ip(queries, codebooks, codes)
+    oi = np.zeros((allp.shape[0], k), dtype=np.int32)
+    od = np.zeros((allp.shape[0], k), dtype=np.float64)
+    for j in range(allp.shape[0]):
+        oi[j], neg = topk(-allp[j], k, ids)
+        od[j] = -neg
+    return oi, od

@@ -176,7 +176,7 @@ struct Plan {
     bool ctx_path = false;    // trees walked with the distance context in registers (no partial-sum tables)
     bool lds_path = false;    // search with every table slice in LDS: no result tables at all
     bool flat_lds = false;    // flat mode through the same kernels
-    int64_t o_counter = 0, o_lutT = 0, o_gmin = 0, o_tau = 0, o_cnt = 0, o_flag = 0, o_cand = 0;
+    int64_t o_counter = 0, o_lutT = 0, o_gmin = 0, o_tau = 0, o_boff = 0, o_cnt = 0, o_flag = 0, o_cand = 0;
     int64_t o_part[ETF_MAX_M][ETF_MAX_M];
     int64_t o_leafp[ETF_MAX_M];
     int64_t total = 0;
@@ -271,6 +271,7 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     if (search) {
         if (P.use_tau) P.o_gmin = take(P.NT * P.ngroups * QT * 4);
         P.o_tau = take(P.NT * QT * 4);
+        P.o_boff = take(P.NT * QT * 4);
         P.o_cnt = take(P.NT * QT * 4);
         P.o_flag = take(P.NT * QT * 4);
         P.o_cand = take(P.NT * QT * (int64_t)P.C * 8);
@@ -310,7 +311,12 @@ int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_
 {
     dim3 grid((unsigned)tiles, (unsigned)ctx->M);
     ProfScope prof(ctx, ETF_K_LUT);
-    if (ctx->opt.lut_kernel == 0) {
+    if (ctx->opt.metric == 1) {
+        const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
+        hipLaunchKernelGGL(k_lut_direct<true>, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M,
+                           ctx->K, cb, lutT, lut_public);
+        LAUNCH_CHECK(ctx, "k_lut_direct");
+    } else if (ctx->opt.lut_kernel == 0) {
         const float *cbc = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_centered);
         const float *cbn = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_norm);
         const float *cbm = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_mean);
@@ -320,7 +326,7 @@ int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_
         LAUNCH_CHECK(ctx, "k_lut_mfma");
     } else {
         const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
-        hipLaunchKernelGGL(k_lut_direct, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M,
+        hipLaunchKernelGGL(k_lut_direct<false>, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M,
                            ctx->K, cb, lutT, lut_public);
         LAUNCH_CHECK(ctx, "k_lut_direct");
     }
@@ -881,6 +887,13 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
         uint64_t *cand = reinterpret_cast<uint64_t *>(w + P.o_cand);
         rc = launch_lut(ctx, queries, Q, q0, tiles, lutT, nullptr);
         if (rc) return rc;
+        float *boff = nullptr;
+        if (ctx->opt.metric == 1) {  // the selection orders non-negative values, smallest first
+            boff = reinterpret_cast<float *>(w + P.o_boff);
+            ProfScope prof(ctx, ETF_K_LUT);
+            hipLaunchKernelGGL(k_lut_shift, dim3((unsigned)tiles), dim3(256), 0, st, lutT, ix.M, ix.K, boff);
+            LAUNCH_CHECK(ctx, "k_lut_shift");
+        }
         const unsigned fb = (unsigned)((nql + 255) / 256);
         hipLaunchKernelGGL(k_fill_u32, dim3(fb), dim3(256), 0, st, cnt, nql, 0u);
         hipLaunchKernelGGL(k_fill_u32, dim3(fb), dim3(256), 0, st, flag, nql, ctx->opt.force_fallback ? 1u : 0u);
@@ -942,6 +955,7 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
         sa.out_ids = out_ids + q0 * k;
         sa.out_dist = out_dist + q0 * k;
         sa.flag = flag;
+        sa.boff = boff;
         {
             ProfScope prof(ctx, ETF_K_SELECT);
             hipLaunchKernelGGL(k_select, dim3((unsigned)nq), dim3(256), select_lds_bytes(k), st, sa);
@@ -973,6 +987,7 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
         ea.k = k;
         ea.out_ids = sa.out_ids;
         ea.out_dist = sa.out_dist;
+        ea.boff = boff;
         {
             ProfScope prof(ctx, ETF_K_EXACT);
             hipLaunchKernelGGL(k_exact, dim3((unsigned)nq), dim3(256), 0, st, ea);

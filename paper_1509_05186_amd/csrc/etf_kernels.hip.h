@@ -75,8 +75,10 @@ __device__ __forceinline__ float run_pick(float loaded, float before, uint32_t m
 
 // ------------------------------------------------------------------------------------------------
 // S1  lookup tables (paper Eq. 1, first term on each group's own dimensions), plain float32 form.
+//     IP: the scalar products q_m . c instead (the paper's remark that the tables may hold scalar products).
 //     grid (tiles, M), block 256: wave w computes codewords [64w, 64w+64) for the tile's 64 queries.
 // ------------------------------------------------------------------------------------------------
+template <bool IP>
 __global__ __launch_bounds__(256) void k_lut_direct(const float *__restrict__ queries, int64_t Q, int64_t q0, int d,
                                                     int M, int K, const float *__restrict__ codebooks,
                                                     float *__restrict__ lutT, float *__restrict__ lut_public)
@@ -102,8 +104,12 @@ __global__ __launch_bounds__(256) void k_lut_direct(const float *__restrict__ qu
             if (k < K) {
                 const float *c = codebooks + ((int64_t)m * K + k) * ds + j0;
                 for (int jj = 0; jj < nj; ++jj) {
-                    float t = x[jj] - c[jj];
-                    acc[i] = fmaf(t, t, acc[i]);
+                    if (IP) {
+                        acc[i] = fmaf(x[jj], c[jj], acc[i]);
+                    } else {
+                        float t = x[jj] - c[jj];
+                        acc[i] = fmaf(t, t, acc[i]);
+                    }
                 }
             }
         }
@@ -115,6 +121,33 @@ __global__ __launch_bounds__(256) void k_lut_direct(const float *__restrict__ qu
             if (lutT) lutT[(((int64_t)tile * M + m) * K + k) * QT + lane] = acc[i];
             if (lut_public && live) lut_public[(q * M + m) * K + k] = acc[i];
         }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Scalar-product searches.  The selection kernels order candidates by the bits of non-negative floats, smallest
+// first; the largest scalar products are found as the smallest values of  B(q) - q.x,  B(q) = sum over groups of
+// the group's largest table entry.  This kernel rewrites a tile's tables of products p[m][k] as B_m - p[m][k]
+// (never negative: B_m is the maximum of the same rounded values) and stores B(q), the sum of the B_m in group
+// order, which the selection kernels subtract from again when they write the results.
+//     grid (tiles), block 256: wave w takes groups w, w + 4, ...; lane = query of the tile.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_lut_shift(float *__restrict__ lutT, int M, int K, float *__restrict__ boff)
+{
+    __shared__ float s_b[ETF_MAX_M][QT];
+    const int tile = blockIdx.x, lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6);
+    for (int m = w; m < M; m += 4) {
+        float *t = lutT + ((int64_t)tile * M + m) * K * QT + lane;
+        float b = t[0];
+        for (int k = 1; k < K; ++k) b = fmaxf(b, t[(int64_t)k * QT]);
+        for (int k = 0; k < K; ++k) t[(int64_t)k * QT] = b - t[(int64_t)k * QT];
+        s_b[m][lane] = b;
+    }
+    __syncthreads();
+    if (w == 0) {
+        float b = 0.f;
+        for (int m = 0; m < M; ++m) b += s_b[m][lane];
+        boff[(int64_t)tile * QT + lane] = b;
     }
 }
 
@@ -1283,6 +1316,7 @@ struct SelectArgs {
     int32_t *out_ids;        // [nq][k]
     float *out_dist;         // [nq][k]
     uint32_t *flag;          // [nq]  set to 1 when the query needs the exact kernel
+    const float *boff;       // [nq] or nullptr: results are written as boff[q] - value (scalar-product searches)
 };
 
 __global__ __launch_bounds__(256) void k_select(SelectArgs a)
@@ -1405,7 +1439,8 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     bitonic_sort_u64(xkeys, nx2);
     for (int i = threadIdx.x; i < k; i += 256) {
         a.out_ids[ql * k + i] = (int32_t)(uint32_t)xkeys[i];
-        a.out_dist[ql * k + i] = __uint_as_float((uint32_t)(xkeys[i] >> 32));
+        const float v = __uint_as_float((uint32_t)(xkeys[i] >> 32));
+        a.out_dist[ql * k + i] = a.boff ? a.boff[ql] - v : v;
     }
 }
 
@@ -1431,6 +1466,7 @@ struct ExactArgs {
     int k;
     int32_t *out_ids;
     float *out_dist;
+    const float *boff;        // as in SelectArgs
 };
 
 __device__ __forceinline__ float exact_distance(const ExactArgs &a, const float *lut, const uint8_t *c)
@@ -1551,7 +1587,8 @@ __global__ __launch_bounds__(256) void k_exact(ExactArgs a)
     bitonic_sort_u64(okeys, n2);
     for (int i = threadIdx.x; i < a.k; i += 256) {
         a.out_ids[ql * a.k + i] = (int32_t)(uint32_t)okeys[i];
-        a.out_dist[ql * a.k + i] = __uint_as_float((uint32_t)(okeys[i] >> 32));
+        const float v = __uint_as_float((uint32_t)(okeys[i] >> 32));
+        a.out_dist[ql * a.k + i] = a.boff ? a.boff[ql] - v : v;
     }
 }
 

@@ -271,3 +271,36 @@ def test_encode_f32_equals_numpy_float32_definition():
             s = (s + (d * d).astype(np.float32)).astype(np.float32)
         want[:, m] = s.argmin(axis=1)        # argmin returns the first minimum
     assert np.array_equal(oracle.encode_f32(x, cb), want)
+
+
+# ---------------------------------------------------------------- scalar-product tables
+def test_scalar_product_golden_worked_example():
+    g = json.load(open(GOLD))
+    cb = np.array(g["codebooks"], dtype=np.float32)
+    q = np.array(g["query"], dtype=np.float32)
+    codes = np.array(g["codes"], dtype=np.uint8)
+    assert np.array_equal(oracle.lut_ip(q, cb), np.array(g["ip_lut"]))
+    assert np.array_equal(oracle.adc_all_ip(q[None], cb, codes)[0], np.array(g["ip_values"]))
+    ids, vals = oracle.search_ip(q[None], cb, codes, 3)
+    assert ids[0].tolist() == g["ip_top3_ids"] and vals[0].tolist() == g["ip_top3"]
+
+
+def test_scalar_product_tables_against_decoded_vectors_and_distance_tables():
+    x, qs, cb, codes = _tiny(seed=5, n=200, d=12, M=3, K=8, q=7)
+    xhat = oracle.decode(codes, cb).astype(np.float64)
+    ip = oracle.adc_all_ip(qs, cb, codes)
+    # the sum of table entries is the scalar product with the reconstruction (brute force, another routine)
+    assert np.allclose(ip, qs.astype(np.float64) @ xhat.T, rtol=0, atol=1e-12)
+    # polarisation ties the scalar-product tables to the (separately pinned) distance tables:
+    #   ||q_m - c||^2 = ||q_m||^2 - 2 <q_m, c> + ||c||^2
+    M, K, ds = cb.shape
+    for q in qs:
+        qn = (q.astype(np.float64).reshape(M, ds) ** 2).sum(1)[:, None]
+        cn = (cb.astype(np.float64) ** 2).sum(2)
+        assert np.allclose(oracle.lut(q, cb), qn - 2 * oracle.lut_ip(q, cb) + cn, rtol=0, atol=1e-11)
+    # the search: a prefix of the order by (descending product, ascending id), with repeated encodings as exact ties
+    ids = np.random.default_rng(1).permutation(1000)[:200].astype(np.int32)
+    oi, ov = oracle.search_ip(qs, cb, codes, 25, ids)
+    for j in range(len(qs)):
+        order = np.lexsort((ids, -ip[j]))[:25]
+        assert np.array_equal(oi[j], ids[order]) and np.array_equal(ov[j], ip[j][order])
