@@ -310,6 +310,17 @@ def main():
             del w2
         others["e_tree_stats"] = tree.index_stats()["trees"]
         del tree
+        # the other payload on the same forest: the k largest scalar products (option metric = 1)
+        ipc = make_ctx(T)
+        ipc.set_option("metric", 1)
+        w4 = ipc.alloc_workspace(Q, k, mode)
+        d4, p4 = time_search(ipc, qd, k, mode, 1, osteps, torch, w4, out_ids, out_dist, cfg.query_batch)
+        others["scalar_product_search"] = {"value": N * Q * osteps / d4, "ms_per_step": d4 / osteps * 1e3,
+                                           "kernels_ms_per_step": {n: v[0] / osteps for n, v in p4.items() if v[1]},
+                                           "fallback_queries": ipc.last_fallback_count()}
+        log("largest scalar products, E-Forest(T=%d) top-%d: %.2f ms/step, %.3e products/s"
+            % (T, k, others["scalar_product_search"]["ms_per_step"], others["scalar_product_search"]["value"]))
+        del ipc, w4
         if args.traversal == 2:
             # the same index built on the device from device-resident codes, and the same search on it
             db = etf.Context(device=0, stream=stream)

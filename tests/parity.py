@@ -62,3 +62,41 @@ def assert_topk_matches(gpu_ids, gpu_dist, ref_all, ids, k, what=""):
         clash = np.count_nonzero((ref_all >= lo) & (ref_all <= hi)) > 1
         if not clash:
             assert gpu_ids[a] == ids[order[a]], what + ": id at rank %d" % a
+
+
+def ip_scale(lut_ip):
+    """Magnitude of a query's table of scalar products: the sum over groups of the largest |entry|.  Scalar
+    products cancel, so float32 results are held to 1e-5 of this scale rather than of the result itself."""
+    return float(np.abs(np.asarray(lut_ip, dtype=np.float64)).max(axis=1).sum())
+
+
+def assert_topk_ip_matches(gpu_ids, gpu_val, ref_all, ids, k, tol, what=""):
+    """Tie-aware check of one query's k largest scalar products against the oracle's products with every vector
+    (ref_all[n] for input position n, ids[n] its id), absolute tolerance tol:
+      - k distinct, valid ids, ordered by (descending returned product, ascending id);
+      - each returned product agrees with the oracle's for the returned id, and position by position with the
+        oracle's sorted top-k;
+      - nothing left out is larger (beyond the tolerance) than the last one returned;
+      - where no other product lies within the tolerance band the ids are identical."""
+    gpu_ids = np.asarray(gpu_ids).astype(np.int64)
+    gpu_val = np.asarray(gpu_val, dtype=np.float64)
+    ref_all = np.asarray(ref_all, dtype=np.float64)
+    ids = np.asarray(ids).astype(np.int64)
+    assert gpu_ids.shape == (k,) and gpu_val.shape == (k,), what
+    assert len(set(gpu_ids.tolist())) == k, what + ": duplicate ids"
+    pos_of = {int(v): i for i, v in enumerate(ids)}
+    assert all(int(i) in pos_of for i in gpu_ids), what + ": unknown id"
+    for a in range(k - 1):
+        assert (-gpu_val[a], gpu_ids[a]) < (-gpu_val[a + 1], gpu_ids[a + 1]), what + ": order at %d" % a
+    pos = np.array([pos_of[int(i)] for i in gpu_ids])
+    assert np.all(np.abs(gpu_val - ref_all[pos]) <= tol), what + ": returned product vs oracle"
+    order = np.lexsort((ids, -ref_all))
+    ref_top = ref_all[order[:k]]
+    assert np.all(np.abs(gpu_val - ref_top) <= tol), what + ": sorted products"
+    kth = ref_top[-1]
+    left_out = np.ones(len(ids), dtype=bool)
+    left_out[pos] = False
+    assert not np.any(ref_all[left_out] > kth + 2 * tol), what + ": a larger product was left out"
+    for a in np.flatnonzero(np.abs(ref_top - kth) > 2 * tol):
+        if np.count_nonzero(np.abs(ref_all - ref_top[a]) <= 2 * tol) == 1:
+            assert gpu_ids[a] == ids[order[a]], what + ": id at rank %d" % a
