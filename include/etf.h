@@ -74,6 +74,7 @@ typedef struct etf_stats {
     int64_t lookups[ETF_MAX_M];            /* table lookups of one traversal: L1 + L2 + sumP            */
     int64_t paper_bytes[ETF_MAX_M];        /* 4N + 2(L1+L2) + sumP (Hierarchical Memory Structure)      */
     int64_t device_bytes;                  /* size of the level-ordered device image                    */
+    int32_t chunk_order[ETF_MAX_M];        /* position j of the index's encodings holds input chunk [j] */
 } etf_stats;
 
 /* ---- context ------------------------------------------------------------ */
@@ -154,6 +155,23 @@ int etf_pq_encode(const etf_ctx *ctx, const float *x, int64_t n, uint8_t *codes_
 int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, const int32_t *ids, int T,
                     const int32_t *chunk_begin);
 int etf_index_stats(const etf_ctx *ctx, etf_stats *out);
+
+/* Chunk order (paper: "Encoding Chunk Ordering": which chunk sits at which level decides how many
+ * prefixes are shared; and the forest's choice of which chunks form a tree).
+ * etf_index_set_chunk_order: the next etf_index_build / etf_index_build_device stores, at position j of
+ * every encoding, the input's chunk order[j] ([M] host, a permutation of 0..M-1; NULL = as given), and
+ * chunk_begin then cuts the reordered positions into trees.  Distances, ids and all-pairs outputs keep
+ * their meaning (queries and codebooks stay in the quantiser's order; the library reorders its lookup
+ * tables to match); float32 sums may differ in the last bits because the order of additions follows the
+ * positions.  The array `codes` of the device image holds the reordered encodings.
+ * etf_suggest_chunk_order: a greedy order for the given codes ([N][M] host) and tree shape: tree after
+ * tree, level after level, the remaining chunk that splits the tree's prefixes so far into the fewest
+ * distinct prefixes (evaluated on at most 2^18 evenly spaced vectors).  order_out [M]; lookups_given /
+ * lookups_order (either may be NULL) receive the table lookups of one traversal, L1 + L2 + sumP summed
+ * over the trees, of those vectors' index in the given and in the suggested order. */
+int etf_index_set_chunk_order(etf_ctx *ctx, const int32_t *order);
+int etf_suggest_chunk_order(const etf_ctx *ctx, const uint8_t *codes, int64_t N, int T, const int32_t *chunk_begin,
+                            int32_t *order_out, int64_t *lookups_given, int64_t *lookups_order);
 /* Bytes of device memory the built index needs. */
 int64_t etf_index_device_bytes(const etf_ctx *ctx);
 /* Copies the index (and the codebooks) into dev_buf (device, 256-byte aligned,

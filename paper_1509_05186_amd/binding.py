@@ -18,7 +18,7 @@ _lib = None
 EXPORTS = [
     "etf_create", "etf_destroy", "etf_set_stream", "etf_strerror", "etf_last_error", "etf_set_option",
     "etf_pq_train", "etf_pq_set_codebooks", "etf_pq_get_codebooks", "etf_pq_encode",
-    "etf_index_build", "etf_index_stats", "etf_index_device_bytes", "etf_index_upload",
+    "etf_index_build", "etf_index_set_chunk_order", "etf_suggest_chunk_order", "etf_index_stats", "etf_index_device_bytes", "etf_index_upload",
     "etf_index_layout", "etf_index_export",
     "etf_encode_workspace_bytes", "etf_pq_encode_device",
     "etf_index_build_device_bytes", "etf_index_build_device",
@@ -39,6 +39,7 @@ class EtfStats(ctypes.Structure):
         ("sumP", ctypes.c_int64 * ETF_MAX_M), ("lookups", ctypes.c_int64 * ETF_MAX_M),
         ("paper_bytes", ctypes.c_int64 * ETF_MAX_M),
         ("device_bytes", ctypes.c_int64),
+        ("chunk_order", ctypes.c_int32 * ETF_MAX_M),
     ]
 
     def as_dict(self) -> dict:
@@ -54,7 +55,8 @@ class EtfStats(ctypes.Structure):
                 "lookups": int(self.lookups[t]), "paper_bytes": int(self.paper_bytes[t]),
             })
         return {"M": self.M, "K": self.K, "T": T, "N": int(self.N), "n_distinct": int(self.n_distinct),
-                "max_dup": int(self.max_dup), "device_bytes": int(self.device_bytes), "trees": trees}
+                "max_dup": int(self.max_dup), "device_bytes": int(self.device_bytes), "trees": trees,
+                "chunk_order": [int(self.chunk_order[j]) for j in range(self.M)]}
 
 
 _Grid64 = (ctypes.c_int64 * ETF_MAX_M) * ETF_MAX_M
@@ -116,6 +118,8 @@ def load_library():
         "etf_pq_get_codebooks": (I, [P, P]),
         "etf_pq_encode": (I, [P, P, L, P]),
         "etf_index_build": (I, [P, P, L, P, I, P]),
+        "etf_index_set_chunk_order": (I, [P, P]),
+        "etf_suggest_chunk_order": (I, [P, P, L, I, P, P, ctypes.POINTER(L), ctypes.POINTER(L)]),
         "etf_index_stats": (I, [P, ctypes.POINTER(EtfStats)]),
         "etf_index_device_bytes": (L, [P]),
         "etf_index_upload": (I, [P, P, L]),
@@ -226,6 +230,28 @@ class Context:
             raise ValueError("chunk_begin must have T+1 entries")
         self._ck(self._lib.etf_index_build(self._h, _host(codes), codes.shape[0], _host(ids_a), T, _host(cb)))
         self._N = codes.shape[0]
+
+    def index_set_chunk_order(self, order: Optional[Sequence[int]]):
+        """Chunk order of the next index build (a permutation of 0..M-1; None = as given)."""
+        o = None if order is None else np.ascontiguousarray(order, dtype=np.int32)
+        if o is not None and o.shape != (self._shape[1],):
+            raise ValueError("order must have M entries")
+        self._ck(self._lib.etf_index_set_chunk_order(self._h, _host(o)))
+
+    def suggest_chunk_order(self, codes: np.ndarray, T: int = 1, chunk_begin: Optional[Sequence[int]] = None):
+        """(order, lookups in the given order, lookups in the suggested order) for host codes [N][M]."""
+        codes = np.ascontiguousarray(codes, dtype=np.uint8)
+        M = self._shape[1]
+        if codes.ndim != 2 or codes.shape[1] != M:
+            raise ValueError("expected [N][%d] codes" % M)
+        cb = None if chunk_begin is None else np.ascontiguousarray(chunk_begin, dtype=np.int32)
+        if cb is not None and cb.shape != (T + 1,):
+            raise ValueError("chunk_begin must have T+1 entries")
+        order = np.zeros(M, dtype=np.int32)
+        a, b = ctypes.c_int64(0), ctypes.c_int64(0)
+        self._ck(self._lib.etf_suggest_chunk_order(self._h, _host(codes), codes.shape[0], T, _host(cb), _host(order),
+                                                   ctypes.byref(a), ctypes.byref(b)))
+        return order, int(a.value), int(b.value)
 
     def index_stats(self) -> dict:
         st = EtfStats()

@@ -52,6 +52,32 @@ __global__ void __launch_bounds__(BT) k_build_init(const uint8_t *codes, const i
     if (bad) atomicOr(&scal[2], bad);
 }
 
+// the input encodings in index order: position j holds input chunk src[j] (a thread reads its whole row before it
+// writes: in and out may be the same buffer)
+struct BuildOrder {
+    uint8_t src[ETF_MAX_M];
+};
+
+__global__ void __launch_bounds__(BT) k_build_permute(const uint8_t *in, uint8_t *out, int64_t N, int M, BuildOrder ord)
+{
+    const int64_t i = (int64_t)blockIdx.x * BT + threadIdx.x;
+    if (i >= N) return;
+    uint8_t row[ETF_MAX_M];
+#pragma unroll
+    for (int j = 0; j < ETF_MAX_M; ++j) row[j] = j < M ? in[i * M + j] : (uint8_t)0;
+    uint8_t res[ETF_MAX_M];
+#pragma unroll
+    for (int j = 0; j < ETF_MAX_M; ++j) {
+        uint8_t v = 0;
+#pragma unroll
+        for (int c = 0; c < ETF_MAX_M; ++c) v = ord.src[j] == c ? row[c] : v;
+        res[j] = v;
+    }
+#pragma unroll
+    for (int j = 0; j < ETF_MAX_M; ++j)
+        if (j < M) out[i * M + j] = res[j];
+}
+
 // Sort key of row pos[i]: chunks [c0, c1) of it (at most eight), most significant first, so that integer order is
 // lexicographic order, in the low 8 (c1 - c0) bits (the sort then leaves out the empty high bits); c0 == c1 asks
 // for the row's id instead.
@@ -367,10 +393,23 @@ int build_impl(etf_ctx *ctx, const uint8_t *codes, int64_t N, const int32_t *ids
     HIP_TRY(ctx, put(L.cb_centered, ctx->cb_centered));
     HIP_TRY(ctx, put(L.cb_norm, ctx->cb_norm));
     HIP_TRY(ctx, put(L.cb_mean, ctx->cb_mean));
-    if (d_codes != codes) HIP_TRY(ctx, hipMemcpyAsync(d_codes, codes, (size_t)N * M, hipMemcpyDeviceToDevice, st));
     HIP_TRY(ctx, hipMemsetAsync(scal, 0, 16, st));
-
     const unsigned nb = blocks(N);
+    ix.order.resize(M);
+    BuildOrder ord;
+    bool identity = true;
+    for (int j = 0; j < ETF_MAX_M; ++j) {
+        const int src = (j < M && !ctx->next_order.empty()) ? ctx->next_order[j] : j;
+        if (j < M) ix.order[j] = src;
+        ord.src[j] = (uint8_t)src;
+        identity = identity && src == j;
+    }
+    if (identity) {
+        if (d_codes != codes) HIP_TRY(ctx, hipMemcpyAsync(d_codes, codes, (size_t)N * M, hipMemcpyDeviceToDevice, st));
+    } else {
+        hipLaunchKernelGGL(k_build_permute, dim3(nb), dim3(BT), 0, st, codes, d_codes, N, M, ord);
+        HIP_TRY(ctx, hipGetLastError());
+    }
     hipLaunchKernelGGL(k_build_init, dim3(nb), dim3(BT), 0, st, d_codes, ids, N, M, K, pos[0], d_ids_in, scal);
     HIP_TRY(ctx, hipGetLastError());
 

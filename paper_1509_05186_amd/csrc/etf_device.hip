@@ -310,11 +310,13 @@ int set_lds(const etf_ctx *ctx, F kernel, size_t bytes)
 int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_t tiles, float *lutT, float *lut_public)
 {
     dim3 grid((unsigned)tiles, (unsigned)ctx->M);
+    ChunkOrder ord;
+    for (int j = 0; j < ETF_MAX_M; ++j) ord.src[j] = (uint8_t)((size_t)j < ctx->idx.order.size() ? ctx->idx.order[j] : j);
     ProfScope prof(ctx, ETF_K_LUT);
     if (ctx->opt.metric == 1) {
         const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
         hipLaunchKernelGGL(k_lut_direct<true>, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M,
-                           ctx->K, cb, lutT, lut_public);
+                           ctx->K, cb, lutT, lut_public, ord);
         LAUNCH_CHECK(ctx, "k_lut_direct");
     } else if (ctx->opt.lut_kernel == 0) {
         const float *cbc = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_centered);
@@ -322,12 +324,12 @@ int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_
         const float *cbm = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_mean);
         const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
         hipLaunchKernelGGL(k_lut_mfma, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
-                           cb, cbc, cbn, cbm, ctx->dsp, lutT, lut_public);
+                           cb, cbc, cbn, cbm, ctx->dsp, lutT, lut_public, ord);
         LAUNCH_CHECK(ctx, "k_lut_mfma");
     } else {
         const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
         hipLaunchKernelGGL(k_lut_direct<false>, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M,
-                           ctx->K, cb, lutT, lut_public);
+                           ctx->K, cb, lutT, lut_public, ord);
         LAUNCH_CHECK(ctx, "k_lut_direct");
     }
     return ETF_OK;

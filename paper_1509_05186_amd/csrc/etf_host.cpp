@@ -441,6 +441,7 @@ extern "C" int etf_pq_set_codebooks(etf_ctx *ctx, const float *cb, int d, int M,
     int rc = check_pq_shape(ctx, d, M, K);
     if (rc) return rc;
     drop_index(ctx);
+    ctx->next_order.clear();
     ctx->d = d; ctx->M = M; ctx->K = K; ctx->ds = d / M;
     try {
         ctx->codebooks.assign(cb, cb + (size_t)M * K * ctx->ds);
@@ -509,6 +510,7 @@ extern "C" int etf_pq_train(etf_ctx *ctx, const float *x, int64_t n, int d, int 
             }
         }
         drop_index(ctx);
+        ctx->next_order.clear();
         ctx->d = d; ctx->M = M; ctx->K = K; ctx->ds = ds;
         ctx->codebooks.swap(cb);
         prepare_centered(ctx);
@@ -572,7 +574,14 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
         HostIndex ix;
         ix.M = M; ix.K = K; ix.T = T; ix.N = N;
         ix.chunk_begin = cb;
-        ix.codes.assign(codes, codes + (size_t)N * M);
+        ix.order.resize(M);
+        for (int j = 0; j < M; ++j) ix.order[j] = ctx->next_order.empty() ? j : ctx->next_order[j];
+        ix.codes.resize((size_t)N * M);
+        parallel_slices(N, host_threads(), [&](int, int64_t lo, int64_t hi) {
+            for (int64_t i = lo; i < hi; ++i)
+                for (int j = 0; j < M; ++j) ix.codes[(size_t)i * M + j] = codes[(size_t)i * M + ix.order[j]];
+        });
+        codes = ix.codes.data();  // from here on: the encodings in index order
         ix.ids_in.resize(N);
         for (int64_t i = 0; i < N; ++i) ix.ids_in[i] = ids ? ids[i] : (int32_t)i;
 
@@ -711,6 +720,122 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
     return ETF_OK;
 }
 
+// =============================================================================================
+// chunk order
+// =============================================================================================
+static int check_order(const etf_ctx *ctx, const int32_t *order)
+{
+    const int M = ctx->M;
+    bool seen[ETF_MAX_M] = {false};
+    for (int j = 0; j < M; ++j) {
+        if (order[j] < 0 || order[j] >= M || seen[order[j]]) return fail(ctx, ETF_EINVAL, "order must be a permutation of 0..%d", M - 1);
+        seen[order[j]] = true;
+    }
+    return ETF_OK;
+}
+
+extern "C" int etf_index_set_chunk_order(etf_ctx *ctx, const int32_t *order)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (ctx->codebooks.empty()) return fail(ctx, ETF_ESTATE, "no codebooks: M is unknown");
+    if (!order) {
+        ctx->next_order.clear();
+        return ETF_OK;
+    }
+    int rc = check_order(ctx, order);
+    if (rc) return rc;
+    ctx->next_order.assign(order, order + ctx->M);
+    return ETF_OK;
+}
+
+// table lookups of one traversal of the index of `codes` in the given order
+static int count_lookups(const etf_ctx *ctx, const uint8_t *codes, int64_t n, int T, const int32_t *chunk_begin,
+                         const int32_t *order, int64_t *out)
+{
+    etf_ctx tmp;
+    tmp.d = ctx->d; tmp.M = ctx->M; tmp.K = ctx->K; tmp.ds = ctx->ds;
+    tmp.codebooks.assign(1, 0.f);  // the builder only asks whether a quantiser is set
+    tmp.opt = ctx->opt;
+    if (order) tmp.next_order.assign(order, order + ctx->M);
+    int rc = etf_index_build(&tmp, codes, n, nullptr, T, chunk_begin);
+    if (rc) return fail(ctx, rc, "%s", tmp.err.c_str());
+    etf_stats st;
+    rc = etf_index_stats(&tmp, &st);
+    if (rc) return fail(ctx, rc, "%s", tmp.err.c_str());
+    *out = 0;
+    for (int t = 0; t < T; ++t) *out += st.lookups[t];
+    return ETF_OK;
+}
+
+extern "C" int etf_suggest_chunk_order(const etf_ctx *ctx, const uint8_t *codes, int64_t N, int T, const int32_t *chunk_begin,
+                                       int32_t *order_out, int64_t *lookups_given, int64_t *lookups_order)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (ctx->codebooks.empty()) return fail(ctx, ETF_ESTATE, "no codebooks: M and K are unknown");
+    const int M = ctx->M;
+    if (!codes || N <= 0 || !order_out) return fail(ctx, ETF_EINVAL, "codes or order_out is null, or N <= 0");
+    if (T < 1 || T > M) return fail(ctx, ETF_EINVAL, "need 1 <= T <= M (T=%d, M=%d)", T, M);
+    std::vector<int32_t> cb(T + 1);
+    if (chunk_begin) {
+        for (int t = 0; t <= T; ++t) cb[t] = chunk_begin[t];
+        if (cb[0] != 0 || cb[T] != M) return fail(ctx, ETF_EINVAL, "chunk_begin must run from 0 to M");
+        for (int t = 0; t < T; ++t)
+            if (cb[t + 1] <= cb[t]) return fail(ctx, ETF_EINVAL, "chunk_begin must be strictly increasing");
+    } else {
+        if (M % T != 0) return fail(ctx, ETF_EINVAL, "T=%d does not divide M=%d and no chunk_begin was given", T, M);
+        for (int t = 0; t <= T; ++t) cb[t] = t * (M / T);
+    }
+    try {
+        // evenly spaced sample
+        const int64_t cap = (int64_t)1 << 18;
+        const int64_t step = (N + cap - 1) / cap, n = (N + step - 1) / step;
+        std::vector<uint8_t> rows((size_t)n * M);
+        for (int64_t i = 0; i < n; ++i) memcpy(rows.data() + (size_t)i * M, codes + (size_t)(i * step) * M, (size_t)M);
+        for (size_t i = 0; i < rows.size(); ++i)
+            if (rows[i] >= ctx->K) return fail(ctx, ETF_EINVAL, "a code byte is >= K=%d", ctx->K);
+        std::vector<bool> used(M, false);
+        std::vector<uint32_t> gid((size_t)n);
+        int pos = 0;
+        for (int t = 0; t < T; ++t) {
+            std::fill(gid.begin(), gid.end(), 0u);  // every tree starts from the empty prefix
+            for (int l = cb[t]; l < cb[t + 1]; ++l, ++pos) {
+                // distinct (prefix so far, chunk c) pairs for every remaining chunk c
+                std::vector<int64_t> distinct(M, -1);
+                std::vector<int> cand;
+                for (int c = 0; c < M; ++c)
+                    if (!used[c]) cand.push_back(c);
+                parallel_slices((int64_t)cand.size(), host_threads(), [&](int, int64_t lo, int64_t hi) {
+                    std::vector<uint64_t> keys((size_t)n);
+                    for (int64_t ci = lo; ci < hi; ++ci) {
+                        const int c = cand[ci];
+                        for (int64_t i = 0; i < n; ++i) keys[i] = ((uint64_t)gid[i] << 8) | rows[(size_t)i * M + c];
+                        std::sort(keys.begin(), keys.end());
+                        distinct[c] = (int64_t)(std::unique(keys.begin(), keys.end()) - keys.begin());
+                    }
+                });
+                int best = cand[0];
+                for (int c : cand)
+                    if (distinct[c] < distinct[best]) best = c;  // ties: the lowest chunk number
+                used[best] = true;
+                order_out[pos] = best;
+                // the prefixes one level further down, numbered densely
+                std::vector<uint64_t> keys((size_t)n);
+                for (int64_t i = 0; i < n; ++i) keys[i] = ((uint64_t)gid[i] << 8) | rows[(size_t)i * M + best];
+                std::vector<uint64_t> uniq(keys);
+                std::sort(uniq.begin(), uniq.end());
+                uniq.erase(std::unique(uniq.begin(), uniq.end()), uniq.end());
+                for (int64_t i = 0; i < n; ++i) gid[i] = (uint32_t)(std::lower_bound(uniq.begin(), uniq.end(), keys[i]) - uniq.begin());
+            }
+        }
+        int rc;
+        if (lookups_given && (rc = count_lookups(ctx, rows.data(), n, T, cb.data(), nullptr, lookups_given))) return rc;
+        if (lookups_order && (rc = count_lookups(ctx, rows.data(), n, T, cb.data(), order_out, lookups_order))) return rc;
+    } catch (const std::bad_alloc &) {
+        return fail(ctx, ETF_ENOMEM, "out of host memory while choosing the chunk order");
+    }
+    return ETF_OK;
+}
+
 extern "C" int etf_index_stats(const etf_ctx *ctx, etf_stats *out)
 {
     if (!ctx) return ETF_EINVAL;
@@ -734,6 +859,7 @@ extern "C" int etf_index_stats(const etf_ctx *ctx, etf_stats *out)
         out->paper_bytes[t] = 4 * ix.N + 2 * (out->L1[t] + out->L2[t]) + out->sumP[t];
     }
     out->device_bytes = ctx->lay.total;
+    for (int j = 0; j < ix.M; ++j) out->chunk_order[j] = ix.order[j];
     return ETF_OK;
 }
 

@@ -58,6 +58,7 @@ struct HostIndex {
     int M = 0, K = 0, T = 0;
     int64_t N = 0, Nd = 0, max_dup = 0;
     std::vector<int32_t> chunk_begin;       // [T+1]
+    std::vector<int32_t> order;             // [M] position j of the index's encodings holds input chunk order[j]
     std::vector<uint8_t> codes;             // [N][M] input order
     std::vector<int32_t> ids_in;            // [N] ids in input order
     std::vector<int32_t> ids_sorted;        // [N] ids in (encoding, id) order
@@ -124,6 +125,7 @@ struct etf_ctx {
     etf::DevLayout lay;
     char *dev_base = nullptr;               // caller-owned buffer holding the device image
     etf::Options opt;
+    std::vector<int32_t> next_order;        // chunk order of the next index build (empty: as given)
     // diagnostics of the most recent search (device address inside the caller's workspace)
     void *last_flag_count = nullptr;
     // per-kernel timing: pairs of hipEvent_t (stored untyped so that host-only code need not see HIP)

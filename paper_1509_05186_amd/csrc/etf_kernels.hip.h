@@ -73,6 +73,12 @@ __device__ __forceinline__ float run_pick(float loaded, float before, uint32_t m
     return __uint_as_float((__float_as_uint(loaded) & m) | (__float_as_uint(before) & ~m));
 }
 
+// Position m of the index's encodings holds chunk src[m] of the encodings as the quantiser produces them (the
+// builder's chunk order): slice m of a tile's tables is the table of dimension group src[m].
+struct ChunkOrder {
+    uint8_t src[ETF_MAX_M];
+};
+
 // ------------------------------------------------------------------------------------------------
 // S1  lookup tables (paper Eq. 1, first term on each group's own dimensions), plain float32 form.
 //     IP: the scalar products q_m . c instead (the paper's remark that the tables may hold scalar products).
@@ -81,14 +87,14 @@ __device__ __forceinline__ float run_pick(float loaded, float before, uint32_t m
 template <bool IP>
 __global__ __launch_bounds__(256) void k_lut_direct(const float *__restrict__ queries, int64_t Q, int64_t q0, int d,
                                                     int M, int K, const float *__restrict__ codebooks,
-                                                    float *__restrict__ lutT, float *__restrict__ lut_public)
+                                                    float *__restrict__ lutT, float *__restrict__ lut_public, ChunkOrder ord)
 {
-    const int tile = blockIdx.x, m = blockIdx.y;
+    const int tile = blockIdx.x, m = blockIdx.y, ms = ord.src[m];
     const int lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6);
     const int ds = d / M;
     const int64_t q = q0 + (int64_t)tile * QT + lane;
     const bool live = q < Q;
-    const float *qv = queries + (live ? q : 0) * d + (int64_t)m * ds;
+    const float *qv = queries + (live ? q : 0) * d + (int64_t)ms * ds;
     const int kbase = w * 64;
     float acc[64];
 #pragma unroll
@@ -102,7 +108,7 @@ __global__ __launch_bounds__(256) void k_lut_direct(const float *__restrict__ qu
         for (int i = 0; i < 64; ++i) {
             const int k = kbase + i;
             if (k < K) {
-                const float *c = codebooks + ((int64_t)m * K + k) * ds + j0;
+                const float *c = codebooks + ((int64_t)ms * K + k) * ds + j0;
                 for (int jj = 0; jj < nj; ++jj) {
                     if (IP) {
                         acc[i] = fmaf(x[jj], c[jj], acc[i]);
@@ -119,7 +125,7 @@ __global__ __launch_bounds__(256) void k_lut_direct(const float *__restrict__ qu
         const int k = kbase + i;
         if (k < K) {
             if (lutT) lutT[(((int64_t)tile * M + m) * K + k) * QT + lane] = acc[i];
-            if (lut_public && live) lut_public[(q * M + m) * K + k] = acc[i];
+            if (lut_public && live) lut_public[(q * M + ms) * K + k] = acc[i];
         }
     }
 }
@@ -169,9 +175,9 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
                                                   int K, const float *__restrict__ cb, const float *__restrict__ cbc,
                                                   const float *__restrict__ cbnorm, const float *__restrict__ cbmean,
                                                   int dsp, float *__restrict__ lutT,
-                                                  float *__restrict__ lut_public)
+                                                  float *__restrict__ lut_public, ChunkOrder ord)
 {
-    const int tile = blockIdx.x, m = blockIdx.y;
+    const int tile = blockIdx.x, m = blockIdx.y, ms = ord.src[m];
     const int lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6);
     const int ds = d / M;
     const int col = lane & 31, half = lane >> 5;
@@ -183,7 +189,7 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
     for (int cb = 0; cb < 2; ++cb) {
         const int64_t q = q0 + (int64_t)tile * QT + cb * 32 + col;
         qlive[cb] = q < Q;
-        qrow[cb] = queries + (qlive[cb] ? q : 0) * d + (int64_t)m * ds;
+        qrow[cb] = queries + (qlive[cb] ? q : 0) * d + (int64_t)ms * ds;
     }
     // A operand: the two codewords this lane feeds (rows col and col + 32 of the wave's 64)
     const float *crow[2];
@@ -192,9 +198,9 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
     for (int rb = 0; rb < 2; ++rb) {
         const int k = kbase + rb * 32 + col;
         clive[rb] = k < K;
-        crow[rb] = cbc + ((int64_t)m * K + (clive[rb] ? k : 0)) * dsp;
+        crow[rb] = cbc + ((int64_t)ms * K + (clive[rb] ? k : 0)) * dsp;
     }
-    const float *mean = cbmean + (int64_t)m * ds;
+    const float *mean = cbmean + (int64_t)ms * ds;
     floatx16 acc[2][2];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
@@ -234,7 +240,7 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
         for (int r = 0; r < 16; ++r) {
             const int k = kbase + rb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
             if (k < K) {
-                const float cc = cbnorm[(int64_t)m * K + k];
+                const float cc = cbnorm[(int64_t)ms * K + k];
 #pragma unroll
                 for (int cb = 0; cb < 2; ++cb) {
                     const float nn = qq[cb] + cc;
@@ -254,7 +260,7 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
                     if (!small) {
                         if (lutT) lutT[(((int64_t)tile * M + m) * K + k) * QT + ql] = v;
                         const int64_t q = q0 + (int64_t)tile * QT + ql;
-                        if (lut_public && q < Q) lut_public[(q * M + m) * K + k] = v;
+                        if (lut_public && q < Q) lut_public[(q * M + ms) * K + k] = v;
                     }
                 }
             }
@@ -265,8 +271,8 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
         const int ql = fix[i] >> 8, k = fix[i] & 255;
         const int64_t q = q0 + (int64_t)tile * QT + ql;
         const bool live = q < Q;
-        const float *x = queries + (live ? q : 0) * d + (int64_t)m * ds;
-        const float *c = cb + ((int64_t)m * K + k) * ds;
+        const float *x = queries + (live ? q : 0) * d + (int64_t)ms * ds;
+        const float *c = cb + ((int64_t)ms * K + k) * ds;
         float sum = 0.f;
         if ((ds & 3) == 0 && (d & 3) == 0) {  // rows of both arrays are 16-byte aligned: four terms per load
             const float4 *x4 = reinterpret_cast<const float4 *>(x), *c4 = reinterpret_cast<const float4 *>(c);
@@ -292,7 +298,7 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
             }
         }
         if (lutT) lutT[(((int64_t)tile * M + m) * K + k) * QT + ql] = sum;
-        if (lut_public && live) lut_public[(q * M + m) * K + k] = sum;
+        if (lut_public && live) lut_public[(q * M + ms) * K + k] = sum;
     }
 }
 

@@ -14,11 +14,12 @@ torch = pytest.importorskip("torch")
 import paper_1509_05186_amd as etf  # noqa: E402
 
 
-def dev_ctx(cb, codes, ids=None, T=1, chunk_begin=None, **opts):
+def dev_ctx(cb, codes, ids=None, T=1, chunk_begin=None, order=None, **opts):
     c = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
     for name, v in opts.items():
         c.set_option(name, v)
     c.pq_set_codebooks(cb)
+    c.index_set_chunk_order(order)
     img = c.index_build_device(torch.from_numpy(codes).cuda(), None if ids is None else torch.from_numpy(ids).cuda(),
                                T=T, chunk_begin=chunk_begin)
     torch.cuda.synchronize()
@@ -73,12 +74,13 @@ def image_arrays(lay, st, M):
     return out
 
 
-def assert_same_as_host_build(c, img, cb, codes, ids, T, chunk_begin, **opts):
-    """Every array of the device-built image equals the host builder's, at the same offset."""
+def assert_same_as_host_build(c, img, cb, codes, ids, T, chunk_begin, order=None, **opts):
+    """Every array of the device-built image equals the host builder's."""
     h = etf.Context(device=None)
     for name, v in opts.items():
         h.set_option(name, v)
     h.pq_set_codebooks(cb)
+    h.index_set_chunk_order(order)
     h.index_build(codes, ids=ids, T=T, chunk_begin=chunk_begin)
     hs, hl, hbuf = h.index_stats(), h.index_layout(), h.index_export()
     ds, dl = c.index_stats(), c.index_layout()

@@ -216,3 +216,76 @@ def test_builder_sampling_on_larger_input():
     lut = rng.random((M, K))
     dist, _ = walk_image(c, lut)
     assert np.allclose(dist, oracle.adc_flat(lut, codes), rtol=1e-13)
+
+
+# ---------------------------------------------------------------- chunk order
+def test_chunk_order_builder():
+    rng = np.random.default_rng(8)
+    N, M, K = 3000, 8, 16
+    codes = rng.integers(0, K, size=(N, M)).astype(np.uint8)
+    codes[:, 5] //= 8                                              # two values only: a chunk worth having on top
+    order = np.array([5, 2, 7, 0, 1, 6, 3, 4], dtype=np.int32)
+    c = host_ctx(np.zeros((M, K, 1), dtype=np.float32))
+    with pytest.raises(etf.EtfError):
+        c.index_set_chunk_order([0, 1, 2, 3, 4, 5, 6, 6])          # not a permutation
+    with pytest.raises(etf.EtfError):
+        c.index_set_chunk_order([0, 1, 2, 3, 4, 5, 6, 8])
+    c.index_set_chunk_order(order)
+    c.index_build(codes, T=2)
+    st, lay, buf = c.index_stats(), c.index_layout(), c.index_export()
+    assert st["chunk_order"] == order.tolist()
+    Nd = st["n_distinct"]
+    # the index holds the encodings with their chunks in that order
+    assert np.array_equal(arr(buf, lay.codes, N * M, np.uint8).reshape(N, M), codes[:, order])
+    assert np.array_equal(arr(buf, lay.ecodes, Nd * M, np.uint8).reshape(Nd, M), np.unique(codes[:, order], axis=0))
+    # a walk over the image with the tables in index order gives the distances of the original codes
+    lut = rng.random((M, K))
+    dist, _ = walk_image(c, lut[order])
+    assert np.allclose(dist, oracle.adc_flat(lut, codes), rtol=1e-13)
+    # and the tree statistics are those of the pointer trie over the reordered chunks
+    for t, (a, b) in enumerate([(0, 4), (4, 8)]):
+        tr = EncodingTree(codes[:, order][:, a:b])
+        assert st["trees"][t]["lookups"] == tr.stats()["lookups"]
+    # the order lasts until it is changed; a new quantiser drops it
+    c.index_build(codes, T=1)
+    assert c.index_stats()["chunk_order"] == order.tolist()
+    c.index_set_chunk_order(None)
+    c.index_build(codes, T=1)
+    assert c.index_stats()["chunk_order"] == list(range(M))
+    c.index_set_chunk_order(order)
+    c.pq_set_codebooks(np.zeros((M, K, 1), dtype=np.float32))
+    c.index_build(codes, T=1)
+    assert c.index_stats()["chunk_order"] == list(range(M))
+
+
+def test_suggest_chunk_order():
+    rng = np.random.default_rng(9)
+    N, M, K = 20000, 8, 64
+    codes = rng.integers(0, K, size=(N, M)).astype(np.uint8)
+    codes[:, 5] //= 32                                             # 2 values
+    codes[:, 2] //= 16                                             # 4 values
+    codes[:, 6] //= 4                                              # 16 values
+    c = host_ctx(np.zeros((M, K, 1), dtype=np.float32))
+    order, given, best = c.suggest_chunk_order(codes, T=1)
+    assert sorted(order.tolist()) == list(range(M))
+    assert order[:3].tolist() == [5, 2, 6]                         # fewest distinct prefixes first
+    assert best < given
+    # the reported counts are the statistics of the index in either order
+    c.index_build(codes, T=1)
+    assert sum(t["lookups"] for t in c.index_stats()["trees"]) == given
+    c.index_set_chunk_order(order)
+    c.index_build(codes, T=1)
+    assert sum(t["lookups"] for t in c.index_stats()["trees"]) == best
+    # a forest: every tree starts from the empty prefix, so the two narrowest chunks head the two trees... no:
+    # tree 0 is filled first (levels 0..3), then tree 1 from what is left
+    c.index_set_chunk_order(None)
+    order2, given2, best2 = c.suggest_chunk_order(codes, T=2)
+    assert sorted(order2.tolist()) == list(range(M)) and order2[:3].tolist() == [5, 2, 6] and best2 <= given2
+    with pytest.raises(etf.EtfError):
+        c.suggest_chunk_order(codes, T=3)                          # 3 does not divide 8
+    # correlated chunks: chunk 4 repeats chunk 1, so once chunk 1 is placed chunk 4 splits nothing
+    codes2 = rng.integers(0, 4, size=(N, M)).astype(np.uint8)
+    codes2[:, 4] = codes2[:, 1]
+    order3, given3, best3 = c.suggest_chunk_order(codes2, T=1)
+    i1, i4 = order3.tolist().index(1), order3.tolist().index(4)
+    assert abs(i1 - i4) == 1 and best3 <= given3
