@@ -321,6 +321,25 @@ def main():
         log("largest scalar products, E-Forest(T=%d) top-%d: %.2f ms/step, %.3e products/s"
             % (T, k, others["scalar_product_search"]["ms_per_step"], others["scalar_product_search"]["value"]))
         del ipc, w4
+        # chunk order: the greedy suggestion for this database, its lookup count and the search on an index in that order
+        oc = etf.Context(device=0, stream=stream)
+        oc.set_option("traversal", args.traversal)
+        oc.pq_set_codebooks(cb)
+        t0 = time.time()
+        order, lk_given, lk_order = oc.suggest_chunk_order(codes, T=T)
+        t_suggest = time.time() - t0
+        oc.index_set_chunk_order(order)
+        oc.index_build(codes, T=T)
+        oc.index_upload()
+        oc.profile_enable(not args.no_profile)
+        w5 = oc.alloc_workspace(Q, k, mode)
+        d5, p5 = time_search(oc, qd, k, mode, 1, osteps, torch, w5, out_ids, out_dist, cfg.query_batch)
+        others["chunk_order"] = {"order": [int(v) for v in order], "lookups_given_order": lk_given, "lookups_suggested_order": lk_order,
+                                 "lookups_on": "at most 2^18 evenly spaced vectors", "suggest_s": t_suggest,
+                                 "ms_per_step": d5 / osteps * 1e3, "n_distinct": oc.index_stats()["n_distinct"],
+                                 "kernels_ms_per_step": {n: v[0] / osteps for n, v in p5.items() if v[1]}}
+        log("chunk order %s: lookups %d -> %d (sample), search %.2f ms/step" % (others["chunk_order"]["order"], lk_given, lk_order, d5 / osteps * 1e3))
+        del oc, w5
         if args.traversal == 2:
             # the same index built on the device from device-resident codes, and the same search on it
             db = etf.Context(device=0, stream=stream)
