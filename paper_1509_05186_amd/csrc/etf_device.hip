@@ -313,7 +313,12 @@ int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_
     ChunkOrder ord;
     for (int j = 0; j < ETF_MAX_M; ++j) ord.src[j] = (uint8_t)((size_t)j < ctx->idx.order.size() ? ctx->idx.order[j] : j);
     ProfScope prof(ctx, ETF_K_LUT);
-    if (ctx->opt.metric == 1) {
+    if (ctx->opt.metric == 1 && ctx->opt.lut_kernel == 0) {
+        const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
+        hipLaunchKernelGGL(k_lut_mfma<true>, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
+                           cb, nullptr, nullptr, nullptr, ctx->dsp, lutT, lut_public, ord);
+        LAUNCH_CHECK(ctx, "k_lut_mfma");
+    } else if (ctx->opt.metric == 1) {
         const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
         hipLaunchKernelGGL(k_lut_direct<true>, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M,
                            ctx->K, cb, lutT, lut_public, ord);
@@ -323,7 +328,7 @@ int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_
         const float *cbn = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_norm);
         const float *cbm = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_mean);
         const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
-        hipLaunchKernelGGL(k_lut_mfma, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
+        hipLaunchKernelGGL(k_lut_mfma<false>, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
                            cb, cbc, cbn, cbm, ctx->dsp, lutT, lut_public, ord);
         LAUNCH_CHECK(ctx, "k_lut_mfma");
     } else {

@@ -167,10 +167,12 @@ __global__ __launch_bounds__(256) void k_lut_shift(float *__restrict__ lutT, int
 //     accumulator register r of lane l is D[i = 8 * (r / 4) + 4 * (l / 32) + r % 4][j = l % 32], so for a
 //     fixed r the lanes 0..31 hold 32 consecutive queries of one codeword: a 128-byte piece of a table row.
 //     Entries that are small against the norms are recomputed exactly (see below).
+//     IP: the tables hold the scalar products q_m . c themselves: the contraction on the unshifted vectors.
 //     grid (tiles, M), block 256 (wave w: codewords 64w .. 64w+63).
 // ------------------------------------------------------------------------------------------------
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
+template <bool IP>
 __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ queries, int64_t Q, int64_t q0, int d, int M,
                                                   int K, const float *__restrict__ cb, const float *__restrict__ cbc,
                                                   const float *__restrict__ cbnorm, const float *__restrict__ cbmean,
@@ -198,9 +200,9 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
     for (int rb = 0; rb < 2; ++rb) {
         const int k = kbase + rb * 32 + col;
         clive[rb] = k < K;
-        crow[rb] = cbc + ((int64_t)ms * K + (clive[rb] ? k : 0)) * dsp;
+        crow[rb] = IP ? cb + ((int64_t)ms * K + (clive[rb] ? k : 0)) * ds : cbc + ((int64_t)ms * K + (clive[rb] ? k : 0)) * dsp;
     }
-    const float *mean = cbmean + (int64_t)ms * ds;
+    const float *mean = IP ? nullptr : cbmean + (int64_t)ms * ds;
     floatx16 acc[2][2];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
@@ -213,10 +215,10 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
         const int j = j0 + half;
         float a[2], b[2];
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) a[rb] = clive[rb] ? crow[rb][j] : 0.f;
+        for (int rb = 0; rb < 2; ++rb) a[rb] = (clive[rb] && (!IP || j < ds)) ? crow[rb][j] : 0.f;
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
-            b[cb] = (qlive[cb] && j < ds) ? qrow[cb][j] - mean[j] : 0.f;
+            b[cb] = (qlive[cb] && j < ds) ? (IP ? qrow[cb][j] : qrow[cb][j] - mean[j]) : 0.f;
             qq[cb] = fmaf(b[cb], b[cb], qq[cb]);
         }
 #pragma unroll
@@ -240,13 +242,13 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
         for (int r = 0; r < 16; ++r) {
             const int k = kbase + rb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
             if (k < K) {
-                const float cc = cbnorm[(int64_t)ms * K + k];
+                const float cc = IP ? 0.f : cbnorm[(int64_t)ms * K + k];
 #pragma unroll
                 for (int cb = 0; cb < 2; ++cb) {
                     const float nn = qq[cb] + cc;
-                    const float v = nn - 2.f * acc[rb][cb][r];
+                    const float v = IP ? acc[rb][cb][r] : nn - 2.f * acc[rb][cb][r];
                     const int ql = cb * 32 + col;
-                    const bool small = v < 0.25f * nn;
+                    const bool small = !IP && v < 0.25f * nn;   // scalar products: the contraction is the result
                     // append the wave's small entries with one reservation (rank among them from the ballot)
                     const uint64_t smask = __ballot(small);
                     if (smask != 0ull) {

@@ -39,16 +39,32 @@ def dups():
     return IpProblem(d=16, M=4, K=4, N=6000, Q=70, ntrain=500, seed=12, dup_factor=3)
 
 
-def test_scalar_product_tables(small):
-    say("scalar-product tables")
+@pytest.mark.parametrize("lut_kernel", [0, 1])     # 0: the contraction on the matrix cores, 1: plain float32 sums
+def test_scalar_product_tables(small, lut_kernel):
+    say("scalar-product tables, table kernel", lut_kernel)
     p = small
-    c = p.ctx(T=1, metric=1)
+    c = p.ctx(T=1, metric=1, lut_kernel=lut_kernel)
     lut = c.lut_build(qdev(p)).cpu().numpy().astype(np.float64)
     M, K, ds = p.cb.shape
     for j in range(0, p.Q, 7):
         ref = oracle.lut_ip(p.q[j], p.cb)
         mag = np.abs(p.cb.astype(np.float64)) @ np.abs(p.q[j].astype(np.float64)).reshape(M, ds, 1)    # sum |q_i| |c_i|
         assert np.all(np.abs(lut[j] - ref) <= IP_TOL * mag[:, :, 0]), j
+
+
+def test_scalar_product_tables_odd_group_width():
+    say("scalar-product tables: 17 dimensions per group, 50 codewords, a ragged tile of queries")
+    p = IpProblem(d=119, M=7, K=50, N=500, Q=70, ntrain=600, seed=21)
+    M, K, ds = p.cb.shape
+    for lut_kernel in (0, 1):
+        c = p.ctx(T=1, metric=1, lut_kernel=lut_kernel)
+        lut = c.lut_build(qdev(p)).cpu().numpy().astype(np.float64)
+        for j in range(p.Q):
+            ref = oracle.lut_ip(p.q[j], p.cb)
+            mag = np.abs(p.cb.astype(np.float64)) @ np.abs(p.q[j].astype(np.float64)).reshape(M, ds, 1)
+            assert np.all(np.abs(lut[j] - ref) <= IP_TOL * mag[:, :, 0]), (lut_kernel, j)
+        got = c.adc(qdev(p), TREE).cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - p.ref_ip) <= IP_TOL * p.scale[:, None])
 
 
 @pytest.mark.parametrize("trav", [0, 1, 2])
