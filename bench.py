@@ -303,9 +303,14 @@ def main():
         tree = make_ctx(1)
         for name, ctx, m in (("flat_gpu", tree, etf.ETF_MODE_FLAT), ("e_tree_gpu", tree, etf.ETF_MODE_TREE)):
             w2 = ctx.alloc_workspace(Q, k, m)
-            d2, p2 = time_search(ctx, qd, k, m, 1, osteps, torch, w2, out_ids, out_dist, cfg.query_batch)
-            others[name] = {"value": N * Q * osteps / d2, "ms_per_step": d2 / osteps * 1e3,
-                            "kernels_ms_per_step": {n: v[0] / osteps for n, v in p2.items() if v[1]}}
+            # The flat scan lists every copy of an encoding; where one encoding has more copies than a candidate
+            # list holds, every query ends in the whole-database selection kernel: one untimed-warm-up-free step
+            heavy = m == etf.ETF_MODE_FLAT and ctx.index_stats()["max_dup"] > 32768
+            fw, fs = (0, 1) if heavy else (1, osteps)
+            d2, p2 = time_search(ctx, qd, k, m, fw, fs, torch, w2, out_ids, out_dist, cfg.query_batch)
+            others[name] = {"value": N * Q * fs / d2, "ms_per_step": d2 / fs * 1e3, "steps": fs,
+                            "fallback_queries": ctx.last_fallback_count(),
+                            "kernels_ms_per_step": {n: v[0] / fs for n, v in p2.items() if v[1]}}
             log("%s: %.2f ms/step, %.3e distances/s" % (name, others[name]["ms_per_step"], others[name]["value"]))
             del w2
         others["e_tree_stats"] = tree.index_stats()["trees"]

@@ -99,6 +99,8 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     etf_index_build): max(sample_min, sample_scale * sqrt(n)), n = number of distinct
  *                     encodings (of vectors in flat mode); defaults 32768 and 90
  *   "cand_cap"        per-query candidate capacity (0 = derived from k)
+ *   "lds_blocks"      workgroups per sub-tile of queries in the LDS-resident kernels (0 = chosen by the
+ *                     library from the number of sub-tiles and items; for experiments)
  *   "metric"          0 (default): squared Euclidean distance.  1: scalar product (the paper notes, after
  *                     Eq. 1 and in its conclusion, that tables of scalar products serve the same
  *                     machinery): etf_lut_build gives lut[q][m][c] = <queries[q] group m, codeword c>,
@@ -166,7 +168,8 @@ int etf_index_stats(const etf_ctx *ctx, etf_stats *out);
  * positions.  The array `codes` of the device image holds the reordered encodings.
  * etf_suggest_chunk_order: a greedy order for the given codes ([N][M] host) and tree shape: tree after
  * tree, level after level, the remaining chunk that splits the tree's prefixes so far into the fewest
- * distinct prefixes (evaluated on at most 2^18 evenly spaced vectors).  order_out [M]; lookups_given /
+ * distinct prefixes (evaluated on at most 2^18 evenly spaced vectors); if that order does not save
+ * lookups on those vectors, the given order is returned.  order_out [M]; lookups_given /
  * lookups_order (either may be NULL) receive the table lookups of one traversal, L1 + L2 + sumP summed
  * over the trees, of those vectors' index in the given and in the suggested order. */
 int etf_index_set_chunk_order(etf_ctx *ctx, const int32_t *order);

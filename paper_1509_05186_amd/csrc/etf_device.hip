@@ -288,6 +288,26 @@ int64_t blocks_for(int64_t n, int64_t min_items_per_block, int64_t other_dims)
     return std::max<int64_t>(1, std::min<int64_t>(b, want));
 }
 
+// Workgroups per sub-tile of queries for the LDS-resident kernels.  A CU holds one workgroup (its tables fill the
+// LDS), so a launch of W * bx workgroups runs in ceil(W * bx / 256) rounds, and each round pays for staging the
+// tables (measured: 11.4 us, the time of about 8600 items at M = 8) before it walks nitems / bx items: the cost of a
+// choice is rounds * (8600 + nitems / bx), in items.  Few large workgroups win unless they leave CUs idle.
+int64_t lds_blocks_for(int64_t W, int64_t nitems, int64_t min_bx)
+{
+    const int64_t cus = 256, stage_items = 8600;
+    int64_t best = min_bx, best_cost = -1;
+    for (int64_t bx = min_bx; bx < min_bx + 256; ++bx) {
+        const int64_t rounds = (W * bx + cus - 1) / cus;
+        const int64_t cost = rounds * (stage_items + (nitems + bx - 1) / bx);
+        if (best_cost < 0 || cost < best_cost) {
+            best = bx;
+            best_cost = cost;
+        }
+        if (W * bx >= 16 * cus) break;  // beyond 16 rounds only the staging grows
+    }
+    return best;
+}
+
 int pick_G(int width, int K)
 {
     int G = 1;
@@ -636,7 +656,10 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
         bx = blocks_for(o.ngroups, 2 * 16 * IPS, tiles * G);
     } else {
         // item numbers inside a workgroup's share travel in 26 bits
-        bx = std::max(blocks_for(nitems, 16384, tiles * G), (nitems >> 25) + 1);
+        bx = lds_blocks_for(tiles * G, nitems, (nitems >> 25) + 1);
+        // the all-pairs output is bound by its stores, which like many workgroups taking turns along the rows
+        if (MODE == OUT_ALLPAIRS) bx = std::max(bx, blocks_for(nitems, 16384, tiles * G));
+        if (ctx->opt.lds_blocks > 0) bx = std::max<int64_t>(ctx->opt.lds_blocks, (nitems >> 25) + 1);
         per_block = (int)((nitems + bx - 1) / bx);
     }
     dim3 grid((unsigned)bx, (unsigned)G, (unsigned)tiles);

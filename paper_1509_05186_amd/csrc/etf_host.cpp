@@ -381,6 +381,9 @@ extern "C" int etf_set_option(etf_ctx *ctx, const char *name, int64_t value)
     } else if (n == "lut_kernel") {
         if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "lut_kernel must be 0 (matrix cores) or 1 (plain sums)");
         ctx->opt.lut_kernel = value;
+    } else if (n == "lds_blocks") {
+        if (value < 0 || value > 65535) return fail(ctx, ETF_EINVAL, "lds_blocks out of range");
+        ctx->opt.lds_blocks = value;
     } else if (n == "metric") {
         if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "metric must be 0 (squared Euclidean distance) or 1 (scalar product)");
         ctx->opt.metric = value;
@@ -827,9 +830,17 @@ extern "C" int etf_suggest_chunk_order(const etf_ctx *ctx, const uint8_t *codes,
                 for (int64_t i = 0; i < n; ++i) gid[i] = (uint32_t)(std::lower_bound(uniq.begin(), uniq.end(), keys[i]) - uniq.begin());
             }
         }
+        // the greedy choice looks one level ahead only: keep the given order unless the suggestion saves lookups
+        int64_t given = 0, suggested = 0;
         int rc;
-        if (lookups_given && (rc = count_lookups(ctx, rows.data(), n, T, cb.data(), nullptr, lookups_given))) return rc;
-        if (lookups_order && (rc = count_lookups(ctx, rows.data(), n, T, cb.data(), order_out, lookups_order))) return rc;
+        if ((rc = count_lookups(ctx, rows.data(), n, T, cb.data(), nullptr, &given))) return rc;
+        if ((rc = count_lookups(ctx, rows.data(), n, T, cb.data(), order_out, &suggested))) return rc;
+        if (suggested >= given) {
+            for (int j = 0; j < M; ++j) order_out[j] = j;
+            suggested = given;
+        }
+        if (lookups_given) *lookups_given = given;
+        if (lookups_order) *lookups_order = suggested;
     } catch (const std::bad_alloc &) {
         return fail(ctx, ETF_ENOMEM, "out of host memory while choosing the chunk order");
     }

@@ -97,6 +97,7 @@ struct Options {
     int64_t sample_scale = 90;  // sample size = max(sample_min, sample_scale * sqrt(n))
     int64_t cand_cap = 0;
     int64_t traversal = 2;  // 0: distance context in registers, 1: level-synchronous kernels, 2: searches with all tables in LDS
+    int64_t lds_blocks = 0; // workgroups per sub-tile of queries in the LDS-resident search kernel (0: chosen by the library)
     int64_t metric = 0;     // 0: squared Euclidean distance (smallest first), 1: scalar product (largest first)
     int64_t lut_kernel = 0; // 0: matrix cores (expanded form on centred vectors, small entries recomputed), 1: plain (a-b)^2 sums
 };
