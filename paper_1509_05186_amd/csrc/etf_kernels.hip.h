@@ -730,13 +730,27 @@ __host__ __device__ constexpr int lds_chunks_per_line(int G) { return G == 8 ? 8
 template <int G>
 __device__ __forceinline__ void stage_lines(float *lds, const float *__restrict__ lutT, int tile, int g, int M, int K, int KP)
 {
-    constexpr int Qs = WAVE / G, CPL = lds_chunks_per_line(G);
-    const int total = M * K * Qs;
+    // 16 bytes per load and store, eight loads in flight per thread before the first store: a workgroup of 1024
+    // threads moves the 128 KB of a sub-tile in one trip
+    constexpr int Qs = WAVE / G, CPL = lds_chunks_per_line(G), P4 = Qs / 4, UN = 8;
+    const int total = M * K * P4;  // 16-byte pieces: row (m, k) has P4 of them
     const float *src = lutT + (int64_t)tile * M * K * QT + g * Qs;
-    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
-        const int row = idx / Qs, qq = idx % Qs;  // row = m * K + k
-        const int m = row / K, k = row - m * K;
-        lds[(((m / CPL) * KP + k) * CPL + (m % CPL)) * Qs + qq] = src[(int64_t)row * QT + qq];
+    for (int base = 0; base < total; base += (int)blockDim.x * UN) {
+        float4 v[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int idx = base + u * (int)blockDim.x + (int)threadIdx.x;
+            if (idx < total) v[u] = *reinterpret_cast<const float4 *>(src + (int64_t)(idx / P4) * QT + (idx % P4) * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int idx = base + u * (int)blockDim.x + (int)threadIdx.x;
+            if (idx < total) {
+                const int row = idx / P4, p = idx % P4;  // row = m * K + k
+                const int m = K == 256 ? row >> 8 : row / K, k = row - m * K;
+                *reinterpret_cast<float4 *>(lds + (((m / CPL) * KP + k) * CPL + (m % CPL)) * Qs + p * 4) = v[u];
+            }
+        }
     }
     __syncthreads();
 }
