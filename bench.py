@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised
 # under profiles/ (counters scaled by what a 1 GiB copy in the same run reads).  Keyed by (workload, kernel class,
 # traversal); reported only for the exact configuration that was profiled.
-MEASURED_TRAFFIC_BYTES = {("cfg2", "reduce", "register-context"): 9.312e9, ("cfg2", "lds", "lds-resident"): 1.164e9}
+MEASURED_TRAFFIC_BYTES = {("cfg2", "reduce", "register-context"): 9.361e9, ("cfg2", "lds", "lds-resident"): 0.875e9}
 # LDS read bandwidth of the chip: 256 compute units x 256 bytes per clock x 2.4 GHz (a conflict-free 16-byte-per-lane
 # wave read, 1 KiB, occupies the LDS pipe for 4 clocks: SQ_LDS_IDX_ACTIVE minus SQ_LDS_BANK_CONFLICT per read)
 LDS_PEAK_GBS = 256 * 256 * 2.4
