@@ -132,3 +132,12 @@ def test_metric_switches_per_call_and_matches_oracle_search(small):
     assert np.all(np.abs(ov.cpu().numpy() - rv) <= IP_TOL * p.scale[:, None])
     with pytest.raises(etf.EtfError):
         c.set_option("metric", 2)
+
+
+@pytest.mark.parametrize("N,Q,k", [(50, 5, 10), (1, 3, 1), (300, 130, 300)])
+def test_scalar_product_search_tiny_databases(N, Q, k):
+    say("largest scalar products on a tiny database: every encoding is a candidate; N", N, "Q", Q, "k", k)
+    p = IpProblem(d=16, M=4, K=16, N=N, Q=Q, ntrain=200, seed=31)
+    for mode, T in [(FLAT, 1), (TREE, 1), (FOREST, 2)]:
+        c = p.ctx(T=T, metric=1)
+        check_ip_search(p, c, mode, k, what="ip tiny m%d" % mode)

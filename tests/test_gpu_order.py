@@ -73,7 +73,7 @@ def test_reordered_index_built_on_the_device(small):
     torch.cuda.synchronize()
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
     check_search(p, c, FOREST, 50, what="reordered device-built")
-    # sixteen chunks, in place: the codes already sit in the image's own array
+    # sixteen chunks, four trees, a random order
     w = Problem(d=64, M=16, K=256, N=12000, Q=70, ntrain=3000, seed=13)
     order16 = np.random.default_rng(2).permutation(16).tolist()
     c2, img2 = dev_ctx(w.cb, w.codes, None, T=4, order=order16, sample_min=1024)
