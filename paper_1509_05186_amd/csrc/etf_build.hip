@@ -144,7 +144,9 @@ __global__ void __launch_bounds__(BT) k_build_maxdup(const uint32_t *ebegin, uin
     const int64_t e = (int64_t)blockIdx.x * BT + threadIdx.x;
     uint32_t n = e < (int64_t)scal[0] ? ebegin[e + 1] - ebegin[e] : 0;
     for (int o = 32; o > 0; o >>= 1) n = max(n, (uint32_t)__shfl_xor((int)n, o));
-    if ((threadIdx.x & 63) == 0 && n) atomicMax(&scal[1], n);
+    // one atomic per wave, and only where it can still raise the maximum (the plain read may be stale: it only
+    // filters; almost every wave then skips the contended address)
+    if ((threadIdx.x & 63) == 0 && n > *(volatile uint32_t *)&scal[1]) atomicMax(&scal[1], n);
 }
 
 // ---- one tree over chunks [c0, c0 + D) of the distinct encodings -------------------------------------------------

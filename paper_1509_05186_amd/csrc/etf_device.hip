@@ -176,7 +176,7 @@ struct Plan {
     bool ctx_path = false;    // trees walked with the distance context in registers (no partial-sum tables)
     bool lds_path = false;    // search with every table slice in LDS: no result tables at all
     bool flat_lds = false;    // flat mode through the same kernels
-    int64_t o_counter = 0, o_lutT = 0, o_gmin = 0, o_tau = 0, o_boff = 0, o_cnt = 0, o_flag = 0, o_cand = 0;
+    int64_t o_counter = 0, o_lutT = 0, o_gmin = 0, o_tau = 0, o_boff = 0, o_bm = 0, o_cnt = 0, o_flag = 0, o_cand = 0;
     int64_t o_part[ETF_MAX_M][ETF_MAX_M];
     int64_t o_leafp[ETF_MAX_M];
     int64_t total = 0;
@@ -272,6 +272,7 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
         if (P.use_tau) P.o_gmin = take(P.NT * P.ngroups * QT * 4);
         P.o_tau = take(P.NT * QT * 4);
         P.o_boff = take(P.NT * QT * 4);
+        P.o_bm = take(P.NT * M * QT * 4);
         P.o_cnt = take(P.NT * QT * 4);
         P.o_flag = take(P.NT * QT * 4);
         P.o_cand = take(P.NT * QT * (int64_t)P.C * 8);
@@ -923,8 +924,11 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
         if (ctx->opt.metric == 1) {  // the selection orders non-negative values, smallest first
             boff = reinterpret_cast<float *>(w + P.o_boff);
             ProfScope prof(ctx, ETF_K_LUT);
-            hipLaunchKernelGGL(k_lut_shift, dim3((unsigned)tiles), dim3(256), 0, st, lutT, ix.M, ix.K, boff);
+            float *bm = reinterpret_cast<float *>(w + P.o_bm);
+            hipLaunchKernelGGL(k_lut_shift, dim3((unsigned)tiles, (unsigned)ix.M), dim3(256), 0, st, lutT, ix.M, ix.K, bm);
             LAUNCH_CHECK(ctx, "k_lut_shift");
+            hipLaunchKernelGGL(k_lut_shift_sum, dim3((unsigned)tiles), dim3(64), 0, st, bm, ix.M, boff);
+            LAUNCH_CHECK(ctx, "k_lut_shift_sum");
         }
         const unsigned fb = (unsigned)((nql + 255) / 256);
         hipLaunchKernelGGL(k_fill_u32, dim3(fb), dim3(256), 0, st, cnt, nql, 0u);

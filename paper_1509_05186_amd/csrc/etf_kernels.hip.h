@@ -136,25 +136,29 @@ __global__ __launch_bounds__(256) void k_lut_direct(const float *__restrict__ qu
 // the group's largest table entry.  This kernel rewrites a tile's tables of products p[m][k] as B_m - p[m][k]
 // (never negative: B_m is the maximum of the same rounded values) and stores B(q), the sum of the B_m in group
 // order, which the selection kernels subtract from again when they write the results.
-//     grid (tiles), block 256: wave w takes groups w, w + 4, ...; lane = query of the tile.
+//     k_lut_shift: grid (tiles, M), block 256: wave w takes codewords w, w + 4, ...; lane = query of the tile.
+//     k_lut_shift_sum: grid (tiles), block 64: B(q) from the M maxima.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_lut_shift(float *__restrict__ lutT, int M, int K, float *__restrict__ boff)
+__global__ __launch_bounds__(256) void k_lut_shift(float *__restrict__ lutT, int M, int K, float *__restrict__ bm)
 {
-    __shared__ float s_b[ETF_MAX_M][QT];
-    const int tile = blockIdx.x, lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6);
-    for (int m = w; m < M; m += 4) {
-        float *t = lutT + ((int64_t)tile * M + m) * K * QT + lane;
-        float b = t[0];
-        for (int k = 1; k < K; ++k) b = fmaxf(b, t[(int64_t)k * QT]);
-        for (int k = 0; k < K; ++k) t[(int64_t)k * QT] = b - t[(int64_t)k * QT];
-        s_b[m][lane] = b;
-    }
+    __shared__ float s_b[4][QT];
+    const int tile = blockIdx.x, m = blockIdx.y, lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6);
+    float *t = lutT + ((int64_t)tile * M + m) * K * QT + lane;
+    float b = -__uint_as_float(0x7F800000u);
+    for (int k = w; k < K; k += 4) b = fmaxf(b, t[(int64_t)k * QT]);
+    s_b[w][lane] = b;
     __syncthreads();
-    if (w == 0) {
-        float b = 0.f;
-        for (int m = 0; m < M; ++m) b += s_b[m][lane];
-        boff[(int64_t)tile * QT + lane] = b;
-    }
+    b = fmaxf(fmaxf(s_b[0][lane], s_b[1][lane]), fmaxf(s_b[2][lane], s_b[3][lane]));
+    for (int k = w; k < K; k += 4) t[(int64_t)k * QT] = b - t[(int64_t)k * QT];
+    if (w == 0) bm[((int64_t)tile * M + m) * QT + lane] = b;
+}
+
+__global__ __launch_bounds__(64) void k_lut_shift_sum(const float *__restrict__ bm, int M, float *__restrict__ boff)
+{
+    const int tile = blockIdx.x, lane = threadIdx.x;
+    float b = 0.f;
+    for (int m = 0; m < M; ++m) b += bm[((int64_t)tile * M + m) * QT + lane];
+    boff[(int64_t)tile * QT + lane] = b;
 }
 
 // ------------------------------------------------------------------------------------------------
