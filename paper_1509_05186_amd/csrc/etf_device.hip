@@ -660,8 +660,6 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
     } else {
         // item numbers inside a workgroup's share travel in 26 bits
         bx = lds_blocks_for(tiles * G, nitems, (nitems >> 25) + 1);
-        // the all-pairs output is bound by its stores, which like many workgroups taking turns along the rows
-        if (MODE == OUT_ALLPAIRS) bx = std::max(bx, blocks_for(nitems, 16384, tiles * G));
         if (ctx->opt.lds_blocks > 0) bx = std::max<int64_t>(ctx->opt.lds_blocks, (nitems >> 25) + 1);
         per_block = (int)((nitems + bx - 1) / bx);
     }

@@ -673,8 +673,9 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
 //     global reservation per query, then LDS atomics hand out the slots.
 //     OUT_SAMPLE: items map[i] (or i itself without a map: the sample's records stored side by side); a wave
 //     walks a stretch of the sample, every lane group's share of it is one sample group, whose minimum it keeps.
-//     OUT_ALLPAIRS: items are input positions (rec = the codes in input order, no context); dist[q][n] written
-//     as 64-byte pieces (16 consecutive n of one query per wave step).
+//     OUT_ALLPAIRS: items are input positions (rec = the codes in input order, no context); a lane group takes
+//     U consecutive positions, so dist[q][n] is written in pieces of U floats per lane, U * IPS adjacent floats
+//     of a row per store instruction.
 //     rec [n][M4] dwords: the codes of an item, chunk 0 in the lowest byte.
 //     grid (blocks, G, tiles), block 1024, dynamic LDS lds_table_bytes + lds_aux_bytes, no static LDS;
 //     per_block < 2^26.
@@ -778,7 +779,7 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
 {
     constexpr int Qs = WAVE / G, V = LDS_V, LPI = Qs / V, IPS = WAVE / LPI, M = 4 * M4;
     constexpr int S = CTX ? 2 : 0;  // chunks kept in the context: the first pair
-    constexpr int U = (M4 >= 4 || MODE == OUT_ALLPAIRS) ? 2 : 4;  // steps unrolled (all pairs: measured 1 / 2 / 4 / 8 -> 2.50 / 2.42 / 2.53 / 2.59 ms)
+    constexpr int U = M4 >= 4 ? 2 : 4;  // steps unrolled
     constexpr int RING = LDS_RING;
     constexpr bool FILTER = MODE == OUT_FILTER;
     // With rows of 64 bytes a line is 256 bytes, and with 256 lines per group the byte address of an entry is
@@ -890,29 +891,43 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     }
 
     if (MODE == OUT_ALLPAIRS) {
-        // items are the N input positions, U * IPS consecutive ones per wave and round: for one query the lane
-        // groups of a step write IPS consecutive floats of its row, the U steps adjacent pieces of it
-        // (the workgroups of a sub-tile take turns along the rows, so that what is written at any time is close)
+        // items are the N input positions, U * IPS consecutive ones per wave and round; lane group g takes the U
+        // consecutive items U g .. U g + U - 1, so that a lane ends up with U adjacent floats of each of its rows
+        // and writes them as one piece: a store instruction of the wave covers U * IPS adjacent floats (256
+        // bytes at U = 4) of four rows.  (The workgroups of a sub-tile take turns along the rows, so that what
+        // is written at any time is close.)  Rows that are not 16-byte aligned get single floats.
+        typedef float vecu __attribute__((ext_vector_type(U)));
         const int64_t bhi = nitems;
+        const bool wide = (o.N % U) == 0 && (reinterpret_cast<uintptr_t>(o.dist) % (U * 4)) == 0;
         for (int64_t j0 = ((int64_t)blockIdx.x * nw + w) * (IPS * U); j0 < bhi; j0 += (int64_t)gridDim.x * nw * (IPS * U)) {
             uint32_t dw[U][M4];
+            const int64_t jf = j0 + U * lg;  // this lane group's first item
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t j = min(j0 + u * IPS + lg, nitems - 1);
+                const int64_t j = min(jf + u, nitems - 1);
 #pragma unroll
                 for (int k2 = 0; k2 < M4; ++k2) dw[u][k2] = rec[j * M4 + k2];
             }
+            vecq d[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t j = j0 + u * IPS + lg;
                 vecq top = 0.f;
-                const vecq d = sum_of(dw[u], false, top);
-                if (j < bhi) {
+                d[u] = sum_of(dw[u], false, top);
+            }
 #pragma unroll
-                    for (int v = 0; v < V; ++v) {
-                        const int64_t ql = (int64_t)tile * QT + col + v;
-                        if (ql < o.nq) __builtin_nontemporal_store(d[v], &o.dist[ql * o.N + j]);  // written once, never read here
-                    }
+            for (int v = 0; v < V; ++v) {
+                const int64_t ql = (int64_t)tile * QT + col + v;
+                if (ql >= o.nq) continue;
+                float *row = o.dist + ql * o.N;
+                if (wide && jf + U <= bhi) {  // written once, never read here
+                    vecu x;
+#pragma unroll
+                    for (int u = 0; u < U; ++u) x[u] = d[u][v];
+                    __builtin_nontemporal_store(x, reinterpret_cast<vecu *>(row + jf));
+                } else {
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        if (jf + u < bhi) __builtin_nontemporal_store(d[u][v], row + jf + u);
                 }
             }
         }
