@@ -740,23 +740,25 @@ __device__ __forceinline__ void stage_lines(float *lds, const float *__restrict_
     constexpr int Qs = WAVE / G, CPL = lds_chunks_per_line(G), P4 = Qs / 4, UN = 8;
     const int total = M * K * P4;  // 16-byte pieces: row (m, k) has P4 of them
     const float *src = lutT + (int64_t)tile * M * K * QT + g * Qs;
-    for (int base = 0; base < total; base += (int)blockDim.x * UN) {
+    auto put = [&](int idx, const float4 &v) {
+        const int row = idx / P4, p = idx % P4;  // row = m * K + k
+        const int m = K == 256 ? row >> 8 : row / K, k = row - m * K;
+        *reinterpret_cast<float4 *>(lds + (((m / CPL) * KP + k) * CPL + (m % CPL)) * Qs + p * 4) = v;
+    };
+    const int trip = (int)blockDim.x * UN;
+    int base = 0;
+    for (; base + trip <= total; base += trip) {  // whole trips: no bounds checks between the loads
         float4 v[UN];
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             const int idx = base + u * (int)blockDim.x + (int)threadIdx.x;
-            if (idx < total) v[u] = *reinterpret_cast<const float4 *>(src + (int64_t)(idx / P4) * QT + (idx % P4) * 4);
+            v[u] = *reinterpret_cast<const float4 *>(src + (int64_t)(idx / P4) * QT + (idx % P4) * 4);
         }
 #pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int idx = base + u * (int)blockDim.x + (int)threadIdx.x;
-            if (idx < total) {
-                const int row = idx / P4, p = idx % P4;  // row = m * K + k
-                const int m = K == 256 ? row >> 8 : row / K, k = row - m * K;
-                *reinterpret_cast<float4 *>(lds + (((m / CPL) * KP + k) * CPL + (m % CPL)) * Qs + p * 4) = v[u];
-            }
-        }
+        for (int u = 0; u < UN; ++u) put(base + u * (int)blockDim.x + (int)threadIdx.x, v[u]);
     }
+    for (int idx = base + (int)threadIdx.x; idx < total; idx += (int)blockDim.x)
+        put(idx, *reinterpret_cast<const float4 *>(src + (int64_t)(idx / P4) * QT + (idx % P4) * 4));
     __syncthreads();
 }
 
