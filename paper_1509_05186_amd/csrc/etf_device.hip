@@ -292,12 +292,12 @@ int64_t blocks_for(int64_t n, int64_t min_items_per_block, int64_t other_dims)
 // Workgroups per sub-tile of queries for the LDS-resident kernels.  A CU holds one workgroup (its tables fill the
 // LDS), so a launch of W * bx workgroups runs in ceil(W * bx / 256) rounds, and each round has a fixed cost beside
 // its nitems / bx items: the workgroup's start, staging the tables, the first record loads, waves that finish at
-// different times while the LDS cannot be handed on (measured: 11 to 14 us, the time of about 8600 items at M = 8).
-// The cost of a choice is rounds * (8600 + nitems / bx), in items.  Few large workgroups win unless they leave
+// different times while the LDS cannot be handed on (measured: 6 us, the time of about 5000 items at M = 8).
+// The cost of a choice is rounds * (5000 + nitems / bx), in items.  Few large workgroups win unless they leave
 // CUs idle.
 int64_t lds_blocks_for(int64_t W, int64_t nitems, int64_t min_bx)
 {
-    const int64_t cus = 256, stage_items = 8600;
+    const int64_t cus = 256, stage_items = 5000;
     int64_t best = min_bx, best_cost = -1;
     for (int64_t bx = min_bx; bx < min_bx + 256; ++bx) {
         const int64_t rounds = (W * bx + cus - 1) / cus;
