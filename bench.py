@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised
 # under profiles/ (counters scaled by what a 1 GiB copy in the same run reads).  Keyed by (workload, kernel class,
 # traversal); reported only for the exact configuration that was profiled.
-MEASURED_TRAFFIC_BYTES = {("cfg2", "reduce", "register-context"): 9.361e9, ("cfg2", "lds", "lds-resident"): 0.875e9}
+MEASURED_TRAFFIC_BYTES = {("cfg2", "reduce", "register-context"): 9.362e9, ("cfg2", "lds", "lds-resident"): 0.545e9}
 # LDS read bandwidth of the chip: 256 compute units x 256 bytes per clock x 2.4 GHz (a conflict-free 16-byte-per-lane
 # wave read, 1 KiB, occupies the LDS pipe for 4 clocks: SQ_LDS_IDX_ACTIVE minus SQ_LDS_BANK_CONFLICT per read)
 LDS_PEAK_GBS = 256 * 256 * 2.4
@@ -161,8 +161,8 @@ def time_search(ctx, qd, k, mode, warmup, steps, torch, ws, out_ids, out_dist, b
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--scale-n", type=int, default=0, help="override N (debugging only; invalidates the metric)")
     ap.add_argument("--scale-q", type=int, default=0, help="override Q (debugging only; invalidates the metric)")
