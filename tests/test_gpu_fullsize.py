@@ -141,3 +141,37 @@ def test_device_built_index_full_size(name, N):
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
     assert dev.last_fallback_count() == 0
     check_sampled_queries(cb, codes, queries, a[0].cpu().numpy(), a[1].cpu().numpy(), cfg.topk, 4, name + " device-built")
+
+
+def test_cfg4_forest_search_full_size():
+    """cfg4 at full size (ten million 16-byte codes, four trees, ten thousand queries), in the launch configuration
+    the benchmark times; the database is encoded by the device encoder (bit-identical to the oracle's float32
+    assignment, see test_gpu_encode), sampled queries are checked completely against the oracle."""
+    cfg = get_config("cfg4")
+    gm = GaussianMixture.from_config(cfg)
+    host = etf.Context(device=None)
+    host.pq_train(gm.sample(cfg.n_train, SEED_TRAIN), cfg.M, cfg.K, cfg.kmeans_iters, seed=SEED_TRAIN)
+    cb = host.pq_get_codebooks()
+    c = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+    c.pq_set_codebooks(cb)
+    codes = np.empty((cfg.N, cfg.M), dtype=np.uint8)
+    done = 0
+    for chunk in gm.chunks(cfg.N, SEED_DATABASE):
+        codes[done:done + len(chunk)] = c.pq_encode_device(torch.from_numpy(chunk).cuda()).cpu().numpy()
+        done += len(chunk)
+        if (done >> 17) % 16 == 0:
+            say("  cfg4: generated + encoded", done, "of", cfg.N)
+    queries = gm.sample(cfg.Q, SEED_QUERIES)
+    qd = torch.from_numpy(queries).cuda()
+    say("cfg4 full size: device build, search")
+    c.index_build_device(torch.from_numpy(codes).cuda(), T=cfg.trees)
+    ids, dist = c.search(qd, cfg.topk, etf.ETF_MODE_FOREST)
+    torch.cuda.synchronize()
+    assert c.last_fallback_count() == 0
+    n = check_sampled_queries(cb, codes, queries, ids.cpu().numpy(), dist.cpu().numpy(), cfg.topk, 6, "cfg4")
+    say("  checked", n, "queries against the oracle")
+    say("cfg4 full size: host build, same lists")
+    h = make_ctx(cb, codes, cfg.trees)
+    hi, hd = h.search(qd, cfg.topk, etf.ETF_MODE_FOREST)
+    torch.cuda.synchronize()
+    assert torch.equal(ids, hi) and torch.equal(dist, hd)
