@@ -238,7 +238,11 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
     // queued, and recomputed below as plain sums of (q - c)^2 by all threads of the workgroup.
     __shared__ uint16_t fix[QT * 256];
     __shared__ int nfix;
+    // the codewords' norms from LDS: a global load per entry inside the loop below, each followed by a ballot and
+    // a branch, is a chain of 32 memory latencies per lane
+    __shared__ float s_cc[256];
     if (threadIdx.x == 0) nfix = 0;
+    if (!IP && (int)threadIdx.x < K) s_cc[threadIdx.x] = cbnorm[(int64_t)ms * K + threadIdx.x];
     __syncthreads();
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
@@ -246,7 +250,7 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
         for (int r = 0; r < 16; ++r) {
             const int k = kbase + rb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
             if (k < K) {
-                const float cc = IP ? 0.f : cbnorm[(int64_t)ms * K + k];
+                const float cc = IP ? 0.f : s_cc[k];
 #pragma unroll
                 for (int cb = 0; cb < 2; ++cb) {
                     const float nn = qq[cb] + cc;
