@@ -299,7 +299,8 @@ int64_t lds_blocks_for(int64_t W, int64_t nitems, int64_t min_bx)
 {
     const int64_t cus = 256, stage_items = 5000;
     int64_t best = min_bx, best_cost = -1;
-    for (int64_t bx = min_bx; bx < min_bx + 256; ++bx) {
+    const int64_t max_bx = std::max(min_bx, (nitems + 4095) / 4096);  // a workgroup of 16 waves wants a few thousand items
+    for (int64_t bx = min_bx; bx <= max_bx && bx < min_bx + 256; ++bx) {
         const int64_t rounds = (W * bx + cus - 1) / cus;
         const int64_t cost = rounds * (stage_items + (nitems + bx - 1) / bx);
         if (best_cost < 0 || cost < best_cost) {
