@@ -180,7 +180,7 @@ def main():
         args.traversal = 1
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus %d is not supported); "
-              "the path shards by query tile or by database range, see DESIGN.md" % args.gpus, file=sys.stderr)
+              "the path would shard by query tile (index replicated) or by ranges of the sorted encodings" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch
