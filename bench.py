@@ -29,6 +29,9 @@ MEASURED_TRAFFIC_BYTES = {("cfg2", "reduce", "register-context"): 9.362e9, ("cfg
 # LDS read bandwidth of the chip: 256 compute units x 256 bytes per clock x 2.4 GHz (a conflict-free 16-byte-per-lane
 # wave read, 1 KiB, occupies the LDS pipe for 4 clocks: SQ_LDS_IDX_ACTIVE minus SQ_LDS_BANK_CONFLICT per read)
 LDS_PEAK_GBS = 256 * 256 * 2.4
+# vector float32 operations that are neither packed nor fused: a quarter of the published 157.3 TFLOP/s (which counts
+# two-wide packed fused multiply-adds); a wave instruction takes 4 clocks on its 16-lane SIMD
+VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 TRAVERSAL_NAMES = {0: "register-context", 1: "level-synchronous", 2: "lds-resident"}
 PAPER_CONTEXT = {              # the paper's own numbers: one Core i7 at 3.6 GHz, one query at a time, SIFT1M, M=8, K=256
     "hardware": "Intel Core i7 3.6 GHz (paper, section Experiments)",
@@ -250,7 +253,11 @@ def main():
             if dom == "lds":
                 # bound by the LDS pipe: algorithmic bytes are the 4-byte table entries the method reads per query
                 roofline = {"bound": "alu", "resource": "LDS read bandwidth", "kernel": dom, "achieved": achieved,
-                            "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": achieved / LDS_PEAK_GBS, "traffic": traffic}
+                            "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": achieved / LDS_PEAK_GBS, "traffic": traffic,
+                            # the same figure on the vector unit: one float32 add per 4-byte entry, against
+                            # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz of unpacked, unfused float32 operations
+                            "alu": {"achieved": achieved / 4e3, "peak": VALU_PEAK_TOPS, "unit": "TFLOP/s",
+                                    "frac": achieved / 4e3 / VALU_PEAK_TOPS}}
             else:
                 roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": achieved / HBM_PEAK_GBS, "traffic": traffic}
