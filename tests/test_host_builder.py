@@ -65,6 +65,14 @@ def test_error_paths_without_gpu():
     # device entry points on a host-only context
     assert lib.etf_lut_build(c._h, 1, 1, 1) == -5
     assert lib.etf_search(c._h, 1, 1, 1, 0, 1, 1, 1, 1) == -5
+    a, b = ctypes.c_int64(0), ctypes.c_int64(0)
+    assert lib.etf_index_build_device_bytes(c._h, 10, 1, None, ctypes.byref(a), ctypes.byref(b)) == -5
+    assert lib.etf_index_build_device(c._h, 1, 10, None, 1, None, 256, 1 << 20, 256, 1 << 20) == -5
+    assert lib.etf_pq_encode_device(c._h, 1, 1, 1, 256, 1 << 20) == -5
+    for name, bad_value in ((b"metric", 2), (b"traversal", 3), (b"lut_kernel", 2), (b"lds_blocks", -1)):
+        assert lib.etf_set_option(c._h, name, bad_value) == -1
+    assert lib.etf_index_set_chunk_order(c._h, np.array([1, 1], dtype=np.int32).ctypes.data) == -1
+    assert lib.etf_suggest_chunk_order(c._h, codes.ctypes.data, 5, 1, None, None, None, None) == -1
     assert lib.etf_set_option(c._h, b"nonsense", 1) == -1
     assert lib.etf_set_option(c._h, b"force_fallback", 2) == -1
     assert lib.etf_strerror(-3) == b"out of memory or buffer too small"
