@@ -219,7 +219,9 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
             // the flat scan lists every copy of an encoding at or below the bound
             const int64_t copies = mode == ETF_MODE_FLAT ? 2 * ix.max_dup : 0;
             C = 4096;
-            while (C < 3 * expect + 2048 + copies && C < (1 << 17)) C <<= 1;
+            // (up to four million entries there: the batch of queries shrinks to keep the workspace under its cap)
+            const int64_t limit = mode == ETF_MODE_FLAT ? (1 << 22) : (1 << 17);
+            while (C < 3 * expect + 2048 + copies && C < limit) C <<= 1;
         }
         if (P.items <= C || P.ngroups < k) {  // few enough encodings: every one is a candidate, no bound needed
             P.use_tau = false;

@@ -307,3 +307,19 @@ def test_search_random_shapes_all_traversals_agree(seed):
     assert_lists_agree(lists[0], lists[2], "random seed %d: traversal 2 against 0" % seed)
     c = p.ctx(T=1, sample_min=256)
     check_search(p, c, FLAT, k, what="random seed %d flat" % seed)
+
+
+def test_search_with_a_huge_group_of_repeated_vectors():
+    """Two thirds of the database are copies of one vector.  The tree modes carry them as one encoding with an id
+    range; the flat scan lists every copy at or below the bound, so its candidate lists must hold them all."""
+    say("200000 copies of one vector among 300000")
+    p = Problem(d=32, M=8, K=256, N=100000, Q=70, ntrain=4000, seed=17)
+    rng = np.random.default_rng(17)
+    p.codes = np.concatenate([p.codes, np.repeat(p.codes[:1], 200000, axis=0)])[rng.permutation(300000)]
+    p.N = 300000
+    p._all = None
+    for mode, T in [(FLAT, 1), (TREE, 1), (FOREST, 2)]:
+        c = p.ctx(T=T)
+        assert c.index_stats()["max_dup"] >= 200000
+        check_search(p, c, mode, 100, what="huge group m%d" % mode)
+        assert c.last_fallback_count() == 0, mode
