@@ -305,10 +305,11 @@ def main():
     # ---- the same workload through the flat kernel and a single E-Tree, same run
     others = {}
     if not args.no_others:
-        osteps = max(2, min(args.steps, 3))
+        osteps = max(2, min(args.steps, 10))   # the other legs: up to ten steps after two warm-ups
+        owarm = 2
         if args.traversal == 2:
             # the same E-Forest search through the table-based traversal (per-tree result tables in HBM)
-            r0 = measure_forest(0, osteps, 1)
+            r0 = measure_forest(0, osteps, owarm)
             others["e_forest_register_context"] = {k2: r0[k2] for k2 in ("value", "ms_per_step", "kernels", "roofline")}
         tree = make_ctx(1)
         for name, ctx, m in (("flat_gpu", tree, etf.ETF_MODE_FLAT), ("e_tree_gpu", tree, etf.ETF_MODE_TREE)):
@@ -316,7 +317,7 @@ def main():
             # The flat scan lists every copy of an encoding; where one encoding has more copies than a candidate
             # list holds, every query ends in the whole-database selection kernel: one untimed-warm-up-free step
             heavy = m == etf.ETF_MODE_FLAT and ctx.index_stats()["max_dup"] > 32768
-            fw, fs = (0, 1) if heavy else (1, osteps)
+            fw, fs = (0, 1) if heavy else (owarm, osteps)
             d2, p2 = time_search(ctx, qd, k, m, fw, fs, torch, w2, out_ids, out_dist, cfg.query_batch)
             others[name] = {"value": N * Q * fs / d2, "ms_per_step": d2 / fs * 1e3, "steps": fs,
                             "fallback_queries": ctx.last_fallback_count(),
@@ -329,7 +330,7 @@ def main():
         ipc = make_ctx(T)
         ipc.set_option("metric", 1)
         w4 = ipc.alloc_workspace(Q, k, mode)
-        d4, p4 = time_search(ipc, qd, k, mode, 1, osteps, torch, w4, out_ids, out_dist, cfg.query_batch)
+        d4, p4 = time_search(ipc, qd, k, mode, owarm, osteps, torch, w4, out_ids, out_dist, cfg.query_batch)
         others["scalar_product_search"] = {"value": N * Q * osteps / d4, "ms_per_step": d4 / osteps * 1e3,
                                            "kernels_ms_per_step": {n: v[0] / osteps for n, v in p4.items() if v[1]},
                                            "fallback_queries": ipc.last_fallback_count()}
@@ -348,7 +349,7 @@ def main():
         oc.index_upload()
         oc.profile_enable(not args.no_profile)
         w5 = oc.alloc_workspace(Q, k, mode)
-        d5, p5 = time_search(oc, qd, k, mode, 1, osteps, torch, w5, out_ids, out_dist, cfg.query_batch)
+        d5, p5 = time_search(oc, qd, k, mode, owarm, osteps, torch, w5, out_ids, out_dist, cfg.query_batch)
         others["chunk_order"] = {"order": [int(v) for v in order], "lookups_given_order": lk_given, "lookups_suggested_order": lk_order,
                                  "lookups_on": "at most 2^18 evenly spaced vectors", "suggest_s": t_suggest,
                                  "ms_per_step": d5 / osteps * 1e3, "n_distinct": oc.index_stats()["n_distinct"],
@@ -371,7 +372,7 @@ def main():
                 times.append((time.perf_counter() - t0) * 1e3)
             del wsb
             w3 = db.alloc_workspace(Q, k, mode)
-            d3, _ = time_search(db, qd, k, mode, 1, osteps, torch, w3, out_ids, out_dist, cfg.query_batch)
+            d3, _ = time_search(db, qd, k, mode, owarm, osteps, torch, w3, out_ids, out_dist, cfg.query_batch)
             others["index_build_device"] = {"ms": min(times[1:]), "vectors_per_s": N / (min(times[1:]) / 1e3),
                                             "image_bytes": db.index_device_bytes(), "image_bytes_bound": nimg, "workspace_bytes": nws,
                                             "search_ms_per_step": d3 / osteps * 1e3,
