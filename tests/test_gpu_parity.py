@@ -323,3 +323,21 @@ def test_search_with_a_huge_group_of_repeated_vectors():
         assert c.index_stats()["max_dup"] >= 200000
         check_search(p, c, mode, 100, what="huge group m%d" % mode)
         assert c.last_fallback_count() == 0, mode
+
+
+@pytest.mark.parametrize("mode,T", [(FLAT, 1), (FOREST, 2)])
+def test_workgroup_count_does_not_change_results(small, mode, T):
+    say("search and all pairs with 1, 3, 7 and the library's choice of workgroups per sub-tile, mode", mode)
+    p = small
+    ref = None
+    for blocks in (0, 1, 3, 7):
+        c = p.ctx(T=T, sample_min=2048, lds_blocks=blocks)
+        oi, od = c.search(qdev(p), 50, mode)
+        dist = c.adc(qdev(p), mode)
+        torch.cuda.synchronize()
+        got = (oi.clone(), od.clone(), dist.clone())
+        if ref is None:
+            ref = got
+            check_search(p, c, mode, 50, what="lds_blocks")
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(ref, got)), blocks
