@@ -141,3 +141,17 @@ def test_scalar_product_search_tiny_databases(N, Q, k):
     for mode, T in [(FLAT, 1), (TREE, 1), (FOREST, 2)]:
         c = p.ctx(T=T, metric=1)
         check_ip_search(p, c, mode, k, what="ip tiny m%d" % mode)
+
+
+def test_scalar_product_search_several_batches_and_device_built_index(small):
+    say("largest scalar products: a workspace cap that forces several query batches; a device-built index")
+    p = small
+    c = p.ctx(T=2, metric=1, sample_min=2048, ws_cap_bytes=8 << 20)
+    a = check_ip_search(p, c, FOREST, 10, what="ip batched")
+    d = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+    d.set_option("metric", 1)
+    d.set_option("sample_min", 2048)
+    d.pq_set_codebooks(p.cb)
+    d.index_build_device(torch.from_numpy(p.codes).cuda(), T=2)
+    b = check_ip_search(p, d, FOREST, 10, what="ip device-built")
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
