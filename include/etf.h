@@ -122,7 +122,8 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     2 (default): every table slice of a group of queries is kept in LDS; searches
  *                     walk the sorted encodings with a short distance context per lane group,
  *                     etf_adc evaluates the input positions in order; no result tables at all (built
- *                     for M in {4, 8, 16} and 1, 2 or 4 equal trees); every other shape runs as 0.
+ *                     for M in {4, 8, 16} and equal trees of 1, 2 or a multiple of 4 chunks); every other
+ *                     shape runs as 0.
  *                     0 and 1 add the chunks left to right and return identical bits; 2 adds the
  *                     chunks of every group of four in pairs and agrees with them to rounding.
  * Returns ETF_EINVAL for an unknown name or a value out of range. */

@@ -636,8 +636,9 @@ int launch_reduce(etf_ctx *ctx, const ReduceArgs &r, int64_t nitems, const uint3
 bool lds_eligible(int M, int K, int T, const int32_t *chunk_begin)
 {
     if (M != 4 && M != 8 && M != 16) return false;
-    if (T != 1 && T != 2 && T != 4) return false;
-    if (M % T != 0) return false;
+    if (T < 1 || T > M || M % T != 0) return false;
+    const int D = M / T;  // trees of whole groups of four chunks, or of one or two chunks inside a pair
+    if (D >= 4 ? D % 4 != 0 : (D != 1 && D != 2)) return false;
     if (chunk_begin)
         for (int t = 0; t <= T; ++t)
             if (chunk_begin[t] != t * (M / T)) return false;
@@ -655,6 +656,9 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
     const int G = std::max(2, pick_G(M, K));
     const size_t lds = lds_table_bytes(G, M, K) + lds_aux_bytes(MODE == OUT_FILTER);
     const int IPS = LDS_V * G;  // items per wave step
+    // The kernels are built for trees of at least four chunks (1, 2 or 4 trees); shorter trees lie inside the
+    // pairs of a group of four, whose sum is formed the same way whatever the trees: they run as trees of four.
+    if (M / T < 4) T = M / 4;
     int64_t bx;
     int per_block = 0;
     if (MODE == OUT_SAMPLE) {
@@ -681,8 +685,8 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
             done = true;                                                                                       \
         }                                                                                                      \
     }
-#define LDS_CASES(GG) LDS_CASE(GG, 1, 1) LDS_CASE(GG, 1, 2) LDS_CASE(GG, 1, 4) LDS_CASE(GG, 2, 1) LDS_CASE(GG, 2, 2) \
-    LDS_CASE(GG, 2, 4) LDS_CASE(GG, 4, 1) LDS_CASE(GG, 4, 2) LDS_CASE(GG, 4, 4)
+#define LDS_CASES(GG) LDS_CASE(GG, 1, 1) LDS_CASE(GG, 2, 1) LDS_CASE(GG, 2, 2) LDS_CASE(GG, 4, 1) LDS_CASE(GG, 4, 2) \
+    LDS_CASE(GG, 4, 4)
     LDS_CASES(2) LDS_CASES(4) LDS_CASES(8)
 #undef LDS_CASES
 #undef LDS_CASE

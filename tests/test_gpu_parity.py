@@ -218,7 +218,7 @@ def wide():
 
 @pytest.mark.parametrize("trav", TRAVERSALS)
 @pytest.mark.parametrize("mode,T,cbeg", [(TREE, 1, None), (FOREST, 2, None), (FOREST, 4, None), (FOREST, 3, [0, 5, 10, 16]),
-                                        (FOREST, 2, [0, 3, 16]), (FLAT, 1, None)])
+                                        (FOREST, 2, [0, 3, 16]), (FLAT, 1, None), (FOREST, 8, None), (FOREST, 16, None)])
 def test_sixteen_chunks(wide, mode, T, cbeg, trav):
     if mode == FLAT and trav == 1:
         pytest.skip("flat mode has no tree traversal")
@@ -341,3 +341,17 @@ def test_workgroup_count_does_not_change_results(small, mode, T):
             check_search(p, c, mode, 50, what="lds_blocks")
         else:
             assert all(torch.equal(a, b) for a, b in zip(ref, got)), blocks
+
+
+@pytest.mark.parametrize("trav", TRAVERSALS)
+def test_forest_of_single_chunk_trees(small, trav):
+    say("eight trees of one chunk each (M = 8), traversal", trav)
+    c = small.ctx(T=8, sample_min=2048, traversal=trav)
+    d = c.adc(qdev(small), FOREST)
+    torch.cuda.synchronize()
+    assert_distances_close(d.cpu().numpy(), small.ref_all, "T=8 adc")
+    check_search(small, c, FOREST, 100, what="T=8 search")
+    assert c.last_fallback_count() == 0
+    if trav == 2:   # one- and two-chunk trees are summed like trees of four chunks: the same bits as T = 2
+        c2 = small.ctx(T=2, sample_min=2048, traversal=2)
+        assert torch.equal(d, c2.adc(qdev(small), FOREST))
