@@ -326,6 +326,18 @@ def main():
             del w2
         others["e_tree_stats"] = tree.index_stats()["trees"]
         del tree
+        # the paper's study of the number of trees: forests of 4 and of M trees beside the tree and the forest above
+        by_trees = {"1": others["e_tree_gpu"]["ms_per_step"], str(T): ms_step}
+        for tt in (4, cfg.M):
+            if str(tt) in by_trees or cfg.M % tt:
+                continue
+            fc = make_ctx(tt)
+            wf = fc.alloc_workspace(Q, k, mode)
+            df, _ = time_search(fc, qd, k, mode, owarm, osteps, torch, wf, out_ids, out_dist, cfg.query_batch)
+            by_trees[str(tt)] = df / osteps * 1e3
+            del fc, wf
+        others["forest_ms_per_step_by_trees"] = by_trees
+        log("E-Forest by number of trees (ms/step): %s" % ", ".join("T=%s %.2f" % kv for kv in sorted(by_trees.items(), key=lambda kv: int(kv[0]))))
         # the other payload on the same forest: the k largest scalar products (option metric = 1)
         ipc = make_ctx(T)
         ipc.set_option("metric", 1)
