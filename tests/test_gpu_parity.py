@@ -355,3 +355,22 @@ def test_forest_of_single_chunk_trees(small, trav):
     if trav == 2:   # one- and two-chunk trees are summed like trees of four chunks: the same bits as T = 2
         c2 = small.ctx(T=2, sample_min=2048, traversal=2)
         assert torch.equal(d, c2.adc(qdev(small), FOREST))
+
+
+@pytest.mark.parametrize("N", [63, 64, 65, 127, 129, 1001, 1002, 1003, 1004, 4099])
+def test_all_pairs_ragged_database_sizes(N):
+    """All-pairs output where the database size is, or is not, a multiple of the 4 positions a lane writes at once and of
+    the 64 a wave takes per round (rows of the output 16-byte aligned or not)."""
+    say("all pairs, N =", N)
+    p = Problem(d=16, M=8, K=32, N=N, Q=70, ntrain=400, seed=40 + N % 7, iters=2)
+    for mode, T in [(FLAT, 1), (TREE, 1), (FOREST, 2)]:
+        c = p.ctx(T=T)
+        d = c.adc(qdev(p), mode)
+        torch.cuda.synchronize()
+        assert_distances_close(d.cpu().numpy(), p.ref_all, "ragged N=%d mode %d" % (N, mode))
+    # an output buffer that is not 16-byte aligned
+    raw = torch.empty(p.Q * N + 1, dtype=torch.float32, device="cuda")
+    out = raw[1:].view(p.Q, N)
+    c.adc(qdev(p), FOREST, dist=out)
+    torch.cuda.synchronize()
+    assert_distances_close(out.cpu().numpy(), p.ref_all, "unaligned output")
