@@ -338,6 +338,23 @@ def main():
             del fc, wf
         others["forest_ms_per_step_by_trees"] = by_trees
         log("E-Forest by number of trees (ms/step): %s" % ", ".join("T=%s %.2f" % kv for kv in sorted(by_trees.items(), key=lambda kv: int(kv[0]))))
+        # control without structure: independent uniform codes (every encoding distinct, prefixes shared at the first
+        # two levels only by chance): the worst case for the tree, on the same queries and codebooks
+        rc = np.random.default_rng(1509).integers(0, cfg.K, size=(N, cfg.M), dtype=np.uint8)
+        uc = etf.Context(device=0, stream=stream)
+        uc.set_option("traversal", args.traversal)
+        uc.pq_set_codebooks(cb)
+        uc.index_build(rc, T=T)
+        uc.index_upload()
+        ust = uc.index_stats()
+        wu = uc.alloc_workspace(Q, k, mode)
+        du, _ = time_search(uc, qd, k, mode, owarm, osteps, torch, wu, out_ids, out_dist, cfg.query_batch)
+        others["unstructured_control"] = {"ms_per_step": du / osteps * 1e3, "value": N * Q * osteps / du, "n_distinct": ust["n_distinct"],
+                                          "lookups_per_encoding": sum(t["lookups"] for t in ust["trees"]) / N,
+                                          "fallback_queries": uc.last_fallback_count()}
+        log("control, uniform random codes: %.2f ms/step, %.3e distances/s (%d distinct, %.2f tree lookups per encoding)"
+            % (du / osteps * 1e3, N * Q * osteps / du, ust["n_distinct"], others["unstructured_control"]["lookups_per_encoding"]))
+        del uc, wu, rc
         # the other payload on the same forest: the k largest scalar products (option metric = 1)
         ipc = make_ctx(T)
         ipc.set_option("metric", 1)
