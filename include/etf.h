@@ -298,7 +298,11 @@ int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, int mode, i
 
 /* Number of queries of the most recent etf_search on this context that were
  * answered by the exact whole-database selection kernel instead of the
- * threshold-filtered path (diagnostic).  Synchronises the stream. */
+ * threshold-filtered path (diagnostic).  Synchronises the stream.  The count
+ * lives in the first word of that search's workspace: the workspace must still
+ * be allocated and unchanged when this is called (the one other place where
+ * the library refers to a caller's buffer after a call).  ETF_ESTATE if no
+ * search has run since the index was built or uploaded. */
 int etf_last_fallback_count(etf_ctx *ctx, int64_t *out);
 
 /* ---- per-kernel timing (for benchmarks) ---------------------------------- */
@@ -325,6 +329,19 @@ int etf_profile_enable(etf_ctx *ctx, int on);
  * milliseconds (ms[ETF_K_COUNT]) and the number of launches
  * (launches[ETF_K_COUNT]) since the last read, and resets both. */
 int etf_profile_read(etf_ctx *ctx, double *ms, int64_t *launches);
+
+/* ---- memory bandwidth probes (for benchmarks) ---------------------------- */
+
+/* Plain streaming kernels over caller-owned device buffers, enqueued on the context's stream: the rates this
+ * card's memory delivers, which a benchmark quotes as ceilings beside the traversal kernels (not part of the
+ * paper's method).  a, b: device, 256-byte aligned; bytes: a multiple of 256, at least 64 KiB; b must hold at
+ * least 16 KiB in every kind.
+ *   ETF_PROBE_READ   reads `bytes` of a front to back (b receives one word per workgroup)
+ *   ETF_PROBE_WRITE  writes `bytes` of a
+ *   ETF_PROBE_COPY   copies `bytes` from a to b
+ *   ETF_PROBE_ROWS   reads a as rows of 256 bytes, one wave per row, every row once, in a scattered order */
+enum { ETF_PROBE_READ = 0, ETF_PROBE_WRITE = 1, ETF_PROBE_COPY = 2, ETF_PROBE_ROWS = 3 };
+int etf_probe_bandwidth(etf_ctx *ctx, int kind, void *a, void *b, int64_t bytes);
 
 #ifdef __cplusplus
 }

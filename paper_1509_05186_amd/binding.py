@@ -23,8 +23,9 @@ EXPORTS = [
     "etf_encode_workspace_bytes", "etf_pq_encode_device",
     "etf_index_build_device_bytes", "etf_index_build_device",
     "etf_workspace_bytes", "etf_lut_build", "etf_adc", "etf_search", "etf_last_fallback_count",
-    "etf_profile_enable", "etf_profile_read",
+    "etf_profile_enable", "etf_profile_read", "etf_probe_bandwidth",
 ]
+ETF_PROBE_READ, ETF_PROBE_WRITE, ETF_PROBE_COPY, ETF_PROBE_ROWS = 0, 1, 2, 3
 KERNEL_CLASSES = ["lut", "level", "leaf", "flat", "reduce", "tau", "select", "exact", "sample", "lds", "encode"]
 
 
@@ -136,6 +137,7 @@ def load_library():
         "etf_last_fallback_count": (I, [P, ctypes.POINTER(L)]),
         "etf_profile_enable": (I, [P, I]),
         "etf_profile_read": (I, [P, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(L)]),
+        "etf_probe_bandwidth": (I, [P, I, P, P, L]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -387,6 +389,10 @@ class Context:
         v = ctypes.c_int64(0)
         self._ck(self._lib.etf_last_fallback_count(self._h, ctypes.byref(v)))
         return int(v.value)
+
+    def probe_bandwidth(self, kind: int, a, b, nbytes: int):
+        """One launch of a streaming probe kernel over the uint8 device tensors a and b (256-byte aligned)."""
+        self._ck(self._lib.etf_probe_bandwidth(self._h, kind, _dev(a), _dev(b), nbytes))
 
     def profile_enable(self, on: bool):
         self._ck(self._lib.etf_profile_enable(self._h, 1 if on else 0))

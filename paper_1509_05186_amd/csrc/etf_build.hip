@@ -429,7 +429,10 @@ int build_impl(etf_ctx *ctx, const uint8_t *codes, int64_t N, const int32_t *ids
         size_t tb = (size_t)W.temp_bytes;
         HIP_TRY(ctx, rocprim::inclusive_scan(ws + W.temp, tb, head, rank, (size_t)N, rocprim::plus<uint32_t>(), st));
     }
-    uint32_t h_scal[4] = {0, 0, 0, 0};
+    // the counts read back from the device land in the context, not in this frame: a copy that is still pending when
+    // an error path returns completes (at the caller's synchronisation) into memory that is still alive
+    uint32_t *h_scal = ctx->build_scal;
+    h_scal[0] = h_scal[1] = h_scal[2] = h_scal[3] = 0;
     HIP_TRY(ctx, hipMemcpyAsync(&h_scal[0], rank + (N - 1), 4, hipMemcpyDeviceToHost, st));
     HIP_TRY(ctx, hipMemcpyAsync(&h_scal[2], scal + 2, 4, hipMemcpyDeviceToHost, st));
     HIP_TRY(ctx, hipStreamSynchronize(st));

@@ -116,6 +116,35 @@ extern "C" int etf_profile_read(etf_ctx *ctx, double *ms, int64_t *launches)
     return ETF_OK;
 }
 
+// plain streaming kernels over the caller's buffers: the memory ceilings a benchmark quotes beside the traversal
+extern "C" int etf_probe_bandwidth(etf_ctx *ctx, int kind, void *a, void *b, int64_t bytes)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (ctx->device < 0) return fail(ctx, ETF_ENOGPU, "host-only context");
+    if (!a || !b || bytes < 65536 || (bytes & 255) != 0 || (((uintptr_t)a | (uintptr_t)b) & 255) != 0)
+        return fail(ctx, ETF_EINVAL, "probe buffers must be 256-byte aligned and a multiple of 256 bytes, at least 64 KiB");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    hipStream_t st = (hipStream_t)ctx->stream;
+    const unsigned grid = 256 * 16;  // sixteen workgroups of 256 threads per compute unit; b must hold 4 bytes per workgroup
+    const int64_t n16 = bytes / 16, nrows = bytes / 256;
+    switch (kind) {
+        case ETF_PROBE_READ: hipLaunchKernelGGL(k_probe_read, dim3(grid), dim3(256), 0, st, (const u32x4 *)a, n16, (uint32_t *)b); break;
+        case ETF_PROBE_WRITE: hipLaunchKernelGGL(k_probe_write, dim3(grid), dim3(256), 0, st, (u32x4 *)a, n16); break;
+        case ETF_PROBE_COPY: hipLaunchKernelGGL(k_probe_copy, dim3(grid), dim3(256), 0, st, (const u32x4 *)a, (u32x4 *)b, n16); break;
+        case ETF_PROBE_ROWS: {
+            // a multiplier near 0.618 nrows that shares no factor with nrows: consecutive rows land far apart
+            uint64_t mult = (uint64_t)((double)nrows * 0.6180339887) | 1u;
+            auto gcd = [](uint64_t x, uint64_t y) { while (y) { const uint64_t t = x % y; x = y; y = t; } return x; };
+            while (gcd(mult, (uint64_t)nrows) != 1) mult += 2;
+            hipLaunchKernelGGL(k_probe_rows, dim3(grid), dim3(256), 0, st, (const float *)a, nrows, mult, (uint32_t *)b);
+            break;
+        }
+        default: return fail(ctx, ETF_EINVAL, "unknown probe kind %d", kind);
+    }
+    LAUNCH_CHECK(ctx, "k_probe");
+    return ETF_OK;
+}
+
 extern "C" int etf_set_stream(etf_ctx *ctx, void *hip_stream)
 {
     if (!ctx) return ETF_EINVAL;
@@ -153,6 +182,7 @@ extern "C" int etf_index_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes)
     HIP_TRY(ctx, first);
     HIP_TRY(ctx, hipStreamSynchronize(st));
     ctx->dev_base = base;
+    ctx->last_flag_count = nullptr;
     return ETF_OK;
 }
 
@@ -186,8 +216,9 @@ int64_t al256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 int tmax_class(int T);
 bool lds_eligible(int M, int K, int T, const int32_t *chunk_begin);
 
-int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan &P)
+int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan &P, int64_t ws_cap = 0)
 {
+    if (ws_cap <= 0) ws_cap = ctx->opt.ws_cap_bytes;
     const HostIndex &ix = ctx->idx;
     if (!ix.built) return fail(ctx, ETF_ESTATE, "no index: call etf_index_build first");
     if (Q <= 0) return fail(ctx, ETF_EINVAL, "Q must be positive");
@@ -252,7 +283,7 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
         if (P.use_tau) per_tile += al256(P.ngroups * QT * 4);
         per_tile += (int64_t)QT * (12 + (int64_t)P.C * 8);
     }
-    int64_t nt = ctx->opt.ws_cap_bytes / std::max<int64_t>(per_tile, 1);
+    int64_t nt = ws_cap / std::max<int64_t>(per_tile + 4096, 1);
     P.NT = std::max<int64_t>(1, std::min<int64_t>(nt, P.tiles_total));
     // offsets
     int64_t off = 0;
@@ -893,14 +924,15 @@ extern "C" int etf_pq_encode_device(etf_ctx *ctx, const float *x, int64_t n, uin
 // =============================================================================================
 // top-k search
 // =============================================================================================
-extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, int mode, int32_t *out_ids,
-                          float *out_dist, void *ws, int64_t ws_bytes)
+// ws_cap > 0: an upper bound of the workspace other than the context's option
+static int search_impl(etf_ctx *ctx, const float *queries, int64_t Q, int k, int mode, int32_t *out_ids, float *out_dist,
+                       void *ws, int64_t ws_bytes, int64_t ws_cap)
 {
     int rc = check_ready(ctx, queries, ws);
     if (rc) return rc;
     if (!out_ids || !out_dist) return fail(ctx, ETF_EINVAL, "output pointer is null");
     Plan P;
-    rc = make_plan(ctx, Q, k, mode, true, P);
+    rc = make_plan(ctx, Q, k, mode, true, P, ws_cap);
     if (rc) return rc;
     if (ws_bytes < P.total) return fail(ctx, ETF_ENOMEM, "workspace too small: %lld < %lld", (long long)ws_bytes, (long long)P.total);
     HIP_TRY(ctx, hipSetDevice(ctx->device));
@@ -1036,6 +1068,12 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
         LAUNCH_CHECK(ctx, "k_exact");
     }
     return ETF_OK;
+}
+
+extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, int mode, int32_t *out_ids,
+                          float *out_dist, void *ws, int64_t ws_bytes)
+{
+    return search_impl(ctx, queries, Q, k, mode, out_ids, out_dist, ws, ws_bytes, 0);
 }
 
 extern "C" int etf_last_fallback_count(etf_ctx *ctx, int64_t *out)

@@ -413,6 +413,7 @@ void drop_index(etf_ctx *ctx)
     ctx->idx = HostIndex();
     ctx->lay = DevLayout();
     ctx->dev_base = nullptr;
+    ctx->last_flag_count = nullptr;  // the diagnostics of a search on the previous index
 }
 }  // namespace etf
 

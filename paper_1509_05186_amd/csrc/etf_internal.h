@@ -129,6 +129,8 @@ struct etf_ctx {
     std::vector<int32_t> next_order;        // chunk order of the next index build (empty: as given)
     // diagnostics of the most recent search (device address inside the caller's workspace)
     void *last_flag_count = nullptr;
+    // landing place of the small device-to-host copies of the device index build
+    uint32_t build_scal[4] = {0, 0, 0, 0};
     // per-kernel timing: pairs of hipEvent_t (stored untyped so that host-only code need not see HIP)
     bool profile_on = false;
     struct Stamp { void *start, *stop; int cls; };

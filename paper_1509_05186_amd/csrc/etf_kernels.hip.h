@@ -1639,4 +1639,70 @@ __global__ __launch_bounds__(256) void k_exact(ExactArgs a)
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Bandwidth probes (benchmark only): what this card's memory delivers to plain streaming kernels, the
+// ceilings the traversal kernels are compared with.  16 bytes per lane and access, grid-stride.
+//     k_probe_read:  sum of `n16` 16-byte pieces of a; one word per workgroup is written to out
+//     k_probe_write: n16 pieces of a constant to a
+//     k_probe_copy:  a -> b
+//     k_probe_rows:  a read as rows of 256 bytes (a wave per row, the unit of every table in this library) in a
+//                    scattered order: row (i * mult) mod nrows for i = 0 .. nrows-1, mult coprime to nrows
+// ------------------------------------------------------------------------------------------------
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void k_probe_read(const u32x4 *__restrict__ a, int64_t n16, uint32_t *__restrict__ out)
+{
+    u32x4 acc = 0u;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {  // four loads in flight per lane
+        const u32x4 v0 = __builtin_nontemporal_load(a + i), v1 = __builtin_nontemporal_load(a + i + stride),
+                    v2 = __builtin_nontemporal_load(a + i + 2 * stride), v3 = __builtin_nontemporal_load(a + i + 3 * stride);
+        acc ^= (v0 ^ v1) ^ (v2 ^ v3);
+    }
+    for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(a + i);
+    const uint32_t x = (acc.x ^ acc.y) ^ (acc.z ^ acc.w);
+    if (x == 0x9E3779B9u || threadIdx.x == 0) out[blockIdx.x] = x;
+}
+
+__global__ __launch_bounds__(256) void k_probe_write(u32x4 *__restrict__ a, int64_t n16)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const u32x4 v = {1u, 2u, 3u, 4u};
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) __builtin_nontemporal_store(v, a + i);
+}
+
+__global__ __launch_bounds__(256) void k_probe_copy(const u32x4 *__restrict__ a, u32x4 *__restrict__ b, int64_t n16)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4 v0 = __builtin_nontemporal_load(a + i), v1 = __builtin_nontemporal_load(a + i + stride),
+                    v2 = __builtin_nontemporal_load(a + i + 2 * stride), v3 = __builtin_nontemporal_load(a + i + 3 * stride);
+        __builtin_nontemporal_store(v0, b + i);
+        __builtin_nontemporal_store(v1, b + i + stride);
+        __builtin_nontemporal_store(v2, b + i + 2 * stride);
+        __builtin_nontemporal_store(v3, b + i + 3 * stride);
+    }
+    for (; i < n16; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(a + i), b + i);
+}
+
+__global__ __launch_bounds__(256) void k_probe_rows(const float *__restrict__ a, int64_t nrows, uint64_t mult, uint32_t *__restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wv = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), nwv = (int64_t)gridDim.x * 4;
+    float acc = 0.f;
+    for (int64_t i0 = wv * 8; i0 < nrows; i0 += nwv * 8) {  // eight rows in flight per wave
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint64_t r = ((uint64_t)min(i0 + u, nrows - 1) * mult) % (uint64_t)nrows;
+            v[u] = a[r * 64 + lane];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    if (acc == 1.2345e-30f || threadIdx.x == 0) out[blockIdx.x] = __float_as_uint(acc);
+}
+
 }  // namespace etf

@@ -64,6 +64,38 @@ def assert_topk_matches(gpu_ids, gpu_dist, ref_all, ids, k, what=""):
             assert gpu_ids[a] == ids[order[a]], what + ": id at rank %d" % a
 
 
+def assert_topk_matches_identity(gpu_ids, gpu_dist, ref_all, k, what=""):
+    """The same requirements as assert_topk_matches for ids = input positions (id n is position n), written
+    without per-id dictionaries or a sort of the whole array, for databases of 10^7..10^8 vectors: everything
+    that can matter lies at or below the k-th oracle distance plus the tolerance band, a set found with one
+    partition."""
+    gpu_ids = np.asarray(gpu_ids).astype(np.int64)
+    gpu_dist = np.asarray(gpu_dist, dtype=np.float64)
+    ref_all = np.asarray(ref_all, dtype=np.float64)
+    n = ref_all.shape[0]
+    assert gpu_ids.shape == (k,) and gpu_dist.shape == (k,), what
+    assert len(np.unique(gpu_ids)) == k, what + ": duplicate ids"
+    assert gpu_ids.min() >= 0 and gpu_ids.max() < n, what + ": unknown id"
+    for a in range(k - 1):
+        assert (gpu_dist[a], gpu_ids[a]) < (gpu_dist[a + 1], gpu_ids[a + 1]), what + ": order at %d" % a
+    floor = 1e-8 * float(np.median(np.abs(ref_all)))
+    tol = lambda v: REL_TOL * np.abs(v) + floor
+    assert np.all(np.abs(gpu_dist - ref_all[gpu_ids]) <= tol(ref_all[gpu_ids])), what + ": returned distance vs oracle"
+    kth = float(np.partition(ref_all, k - 1)[k - 1])
+    band = REL_TOL * abs(kth) * 2 + floor
+    near = np.flatnonzero(ref_all <= kth + 2 * band)          # every position that can appear or clash
+    order = near[np.lexsort((near, ref_all[near]))]
+    ref_top = ref_all[order[:k]]
+    assert np.all(np.abs(gpu_dist - ref_top) <= tol(ref_top) + 1e-300), what + ": sorted distances"
+    closer = near[ref_all[near] < kth - band]
+    assert np.all(np.isin(closer, gpu_ids)), what + ": a closer vector was left out"
+    near_ref = np.sort(ref_all[near])
+    for a in np.flatnonzero(np.abs(ref_top - kth) > band):
+        lo, hi = ref_top[a] - band, ref_top[a] + band
+        if np.searchsorted(near_ref, hi, "right") - np.searchsorted(near_ref, lo, "left") == 1:
+            assert gpu_ids[a] == order[a], what + ": id at rank %d" % a
+
+
 def ip_scale(lut_ip):
     """Magnitude of a query's table of scalar products: the sum over groups of the largest |entry|.  Scalar
     products cancel, so float32 results are held to 1e-5 of this scale rather than of the result itself."""

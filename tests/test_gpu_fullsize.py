@@ -8,7 +8,7 @@ import pytest
 
 import oracle
 from workload import GaussianMixture, get_config, SEED_TRAIN, SEED_DATABASE, SEED_QUERIES
-from parity import assert_distances_close, assert_topk_matches
+from parity import assert_distances_close, assert_topk_matches, assert_topk_matches_identity
 
 pytestmark = pytest.mark.gpu
 
@@ -175,3 +175,79 @@ def test_cfg4_forest_search_full_size():
     hi, hd = h.search(qd, cfg.topk, etf.ETF_MODE_FOREST)
     torch.cuda.synchronize()
     assert torch.equal(ids, hi) and torch.equal(dist, hd)
+
+
+def device_encoded_database(cfg, workers=12):
+    """Codebooks trained by the library, the database encoded chunk by chunk by the device encoder (the way
+    bench.py prepares every configuration): (codebooks, codes [N][M] on the host, queries)."""
+    gm = GaussianMixture.from_config(cfg)
+    host = etf.Context(device=None)
+    host.pq_train(gm.sample(cfg.n_train, SEED_TRAIN), cfg.M, cfg.K, cfg.kmeans_iters, seed=SEED_TRAIN)
+    cb = host.pq_get_codebooks()
+    enc = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+    enc.pq_set_codebooks(cb)
+    codes = np.empty((cfg.N, cfg.M), dtype=np.uint8)
+    done, step = 0, max(1, (cfg.N >> 17) // 8)
+    for i, chunk in enumerate(gm.chunks_threaded(cfg.N, SEED_DATABASE, workers)):
+        codes[done:done + len(chunk)] = enc.pq_encode_device(torch.from_numpy(chunk).cuda()).cpu().numpy()
+        done += len(chunk)
+        if i % step == 0:
+            say("  %s: generated + encoded %d of %d" % (cfg.name, done, cfg.N))
+    return cb, codes, gm.sample(cfg.Q, SEED_QUERIES)
+
+
+def check_spread_queries(cb, codes, queries, ids, dist, k, picks, what):
+    """Complete check of a few queries: the oracle's distances to every encoding, one query at a time."""
+    for j in picks:
+        ref = oracle.adc_all(queries[j:j + 1], cb, codes)[0]
+        assert_topk_matches_identity(ids[j], dist[j], ref, k, "%s q%d" % (what, j))
+        say("  %s: query %d matches the oracle" % (what, j))
+
+
+def test_cfg3_tree_and_forest_full_size():
+    """cfg3 at full size (d = 960, one million vectors, one thousand queries): the single E-Tree and the E-Forest of
+    two trees, both of which this configuration times."""
+    cfg = get_config("cfg3")
+    say("cfg3 full size: inputs")
+    cb, codes, queries = device_encoded_database(cfg)
+    # the device encoder's decisions at 120 dimensions per group, on a spread of the database
+    gm = GaussianMixture.from_config(cfg)
+    first = next(gm.chunks(cfg.N, SEED_DATABASE))
+    assert np.array_equal(codes[:4096], oracle.encode_f32(first[:4096], cb))
+    qd = torch.from_numpy(queries).cuda()
+    picks = [0, 63, 64, 500, 959, 960, cfg.Q - 1]          # first tile, a tile boundary, the ragged last tile
+    for T, mode, what in ((1, etf.ETF_MODE_TREE, "cfg3 E-Tree"), (cfg.trees, etf.ETF_MODE_FOREST, "cfg3 E-Forest")):
+        say(what)
+        c = make_ctx(cb, codes, T)
+        ids, dist = c.search(qd, cfg.topk, mode)
+        torch.cuda.synchronize()
+        assert c.last_fallback_count() == 0
+        check_spread_queries(cb, codes, queries, ids.cpu().numpy(), dist.cpu().numpy(), cfg.topk, picks, what)
+
+
+def test_cfg5_forest_search_full_size():
+    """cfg5 at full size: 10^8 vectors of 96 dimensions (800 MB of codes; 16.8 million distinct encodings, one of
+    them with more than a million copies), E-Forest of two trees, the thousand queries sent in calls of 256 as the
+    workload defines and bench.py times; index built on the device from the device encoder's codes."""
+    cfg = get_config("cfg5")
+    say("cfg5 full size: inputs")
+    cb, codes, queries = device_encoded_database(cfg)
+    c = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+    c.pq_set_codebooks(cb)
+    say("cfg5: index build on the device")
+    c.index_build_device(torch.from_numpy(codes).cuda(), T=cfg.trees)
+    st = c.index_stats()
+    say("  distinct encodings %d, largest group of equal encodings %d" % (st["n_distinct"], st["max_dup"]))
+    qd = torch.from_numpy(queries).cuda()
+    ids = torch.empty((cfg.Q, cfg.topk), dtype=torch.int32, device="cuda")
+    dist = torch.empty((cfg.Q, cfg.topk), dtype=torch.float32, device="cuda")
+    ws = c.alloc_workspace(cfg.query_batch, cfg.topk, etf.ETF_MODE_FOREST)
+    fallbacks = 0
+    for a in range(0, cfg.Q, cfg.query_batch):
+        b = min(cfg.Q, a + cfg.query_batch)
+        c.search(qd[a:b], cfg.topk, etf.ETF_MODE_FOREST, ids[a:b], dist[a:b], ws)
+        fallbacks += c.last_fallback_count()
+    torch.cuda.synchronize()
+    assert fallbacks == 0
+    picks = [0, 255, 256, 640, cfg.Q - 1]                   # both sides of a call boundary, the ragged last call
+    check_spread_queries(cb, codes, queries, ids.cpu().numpy(), dist.cpu().numpy(), cfg.topk, picks, "cfg5")
