@@ -296,6 +296,21 @@ int etf_adc(etf_ctx *ctx, const float *queries, int64_t Q, int mode, float *dist
 int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, int mode, int32_t *out_ids,
                float *out_dist, void *ws, int64_t ws_bytes);
 
+/* etf_search for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results (bit for
+ * bit) and same kernels as etf_search, but the workspace is a fixed array of ETF_STATIC_SCRATCH_BYTES in the
+ * library's device image, one per GPU, held until the process ends; the call allocates nothing (no
+ * hipMalloc / hipFree, no event creation: etf_profile_enable has no effect on it).  Queries go through in
+ * batches of tiles of 64 that fit the array; a search whose single tile does not fit (very large candidate
+ * capacity: flat mode over heavily repeated encodings, a large "cand_cap") returns ETF_ENOMEM and launches
+ * nothing.  Every call on a GPU uses that GPU's one array (the counters in it are cleared by the call
+ * itself): calls that overlap on one GPU, from any context or stream, race; so does etf_last_fallback_count
+ * against a later call.  etf_static_scratch_bytes() returns the array's size. */
+#define ETF_STATIC_SCRATCH_BYTES (64 << 20)
+int64_t etf_static_scratch_bytes(void);
+int etf_search_static(etf_ctx *ctx, const float *queries, int64_t Q, int k, int mode, int32_t *out_ids,
+                      float *out_dist);
+
 /* Number of queries of the most recent etf_search on this context that were
  * answered by the exact whole-database selection kernel instead of the
  * threshold-filtered path (diagnostic).  Synchronises the stream.  The count

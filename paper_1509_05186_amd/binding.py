@@ -23,6 +23,7 @@ EXPORTS = [
     "etf_encode_workspace_bytes", "etf_pq_encode_device",
     "etf_index_build_device_bytes", "etf_index_build_device",
     "etf_workspace_bytes", "etf_lut_build", "etf_adc", "etf_search", "etf_last_fallback_count",
+    "etf_static_scratch_bytes", "etf_search_static",
     "etf_profile_enable", "etf_profile_read", "etf_probe_bandwidth",
 ]
 ETF_PROBE_READ, ETF_PROBE_WRITE, ETF_PROBE_COPY, ETF_PROBE_ROWS = 0, 1, 2, 3
@@ -135,6 +136,8 @@ def load_library():
         "etf_adc": (I, [P, P, L, I, P, P, L]),
         "etf_search": (I, [P, P, L, I, I, P, P, P, L]),
         "etf_last_fallback_count": (I, [P, ctypes.POINTER(L)]),
+        "etf_static_scratch_bytes": (L, []),
+        "etf_search_static": (I, [P, P, L, I, I, P, P]),
         "etf_profile_enable": (I, [P, I]),
         "etf_profile_read": (I, [P, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(L)]),
         "etf_probe_bandwidth": (I, [P, I, P, P, L]),
@@ -383,6 +386,11 @@ class Context:
             ws = self.alloc_workspace(Q, k, mode)
         p, n = self._ws(ws)
         self._ck(self._lib.etf_search(self._h, _dev(queries), Q, k, mode, _dev(out_ids), _dev(out_dist), p, n))
+        return out_ids, out_dist
+
+    def search_static(self, queries, k: int, mode: int, out_ids, out_dist):
+        """etf_search_static: the caller passes inputs and outputs only; nothing is allocated by the call."""
+        self._ck(self._lib.etf_search_static(self._h, _dev(queries), queries.shape[0], k, mode, _dev(out_ids), _dev(out_dist)))
         return out_ids, out_dist
 
     def last_fallback_count(self) -> int:

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cstring>
 #include <functional>
+#include <mutex>
 
 #include "etf_internal.h"
 #include "etf_kernels.hip.h"
@@ -30,7 +31,7 @@ struct ProfScope {
     bool live = false;
     ProfScope(etf_ctx *c, int cls) : ctx(c)
     {
-        if (!c->profile_on) return;
+        if (!c->profile_on || c->no_alloc_call) return;
         if (!c->stamp_pool.empty()) {
             st = c->stamp_pool.back();
             c->stamp_pool.pop_back();
@@ -53,6 +54,8 @@ struct ProfScope {
     }
 };
 
+static void lookup_scratch(int device);
+
 static constexpr int64_t LDS_BUDGET = 128 * 1024;  // bytes of table slices a workgroup may stage
 static constexpr int CUB = 4;                       // items per batch of the register-context kernels (measured best)
 
@@ -71,6 +74,7 @@ extern "C" int etf_create(etf_ctx **out, int device, void *hip_stream)
     if (!c) return ETF_ENOMEM;
     c->device = device;
     c->stream = hip_stream;
+    if (device >= 0) lookup_scratch(device);  // once per device: where the scratch of etf_search_static lives there
     *out = c;
     return ETF_OK;
 }
@@ -924,7 +928,7 @@ extern "C" int etf_pq_encode_device(etf_ctx *ctx, const float *x, int64_t n, uin
 // =============================================================================================
 // top-k search
 // =============================================================================================
-// ws_cap > 0: an upper bound of the workspace other than the context's option
+// ws_cap > 0: the workspace is the fixed scratch array of the allocation-free entry point
 static int search_impl(etf_ctx *ctx, const float *queries, int64_t Q, int k, int mode, int32_t *out_ids, float *out_dist,
                        void *ws, int64_t ws_bytes, int64_t ws_cap)
 {
@@ -934,7 +938,12 @@ static int search_impl(etf_ctx *ctx, const float *queries, int64_t Q, int k, int
     Plan P;
     rc = make_plan(ctx, Q, k, mode, true, P, ws_cap);
     if (rc) return rc;
-    if (ws_bytes < P.total) return fail(ctx, ETF_ENOMEM, "workspace too small: %lld < %lld", (long long)ws_bytes, (long long)P.total);
+    if (ws_bytes < P.total) {
+        if (ws_cap > 0)
+            return fail(ctx, ETF_ENOMEM, "this search needs %lld bytes of scratch for one tile of 64 queries; the allocation-free entry point has %lld",
+                        (long long)P.total, (long long)ws_bytes);
+        return fail(ctx, ETF_ENOMEM, "workspace too small: %lld < %lld", (long long)ws_bytes, (long long)P.total);
+    }
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     hipStream_t st = (hipStream_t)ctx->stream;
     const HostIndex &ix = ctx->idx;
@@ -1074,6 +1083,58 @@ extern "C" int etf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, 
                           float *out_dist, void *ws, int64_t ws_bytes)
 {
     return search_impl(ctx, queries, Q, k, mode, out_ids, out_dist, ws, ws_bytes, 0);
+}
+
+// =============================================================================================
+// the search without any allocation
+// =============================================================================================
+// Scratch of etf_search_static: one array per GPU the library runs on, held until the process ends and shared by
+// every call on that GPU.  In host code the array's name is only a handle for hipGetSymbolAddress; the address
+// kernels and copies use is looked up once per device (etf_create) and kept in g_scratch.
+static __device__ __align__(256) unsigned char scratch[ETF_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void *g_scratch[MAX_DEVICES];          // device address of `scratch` on every device seen so far
+hipError_t g_scratch_err[MAX_DEVICES];
+bool g_scratch_tried[MAX_DEVICES];
+std::mutex g_scratch_mu;
+}  // namespace
+
+// called by etf_create with a device context; the device is made current here
+static void lookup_scratch(int device)
+{
+    if (device < 0 || device >= MAX_DEVICES) return;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (g_scratch_tried[device]) return;
+    g_scratch_tried[device] = true;
+    hipError_t e = hipSetDevice(device);
+    void *p = nullptr;
+    if (e == hipSuccess) e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    g_scratch_err[device] = e;
+    g_scratch[device] = e == hipSuccess ? p : nullptr;
+}
+
+extern "C" int64_t etf_static_scratch_bytes(void) { return (int64_t)ETF_STATIC_SCRATCH_BYTES; }
+
+extern "C" int etf_search_static(etf_ctx *ctx, const float *queries, int64_t Q, int k, int mode, int32_t *out_ids,
+                                 float *out_dist)
+{
+    int rc = need_device(ctx);
+    if (rc) return rc;
+    if (ctx->device >= MAX_DEVICES) return fail(ctx, ETF_EINVAL, "device %d: the scratch table holds %d devices", ctx->device, MAX_DEVICES);
+    void *ws;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mu);
+        ws = g_scratch[ctx->device];
+        if (!ws)
+            return fail(ctx, ETF_EHIP, "the scratch array has no address on device %d: %s", ctx->device,
+                        g_scratch_tried[ctx->device] ? hipGetErrorString(g_scratch_err[ctx->device]) : "etf_create did not look it up");
+    }
+    ctx->no_alloc_call = true;  // no event pairs around the launches: creating an event allocates
+    rc = search_impl(ctx, queries, Q, k, mode, out_ids, out_dist, ws, ETF_STATIC_SCRATCH_BYTES, ETF_STATIC_SCRATCH_BYTES);
+    ctx->no_alloc_call = false;
+    return rc;
 }
 
 extern "C" int etf_last_fallback_count(etf_ctx *ctx, int64_t *out)

@@ -133,6 +133,7 @@ struct etf_ctx {
     uint32_t build_scal[4] = {0, 0, 0, 0};
     // per-kernel timing: pairs of hipEvent_t (stored untyped so that host-only code need not see HIP)
     bool profile_on = false;
+    bool no_alloc_call = false;     // inside etf_search_static: nothing that allocates (no new event pairs)
     struct Stamp { void *start, *stop; int cls; };
     std::vector<Stamp> stamps;      // recorded since the last read
     std::vector<Stamp> stamp_pool;  // events ready for reuse
