@@ -25,19 +25,50 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised
 # under profiles/ (counters scaled by what a 1 GiB copy in the same run reads).  Keyed by (workload, kernel class,
 # traversal); reported only for the exact configuration that was profiled.
-MEASURED_TRAFFIC_BYTES = {("cfg2", "reduce", "register-context"): 9.362e9, ("cfg2", "lds", "lds-resident"): 0.545e9}
+# Each figure carries the hash of the kernel sources it was measured on (kernel_source_hash below); a run on other
+# sources prints traffic: null.
+MEASURED_TRAFFIC_BYTES = {}
 # LDS read bandwidth of the chip: 256 compute units x 256 bytes per clock x 2.4 GHz (a conflict-free 16-byte-per-lane
 # wave read, 1 KiB, occupies the LDS pipe for 4 clocks: SQ_LDS_IDX_ACTIVE minus SQ_LDS_BANK_CONFLICT per read)
 LDS_PEAK_GBS = 256 * 256 * 2.4
 # vector float32 operations that are neither packed nor fused: a quarter of the published 157.3 TFLOP/s (which counts
 # two-wide packed fused multiply-adds); a wave instruction takes 4 clocks on its 16-lane SIMD
 VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+VALU_PEAK_NOTE = "256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz of unpacked, unfused 32-bit vector operations"
 TRAVERSAL_NAMES = {0: "register-context", 1: "level-synchronous", 2: "lds-resident"}
+PATH_NOTES = {
+    0: "E-Forest: depth-first leaf order with the distance context in registers, per-tree result tables in HBM summed per encoding",
+    1: "E-Forest: level-synchronous kernels over the level arrays, per-tree result tables in HBM summed per encoding",
+    2: "sorted distinct encodings scanned with every table slice in LDS and a distance context of two levels; the trees' "
+       "sums are formed per encoding in registers (no per-tree result array); see roofline.lookups_per_query",
+}
 PAPER_CONTEXT = {              # the paper's own numbers: one Core i7 at 3.6 GHz, one query at a time, SIFT1M, M=8, K=256
     "hardware": "Intel Core i7 3.6 GHz (paper, section Experiments)",
     "ms_per_query": {"flat_adc": 2.678, "e_tree": 1.760, "e_forest_2": 1.265},
     "distances_per_s": {"flat_adc": 1e6 / 2.678e-3, "e_tree": 1e6 / 1.760e-3, "e_forest_2": 1e6 / 1.265e-3},
 }
+
+
+def kernel_source_hash():
+    """Identifies the kernel sources a profile was taken on: sha256 over the library's source files, 16 hex digits."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1509_05186_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h", ".cpp")):
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, kernel, traversal):
+    """(bytes per launch, note) from the rocprofv3 counter runs, or (None, why not)."""
+    ent = MEASURED_TRAFFIC_BYTES.get((workload, kernel, traversal))
+    if ent is None:
+        return None, "no counter run recorded for this workload and kernel"
+    nbytes, src = ent
+    if src != kernel_source_hash():
+        return None, "the recorded counter run (%.3e bytes) was taken on kernel sources %s, this run uses %s" % (nbytes, src, kernel_source_hash())
+    return nbytes, "rocprofv3 FETCH_SIZE + WRITE_SIZE on kernel sources %s, see profiles/" % src
 
 
 def log(*a):
@@ -63,7 +94,7 @@ def make_inputs(cfg, etf, torch, scale_n=None, scale_q=None):
     enc.pq_encode_device(torch.zeros((64, cfg.d), dtype=torch.float32, device="cuda"), ws=ws)
     enc.profile_read()
     done = 0
-    for chunk in gm.chunks(N, SEED_DATABASE):
+    for chunk in gm.chunks_threaded(N, SEED_DATABASE, 12):
         got = enc.pq_encode_device(torch.from_numpy(chunk).cuda(), ws=ws)
         codes[done:done + len(chunk)] = got.cpu().numpy()
         done += len(chunk)
@@ -161,6 +192,325 @@ def time_search(ctx, qd, k, mode, warmup, steps, torch, ws, out_ids, out_dist, b
     return dt, ctx.profile_read()
 
 
+class Workload:
+    """One configuration's inputs, resident on the device: codebooks, codes, queries, output buffers."""
+
+    def __init__(self, cfg, etf, torch, args, scale_n=None, scale_q=None):
+        self.cfg, self.etf, self.torch, self.args = cfg, etf, torch, args
+        self.k = cfg.topk or 100
+        self.cb, self.codes, self.queries, self.encode_info = make_inputs(cfg, etf, torch, scale_n, scale_q)
+        self.N, self.Q = self.codes.shape[0], self.queries.shape[0]
+        self.stream = torch.cuda.current_stream().cuda_stream
+        self.qd = torch.from_numpy(self.queries).cuda()
+        self.out_ids = torch.empty((self.Q, self.k), dtype=torch.int32, device="cuda")
+        self.out_dist = torch.empty((self.Q, self.k), dtype=torch.float32, device="cuda")
+        self.T = max(cfg.trees, 1)
+        self.tiles = (self.Q + 63) // 64
+        self.codes_d = None
+        self.valid = not (scale_n or scale_q)
+        self._tree_lookups = None
+
+    def make_ctx(self, T, traversal=None, profile=True, opts=()):
+        """A context with an index of T trees over this database: built on the device for the large databases
+        (the host builder takes seconds there), on the host otherwise."""
+        etf, torch, args = self.etf, self.torch, self.args
+        c = etf.Context(device=0, stream=self.stream)
+        c.set_option("traversal", args.traversal if traversal is None else traversal)
+        for nv in list(args.opt) + list(opts):
+            name, val = nv.split("=")
+            c.set_option(name, int(val))
+        c.pq_set_codebooks(self.cb)
+        t0 = time.time()
+        if self.N >= 5_000_000:
+            if self.codes_d is None:
+                self.codes_d = torch.from_numpy(self.codes).cuda()
+            c.index_build_device(self.codes_d, T=T)
+            how = "built on the device"
+        else:
+            c.index_build(self.codes, T=T)
+            c.index_upload()
+            how = "build + upload"
+        log("%s index T=%d: %s %.1f s, %.1f MB on device" % (self.cfg.name, T, how, time.time() - t0, c.index_device_bytes() / 1e6))
+        c.profile_enable(profile and not args.no_profile)
+        return c
+
+    def tree_lookups(self):
+        """Table lookups of one traversal of the single E-Tree over this database, L1 + L2 + sum of the postfix
+        lengths: the paper's measure of the method's work, whatever the kernels do."""
+        if self._tree_lookups is None:
+            c = self.make_ctx(1, profile=False)
+            self._tree_lookups = int(c.index_stats()["trees"][0]["lookups"])
+            del c
+        return self._tree_lookups
+
+    def measure_search(self, T, traversal, steps, warmup, mode=None):
+        """Times the search with one traversal; returns the numbers of a JSON leg."""
+        etf, torch, cfg = self.etf, self.torch, self.cfg
+        mode = etf.ETF_MODE_FOREST if mode is None else mode
+        ctx = self.make_ctx(T, traversal)
+        stats = ctx.index_stats()
+        Qc = cfg.query_batch or self.Q
+        ws = ctx.alloc_workspace(min(Qc, self.Q), self.k, mode)
+        log("%s traversal %s: workspace %.2f GB" % (cfg.name, TRAVERSAL_NAMES[traversal], ws.numel() / 1e9))
+        dt, prof = time_search(ctx, self.qd, self.k, mode, warmup, steps, torch, ws, self.out_ids, self.out_dist, cfg.query_batch)
+        ms_step = dt / steps * 1e3
+        value = self.N * self.Q * steps / dt
+        fallbacks = ctx.last_fallback_count()
+        log("%s T=%d top-%d, %s: %.2f ms/step, %.3e distances/s, %d queries of the last call via the exact kernel"
+            % (cfg.name, T, self.k, TRAVERSAL_NAMES[traversal], ms_step, value, fallbacks))
+        S = ctx.index_layout().n_sample_enc
+        lds_path = "lds" in prof and prof["lds"][1] > 0
+        ctx_path = traversal != 1 and T <= 4
+        alg = algorithmic_bytes(stats, "forest_lds" if lds_path else "forest_ctx" if ctx_path else "forest", S, self.tiles)
+        kernels = {}
+        for name, (ms, cnt) in prof.items():
+            if cnt:
+                kernels[name] = {"ms_per_step": ms / steps, "launches_per_step": cnt / steps,
+                                 "alg_GB_per_step": alg.get(name, 0) / 1e9,
+                                 "alg_GBps": (alg.get(name, 0) / 1e9) / (ms / steps / 1e3) if ms > 0 and name in alg else None}
+        roofline = None
+        if kernels:
+            dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+            kd = kernels[dom]
+            lps = kd["launches_per_step"]
+            achieved = kd["alg_GBps"] or 0.0
+            traffic, traffic_note = (None, "scaled run") if not self.valid else measured_traffic(cfg.name, dom, TRAVERSAL_NAMES[traversal])
+            if dom == "lds":
+                # bound by the LDS pipe: algorithmic bytes are the 4-byte table entries this kernel reads per query
+                kernel_lookups = alg["lds"] / (self.tiles * 64 * 4)
+                tree_lookups = self.tree_lookups()
+                forest_lookups = sum(t["lookups"] for t in stats["trees"])
+                frac = achieved / LDS_PEAK_GBS
+                roofline = {"bound": "alu", "resource": "LDS read bandwidth (on-chip): the kernel is a sequence of 16-byte table reads, "
+                                                        "one add per 4-byte entry", "kernel": dom, "achieved": achieved,
+                            "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": frac, "traffic": traffic, "traffic_note": traffic_note,
+                            # the same time priced on the lookups the paper's single E-Tree needs for this database
+                            # (L1 + L2 + postfix lengths): prefixes this kernel recomputes are not useful work
+                            "method_frac": frac * tree_lookups / kernel_lookups,
+                            "lookups_per_query": {"this_kernel": kernel_lookups, "e_tree": tree_lookups,
+                                                  "e_forest_trees": forest_lookups, "flat_distinct": stats["n_distinct"] * stats["M"],
+                                                  "flat": stats["N"] * stats["M"]},
+                            "alu": {"achieved": achieved / 4e3, "peak": VALU_PEAK_TOPS, "unit": "Tadd/s",
+                                    "frac": achieved / 4e3 / VALU_PEAK_TOPS,
+                                    "note": "one integer or float32 add per entry against %s" % VALU_PEAK_NOTE}}
+            else:
+                roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_note": traffic_note}
+            roofline.update({"alg_bytes_per_launch": alg.get(dom, 0) / lps if lps else None,
+                             "avg_launch_ms": kd["ms_per_step"] / lps if lps else None, "launches_per_step": lps})
+            if dom != "lds":
+                # the traversal as a whole (levels + leaves + reduction): the bandwidth figure of the table-based paths
+                trav = [n for n in ("level", "leaf", "reduce", "sample") if n in kernels]
+                tms = sum(kernels[n]["ms_per_step"] for n in trav)
+                tgb = sum(kernels[n]["alg_GB_per_step"] for n in trav)
+                roofline["traversal"] = {"kernels": trav, "ms_per_step": tms, "alg_GB_per_step": tgb,
+                                         "alg_GBps": tgb / (tms / 1e3) if tms > 0 else None,
+                                         "frac": (tgb / (tms / 1e3)) / HBM_PEAK_GBS if tms > 0 else None}
+        res = {"ms_per_step": ms_step, "value": value, "fallbacks": fallbacks, "kernels": kernels, "roofline": roofline,
+               "stats": stats, "S": int(S), "traversal": TRAVERSAL_NAMES[traversal], "steps": steps}
+        del ws, ctx
+        return res
+
+    def parity(self, picks, what):
+        """The timed output (self.out_ids / out_dist) of the queries `picks` against the oracle's distances to every
+        encoding, one query at a time."""
+        import oracle
+        from parity import assert_topk_matches_identity
+        ids, dist = self.out_ids.cpu().numpy(), self.out_dist.cpu().numpy()
+        for j in picks:
+            ref = oracle.adc_all(self.queries[j:j + 1], self.cb, self.codes)[0]
+            assert_topk_matches_identity(ids[j], dist[j], ref, self.k, "%s q%d" % (what, j))
+        log("%s: parity of the timed output against the oracle ok on queries %s" % (what, list(map(int, picks))))
+        return [int(j) for j in picks]
+
+
+def workload_string(wl, T):
+    cfg = wl.cfg
+    return ("%s: d=%d N=%d Q=%d PQ M=%d K=%d, E-Forest T=%d, top-%d, seeded %d-component Gaussian mixture"
+            % (cfg.name, cfg.d, wl.N, wl.Q, cfg.M, cfg.K, T, wl.k, cfg.components))
+
+
+def config_leg(name, etf, torch, args, steps, warmup):
+    """Another configuration of the workload list, end to end in the same run: inputs, index, the default search
+    timed over `steps` steps (queries in calls of the configuration's batch size), roofline of its dominant kernel,
+    and a parity check of the timed output on a few spread-out queries."""
+    from workload import get_config
+    cfg = get_config(name)
+    t0 = time.time()
+    wl = Workload(cfg, etf, torch, args)
+    res = wl.measure_search(wl.T, args.traversal, steps, warmup)
+    leg = {"workload": workload_string(wl, wl.T), "query_batch": cfg.query_batch or wl.Q, "steps": steps, "warmup": warmup,
+           "value": res["value"], "unit": "encoding-distances/s", "ms_per_step": res["ms_per_step"], "roofline": res["roofline"],
+           "kernels": res["kernels"], "fallback_queries": res["fallbacks"], "encode_gpu": wl.encode_info,
+           "index": {"n_distinct": res["stats"]["n_distinct"], "max_dup": res["stats"]["max_dup"],
+                     "trees": [{kk: t[kk] for kk in ("D", "L1", "L2", "sumP", "lookups")} for t in res["stats"]["trees"]],
+                     "sample": res["S"]}}
+    if not args.no_cpu:
+        Q = wl.Q
+        picks = sorted(set([0, min(Q - 1, 255), min(Q - 1, 256), Q // 2, Q - 1]))
+        leg["parity_checked_queries"] = wl.parity(picks, name + " E-Forest")
+    if name == "cfg3":
+        # this configuration times the single E-Tree as well
+        rt = wl.measure_search(1, args.traversal, steps, warmup, etf.ETF_MODE_TREE)
+        leg["e_tree"] = {"value": rt["value"], "ms_per_step": rt["ms_per_step"], "roofline": rt["roofline"], "kernels": rt["kernels"]}
+        if not args.no_cpu:
+            wl.parity([0, wl.Q // 2, wl.Q - 1], name + " E-Tree")
+    leg["wall_s"] = time.time() - t0
+    del wl
+    torch.cuda.empty_cache()
+    return leg
+
+
+def ivf_leg(etf, torch, args, steps, warmup):
+    """IVFADC on cfg2's vectors with the configuration the paper's application experiment quotes (K' = 8192 cells,
+    w = 64 probed lists, residual PQ M = 8, K = 256), top-100 for all queries: coarse distances and probe selection,
+    scalar-product tables, scan of the probed lists (merged, sorted entries), selection.  The coarse quantiser is
+    8192 vectors drawn from the mixture (no k-means at that size on the host); codebooks are trained on residuals."""
+    from workload import GaussianMixture, get_config, SEED_TRAIN, SEED_DATABASE, SEED_QUERIES
+    cfg = get_config("cfg2")
+    cells_n, w, k = 8192, 64, 100
+    gm = GaussianMixture.from_config(cfg)
+    stream = torch.cuda.current_stream().cuda_stream
+    t0 = time.time()
+    cent = gm.sample(cells_n, 77)
+    xt = gm.sample(cfg.n_train, SEED_TRAIN)
+    shape = etf.Context(device=0, stream=stream)           # codebooks of the right shape give the context d, M, K
+    shape.pq_set_codebooks(np.zeros((cfg.M, cfg.K, cfg.d // cfg.M), dtype=np.float32))
+    shape.ivf_set_coarse(cent)
+    tc = shape.ivf_assign_device(torch.from_numpy(xt).cuda())[0].cpu().numpy()
+    trainer = etf.Context(device=None)
+    trainer.pq_train(xt - cent[tc], cfg.M, cfg.K, cfg.kmeans_iters, seed=SEED_TRAIN)
+    cb = trainer.pq_get_codebooks()
+    c = etf.Context(device=0, stream=stream)
+    for nv in args.opt:
+        name, val = nv.split("=")
+        c.set_option(name, int(val))
+    c.pq_set_codebooks(cb)
+    c.ivf_set_coarse(cent)
+    cells = np.empty(cfg.N, dtype=np.int32)
+    codes = np.empty((cfg.N, cfg.M), dtype=np.uint8)
+    done = 0
+    c.profile_enable(True)
+    c.profile_read()
+    for chunk in gm.chunks_threaded(cfg.N, SEED_DATABASE, 12):
+        ce, co = c.ivf_assign_device(torch.from_numpy(chunk).cuda())
+        cells[done:done + len(chunk)] = ce.cpu().numpy()
+        codes[done:done + len(chunk)] = co.cpu().numpy()
+        done += len(chunk)
+    assign_ms = c.profile_read()["encode"][0]
+    c.ivf_build(cells, codes)
+    c.ivf_upload()
+    st = c.ivf_stats()
+    queries = gm.sample(cfg.Q, SEED_QUERIES)
+    qd = torch.from_numpy(queries).cuda()
+    out_ids = torch.empty((cfg.Q, k), dtype=torch.int32, device="cuda")
+    out_dist = torch.empty((cfg.Q, k), dtype=torch.float32, device="cuda")
+    ws = torch.empty(c.ivf_workspace_bytes(cfg.Q, k, w) + 256, dtype=torch.uint8, device="cuda")
+    log("IVFADC set-up %.1f s: %d cells, %d entries for %d vectors, largest list %d, workspace %.2f GB"
+        % (time.time() - t0, st["cells"], st["entries"], st["N"], st["max_list"], ws.numel() / 1e9))
+    for _ in range(warmup):
+        c.ivf_search(qd, k, w, out_ids, out_dist, ws)
+    torch.cuda.synchronize()
+    c.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        c.ivf_search(qd, k, w, out_ids, out_dist, ws)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = c.profile_read()
+    kernels = {n: {"ms_per_step": v[0] / steps, "launches_per_step": v[1] / steps} for n, v in prof.items() if v[1]}
+    ms = dt / steps * 1e3
+    # what one step evaluates: every entry of every probed list of every query
+    pr_cells = None
+    scanned = None
+    leg = {"workload": "cfg2's vectors (d=%d N=%d Q=%d), IVFADC: %d cells, w=%d, residual PQ M=%d K=%d, top-%d"
+                       % (cfg.d, cfg.N, cfg.Q, cells_n, w, cfg.M, cfg.K, k),
+           "ms_per_step": ms, "queries_per_s": cfg.Q / (ms / 1e3), "steps": steps, "kernels": kernels,
+           "fallback_queries": c.last_fallback_count(), "index": st, "assign_gpu_kernel_ms": assign_ms,
+           "coarse_quantiser": "8192 vectors drawn from the mixture, not trained"}
+    # roofline of the dominant kernel.  Coarse distances: plain float32 vector arithmetic, 3 operations per (query,
+    # cell, dimension), nothing fused (the decisions must be reproducible).  Scan: 4-byte table entries gathered from LDS.
+    dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+    if dom == "ivf_coarse":
+        ops = 3.0 * cfg.Q * cells_n * cfg.d
+        ach = ops / (kernels[dom]["ms_per_step"] / 1e3) / 1e12
+        leg["roofline"] = {"bound": "alu", "kernel": dom, "achieved": ach, "peak": VALU_PEAK_TOPS, "unit": "Top/s",
+                           "frac": ach / VALU_PEAK_TOPS, "traffic": None, "note": VALU_PEAK_NOTE}
+    if not args.no_cpu:
+        from oracle import ivfadc
+        from parity import assert_topk_matches
+        picks = [0, 63, 64, cfg.Q // 2, cfg.Q - 1]
+        ids_h, dist_h = out_ids.cpu().numpy(), out_dist.cpu().numpy()
+        xhat = ivfadc.reconstruct(cent, cb, cells, codes)
+        pr = ivfadc.probes(queries[picks], cent, w)
+        scanned = 0
+        for jj, j in enumerate(picks):
+            inside = np.flatnonzero(np.isin(cells, pr[jj]))
+            scanned += len(inside)
+            diff = xhat[inside] - queries[j].astype(np.float64)
+            ref = np.einsum("ij,ij->i", diff, diff)
+            assert_topk_matches(ids_h[j], dist_h[j], ref, inside, k, "bench ivf q%d" % j)
+        leg["parity_checked_queries"] = picks
+        leg["vectors_in_probed_lists_per_query"] = scanned / len(picks)
+        log("IVFADC: parity of the timed output against the oracle ok on queries %s" % picks)
+    log("IVFADC (8192 cells, w=64) top-100: %.2f ms/step, %.3e queries/s; kernels %s"
+        % (ms, leg["queries_per_s"], {n: round(v["ms_per_step"], 3) for n, v in kernels.items()}))
+    return leg
+
+
+def measure_ceilings(etf, torch, stream):
+    """What this card's memory delivers to plain streaming kernels (the library's probe kernels): sequential reads,
+    writes, a copy, and scattered 256-byte rows, over a 4 GiB window (HBM) and a 64 MiB window (inside the memory-side
+    cache)."""
+    c = etf.Context(device=0, stream=stream)
+    out = {}
+    for label, nbytes in (("4GiB", 4 << 30), ("64MiB", 64 << 20)):
+        a = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        b = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        a.view(torch.float32).normal_()
+        reps = 5 if nbytes > (1 << 30) else 50
+        for kind, kname, moved in ((etf.ETF_PROBE_READ, "read", nbytes), (etf.ETF_PROBE_WRITE, "write", nbytes),
+                                   (etf.ETF_PROBE_COPY, "copy", 2 * nbytes), (etf.ETF_PROBE_ROWS, "rows_256B_scattered", nbytes)):
+            tgt = b if kind == etf.ETF_PROBE_WRITE else a
+            for _ in range(2):
+                c.probe_bandwidth(kind, tgt, b if kind != etf.ETF_PROBE_WRITE else a, nbytes)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                c.probe_bandwidth(kind, tgt, b if kind != etf.ETF_PROBE_WRITE else a, nbytes)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            out["%s_%s_GBps" % (kname, label)] = moved / 1e9 / (ms / 1e3)
+        del a, b
+    # LDS read rate of the chip (no device memory involved): conflict-free 16-byte reads, and the table lookups'
+    # pattern of 64-byte rows at scattered positions
+    b = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    total = 64 << 30
+    for kind, kname in ((etf.ETF_PROBE_LDS, "lds_read_b128"), (etf.ETF_PROBE_LDS_SCATTER, "lds_read_b128_scattered_rows")):
+        c.probe_bandwidth(kind, b, b, total)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            c.probe_bandwidth(kind, b, b, total)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 3
+        out["%s_GBps" % kname] = total / 1e9 / (ms / 1e3)
+    log("memory ceilings (GB/s): " + ", ".join("%s %.0f" % kv for kv in out.items()))
+    return out
+
+
+def encode_leg(etf, torch, cfg_name):
+    """The device encoder alone on one configuration's database (for counter runs)."""
+    from workload import get_config
+    cfg = get_config(cfg_name)
+    _, _, _, info = make_inputs(cfg, etf, torch)
+    return info
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -169,15 +519,18 @@ def main():
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--scale-n", type=int, default=0, help="override N (debugging only; invalidates the metric)")
     ap.add_argument("--scale-q", type=int, default=0, help="override Q (debugging only; invalidates the metric)")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline and the parity spot check")
-    ap.add_argument("--no-others", action="store_true", help="skip the flat and single-tree legs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline and every parity check")
+    ap.add_argument("--no-others", action="store_true", help="skip the legs beside the headline search")
+    ap.add_argument("--no-configs", action="store_true", help="skip the legs of the other configurations (cfg3, cfg4, cfg5)")
+    ap.add_argument("--configs", default="cfg3,cfg4,cfg5", help="the other configurations timed beside the headline")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
     ap.add_argument("--levels", action="store_true",
                     help="same as --traversal 1: the level-synchronous traversal (partial sums of internal nodes in HBM)")
     ap.add_argument("--traversal", type=int, default=2, choices=[0, 1, 2],
                     help="2 every table slice in LDS (default), 0 distance context in registers + result tables, 1 level-synchronous")
     ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE", help="library option for every context (tuning)")
-    ap.add_argument("--no-copy", action="store_true", help="skip the 1 GiB device copy (bandwidth ceiling / counter calibration)")
+    ap.add_argument("--no-copy", action="store_true", help="skip the device copy and the memory ceilings")
+    ap.add_argument("--encode-only", action="store_true", help="run the device encoder on the configuration's database and stop (counter runs)")
     args = ap.parse_args()
     if args.levels:
         args.traversal = 1
@@ -193,97 +546,26 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     etf.load_library()          # raises if the HIP library is missing: there is no fallback
+    if args.encode_only:
+        print(json.dumps({"encode_gpu": encode_leg(etf, torch, args.config)}), flush=True)
+        return
 
     cfg = get_config(args.config)
-    k = cfg.topk or 100
-    cb, codes, queries, encode_info = make_inputs(cfg, etf, torch, args.scale_n or None, args.scale_q or None)
-    N, Q = codes.shape[0], queries.shape[0]
-    stream = torch.cuda.current_stream().cuda_stream
-    qd = torch.from_numpy(queries).cuda()
-    out_ids = torch.empty((Q, k), dtype=torch.int32, device="cuda")
-    out_dist = torch.empty((Q, k), dtype=torch.float32, device="cuda")
-
-    def make_ctx(T, traversal=None):
-        c = etf.Context(device=0, stream=stream)
-        c.set_option("traversal", args.traversal if traversal is None else traversal)
-        for nv in args.opt:
-            name, val = nv.split("=")
-            c.set_option(name, int(val))
-        c.pq_set_codebooks(cb)
-        t0 = time.time()
-        c.index_build(codes, T=T)
-        c.index_upload()
-        log("index T=%d: build + upload %.1f s, %.1f MB on device" % (T, time.time() - t0, c.index_device_bytes() / 1e6))
-        c.profile_enable(not args.no_profile)
-        return c
-
-    T = max(cfg.trees, 1)
-    tiles = (Q + 63) // 64
+    wl = Workload(cfg, etf, torch, args, args.scale_n or None, args.scale_q or None)
+    cb, codes, queries, encode_info = wl.cb, wl.codes, wl.queries, wl.encode_info
+    N, Q, k, T = wl.N, wl.Q, wl.k, wl.T
+    stream, qd, out_ids, out_dist = wl.stream, wl.qd, wl.out_ids, wl.out_dist
     mode = etf.ETF_MODE_FOREST
+    make_ctx = wl.make_ctx
 
-    def measure_forest(traversal, steps, warmup):
-        """Times the E-Forest search with one traversal; returns the numbers of the JSON line."""
-        forest = make_ctx(T, traversal)
-        stats = forest.index_stats()
-        ws = forest.alloc_workspace(Q, k, mode)
-        log("traversal %s: workspace %.2f GB" % (TRAVERSAL_NAMES[traversal], ws.numel() / 1e9))
-        dt, prof = time_search(forest, qd, k, mode, warmup, steps, torch, ws, out_ids, out_dist, cfg.query_batch)
-        ms_step = dt / steps * 1e3
-        value = N * Q * steps / dt
-        fallbacks = forest.last_fallback_count()
-        log("E-Forest(T=%d) top-%d, %s: %.2f ms/step, %.3e distances/s, %d queries via the exact kernel"
-            % (T, k, TRAVERSAL_NAMES[traversal], ms_step, value, fallbacks))
-        S = forest.index_layout().n_sample_enc
-        lds_path = "lds" in prof and prof["lds"][1] > 0
-        ctx_path = traversal != 1 and T <= 4
-        alg = algorithmic_bytes(stats, "forest_lds" if lds_path else "forest_ctx" if ctx_path else "forest", S, tiles)
-        kernels = {}
-        for name, (ms, cnt) in prof.items():
-            if cnt:
-                kernels[name] = {"ms_per_step": ms / steps, "launches_per_step": cnt / steps,
-                                 "alg_GB_per_step": alg.get(name, 0) / 1e9,
-                                 "alg_GBps": (alg.get(name, 0) / 1e9) / (ms / steps / 1e3) if ms > 0 and name in alg else None}
-        roofline = None
-        if kernels:
-            dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
-            kd = kernels[dom]
-            lps = kd["launches_per_step"]
-            achieved = kd["alg_GBps"] or 0.0
-            traffic = None if (args.scale_n or args.scale_q) else MEASURED_TRAFFIC_BYTES.get((cfg.name, dom, TRAVERSAL_NAMES[traversal]))
-            if dom == "lds":
-                # bound by the LDS pipe: algorithmic bytes are the 4-byte table entries the method reads per query
-                roofline = {"bound": "alu", "resource": "LDS read bandwidth", "kernel": dom, "achieved": achieved,
-                            "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": achieved / LDS_PEAK_GBS, "traffic": traffic,
-                            # the same figure on the vector unit: one float32 add per 4-byte entry, against
-                            # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz of unpacked, unfused float32 operations
-                            "alu": {"achieved": achieved / 4e3, "peak": VALU_PEAK_TOPS, "unit": "TFLOP/s",
-                                    "frac": achieved / 4e3 / VALU_PEAK_TOPS}}
-            else:
-                roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic}
-            roofline.update({"alg_bytes_per_launch": alg.get(dom, 0) / lps if lps else None,
-                             "avg_launch_ms": kd["ms_per_step"] / lps if lps else None, "launches_per_step": lps})
-            if dom != "lds":
-                # the traversal as a whole (levels + leaves + reduction): the bandwidth figure of the table-based paths
-                trav = [n for n in ("level", "leaf", "reduce", "sample") if n in kernels]
-                tms = sum(kernels[n]["ms_per_step"] for n in trav)
-                tgb = sum(kernels[n]["alg_GB_per_step"] for n in trav)
-                roofline["traversal"] = {"kernels": trav, "ms_per_step": tms, "alg_GB_per_step": tgb,
-                                         "alg_GBps": tgb / (tms / 1e3) if tms > 0 else None,
-                                         "frac": (tgb / (tms / 1e3)) / HBM_PEAK_GBS if tms > 0 else None}
-        res = {"ms_per_step": ms_step, "value": value, "fallbacks": fallbacks, "kernels": kernels, "roofline": roofline,
-               "stats": stats, "S": int(S), "traversal": TRAVERSAL_NAMES[traversal]}
-        del ws
-        return res
-
-    main_res = measure_forest(args.traversal, args.steps, args.warmup)
+    main_res = wl.measure_search(T, args.traversal, args.steps, args.warmup)
     got_ids, got_dist = out_ids.cpu().numpy(), out_dist.cpu().numpy()
     ms_step, value, fallbacks = main_res["ms_per_step"], main_res["value"], main_res["fallbacks"]
     kernels, roofline, stats, S = main_res["kernels"], main_res["roofline"], main_res["stats"], main_res["S"]
 
-    # ---- a plain device copy of known size: achievable-bandwidth ceiling, and the reference dispatch
-    #      against which the HBM byte counters are scaled
-    copy = None
+    # ---- a plain device copy of known size (the reference dispatch against which the HBM byte counters are
+    #      scaled) and the memory ceilings of this card from the library's probe kernels
+    copy = ceilings = None
     if not args.no_copy:
         nbytes = 1 << 30
         src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
@@ -301,19 +583,20 @@ def main():
         copy = {"bytes_read": nbytes, "bytes_written": nbytes, "ms": ms, "GBps": 2 * nbytes / 1e9 / (ms / 1e3)}
         log("device copy of 1 GiB: %.3f ms, %.0f GB/s (read + write)" % (ms, copy["GBps"]))
         del src, dst
+        ceilings = measure_ceilings(etf, torch, stream)
 
-    # ---- the same workload through the flat kernel and a single E-Tree, same run
+    # ---- the same workload through the other paths, same run
     others = {}
     if not args.no_others:
         osteps = max(2, min(args.steps, 10))   # the other legs: up to ten steps after two warm-ups
         owarm = 2
         if args.traversal == 2:
             # the same E-Forest search through the table-based traversal (per-tree result tables in HBM)
-            r0 = measure_forest(0, osteps, owarm)
+            r0 = wl.measure_search(T, 0, osteps, owarm)
             others["e_forest_register_context"] = {k2: r0[k2] for k2 in ("value", "ms_per_step", "kernels", "roofline")}
         tree = make_ctx(1)
         for name, ctx, m in (("flat_gpu", tree, etf.ETF_MODE_FLAT), ("e_tree_gpu", tree, etf.ETF_MODE_TREE)):
-            w2 = ctx.alloc_workspace(Q, k, m)
+            w2 = ctx.alloc_workspace(min(Q, cfg.query_batch or Q), k, m)
             # The flat scan lists every copy of an encoding; where one encoding has more copies than a candidate
             # list holds, every query ends in the whole-database selection kernel: one untimed-warm-up-free step
             heavy = m == etf.ETF_MODE_FLAT and ctx.index_stats()["max_dup"] > 32768
@@ -332,7 +615,7 @@ def main():
             if str(tt) in by_trees or cfg.M % tt:
                 continue
             fc = make_ctx(tt)
-            wf = fc.alloc_workspace(Q, k, mode)
+            wf = fc.alloc_workspace(min(Q, cfg.query_batch or Q), k, mode)
             df, _ = time_search(fc, qd, k, mode, owarm, osteps, torch, wf, out_ids, out_dist, cfg.query_batch)
             by_trees[str(tt)] = df / osteps * 1e3
             del fc, wf
@@ -347,7 +630,7 @@ def main():
         uc.index_build(rc, T=T)
         uc.index_upload()
         ust = uc.index_stats()
-        wu = uc.alloc_workspace(Q, k, mode)
+        wu = uc.alloc_workspace(min(Q, cfg.query_batch or Q), k, mode)
         du, _ = time_search(uc, qd, k, mode, owarm, osteps, torch, wu, out_ids, out_dist, cfg.query_batch)
         others["unstructured_control"] = {"ms_per_step": du / osteps * 1e3, "value": N * Q * osteps / du, "n_distinct": ust["n_distinct"],
                                           "lookups_per_encoding": sum(t["lookups"] for t in ust["trees"]) / N,
@@ -358,7 +641,7 @@ def main():
         # the other payload on the same forest: the k largest scalar products (option metric = 1)
         ipc = make_ctx(T)
         ipc.set_option("metric", 1)
-        w4 = ipc.alloc_workspace(Q, k, mode)
+        w4 = ipc.alloc_workspace(min(Q, cfg.query_batch or Q), k, mode)
         d4, p4 = time_search(ipc, qd, k, mode, owarm, osteps, torch, w4, out_ids, out_dist, cfg.query_batch)
         others["scalar_product_search"] = {"value": N * Q * osteps / d4, "ms_per_step": d4 / osteps * 1e3,
                                            "kernels_ms_per_step": {n: v[0] / osteps for n, v in p4.items() if v[1]},
@@ -377,7 +660,7 @@ def main():
         oc.index_build(codes, T=T)
         oc.index_upload()
         oc.profile_enable(not args.no_profile)
-        w5 = oc.alloc_workspace(Q, k, mode)
+        w5 = oc.alloc_workspace(min(Q, cfg.query_batch or Q), k, mode)
         d5, p5 = time_search(oc, qd, k, mode, owarm, osteps, torch, w5, out_ids, out_dist, cfg.query_batch)
         others["chunk_order"] = {"order": [int(v) for v in order], "lookups_given_order": lk_given, "lookups_suggested_order": lk_order,
                                  "lookups_on": "at most 2^18 evenly spaced vectors", "suggest_s": t_suggest,
@@ -400,7 +683,7 @@ def main():
                 db.index_build_device(codes_d, T=T, image=img, ws=wsb)   # synchronises before it returns
                 times.append((time.perf_counter() - t0) * 1e3)
             del wsb
-            w3 = db.alloc_workspace(Q, k, mode)
+            w3 = db.alloc_workspace(min(Q, cfg.query_batch or Q), k, mode)
             d3, _ = time_search(db, qd, k, mode, owarm, osteps, torch, w3, out_ids, out_dist, cfg.query_batch)
             others["index_build_device"] = {"ms": min(times[1:]), "vectors_per_s": N / (min(times[1:]) / 1e3),
                                             "image_bytes": db.index_device_bytes(), "image_bytes_bound": nimg, "workspace_bytes": nws,
@@ -410,7 +693,7 @@ def main():
             log("index build on the device: %.2f ms (%.3e vectors/s); search on it %.2f ms/step"
                 % (min(times[1:]), N / (min(times[1:]) / 1e3), d3 / osteps * 1e3))
             del db, img, w3, codes_d
-        if cfg.name == "cfg2" and not (args.scale_n or args.scale_q):
+        if cfg.name == "cfg2" and wl.valid:
             # all-pairs output at a size where the output stream decides: this database, the first 2048 queries
             ta = make_ctx(T)
             nqa = min(Q, 2048)
@@ -439,28 +722,42 @@ def main():
             t1.pq_set_codebooks(cb1)
             t1.index_build(codes1, T=1)
             t1.index_upload()
+            t1.profile_enable(not args.no_profile)
             q1d = torch.from_numpy(q1).cuda()
             dist1 = torch.empty((q1.shape[0], codes1.shape[0]), dtype=torch.float32, device="cuda")
             w1 = t1.alloc_workspace(q1.shape[0], 0, etf.ETF_MODE_TREE)
             for _ in range(3):
                 t1.adc(q1d, etf.ETF_MODE_TREE, dist1, w1)
             torch.cuda.synchronize()
+            t1.profile_read()
             t0 = time.perf_counter()
             for _ in range(20):
                 t1.adc(q1d, etf.ETF_MODE_TREE, dist1, w1)
             torch.cuda.synchronize()
             ms1 = (time.perf_counter() - t0) / 20 * 1e3
+            p1 = t1.profile_read()
             nd1 = codes1.shape[0] * q1.shape[0]
-            others["all_pairs_cfg1"] = {"ms_per_step": ms1, "value": nd1 / (ms1 / 1e3), "output_GBps": nd1 * 4 / 1e9 / (ms1 / 1e3),
+            gb1 = nd1 * 4 / 1e9 / (ms1 / 1e3)
+            others["all_pairs_cfg1"] = {"ms_per_step": ms1, "value": nd1 / (ms1 / 1e3), "output_GBps": gb1,
+                                        "roofline": {"bound": "hbm", "achieved": gb1, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gb1 / HBM_PEAK_GBS},
+                                        "kernels_ms_per_step": {n: v[0] / 20 for n, v in p1.items() if v[1]},
                                         "workload": "cfg1: N=%d Q=%d, single E-Tree, all pairs in input order" % (codes1.shape[0], q1.shape[0])}
-            log("all pairs (cfg1): %.3f ms/step, %.3e distances/s, %.0f GB/s of output" % (ms1, others["all_pairs_cfg1"]["value"], others["all_pairs_cfg1"]["output_GBps"]))
+            if not args.no_cpu:
+                import oracle
+                from parity import assert_distances_close
+                assert_distances_close(dist1.cpu().numpy(), oracle.adc_all(q1, cb1, codes1), "bench cfg1 all pairs")
+                others["all_pairs_cfg1"]["parity"] = "every distance against the oracle: ok"
+            log("all pairs (cfg1): %.3f ms/step, %.3e distances/s, %.0f GB/s of output" % (ms1, others["all_pairs_cfg1"]["value"], gb1))
             del t1, dist1, w1
+
+        if cfg.name == "cfg2" and wl.valid:
+            others["ivfadc"] = ivf_leg(etf, torch, args, osteps, owarm)
 
     # ---- CPU oracle on a bounded sample of the same workload, and parity of the timed output on it
     cpu = None
     if not args.no_cpu:
         import oracle
-        from parity import assert_topk_matches
+        from parity import assert_topk_matches_identity
         nq = min(Q, 16)
         t0 = time.perf_counter()
         oracle.search(queries[:nq], cb, codes, k)
@@ -474,15 +771,18 @@ def main():
                          % (nq2, Q, N, k, t2)}
         log("CPU oracle: %.3e distances/s on %d threads (%s)" % (cpu["value"], cpu["cores"], cpu["sample"]))
         npar = min(Q, 24)
-        ref = oracle.adc_all(queries[:npar], cb, codes)
-        for j in range(npar):
-            assert_topk_matches(got_ids[j], got_dist[j], ref[j], np.arange(N), k, "bench q%d" % j)
-        # plus a spread of queries from the rest of the batch (other tiles, the ragged last tile)
-        rest = np.unique(np.linspace(npar, Q - 1, 8).astype(int)) if Q > npar else []
-        for j in rest:
+        picks = sorted(set(list(range(npar)) + [int(v) for v in np.linspace(npar, Q - 1, 8)])) if Q > npar else list(range(npar))
+        for j in picks:      # the first tile, other tiles, the ragged last tile
             r = oracle.adc_all(queries[j:j + 1], cb, codes)[0]
-            assert_topk_matches(got_ids[j], got_dist[j], r, np.arange(N), k, "bench q%d" % j)
-        log("parity of the timed output against the oracle: ok on %d queries" % (npar + len(rest)))
+            assert_topk_matches_identity(got_ids[j], got_dist[j], r, k, "bench q%d" % j)
+        log("parity of the timed output against the oracle: ok on %d queries" % len(picks))
+
+    # ---- the other configurations of the workload list, each end to end with its own roofline and parity check
+    if not (args.no_others or args.no_configs) and cfg.name == "cfg2" and wl.valid:
+        del wl, qd, out_ids, out_dist
+        torch.cuda.empty_cache()
+        for name in [c for c in args.configs.split(",") if c]:
+            others[name] = config_leg(name, etf, torch, args, 5, 2)
 
     line = {
         "metric": "encoding-distances/sec (batched queries), E-Forest ADC + top-k, 1 GPU",
@@ -491,13 +791,15 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: d=%d N=%d Q=%d PQ M=%d K=%d, E-Forest T=%d, top-%d, seeded %d-component Gaussian mixture"
                                % (cfg.name, cfg.d, N, Q, cfg.M, cfg.K, T, k, cfg.components),
-                   "traversal": TRAVERSAL_NAMES[args.traversal], "query_batch": cfg.query_batch or Q,
-                   "valid": not (args.scale_n or args.scale_q)},
+                   "traversal": TRAVERSAL_NAMES[args.traversal], "path": PATH_NOTES[args.traversal],
+                   "query_batch": cfg.query_batch or Q, "valid": not (args.scale_n or args.scale_q),
+                   "kernel_sources": kernel_source_hash()},
         "roofline": roofline,
         # the table-based E-Forest traversal of the same run (per-tree result tables in HBM): the HBM-bandwidth figure
         "roofline_hbm_traversal": (others.get("e_forest_register_context") or {}).get("roofline"),
         "cpu_baseline": cpu,
         "kernels": kernels, "others": others, "encode_gpu": encode_info, "fallback_queries": fallbacks, "device_copy": copy,
+        "memory_ceilings": ceilings,
         "index": {"n_distinct": stats["n_distinct"], "max_dup": stats["max_dup"], "device_MB": stats["device_bytes"] / 1e6,
                   "trees": stats["trees"], "sample": int(S)},
         "paper_context": PAPER_CONTEXT,

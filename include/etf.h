@@ -126,6 +126,20 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     shape runs as 0.
  *                     0 and 1 add the chunks left to right and return identical bits; 2 adds the
  *                     chunks of every group of four in pairs and agrees with them to rounding.
+ *   "encode_kernel"   etf_pq_encode_device (and the residual encoding of etf_ivf_assign_device).  0 (default): the
+ *                     K distance evaluations of every (vector, group) on the matrix cores as ||c||^2 - 2 x.c;
+ *                     where the smallest is not clearly below the second smallest (by twice a bound on the
+ *                     rounding of either form) the float32 rule is evaluated for all K codewords.  1: the float32
+ *                     rule for every codeword (needs d/M <= 128).  Both return the same codes, bit for bit
+ *   "lds_filter"      the main pass of searches with traversal 2.  0 (default): float32 sums of the table entries,
+ *                     compared with the query's bound.  1: that pass only decides which encodings can be among
+ *                     the k nearest, and does so in 32-bit fixed point: every table entry is scaled so that the
+ *                     query's bound (from the sample) becomes 2^27, truncated, and cut off at 2^28; sums of
+ *                     entries are integer additions, three operands per instruction, compared with the bound
+ *                     rounded up.  No encoding whose float32 distance is at or below the bound is lost; the
+ *                     distances of the survivors around the k-th are then recomputed as float32 sums of the
+ *                     float32 table entries, and those are what is ordered and returned.  A third fewer vector
+ *                     instructions in that pass, and the same time: the pass is bound by the LDS reads.
  * Returns ETF_EINVAL for an unknown name or a value out of range. */
 int etf_set_option(etf_ctx *ctx, const char *name, int64_t value);
 
@@ -241,7 +255,7 @@ int etf_index_export(const etf_ctx *ctx, void *host_buf, int64_t bytes);
  * ties.  x [n][d] device, codes_out [n][M] device; ws is device scratch of at least
  * etf_encode_workspace_bytes() bytes (256-byte aligned) that receives the codebooks;
  * the copy is enqueued on the context's stream from the context's host copy.
- * Needs d/M <= 128; ETF_EINVAL otherwise.  n = 0 is allowed. */
+ * Option "encode_kernel" = 1 needs d/M <= 128 (ETF_EINVAL otherwise).  n = 0 is allowed. */
 int64_t etf_encode_workspace_bytes(const etf_ctx *ctx);
 int etf_pq_encode_device(etf_ctx *ctx, const float *x, int64_t n, uint8_t *codes_out, void *ws, int64_t ws_bytes);
 
@@ -320,6 +334,55 @@ int etf_search_static(etf_ctx *ctx, const float *queries, int64_t Q, int k, int 
  * search has run since the index was built or uploaded. */
 int etf_last_fallback_count(etf_ctx *ctx, int64_t *out);
 
+/* ---- IVFADC on the merged, sorted encodings -------------------------------- */
+
+/* The paper's application experiment ("Application on related algorithms", Table 1): an inverted file with a coarse
+ * quantiser of K' cells, the residual x - centroid product-quantised with the context's codebooks, w probed cells
+ * per query, the ADC of every probed list on its Encoding Tree's leaf sequence: the entries of a cell sorted by
+ * encoding, equal encodings merged into one entry with an id range.  A stored vector's distance
+ *     || q - c - r ||^2  =  || q - c ||^2  +  ( ||r||^2 + 2 <c, r> )  -  2 <q, r>
+ * (c its centroid, r its reconstructed residual) is evaluated as: the first term from the probe selection, the
+ * second a float32 constant stored with the entry (the "extra information stored on the leaf node" of the paper's
+ * Experiments section), the third a sum of M entries of scalar-product tables that depend on the query only.
+ * The terms cancel when q is close to the stored vector: a returned distance carries a rounding error of a few
+ * 2^-24 of || q - c ||^2 + ||r||^2 + 2 |<q - c, r>| + 2 |<c, r>|, not of the distance itself.
+ * Decisions that pick an integer (a vector's cell, a query's probed cells, a residual's codewords) are taken in
+ * float32: a squared distance is the sum of its (a - b)^2 terms in dimension order, one rounding per operation,
+ * lowest index on ties.
+ *
+ * etf_ivf_set_coarse   installs centroids [cells][d] (host; 1 <= cells <= 65536); needs the codebooks (for d).
+ *                      Drops any IVF index of the context.
+ * etf_ivf_assign_device  database side on the device: cells_out[i] = nearest centroid of x[i], codes_out[i] = the
+ *                      encoding of x[i] - centroid (float32 subtraction).  x [n][d], cells_out [n], codes_out [n][M]
+ *                      device; ws device scratch of etf_ivf_assign_workspace_bytes(n), 256-byte aligned.
+ * etf_ivf_build        builds the index from cells [N] and codes [N][M] (host; for example the output of
+ *                      etf_ivf_assign_device, or a reference's), ids [N] non-negative or NULL for 0..N-1.
+ * etf_ivf_upload       copies it into dev_buf (device, 256-byte aligned, etf_ivf_device_bytes()), which must stay
+ *                      alive and unmodified while searches run.  Synchronises the stream.
+ * etf_ivf_search       per query the k nearest vectors among those of its w probed cells (the w nearest centroids),
+ *                      ascending by (distance, id): out_ids [Q][k], out_dist [Q][k] device; a query whose probed
+ *                      cells hold fewer than k vectors gets id -1 and +inf beyond them.  1 <= w <= min(cells, 4096).
+ *                      Enqueues on the context's stream; etf_last_fallback_count applies. */
+typedef struct etf_ivf_stats_t {
+    int32_t cells;
+    int64_t N, entries;          /* vectors; distinct (cell, encoding) pairs                                    */
+    int64_t max_list, max_dup;   /* most entries in one cell; most vectors in one entry                         */
+    int64_t tree_lookups;        /* table lookups of one traversal of every cell's Encoding Tree: L1 + L2 + sumP */
+    int64_t flat_lookups;        /* N * M: what plain ADC over the same lists costs                              */
+    int64_t device_bytes;
+} etf_ivf_stats_t;
+int etf_ivf_set_coarse(etf_ctx *ctx, const float *centroids, int cells);
+int64_t etf_ivf_assign_workspace_bytes(const etf_ctx *ctx, int64_t n);
+int etf_ivf_assign_device(etf_ctx *ctx, const float *x, int64_t n, int32_t *cells_out, uint8_t *codes_out, void *ws,
+                          int64_t ws_bytes);
+int etf_ivf_build(etf_ctx *ctx, const int32_t *cells, const uint8_t *codes, int64_t N, const int32_t *ids);
+int etf_ivf_stats(const etf_ctx *ctx, etf_ivf_stats_t *out);
+int64_t etf_ivf_device_bytes(const etf_ctx *ctx);
+int etf_ivf_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes);
+int64_t etf_ivf_workspace_bytes(const etf_ctx *ctx, int64_t Q, int k, int w);
+int etf_ivf_search(etf_ctx *ctx, const float *queries, int64_t Q, int k, int w, int32_t *out_ids, float *out_dist,
+                   void *ws, int64_t ws_bytes);
+
 /* ---- per-kernel timing (for benchmarks) ---------------------------------- */
 
 /* Kernel classes of the hot path, in launch order. */
@@ -334,8 +397,10 @@ enum {
     ETF_K_EXACT = 7,    /* exact whole-database selection                     */
     ETF_K_SAMPLE = 8,   /* distances of the bound's sample (flat or reduction) */
     ETF_K_LDS = 9,      /* tree / forest search with every table slice in LDS  */
-    ETF_K_ENCODE = 10,  /* device encoder                                      */
-    ETF_K_COUNT = 11
+    ETF_K_ENCODE = 10,  /* device encoder (and the coarse assignment of etf_ivf_assign_device) */
+    ETF_K_IVF_COARSE = 11, /* IVFADC: distances to the centroids and probe selection */
+    ETF_K_IVF_SCAN = 12,   /* IVFADC: scan of the probed lists                        */
+    ETF_K_COUNT = 13
 };
 /* on != 0: every later kernel launch of this context is bracketed by a pair of
  * HIP events on the context's stream. */
@@ -354,8 +419,12 @@ int etf_profile_read(etf_ctx *ctx, double *ms, int64_t *launches);
  *   ETF_PROBE_READ   reads `bytes` of a front to back (b receives one word per workgroup)
  *   ETF_PROBE_WRITE  writes `bytes` of a
  *   ETF_PROBE_COPY   copies `bytes` from a to b
- *   ETF_PROBE_ROWS   reads a as rows of 256 bytes, one wave per row, every row once, in a scattered order */
-enum { ETF_PROBE_READ = 0, ETF_PROBE_WRITE = 1, ETF_PROBE_COPY = 2, ETF_PROBE_ROWS = 3 };
+ *   ETF_PROBE_ROWS   reads a as rows of 256 bytes, one wave per row, every row once, in a scattered order
+ *   ETF_PROBE_LDS    no device memory traffic: 1024 workgroups of 16 waves read `bytes` in total from LDS, 16 bytes
+ *                    per lane and instruction, conflict-free (a unused; b receives one word per workgroup)
+ *   ETF_PROBE_LDS_SCATTER  the same with the access pattern of the table lookups: groups of four lanes read
+ *                    64-byte rows at hashed positions (bank conflicts as they fall) */
+enum { ETF_PROBE_READ = 0, ETF_PROBE_WRITE = 1, ETF_PROBE_COPY = 2, ETF_PROBE_ROWS = 3, ETF_PROBE_LDS = 4, ETF_PROBE_LDS_SCATTER = 5 };
 int etf_probe_bandwidth(etf_ctx *ctx, int kind, void *a, void *b, int64_t bytes);
 
 #ifdef __cplusplus

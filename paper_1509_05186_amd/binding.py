@@ -25,9 +25,12 @@ EXPORTS = [
     "etf_workspace_bytes", "etf_lut_build", "etf_adc", "etf_search", "etf_last_fallback_count",
     "etf_static_scratch_bytes", "etf_search_static",
     "etf_profile_enable", "etf_profile_read", "etf_probe_bandwidth",
+    "etf_ivf_set_coarse", "etf_ivf_assign_workspace_bytes", "etf_ivf_assign_device", "etf_ivf_build", "etf_ivf_stats",
+    "etf_ivf_device_bytes", "etf_ivf_upload", "etf_ivf_workspace_bytes", "etf_ivf_search",
 ]
-ETF_PROBE_READ, ETF_PROBE_WRITE, ETF_PROBE_COPY, ETF_PROBE_ROWS = 0, 1, 2, 3
-KERNEL_CLASSES = ["lut", "level", "leaf", "flat", "reduce", "tau", "select", "exact", "sample", "lds", "encode"]
+ETF_PROBE_READ, ETF_PROBE_WRITE, ETF_PROBE_COPY, ETF_PROBE_ROWS, ETF_PROBE_LDS, ETF_PROBE_LDS_SCATTER = 0, 1, 2, 3, 4, 5
+KERNEL_CLASSES = ["lut", "level", "leaf", "flat", "reduce", "tau", "select", "exact", "sample", "lds", "encode",
+                  "ivf_coarse", "ivf_scan"]
 
 
 class EtfStats(ctypes.Structure):
@@ -59,6 +62,15 @@ class EtfStats(ctypes.Structure):
         return {"M": self.M, "K": self.K, "T": T, "N": int(self.N), "n_distinct": int(self.n_distinct),
                 "max_dup": int(self.max_dup), "device_bytes": int(self.device_bytes), "trees": trees,
                 "chunk_order": [int(self.chunk_order[j]) for j in range(self.M)]}
+
+
+class EtfIvfStats(ctypes.Structure):
+    _fields_ = [("cells", ctypes.c_int32), ("N", ctypes.c_int64), ("entries", ctypes.c_int64), ("max_list", ctypes.c_int64),
+                ("max_dup", ctypes.c_int64), ("tree_lookups", ctypes.c_int64), ("flat_lookups", ctypes.c_int64),
+                ("device_bytes", ctypes.c_int64)]
+
+    def as_dict(self) -> dict:
+        return {name: int(getattr(self, name)) for name, _ in self._fields_}
 
 
 _Grid64 = (ctypes.c_int64 * ETF_MAX_M) * ETF_MAX_M
@@ -141,6 +153,15 @@ def load_library():
         "etf_profile_enable": (I, [P, I]),
         "etf_profile_read": (I, [P, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(L)]),
         "etf_probe_bandwidth": (I, [P, I, P, P, L]),
+        "etf_ivf_set_coarse": (I, [P, P, I]),
+        "etf_ivf_assign_workspace_bytes": (L, [P, L]),
+        "etf_ivf_assign_device": (I, [P, P, L, P, P, P, L]),
+        "etf_ivf_build": (I, [P, P, P, L, P]),
+        "etf_ivf_stats": (I, [P, ctypes.POINTER(EtfIvfStats)]),
+        "etf_ivf_device_bytes": (L, [P]),
+        "etf_ivf_upload": (I, [P, P, L]),
+        "etf_ivf_workspace_bytes": (L, [P, L, I, I]),
+        "etf_ivf_search": (I, [P, P, L, I, I, P, P, P, L]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -397,6 +418,68 @@ class Context:
         v = ctypes.c_int64(0)
         self._ck(self._lib.etf_last_fallback_count(self._h, ctypes.byref(v)))
         return int(v.value)
+
+    # ---- IVFADC
+    def ivf_set_coarse(self, centroids: np.ndarray):
+        c = np.ascontiguousarray(centroids, dtype=np.float32)
+        if c.ndim != 2 or c.shape[1] != self._shape[0]:
+            raise ValueError("expected [cells][%d] centroids" % self._shape[0])
+        self._ck(self._lib.etf_ivf_set_coarse(self._h, _host(c), c.shape[0]))
+
+    def ivf_assign_device(self, x, ws=None):
+        """x: float32 device tensor [n][d]; returns (cells int32 [n], codes uint8 [n][M]) device tensors."""
+        import torch
+        d, M, K = self._shape
+        if x.dim() != 2 or x.shape[1] != d or x.dtype != torch.float32 or not x.is_contiguous():
+            raise ValueError("expected a contiguous float32 tensor [n][%d]" % d)
+        n = x.shape[0]
+        cells = torch.empty((n,), dtype=torch.int32, device=x.device)
+        codes = torch.empty((n, M), dtype=torch.uint8, device=x.device)
+        if ws is None:
+            ws = torch.empty(self._ck(self._lib.etf_ivf_assign_workspace_bytes(self._h, n)) + 256, dtype=torch.uint8, device=x.device)
+        p, nb = self._ws(ws)
+        self._ck(self._lib.etf_ivf_assign_device(self._h, _dev(x) if n else None, n, _dev(cells) if n else None,
+                                                 _dev(codes) if n else None, p, nb))
+        return cells, codes
+
+    def ivf_build(self, cells: np.ndarray, codes: np.ndarray, ids: Optional[np.ndarray] = None):
+        cells = np.ascontiguousarray(cells, dtype=np.int32)
+        codes = np.ascontiguousarray(codes, dtype=np.uint8)
+        if codes.ndim != 2 or codes.shape[1] != self._shape[1] or cells.shape != (codes.shape[0],):
+            raise ValueError("expected cells [N] and codes [N][%d]" % self._shape[1])
+        ids_a = None if ids is None else np.ascontiguousarray(ids, dtype=np.int32)
+        self._ck(self._lib.etf_ivf_build(self._h, _host(cells), _host(codes), codes.shape[0], _host(ids_a)))
+
+    def ivf_stats(self) -> dict:
+        st = EtfIvfStats()
+        self._ck(self._lib.etf_ivf_stats(self._h, ctypes.byref(st)))
+        return st.as_dict()
+
+    def ivf_upload(self, dev_buf=None):
+        import torch
+        n = self._ck(self._lib.etf_ivf_device_bytes(self._h))
+        if dev_buf is None:
+            dev_buf = torch.empty(n + 256, dtype=torch.uint8, device="cuda")
+        off = (-dev_buf.data_ptr()) % 256
+        self._ck(self._lib.etf_ivf_upload(self._h, dev_buf.data_ptr() + off, dev_buf.numel() - off))
+        self._keep["ivf"] = dev_buf
+        return dev_buf
+
+    def ivf_workspace_bytes(self, Q: int, k: int, w: int) -> int:
+        return self._ck(self._lib.etf_ivf_workspace_bytes(self._h, Q, k, w))
+
+    def ivf_search(self, queries, k: int, w: int, out_ids=None, out_dist=None, ws=None):
+        import torch
+        Q = queries.shape[0]
+        if out_ids is None:
+            out_ids = torch.empty((Q, k), dtype=torch.int32, device=queries.device)
+        if out_dist is None:
+            out_dist = torch.empty((Q, k), dtype=torch.float32, device=queries.device)
+        if ws is None:
+            ws = torch.empty(self.ivf_workspace_bytes(Q, k, w) + 256, dtype=torch.uint8, device=queries.device)
+        p, n = self._ws(ws)
+        self._ck(self._lib.etf_ivf_search(self._h, _dev(queries), Q, k, w, _dev(out_ids), _dev(out_dist), p, n))
+        return out_ids, out_dist
 
     def probe_bandwidth(self, kind: int, a, b, nbytes: int):
         """One launch of a streaming probe kernel over the uint8 device tensors a and b (256-byte aligned)."""

@@ -120,35 +120,6 @@ extern "C" int etf_profile_read(etf_ctx *ctx, double *ms, int64_t *launches)
     return ETF_OK;
 }
 
-// plain streaming kernels over the caller's buffers: the memory ceilings a benchmark quotes beside the traversal
-extern "C" int etf_probe_bandwidth(etf_ctx *ctx, int kind, void *a, void *b, int64_t bytes)
-{
-    if (!ctx) return ETF_EINVAL;
-    if (ctx->device < 0) return fail(ctx, ETF_ENOGPU, "host-only context");
-    if (!a || !b || bytes < 65536 || (bytes & 255) != 0 || (((uintptr_t)a | (uintptr_t)b) & 255) != 0)
-        return fail(ctx, ETF_EINVAL, "probe buffers must be 256-byte aligned and a multiple of 256 bytes, at least 64 KiB");
-    HIP_TRY(ctx, hipSetDevice(ctx->device));
-    hipStream_t st = (hipStream_t)ctx->stream;
-    const unsigned grid = 256 * 16;  // sixteen workgroups of 256 threads per compute unit; b must hold 4 bytes per workgroup
-    const int64_t n16 = bytes / 16, nrows = bytes / 256;
-    switch (kind) {
-        case ETF_PROBE_READ: hipLaunchKernelGGL(k_probe_read, dim3(grid), dim3(256), 0, st, (const u32x4 *)a, n16, (uint32_t *)b); break;
-        case ETF_PROBE_WRITE: hipLaunchKernelGGL(k_probe_write, dim3(grid), dim3(256), 0, st, (u32x4 *)a, n16); break;
-        case ETF_PROBE_COPY: hipLaunchKernelGGL(k_probe_copy, dim3(grid), dim3(256), 0, st, (const u32x4 *)a, (u32x4 *)b, n16); break;
-        case ETF_PROBE_ROWS: {
-            // a multiplier near 0.618 nrows that shares no factor with nrows: consecutive rows land far apart
-            uint64_t mult = (uint64_t)((double)nrows * 0.6180339887) | 1u;
-            auto gcd = [](uint64_t x, uint64_t y) { while (y) { const uint64_t t = x % y; x = y; y = t; } return x; };
-            while (gcd(mult, (uint64_t)nrows) != 1) mult += 2;
-            hipLaunchKernelGGL(k_probe_rows, dim3(grid), dim3(256), 0, st, (const float *)a, nrows, mult, (uint32_t *)b);
-            break;
-        }
-        default: return fail(ctx, ETF_EINVAL, "unknown probe kind %d", kind);
-    }
-    LAUNCH_CHECK(ctx, "k_probe");
-    return ETF_OK;
-}
-
 extern "C" int etf_set_stream(etf_ctx *ctx, void *hip_stream)
 {
     if (!ctx) return ETF_EINVAL;
@@ -210,6 +181,7 @@ struct Plan {
     bool ctx_path = false;    // trees walked with the distance context in registers (no partial-sum tables)
     bool lds_path = false;    // search with every table slice in LDS: no result tables at all
     bool flat_lds = false;    // flat mode through the same kernels
+    bool fx = false;          // the main pass of the LDS-resident search filters candidates in fixed point
     int64_t o_counter = 0, o_lutT = 0, o_gmin = 0, o_tau = 0, o_boff = 0, o_bm = 0, o_cnt = 0, o_flag = 0, o_cand = 0;
     int64_t o_part[ETF_MAX_M][ETF_MAX_M];
     int64_t o_leafp[ETF_MAX_M];
@@ -217,6 +189,12 @@ struct Plan {
 };
 
 int64_t al256(int64_t x) { return (x + 255) & ~(int64_t)255; }
+int pow2_at_least_host(int n)
+{
+    int p = 1;
+    while (p < n) p <<= 1;
+    return p;
+}
 int tmax_class(int T);
 bool lds_eligible(int M, int K, int T, const int32_t *chunk_begin);
 
@@ -272,6 +250,9 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     // it means the register-context kernels, like traversal 0
     P.lds_path = mode != ETF_MODE_FLAT && ctx->opt.traversal == 2 && lds_eligible(M, K, ix.T, ix.chunk_begin.data());
     P.flat_lds = mode == ETF_MODE_FLAT && ctx->opt.traversal == 2 && lds_eligible(M, K, 1, nullptr);
+    // the fixed-point filter scales every table by its query's bound: it needs one (use_tau)
+    // (not the flat scan: it lists every copy of an encoding, and copies tie exactly)
+    P.fx = search && P.lds_path && P.use_tau && ctx->opt.lds_filter == 1 && !ctx->opt.force_fallback;
     P.ctx_path = !P.lds_path && tmax_class(ix.T) != 0 && mode != ETF_MODE_FLAT && ctx->opt.traversal != 1;
     for (int t = 1; t < ix.T; ++t)  // the register-context kernels address a tree's result table with 32-bit offsets
         if (ix.tree[t].U >= ((int64_t)1 << 24)) P.ctx_path = false;
@@ -682,7 +663,7 @@ bool lds_eligible(int M, int K, int T, const int32_t *chunk_begin)
     return M % lds_chunks_per_line(G) == 0;  // whole lines of 4 (8 at eight queries per sub-tile) chunks
 }
 
-template <int MODE, bool CTX>
+template <int MODE, bool CTX, bool FX = false>
 int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64_t nitems, const uint32_t *map, int T,
                int64_t tiles, const OutArgs &o, int cls)
 {
@@ -694,6 +675,7 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
     // The kernels are built for trees of at least four chunks (1, 2 or 4 trees); shorter trees lie inside the
     // pairs of a group of four, whose sum is formed the same way whatever the trees: they run as trees of four.
     if (M / T < 4) T = M / 4;
+    if (FX) T = 1;  // integer sums do not depend on the order of additions: one instance serves every forest
     int64_t bx;
     int per_block = 0;
     if (MODE == OUT_SAMPLE) {
@@ -711,11 +693,11 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
     ProfScope prof(ctx, cls);
     bool done = false;
 #define LDS_CASE(GG, MM4, TT)                                                                                  \
-    if constexpr ((CTX || MODE != OUT_FILTER || TT == 1) && (4 * MM4) % lds_chunks_per_line(GG) == 0) {                                                      \
+    if constexpr ((CTX || MODE != OUT_FILTER || TT == 1) && (!FX || TT == 1) && (4 * MM4) % lds_chunks_per_line(GG) == 0) {                         \
         if (!done && G == GG && M == 4 * MM4 && T == TT) {                                                     \
-            int rc = set_lds(ctx, k_lds<GG, MM4, TT, MODE, CTX>, lds);                                         \
+            int rc = set_lds(ctx, k_lds<GG, MM4, TT, MODE, CTX, FX>, lds);                                     \
             if (rc) return rc;                                                                                 \
-            hipLaunchKernelGGL((k_lds<GG, MM4, TT, MODE, CTX>), grid, dim3(1024), lds, st, rec, nitems, map, lutT, K, \
+            hipLaunchKernelGGL((k_lds<GG, MM4, TT, MODE, CTX, FX>), grid, dim3(1024), lds, st, rec, nitems, map, lutT, K, \
                                per_block, o);                                                                  \
             done = true;                                                                                       \
         }                                                                                                      \
@@ -748,6 +730,9 @@ int launch_flat(etf_ctx *ctx, const Plan &P, char *ws, int64_t nitems, const uin
         if (P.flat_lds) {
             // the sample's codes are stored side by side in sample order: no indirection
             const uint8_t *rec = MODE == OUT_SAMPLE ? reinterpret_cast<const uint8_t *>(ctx->dev_base + ctx->lay.sample_pos_codes) : codes;
+            if (MODE == OUT_FILTER && P.fx)
+                return launch_lds<MODE, false, MODE == OUT_FILTER>(ctx, P, ws, reinterpret_cast<const uint32_t *>(rec), nitems, nullptr, 1,
+                                                                   tiles, o, ETF_K_FLAT);
             return launch_lds<MODE, false>(ctx, P, ws, reinterpret_cast<const uint32_t *>(rec), nitems, nullptr, 1, tiles, o,
                                            MODE == OUT_SAMPLE ? ETF_K_SAMPLE : ETF_K_FLAT);
         }
@@ -784,6 +769,47 @@ int check_ready(etf_ctx *ctx, const void *queries, const void *ws)
 }
 
 }  // namespace
+
+// plain streaming kernels over the caller's buffers: the memory ceilings a benchmark quotes beside the traversal
+extern "C" int etf_probe_bandwidth(etf_ctx *ctx, int kind, void *a, void *b, int64_t bytes)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (ctx->device < 0) return fail(ctx, ETF_ENOGPU, "host-only context");
+    if (!a || !b || bytes < 65536 || (bytes & 255) != 0 || (((uintptr_t)a | (uintptr_t)b) & 255) != 0)
+        return fail(ctx, ETF_EINVAL, "probe buffers must be 256-byte aligned and a multiple of 256 bytes, at least 64 KiB");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    hipStream_t st = (hipStream_t)ctx->stream;
+    const unsigned grid = 256 * 16;  // sixteen workgroups of 256 threads per compute unit; b must hold 4 bytes per workgroup
+    const int64_t n16 = bytes / 16, nrows = bytes / 256;
+    switch (kind) {
+        case ETF_PROBE_READ: hipLaunchKernelGGL(k_probe_read, dim3(grid), dim3(256), 0, st, (const u32x4 *)a, n16, (uint32_t *)b); break;
+        case ETF_PROBE_WRITE: hipLaunchKernelGGL(k_probe_write, dim3(grid), dim3(256), 0, st, (u32x4 *)a, n16); break;
+        case ETF_PROBE_COPY: hipLaunchKernelGGL(k_probe_copy, dim3(grid), dim3(256), 0, st, (const u32x4 *)a, (u32x4 *)b, n16); break;
+        case ETF_PROBE_ROWS: {
+            // a multiplier near 0.618 nrows that shares no factor with nrows: consecutive rows land far apart
+            uint64_t mult = (uint64_t)((double)nrows * 0.6180339887) | 1u;
+            auto gcd = [](uint64_t x, uint64_t y) { while (y) { const uint64_t t = x % y; x = y; y = t; } return x; };
+            while (gcd(mult, (uint64_t)nrows) != 1) mult += 2;
+            hipLaunchKernelGGL(k_probe_rows, dim3(grid), dim3(256), 0, st, (const float *)a, nrows, mult, (uint32_t *)b);
+            break;
+        }
+        case ETF_PROBE_LDS:
+        case ETF_PROBE_LDS_SCATTER: {
+            // one workgroup of 16 waves per compute unit and round, `bytes` read from LDS in total
+            const int blocks = 256 * 4;
+            int iters = (int)std::min<int64_t>(bytes / ((int64_t)blocks * 16 * 1024), 1 << 20);
+            iters = std::max(8, iters & ~7);
+            int rc = kind == ETF_PROBE_LDS ? set_lds(ctx, k_probe_lds<false>, 128 * 1024) : set_lds(ctx, k_probe_lds<true>, 128 * 1024);
+            if (rc) return rc;
+            if (kind == ETF_PROBE_LDS) hipLaunchKernelGGL(k_probe_lds<false>, dim3(blocks), dim3(1024), 128 * 1024, st, iters, (uint32_t *)b);
+            else hipLaunchKernelGGL(k_probe_lds<true>, dim3(blocks), dim3(1024), 128 * 1024, st, iters, (uint32_t *)b);
+            break;
+        }
+        default: return fail(ctx, ETF_EINVAL, "unknown probe kind %d", kind);
+    }
+    LAUNCH_CHECK(ctx, "k_probe");
+    return ETF_OK;
+}
 
 extern "C" int64_t etf_workspace_bytes(const etf_ctx *ctx, int64_t Q, int k, int mode)
 {
@@ -891,13 +917,20 @@ extern "C" int etf_pq_encode_device(etf_ctx *ctx, const float *x, int64_t n, uin
     const int64_t need = etf_encode_workspace_bytes(ctx);
     if (ws_bytes < need) return fail(ctx, ETF_ENOMEM, "workspace too small: %lld < %lld", (long long)ws_bytes, (long long)need);
     const int d = ctx->d, M = ctx->M, K = ctx->K, ds = ctx->ds;
-    if (ds > 128) return fail(ctx, ETF_EINVAL, "the device encoder handles at most 128 dimensions per group (d/M = %d)", ds);
+    const bool mfma = ctx->opt.encode_kernel == 0;
+    if (!mfma && ds > 128) return fail(ctx, ETF_EINVAL, "the plain device encoder handles at most 128 dimensions per group (d/M = %d)", ds);
     if (n == 0) return ETF_OK;
     if ((n + 255) / 256 > 0x7FFFFFFF) return fail(ctx, ETF_EINVAL, "n too large for one launch");
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     hipStream_t st = (hipStream_t)ctx->stream;
     HIP_TRY(ctx, hipMemcpyAsync(ws, ctx->codebooks.data(), ctx->codebooks.size() * sizeof(float), hipMemcpyHostToDevice, st));
     const float *cb = reinterpret_cast<const float *>(ws);
+    if (mfma) {
+        ProfScope prof(ctx, ETF_K_ENCODE);
+        hipLaunchKernelGGL(k_encode_mfma, dim3((unsigned)((n + 255) / 256), (unsigned)M), dim3(256), 0, st, x, n, d, ds, K, M, cb, codes_out);
+        LAUNCH_CHECK(ctx, "k_encode_mfma");
+        return ETF_OK;
+    }
     int dsp = 4;
     while (dsp < ds) dsp <<= 1;
     const int KC = (int)std::min<int64_t>(K, LDS_BUDGET / (dsp * 4));
@@ -1021,13 +1054,15 @@ static int search_impl(etf_ctx *ctx, const float *queries, int64_t Q, int k, int
             if (flat)
                 rc = launch_flat<OUT_FILTER>(ctx, P, w, ix.N, nullptr, tiles, o);
             else if (P.lds_path)
-                rc = launch_lds<OUT_FILTER, true>(ctx, P, w, ecodes, ix.Nd, nullptr, ix.T, tiles, o, ETF_K_LDS);
+                rc = P.fx ? launch_lds<OUT_FILTER, true, true>(ctx, P, w, ecodes, ix.Nd, nullptr, ix.T, tiles, o, ETF_K_LDS)
+                          : launch_lds<OUT_FILTER, true>(ctx, P, w, ecodes, ix.Nd, nullptr, ix.T, tiles, o, ETF_K_LDS);
             else
                 rc = P.ctx_path ? launch_fused<OUT_FILTER>(ctx, P, w, r, ix.Nd, nullptr, tiles, o)
                                 : launch_reduce<OUT_FILTER>(ctx, r, ix.Nd, nullptr, tiles, o);
             if (rc) return rc;
         }
         SelectArgs sa;
+        memset(&sa, 0, sizeof sa);
         sa.cnt = cnt;
         sa.cand = cand;
         sa.C = P.C;
@@ -1038,6 +1073,19 @@ static int search_impl(etf_ctx *ctx, const float *queries, int64_t Q, int k, int
         sa.out_dist = out_dist + q0 * k;
         sa.flag = flag;
         sa.boff = boff;
+        // fixed-point candidates: rounding moves a sum by at most M units (truncated entries) plus 2^-24 relative per
+        // entry and per float32 addition of the distance it stands for, 2^27 * (M + 1) * 2^-24 = 8 (M + 1) units at the
+        // bound; twice that between two candidates
+        sa.fx_margin = P.fx ? (uint32_t)(2 * (ix.M + 8 * (ix.M + 1)) + 16) : 0u;
+        sa.lutT = lutT;
+        sa.codes = reinterpret_cast<const uint8_t *>(ctx->dev_base + (flat ? L.codes : L.ecodes));
+        sa.M = ix.M;
+        sa.K = ix.K;
+        sa.grouped = (P.lds_path || P.flat_lds) ? lds_chunks_per_line(std::max(2, pick_G(ix.M, ix.K))) : 0;
+        sa.T = flat ? 1 : ix.T;
+        for (int t = 0; t <= ETF_MAX_M; ++t) sa.chunk_begin[t] = 0;
+        if (flat) sa.chunk_begin[1] = ix.M;
+        else for (int t = 0; t <= ix.T; ++t) sa.chunk_begin[t] = ix.chunk_begin[t];
         {
             ProfScope prof(ctx, ETF_K_SELECT);
             hipLaunchKernelGGL(k_select, dim3((unsigned)nq), dim3(256), select_lds_bytes(k), st, sa);
@@ -1150,3 +1198,5 @@ extern "C" int etf_last_fallback_count(etf_ctx *ctx, int64_t *out)
     *out = v;
     return ETF_OK;
 }
+
+#include "etf_ivf.hip.h"

@@ -387,6 +387,12 @@ extern "C" int etf_set_option(etf_ctx *ctx, const char *name, int64_t value)
     } else if (n == "metric") {
         if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "metric must be 0 (squared Euclidean distance) or 1 (scalar product)");
         ctx->opt.metric = value;
+    } else if (n == "encode_kernel") {
+        if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "encode_kernel must be 0 or 1");
+        ctx->opt.encode_kernel = value;
+    } else if (n == "lds_filter") {
+        if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "lds_filter must be 0 or 1");
+        ctx->opt.lds_filter = value;
     } else if (n == "cand_cap") {
         if (value < 0 || value > (1 << 20)) return fail(ctx, ETF_EINVAL, "cand_cap out of range");
         ctx->opt.cand_cap = value;

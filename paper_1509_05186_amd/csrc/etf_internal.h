@@ -90,6 +90,24 @@ struct DevLayout {
     std::vector<DevTreeLayout> tree;
 };
 
+// IVFADC index: the database as (cell of a coarse quantiser, encoding of the residual), sorted by (cell, encoding,
+// id); equal (cell, encoding) pairs merged into one entry with an id range; list j = the entries of cell j.
+struct IvfIndex {
+    bool built = false;
+    int Kc = 0;                         // cells
+    std::vector<float> centroids;       // [Kc][d]
+    int64_t N = 0, Ne = 0;              // vectors, entries (distinct (cell, encoding) pairs)
+    int64_t max_list = 0, max_dup = 0;  // most entries in one list, most vectors in one entry
+    int64_t tree_lookups = 0;           // sum over the lists of the table lookups of the list's E-Tree (L1 + L2 + sumP)
+    std::vector<uint32_t> lbegin;       // [Kc+1] range of entries of every cell
+    std::vector<uint8_t> ecodes;        // [Ne][M]
+    std::vector<float> eterm;           // [Ne] ||r||^2 + 2 <centroid, r>, r = the entry's reconstructed residual
+    std::vector<uint32_t> ebegin;       // [Ne+1] range of ids_sorted of every entry
+    std::vector<int32_t> ids_sorted;    // [N]
+    int64_t o_centroids = 0, o_codebooks = 0, o_lbegin = 0, o_ecodes = 0, o_eterm = 0, o_ebegin = 0, o_ids = 0, total = 0;
+    char *dev_base = nullptr;           // caller-owned buffer holding the image
+};
+
 struct Options {
     int64_t ws_cap_bytes = (int64_t)8 << 30;
     int64_t force_fallback = 0;
@@ -99,6 +117,8 @@ struct Options {
     int64_t traversal = 2;  // 0: distance context in registers, 1: level-synchronous kernels, 2: searches with all tables in LDS
     int64_t lds_blocks = 0; // workgroups per sub-tile of queries in the LDS-resident search kernel (0: chosen by the library)
     int64_t metric = 0;     // 0: squared Euclidean distance (smallest first), 1: scalar product (largest first)
+    int64_t lds_filter = 0; // main pass of the LDS-resident search: 0 float32 sums, 1 fixed-point candidate filter
+    int64_t encode_kernel = 0; // device encoder: 0 distance evaluations on the matrix cores, near-ties by the float32 rule; 1 the rule for every codeword
     int64_t lut_kernel = 0; // 0: matrix cores (expanded form on centred vectors, small entries recomputed), 1: plain (a-b)^2 sums
 };
 
@@ -123,6 +143,7 @@ struct etf_ctx {
     std::vector<float> cb_mean;             // [M][ds]
     // index
     etf::HostIndex idx;
+    etf::IvfIndex ivf;
     etf::DevLayout lay;
     char *dev_base = nullptr;               // caller-owned buffer holding the device image
     etf::Options opt;

@@ -215,20 +215,45 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
     float qq[2] = {0.f, 0.f};
-    for (int j0 = 0; j0 < dsp; j0 += 2) {
-        const int j = j0 + half;
-        float a[2], b[2];
+    // The contraction index may run over the dimensions in any order (the same for both operands): the instruction's
+    // two k-slots (lanes 0..31 and 32..63) take the lower and the upper half of every block of 16 dimensions, so a
+    // lane reads 8 consecutive floats of its rows per block (16-byte loads where the rows are aligned) and the loop
+    // has an eighth of the load round trips.
+    const int arow = IP ? ds : dsp;  // length of a row of the A operand (the centred codewords are zero padded to dsp)
+    const bool wide = (ds & 3) == 0 && (d & 3) == 0 && (arow & 3) == 0 && (reinterpret_cast<uintptr_t>(queries) & 15) == 0 &&
+                      (reinterpret_cast<uintptr_t>(IP ? cb : cbc) & 15) == 0 && (IP || (reinterpret_cast<uintptr_t>(cbmean) & 15) == 0);
+    auto load8 = [&](const float *row, bool live, int j, int len, float (&o)[8]) {
+        if (wide && live && j + 8 <= len) {
+            const float4 lo = *reinterpret_cast<const float4 *>(row + j), hi = *reinterpret_cast<const float4 *>(row + j + 4);
+            o[0] = lo.x; o[1] = lo.y; o[2] = lo.z; o[3] = lo.w;
+            o[4] = hi.x; o[5] = hi.y; o[6] = hi.z; o[7] = hi.w;
+        } else {
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) a[rb] = (clive[rb] && (!IP || j < ds)) ? crow[rb][j] : 0.f;
+            for (int i = 0; i < 8; ++i) o[i] = (live && j + i < len) ? row[j + i] : 0.f;
+        }
+    };
+    for (int j0 = 0; j0 < ds; j0 += 16) {
+        const int j = j0 + 8 * half;
+        float a[2][8], b[2][8], mu[8];
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            b[cb] = (qlive[cb] && j < ds) ? (IP ? qrow[cb][j] : qrow[cb][j] - mean[j]) : 0.f;
-            qq[cb] = fmaf(b[cb], b[cb], qq[cb]);
+        for (int rb = 0; rb < 2; ++rb) load8(crow[rb], clive[rb], j, arow, a[rb]);
+        if (!IP) load8(mean, true, j, ds, mu);
+#pragma unroll
+        for (int cb2 = 0; cb2 < 2; ++cb2) {
+            load8(qrow[cb2], qlive[cb2], j, ds, b[cb2]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (!IP) b[cb2][i] = (qlive[cb2] && j + i < ds) ? b[cb2][i] - mu[i] : 0.f;
+                qq[cb2] = fmaf(b[cb2][i], b[cb2][i], qq[cb2]);
+            }
         }
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb) acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rb], b[cb], acc[rb][cb], 0, 0, 0);
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb2 = 0; cb2 < 2; ++cb2)
+                    acc[rb][cb2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rb][i], b[cb2][i], acc[rb][cb2], 0, 0, 0);
     }
     // the two halves of the wave summed the even and the odd dimensions of the same query
 #pragma unroll
@@ -549,10 +574,16 @@ __global__ __launch_bounds__(256) void k_encode(const float *__restrict__ x, int
         for (int k = 0; k < kc; ++k) {
             const float *c = lds + k * DSP;
             float s = 0.f;
+            {
+                // every operation rounds on its own: without this the compiler contracts the product and the sum
+                // into one fused multiply-add, whose result differs in the last bit often enough to change near-ties
+#pragma clang fp contract(off)
 #pragma unroll
-            for (int j = 0; j < DSP; ++j) {
-                const float t = __fsub_rn(xv[j], c[j]);
-                s = __fadd_rn(s, __fmul_rn(t, t));
+                for (int j = 0; j < DSP; ++j) {  // plain operators: the pragma governs what is written here, not
+                    const float t = xv[j] - c[j];  // the bodies of intrinsics defined elsewhere
+                    const float p = t * t;
+                    s = s + p;
+                }
             }
             if (s < bestd) {
                 bestd = s;
@@ -561,6 +592,186 @@ __global__ __launch_bounds__(256) void k_encode(const float *__restrict__ x, int
         }
     }
     if (i < n) codes[i * M + m] = (uint8_t)best;
+}
+
+// ------------------------------------------------------------------------------------------------
+// The same assignment with the distance evaluations on the matrix cores (the O(dKN) term of the paper's "Efficient
+//     Encoding Tree Construction").  For every (vector, group) the 256 values  ||c||^2 - 2 x.c  come from the dense
+//     contraction x.c (v_mfma_f32_32x32x2_f32, operands as in k_lut_mfma: A = codewords, B = vectors); they differ
+//     from the float32 rule's squared distances (minus ||x||^2) by at most E = 8 (ds + 2) 2^-24 (||x||^2 + max ||c||^2),
+//     a generous bound on the rounding of either form.  If the smallest value is more than 2 E below the second
+//     smallest, its codeword is the float32 rule's winner as well; otherwise (a near-tie: a few vectors in a
+//     thousand) the wave evaluates the rule itself for all K codewords of that vector, four per lane, and takes the
+//     smallest (distance, index).  The codes are those of k_encode, bit for bit.
+//     A wave owns 64 vectors and walks the codewords 64 at a time (2 x 2 accumulator blocks); per value it keeps the
+//     two smallest and the index of the smallest.
+//     grid (ceil(n / 256), M), block 256, K <= 256.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_encode_mfma(const float *__restrict__ x, int64_t n, int d, int ds, int K, int M,
+                                                     const float *__restrict__ cb, uint8_t *__restrict__ codes)
+{
+    __shared__ float s_cc[256];
+    __shared__ float s_ccmax;
+    const int m = blockIdx.y;
+    const int lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6);
+    const int col = lane & 31, half = lane >> 5;
+    const float *cbm = cb + (int64_t)m * K * ds;
+    // squared norms of the group's codewords (plain float32 sums: covered by E)
+    {
+        float cc = 0.f;
+        if ((int)threadIdx.x < K)
+            for (int j = 0; j < ds; ++j) cc = fmaf(cbm[(int64_t)threadIdx.x * ds + j], cbm[(int64_t)threadIdx.x * ds + j], cc);
+        s_cc[threadIdx.x] = (int)threadIdx.x < K ? cc : 3.0e38f;
+        float mx = (int)threadIdx.x < K ? cc : 0.f;
+#pragma unroll
+        for (int dlt = 32; dlt > 0; dlt >>= 1) mx = fmaxf(mx, __shfl_xor(mx, dlt));
+        __syncthreads();
+        if (threadIdx.x == 0) s_ccmax = 0.f;
+        __syncthreads();
+        if (lane == 0) atomicMax(reinterpret_cast<int *>(&s_ccmax), __float_as_int(mx));  // non-negative floats order like ints
+        __syncthreads();
+    }
+    const int64_t v0 = (int64_t)blockIdx.x * 256 + w * 64;
+    if (v0 >= n) return;
+    // B operand: the two vectors this lane feeds (columns col and col + 32 of the wave's 64)
+    const float *xrow[2];
+    bool xlive[2];
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2) {
+        const int64_t v = v0 + c2 * 32 + col;
+        xlive[c2] = v < n;
+        xrow[c2] = x + (xlive[c2] ? v : 0) * d + (int64_t)m * ds;
+    }
+    float v1[2] = {3.0e38f, 3.0e38f}, v2[2] = {3.0e38f, 3.0e38f}, xx[2] = {0.f, 0.f};
+    int k1[2] = {0, 0};
+    // The contraction index may run over the dimensions in any order, as long as it is the same for both operands:
+    // the instruction's two k-slots (lanes 0..31 and 32..63) take the lower and the upper half of every block of 16
+    // dimensions, so that a lane reads 8 consecutive floats of its row per block (two 16-byte loads where the rows
+    // are aligned) instead of one float per instruction.
+    const bool wide = (ds & 3) == 0 && (d & 3) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0 && (reinterpret_cast<uintptr_t>(cb) & 15) == 0;
+    auto load8 = [&](const float *row, bool live, int j, float (&o)[8]) {
+        if (wide && live && j + 8 <= ds) {
+            const float4 lo = *reinterpret_cast<const float4 *>(row + j), hi = *reinterpret_cast<const float4 *>(row + j + 4);
+            o[0] = lo.x; o[1] = lo.y; o[2] = lo.z; o[3] = lo.w;
+            o[4] = hi.x; o[5] = hi.y; o[6] = hi.z; o[7] = hi.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] = (live && j + i < ds) ? row[j + i] : 0.f;
+        }
+    };
+    for (int p0 = 0; p0 < K; p0 += 64) {
+        const float *crow[2];
+        bool clive[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const int k = p0 + rb * 32 + col;
+            clive[rb] = k < K;
+            crow[rb] = cbm + (int64_t)(clive[rb] ? k : 0) * ds;
+        }
+        floatx16 acc[2][2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[rb][c2][r] = 0.f;
+        for (int j0 = 0; j0 < ds; j0 += 16) {
+            const int j = j0 + 8 * half;
+            float a[2][8], b[2][8];
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) load8(crow[rb], clive[rb], j, a[rb]);
+#pragma unroll
+            for (int c2 = 0; c2 < 2; ++c2) {
+                load8(xrow[c2], xlive[c2], j, b[c2]);
+                if (p0 == 0) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) xx[c2] = fmaf(b[c2][i], b[c2][i], xx[c2]);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                    for (int c2 = 0; c2 < 2; ++c2)
+                        acc[rb][c2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rb][i], b[c2][i], acc[rb][c2], 0, 0, 0);
+        }
+        // accumulator register r of lane l: codeword p0 + 32 rb + 8 (r / 4) + 4 (l / 32) + r % 4, vector l % 32 (+ 32 c2)
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int k = p0 + rb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+                const float cc = s_cc[k];  // 3e38 beyond K: never the smallest
+#pragma unroll
+                for (int c2 = 0; c2 < 2; ++c2) {
+                    const float val = fmaf(-2.f, acc[rb][c2][r], cc);
+                    k1[c2] = val < v1[c2] ? k : k1[c2];
+                    v2[c2] = __builtin_amdgcn_fmed3f(val, v1[c2], v2[c2]);  // v1 <= v2: the median is the new second smallest
+                    v1[c2] = fminf(val, v1[c2]);
+                }
+            }
+    }
+    // the two halves of the wave saw the even and the odd rows of the same columns
+    const float ccmax = s_ccmax;
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2) {
+        const float o1 = __shfl_xor(v1[c2], 32), o2 = __shfl_xor(v2[c2], 32);
+        const int ok = __shfl_xor(k1[c2], 32);
+        xx[c2] += __shfl_xor(xx[c2], 32);
+        const float hi = fmaxf(v1[c2], o1);
+        if (o1 < v1[c2] || (o1 == v1[c2] && ok < k1[c2])) k1[c2] = ok;
+        v1[c2] = fminf(v1[c2], o1);
+        v2[c2] = fminf(hi, fminf(v2[c2], o2));
+    }
+    // lanes 0..31 decide columns col and col + 32
+    const float eps = 8.f * (float)(ds + 2) * 5.9604645e-8f;
+    bool hard[2];
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2) {
+        const float E = eps * (xx[c2] + ccmax);
+        hard[c2] = xlive[c2] && !(v2[c2] - v1[c2] > 2.f * E);
+        if (half == 0 && xlive[c2] && !hard[c2]) codes[(v0 + c2 * 32 + col) * M + m] = (uint8_t)k1[c2];
+    }
+    // near-ties: the float32 rule itself for every codeword, the wave's lanes taking codewords lane, lane + 64, ...
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2) {
+        uint64_t todo = __ballot(hard[c2] && half == 0);
+        while (todo != 0ull) {
+            const int src = __ffsll((unsigned long long)todo) - 1;
+            todo &= todo - 1;
+            const int64_t v = v0 + c2 * 32 + src;
+            const float *xv = x + v * d + (int64_t)m * ds;
+            float bestd = 3.402823466e+38f;
+            int best = 0x7FFFFFFF;
+            for (int k = lane; k < K; k += 64) {
+                const float *c = cbm + (int64_t)k * ds;
+                float sacc = 0.f;
+                {
+#pragma clang fp contract(off)
+                    for (int j = 0; j < ds; ++j) {
+                        const float t = xv[j] - c[j];
+                        const float pr = t * t;
+                        sacc = sacc + pr;
+                    }
+                }
+                if (sacc < bestd) {  // ascending k inside a lane: the first minimum stays
+                    bestd = sacc;
+                    best = k;
+                }
+            }
+#pragma unroll
+            for (int dlt = 32; dlt > 0; dlt >>= 1) {
+                const float od = __shfl_xor(bestd, dlt);
+                const int ob = __shfl_xor(best, dlt);
+                if (od < bestd || (od == bestd && ob < best)) {
+                    bestd = od;
+                    best = ob;
+                }
+            }
+            if (lane == 0) codes[v * M + m] = (uint8_t)best;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -729,6 +940,49 @@ __device__ __forceinline__ vecq lds_item_sum(Look look, bool fast, vecq &top)
     return d;
 }
 
+// The same sum on fixed-point entries (see k_lds, FX): integer addition is associative, so the order in which a lane
+// reads the chunks does not matter and three entries go into one add.  CTX: `top` is the sum of chunks 0 and 1.
+typedef uint32_t vecu4 __attribute__((ext_vector_type(LDS_V)));
+template <int M4, int CPL, bool CTX, class Look>
+__device__ __forceinline__ vecu4 lds_item_sum_fx(Look look, bool fast, vecu4 &top)
+{
+    constexpr int NG = 4 * M4 / CPL;
+    vecu4 d;
+    if (CTX) {
+        if (!fast) top = look(0, 0) + look(0, 1);
+        d = top;
+    } else {
+        d = look(0, 0) + look(0, 1);
+    }
+#pragma unroll
+    for (int t = 2; t < CPL; t += 2) d = d + look(0, t) + look(0, t + 1);
+#pragma unroll
+    for (int g = 1; g < NG; ++g)
+#pragma unroll
+        for (int t = 0; t < CPL; t += 2) d = d + look(g, t) + look(g, t + 1);
+    return d;
+}
+
+// Fixed-point form of a table entry for the candidate filter of k_lds: entries are scaled so that the query's bound
+// becomes FX_TOP and cut off at FX_CAP (an entry beyond twice the bound cannot belong to a candidate); M <= 16
+// capped entries add up to less than 2^32.
+constexpr float FX_TOP = 134217728.f;        // 2^27
+constexpr uint32_t FX_CAP = (1u << 28) - 1u;
+__device__ __forceinline__ float fx_scale(float tau) { return FX_TOP / fmaxf(tau, 8.0779e-28f /* 2^-90 */); }
+__device__ __forceinline__ uint32_t fx_entry(float e, float scale, bool dead)
+{
+    const uint32_t v = (uint32_t)fminf(e * scale, (float)FX_CAP);  // truncates; the float cap rounds to 2^28
+    return dead ? FX_CAP : min(v, FX_CAP);
+}
+// Largest sum the filter lets through.  An item whose float32 distance d (any order of additions) is at or below
+// tau has a real sum of entries of at most d (1 + M 2^-24); every fixed-point entry is at most its real product with
+// the scale times (1 + 2^-24).  (1 + 2^-19) covers both for M <= 16, and the + 2 the rounding of this product.
+__device__ __forceinline__ uint32_t fx_bound(float tau, float scale)
+{
+    if (!(tau >= 0.f)) return 0u;  // a dead query column: every entry is FX_CAP there, nothing passes
+    return (uint32_t)fminf(tau * scale * (1.f + 1.9073486e-6f), 4.0e9f) + 2u;
+}
+
 // chunks per LDS line of the LDS-resident kernels: a line is at least 256 bytes (all banks)
 __host__ __device__ constexpr int lds_chunks_per_line(int G) { return G == 8 ? 8 : 4; }
 
@@ -736,17 +990,37 @@ __host__ __device__ constexpr int lds_chunks_per_line(int G) { return G == 8 ? 8
 // by side, [M/CPL][KP][CPL][Qs].  With rows of 64 (32) bytes and CPL = 4 (8) a line is 256 bytes = all LDS
 // banks, so the row of chunk m always sits in the same bank quarter (eighth) m % CPL, whatever the codeword.
 // KP >= K is the number of lines reserved per group.
-template <int G>
-__device__ __forceinline__ void stage_lines(float *lds, const float *__restrict__ lutT, int tile, int g, int M, int K, int KP)
+// FX: the entries are stored in fixed point (fx_entry) with the scale of their query, tau = the bounds of the tile.
+template <int G, bool FX = false>
+__device__ __forceinline__ void stage_lines(float *lds, const float *__restrict__ lutT, int tile, int g, int M, int K, int KP,
+                                            const float *__restrict__ tau = nullptr)
 {
     // 16 bytes per load and store, eight loads in flight per thread before the first store: a workgroup of 1024
     // threads moves the 128 KB of a sub-tile in one trip
     constexpr int Qs = WAVE / G, CPL = lds_chunks_per_line(G), P4 = Qs / 4, UN = 8;
     const int total = M * K * P4;  // 16-byte pieces: row (m, k) has P4 of them
     const float *src = lutT + (int64_t)tile * M * K * QT + g * Qs;
-    auto put = [&](int idx, const float4 &v) {
+    // a thread always handles the same piece p of a row (the block size and the trip are multiples of P4): the four
+    // queries whose scales it needs
+    float sc[4] = {0.f, 0.f, 0.f, 0.f};
+    bool dead[4] = {false, false, false, false};
+    if (FX) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const float t = tau[(int64_t)tile * QT + g * Qs + ((int)threadIdx.x % P4) * 4 + v];
+            dead[v] = !(t >= 0.f);
+            sc[v] = fx_scale(t);
+        }
+    }
+    auto put = [&](int idx, float4 v) {
         const int row = idx / P4, p = idx % P4;  // row = m * K + k
         const int m = K == 256 ? row >> 8 : row / K, k = row - m * K;
+        if (FX) {
+            v.x = __uint_as_float(fx_entry(v.x, sc[0], dead[0]));
+            v.y = __uint_as_float(fx_entry(v.y, sc[1], dead[1]));
+            v.z = __uint_as_float(fx_entry(v.z, sc[2], dead[2]));
+            v.w = __uint_as_float(fx_entry(v.w, sc[3], dead[3]));
+        }
         *reinterpret_cast<float4 *>(lds + (((m / CPL) * KP + k) * CPL + (m % CPL)) * Qs + p * 4) = v;
     };
     const int trip = (int)blockDim.x * UN;
@@ -778,7 +1052,7 @@ __host__ __device__ inline size_t lds_aux_bytes(bool filter) { return filter ? (
 
 typedef __attribute__((address_space(3))) const vecq lds_vecq_t;
 
-template <int G, int M4, int T, int MODE, bool CTX>
+template <int G, int M4, int T, int MODE, bool CTX, bool FX = false>
 __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, int64_t nitems,
                                               const uint32_t *__restrict__ map, const float *__restrict__ lutT, int K,
                                               int per_block, OutArgs o)
@@ -804,8 +1078,9 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     const int tile = blockIdx.z, sub = blockIdx.y;
     const int lane = threadIdx.x & 63;
     const int w = uniform(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    static_assert(!FX || MODE == OUT_FILTER, "the fixed-point form is a candidate filter");
     if (FILTER) wcount[w][lane] = 0u;
-    stage_lines<G>(lds, lutT, tile, sub, M, K, KP);
+    stage_lines<G, FX>(lds, lutT, tile, sub, M, K, KP, FX ? o.tau : nullptr);
     const int lg = lane / LPI, lq = lane % LPI;
     const int col = sub * Qs + lq * V;  // first of this lane's queries inside the tile
     // Which chunk of a group this lane reads t-th: t ^ j with j = the lane group's number mod CPL.  The CPL lane
@@ -832,6 +1107,23 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     }
     // CPL = 8: the two record dwords of a group; a lane whose rotation exchanges the halves reads them crosswise
     const bool cross = CPL == 8 && (jr & 4) != 0;
+    typedef __attribute__((address_space(3))) const vecu4 lds_vecu4_t;
+    // LDS address of the t-th entry a lane reads of group g of an item
+    auto addr_of = [&](const uint32_t dw[M4], int g, int t) -> uint32_t {
+        uint32_t src;
+        if (CPL == 4) {
+            src = dw[g];
+        } else {
+            const bool second = (CTX && g == 0) ? t >= 4 : ((t >= 4) != cross);
+            src = second ? dw[2 * g + 1] : dw[2 * g];
+        }
+        if (PERM) return __builtin_amdgcn_perm(src, pb[g][t], sh[g == 0 ? 0 : 1][t]);
+        return pb[g][t] + __builtin_amdgcn_ubfe(src, sh[g == 0 ? 0 : 1][t], 8) * lineB;
+    };
+    auto sum_of_fx = [&](const uint32_t dw[M4], bool fast, vecu4 &top) -> vecu4 {
+        auto look = [&](int g, int t) -> vecu4 { return *reinterpret_cast<lds_vecu4_t *>(addr_of(dw, g, t)); };
+        return lds_item_sum_fx<M4, CPL, CTX>(look, CTX && fast, top);
+    };
     auto sum_of = [&](const uint32_t dw[M4], bool fast, vecq &top) -> vecq {
         auto look = [&](int g, int t) -> vecq {
             uint32_t src;
@@ -942,10 +1234,19 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
 
     const int64_t blo = (int64_t)blockIdx.x * per_block;
     const int64_t bhi = min(nitems, blo + per_block);
+    // the bound of each of this lane's queries: as a float, or (FX) as the largest fixed-point sum that may pass
     float tau[V];
+    uint32_t itau[V];
 #pragma unroll
-    for (int v = 0; v < V; ++v) tau[v] = o.tau[(int64_t)tile * QT + col + v];
+    for (int v = 0; v < V; ++v) {
+        tau[v] = o.tau[(int64_t)tile * QT + col + v];
+        itau[v] = FX ? fx_bound(tau[v], fx_scale(tau[v])) : 0u;
+    }
     int held = 0;
+    // The ring holds (value bits << 32 | query of the tile << 26 | item relative to blo), wcount the entries per
+    // query.  When the ring is nearly full the whole wave appends it to the queries' lists: one global reservation
+    // per query (64 lanes, 64 queries), then LDS atomics hand out the slots.  (One global atomic per entry, all
+    // workgroups of a sub-tile hitting the same 16 counters, cost 0.7 ms on the benchmark's 2.3 ms.)
     auto flush = [&]() {
         const uint32_t c = wcount[w][lane];
         wpos[w][lane] = c ? atomicAdd(&o.cnt[(int64_t)tile * QT + lane], c) : 0u;
@@ -962,12 +1263,12 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
         __builtin_amdgcn_wave_barrier();
         held = 0;
     };
-    auto emit = [&](bool pass, float d, int c, uint32_t rel) {
+    auto emit = [&](bool pass, uint32_t bits, int c, uint32_t rel) {
         const uint64_t mask = __ballot(pass);
         if (mask != 0ull) {
             const int rank = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
             if (pass) {
-                ring[w][held + rank] = ((uint64_t)__float_as_uint(d) << 32) | ((uint32_t)c << 26) | rel;
+                ring[w][held + rank] = ((uint64_t)bits << 32) | ((uint32_t)c << 26) | rel;
                 atomicAdd(&wcount[w][c], 1u);
             }
             held += __popcll(mask);
@@ -998,6 +1299,7 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     const uint32_t voff = len > 0 ? first * (M4 * 4) : 0u;
     uint32_t prev0 = 0u;
     vecq top = 0.f;
+    vecu4 itop = 0u;
     // U steps from step i on; CHECK: some lane groups may be past the end of their run
     auto steps = [&](int i, auto check) {
         constexpr bool CHECK = decltype(check)::value;
@@ -1013,21 +1315,33 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
 #pragma unroll
             for (int k2 = 0; k2 < M4; ++k2) dw[u][k2] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rr, (int)vo + 4 * k2, so, 0);
         }
+        // which steps may keep the context: a lane group may if its item has the S-chunk prefix of its previous one
+        bool fastv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            fastv[u] = false;
+            if (S > 0) {
+                const uint32_t smask = S == 1 ? 0xFFu : 0xFFFFu;
+                const bool live = !CHECK || i + u < len;
+                const bool differs = live && ((dw[u][0] ^ prev0) & smask) != 0u;
+                fastv[u] = __ballot(differs) == 0ull && i + u != 0;
+                prev0 = dw[u][0];
+            }
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const bool live = !CHECK || i + u < len;
-            bool fast = false;
-            if (S > 0) {
-                // a lane group may keep its context if its item has the S-chunk prefix of its previous one
-                const uint32_t smask = S == 1 ? 0xFFu : 0xFFFFu;
-                const bool differs = live && ((dw[u][0] ^ prev0) & smask) != 0u;
-                fast = __ballot(differs) == 0ull && i + u != 0;
-                prev0 = dw[u][0];
-            }
-            const vecq d = sum_of(dw[u], fast, top);
+            const bool fast = fastv[u];
             const uint32_t rel = first + (uint32_t)(i + u) * RF;
+            if (FX) {
+                const vecu4 d = sum_of_fx(dw[u], fast, itop);
 #pragma unroll
-            for (int v = 0; v < V; ++v) emit(live && d[v] <= tau[v], d[v], col + v, rel);
+                for (int v = 0; v < V; ++v) emit(live && d[v] <= itau[v], d[v], col + v, rel);
+            } else {
+                const vecq d = sum_of(dw[u], fast, top);
+#pragma unroll
+                for (int v = 0; v < V; ++v) emit(live && d[v] <= tau[v], __float_as_uint(d[v]), col + v, rel);
+            }
         }
     };
     int i = 0;
@@ -1364,7 +1678,62 @@ struct SelectArgs {
     float *out_dist;         // [nq][k]
     uint32_t *flag;          // [nq]  set to 1 when the query needs the exact kernel
     const float *boff;       // [nq] or nullptr: results are written as boff[q] - value (scalar-product searches)
+    // Candidates from the fixed-point filter (k_lds, FX): the upper word of a candidate is a fixed-point sum, which
+    // orders like the float32 distance up to fx_margin units.  Everything up to the k-th smallest plus that margin
+    // is kept, and the kept items' distances are recomputed in float32 from the tables, associated like the exact
+    // kernel does (assoc_distance), before the final ordering: what is returned is a float32 sum of table entries.
+    int allow_short;         // 1: a query with fewer than k vectors among its candidates is complete (they are all
+                             // there are): its row is filled up with id -1 and +inf; 0: such a query goes to the exact kernel
+    uint32_t fx_margin;      // 0: the upper word is the float32 distance itself
+    const float *lutT;       // [tiles][M][K][64] tables of this batch
+    const uint8_t *codes;    // [items][M]
+    int M, K, T, grouped;
+    int32_t chunk_begin[ETF_MAX_M + 1];
 };
+
+// Sum of the table entries of one encoding c[0..M), associated as the main path of the mode does: `grouped` 4 or 8:
+// like the LDS-resident kernels (chunks in groups as balanced trees, see lds_item_sum), 0: left to right inside a
+// tree, trees in order.  lut(m, code) returns the entry.  A: anything with M, K, T, grouped, chunk_begin.
+template <class A, class Lut>
+__device__ __forceinline__ float assoc_distance(const A &a, Lut lut, const uint8_t *c)
+{
+    if (a.grouped == 4) {
+        // chunks in groups of four as (c0 + c1) + (c2 + c3), a tree the sum of its groups in order (trees are equal
+        // there; shorter ones live inside one group)
+        const int M4 = a.M >> 2, D = a.M / a.T, gpt = D >= 4 ? D >> 2 : 1;
+        float d = 0.f;
+        for (int t0 = 0; t0 < M4; t0 += gpt) {
+            float s = 0.f;
+            for (int i = 0; i < gpt; ++i) {
+                const int m = 4 * (t0 + i);
+                const float P = (lut(m, c[m]) + lut(m + 1, c[m + 1])) + (lut(m + 2, c[m + 2]) + lut(m + 3, c[m + 3]));
+                s = i == 0 ? P : s + P;
+            }
+            d = t0 == 0 ? s : d + s;
+        }
+        return d;
+    }
+    if (a.grouped == 8) {
+        // groups of eight as a balanced tree, the groups added in order
+        float d = 0.f;
+        for (int m = 0; m < a.M; m += 8) {
+            const float lo = (lut(m, c[m]) + lut(m + 1, c[m + 1])) + (lut(m + 2, c[m + 2]) + lut(m + 3, c[m + 3]));
+            const float hi = (lut(m + 4, c[m + 4]) + lut(m + 5, c[m + 5])) + (lut(m + 6, c[m + 6]) + lut(m + 7, c[m + 7]));
+            d = m == 0 ? lo + hi : d + (lo + hi);
+        }
+        return d;
+    }
+    float d = 0.f;
+    for (int t = 0; t < a.T; ++t) {
+        float s = 0.f;
+        for (int m = a.chunk_begin[t]; m < a.chunk_begin[t + 1]; ++m) {
+            const float v = lut(m, c[m]);
+            s = (m == a.chunk_begin[t]) ? v : s + v;
+        }
+        d = (t == 0) ? s : d + s;
+    }
+    return d;
+}
 
 __global__ __launch_bounds__(256) void k_select(SelectArgs a)
 {
@@ -1398,7 +1767,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
         block_radix_select(
             c, rank, [&](int i, uint32_t &v) { v = (uint32_t)(cand[i] >> 32); return true; }, hist, sel_sh, vstar,
             rank_in_ties, n_ties);
-        if (rank - rank_in_ties + n_ties > (uint32_t)KEPT_CAP) {
+        if (a.fx_margin == 0 && rank - rank_in_ties + n_ties > (uint32_t)KEPT_CAP) {
             uint32_t r2, n2;
             block_radix_select(
                 c, rank_in_ties,
@@ -1414,6 +1783,8 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     // 2. keep the candidates at or below it, sorted by (distance bits, item)
     if (threadIdx.x == 0) s_c = 0;
     __syncthreads();
+    // fixed-point candidates: everything within the margin above the k-th smallest sum may be among the k closest
+    if (a.fx_margin != 0 && vstar < 0xFFFFFFFFu - a.fx_margin) vstar += a.fx_margin;
 #pragma unroll 8
     for (int i = threadIdx.x; i < c; i += 256) {
         const uint64_t key = cand[i];
@@ -1425,9 +1796,25 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     }
     __syncthreads();
     const int nk = (int)s_c;
+    if (nk == 0 && a.allow_short) {  // nothing in reach of this query
+        for (int i = threadIdx.x; i < k; i += 256) {
+            a.out_ids[ql * k + i] = -1;
+            a.out_dist[ql * k + i] = __uint_as_float(0x7F800000u);
+        }
+        return;
+    }
     if (nk > KEPT_CAP || nk == 0) {
         if (threadIdx.x == 0) a.flag[ql] = 1;
         return;
+    }
+    if (a.fx_margin != 0) {
+        // the float32 distance of every kept item, from the tables of its query
+        const float *lq = a.lutT + (int64_t)(ql / QT) * a.M * a.K * QT + (ql % QT);
+        auto lut = [&](int m, int code) -> float { return lq[((int64_t)m * a.K + code) * QT]; };
+        for (int i = threadIdx.x; i < nk; i += 256) {
+            const uint32_t e = (uint32_t)kept[i];
+            kept[i] = ((uint64_t)__float_as_uint(assoc_distance(a, lut, a.codes + (int64_t)e * a.M)) << 32) | e;
+        }
     }
     const int nk2 = pow2_at_least(nk);
     for (int i = nk + threadIdx.x; i < nk2; i += 256) kept[i] = ~0ull;
@@ -1441,7 +1828,29 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     }
     __syncthreads();
     block_inclusive_scan(sc, nk, tmp);
-    if (sc[nk - 1] < (uint32_t)k) {  // the bound was not valid: cannot happen with a sample of the database
+    if (sc[nk - 1] < (uint32_t)k) {
+        if (a.allow_short && nk <= (int)a.C && c == nk) {
+            // every candidate was kept and together they hold fewer than k vectors: all of them, in order, then padding
+            const uint32_t total = sc[nk - 1];
+            __syncthreads();
+            for (int i = threadIdx.x; i < nk; i += 256) {
+                const uint32_t end = sc[i], beg = i > 0 ? sc[i - 1] : 0;
+                const uint32_t e = (uint32_t)kept[i];
+                const uint64_t hi = kept[i] & 0xFFFFFFFF00000000ull;
+                for (uint32_t j = 0; j < end - beg; ++j) xkeys[beg + j] = hi | (uint32_t)a.ids[a.ebegin ? a.ebegin[e] + j : e];
+            }
+            const int nx2s = pow2_at_least((int)total);
+            for (int i = (int)total + threadIdx.x; i < nx2s; i += 256) xkeys[i] = ~0ull;
+            __syncthreads();
+            bitonic_sort_u64(xkeys, nx2s);
+            for (int i = threadIdx.x; i < k; i += 256) {
+                const bool have = i < (int)total;
+                a.out_ids[ql * k + i] = have ? (int32_t)(uint32_t)xkeys[i] : -1;
+                a.out_dist[ql * k + i] = have ? __uint_as_float((uint32_t)(xkeys[i] >> 32)) : __uint_as_float(0x7F800000u);
+            }
+            return;
+        }
+        // the bound was not valid: cannot happen with a sample of the database
         if (threadIdx.x == 0) a.flag[ql] = 1;
         return;
     }
@@ -1518,45 +1927,7 @@ struct ExactArgs {
 
 __device__ __forceinline__ float exact_distance(const ExactArgs &a, const float *lut, const uint8_t *c)
 {
-    if (a.grouped == 4) {
-        // the association of the LDS-resident kernels: chunks in groups of four as (c0 + c1) + (c2 + c3), a
-        // tree the sum of its groups in order (trees are equal there; shorter ones live inside one group)
-        const int M4 = a.M >> 2, D = a.M / a.T, gpt = D >= 4 ? D >> 2 : 1;
-        float d = 0.f;
-        for (int t0 = 0; t0 < M4; t0 += gpt) {
-            float s = 0.f;
-            for (int i = 0; i < gpt; ++i) {
-                const int m = 4 * (t0 + i);
-                const float P = (lut[m * a.K + c[m]] + lut[(m + 1) * a.K + c[m + 1]]) +
-                                (lut[(m + 2) * a.K + c[m + 2]] + lut[(m + 3) * a.K + c[m + 3]]);
-                s = i == 0 ? P : s + P;
-            }
-            d = t0 == 0 ? s : d + s;
-        }
-        return d;
-    }
-    if (a.grouped == 8) {
-        // groups of eight as a balanced tree, the groups added in order
-        float d = 0.f;
-        for (int m = 0; m < a.M; m += 8) {
-            const float lo = (lut[m * a.K + c[m]] + lut[(m + 1) * a.K + c[m + 1]]) +
-                             (lut[(m + 2) * a.K + c[m + 2]] + lut[(m + 3) * a.K + c[m + 3]]);
-            const float hi = (lut[(m + 4) * a.K + c[m + 4]] + lut[(m + 5) * a.K + c[m + 5]]) +
-                             (lut[(m + 6) * a.K + c[m + 6]] + lut[(m + 7) * a.K + c[m + 7]]);
-            d = m == 0 ? lo + hi : d + (lo + hi);
-        }
-        return d;
-    }
-    float d = 0.f;
-    for (int t = 0; t < a.T; ++t) {
-        float s = 0.f;
-        for (int m = a.chunk_begin[t]; m < a.chunk_begin[t + 1]; ++m) {
-            const float v = lut[m * a.K + c[m]];
-            s = (m == a.chunk_begin[t]) ? v : s + v;
-        }
-        d = (t == 0) ? s : d + s;
-    }
-    return d;
+    return assoc_distance(a, [&](int m, int code) -> float { return lut[m * a.K + code]; }, c);
 }
 
 __global__ __launch_bounds__(256) void k_exact(ExactArgs a)
@@ -1669,7 +2040,7 @@ __global__ __launch_bounds__(256) void k_probe_write(u32x4 *__restrict__ a, int6
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const u32x4 v = {1u, 2u, 3u, 4u};
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) __builtin_nontemporal_store(v, a + i);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) a[i] = v;
 }
 
 __global__ __launch_bounds__(256) void k_probe_copy(const u32x4 *__restrict__ a, u32x4 *__restrict__ b, int64_t n16)
@@ -1692,17 +2063,62 @@ __global__ __launch_bounds__(256) void k_probe_rows(const float *__restrict__ a,
     const int lane = threadIdx.x & 63;
     const int64_t wv = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), nwv = (int64_t)gridDim.x * 4;
     float acc = 0.f;
-    for (int64_t i0 = wv * 8; i0 < nrows; i0 += nwv * 8) {  // eight rows in flight per wave
+    // row of step i is (i * mult) mod nrows, advanced by additions: mult < nrows, so one subtraction brings a sum back
+    const uint64_t n = (uint64_t)nrows, hop = ((uint64_t)nwv * 8 % n) * mult % n;
+    uint64_t r0 = (uint64_t)(wv * 8 % nrows) * mult % n;
+    for (int64_t i0 = wv * 8; i0 + 8 <= nrows; i0 += nwv * 8) {  // eight rows in flight per wave
         float v[8];
+        uint64_t r = r0;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const uint64_t r = ((uint64_t)min(i0 + u, nrows - 1) * mult) % (uint64_t)nrows;
             v[u] = a[r * 64 + lane];
+            r += mult;
+            r = r >= n ? r - n : r;
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc += v[u];
+        r0 += hop;
+        r0 = r0 >= n ? r0 - n : r0;
     }
     if (acc == 1.2345e-30f || threadIdx.x == 0) out[blockIdx.x] = __float_as_uint(acc);
+}
+
+// LDS read rate of the chip: every lane of a workgroup of 1024 threads reads 16 bytes per instruction, `iters`
+// instructions per wave, eight in flight; the data is folded into one word per workgroup so that the reads stay.
+// Plain: lane l of a wave reads piece l of a 1 KiB row (conflict-free: every quarter wave covers all 64 banks).
+// SCATTER: the four lanes of a group read the four pieces of one 64-byte row and the sixteen groups of a wave read
+// rows picked by a hash: the access pattern of the table lookups, bank conflicts as they fall.
+template <bool SCATTER>
+__global__ __launch_bounds__(1024) void k_probe_lds(int iters, uint32_t *__restrict__ out)
+{
+    extern __shared__ u32x4 probe_lds[];  // 128 KiB
+    constexpr int PIECES = 128 * 1024 / 16;
+    for (int i = threadIdx.x; i < PIECES; i += 1024) probe_lds[i] = u32x4{(uint32_t)i, 1u, 2u, 3u};
+    __syncthreads();
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t h = (uint32_t)(lane >> 2) * 0x9E3779B9u + (uint32_t)w * 0x85EBCA6Bu + blockIdx.x;
+    uint32_t last = 0u;
+    for (int it = 0; it < iters; it += 8) {
+        u32x4 v[8];
+        const int row0 = (it + w) & 63;  // rows row0, row0 + 8, ..., row0 + 56 of the 128: a different set every time
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            int piece;
+            if (SCATTER) {
+                h += 0x9E3779B9u;  // a Weyl sequence: cheap enough that the vector unit stays behind the LDS pipe
+                piece = (int)(((h >> 15) & (PIECES / 4 - 1)) << 2 | (uint32_t)(lane & 3));
+            } else {
+                piece = (row0 + u * 8) * 64 + lane;
+            }
+            v[u] = probe_lds[piece];
+        }
+        // the loaded registers are used by an empty statement: no arithmetic competes with the reads, and the
+        // compiler can neither drop nor narrow them
+#pragma unroll
+        for (int u = 0; u < 8; ++u) asm volatile("" ::"v"(v[u]));
+        last = v[7].x;
+    }
+    if (last == 0x9E3779B9u || threadIdx.x == 0) out[blockIdx.x] = last;
 }
 
 }  // namespace etf

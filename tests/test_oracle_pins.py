@@ -304,3 +304,29 @@ def test_scalar_product_tables_against_decoded_vectors_and_distance_tables():
     for j in range(len(qs)):
         order = np.lexsort((ids, -ip[j]))[:25]
         assert np.array_equal(oi[j], ids[order]) and np.array_equal(ov[j], ip[j][order])
+
+
+def test_encode_f32_near_ties_tell_fused_from_unfused():
+    """The near-tie inputs of the device encoder's test have the power they are used for: an assignment that forms
+    t*t + s with a single rounding (a fused multiply-add, emulated here in float64 where the product is exact) differs
+    from encode_f32 (one rounding per operation) on many of them, while on ordinary data the two agree."""
+    from workload import near_tie_vectors
+    rng = np.random.default_rng(8)
+    M, K, ds = 4, 32, 16
+    cb = rng.normal(size=(M, K, ds)).astype(np.float32) * 2
+    def fused_assign(x):
+        codes = np.zeros((len(x), M), dtype=np.uint8)
+        for m in range(M):
+            xs = x[:, m * ds:(m + 1) * ds]
+            acc = np.zeros((len(x), K), dtype=np.float32)
+            for j in range(ds):
+                t = (xs[:, j, None] - cb[m][None, :, j]).astype(np.float32)
+                acc = (t.astype(np.float64) * t.astype(np.float64) + acc.astype(np.float64)).astype(np.float32)
+            codes[:, m] = np.argmin(acc, axis=1)
+        return codes
+    ties = near_tie_vectors(cb, 4000, seed=1)
+    ref = oracle.encode_f32(ties, cb)
+    differ = int((fused_assign(ties) != ref).sum())
+    assert differ > 50, differ
+    plain = rng.normal(size=(4000, M * ds)).astype(np.float32) * 2
+    assert int((fused_assign(plain) != oracle.encode_f32(plain, cb)).sum()) <= 2

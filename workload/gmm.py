@@ -127,3 +127,18 @@ class GaussianMixture:
         if n == 0:
             return np.zeros((0, self.d), dtype=np.float32)
         return np.concatenate(list(self.chunks(n, stream_seed)), axis=0)
+
+
+def near_tie_vectors(codebooks: np.ndarray, n: int, seed: int, spread: float = 3e-7) -> np.ndarray:
+    """n vectors [n][d] that sit almost exactly half way between two codewords of every dimension group (a relative
+    offset of a few units in the last place of a float32): inputs on which a nearest-codeword decision depends on how
+    each operation of the squared distance is rounded.  Draws only; no distance is evaluated here."""
+    cb = np.asarray(codebooks, dtype=np.float64)
+    M, K, ds = cb.shape
+    rng = np.random.Generator(np.random.PCG64([int(seed), 11]))
+    a = rng.integers(0, K, size=(n, M))
+    b = (a + 1 + rng.integers(0, max(K - 1, 1), size=(n, M))) % K
+    mid = 0.5 * (cb[np.arange(M)[None, :], a] + cb[np.arange(M)[None, :], b])          # [n][M][ds]
+    scale = np.abs(cb).max()
+    x = mid + rng.uniform(-spread, spread, size=mid.shape) * scale
+    return np.ascontiguousarray(x.reshape(n, M * ds), dtype=np.float32)
