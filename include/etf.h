@@ -173,6 +173,18 @@ int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, const int32_t
                     const int32_t *chunk_begin);
 int etf_index_stats(const etf_ctx *ctx, etf_stats *out);
 
+/* Leaf payload (paper, Experiments: an additive quantiser's extra term, quantised to one byte, stored on the leaf
+ * node).  The next etf_index_build attaches the additive term term[n] (host, [N] float32, non-negative and finite) to
+ * vector n; every distance the library then reports for that vector (etf_adc, etf_search, all modes and traversals)
+ * is the sum of its table entries plus its term, the term added last.  Vectors that share an encoding but not the
+ * term are separate leaves (separate entries of the index; n_distinct counts (encoding, term) pairs), vectors that
+ * share both share one.  etf_index_set_leaf_bytes is the one-byte form: term = offset + scale * bytes[n], evaluated
+ * once in float32 with a fused multiply-add.  A NULL pointer clears a pending payload; a payload belongs to one build.
+ * etf_index_build_device does not take a payload (ETF_ESTATE while one is pending); scalar-product searches (option
+ * "metric" = 1) add the term to the shifted value they order by, i.e. they return the k largest <q, x> - term. */
+int etf_index_set_leaf_term(etf_ctx *ctx, const float *term, int64_t N);
+int etf_index_set_leaf_bytes(etf_ctx *ctx, const uint8_t *bytes, int64_t N, float scale, float offset);
+
 /* Chunk order (paper: "Encoding Chunk Ordering": which chunk sits at which level decides how many
  * prefixes are shared; and the forest's choice of which chunks form a tree).
  * etf_index_set_chunk_order: the next etf_index_build / etf_index_build_device stores, at position j of
@@ -240,6 +252,8 @@ typedef struct etf_layout {
     int64_t sample_enc_codes;      /* u8 [n_sample_enc][M]: ecodes rows of sample_enc, in sample order               */
     int64_t sample_pos_codes;      /* u8 [n_sample_pos][M]: codes rows of sample_pos, in sample order                */
     int32_t cb_row;
+    int64_t eterm;                 /* float [n_distinct]: leaf term of every entry; -1 without a leaf payload         */
+    int64_t pterm;                 /* float [N]: leaf term of every vector, input order; -1 without a leaf payload    */
 } etf_layout;
 int etf_index_layout(const etf_ctx *ctx, etf_layout *out);
 /* Writes the device image to host memory (at least etf_index_device_bytes()): the

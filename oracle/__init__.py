@@ -222,3 +222,24 @@ def search_ip(queries, codebooks, codes, k: int, ids=None) -> Tuple[np.ndarray, 
         oi[j], neg = topk(-allp[j], k, ids)
         od[j] = -neg
     return oi, od
+
+
+def adc_all_term(q, codebooks, codes, term) -> np.ndarray:
+    """Distances with a leaf payload (the paper's Experiments section stores an additive quantiser's extra term on the
+    leaf): float64 [Q][N], the flat sum of table entries of vector n plus term[n]."""
+    term = np.asarray(term, dtype=np.float64)
+    d = adc_all(q, codebooks, codes)
+    assert term.shape == (d.shape[1],)
+    return d + term[None, :]
+
+
+def search_term(q, codebooks, codes, term, k: int, ids: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """(ids [Q][k], distances float64 [Q][k]): the k smallest (distance + term, id) per query, by a full sort."""
+    d = adc_all_term(q, codebooks, codes, term)
+    idv = np.arange(d.shape[1], dtype=np.int64) if ids is None else np.asarray(ids, dtype=np.int64)
+    out_i = np.zeros((d.shape[0], k), dtype=np.int64)
+    out_d = np.zeros((d.shape[0], k), dtype=np.float64)
+    for j in range(d.shape[0]):
+        order = np.lexsort((idv, d[j]))[:k]
+        out_i[j], out_d[j] = idv[order], d[j][order]
+    return out_i, out_d

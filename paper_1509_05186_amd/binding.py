@@ -18,7 +18,7 @@ _lib = None
 EXPORTS = [
     "etf_create", "etf_destroy", "etf_set_stream", "etf_strerror", "etf_last_error", "etf_set_option",
     "etf_pq_train", "etf_pq_set_codebooks", "etf_pq_get_codebooks", "etf_pq_encode",
-    "etf_index_build", "etf_index_set_chunk_order", "etf_suggest_chunk_order", "etf_index_stats", "etf_index_device_bytes", "etf_index_upload",
+    "etf_index_build", "etf_index_set_leaf_term", "etf_index_set_leaf_bytes", "etf_index_set_chunk_order", "etf_suggest_chunk_order", "etf_index_stats", "etf_index_device_bytes", "etf_index_upload",
     "etf_index_layout", "etf_index_export",
     "etf_encode_workspace_bytes", "etf_pq_encode_device",
     "etf_index_build_device_bytes", "etf_index_build_device",
@@ -92,6 +92,7 @@ class EtfLayout(ctypes.Structure):
         ("cb_centered", ctypes.c_int64), ("cb_norm", ctypes.c_int64), ("cb_mean", ctypes.c_int64),
         ("sample_enc_codes", ctypes.c_int64), ("sample_pos_codes", ctypes.c_int64),
         ("cb_row", ctypes.c_int32),
+        ("eterm", ctypes.c_int64), ("pterm", ctypes.c_int64),
     ]
 
 
@@ -133,6 +134,8 @@ def load_library():
         "etf_pq_encode": (I, [P, P, L, P]),
         "etf_index_build": (I, [P, P, L, P, I, P]),
         "etf_index_set_chunk_order": (I, [P, P]),
+        "etf_index_set_leaf_term": (I, [P, P, L]),
+        "etf_index_set_leaf_bytes": (I, [P, P, L, ctypes.c_float, ctypes.c_float]),
         "etf_suggest_chunk_order": (I, [P, P, L, I, P, P, ctypes.POINTER(L), ctypes.POINTER(L)]),
         "etf_index_stats": (I, [P, ctypes.POINTER(EtfStats)]),
         "etf_index_device_bytes": (L, [P]),
@@ -256,6 +259,16 @@ class Context:
             raise ValueError("chunk_begin must have T+1 entries")
         self._ck(self._lib.etf_index_build(self._h, _host(codes), codes.shape[0], _host(ids_a), T, _host(cb)))
         self._N = codes.shape[0]
+
+    def index_set_leaf_term(self, term: Optional[np.ndarray]):
+        """Additive float32 term per vector for the next index_build (None clears a pending one)."""
+        t = None if term is None else np.ascontiguousarray(term, dtype=np.float32)
+        self._ck(self._lib.etf_index_set_leaf_term(self._h, _host(t), 0 if t is None else t.shape[0]))
+
+    def index_set_leaf_bytes(self, b: Optional[np.ndarray], scale: float, offset: float):
+        """One byte per vector: the next index_build attaches offset + scale * b[n]."""
+        a = None if b is None else np.ascontiguousarray(b, dtype=np.uint8)
+        self._ck(self._lib.etf_index_set_leaf_bytes(self._h, _host(a), 0 if a is None else a.shape[0], scale, offset))
 
     def index_set_chunk_order(self, order: Optional[Sequence[int]]):
         """Chunk order of the next index build (a permutation of 0..M-1; None = as given)."""

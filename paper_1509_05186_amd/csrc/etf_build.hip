@@ -576,6 +576,7 @@ extern "C" int etf_index_build_device(etf_ctx *ctx, const uint8_t *codes, int64_
     std::vector<int32_t> cb;
     rc = check_trees(ctx, T, chunk_begin, cb);
     if (rc) return rc;
+    if (!ctx->next_term.empty()) return fail(ctx, ETF_ESTATE, "a leaf payload is pending: indexes with leaf terms are built by etf_index_build");
     if (!image || !workspace) return fail(ctx, ETF_EINVAL, "image or workspace is null");
     if ((((uintptr_t)image | (uintptr_t)workspace) & 255) != 0) return fail(ctx, ETF_EINVAL, "image and workspace must be 256-byte aligned");
     HIP_TRY(ctx, hipSetDevice(ctx->device));

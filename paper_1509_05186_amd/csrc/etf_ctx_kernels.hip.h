@@ -315,9 +315,10 @@ __global__ __launch_bounds__(1024) void k_fused(const uint32_t *__restrict__ cod
     for (int s = 0; s < DT; ++s) ctx[s] = 0.f;
 
     // encoding number, tree-0 record and gather offsets of the item a lane owns in the chunk at `base`
-    auto fetch = [&](int64_t base, uint32_t dw[NDW], uint32_t goff[TMAX]) {
+    auto fetch = [&](int64_t base, uint32_t dw[NDW], uint32_t goff[TMAX], float &tm) {
         const bool live = base + lane < hi;
         const uint32_t e = live ? (MODE == OUT_FILTER ? (uint32_t)(base + lane) : map[base + lane]) : 0u;
+        tm = (o.term && live) ? o.term[e] : 0.f;  // leaf term of the item this lane owns
 #pragma unroll
         for (int i = 0; i < NDW; ++i) dw[i] = live ? codes0[(int64_t)e * NDW + i] : 0u;
 #pragma unroll
@@ -336,12 +337,13 @@ __global__ __launch_bounds__(1024) void k_fused(const uint32_t *__restrict__ cod
     };
 
     uint32_t my_dw[NDW], my_goff[TMAX], next_dw[NDW], next_goff[TMAX];
+    float my_tm = 0.f, next_tm = 0.f;
     float va[GV][NV], vb[GV][NV];  // rows of the group being evaluated / of the group after it, alternating
-    fetch(lo, my_dw, my_goff);
+    fetch(lo, my_dw, my_goff, my_tm);
     if (NG1 > 0) gather(my_goff, 0, va);
     for (int64_t base = lo; base < hi; base += 64) {
         const int cnt = uniform((int)min<int64_t>(64, hi - base));
-        fetch(base + 64, next_dw, next_goff);  // arrives while this chunk is evaluated
+        fetch(base + 64, next_dw, next_goff, next_tm);  // arrives while this chunk is evaluated
         ChunkMeta<DT> m;
         chunk_meta<DT, NDW, NL, UBT>(m, my_dw, codes0, base, lo, lane, cnt, pad, K, MODE == OUT_FILTER);
         // one group: evaluate its items with the rows in `cur`, and right after the first batch's lookups
@@ -366,6 +368,7 @@ __global__ __launch_bounds__(1024) void k_fused(const uint32_t *__restrict__ cod
                         for (int u = 0; u < UBT; ++u) {
 #pragma unroll
                             for (int t = 1; t < TMAX; ++t) d[u] += (TMAX == 2 || t < r.T) ? cur[b * UBT + u][t - 1] : 0.f;
+                            d[u] += __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_tm), min(s0 + u, 63)));
                         }
 #pragma unroll
                         for (int u = 0; u < UBT; ++u) {
@@ -408,6 +411,7 @@ __global__ __launch_bounds__(1024) void k_fused(const uint32_t *__restrict__ cod
         for (int i = 0; i < NDW; ++i) my_dw[i] = next_dw[i];
 #pragma unroll
         for (int t = 1; t < TMAX; ++t) my_goff[t] = next_goff[t];
+        my_tm = next_tm;
     }
     if (MODE == OUT_FILTER) flush();
     if (MODE == OUT_SAMPLE) o.gmin[((int64_t)tile * o.ngroups + wv) * QT + lane] = best;

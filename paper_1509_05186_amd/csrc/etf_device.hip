@@ -252,7 +252,7 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     P.flat_lds = mode == ETF_MODE_FLAT && ctx->opt.traversal == 2 && lds_eligible(M, K, 1, nullptr);
     // the fixed-point filter scales every table by its query's bound: it needs one (use_tau)
     // (not the flat scan: it lists every copy of an encoding, and copies tie exactly)
-    P.fx = search && P.lds_path && P.use_tau && ctx->opt.lds_filter == 1 && !ctx->opt.force_fallback;
+    P.fx = search && P.lds_path && P.use_tau && ctx->opt.lds_filter == 1 && !ctx->opt.force_fallback && !ix.has_term;
     P.ctx_path = !P.lds_path && tmax_class(ix.T) != 0 && mode != ETF_MODE_FLAT && ctx->opt.traversal != 1;
     for (int t = 1; t < ix.T; ++t)  // the register-context kernels address a tree's result table with 32-bit offsets
         if (ix.tree[t].U >= ((int64_t)1 << 24)) P.ctx_path = false;
@@ -866,6 +866,11 @@ extern "C" int etf_adc(etf_ctx *ctx, const float *queries, int64_t Q, int mode, 
         o.dist = dist + q0 * ix.N;
         o.N = ix.N;
         o.nq = std::min<int64_t>(tiles * QT, Q - q0);
+        if (ix.has_term) {
+            // the kernels that walk the input positions add the vector's term, those that walk the entries the entry's
+            const bool by_position = P.flat_lds || mode == ETF_MODE_FLAT || P.lds_path;
+            o.term = reinterpret_cast<const float *>(ctx->dev_base + (by_position ? ctx->lay.pterm : ctx->lay.eterm));
+        }
         const uint32_t *codes_in = reinterpret_cast<const uint32_t *>(ctx->dev_base + ctx->lay.codes);
         if (P.flat_lds) {
             rc = launch_lds<OUT_ALLPAIRS, false>(ctx, P, w, codes_in, ix.N, nullptr, 1, tiles, o, ETF_K_FLAT);
@@ -1023,6 +1028,12 @@ static int search_impl(etf_ctx *ctx, const float *queries, int64_t Q, int k, int
         o.cand = cand;
         o.C = P.C;
         o.nq = nq;
+        const float *term = nullptr;
+        if (ix.has_term) {
+            term = reinterpret_cast<const float *>(ctx->dev_base + (flat ? L.pterm : L.eterm));
+            o.term = term;
+            o.term_map = reinterpret_cast<const uint32_t *>(ctx->dev_base + (flat ? L.sample_pos : L.sample_enc));
+        }
         ReduceArgs r;
         const uint32_t *ecodes = reinterpret_cast<const uint32_t *>(ctx->dev_base + L.ecodes);
         if (!flat && !P.lds_path) {
@@ -1079,6 +1090,7 @@ static int search_impl(etf_ctx *ctx, const float *queries, int64_t Q, int k, int
         sa.fx_margin = P.fx ? (uint32_t)(2 * (ix.M + 8 * (ix.M + 1)) + 16) : 0u;
         sa.lutT = lutT;
         sa.codes = reinterpret_cast<const uint8_t *>(ctx->dev_base + (flat ? L.codes : L.ecodes));
+        sa.term = term;
         sa.M = ix.M;
         sa.K = ix.K;
         sa.grouped = (P.lds_path || P.flat_lds) ? lds_chunks_per_line(std::max(2, pick_G(ix.M, ix.K))) : 0;
@@ -1113,6 +1125,7 @@ static int search_impl(etf_ctx *ctx, const float *queries, int64_t Q, int k, int
             ea.rows = ix.Nd;
             ea.ebegin = sa.ebegin;
         }
+        ea.term = term;
         ea.ids = sa.ids;
         ea.k = k;
         ea.out_ids = sa.out_ids;

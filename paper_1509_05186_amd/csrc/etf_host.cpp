@@ -115,7 +115,8 @@ static void radix_sort_records(std::vector<Rec> &a, int nbytes, ByteOf byte_of)
 struct KeyRec {
     uint64_t k[2];   // code bytes packed big-endian: integer order == lexicographic order
     uint32_t pos;    // payload: input position or distinct-encoding number
-    int32_t id;      // secondary key
+    int32_t id;      // last key
+    uint32_t tb;     // bits of the vector's leaf term (non-negative float: orders like the value), 0 without payload
 };
 
 static inline void pack_key(const uint8_t *code, int c0, int c1, uint64_t k[2])
@@ -289,7 +290,7 @@ void compute_layout(etf_ctx *ctx)
     for (int t = 0; t < ix.T; ++t) {
         const HostTree &tr = ix.tree[t];
         DevTreeLayout &TL = L.tree[t];
-        TL.leaf_of = ix.T == 1 ? -1 : take(ix.Nd * 4);
+        TL.leaf_of = (ix.T == 1 && !ix.has_term) ? -1 : take(ix.Nd * 4);
         TL.rec = take(tr.U * tr.rstride);
         for (int l = 0; l < tr.D; ++l) {
             TL.icode[l] = take(tr.nI[l]);
@@ -299,6 +300,8 @@ void compute_layout(etf_ctx *ctx)
             TL.lrow[l] = take(tr.nL[l] * 4);
         }
     }
+    L.eterm = ix.has_term ? take(ix.Nd * 4) : -1;
+    L.pterm = ix.has_term ? take(ix.N * 4) : -1;
     L.total = off;
 }
 
@@ -334,6 +337,8 @@ void for_each_image_array(const etf_ctx *ctx, const std::function<void(int64_t, 
             put(TL.lrow[l], tr.bucket[l].row.data(), tr.bucket[l].row.size() * 4);
         }
     }
+    if (L.eterm >= 0) put(L.eterm, ix.eterm.data(), ix.eterm.size() * 4);
+    if (L.pterm >= 0) put(L.pterm, ix.pterm.data(), ix.pterm.size() * 4);
 }
 
 }  // namespace etf
@@ -558,6 +563,8 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
     if (!codes || N <= 0) return fail(ctx, ETF_EINVAL, "codes is null or N <= 0");
     if (N >= ((int64_t)1 << 31)) return fail(ctx, ETF_EINVAL, "N must be below 2^31");
     if (T < 1 || T > M) return fail(ctx, ETF_EINVAL, "need 1 <= T <= M (T=%d, M=%d)", T, M);
+    if (!ctx->next_term.empty() && (int64_t)ctx->next_term.size() != N)
+        return fail(ctx, ETF_EINVAL, "the leaf terms were given for %lld vectors, the build has %lld", (long long)ctx->next_term.size(), (long long)N);
     std::vector<int32_t> cb(T + 1);
     if (chunk_begin) {
         for (int t = 0; t <= T; ++t) cb[t] = chunk_begin[t];
@@ -594,6 +601,8 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
         codes = ix.codes.data();  // from here on: the encodings in index order
         ix.ids_in.resize(N);
         for (int64_t i = 0; i < N; ++i) ix.ids_in[i] = ids ? ids[i] : (int32_t)i;
+        ix.has_term = !ctx->next_term.empty();
+        if (ix.has_term) ix.pterm = ctx->next_term;
 
         // 1. lexicographic sort of (encoding, id)  -- "in place sort of the encoded dataset"
         std::vector<KeyRec> rec((size_t)N);
@@ -602,12 +611,17 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
                 pack_key(codes + (size_t)i * M, 0, M, rec[i].k);
                 rec[i].pos = (uint32_t)i;
                 rec[i].id = ix.ids_in[i];
+                uint32_t tb = 0;
+                if (ix.has_term) memcpy(&tb, &ix.pterm[i], 4);
+                rec[i].tb = tb;
             }
         });
         const int idbytes = ids ? 4 : 0;  // positions are already ascending when ids are implicit
-        radix_sort_records(rec, idbytes + M, [idbytes, M](const KeyRec &r, int p) -> int {
+        const int tbytes = ix.has_term ? 4 : 0;  // order: encoding, then term, then id
+        radix_sort_records(rec, idbytes + tbytes + M, [idbytes, tbytes, M](const KeyRec &r, int p) -> int {
             if (p < idbytes) return (int)(((uint32_t)r.id >> (8 * p)) & 255);
-            return key_byte(r.k, M - 1 - (p - idbytes));
+            if (p < idbytes + tbytes) return (int)((r.tb >> (8 * (p - idbytes))) & 255);
+            return key_byte(r.k, M - 1 - (p - idbytes - tbytes));
         });
 
         // 2. distinct encodings and their id ranges
@@ -616,7 +630,7 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
         ix.ebegin.clear();
         std::vector<KeyRec> distinct;  // key + pos = distinct number
         for (int64_t i = 0; i < N; ++i) {
-            if (i == 0 || rec[i].k[0] != rec[i - 1].k[0] || rec[i].k[1] != rec[i - 1].k[1]) {
+            if (i == 0 || rec[i].k[0] != rec[i - 1].k[0] || rec[i].k[1] != rec[i - 1].k[1] || rec[i].tb != rec[i - 1].tb) {
                 ix.ebegin.push_back((uint32_t)i);
                 KeyRec r = rec[i];
                 r.pos = (uint32_t)distinct.size();
@@ -632,6 +646,10 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
         ix.ecodes.resize((size_t)ix.Nd * M);
         for (int64_t e = 0; e < ix.Nd; ++e)
             for (int m = 0; m < M; ++m) ix.ecodes[(size_t)e * M + m] = (uint8_t)key_byte(distinct[e].k, m);
+        if (ix.has_term) {
+            ix.eterm.resize((size_t)ix.Nd);
+            for (int64_t e = 0; e < ix.Nd; ++e) memcpy(&ix.eterm[e], &distinct[e].tb, 4);
+        }
         { std::vector<KeyRec>().swap(rec); }
 
         // 3. one tree per chunk group
@@ -640,7 +658,7 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
             HostTree &tr = ix.tree[t];
             tr.c0 = cb[t];
             tr.D = cb[t + 1] - cb[t];
-            if (T == 1) {
+            if (T == 1 && !ix.has_term) {  // (with a payload several entries may share a leaf: the general path below)
                 build_tree(distinct, tr.D, tr);
                 continue;
             }
@@ -722,12 +740,50 @@ extern "C" int etf_index_build(etf_ctx *ctx, const uint8_t *codes, int64_t N, co
         ix.built = true;
         ctx->idx = std::move(ix);
         ctx->dev_base = nullptr;
+        ctx->next_term.clear();  // a payload belongs to one build
         compute_layout(ctx);
     } catch (const std::bad_alloc &) {
         drop_index(ctx);
         return fail(ctx, ETF_ENOMEM, "out of host memory while building the index");
     }
     return ETF_OK;
+}
+
+// =============================================================================================
+// leaf payload
+// =============================================================================================
+extern "C" int etf_index_set_leaf_term(etf_ctx *ctx, const float *term, int64_t N)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (!term) {
+        ctx->next_term.clear();
+        return ETF_OK;
+    }
+    if (N <= 0) return fail(ctx, ETF_EINVAL, "N must be positive");
+    for (int64_t i = 0; i < N; ++i)
+        if (!(term[i] >= 0.f) || !(term[i] <= 3.0e38f)) return fail(ctx, ETF_EINVAL, "leaf term %lld is negative or not finite", (long long)i);
+    try {
+        ctx->next_term.resize((size_t)N);
+        for (int64_t i = 0; i < N; ++i) ctx->next_term[i] = term[i] == 0.f ? 0.f : term[i];  // -0 becomes +0: one bit pattern per value
+    } catch (const std::bad_alloc &) {
+        ctx->next_term.clear();
+        return fail(ctx, ETF_ENOMEM, "out of host memory");
+    }
+    return ETF_OK;
+}
+
+extern "C" int etf_index_set_leaf_bytes(etf_ctx *ctx, const uint8_t *bytes, int64_t N, float scale, float offset)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (!bytes) return etf_index_set_leaf_term(ctx, nullptr, 0);
+    if (N <= 0) return fail(ctx, ETF_EINVAL, "N must be positive");
+    try {
+        std::vector<float> t((size_t)N);
+        for (int64_t i = 0; i < N; ++i) t[i] = fmaf(scale, (float)bytes[i], offset);
+        return etf_index_set_leaf_term(ctx, t.data(), N);
+    } catch (const std::bad_alloc &) {
+        return fail(ctx, ETF_ENOMEM, "out of host memory");
+    }
 }
 
 // =============================================================================================
@@ -904,6 +960,8 @@ extern "C" int etf_index_layout(const etf_ctx *ctx, etf_layout *out)
     out->rec0 = L.rec0;
     out->cb_centered = L.cb_centered; out->cb_norm = L.cb_norm; out->cb_mean = L.cb_mean;
     out->cb_row = ctx->dsp;
+    out->eterm = L.eterm;
+    out->pterm = L.pterm;
     out->rec0_stride = ix.rstride0;
     out->n_sample_enc = ix.n_sample_enc;
     out->n_sample_pos = ix.n_sample_pos;

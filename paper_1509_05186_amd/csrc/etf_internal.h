@@ -69,6 +69,11 @@ struct HostIndex {
     std::vector<uint32_t> sample_pos;       // input positions of the flat-mode threshold sample
     std::vector<uint8_t> sample_enc_codes;  // [n_sample_enc][M] the sampled encodings themselves, in sample order
     std::vector<uint8_t> sample_pos_codes;  // [n_sample_pos][M] likewise for the flat-mode sample
+    // Leaf payload: one additive float32 term per vector, given before the build.  Vectors that share an encoding but
+    // not the term are separate entries ("distinct encodings" below then means distinct (encoding, term) pairs).
+    bool has_term = false;
+    std::vector<float> eterm;               // [Nd] term of every entry
+    std::vector<float> pterm;               // [N] term of every vector, input order
     int rstride0 = 0;
     std::vector<uint8_t> rec0;              // [Nd][rstride0] tree 0's chunks of every distinct encoding, zero padded
     std::vector<HostTree> tree;
@@ -87,6 +92,7 @@ struct DevLayout {
     int64_t codebooks = 0, codes = 0, ids_in = 0, ids_sorted = 0, ebegin = 0, enc_of_pos = 0, ecodes = 0,
             sample_enc = 0, sample_pos = 0, rec0 = 0, cb_centered = 0, cb_norm = 0, cb_mean = 0, sample_enc_codes = 0,
             sample_pos_codes = 0;
+    int64_t eterm = -1, pterm = -1;         // only with a leaf payload
     std::vector<DevTreeLayout> tree;
 };
 
@@ -148,6 +154,7 @@ struct etf_ctx {
     char *dev_base = nullptr;               // caller-owned buffer holding the device image
     etf::Options opt;
     std::vector<int32_t> next_order;        // chunk order of the next index build (empty: as given)
+    std::vector<float> next_term;           // leaf payload of the next index build (empty: none)
     // diagnostics of the most recent search (device address inside the caller's workspace)
     void *last_flag_count = nullptr;
     // landing place of the small device-to-host copies of the device index build

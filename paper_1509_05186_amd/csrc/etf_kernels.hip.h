@@ -794,6 +794,12 @@ struct OutArgs {
     uint32_t *cnt;      // [tiles*64]
     uint64_t *cand;     // [tiles*64][C]
     uint32_t C;
+    // Leaf payload (paper, Experiments: extra information stored on the leaf node): a term added to the finished sum
+    // of an item, after the table entries.  term is indexed by the item's number in the array the kernel walks
+    // (distinct entries, or input positions); where the kernel walks a stream that stands for other items (the
+    // bound's sample stored side by side) term_map gives the item number of stream position i.  nullptr: none.
+    const float *term;
+    const uint32_t *term_map;
 };
 
 __device__ __forceinline__ void emit_filter(const OutArgs &o, int tile, int col, float tauv, float d, uint32_t item)
@@ -845,7 +851,8 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
         for (int64_t g = ((int64_t)blockIdx.x * nw + w) * G + lg; g < o.ngroups; g += (int64_t)gridDim.x * nw * G) {
             const int64_t lo = g * o.gsize, hi = min(nitems, lo + o.gsize);
             float best = __uint_as_float(0x7F800000u);
-            for (int64_t j = lo; j < hi; ++j) best = fminf(best, flat_one<G>(lds, codes + (int64_t)sample[j] * M, M, K, qq));
+            for (int64_t j = lo; j < hi; ++j)
+                best = fminf(best, flat_one<G>(lds, codes + (int64_t)sample[j] * M, M, K, qq) + (o.term ? o.term[sample[j]] : 0.f));
             o.gmin[((int64_t)tile * o.ngroups + g) * QT + col] = best;
         }
         return;
@@ -855,7 +862,7 @@ __global__ void k_flat(const uint8_t *__restrict__ codes, int64_t nitems, const 
     float tauv = 0.f;
     if (MODE == OUT_FILTER) tauv = o.tau[(int64_t)tile * QT + col];
     for (int64_t j = blo + (int64_t)w * G + lg; j < bhi; j += (int64_t)nw * G) {
-        const float acc = flat_one<G>(lds, codes + j * M, M, K, qq);
+        const float acc = flat_one<G>(lds, codes + j * M, M, K, qq) + (o.term ? o.term[j] : 0.f);
         if (MODE == OUT_ALLPAIRS) {
             const int64_t ql = (int64_t)tile * QT + col;
             if (ql < o.nq) o.dist[ql * o.N + j] = acc;
@@ -1159,6 +1166,7 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
             for (int64_t j0 = lo; j0 < hi; j0 += IPS * U) {
                 uint32_t dw[U][M4];
                 bool live[U];
+                float tm[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int64_t idx = j0 + u * IPS + lg;
@@ -1167,11 +1175,12 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
                     const int64_t e = map ? (int64_t)map[ic] : ic;
 #pragma unroll
                     for (int i = 0; i < M4; ++i) dw[u][i] = rec[e * M4 + i];
+                    tm[u] = o.term ? o.term[o.term_map ? (int64_t)o.term_map[ic] : e] : 0.f;
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     vecq top = 0.f;
-                    const vecq d = sum_of(dw[u], false, top);
+                    const vecq d = sum_of(dw[u], false, top) + tm[u];
                     if (live[u]) {
 #pragma unroll
                         for (int v = 0; v < V; ++v) best[v] = fminf(best[v], d[v]);
@@ -1199,18 +1208,20 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
         const bool wide = (o.N % U) == 0 && (reinterpret_cast<uintptr_t>(o.dist) % (U * 4)) == 0;
         for (int64_t j0 = ((int64_t)blockIdx.x * nw + w) * (IPS * U); j0 < bhi; j0 += (int64_t)gridDim.x * nw * (IPS * U)) {
             uint32_t dw[U][M4];
+            float tm[U];
             const int64_t jf = j0 + U * lg;  // this lane group's first item
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int64_t j = min(jf + u, nitems - 1);
 #pragma unroll
                 for (int k2 = 0; k2 < M4; ++k2) dw[u][k2] = rec[j * M4 + k2];
+                tm[u] = o.term ? o.term[j] : 0.f;
             }
             vecq d[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 vecq top = 0.f;
-                d[u] = sum_of(dw[u], false, top);
+                d[u] = sum_of(dw[u], false, top) + tm[u];
             }
 #pragma unroll
             for (int v = 0; v < V; ++v) {
@@ -1338,7 +1349,8 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
 #pragma unroll
                 for (int v = 0; v < V; ++v) emit(live && d[v] <= itau[v], d[v], col + v, rel);
             } else {
-                const vecq d = sum_of(dw[u], fast, top);
+                vecq d = sum_of(dw[u], fast, top);
+                if (o.term) d += o.term[min(blo + (int64_t)rel, nitems - 1)];  // (uniform branch; a payload costs a load per step)
 #pragma unroll
                 for (int v = 0; v < V; ++v) emit(live && d[v] <= tau[v], __float_as_uint(d[v]), col + v, rel);
             }
@@ -1431,12 +1443,14 @@ __global__ __launch_bounds__(256) void k_reduce(ReduceArgs r, int64_t nitems, co
         const uint32_t e = live ? (MODE == OUT_FILTER ? (uint32_t)(base + lane) : map[base + lane]) : 0u;
         uint32_t my_rows[TMAX];
         reduce_rows<TMAX>(r, e, live, my_rows);
+        const float my_tm = (o.term && live) ? o.term[e] : 0.f;  // the leaf term of the item this lane owns
         for (int s0 = 0; s0 < cnt; s0 += UB) {
             float d[UB];
             reduce_batch<TMAX>(r, tile, lane, my_rows, s0, cnt, d);
 #pragma unroll
             for (int u = 0; u < UB; ++u) {
                 if (s0 + u >= cnt) break;
+                d[u] += __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_tm), s0 + u));
                 if (MODE == OUT_ALLPAIRS) tbuf[w][s0 + u][lane] = d[u];
                 else if (MODE == OUT_SAMPLE) best = fminf(best, d[u]);
                 else if (d[u] <= tauv) {
@@ -1687,6 +1701,7 @@ struct SelectArgs {
     uint32_t fx_margin;      // 0: the upper word is the float32 distance itself
     const float *lutT;       // [tiles][M][K][64] tables of this batch
     const uint8_t *codes;    // [items][M]
+    const float *term;       // [items] leaf payload or nullptr
     int M, K, T, grouped;
     int32_t chunk_begin[ETF_MAX_M + 1];
 };
@@ -1813,7 +1828,8 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
         auto lut = [&](int m, int code) -> float { return lq[((int64_t)m * a.K + code) * QT]; };
         for (int i = threadIdx.x; i < nk; i += 256) {
             const uint32_t e = (uint32_t)kept[i];
-            kept[i] = ((uint64_t)__float_as_uint(assoc_distance(a, lut, a.codes + (int64_t)e * a.M)) << 32) | e;
+            const float dd = assoc_distance(a, lut, a.codes + (int64_t)e * a.M) + (a.term ? a.term[e] : 0.f);
+            kept[i] = ((uint64_t)__float_as_uint(dd) << 32) | e;
         }
     }
     const int nk2 = pow2_at_least(nk);
@@ -1916,6 +1932,7 @@ struct ExactArgs {
     int grouped;              // 4 or 8: sums associated as the LDS-resident kernels do (see exact_distance), 0: left to right
     int32_t chunk_begin[ETF_MAX_M + 1];
     const uint8_t *codes;     // [rows][M]
+    const float *term;        // [rows] leaf payload or nullptr
     int64_t rows;
     const uint32_t *ebegin;   // id ranges per row or nullptr (one id per row)
     const int32_t *ids;
@@ -1928,6 +1945,11 @@ struct ExactArgs {
 __device__ __forceinline__ float exact_distance(const ExactArgs &a, const float *lut, const uint8_t *c)
 {
     return assoc_distance(a, [&](int m, int code) -> float { return lut[m * a.K + code]; }, c);
+}
+// the same with the row's leaf term
+__device__ __forceinline__ float exact_distance_row(const ExactArgs &a, const float *lut, int64_t e)
+{
+    return exact_distance(a, lut, a.codes + e * a.M) + (a.term ? a.term[e] : 0.f);
 }
 
 __global__ __launch_bounds__(256) void k_exact(ExactArgs a)
@@ -1949,7 +1971,7 @@ __global__ __launch_bounds__(256) void k_exact(ExactArgs a)
         hist[threadIdx.x] = 0;
         __syncthreads();
         for (int64_t e = threadIdx.x; e < a.rows; e += 256) {
-            const uint32_t v = __float_as_uint(exact_distance(a, lut, a.codes + e * a.M));
+            const uint32_t v = __float_as_uint(exact_distance_row(a, lut, e));
             const uint32_t first = a.ebegin ? a.ebegin[e] : (uint32_t)e;
             const uint32_t mult = min(a.ebegin ? a.ebegin[e + 1] - first : 1u, k);
             if (p < 4) {
@@ -1985,7 +2007,7 @@ __global__ __launch_bounds__(256) void k_exact(ExactArgs a)
     __syncthreads();
     const uint32_t vk = (uint32_t)(prefix >> 32), idk = (uint32_t)prefix;
     for (int64_t e = threadIdx.x; e < a.rows; e += 256) {
-        const uint32_t v = __float_as_uint(exact_distance(a, lut, a.codes + e * a.M));
+        const uint32_t v = __float_as_uint(exact_distance_row(a, lut, e));
         if (v > vk) continue;
         const uint32_t first = a.ebegin ? a.ebegin[e] : (uint32_t)e;
         const uint32_t mult = min(a.ebegin ? a.ebegin[e + 1] - first : 1u, k);

@@ -57,9 +57,13 @@ def walk_image(ctx, lut):
                 leafp[row] = acc
             part_prev = part
         assert not np.any(np.isnan(leafp))
-        if T == 1:
+        if lay.leaf_of[t] < 0:          # a single tree without leaf payload: entry e is leaf e
+            assert T == 1 and U == Nd
             total += leafp
         else:
             leaf_of = arr(buf, lay.leaf_of[t], Nd, np.uint32)
             total += leafp[leaf_of]
+    if lay.eterm >= 0:                  # leaf payload: the entry's term, added last
+        total = total + arr(buf, lay.eterm, Nd, np.float32).astype(np.float64)
+        assert np.array_equal(arr(buf, lay.pterm, N, np.float32), arr(buf, lay.eterm, Nd, np.float32)[enc_of_pos])
     return total[enc_of_pos], lookups

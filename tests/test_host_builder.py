@@ -297,3 +297,47 @@ def test_suggest_chunk_order():
     order3, given3, best3 = c.suggest_chunk_order(codes2, T=1)
     i1, i4 = order3.tolist().index(1), order3.tolist().index(4)
     assert abs(i1 - i4) == 1 and best3 <= given3
+
+
+@pytest.mark.parametrize("T,M,K,N", [(1, 4, 3, 400), (2, 6, 3, 500), (3, 6, 2, 300), (1, 8, 256, 200)])
+def test_builder_with_leaf_payload(T, M, K, N):
+    """Index with a leaf term per vector: entries are the distinct (encoding, term) pairs in (encoding, term) order,
+    ids inside an entry ascend, and the exported image evaluates to the flat sum plus the vector's term."""
+    rng = np.random.default_rng(T * 100 + M)
+    codes = rng.integers(0, K, size=(N, M)).astype(np.uint8)
+    codes[N // 2:] = codes[: N - N // 2]                       # every encoding (at least) twice
+    term = rng.integers(0, 3, size=N).astype(np.float32) * 0.75   # few values: equal and unequal terms on equal encodings
+    cb = rng.normal(size=(M, K, 2)).astype(np.float32)
+    c = host_ctx(cb)
+    c.index_set_leaf_term(term)
+    c.index_build(codes, T=T)
+    st, lay = c.index_stats(), c.index_layout()
+    pairs = np.unique(np.concatenate([codes.astype(np.float64), term[:, None].astype(np.float64)], axis=1), axis=0)
+    assert st["n_distinct"] == len(pairs) and st["n_distinct"] > len(np.unique(codes, axis=0))
+    buf = c.index_export()
+    ecodes = arr(buf, lay.ecodes, len(pairs) * M, np.uint8).reshape(len(pairs), M)
+    eterm = arr(buf, lay.eterm, len(pairs), np.float32)
+    assert np.array_equal(ecodes, pairs[:, :M].astype(np.uint8)) and np.array_equal(eterm, pairs[:, M].astype(np.float32))
+    ebegin = arr(buf, lay.ebegin, len(pairs) + 1, np.uint32)
+    ids_sorted = arr(buf, lay.ids_sorted, N, np.int32)
+    for e in range(len(pairs)):
+        members = ids_sorted[ebegin[e]:ebegin[e + 1]]
+        assert np.all(np.diff(members) > 0)
+        assert np.all(codes[members] == ecodes[e]) and np.all(term[members] == eterm[e])
+    lut = rng.normal(size=(M, K)) ** 2
+    want = lut[np.arange(M)[None, :], codes].sum(1) + term.astype(np.float64)
+    got, _ = walk_image(c, lut)
+    assert np.allclose(got, want, rtol=1e-12)
+    # the byte form, the clearing call, a payload of the wrong length, negative terms
+    c2 = host_ctx(cb)
+    c2.index_set_leaf_bytes((term / 0.75).astype(np.uint8), 0.75, 0.0)
+    c2.index_build(codes, T=T)
+    assert np.array_equal(c2.index_export(), buf)
+    c2.index_set_leaf_term(term[:-1])
+    with pytest.raises(etf.EtfError):
+        c2.index_build(codes, T=T)
+    c2.index_set_leaf_term(None)
+    c2.index_build(codes, T=T)
+    assert c2.index_layout().eterm == -1 and c2.index_stats()["n_distinct"] == len(np.unique(codes, axis=0))
+    with pytest.raises(etf.EtfError):
+        c2.index_set_leaf_term(-term - 1)

@@ -330,3 +330,32 @@ def test_encode_f32_near_ties_tell_fused_from_unfused():
     assert differ > 50, differ
     plain = rng.normal(size=(4000, M * ds)).astype(np.float32) * 2
     assert int((fused_assign(plain) != oracle.encode_f32(plain, cb)).sum()) <= 2
+
+
+def test_leaf_term_golden_and_properties():
+    """adc_all_term / search_term: the hand-worked example; a zero term changes nothing; a constant term shifts every
+    distance and no rank; the sum equals the brute-force distance to the reconstruction plus the term."""
+    g = json.load(open(GOLD))
+    cb = np.array(g["codebooks"], dtype=np.float32)
+    q = np.array([g["query"]], dtype=np.float32)
+    codes = np.array(g["codes"], dtype=np.uint8)
+    lt = g["leaf_term"]
+    term = np.float32(lt["offset"]) + np.float32(lt["scale"]) * np.array(lt["bytes"], dtype=np.float32)
+    assert term.tolist() == lt["terms"]
+    assert oracle.adc_all_term(q, cb, codes, term)[0].tolist() == lt["distances"]
+    ids, dist = oracle.search_term(q, cb, codes, term, 3)
+    assert ids[0].tolist() == lt["top3_ids"] and dist[0].tolist() == lt["top3_dist"]
+    rng = np.random.default_rng(12)
+    cb2 = rng.normal(size=(3, 5, 2)).astype(np.float32)
+    codes2 = rng.integers(0, 5, size=(40, 3)).astype(np.uint8)
+    q2 = rng.normal(size=(4, 6)).astype(np.float32)
+    t2 = rng.uniform(0, 3, size=40).astype(np.float32)
+    plain = oracle.adc_all(q2, cb2, codes2)
+    assert np.array_equal(oracle.adc_all_term(q2, cb2, codes2, np.zeros(40)), plain)
+    brute = ((q2[:, None, :].astype(np.float64) - oracle.decode(codes2, cb2)[None].astype(np.float64)) ** 2).sum(-1)
+    assert np.allclose(oracle.adc_all_term(q2, cb2, codes2, t2), brute + t2[None].astype(np.float64), rtol=1e-12)
+    i0, d0 = oracle.search_term(q2, cb2, codes2, np.zeros(40), 7)
+    i1, d1 = oracle.search_term(q2, cb2, codes2, np.full(40, 2.5), 7)
+    assert np.array_equal(i0, i1) and np.allclose(d1, d0 + 2.5, rtol=1e-12)
+    ri, rd = oracle.search(q2, cb2, codes2, 7)
+    assert np.array_equal(i0, ri) and np.allclose(d0, rd, rtol=1e-12)
