@@ -75,6 +75,9 @@ def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
 
 
+EXTRA_OPTS = []   # --opt NAME=VALUE pairs, applied to the encoding context as well
+
+
 def make_inputs(cfg, etf, torch, scale_n=None, scale_q=None):
     """Synthetic workload: library-trained codebooks, database encoded by the library's device encoder, queries.
     Returns the encode timing as well (set-up work, outside the benchmark's timed region)."""
@@ -83,6 +86,11 @@ def make_inputs(cfg, etf, torch, scale_n=None, scale_q=None):
     N = scale_n or cfg.N
     Q = scale_q or cfg.Q
     enc = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+    plain = False
+    for nv in EXTRA_OPTS:
+        name, val = nv.split("=")
+        enc.set_option(name, int(val))
+        plain = plain or (name == "encode_kernel" and int(val) == 1)
     t0 = time.time()
     enc.pq_train(gm.sample(cfg.n_train, SEED_TRAIN), cfg.M, cfg.K, cfg.kmeans_iters, seed=SEED_TRAIN)
     log("k-means (%d x %d, %d iters): %.1f s" % (cfg.n_train, cfg.d, cfg.kmeans_iters, time.time() - t0))
@@ -101,9 +109,13 @@ def make_inputs(cfg, etf, torch, scale_n=None, scale_q=None):
         if (done >> 17) % 64 == 0:
             log("  generated + encoded %d of %d vectors, %.0f s" % (done, N, time.time() - t0))
     ms, cnt = enc.profile_read()["encode"]
-    flops = 3.0 * N * cfg.d * cfg.K          # subtract, multiply, add per (vector, codeword, dimension)
+    # plain kernel: subtract, multiply, add per (vector, codeword, dimension), three unfused vector instructions;
+    # matrix-core kernel: the contraction x.c, two operations per (vector, codeword, dimension)
+    flops = (3.0 if plain else 2.0) * N * cfg.d * cfg.K
     encode = {"vectors": N, "kernel_ms": ms, "launches": cnt, "vectors_per_s": N / (ms / 1e3) if ms > 0 else None,
+              "kernel": "float32 rule for every codeword (vector unit)" if plain else "distances on the matrix cores, near-ties by the float32 rule",
               "TFLOPs": flops / (ms / 1e3) / 1e12 if ms > 0 else None,
+              "ops_counted": "3 N d K unfused vector operations" if plain else "2 N d K of the float32 contraction",
               "note": "device encoder kernel time only; generation on the host and the copies are not included"}
     log("generate + encode %d vectors: %.1f s (device encoder kernels %.1f ms, %.1f TFLOP/s)"
         % (N, time.time() - t0, ms, encode["TFLOPs"] or 0.0))
@@ -532,6 +544,7 @@ def main():
     ap.add_argument("--no-copy", action="store_true", help="skip the device copy and the memory ceilings")
     ap.add_argument("--encode-only", action="store_true", help="run the device encoder on the configuration's database and stop (counter runs)")
     args = ap.parse_args()
+    EXTRA_OPTS[:] = list(args.opt)
     if args.levels:
         args.traversal = 1
     if args.gpus != 1:

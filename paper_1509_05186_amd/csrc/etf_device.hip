@@ -352,12 +352,15 @@ int set_lds(const etf_ctx *ctx, F kernel, size_t bytes)
 int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_t tiles, float *lutT, float *lut_public)
 {
     dim3 grid((unsigned)tiles, (unsigned)ctx->M);
+    // few tiles: one wave per workgroup for the matrix-core kernel, so that the launch spreads over more compute units
+    const bool narrow = tiles * ctx->M < 128;
+    const dim3 mgrid((unsigned)tiles, (unsigned)ctx->M, narrow ? (unsigned)((ctx->K + 63) / 64) : 1u), mblock(narrow ? 64 : 256);
     ChunkOrder ord;
     for (int j = 0; j < ETF_MAX_M; ++j) ord.src[j] = (uint8_t)((size_t)j < ctx->idx.order.size() ? ctx->idx.order[j] : j);
     ProfScope prof(ctx, ETF_K_LUT);
     if (ctx->opt.metric == 1 && ctx->opt.lut_kernel == 0) {
         const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
-        hipLaunchKernelGGL(k_lut_mfma<true>, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
+        hipLaunchKernelGGL(k_lut_mfma<true>, mgrid, mblock, 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
                            cb, nullptr, nullptr, nullptr, ctx->dsp, lutT, lut_public, ord);
         LAUNCH_CHECK(ctx, "k_lut_mfma");
     } else if (ctx->opt.metric == 1) {
@@ -370,7 +373,7 @@ int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_
         const float *cbn = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_norm);
         const float *cbm = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_mean);
         const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
-        hipLaunchKernelGGL(k_lut_mfma<false>, grid, dim3(256), 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
+        hipLaunchKernelGGL(k_lut_mfma<false>, mgrid, mblock, 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
                            cb, cbc, cbn, cbm, ctx->dsp, lutT, lut_public, ord);
         LAUNCH_CHECK(ctx, "k_lut_mfma");
     } else {
@@ -663,7 +666,7 @@ bool lds_eligible(int M, int K, int T, const int32_t *chunk_begin)
     return M % lds_chunks_per_line(G) == 0;  // whole lines of 4 (8 at eight queries per sub-tile) chunks
 }
 
-template <int MODE, bool CTX, bool FX = false>
+template <int MODE, bool CTX, bool FX = false, bool TERM = false>
 int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64_t nitems, const uint32_t *map, int T,
                int64_t tiles, const OutArgs &o, int cls)
 {
@@ -695,9 +698,9 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
 #define LDS_CASE(GG, MM4, TT)                                                                                  \
     if constexpr ((CTX || MODE != OUT_FILTER || TT == 1) && (!FX || TT == 1) && (4 * MM4) % lds_chunks_per_line(GG) == 0) {                         \
         if (!done && G == GG && M == 4 * MM4 && T == TT) {                                                     \
-            int rc = set_lds(ctx, k_lds<GG, MM4, TT, MODE, CTX, FX>, lds);                                     \
+            int rc = set_lds(ctx, k_lds<GG, MM4, TT, MODE, CTX, FX, TERM>, lds);                                     \
             if (rc) return rc;                                                                                 \
-            hipLaunchKernelGGL((k_lds<GG, MM4, TT, MODE, CTX, FX>), grid, dim3(1024), lds, st, rec, nitems, map, lutT, K, \
+            hipLaunchKernelGGL((k_lds<GG, MM4, TT, MODE, CTX, FX, TERM>), grid, dim3(1024), lds, st, rec, nitems, map, lutT, K, \
                                per_block, o);                                                                  \
             done = true;                                                                                       \
         }                                                                                                      \
@@ -730,9 +733,9 @@ int launch_flat(etf_ctx *ctx, const Plan &P, char *ws, int64_t nitems, const uin
         if (P.flat_lds) {
             // the sample's codes are stored side by side in sample order: no indirection
             const uint8_t *rec = MODE == OUT_SAMPLE ? reinterpret_cast<const uint8_t *>(ctx->dev_base + ctx->lay.sample_pos_codes) : codes;
-            if (MODE == OUT_FILTER && P.fx)
-                return launch_lds<MODE, false, MODE == OUT_FILTER>(ctx, P, ws, reinterpret_cast<const uint32_t *>(rec), nitems, nullptr, 1,
-                                                                   tiles, o, ETF_K_FLAT);
+            if (MODE == OUT_FILTER && ctx->idx.has_term)
+                return launch_lds<MODE, false, false, MODE == OUT_FILTER>(ctx, P, ws, reinterpret_cast<const uint32_t *>(rec), nitems, nullptr,
+                                                                          1, tiles, o, ETF_K_FLAT);
             return launch_lds<MODE, false>(ctx, P, ws, reinterpret_cast<const uint32_t *>(rec), nitems, nullptr, 1, tiles, o,
                                            MODE == OUT_SAMPLE ? ETF_K_SAMPLE : ETF_K_FLAT);
         }
@@ -1066,7 +1069,8 @@ static int search_impl(etf_ctx *ctx, const float *queries, int64_t Q, int k, int
                 rc = launch_flat<OUT_FILTER>(ctx, P, w, ix.N, nullptr, tiles, o);
             else if (P.lds_path)
                 rc = P.fx ? launch_lds<OUT_FILTER, true, true>(ctx, P, w, ecodes, ix.Nd, nullptr, ix.T, tiles, o, ETF_K_LDS)
-                          : launch_lds<OUT_FILTER, true>(ctx, P, w, ecodes, ix.Nd, nullptr, ix.T, tiles, o, ETF_K_LDS);
+                    : ix.has_term ? launch_lds<OUT_FILTER, true, false, true>(ctx, P, w, ecodes, ix.Nd, nullptr, ix.T, tiles, o, ETF_K_LDS)
+                                  : launch_lds<OUT_FILTER, true>(ctx, P, w, ecodes, ix.Nd, nullptr, ix.T, tiles, o, ETF_K_LDS);
             else
                 rc = P.ctx_path ? launch_fused<OUT_FILTER>(ctx, P, w, r, ix.Nd, nullptr, tiles, o)
                                 : launch_reduce<OUT_FILTER>(ctx, r, ix.Nd, nullptr, tiles, o);

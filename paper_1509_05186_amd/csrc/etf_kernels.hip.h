@@ -172,7 +172,9 @@ __global__ __launch_bounds__(64) void k_lut_shift_sum(const float *__restrict__ 
 //     fixed r the lanes 0..31 hold 32 consecutive queries of one codeword: a 128-byte piece of a table row.
 //     Entries that are small against the norms are recomputed exactly (see below).
 //     IP: the tables hold the scalar products q_m . c themselves: the contraction on the unshifted vectors.
-//     grid (tiles, M), block 256 (wave w: codewords 64w .. 64w+63).
+//     grid (tiles, M), block 256 (wave w: codewords 64w .. 64w+63); or, for batches of few tiles, grid (tiles, M,
+//     ceil(K / 64)), block 64 (one wave per workgroup, its 64 codewords given by blockIdx.z): four times the
+//     workgroups, each with a quarter of the entries to recompute.
 // ------------------------------------------------------------------------------------------------
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -184,7 +186,7 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
                                                   float *__restrict__ lut_public, ChunkOrder ord)
 {
     const int tile = blockIdx.x, m = blockIdx.y, ms = ord.src[m];
-    const int lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, w = uniform(blockDim.x == 64 ? (int)blockIdx.z : (int)(threadIdx.x >> 6));
     const int ds = d / M;
     const int col = lane & 31, half = lane >> 5;
     const int kbase = w * 64;
@@ -267,7 +269,8 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
     // a branch, is a chain of 32 memory latencies per lane
     __shared__ float s_cc[256];
     if (threadIdx.x == 0) nfix = 0;
-    if (!IP && (int)threadIdx.x < K) s_cc[threadIdx.x] = cbnorm[(int64_t)ms * K + threadIdx.x];
+    if (!IP)
+        for (int k = threadIdx.x; k < K; k += blockDim.x) s_cc[k] = cbnorm[(int64_t)ms * K + k];
     __syncthreads();
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
@@ -1059,7 +1062,7 @@ __host__ __device__ inline size_t lds_aux_bytes(bool filter) { return filter ? (
 
 typedef __attribute__((address_space(3))) const vecq lds_vecq_t;
 
-template <int G, int M4, int T, int MODE, bool CTX, bool FX = false>
+template <int G, int M4, int T, int MODE, bool CTX, bool FX = false, bool TERM = false>
 __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, int64_t nitems,
                                               const uint32_t *__restrict__ map, const float *__restrict__ lutT, int K,
                                               int per_block, OutArgs o)
@@ -1086,6 +1089,7 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     const int lane = threadIdx.x & 63;
     const int w = uniform(threadIdx.x >> 6), nw = blockDim.x >> 6;
     static_assert(!FX || MODE == OUT_FILTER, "the fixed-point form is a candidate filter");
+    static_assert(!TERM || (MODE == OUT_FILTER && !FX), "TERM selects the filter pass with a leaf payload; the other modes test o.term");
     if (FILTER) wcount[w][lane] = 0u;
     stage_lines<G, FX>(lds, lutT, tile, sub, M, K, KP, FX ? o.tau : nullptr);
     const int lg = lane / LPI, lq = lane % LPI;
@@ -1326,23 +1330,52 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
 #pragma unroll
             for (int k2 = 0; k2 < M4; ++k2) dw[u][k2] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rr, (int)vo + 4 * k2, so, 0);
         }
-        // which steps may keep the context: a lane group may if its item has the S-chunk prefix of its previous one
-        bool fastv[U];
+        if constexpr (FX && CTX && CPL == 4 && M4 == 2) {
+            // The table reads of step u + 1 are issued before the entries of step u are added up and tested, so that
+            // the LDS pipe, which bounds this kernel, always has reads of this wave queued (one workgroup of 16 waves
+            // per CU cannot hide a read's latency by switching waves alone).  Only the six reads every step needs
+            // are kept in flight (2 x 24 registers); the two of the context's chunks are read when a step renews it.
+            bool fastv[U];  // which steps may keep the context (see below)
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            fastv[u] = false;
-            if (S > 0) {
-                const uint32_t smask = S == 1 ? 0xFFu : 0xFFFFu;
+            for (int u = 0; u < U; ++u) {
                 const bool live = !CHECK || i + u < len;
-                const bool differs = live && ((dw[u][0] ^ prev0) & smask) != 0u;
+                const bool differs = live && ((dw[u][0] ^ prev0) & 0xFFFFu) != 0u;
                 fastv[u] = __ballot(differs) == 0ull && i + u != 0;
                 prev0 = dw[u][0];
             }
+            vecu4 xr[2][M - 2];
+            auto issue = [&](int u, vecu4 *x) {
+#pragma unroll
+                for (int t = 2; t < M; ++t) x[t - 2] = *reinterpret_cast<lds_vecu4_t *>(addr_of(dw[u], t / CPL, t % CPL));
+            };
+            issue(0, xr[0]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (u + 1 < U) issue(u + 1, xr[(u + 1) & 1]);
+                if (!fastv[u])
+                    itop = *reinterpret_cast<lds_vecu4_t *>(addr_of(dw[u], 0, 0)) + *reinterpret_cast<lds_vecu4_t *>(addr_of(dw[u], 0, 1));
+                const vecu4 *x = xr[u & 1];
+                vecu4 d = itop + x[0] + x[1];
+                d = d + x[2] + x[3];
+                d = d + x[4] + x[5];
+                const bool live = !CHECK || i + u < len;
+                const uint32_t rel = first + (uint32_t)(i + u) * RF;
+#pragma unroll
+                for (int v = 0; v < V; ++v) emit(live && d[v] <= itau[v], d[v], col + v, rel);
+            }
+            return;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const bool live = !CHECK || i + u < len;
-            const bool fast = fastv[u];
+            bool fast = false;
+            if (S > 0) {
+                // a lane group may keep its context if its item has the S-chunk prefix of its previous one
+                const uint32_t smask = S == 1 ? 0xFFu : 0xFFFFu;
+                const bool differs = live && ((dw[u][0] ^ prev0) & smask) != 0u;
+                fast = __ballot(differs) == 0ull && i + u != 0;
+                prev0 = dw[u][0];
+            }
             const uint32_t rel = first + (uint32_t)(i + u) * RF;
             if (FX) {
                 const vecu4 d = sum_of_fx(dw[u], fast, itop);
@@ -1350,7 +1383,7 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
                 for (int v = 0; v < V; ++v) emit(live && d[v] <= itau[v], d[v], col + v, rel);
             } else {
                 vecq d = sum_of(dw[u], fast, top);
-                if (o.term) d += o.term[min(blo + (int64_t)rel, nitems - 1)];  // (uniform branch; a payload costs a load per step)
+                if (TERM) d += o.term[min(blo + (int64_t)rel, nitems - 1)];  // leaf payload: an instance of its own (a load per step)
 #pragma unroll
                 for (int v = 0; v < V; ++v) emit(live && d[v] <= tau[v], __float_as_uint(d[v]), col + v, rel);
             }
