@@ -182,6 +182,7 @@ struct Plan {
     bool lds_path = false;    // search with every table slice in LDS: no result tables at all
     bool flat_lds = false;    // flat mode through the same kernels
     bool fx = false;          // the main pass of the LDS-resident search filters candidates in fixed point
+    bool fx16 = false;        // ... on 16-bit tables (k_lds16)
     int64_t o_counter = 0, o_lutT = 0, o_gmin = 0, o_tau = 0, o_boff = 0, o_bm = 0, o_cnt = 0, o_flag = 0, o_cand = 0;
     int64_t o_part[ETF_MAX_M][ETF_MAX_M];
     int64_t o_leafp[ETF_MAX_M];
@@ -196,6 +197,7 @@ int pow2_at_least_host(int n)
     return p;
 }
 int tmax_class(int T);
+int pick_G(int width, int K);
 bool lds_eligible(int M, int K, int T, const int32_t *chunk_begin);
 
 int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan &P, int64_t ws_cap = 0)
@@ -253,6 +255,9 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
     // the fixed-point filter scales every table by its query's bound: it needs one (use_tau)
     // (not the flat scan: it lists every copy of an encoding, and copies tie exactly)
     P.fx = search && P.lds_path && P.use_tau && ctx->opt.lds_filter == 1 && !ctx->opt.force_fallback && !ix.has_term;
+    // 16-bit tables: built for rows of 64 and 32 bytes (M = 8 and M = 16 at K = 256); other shapes keep the float32 sums
+    P.fx16 = search && P.lds_path && P.use_tau && ctx->opt.lds_filter == 2 && !ctx->opt.force_fallback && !ix.has_term &&
+             (M == 8 || M == 16) && std::max(2, pick_G(M, K)) == (M == 8 ? 4 : 8);
     P.ctx_path = !P.lds_path && tmax_class(ix.T) != 0 && mode != ETF_MODE_FLAT && ctx->opt.traversal != 1;
     for (int t = 1; t < ix.T; ++t)  // the register-context kernels address a tree's result table with 32-bit offsets
         if (ix.tree[t].U >= ((int64_t)1 << 24)) P.ctx_path = false;
@@ -715,6 +720,34 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
     return ETF_OK;
 }
 
+// the filter pass on 16-bit tables (see k_lds16)
+int launch_lds16(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64_t nitems, int64_t tiles, const OutArgs &o)
+{
+    if (nitems == 0) return ETF_OK;
+    const int M = ctx->M, K = ctx->K;
+    const int G = std::max(2, pick_G(M, K));
+    const size_t lds = lds_table_bytes(G, M, K) + lds_aux_bytes(true);
+    int64_t bx = lds_blocks_for(tiles * (G / 2), nitems, (nitems >> 25) + 1);
+    if (ctx->opt.lds_blocks > 0) bx = std::max<int64_t>(ctx->opt.lds_blocks, (nitems >> 25) + 1);
+    const int per_block = (int)((nitems + bx - 1) / bx);
+    dim3 grid((unsigned)bx, (unsigned)(G / 2), (unsigned)tiles);
+    hipStream_t st = (hipStream_t)ctx->stream;
+    const float *lutT = reinterpret_cast<const float *>(ws + P.o_lutT);
+    ProfScope prof(ctx, ETF_K_LDS);
+    int rc;
+    if (M == 8) {
+        if ((rc = set_lds(ctx, k_lds16<4, 2, true>, lds))) return rc;
+        hipLaunchKernelGGL((k_lds16<4, 2, true>), grid, dim3(1024), lds, st, rec, nitems, lutT, K, per_block, o);
+    } else if (M == 16) {
+        if ((rc = set_lds(ctx, k_lds16<8, 4, true>, lds))) return rc;
+        hipLaunchKernelGGL((k_lds16<8, 4, true>), grid, dim3(1024), lds, st, rec, nitems, lutT, K, per_block, o);
+    } else {
+        return fail(ctx, ETF_EINVAL, "no 16-bit filter kernel for M=%d", M);
+    }
+    LAUNCH_CHECK(ctx, "k_lds16");
+    return ETF_OK;
+}
+
 template <int MODE>
 int launch_flat(etf_ctx *ctx, const Plan &P, char *ws, int64_t nitems, const uint32_t *sample, int64_t tiles, const OutArgs &o)
 {
@@ -1068,7 +1101,8 @@ static int search_impl(etf_ctx *ctx, const float *queries, int64_t Q, int k, int
             if (flat)
                 rc = launch_flat<OUT_FILTER>(ctx, P, w, ix.N, nullptr, tiles, o);
             else if (P.lds_path)
-                rc = P.fx ? launch_lds<OUT_FILTER, true, true>(ctx, P, w, ecodes, ix.Nd, nullptr, ix.T, tiles, o, ETF_K_LDS)
+                rc = P.fx16 ? launch_lds16(ctx, P, w, ecodes, ix.Nd, tiles, o)
+                    : P.fx ? launch_lds<OUT_FILTER, true, true>(ctx, P, w, ecodes, ix.Nd, nullptr, ix.T, tiles, o, ETF_K_LDS)
                     : ix.has_term ? launch_lds<OUT_FILTER, true, false, true>(ctx, P, w, ecodes, ix.Nd, nullptr, ix.T, tiles, o, ETF_K_LDS)
                                   : launch_lds<OUT_FILTER, true>(ctx, P, w, ecodes, ix.Nd, nullptr, ix.T, tiles, o, ETF_K_LDS);
             else
@@ -1092,6 +1126,9 @@ static int search_impl(etf_ctx *ctx, const float *queries, int64_t Q, int k, int
         // entry and per float32 addition of the distance it stands for, 2^27 * (M + 1) * 2^-24 = 8 (M + 1) units at the
         // bound; twice that between two candidates
         sa.fx_margin = P.fx ? (uint32_t)(2 * (ix.M + 8 * (ix.M + 1)) + 16) : 0u;
+        // 16-bit tables: truncation makes a sum too small by at most M units, everything else is far below one unit
+        if (P.fx16) sa.fx_margin = (uint32_t)(ix.M + 2);
+        sa.fx_first_pass = P.fx16 ? 2 : 0;
         sa.lutT = lutT;
         sa.codes = reinterpret_cast<const uint8_t *>(ctx->dev_base + (flat ? L.codes : L.ecodes));
         sa.term = term;

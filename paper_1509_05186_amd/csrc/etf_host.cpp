@@ -396,7 +396,7 @@ extern "C" int etf_set_option(etf_ctx *ctx, const char *name, int64_t value)
         if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "encode_kernel must be 0 or 1");
         ctx->opt.encode_kernel = value;
     } else if (n == "lds_filter") {
-        if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "lds_filter must be 0 or 1");
+        if (value < 0 || value > 2) return fail(ctx, ETF_EINVAL, "lds_filter must be 0, 1 or 2");
         ctx->opt.lds_filter = value;
     } else if (n == "cand_cap") {
         if (value < 0 || value > (1 << 20)) return fail(ctx, ETF_EINVAL, "cand_cap out of range");

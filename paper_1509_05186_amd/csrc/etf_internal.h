@@ -123,7 +123,7 @@ struct Options {
     int64_t traversal = 2;  // 0: distance context in registers, 1: level-synchronous kernels, 2: searches with all tables in LDS
     int64_t lds_blocks = 0; // workgroups per sub-tile of queries in the LDS-resident search kernel (0: chosen by the library)
     int64_t metric = 0;     // 0: squared Euclidean distance (smallest first), 1: scalar product (largest first)
-    int64_t lds_filter = 0; // main pass of the LDS-resident search: 0 float32 sums, 1 fixed-point candidate filter
+    int64_t lds_filter = 2; // main pass of the LDS-resident search: 0 float32 sums, 1 / 2 candidate filter in 32 / 16-bit fixed point
     int64_t encode_kernel = 0; // device encoder: 0 distance evaluations on the matrix cores, near-ties by the float32 rule; 1 the rule for every codeword
     int64_t lut_kernel = 0; // 0: matrix cores (expanded form on centred vectors, small entries recomputed), 1: plain (a-b)^2 sums
 };

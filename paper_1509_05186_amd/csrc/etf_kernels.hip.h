@@ -1396,6 +1396,237 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
 }
 
 // ------------------------------------------------------------------------------------------------
+// The filter pass of the LDS-resident search on 16-bit tables (option lds_filter = 2).
+//     The pass that looks at every encoding only has to decide which ones can be among the k nearest; it is bound by
+//     the LDS reads of table entries.  Here an entry is two bytes: scaled so that the query's bound becomes
+//     2^(C-1), truncated, and cut off at 2^C - 1, with C = 13 for M = 8 and 12 for M = 16 chunks, so that the sum of
+//     M entries fits 16 bits.  A sub-tile then holds twice the queries in the same LDS (32 at M = 8), a lane's
+//     16-byte read serves 8 queries, and a packed 16-bit add two of them: half the LDS reads and about two thirds
+//     of the vector instructions per distance.  Truncation makes a sum too small by at most M units, never too
+//     large, and the bound is rounded up: no encoding whose float32 distance is at or below the bound is lost; a
+//     share of M / 2^(C-1) of the bound's neighbourhood comes along.  k_select keeps what lies within the rounding
+//     of the k-th smallest sum and recomputes those distances as float32 sums of the float32 tables, which is what
+//     is ordered and returned (see SelectArgs::fx_margin).
+//     Geometry, item walk, distance context and line layout are those of k_lds<G> (rows of 64 or 32 bytes, lines
+//     of 256 bytes, chunk order rotated per lane group); a sub-tile has 128 / G queries.
+//     grid (blocks, G / 2, tiles), block 1024, dynamic LDS lds_table_bytes(G) + lds_aux_bytes(true); G in {4, 8}.
+// ------------------------------------------------------------------------------------------------
+typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) const u16x8 lds_u16x8_t;
+
+__host__ __device__ constexpr int fx16_cap_bits(int M) { return M <= 4 ? 14 : M <= 8 ? 13 : 12; }
+
+template <int G, int M4, bool CTX>
+__global__ __launch_bounds__(1024) void k_lds16(const uint32_t *__restrict__ rec, int64_t nitems, const float *__restrict__ lutT,
+                                                int K, int per_block, OutArgs o)
+{
+    constexpr int M = 4 * M4, Qs = 2 * WAVE / G, V = 8, LPI = Qs / V, IPS = WAVE / LPI;
+    constexpr int CPL = lds_chunks_per_line(G), NG = M / CPL, U = M4 >= 4 ? 2 : 4, RING = LDS_RING;
+    constexpr int CB = fx16_cap_bits(M);
+    constexpr uint32_t CAP = (1u << CB) - 1u;
+    constexpr float TOP = (float)(1u << (CB - 1));
+    static_assert(CPL * Qs * 2 == 256 && (G == 4 || G == 8), "lines of 256 bytes");
+    extern __shared__ float lds[];
+    constexpr uint32_t rowB = Qs * 2, lineB = CPL * rowB, KP = 256;
+    char *aux = reinterpret_cast<char *>(lds) + (size_t)NG * KP * lineB;
+    uint64_t(*ring)[RING] = reinterpret_cast<uint64_t(*)[RING]>(aux);
+    uint32_t(*wcount)[64] = reinterpret_cast<uint32_t(*)[64]>(aux + 16 * RING * 8);
+    uint32_t(*wpos)[64] = reinterpret_cast<uint32_t(*)[64]>(aux + 16 * RING * 8 + 16 * 64 * 4);
+    const int tile = blockIdx.z, sub = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int w = uniform(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    wcount[w][lane] = 0u;
+    // ---- stage the sub-tile's tables as 16-bit entries: piece p of row (m, k) holds queries 8p .. 8p+7
+    {
+        constexpr int P8 = Qs / 8;
+        const int p = (int)threadIdx.x % P8;  // the block size is a multiple of P8: a thread always converts the same queries
+        float sc[8];
+        bool dead[8];
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            const float t = o.tau[(int64_t)tile * QT + sub * Qs + p * 8 + v];
+            dead[v] = !(t >= 0.f);
+            sc[v] = TOP / fmaxf(t, 8.0779e-28f);
+        }
+        const float *src = lutT + (int64_t)tile * M * K * QT + sub * Qs + p * 8;
+        const int total = M * K * P8;
+        for (int idx0 = 0; idx0 < total; idx0 += (int)blockDim.x * 4) {
+            float4 a[4][2];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = idx0 + u * (int)blockDim.x + (int)threadIdx.x;
+                const int row = min(idx, total - 1) / P8;
+                a[u][0] = *reinterpret_cast<const float4 *>(src + (int64_t)row * QT);
+                a[u][1] = *reinterpret_cast<const float4 *>(src + (int64_t)row * QT + 4);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = idx0 + u * (int)blockDim.x + (int)threadIdx.x;
+                if (idx >= total) break;
+                const int row = idx / P8;
+                const int m = K == 256 ? row >> 8 : row / K, k = row - m * K;
+                const float e[8] = {a[u][0].x, a[u][0].y, a[u][0].z, a[u][0].w, a[u][1].x, a[u][1].y, a[u][1].z, a[u][1].w};
+                uint32_t q[8];
+#pragma unroll
+                for (int v = 0; v < 8; ++v) q[v] = dead[v] ? CAP : min((uint32_t)fminf(e[v] * sc[v], (float)CAP), CAP);
+                uint4 pk;
+                pk.x = q[0] | (q[1] << 16);
+                pk.y = q[2] | (q[3] << 16);
+                pk.z = q[4] | (q[5] << 16);
+                pk.w = q[6] | (q[7] << 16);
+                *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(lds) + (size_t)(((m / CPL) * KP + k) * CPL + (m % CPL)) * rowB + p * 16) = pk;
+            }
+        }
+        __syncthreads();
+    }
+    const int lg = lane / LPI, lq = lane % LPI;
+    const int col = sub * Qs + lq * V;  // first of this lane's queries inside the tile
+    const int jr = lg & (CPL - 1);
+    uint32_t sh[2][CPL], pb[NG][CPL];
+#pragma unroll
+    for (int t = 0; t < CPL; ++t) {
+        int c0 = t ^ jr;
+        if (CTX) c0 = t < 4 ? (t ^ (jr & 1)) : 4 + ((t - 4) ^ (jr & 3));
+        const int c1 = t ^ jr;
+        sh[0][t] = 0x03020000u | ((4u + (uint32_t)(c0 & 3)) << 8);
+        sh[1][t] = 0x03020000u | ((4u + (uint32_t)(c1 & 3)) << 8);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) pb[g][t] = (uint32_t)(lq * 16) + (uint32_t)g * KP * lineB + (uint32_t)(g == 0 ? c0 : c1) * rowB;
+    }
+    const bool cross = CPL == 8 && (jr & 4) != 0;
+    // a lane's 16 bytes are eight 16-bit entries, added as four dwords: no half can carry into its neighbour because
+    // a sum of M capped entries stays below 2^16, and three dwords add in one instruction
+    typedef uint32_t u32v4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) const u32v4 lds_u32v4_t;
+    auto look = [&](const uint32_t dw[M4], int g, int t) -> u32v4 {
+        uint32_t src;
+        if (CPL == 4) {
+            src = dw[g];
+        } else {
+            const bool second = (CTX && g == 0) ? t >= 4 : ((t >= 4) != cross);
+            src = second ? dw[2 * g + 1] : dw[2 * g];
+        }
+        return *reinterpret_cast<lds_u32v4_t *>(__builtin_amdgcn_perm(src, pb[g][t], sh[g == 0 ? 0 : 1][t]));
+    };
+    const int64_t blo = (int64_t)blockIdx.x * per_block;
+    const int64_t bhi = min(nitems, blo + per_block);
+    // the largest sum that may pass, plus one, per query of this lane
+    u16x8 tp1;
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const float t = o.tau[(int64_t)tile * QT + col + v];
+        const float scale = TOP / fmaxf(t, 8.0779e-28f);
+        tp1[v] = (t >= 0.f) ? (unsigned short)(min((uint32_t)fminf(t * scale * (1.f + 1.9073486e-6f), 60000.f), 60000u) + 2u) : (unsigned short)0;
+    }
+    int held = 0;
+    auto flush = [&]() {
+        const uint32_t c = wcount[w][lane];
+        wpos[w][lane] = c ? atomicAdd(&o.cnt[(int64_t)tile * QT + lane], c) : 0u;
+        wcount[w][lane] = 0u;
+        __builtin_amdgcn_wave_barrier();
+        for (int i = lane; i < held; i += 64) {
+            const uint64_t e = ring[w][i];
+            const int owner = (int)((e >> 26) & 63u);
+            const uint32_t pos = atomicAdd(&wpos[w][owner], 1u);
+            const int64_t q = (int64_t)tile * QT + owner;
+            if (pos < o.C)
+                o.cand[q * o.C + pos] = (e & 0xFFFFFFFF00000000ull) | (uint32_t)(blo + (int64_t)(e & 0x3FFFFFFull));
+        }
+        __builtin_amdgcn_wave_barrier();
+        held = 0;
+    };
+    // x: per query of the lane, bound + 1 - sum where the sum is at or below the bound, else 0 (four dwords of two
+    // halves).  The lanes that hold a non-zero half put one candidate each into the wave's ring (slot = rank among
+    // those lanes) and clear that half; nearly always that empties x everywhere, otherwise the wave goes round again.
+    auto emit = [&](u32v4 x, const u32v4 &dd, uint32_t rel) {
+        uint64_t bal = __ballot(((x.x | x.y) | (x.z | x.w)) != 0u);
+        while (bal != 0ull) {
+            const int rank = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+            if (((x.x | x.y) | (x.z | x.w)) != 0u) {
+                // first non-zero half: dword j, half h
+                const int j = x.x != 0u ? 0 : x.y != 0u ? 1 : x.z != 0u ? 2 : 3;
+                const uint32_t xw = j == 0 ? x.x : j == 1 ? x.y : j == 2 ? x.z : x.w;
+                const uint32_t dw2 = j == 0 ? dd.x : j == 1 ? dd.y : j == 2 ? dd.z : dd.w;
+                const int h = (xw & 0xFFFFu) != 0u ? 0 : 1;
+                const uint32_t val = h ? dw2 >> 16 : dw2 & 0xFFFFu;
+                const int c = col + 2 * j + h;
+                ring[w][held + rank] = ((uint64_t)val << 32) | ((uint32_t)c << 26) | rel;
+                atomicAdd(&wcount[w][c], 1u);
+                const uint32_t keep = h ? 0x0000FFFFu : 0xFFFF0000u;
+                x.x = j == 0 ? x.x & keep : x.x;
+                x.y = j == 1 ? x.y & keep : x.y;
+                x.z = j == 2 ? x.z & keep : x.z;
+                x.w = j == 3 ? x.w & keep : x.w;
+            }
+            held += __popcll(bal);
+            if (held > RING - 64) flush();
+            bal = __ballot(((x.x | x.y) | (x.z | x.w)) != 0u);
+        }
+    };
+    constexpr int RF = IPS;
+    if (blo >= bhi) return;
+    const int nruns = nw * IPS / RF;
+    const int RLr = (per_block + nruns - 1) / nruns;
+    const int RL = (RLr + RF - 1) / RF;
+    const int ph = lg % RF;
+    const int64_t rlo = blo + (int64_t)((w * IPS + lg) / RF) * RLr;
+    const int runlen = (int)max<int64_t>(0, min<int64_t>(bhi - rlo, RLr));
+    const int len = runlen > ph ? (runlen - ph + RF - 1) / RF : 0;
+    int minlen = len;
+#pragma unroll
+    for (int dlt = LPI; dlt < WAVE; dlt <<= 1) minlen = min(minlen, __shfl_xor(minlen, dlt));
+    minlen = uniform(minlen);
+    const rsrc_t rr = make_rsrc(rec + blo * M4, (uint32_t)((bhi - blo) * (M4 * 4)));
+    const uint32_t first = (uint32_t)(rlo - blo) + (uint32_t)ph;
+    const uint32_t voff = len > 0 ? first * (M4 * 4) : 0u;
+    uint32_t prev0 = 0u;
+    u32v4 top = 0u;
+    auto steps = [&](int i, auto check) {
+        constexpr bool CHECK = decltype(check)::value;
+        uint32_t dw[U][M4];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            uint32_t vo = voff;
+            int so = (i + u) * (RF * M4 * 4);
+            if (CHECK) {
+                vo += (uint32_t)max(0, min(i + u, len - 1)) * (RF * M4 * 4);
+                so = 0;
+            }
+#pragma unroll
+            for (int k2 = 0; k2 < M4; ++k2) dw[u][k2] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rr, (int)vo + 4 * k2, so, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool live = !CHECK || i + u < len;
+            bool fast = false;
+            if (CTX) {
+                const bool differs = live && ((dw[u][0] ^ prev0) & 0xFFFFu) != 0u;
+                fast = __ballot(differs) == 0ull && i + u != 0;
+                prev0 = dw[u][0];
+            }
+            if (!CTX || !fast) top = look(dw[u], 0, 0) + look(dw[u], 0, 1);
+            u32v4 d = top;
+            {
+                // the remaining M - 2 entries, two at a time
+                u32v4 e[M - 2];
+#pragma unroll
+                for (int j = 2; j < M; ++j) e[j - 2] = look(dw[u], j / CPL, j % CPL);
+#pragma unroll
+                for (int j = 0; j < M - 2; j += 2) d = d + e[j] + e[j + 1];
+            }
+            // a sum at or below its bound: (bound + 1) - sum, saturating at zero, is not zero
+            u32v4 x = __builtin_bit_cast(u32v4, __builtin_elementwise_sub_sat(tp1, __builtin_bit_cast(u16x8, d)));
+            if (CHECK && !live) x = 0u;
+            if (__ballot(((x.x | x.y) | (x.z | x.w)) != 0u) != 0ull) emit(x, d, first + (uint32_t)(i + u) * RF);
+        }
+    };
+    int i = 0;
+    for (; i + U <= minlen; i += U) steps(i, std::false_type{});
+    for (; i < RL; i += U) steps(i, std::true_type{});
+    flush();
+}
+
+// ------------------------------------------------------------------------------------------------
 // S4  forest reduction (paper "Encoding Forests": per-tree result arrays summed per vector):
 //     dist(e) = leafp[0][leaf_of[0][e]] + leafp[1][leaf_of[1][e]] + ...   (tree order).
 //     Lane = query; a wave walks consecutive items, each item is T coalesced row reads.
@@ -1646,19 +1877,19 @@ __device__ __forceinline__ void block_inclusive_scan(uint32_t *v, int n, uint32_
 // Smallest 32-bit value v such that at least `rank` of the participating keys are <= v (block of 256
 // threads, most significant digit first, 4 passes of 8 bits).  key(i, v) returns false for entries
 // that do not take part.  Also returns how many keys equal v and how many of those the rank needs.
-// hist: 256 words of LDS, sh: 8 words of LDS.
+// hist: 256 words of LDS, sh: 8 words of LDS.  first_pass: 0, or 2 when every key is below 2^16 (two passes then do).
 template <class KeyFn>
 __device__ __forceinline__ void block_radix_select(int n, uint32_t rank, KeyFn key, uint32_t *hist, uint32_t *sh,
-                                                   uint32_t &value, uint32_t &rank_in_ties, uint32_t &n_ties)
+                                                   uint32_t &value, uint32_t &rank_in_ties, uint32_t &n_ties, int first_pass = 0)
 {
     uint32_t prefix = 0;
-    for (int p = 0, shift = 24; p < 4; ++p, shift -= 8) {
+    for (int p = first_pass, shift = 24 - 8 * first_pass; p < 4; ++p, shift -= 8) {
         hist[threadIdx.x] = 0;
         __syncthreads();
 #pragma unroll 8
         for (int i = threadIdx.x; i < n; i += 256) {
             uint32_t v;
-            if (key(i, v) && (p == 0 || (v >> (shift + 8)) == (prefix >> (shift + 8)))) atomicAdd(&hist[(v >> shift) & 255], 1u);
+            if (key(i, v) && (p == first_pass || (v >> (shift + 8)) == (prefix >> (shift + 8)))) atomicAdd(&hist[(v >> shift) & 255], 1u);
         }
         __syncthreads();
         // the digit at which the running count reaches the rank: a scan over the 256 bins, one bin per thread
@@ -1725,13 +1956,15 @@ struct SelectArgs {
     float *out_dist;         // [nq][k]
     uint32_t *flag;          // [nq]  set to 1 when the query needs the exact kernel
     const float *boff;       // [nq] or nullptr: results are written as boff[q] - value (scalar-product searches)
-    // Candidates from the fixed-point filter (k_lds, FX): the upper word of a candidate is a fixed-point sum, which
-    // orders like the float32 distance up to fx_margin units.  Everything up to the k-th smallest plus that margin
-    // is kept, and the kept items' distances are recomputed in float32 from the tables, associated like the exact
-    // kernel does (assoc_distance), before the final ordering: what is returned is a float32 sum of table entries.
+    // Candidates from a fixed-point filter (k_lds with FX, k_lds16): the upper word of a candidate is a fixed-point
+    // sum, which orders like the float32 distance up to fx_margin units.  First the k-th smallest sum is found; every
+    // candidate up to it plus the margin gets its float32 distance from the tables (associated like the exact kernel
+    // does, assoc_distance) written over the sum, every other candidate +inf; then the selection runs as on float32
+    // candidates: what is ordered and returned is a float32 sum of table entries.
     int allow_short;         // 1: a query with fewer than k vectors among its candidates is complete (they are all
                              // there are): its row is filled up with id -1 and +inf; 0: such a query goes to the exact kernel
     uint32_t fx_margin;      // 0: the upper word is the float32 distance itself
+    int fx_first_pass;       // 2: the fixed-point sums are below 2^16 (see block_radix_select), else 0
     const float *lutT;       // [tiles][M][K][64] tables of this batch
     const uint8_t *codes;    // [items][M]
     const float *term;       // [items] leaf payload or nullptr
@@ -1808,6 +2041,47 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     //    fit, only those with the smallest first ids can matter (ids inside an encoding ascend, so the r
     //    smallest ids of a set of encodings lie in the r encodings with the smallest first id).
     auto first_id = [&](uint32_t e) -> uint32_t { return (uint32_t)a.ids[a.ebegin ? a.ebegin[e] : e]; };
+    bool have_kept = false;
+    if (a.fx_margin != 0) {
+        // fixed-point sums: everything within the margin above the k-th smallest sum may be among the k closest
+        uint32_t cut = 0xFFFFFFFFu;
+        if (c > k) {
+            uint32_t r2, n2;
+            block_radix_select(
+                c, (uint32_t)k, [&](int i, uint32_t &v) { v = (uint32_t)(cand[i] >> 32); return true; }, hist, sel_sh, cut, r2, n2,
+                a.fx_first_pass);
+            cut = cut < 0xFFFFFFFFu - a.fx_margin ? cut + a.fx_margin : 0xFFFFFFFFu;
+        }
+        const float *lq = a.lutT + (int64_t)(ql / QT) * a.M * a.K * QT + (ql % QT);
+        auto lut = [&](int m, int code) -> float { return lq[((int64_t)m * a.K + code) * QT]; };
+        auto float_key = [&](uint32_t e) -> uint64_t {
+            const float dd = assoc_distance(a, lut, a.codes + (int64_t)e * a.M) + (a.term ? a.term[e] : 0.f);
+            return ((uint64_t)__float_as_uint(dd) << 32) | e;
+        };
+        // nearly always the survivors fit the kept list: straight into it
+        if (threadIdx.x == 0) s_c = 0;
+        __syncthreads();
+        for (int i = threadIdx.x; i < c; i += 256) {
+            const uint64_t key = cand[i];
+            if ((uint32_t)(key >> 32) <= cut) {
+                const uint32_t pos = atomicAdd(&s_c, 1u);
+                if (pos < (uint32_t)KEPT_CAP) kept[pos] = float_key((uint32_t)key);
+            }
+        }
+        __syncthreads();
+        have_kept = s_c <= (uint32_t)KEPT_CAP;
+        __syncthreads();
+        if (!have_kept) {
+            // a crowd within the rounding of the k-th sum: the list itself becomes a list of float32 candidates
+            uint64_t *cw = const_cast<uint64_t *>(cand);  // it lives in the call's workspace
+            for (int i = threadIdx.x; i < c; i += 256) {
+                const uint64_t key = cand[i];
+                cw[i] = (uint32_t)(key >> 32) <= cut ? float_key((uint32_t)key) : (0x7F80000000000000ull | (uint32_t)key);
+            }
+            __syncthreads();
+        }
+    }
+    if (!have_kept) {
     uint32_t vstar = 0xFFFFFFFFu, idstar = 0xFFFFFFFFu;
     if (c > 256) {  // more than the sort below should see: cut at the k-th closest first
         const uint32_t rank = (uint32_t)min(k, c);
@@ -1815,7 +2089,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
         block_radix_select(
             c, rank, [&](int i, uint32_t &v) { v = (uint32_t)(cand[i] >> 32); return true; }, hist, sel_sh, vstar,
             rank_in_ties, n_ties);
-        if (a.fx_margin == 0 && rank - rank_in_ties + n_ties > (uint32_t)KEPT_CAP) {
+        if (rank - rank_in_ties + n_ties > (uint32_t)KEPT_CAP) {
             uint32_t r2, n2;
             block_radix_select(
                 c, rank_in_ties,
@@ -1831,8 +2105,6 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     // 2. keep the candidates at or below it, sorted by (distance bits, item)
     if (threadIdx.x == 0) s_c = 0;
     __syncthreads();
-    // fixed-point candidates: everything within the margin above the k-th smallest sum may be among the k closest
-    if (a.fx_margin != 0 && vstar < 0xFFFFFFFFu - a.fx_margin) vstar += a.fx_margin;
 #pragma unroll 8
     for (int i = threadIdx.x; i < c; i += 256) {
         const uint64_t key = cand[i];
@@ -1843,6 +2115,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
         }
     }
     __syncthreads();
+    }
     const int nk = (int)s_c;
     if (nk == 0 && a.allow_short) {  // nothing in reach of this query
         for (int i = threadIdx.x; i < k; i += 256) {
@@ -1854,16 +2127,6 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     if (nk > KEPT_CAP || nk == 0) {
         if (threadIdx.x == 0) a.flag[ql] = 1;
         return;
-    }
-    if (a.fx_margin != 0) {
-        // the float32 distance of every kept item, from the tables of its query
-        const float *lq = a.lutT + (int64_t)(ql / QT) * a.M * a.K * QT + (ql % QT);
-        auto lut = [&](int m, int code) -> float { return lq[((int64_t)m * a.K + code) * QT]; };
-        for (int i = threadIdx.x; i < nk; i += 256) {
-            const uint32_t e = (uint32_t)kept[i];
-            const float dd = assoc_distance(a, lut, a.codes + (int64_t)e * a.M) + (a.term ? a.term[e] : 0.f);
-            kept[i] = ((uint64_t)__float_as_uint(dd) << 32) | e;
-        }
     }
     const int nk2 = pow2_at_least(nk);
     for (int i = nk + threadIdx.x; i < nk2; i += 256) kept[i] = ~0ull;

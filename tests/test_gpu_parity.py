@@ -160,13 +160,14 @@ def test_search(small, mode, T, k, trav):
     assert c.last_fallback_count() == 0
 
 
+@pytest.mark.parametrize("filt", [1, 2])
 @pytest.mark.parametrize("mode,T,k", [(TREE, 1, 1), (TREE, 1, 100), (FOREST, 2, 10), (FOREST, 2, 1000), (FOREST, 4, 100), (FLAT, 1, 100)])
-def test_search_fixed_point_filter(small, dups, mode, T, k):
-    """Option lds_filter = 1: the main pass selects candidates by integer sums of scaled table entries; what is
-    returned are float32 sums recomputed from the float32 tables, held to the same bar as every other search, and
-    bit-identical to the float32 filter's results outside exact-tie handling."""
-    say("search with the fixed-point candidate filter, mode", mode, "T", T, "k", k)
-    c = small.ctx(T=T, sample_min=2048, lds_filter=1)
+def test_search_fixed_point_filter(small, dups, mode, T, k, filt):
+    """Option lds_filter = 1 / 2: the main pass selects candidates by integer sums of scaled table entries (32-bit /
+    16-bit); what is returned are float32 sums recomputed from the float32 tables, held to the same bar as every
+    other search, and bit-identical to the float32 filter's results."""
+    say("search with the fixed-point candidate filter", filt, "mode", mode, "T", T, "k", k)
+    c = small.ctx(T=T, sample_min=2048, lds_filter=filt)
     oi, od = check_search(small, c, mode, k, what="fixed-point m%d T%d k%d" % (mode, T, k))
     assert c.last_fallback_count() == 0
     f = small.ctx(T=T, sample_min=2048, lds_filter=0)
@@ -174,7 +175,7 @@ def test_search_fixed_point_filter(small, dups, mode, T, k):
     torch.cuda.synchronize()
     assert np.array_equal(od, fd.cpu().numpy()) and np.array_equal(oi, fi.cpu().numpy())
     if k <= 100 and mode != FLAT:      # many equal encodings and exact ties
-        cd = dups.ctx(T=T if T <= 2 else 2, sample_min=512, lds_filter=1)
+        cd = dups.ctx(T=T if T <= 2 else 2, sample_min=512, lds_filter=filt)
         check_search(dups, cd, mode if T <= 2 else FOREST, min(k, 50), what="fixed-point dups")
 
 
