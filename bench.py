@@ -34,13 +34,17 @@ LDS_PEAK_GBS = 256 * 256 * 2.4
 # vector float32 operations that are neither packed nor fused: a quarter of the published 157.3 TFLOP/s (which counts
 # two-wide packed fused multiply-adds); a wave instruction takes 4 clocks on its 16-lane SIMD
 VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+CEILINGS = {}   # this run's probe results (measure_ceilings), filled in before the first timed search
 VALU_PEAK_NOTE = "256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz of unpacked, unfused 32-bit vector operations"
 TRAVERSAL_NAMES = {0: "register-context", 1: "level-synchronous", 2: "lds-resident"}
 PATH_NOTES = {
     0: "E-Forest: depth-first leaf order with the distance context in registers, per-tree result tables in HBM summed per encoding",
     1: "E-Forest: level-synchronous kernels over the level arrays, per-tree result tables in HBM summed per encoding",
     2: "sorted distinct encodings scanned with every table slice in LDS and a distance context of two levels; the trees' "
-       "sums are formed per encoding in registers (no per-tree result array); see roofline.lookups_per_query",
+       "sums are formed per encoding in registers (no per-tree result array); see roofline.lookups_per_query.  With "
+       "kernel lds16 in `kernels` the scan that picks candidates runs on 16-bit fixed-point copies of the tables "
+       "(entries rounded down, bound rounded up: nothing at or below the bound is lost) and every returned distance is "
+       "recomputed as the float32 sum of the float32 table entries",
 }
 PAPER_CONTEXT = {              # the paper's own numbers: one Core i7 at 3.6 GHz, one query at a time, SIFT1M, M=8, K=256
     "hardware": "Intel Core i7 3.6 GHz (paper, section Experiments)",
@@ -145,6 +149,7 @@ def algorithmic_bytes(stats, mode, S, tiles):
         Sl = 2 if D0 >= 3 else D0 - 1
         prefixes = (tr0["nI"][Sl - 1] + sum(tr0["nL"][:Sl])) if Sl > 0 else 0
         out["lds"] = tiles * 64 * 4 * (Nd * (M - Sl) + Sl * prefixes)
+        out["lds16"] = out["lds"] // 2      # the same entries as 16-bit ones (k_lds16)
         out["sample"] = tiles * 64 * 4 * S * M
         G = 2
         while M * K * (64 // G) * 4 > 128 * 1024:
@@ -271,7 +276,7 @@ class Workload:
         log("%s T=%d top-%d, %s: %.2f ms/step, %.3e distances/s, %d queries of the last call via the exact kernel"
             % (cfg.name, T, self.k, TRAVERSAL_NAMES[traversal], ms_step, value, fallbacks))
         S = ctx.index_layout().n_sample_enc
-        lds_path = "lds" in prof and prof["lds"][1] > 0
+        lds_path = any(n in prof and prof[n][1] > 0 for n in ("lds", "lds16"))
         ctx_path = traversal != 1 and T <= 4
         alg = algorithmic_bytes(stats, "forest_lds" if lds_path else "forest_ctx" if ctx_path else "forest", S, self.tiles)
         kernels = {}
@@ -287,30 +292,38 @@ class Workload:
             lps = kd["launches_per_step"]
             achieved = kd["alg_GBps"] or 0.0
             traffic, traffic_note = (None, "scaled run") if not self.valid else measured_traffic(cfg.name, dom, TRAVERSAL_NAMES[traversal])
-            if dom == "lds":
-                # bound by the LDS pipe: algorithmic bytes are the 4-byte table entries this kernel reads per query
-                kernel_lookups = alg["lds"] / (self.tiles * 64 * 4)
+            if dom in ("lds", "lds16"):
+                # bound by the LDS pipe and the vector adds behind it: algorithmic bytes are the table entries this kernel
+                # reads from LDS per query, 4 bytes each in k_lds, 2 bytes each in k_lds16
+                eb = 4 if dom == "lds" else 2
+                kernel_lookups = alg[dom] / (self.tiles * 64 * eb)
                 tree_lookups = self.tree_lookups()
                 forest_lookups = sum(t["lookups"] for t in stats["trees"])
                 frac = achieved / LDS_PEAK_GBS
+                ceil = CEILINGS.get("lds_read_b128_scattered_rows_GBps")
                 roofline = {"bound": "alu", "resource": "LDS read bandwidth (on-chip): the kernel is a sequence of 16-byte table reads, "
-                                                        "one add per 4-byte entry", "kernel": dom, "achieved": achieved,
-                            "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": frac, "traffic": traffic, "traffic_note": traffic_note,
+                                                        "one add per %d-byte entry" % eb, "kernel": dom, "entry_bytes": eb,
+                            "achieved": achieved, "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": frac,
+                            "frac_of_measured_ceiling": achieved / ceil if ceil else None,
+                            "measured_ceiling": {"GBps": ceil, "what": "ds_read_b128 of scattered 64-byte rows, this run's probe"} if ceil else None,
+                            "traffic": traffic, "traffic_note": traffic_note,
+                            "lookups_per_s": achieved * 1e9 / eb,
                             # the same time priced on the lookups the paper's single E-Tree needs for this database
                             # (L1 + L2 + postfix lengths): prefixes this kernel recomputes are not useful work
                             "method_frac": frac * tree_lookups / kernel_lookups,
                             "lookups_per_query": {"this_kernel": kernel_lookups, "e_tree": tree_lookups,
                                                   "e_forest_trees": forest_lookups, "flat_distinct": stats["n_distinct"] * stats["M"],
                                                   "flat": stats["N"] * stats["M"]},
-                            "alu": {"achieved": achieved / 4e3, "peak": VALU_PEAK_TOPS, "unit": "Tadd/s",
-                                    "frac": achieved / 4e3 / VALU_PEAK_TOPS,
-                                    "note": "one integer or float32 add per entry against %s" % VALU_PEAK_NOTE}}
+                            "alu": {"achieved": achieved / eb / 1e3, "peak": VALU_PEAK_TOPS * (4 // eb), "unit": "Tadd/s",
+                                    "frac": achieved / eb / 1e3 / (VALU_PEAK_TOPS * (4 // eb)),
+                                    "note": "one add per entry against %s%s" % (VALU_PEAK_NOTE, "" if eb == 4 else
+                                                                               ", two 16-bit entries per 32-bit lane operation")}}
             else:
                 roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_note": traffic_note}
             roofline.update({"alg_bytes_per_launch": alg.get(dom, 0) / lps if lps else None,
                              "avg_launch_ms": kd["ms_per_step"] / lps if lps else None, "launches_per_step": lps})
-            if dom != "lds":
+            if dom not in ("lds", "lds16"):
                 # the traversal as a whole (levels + leaves + reduction): the bandwidth figure of the table-based paths
                 trav = [n for n in ("level", "leaf", "reduce", "sample") if n in kernels]
                 tms = sum(kernels[n]["ms_per_step"] for n in trav)
@@ -571,11 +584,6 @@ def main():
     mode = etf.ETF_MODE_FOREST
     make_ctx = wl.make_ctx
 
-    main_res = wl.measure_search(T, args.traversal, args.steps, args.warmup)
-    got_ids, got_dist = out_ids.cpu().numpy(), out_dist.cpu().numpy()
-    ms_step, value, fallbacks = main_res["ms_per_step"], main_res["value"], main_res["fallbacks"]
-    kernels, roofline, stats, S = main_res["kernels"], main_res["roofline"], main_res["stats"], main_res["S"]
-
     # ---- a plain device copy of known size (the reference dispatch against which the HBM byte counters are
     #      scaled) and the memory ceilings of this card from the library's probe kernels
     copy = ceilings = None
@@ -597,6 +605,13 @@ def main():
         log("device copy of 1 GiB: %.3f ms, %.0f GB/s (read + write)" % (ms, copy["GBps"]))
         del src, dst
         ceilings = measure_ceilings(etf, torch, stream)
+    CEILINGS.clear()
+    CEILINGS.update(ceilings or {})
+
+    main_res = wl.measure_search(T, args.traversal, args.steps, args.warmup)
+    got_ids, got_dist = out_ids.cpu().numpy(), out_dist.cpu().numpy()
+    ms_step, value, fallbacks = main_res["ms_per_step"], main_res["value"], main_res["fallbacks"]
+    kernels, roofline, stats, S = main_res["kernels"], main_res["roofline"], main_res["stats"], main_res["S"]
 
     # ---- the same workload through the other paths, same run
     others = {}
@@ -791,7 +806,7 @@ def main():
         log("parity of the timed output against the oracle: ok on %d queries" % len(picks))
 
     # ---- the other configurations of the workload list, each end to end with its own roofline and parity check
-    if not (args.no_others or args.no_configs) and cfg.name == "cfg2" and wl.valid:
+    if not args.no_configs and cfg.name == "cfg2" and wl.valid:
         del wl, qd, out_ids, out_dist
         torch.cuda.empty_cache()
         for name in [c for c in args.configs.split(",") if c]:
@@ -802,6 +817,8 @@ def main():
         "value": value, "unit": "encoding-distances/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
+        "dtype_note": "returned distances and their order: float32 sums of float32 table entries; the candidate filter "
+                      "(kernel lds16, if listed in `kernels`) adds 16-bit fixed-point entries",
         "config": {"workload": "%s: d=%d N=%d Q=%d PQ M=%d K=%d, E-Forest T=%d, top-%d, seeded %d-component Gaussian mixture"
                                % (cfg.name, cfg.d, N, Q, cfg.M, cfg.K, T, k, cfg.components),
                    "traversal": TRAVERSAL_NAMES[args.traversal], "path": PATH_NOTES[args.traversal],

@@ -97,7 +97,7 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     whole-database selection kernel (testing)
  *   "sample_min" / "sample_scale"   size of the sample that bounds the k-th distance (drawn by
  *                     etf_index_build): max(sample_min, sample_scale * sqrt(n)), n = number of distinct
- *                     encodings (of vectors in flat mode); defaults 32768 and 90
+ *                     encodings (of vectors in flat mode); defaults 32768 and 120
  *   "cand_cap"        per-query candidate capacity (0 = derived from k)
  *   "lds_blocks"      workgroups per sub-tile of queries in the LDS-resident kernels (0 = chosen by the
  *                     library from the number of sub-tiles and items; for experiments)
@@ -131,15 +131,22 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     where the smallest is not clearly below the second smallest (by twice a bound on the
  *                     rounding of either form) the float32 rule is evaluated for all K codewords.  1: the float32
  *                     rule for every codeword (needs d/M <= 128).  Both return the same codes, bit for bit
- *   "lds_filter"      the main pass of searches with traversal 2.  0 (default): float32 sums of the table entries,
- *                     compared with the query's bound.  1: that pass only decides which encodings can be among
- *                     the k nearest, and does so in 32-bit fixed point: every table entry is scaled so that the
- *                     query's bound (from the sample) becomes 2^27, truncated, and cut off at 2^28; sums of
- *                     entries are integer additions, three operands per instruction, compared with the bound
- *                     rounded up.  No encoding whose float32 distance is at or below the bound is lost; the
- *                     distances of the survivors around the k-th are then recomputed as float32 sums of the
- *                     float32 table entries, and those are what is ordered and returned.  A third fewer vector
- *                     instructions in that pass, and the same time: the pass is bound by the LDS reads.
+ *   "lds_filter"      the main pass of searches with traversal 2, which looks at every distinct encoding and only has
+ *                     to decide which of them can be among the k nearest.
+ *                     0: float32 sums of the table entries, compared with the query's bound (from the sample).
+ *                     1: 32-bit fixed point: every table entry is scaled so that the query's bound becomes 2^27,
+ *                     truncated, and cut off at 2^28; sums of entries are integer additions, three operands per
+ *                     instruction, compared with the bound rounded up.
+ *                     2 (default): 16-bit fixed point, for M = 8 and M = 16 at K = 256 without leaf payload (other
+ *                     shapes run as 0): the bound becomes 2^12 (M = 8) or 2^11 (M = 16), entries are truncated and
+ *                     cut off at twice that, so that a sum of M entries fits 16 bits; twice the queries share a
+ *                     workgroup's tables, a 16-byte LDS read serves 8 queries, and the sums are 32-bit additions of
+ *                     two packed entries each, three operands per instruction.
+ *                     With 1 and 2 no encoding whose float32 distance is at or below the bound is lost (entries are
+ *                     rounded down, the bound up); of the survivors, those within the rounding of the k-th smallest
+ *                     sum get their distance recomputed as the float32 sum of the float32 table entries, and those
+ *                     distances are what is ordered and returned.  The recomputation adds in the order of the float32
+ *                     pass, so ids and distances are those of 0, bit for bit.
  * Returns ETF_EINVAL for an unknown name or a value out of range. */
 int etf_set_option(etf_ctx *ctx, const char *name, int64_t value);
 
@@ -414,7 +421,8 @@ enum {
     ETF_K_ENCODE = 10,  /* device encoder (and the coarse assignment of etf_ivf_assign_device) */
     ETF_K_IVF_COARSE = 11, /* IVFADC: distances to the centroids and probe selection */
     ETF_K_IVF_SCAN = 12,   /* IVFADC: scan of the probed lists                        */
-    ETF_K_COUNT = 13
+    ETF_K_LDS16 = 13,      /* tree / forest candidate filter on 16-bit tables in LDS  */
+    ETF_K_COUNT = 14
 };
 /* on != 0: every later kernel launch of this context is bracketed by a pair of
  * HIP events on the context's stream. */

@@ -30,7 +30,7 @@ EXPORTS = [
 ]
 ETF_PROBE_READ, ETF_PROBE_WRITE, ETF_PROBE_COPY, ETF_PROBE_ROWS, ETF_PROBE_LDS, ETF_PROBE_LDS_SCATTER = 0, 1, 2, 3, 4, 5
 KERNEL_CLASSES = ["lut", "level", "leaf", "flat", "reduce", "tau", "select", "exact", "sample", "lds", "encode",
-                  "ivf_coarse", "ivf_scan"]
+                  "ivf_coarse", "ivf_scan", "lds16"]
 
 
 class EtfStats(ctypes.Structure):

@@ -733,7 +733,7 @@ int launch_lds16(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int
     dim3 grid((unsigned)bx, (unsigned)(G / 2), (unsigned)tiles);
     hipStream_t st = (hipStream_t)ctx->stream;
     const float *lutT = reinterpret_cast<const float *>(ws + P.o_lutT);
-    ProfScope prof(ctx, ETF_K_LDS);
+    ProfScope prof(ctx, ETF_K_LDS16);
     int rc;
     if (M == 8) {
         if ((rc = set_lds(ctx, k_lds16<4, 2, true>, lds))) return rc;

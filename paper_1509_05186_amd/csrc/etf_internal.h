@@ -118,7 +118,7 @@ struct Options {
     int64_t ws_cap_bytes = (int64_t)8 << 30;
     int64_t force_fallback = 0;
     int64_t sample_min = 32768;
-    int64_t sample_scale = 90;  // sample size = max(sample_min, sample_scale * sqrt(n))
+    int64_t sample_scale = 120; // sample size = max(sample_min, sample_scale * sqrt(n))
     int64_t cand_cap = 0;
     int64_t traversal = 2;  // 0: distance context in registers, 1: level-synchronous kernels, 2: searches with all tables in LDS
     int64_t lds_blocks = 0; // workgroups per sub-tile of queries in the LDS-resident search kernel (0: chosen by the library)

@@ -132,7 +132,7 @@ def test_device_build_sample_sizes_and_spread():
     c, img = dev_ctx(np.zeros((M, K, 1), dtype=np.float32), codes, None, T=2, sample_min=1000)
     st, lay, se, sp = check_image(c, img, codes, None)
     Nd = st["n_distinct"]
-    assert len(se) == int(90 * np.sqrt(Nd)) and len(sp) == int(90 * np.sqrt(N))
+    assert len(se) == int(120 * np.sqrt(Nd)) and len(sp) == int(120 * np.sqrt(N))   # the default sample_scale
     # one draw from each of len(se) equal strata of the sorted encodings, in scattered order
     srt, s = np.sort(se.astype(np.int64)), np.arange(len(se), dtype=np.int64)
     assert np.all(srt >= s * Nd // len(se)) and np.all(srt < (s + 1) * Nd // len(se))

@@ -216,9 +216,12 @@ def test_builder_sampling_on_larger_input():
     st, lay, buf = c.index_stats(), c.index_layout(), c.index_export()
     se = arr(buf, lay.sample_enc, lay.n_sample_enc, np.uint32)
     sp = arr(buf, lay.sample_pos, lay.n_sample_pos, np.uint32)
-    want_e, want_p = 90 * np.sqrt(st["n_distinct"]), 90 * np.sqrt(N)         # sample_scale * sqrt(n), duplicates of the draw removed
-    assert 0.9 * want_e <= len(se) <= want_e + 1 and se.max() < st["n_distinct"]
-    assert 0.9 * want_p <= len(sp) <= want_p + 1 and sp.max() < N
+    # sample_scale * sqrt(n) draws with the default scale of 120; repeats of the draw are removed, which leaves
+    # n (1 - exp(-draws / n)) of them on average
+    for got, n in ((se, st["n_distinct"]), (sp, N)):
+        draws = 120 * np.sqrt(n)
+        left = n * (1 - np.exp(-draws / n))
+        assert 0.97 * left <= len(got) <= min(draws + 1, 1.03 * left) and got.max() < n
     assert len(np.unique(se)) == len(se) and len(np.unique(sp)) == len(sp)
     assert not np.all(np.diff(se.astype(np.int64)) > 0)       # stored in random order
     lut = rng.random((M, K))
