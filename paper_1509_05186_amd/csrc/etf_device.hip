@@ -726,7 +726,7 @@ int launch_lds16(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int
     if (nitems == 0) return ETF_OK;
     const int M = ctx->M, K = ctx->K;
     const int G = std::max(2, pick_G(M, K));
-    const size_t lds = lds_table_bytes(G, M, K) + lds_aux_bytes(true);
+    const size_t lds = lds_table_bytes(G, M, K) + lds16_aux_bytes();
     int64_t bx = lds_blocks_for(tiles * (G / 2), nitems, (nitems >> 25) + 1);
     if (ctx->opt.lds_blocks > 0) bx = std::max<int64_t>(ctx->opt.lds_blocks, (nitems >> 25) + 1);
     const int per_block = (int)((nitems + bx - 1) / bx);

@@ -1059,6 +1059,9 @@ __host__ __device__ inline size_t lds_table_bytes(int G, int M, int K)
     return (size_t)(M / CPL) * lds_lines_per_group(G, K) * (size_t)(CPL * (WAVE / G) * 4);
 }
 __host__ __device__ inline size_t lds_aux_bytes(bool filter) { return filter ? (size_t)16 * LDS_RING * 8 + 2 * 16 * 64 * 4 : 0; }
+// k_lds16: a ring entry is a lane's eight results (16 bytes) and a word that says whose they are
+constexpr int LDS16_RING = 76;
+__host__ __device__ inline size_t lds16_aux_bytes() { return (size_t)16 * LDS16_RING * 20 + 2 * 16 * 64 * 4; }
 
 typedef __attribute__((address_space(3))) const vecq lds_vecq_t;
 
@@ -1409,7 +1412,7 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
 //     is ordered and returned (see SelectArgs::fx_margin).
 //     Geometry, item walk, distance context and line layout are those of k_lds<G> (rows of 64 or 32 bytes, lines
 //     of 256 bytes, chunk order rotated per lane group); a sub-tile has 128 / G queries.
-//     grid (blocks, G / 2, tiles), block 1024, dynamic LDS lds_table_bytes(G) + lds_aux_bytes(true); G in {4, 8}.
+//     grid (blocks, G / 2, tiles), block 1024, dynamic LDS lds_table_bytes(G) + lds16_aux_bytes(); G in {4, 8}.
 // ------------------------------------------------------------------------------------------------
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) const u16x8 lds_u16x8_t;
@@ -1421,7 +1424,7 @@ __global__ __launch_bounds__(1024) void k_lds16(const uint32_t *__restrict__ rec
                                                 int K, int per_block, OutArgs o)
 {
     constexpr int M = 4 * M4, Qs = 2 * WAVE / G, V = 8, LPI = Qs / V, IPS = WAVE / LPI;
-    constexpr int CPL = lds_chunks_per_line(G), NG = M / CPL, U = M4 >= 4 ? 2 : 4, RING = LDS_RING;
+    constexpr int CPL = lds_chunks_per_line(G), NG = M / CPL, U = M4 >= 4 ? 2 : 4, RING = LDS16_RING;
     constexpr int CB = fx16_cap_bits(M);
     constexpr uint32_t CAP = (1u << CB) - 1u;
     constexpr float TOP = (float)(1u << (CB - 1));
@@ -1429,9 +1432,11 @@ __global__ __launch_bounds__(1024) void k_lds16(const uint32_t *__restrict__ rec
     extern __shared__ float lds[];
     constexpr uint32_t rowB = Qs * 2, lineB = CPL * rowB, KP = 256;
     char *aux = reinterpret_cast<char *>(lds) + (size_t)NG * KP * lineB;
-    uint64_t(*ring)[RING] = reinterpret_cast<uint64_t(*)[RING]>(aux);
-    uint32_t(*wcount)[64] = reinterpret_cast<uint32_t(*)[64]>(aux + 16 * RING * 8);
-    uint32_t(*wpos)[64] = reinterpret_cast<uint32_t(*)[64]>(aux + 16 * RING * 8 + 16 * 64 * 4);
+    typedef uint32_t u32v4 __attribute__((ext_vector_type(4)));
+    u32v4(*ringx)[RING] = reinterpret_cast<u32v4(*)[RING]>(aux);
+    uint32_t(*ringm)[RING] = reinterpret_cast<uint32_t(*)[RING]>(aux + 16 * RING * 16);
+    uint32_t(*wcount)[64] = reinterpret_cast<uint32_t(*)[64]>(aux + 16 * RING * 20);
+    uint32_t(*wpos)[64] = reinterpret_cast<uint32_t(*)[64]>(aux + 16 * RING * 20 + 16 * 64 * 4);
     const int tile = blockIdx.z, sub = blockIdx.y;
     const int lane = threadIdx.x & 63;
     const int w = uniform(threadIdx.x >> 6), nw = blockDim.x >> 6;
@@ -1496,7 +1501,6 @@ __global__ __launch_bounds__(1024) void k_lds16(const uint32_t *__restrict__ rec
     const bool cross = CPL == 8 && (jr & 4) != 0;
     // a lane's 16 bytes are eight 16-bit entries, added as four dwords: no half can carry into its neighbour because
     // a sum of M capped entries stays below 2^16, and three dwords add in one instruction
-    typedef uint32_t u32v4 __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) const u32v4 lds_u32v4_t;
     auto look = [&](const uint32_t dw[M4], int g, int t) -> u32v4 {
         uint32_t src;
@@ -1518,50 +1522,58 @@ __global__ __launch_bounds__(1024) void k_lds16(const uint32_t *__restrict__ rec
         const float scale = TOP / fmaxf(t, 8.0779e-28f);
         tp1[v] = (t >= 0.f) ? (unsigned short)(min((uint32_t)fminf(t * scale * (1.f + 1.9073486e-6f), 60000.f), 60000u) + 2u) : (unsigned short)0;
     }
+    // Candidates.  x holds, per query of the lane, bound + 1 - sum where the sum is at or below the bound, else 0 (four
+    // dwords of two halves).  The loop over the items only parks what it finds: a lane with a non-zero half puts all of x
+    // and (its lane number, the item) into the wave's ring, slot = its rank among such lanes.  When the next step's
+    // entries might not fit, the wave takes the ring apart, all lanes at once: the non-zero halves are counted per
+    // query (LDS atomics), the wave reserves that many slots of each query's list with one global atomic per query,
+    // and every half is written as (sum, item), the sum being its owner's bound + 1 minus the half.
+    const u32v4 tp1w = __builtin_bit_cast(u32v4, tp1);
     int held = 0;
     auto flush = [&]() {
-        const uint32_t c = wcount[w][lane];
-        wpos[w][lane] = c ? atomicAdd(&o.cnt[(int64_t)tile * QT + lane], c) : 0u;
+        auto each_half = [&](auto f) {
+            for (int base = 0; base < held; base += 64) {  // every lane goes round: the bounds come from other lanes
+                const bool valid = base + lane < held;
+                const int i = valid ? base + lane : 0;
+                const u32v4 x = ringx[w][i];
+                const uint32_t meta = ringm[w][i];
+                const int src = (int)(meta >> 26);
+                const int c0 = sub * Qs + (src % LPI) * V;  // the owner's first query inside the tile
+                u32v4 t;
+                t.x = (uint32_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)tp1w.x);
+                t.y = (uint32_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)tp1w.y);
+                t.z = (uint32_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)tp1w.z);
+                t.w = (uint32_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)tp1w.w);
+#pragma unroll
+                for (int h = 0; h < 8; ++h) {
+                    const uint32_t xh = (x[h >> 1] >> (16 * (h & 1))) & 0xFFFFu;
+                    const uint32_t th = (t[h >> 1] >> (16 * (h & 1))) & 0xFFFFu;
+                    if (valid && xh != 0u) f(c0 + h, th - xh, meta & 0x3FFFFFFu);
+                }
+            }
+        };
+        each_half([&](int c, uint32_t, uint32_t) { atomicAdd(&wcount[w][c], 1u); });
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t cq = wcount[w][lane];
+        wpos[w][lane] = cq ? atomicAdd(&o.cnt[(int64_t)tile * QT + lane], cq) : 0u;
         wcount[w][lane] = 0u;
         __builtin_amdgcn_wave_barrier();
-        for (int i = lane; i < held; i += 64) {
-            const uint64_t e = ring[w][i];
-            const int owner = (int)((e >> 26) & 63u);
-            const uint32_t pos = atomicAdd(&wpos[w][owner], 1u);
-            const int64_t q = (int64_t)tile * QT + owner;
-            if (pos < o.C)
-                o.cand[q * o.C + pos] = (e & 0xFFFFFFFF00000000ull) | (uint32_t)(blo + (int64_t)(e & 0x3FFFFFFull));
-        }
+        each_half([&](int c, uint32_t val, uint32_t rel) {
+            const uint32_t pos = atomicAdd(&wpos[w][c], 1u);
+            if (pos < o.C) o.cand[((int64_t)tile * QT + c) * o.C + pos] = ((uint64_t)val << 32) | (uint32_t)(blo + (int64_t)rel);
+        });
         __builtin_amdgcn_wave_barrier();
         held = 0;
     };
-    // x: per query of the lane, bound + 1 - sum where the sum is at or below the bound, else 0 (four dwords of two
-    // halves).  The lanes that hold a non-zero half put one candidate each into the wave's ring (slot = rank among
-    // those lanes) and clear that half; nearly always that empties x everywhere, otherwise the wave goes round again.
-    auto emit = [&](u32v4 x, const u32v4 &dd, uint32_t rel) {
-        uint64_t bal = __ballot(((x.x | x.y) | (x.z | x.w)) != 0u);
-        while (bal != 0ull) {
-            const int rank = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
-            if (((x.x | x.y) | (x.z | x.w)) != 0u) {
-                // first non-zero half: dword j, half h
-                const int j = x.x != 0u ? 0 : x.y != 0u ? 1 : x.z != 0u ? 2 : 3;
-                const uint32_t xw = j == 0 ? x.x : j == 1 ? x.y : j == 2 ? x.z : x.w;
-                const uint32_t dw2 = j == 0 ? dd.x : j == 1 ? dd.y : j == 2 ? dd.z : dd.w;
-                const int h = (xw & 0xFFFFu) != 0u ? 0 : 1;
-                const uint32_t val = h ? dw2 >> 16 : dw2 & 0xFFFFu;
-                const int c = col + 2 * j + h;
-                ring[w][held + rank] = ((uint64_t)val << 32) | ((uint32_t)c << 26) | rel;
-                atomicAdd(&wcount[w][c], 1u);
-                const uint32_t keep = h ? 0x0000FFFFu : 0xFFFF0000u;
-                x.x = j == 0 ? x.x & keep : x.x;
-                x.y = j == 1 ? x.y & keep : x.y;
-                x.z = j == 2 ? x.z & keep : x.z;
-                x.w = j == 3 ? x.w & keep : x.w;
-            }
-            held += __popcll(bal);
-            if (held > RING - 64) flush();
-            bal = __ballot(((x.x | x.y) | (x.z | x.w)) != 0u);
+    auto emit = [&](const u32v4 &x, uint64_t bal, uint32_t rel) {
+        const int n = __popcll(bal);
+        if (held + n > RING) flush();
+        if (((x.x | x.y) | (x.z | x.w)) != 0u) {
+            const int slot = held + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+            ringx[w][slot] = x;
+            ringm[w][slot] = ((uint32_t)lane << 26) | rel;
         }
+        held += n;
     };
     constexpr int RF = IPS;
     if (blo >= bhi) return;
@@ -1617,7 +1629,8 @@ __global__ __launch_bounds__(1024) void k_lds16(const uint32_t *__restrict__ rec
             // a sum at or below its bound: (bound + 1) - sum, saturating at zero, is not zero
             u32v4 x = __builtin_bit_cast(u32v4, __builtin_elementwise_sub_sat(tp1, __builtin_bit_cast(u16x8, d)));
             if (CHECK && !live) x = 0u;
-            if (__ballot(((x.x | x.y) | (x.z | x.w)) != 0u) != 0ull) emit(x, d, first + (uint32_t)(i + u) * RF);
+            const uint64_t bal = __ballot(((x.x | x.y) | (x.z | x.w)) != 0u);
+            if (bal != 0ull) emit(x, bal, first + (uint32_t)(i + u) * RF);
         }
     };
     int i = 0;
