@@ -735,12 +735,19 @@ int launch_lds16(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int
     const float *lutT = reinterpret_cast<const float *>(ws + P.o_lutT);
     ProfScope prof(ctx, ETF_K_LDS16);
     int rc;
-    if (M == 8) {
+    const bool cx = ctx->opt.lds16_context != 0;
+    if (M == 8 && cx) {
         if ((rc = set_lds(ctx, k_lds16<4, 2, true>, lds))) return rc;
         hipLaunchKernelGGL((k_lds16<4, 2, true>), grid, dim3(1024), lds, st, rec, nitems, lutT, K, per_block, o);
-    } else if (M == 16) {
+    } else if (M == 8) {
+        if ((rc = set_lds(ctx, k_lds16<4, 2, false>, lds))) return rc;
+        hipLaunchKernelGGL((k_lds16<4, 2, false>), grid, dim3(1024), lds, st, rec, nitems, lutT, K, per_block, o);
+    } else if (M == 16 && cx) {
         if ((rc = set_lds(ctx, k_lds16<8, 4, true>, lds))) return rc;
         hipLaunchKernelGGL((k_lds16<8, 4, true>), grid, dim3(1024), lds, st, rec, nitems, lutT, K, per_block, o);
+    } else if (M == 16) {
+        if ((rc = set_lds(ctx, k_lds16<8, 4, false>, lds))) return rc;
+        hipLaunchKernelGGL((k_lds16<8, 4, false>), grid, dim3(1024), lds, st, rec, nitems, lutT, K, per_block, o);
     } else {
         return fail(ctx, ETF_EINVAL, "no 16-bit filter kernel for M=%d", M);
     }
@@ -945,7 +952,8 @@ extern "C" int64_t etf_encode_workspace_bytes(const etf_ctx *ctx)
 {
     if (!ctx) return ETF_EINVAL;
     if (ctx->codebooks.empty()) return fail(ctx, ETF_ESTATE, "no codebooks: call etf_pq_train or etf_pq_set_codebooks first");
-    return (int64_t)((ctx->codebooks.size() * sizeof(float) + 255) & ~(size_t)255);
+    // the codebooks, then per group 256 halved squared norms and the largest norm (k_encode_norms)
+    return (int64_t)((ctx->codebooks.size() * sizeof(float) + 255) & ~(size_t)255) + (int64_t)(((size_t)ctx->M * 257 * sizeof(float) + 255) & ~(size_t)255);
 }
 
 extern "C" int etf_pq_encode_device(etf_ctx *ctx, const float *x, int64_t n, uint8_t *codes_out, void *ws, int64_t ws_bytes)
@@ -968,6 +976,30 @@ extern "C" int etf_pq_encode_device(etf_ctx *ctx, const float *x, int64_t n, uin
     const float *cb = reinterpret_cast<const float *>(ws);
     if (mfma) {
         ProfScope prof(ctx, ETF_K_ENCODE);
+        const bool aligned = (ds & 3) == 0 && (d & 3) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+        if (aligned && ds <= 64 && K <= 256) {
+            float *cc2 = reinterpret_cast<float *>((char *)ws + ((ctx->codebooks.size() * sizeof(float) + 255) & ~(size_t)255));
+            hipLaunchKernelGGL(k_encode_norms, dim3((unsigned)M), dim3(256), 0, st, cb, ds, K, M, cc2);
+            // operands staged in LDS in instruction order; stretches of 128 vectors per workgroup, as many as leave
+            // about eight workgroups per compute unit
+            const int64_t chunks = (n + 127) / 128;
+            const int reps = (int)std::max<int64_t>(1, std::min<int64_t>(16, chunks * M / 2048));
+            const dim3 grid((unsigned)((chunks + reps - 1) / reps), (unsigned)M);
+#define TC_CASE(RL, NB)                                                                                        \
+    {                                                                                                         \
+        const size_t lds = (size_t)256 * NB * 2 * RL * 4;                                                     \
+        int rc2 = set_lds(ctx, k_encode_tc<RL, NB>, lds);                                                     \
+        if (rc2) return rc2;                                                                                  \
+        hipLaunchKernelGGL((k_encode_tc<RL, NB>), grid, dim3(256), lds, st, x, n, d, ds, K, M, cb, cc2, codes_out, reps); \
+    }
+            if (ds <= 8) TC_CASE(4, 1)
+            else if (ds <= 16) TC_CASE(8, 1)
+            else if (ds <= 32) TC_CASE(8, 2)
+            else TC_CASE(8, 4)
+#undef TC_CASE
+            LAUNCH_CHECK(ctx, "k_encode_tc");
+            return ETF_OK;
+        }
         hipLaunchKernelGGL(k_encode_mfma, dim3((unsigned)((n + 255) / 256), (unsigned)M), dim3(256), 0, st, x, n, d, ds, K, M, cb, codes_out);
         LAUNCH_CHECK(ctx, "k_encode_mfma");
         return ETF_OK;

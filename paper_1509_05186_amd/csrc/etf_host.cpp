@@ -386,6 +386,9 @@ extern "C" int etf_set_option(etf_ctx *ctx, const char *name, int64_t value)
     } else if (n == "lut_kernel") {
         if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "lut_kernel must be 0 (matrix cores) or 1 (plain sums)");
         ctx->opt.lut_kernel = value;
+    } else if (n == "lds16_context") {
+        if (value < 0 || value > 1) return fail(ctx, ETF_EINVAL, "lds16_context is 0 or 1");
+        ctx->opt.lds16_context = (int)value;
     } else if (n == "lds_blocks") {
         if (value < 0 || value > 65535) return fail(ctx, ETF_EINVAL, "lds_blocks out of range");
         ctx->opt.lds_blocks = value;

@@ -121,6 +121,7 @@ struct Options {
     int64_t sample_scale = 120; // sample size = max(sample_min, sample_scale * sqrt(n))
     int64_t cand_cap = 0;
     int64_t traversal = 2;  // 0: distance context in registers, 1: level-synchronous kernels, 2: searches with all tables in LDS
+    int lds16_context = 1;  // k_lds16 keeps a distance context of two levels (1) or looks every chunk up (0)
     int64_t lds_blocks = 0; // workgroups per sub-tile of queries in the LDS-resident search kernel (0: chosen by the library)
     int64_t metric = 0;     // 0: squared Euclidean distance (smallest first), 1: scalar product (largest first)
     int64_t lds_filter = 2; // main pass of the LDS-resident search: 0 float32 sums, 1 / 2 candidate filter in 32 / 16-bit fixed point

@@ -610,7 +610,7 @@ __global__ __launch_bounds__(256) void k_encode(const float *__restrict__ x, int
 //     two smallest and the index of the smallest.
 //     grid (ceil(n / 256), M), block 256, K <= 256.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_encode_mfma(const float *__restrict__ x, int64_t n, int d, int ds, int K, int M,
+__global__ __launch_bounds__(256, 2) void k_encode_mfma(const float *__restrict__ x, int64_t n, int d, int ds, int K, int M,
                                                      const float *__restrict__ cb, uint8_t *__restrict__ codes)
 {
     __shared__ float s_cc[256];
@@ -773,6 +773,181 @@ __global__ __launch_bounds__(256) void k_encode_mfma(const float *__restrict__ x
                 }
             }
             if (lane == 0) codes[v * M + m] = (uint8_t)best;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// The matrix-core assignment again, laid out for the instruction rather than for the arrays (aligned rows, groups of at
+//     most 64 dimensions; everything else takes k_encode_mfma).  A workgroup stages its group's codewords in LDS once,
+//     already in operand order: for every tile of 32 codewords and every block of 2 RL dimensions, lane (codeword,
+//     half) finds its RL consecutive values side by side (one or two 16-byte reads).  A wave then takes 32 vectors at a
+//     time, loads their values of the group once (the other operand, NB x RL registers), and walks the 8 tiles with
+//     one accumulator block, which starts at -||c||^2 / 2: the largest x.c - ||c||^2 / 2 is the smallest
+//     ||c||^2 - 2 x.c, exactly (a factor of -2), so the two largest values and the index of the largest are kept with
+//     four instructions per value and the bound of k_encode_mfma applies to the difference of the two largest as E.
+//     Near-ties go through the float32 rule as there; the codes are k_encode's, bit for bit.
+//     cc2: from k_encode_norms.  grid (ceil(n / (128 reps)), M), block 256, dynamic LDS 256 * NB * 2 RL * 4 bytes.
+// ------------------------------------------------------------------------------------------------
+// -0.5 ||c||^2 of every codeword (-3e38 beyond K) as cc2[M][256], and the largest ||c||^2 of every group as
+// cc2[M * 256 + m]: what k_encode_tc starts its accumulators from.  grid (M), block 256.
+__global__ __launch_bounds__(256) void k_encode_norms(const float *__restrict__ cb, int ds, int K, int M, float *__restrict__ cc2)
+{
+    __shared__ float s_mx[4];
+    const int m = blockIdx.x, t = threadIdx.x;
+    const float *c = cb + ((int64_t)m * K + t) * ds;
+    float cc = 0.f;
+    if (t < K)
+        for (int j = 0; j < ds; ++j) cc = fmaf(c[j], c[j], cc);
+    cc2[m * 256 + t] = t < K ? -0.5f * cc : -3.0e38f;
+    float mx = t < K ? cc : 0.f;
+#pragma unroll
+    for (int dlt = 32; dlt > 0; dlt >>= 1) mx = fmaxf(mx, __shfl_xor(mx, dlt));
+    if ((t & 63) == 0) s_mx[t >> 6] = mx;
+    __syncthreads();
+    if (t == 0) cc2[M * 256 + m] = fmaxf(fmaxf(s_mx[0], s_mx[1]), fmaxf(s_mx[2], s_mx[3]));
+}
+
+template <int RL, int NB>
+__global__ __launch_bounds__(256, 2) void k_encode_tc(const float *__restrict__ x, int64_t n, int d, int ds, int K, int M,
+                                                      const float *__restrict__ cb, const float *__restrict__ cc2, uint8_t *__restrict__ codes, int reps)
+{
+    extern __shared__ float enc_lds[];  // [8 tiles][NB][64 lanes][RL]
+    __shared__ __align__(16) float s_cc2[256];
+    constexpr int DSP = NB * 2 * RL;
+    const int m = blockIdx.y;
+    const int lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6);
+    const int col = lane & 31, half = lane >> 5;
+    const float *cbm = cb + (int64_t)m * K * ds;
+    for (int idx = threadIdx.x; idx < 256 * DSP; idx += 256) {
+        const int k = idx / DSP, j = idx % DSP;
+        const int blk = j / (2 * RL), hf = (j / RL) & 1, i = j % RL;
+        enc_lds[((((k >> 5) * NB + blk) * 64) + hf * 32 + (k & 31)) * RL + i] = (k < K && j < ds) ? cbm[(int64_t)k * ds + j] : 0.f;
+    }
+    s_cc2[threadIdx.x] = cc2[m * 256 + threadIdx.x];
+    __syncthreads();
+    const float ccmax = cc2[M * 256 + m];
+    const float eps = 8.f * (float)(ds + 2) * 5.9604645e-8f;
+    const int tiles = (K + 31) >> 5;
+    for (int rep = 0; rep < reps; ++rep) {
+        const int64_t v0 = ((int64_t)blockIdx.x * reps + rep) * 128 + w * 32;
+        if (v0 >= n) return;
+        const int64_t v = v0 + col;
+        const bool live = v < n;
+        const float *xrow = x + (live ? v : 0) * d + (int64_t)m * ds;
+        float b[NB][RL];
+        float xx = 0.f;
+#pragma unroll
+        for (int blk = 0; blk < NB; ++blk)
+#pragma unroll
+            for (int q4 = 0; q4 < RL / 4; ++q4) {
+                const int j = blk * 2 * RL + half * RL + 4 * q4;
+                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (live && j + 4 <= ds) t = *reinterpret_cast<const float4 *>(xrow + j);
+                b[blk][4 * q4 + 0] = t.x;
+                b[blk][4 * q4 + 1] = t.y;
+                b[blk][4 * q4 + 2] = t.z;
+                b[blk][4 * q4 + 3] = t.w;
+                xx = fmaf(t.x, t.x, fmaf(t.y, t.y, fmaf(t.z, t.z, fmaf(t.w, t.w, xx))));
+            }
+        // the largest value so far, the second largest, and where the largest is: tile and accumulator register
+        float v1 = -3.0e38f, v2 = -3.0e38f;
+        int k1t = 0, k1r = 0;
+        const float inf = __uint_as_float(0x7F800000u);
+        auto start = [&](int tile, floatx16 &acc) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 c4 = *reinterpret_cast<const float4 *>(&s_cc2[tile * 32 + 8 * g + 4 * half]);
+                acc[4 * g + 0] = c4.x;
+                acc[4 * g + 1] = c4.y;
+                acc[4 * g + 2] = c4.z;
+                acc[4 * g + 3] = c4.w;
+            }
+            const float *ap = enc_lds + ((int64_t)tile * NB * 64 + lane) * RL;
+#pragma unroll
+            for (int blk = 0; blk < NB; ++blk) {
+                float a[RL];
+#pragma unroll
+                for (int q4 = 0; q4 < RL / 4; ++q4) {
+                    const float4 t = *reinterpret_cast<const float4 *>(ap + blk * 64 * RL + 4 * q4);
+                    a[4 * q4 + 0] = t.x;
+                    a[4 * q4 + 1] = t.y;
+                    a[4 * q4 + 2] = t.z;
+                    a[4 * q4 + 3] = t.w;
+                }
+#pragma unroll
+                for (int i = 0; i < RL; ++i) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[blk][i], acc, 0, 0, 0);
+            }
+        };
+        auto finish = [&](int tile, const floatx16 &acc) {
+            const float before = v1;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float val = acc[r];
+                k1r = val > v1 ? r : k1r;
+                v2 = __builtin_amdgcn_fmed3f(val, v1, v2);   // v1 >= v2: the median is the new second largest
+                v1 = __builtin_amdgcn_fmed3f(val, v1, inf);  // the larger of the two
+            }
+            k1t = v1 != before ? tile : k1t;
+        };
+        // (taking turns between two accumulator blocks, with the vector work on one tile's values scheduled between the
+        // matrix instructions of the next, gained 4 % on a million vectors per call and lost 8 % on 131 072: float32
+        // matrix instructions and vector instructions share the SIMD's issue, so there is little to overlap)
+        for (int tile = 0; tile < tiles; ++tile) {
+            floatx16 acc;
+            start(tile, acc);
+            finish(tile, acc);
+        }
+        // accumulator register r of lane l: codeword 32 tile + 8 (r / 4) + 4 (l / 32) + r % 4, vector l % 32
+        int k1 = k1t * 32 + 8 * (k1r >> 2) + 4 * half + (k1r & 3);
+        // the two halves of the wave saw different codewords of the same vectors
+        {
+            const float o1 = __shfl_xor(v1, 32), o2 = __shfl_xor(v2, 32);
+            const int ok = __shfl_xor(k1, 32);
+            xx += __shfl_xor(xx, 32);
+            const float lo = fminf(v1, o1);
+            if (o1 > v1 || (o1 == v1 && ok < k1)) k1 = ok;
+            v1 = fmaxf(v1, o1);
+            v2 = fmaxf(lo, fmaxf(v2, o2));
+        }
+        const float E = eps * (xx + ccmax);
+        const bool hard = live && !(v1 - v2 > E);
+        if (half == 0 && live && !hard) codes[v * M + m] = (uint8_t)k1;
+        // near-ties: the float32 rule itself for every codeword, the wave's lanes taking codewords lane, lane + 64, ...
+        uint64_t todo = __ballot(hard && half == 0);
+        while (todo != 0ull) {
+            const int src = __ffsll((unsigned long long)todo) - 1;
+            todo &= todo - 1;
+            const int64_t vh = v0 + src;
+            const float *xv = x + vh * d + (int64_t)m * ds;
+            float bestd = 3.402823466e+38f;
+            int best = 0x7FFFFFFF;
+            for (int k = lane; k < K; k += 64) {
+                const float *c = cbm + (int64_t)k * ds;
+                float sacc = 0.f;
+                {
+#pragma clang fp contract(off)
+                    for (int j = 0; j < ds; ++j) {
+                        const float t = xv[j] - c[j];
+                        const float pr = t * t;
+                        sacc = sacc + pr;
+                    }
+                }
+                if (sacc < bestd) {  // ascending k inside a lane: the first minimum stays
+                    bestd = sacc;
+                    best = k;
+                }
+            }
+#pragma unroll
+            for (int dlt = 32; dlt > 0; dlt >>= 1) {
+                const float od = __shfl_xor(bestd, dlt);
+                const int ob = __shfl_xor(best, dlt);
+                if (od < bestd || (od == bestd && ob < best)) {
+                    bestd = od;
+                    best = ob;
+                }
+            }
+            if (lane == 0) codes[vh * M + m] = (uint8_t)best;
         }
     }
 }

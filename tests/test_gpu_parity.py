@@ -179,6 +179,26 @@ def test_search_fixed_point_filter(small, dups, mode, T, k, filt):
         check_search(dups, cd, mode if T <= 2 else FOREST, min(k, 50), what="fixed-point dups")
 
 
+@pytest.mark.parametrize("context", [0, 1])
+@pytest.mark.parametrize("M", [8, 16])
+def test_search_sixteen_bit_filter_shapes(small, M, context):
+    """The 16-bit filter kernel in both of its shapes (8 chunks: rows of 64 bytes; 16 chunks: rows of 32 bytes, two-word
+    records), with and without its distance context: the bar of every other search, and the float32 filter's bits."""
+    say("16-bit candidate filter, M", M, "context", context)
+    p = small if M == 8 else Problem(d=32, M=16, K=256, N=20000, Q=150, ntrain=4000, seed=15)
+    for T, k in ((1, 10), (M // 4, 100)):
+        c = p.ctx(T=T, sample_min=2048, lds_filter=2, lds16_context=context)
+        mode = TREE if T == 1 else FOREST
+        c.profile_enable(True)
+        oi, od = check_search(p, c, mode, k, what="16-bit filter M%d T%d ctx%d" % (M, T, context))
+        assert c.last_fallback_count() == 0
+        assert c.profile_read()["lds16"][1] > 0          # the kernel this test is about did run
+        f = p.ctx(T=T, sample_min=2048, lds_filter=0)
+        fi, fd = f.search(torch.from_numpy(p.q).cuda(), k, mode)
+        torch.cuda.synchronize()
+        assert np.array_equal(od, fd.cpu().numpy()) and np.array_equal(oi, fi.cpu().numpy())
+
+
 @pytest.mark.parametrize("mode,T", [(FLAT, 1), (FOREST, 2)])
 def test_search_large_k(small, mode, T):
     say("search with k near the maximum (largest selection buffers), mode", mode)
