@@ -27,15 +27,22 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # traversal); reported only for the exact configuration that was profiled.
 # Each figure carries the hash of the kernel sources it was measured on (kernel_source_hash below); a run on other
 # sources prints traffic: null.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg2", "lds16", "lds-resident"): (483.7e6, "7fd2846c770a44f4"),       # profiles/cfg2_forest_lds_resident.md
+    ("cfg2", "reduce", "register-context"): (9.344e9, "7fd2846c770a44f4"),  # profiles/cfg2_forest_register_context.md
+    ("cfg4", "lds16", "lds-resident"): (2.785e9, "7fd2846c770a44f4"),       # profiles/cfg4_forest_lds_resident.md
+}
 # LDS read bandwidth of the chip: 256 compute units x 256 bytes per clock x 2.4 GHz (a conflict-free 16-byte-per-lane
 # wave read, 1 KiB, occupies the LDS pipe for 4 clocks: SQ_LDS_IDX_ACTIVE minus SQ_LDS_BANK_CONFLICT per read)
 LDS_PEAK_GBS = 256 * 256 * 2.4
-# vector float32 operations that are neither packed nor fused: a quarter of the published 157.3 TFLOP/s (which counts
-# two-wide packed fused multiply-adds); a wave instruction takes 4 clocks on its 16-lane SIMD
-VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# Vector instructions: a float32 add, multiply or fused multiply-add issues for 128 lanes per clock and compute unit
+# (the probe ETF_PROBE_VALU_F32 measures 2 wave instructions per CU-clock; the published 157.3 TFLOP/s is that rate
+# with packed two-wide fused multiply-adds, four flops per lane); v_add3_u32 and the packed 16-bit operations issue
+# for 64 lanes per clock (1 wave instruction per CU-clock; probes ETF_PROBE_VALU_ADD3, _PK16).
+VALU_F32_PEAK_TOPS = 256 * 128 * 2.4e9 / 1e12     # single float32 operations per second, nominal clock
+VALU_HALF_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12     # v_add3_u32 / v_pk_* lane instructions per second, nominal clock
+VALU_PEAK_NOTE = "256 CUs x 128 lanes x 2.4 GHz of single float32 vector operations (not packed, not fused)"
 CEILINGS = {}   # this run's probe results (measure_ceilings), filled in before the first timed search
-VALU_PEAK_NOTE = "256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz of unpacked, unfused 32-bit vector operations"
 TRAVERSAL_NAMES = {0: "register-context", 1: "level-synchronous", 2: "lds-resident"}
 PATH_NOTES = {
     0: "E-Forest: depth-first leaf order with the distance context in registers, per-tree result tables in HBM summed per encoding",
@@ -51,6 +58,21 @@ PAPER_CONTEXT = {              # the paper's own numbers: one Core i7 at 3.6 GHz
     "ms_per_query": {"flat_adc": 2.678, "e_tree": 1.760, "e_forest_2": 1.265},
     "distances_per_s": {"flat_adc": 1e6 / 2.678e-3, "e_tree": 1e6 / 1.760e-3, "e_forest_2": 1e6 / 1.265e-3},
 }
+
+
+def lds_alu(tadds, eb):
+    """The adds of a scan kernel (one per table entry, `tadds` T entries/s) against the vector units' rate for the
+    instruction that does them: v_add_f32 for 4-byte entries (one entry per lane instruction), v_add3_u32 for 2-byte
+    entries (two additions of two packed entries each per lane instruction)."""
+    if eb == 4:
+        peak, key, what = VALU_F32_PEAK_TOPS, "valu_v_add_f32_Tlane_instr_per_s", "one v_add_f32 per entry; " + VALU_PEAK_NOTE
+        per = 1
+    else:
+        peak, key, per = VALU_HALF_PEAK_TOPS * 4, "valu_v_add3_u32_Tlane_instr_per_s", 4
+        what = "four entry additions per v_add3_u32 lane instruction; 256 CUs x 64 lanes x 2.4 GHz of those"
+    meas = CEILINGS.get(key)
+    return {"achieved": tadds, "peak": peak, "unit": "Tadd/s", "frac": tadds / peak, "note": what,
+            "measured_peak": meas * per if meas else None, "frac_of_measured_peak": tadds / (meas * per) if meas else None}
 
 
 def kernel_source_hash():
@@ -314,10 +336,7 @@ class Workload:
                             "lookups_per_query": {"this_kernel": kernel_lookups, "e_tree": tree_lookups,
                                                   "e_forest_trees": forest_lookups, "flat_distinct": stats["n_distinct"] * stats["M"],
                                                   "flat": stats["N"] * stats["M"]},
-                            "alu": {"achieved": achieved / eb / 1e3, "peak": VALU_PEAK_TOPS * (4 // eb), "unit": "Tadd/s",
-                                    "frac": achieved / eb / 1e3 / (VALU_PEAK_TOPS * (4 // eb)),
-                                    "note": "one add per entry against %s%s" % (VALU_PEAK_NOTE, "" if eb == 4 else
-                                                                               ", two 16-bit entries per 32-bit lane operation")}}
+                            "alu": lds_alu(achieved / eb / 1e3, eb)}
             else:
                 roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_note": traffic_note}
@@ -459,8 +478,10 @@ def ivf_leg(etf, torch, args, steps, warmup):
     if dom == "ivf_coarse":
         ops = 3.0 * cfg.Q * cells_n * cfg.d
         ach = ops / (kernels[dom]["ms_per_step"] / 1e3) / 1e12
-        leg["roofline"] = {"bound": "alu", "kernel": dom, "achieved": ach, "peak": VALU_PEAK_TOPS, "unit": "Top/s",
-                           "frac": ach / VALU_PEAK_TOPS, "traffic": None, "note": VALU_PEAK_NOTE}
+        meas = CEILINGS.get("valu_v_add_f32_Tlane_instr_per_s")
+        leg["roofline"] = {"bound": "alu", "kernel": dom, "achieved": ach, "peak": VALU_F32_PEAK_TOPS, "unit": "Top/s",
+                           "frac": ach / VALU_F32_PEAK_TOPS, "traffic": None, "note": VALU_PEAK_NOTE,
+                           "frac_of_measured_peak": ach / meas if meas else None}
     if not args.no_cpu:
         from oracle import ivfadc
         from parity import assert_topk_matches
@@ -524,7 +545,22 @@ def measure_ceilings(etf, torch, stream):
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / 3
         out["%s_GBps" % kname] = total / 1e9 / (ms / 1e3)
-    log("memory ceilings (GB/s): " + ", ".join("%s %.0f" % kv for kv in out.items()))
+    # issue rate of the vector units for the instructions the scan kernels are made of, in lane instructions per second
+    # (a wave instruction is 64 of them): one float32 add, the three-operand integer add, the packed 16-bit add
+    nops = 2048 * 256 * 64 * 4096
+    for kind, kname in ((etf.ETF_PROBE_VALU_F32, "valu_v_add_f32"), (etf.ETF_PROBE_VALU_ADD3, "valu_v_add3_u32"),
+                        (etf.ETF_PROBE_VALU_PK16, "valu_v_pk_add_u16")):
+        c.probe_bandwidth(kind, b, b, nops)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            c.probe_bandwidth(kind, b, b, nops)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 3
+        out["%s_Tlane_instr_per_s" % kname] = nops / 1e12 / (ms / 1e3)
+    log("ceilings (GB/s; T lane instructions/s): " + ", ".join("%s %.4g" % kv for kv in out.items()))
     return out
 
 

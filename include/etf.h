@@ -449,8 +449,15 @@ int etf_profile_read(etf_ctx *ctx, double *ms, int64_t *launches);
  *   ETF_PROBE_LDS    no device memory traffic: 1024 workgroups of 16 waves read `bytes` in total from LDS, 16 bytes
  *                    per lane and instruction, conflict-free (a unused; b receives one word per workgroup)
  *   ETF_PROBE_LDS_SCATTER  the same with the access pattern of the table lookups: groups of four lanes read
- *                    64-byte rows at hashed positions (bank conflicts as they fall) */
-enum { ETF_PROBE_READ = 0, ETF_PROBE_WRITE = 1, ETF_PROBE_COPY = 2, ETF_PROBE_ROWS = 3, ETF_PROBE_LDS = 4, ETF_PROBE_LDS_SCATTER = 5 };
+ *                    64-byte rows at hashed positions (bank conflicts as they fall)
+ *   ETF_PROBE_VALU_F32 / _ADD3 / _PK16  no memory traffic either: the rate at which the vector units issue one kind of
+ *                    instruction (v_add_f32; v_add3_u32; v_pk_add_u16) from eight independent chains per lane; here
+ *                    `bytes` is the number of lane instructions to execute in total, rounded down to a multiple of
+ *                    2048 x 256 x 64 (a unused; b receives one word per workgroup, 8 KiB) */
+enum {
+    ETF_PROBE_READ = 0, ETF_PROBE_WRITE = 1, ETF_PROBE_COPY = 2, ETF_PROBE_ROWS = 3, ETF_PROBE_LDS = 4, ETF_PROBE_LDS_SCATTER = 5,
+    ETF_PROBE_VALU_F32 = 6, ETF_PROBE_VALU_ADD3 = 7, ETF_PROBE_VALU_PK16 = 8
+};
 int etf_probe_bandwidth(etf_ctx *ctx, int kind, void *a, void *b, int64_t bytes);
 
 #ifdef __cplusplus

@@ -848,6 +848,16 @@ extern "C" int etf_probe_bandwidth(etf_ctx *ctx, int kind, void *a, void *b, int
             else hipLaunchKernelGGL(k_probe_lds<true>, dim3(blocks), dim3(1024), 128 * 1024, st, iters, (uint32_t *)b);
             break;
         }
+        case ETF_PROBE_VALU_F32:
+        case ETF_PROBE_VALU_ADD3:
+        case ETF_PROBE_VALU_PK16: {
+            // `bytes` counts lane instructions here: 2048 workgroups x 256 lanes x 64 per iteration
+            const int iters = (int)std::max<int64_t>(1, std::min<int64_t>(bytes / ((int64_t)2048 * 256 * 64), 1 << 24));
+            if (kind == ETF_PROBE_VALU_F32) hipLaunchKernelGGL(k_probe_valu<0>, dim3(2048), dim3(256), 0, st, iters, (uint32_t *)b);
+            else if (kind == ETF_PROBE_VALU_ADD3) hipLaunchKernelGGL(k_probe_valu<1>, dim3(2048), dim3(256), 0, st, iters, (uint32_t *)b);
+            else hipLaunchKernelGGL(k_probe_valu<2>, dim3(2048), dim3(256), 0, st, iters, (uint32_t *)b);
+            break;
+        }
         default: return fail(ctx, ETF_EINVAL, "unknown probe kind %d", kind);
     }
     LAUNCH_CHECK(ctx, "k_probe");

@@ -2591,6 +2591,33 @@ __global__ __launch_bounds__(256) void k_probe_rows(const float *__restrict__ a,
 
 // LDS read rate of the chip: every lane of a workgroup of 1024 threads reads 16 bytes per instruction, `iters`
 // instructions per wave, eight in flight; the data is folded into one word per workgroup so that the reads stay.
+// The vector unit's issue rate for one instruction kind: eight independent dependency chains per lane, 64 instructions
+// per lane and iteration, nothing else in the loop.  KIND 0: v_add_f32 (one float32 operation per lane), 1: v_add3_u32
+// (the 16-bit filter's adds: two additions of two packed 16-bit entries each), 2: v_pk_add_u16.
+// grid (2048), block 256; out receives one word per workgroup.
+template <int KIND>
+__global__ __launch_bounds__(256) void k_probe_valu(int iters, uint32_t *__restrict__ out)
+{
+    uint32_t v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = threadIdx.x * 8u + (uint32_t)u;
+    const uint32_t c = blockIdx.x + 1u;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int rep = 0; rep < 8; ++rep)
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (KIND == 0) asm volatile("v_add_f32 %0, %1, %0" : "+v"(v[u]) : "v"(c));
+                if (KIND == 1) asm volatile("v_add3_u32 %0, %0, %1, %1" : "+v"(v[u]) : "v"(c));
+                if (KIND == 2) asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(v[u]) : "v"(c));
+            }
+    }
+    uint32_t x = 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) x ^= v[u];
+    if (threadIdx.x == (x & 255u)) out[blockIdx.x] = x;
+}
+
 // Plain: lane l of a wave reads piece l of a 1 KiB row (conflict-free: every quarter wave covers all 64 banks).
 // SCATTER: the four lanes of a group read the four pieces of one 64-byte row and the sixteen groups of a wave read
 // rows picked by a hash: the access pattern of the table lookups, bank conflicts as they fall.
