@@ -229,7 +229,9 @@ int etf_index_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes);
  *   ebegin      u32 [n_distinct+1]  range of ids_sorted held by every distinct encoding
  *   enc_of_pos  u32 [N]          distinct-encoding number of the n-th input vector
  *   ecodes      u8  [n_distinct][M]  distinct encodings in lexicographic order
- *   sample_enc  u32 [n_sample_enc]   distinct encodings used to bound the k-th distance (random order)
+ *   sample_enc  u32 [n_sample_enc]   numbers of distinct encodings used to bound the k-th distance (random order),
+ *                                    drawn through vectors: an encoding appears in proportion to the number of
+ *                                    vectors that have it, repeats dropped
  *   sample_pos  u32 [n_sample_pos]   input positions used for the same purpose in flat mode
  *   sample_enc_codes / sample_pos_codes  u8 [n_sample_*][M]  the encodings of those samples, in sample order
  *   leaf_of[t]  u32 [n_distinct] leaf (row of tree t's result table) of every distinct

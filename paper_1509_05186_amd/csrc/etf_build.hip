@@ -237,8 +237,7 @@ __device__ inline uint64_t mix64(uint64_t z)
 
 // A sample of S of n rows without repeats: [0, n) is cut into S strata of (almost) equal length and one row is
 // drawn from each.  Slot i of the sample holds stratum (i * A + B) mod S, A coprime to S: neighbouring slots (and
-// with them the sample groups the kernels cut the sample into) hold rows from all over the range, never a run of
-// neighbouring encodings.
+// with them the sample groups the kernels cut the sample into) hold rows from all over the range.
 __global__ void __launch_bounds__(BT) k_build_sample(const uint8_t *rows, int64_t n, int M, int64_t S, uint64_t A, uint64_t B,
                                                      uint64_t seed, uint32_t *out_idx, uint8_t *out_rows)
 {
@@ -251,7 +250,62 @@ __global__ void __launch_bounds__(BT) k_build_sample(const uint8_t *rows, int64_
     for (int m = 0; m < M; ++m) out_rows[i * M + m] = rows[r * M + m];
 }
 
+// The sample of distinct encodings behind the bound of the tree modes, drawn through the vectors: the N vectors in
+// sorted order are cut into S0 strata, one vector is drawn from each, and the draw stands for its encoding, found by
+// bisection in ebegin.  An encoding is then drawn in proportion to the number of vectors that have it, which for
+// queries that fall where the database is dense gives a much tighter bound than drawing every encoding equally
+// (the bound counts vectors).  Draws of one encoding come from neighbouring strata; keep[s] = 1 marks the first.
+__device__ inline uint32_t stratum_encoding(const uint32_t *ebegin, int64_t Nd, int64_t N, int64_t S0, uint64_t seed, uint64_t s)
+{
+    const uint64_t lo = s * (uint64_t)N / (uint64_t)S0, hi = (s + 1) * (uint64_t)N / (uint64_t)S0;
+    const uint32_t r = (uint32_t)(lo + mix64(seed ^ s) % (hi - lo));  // S0 <= N: every stratum holds a vector
+    int64_t a = 0, b = Nd;  // the e with ebegin[e] <= r < ebegin[e + 1]
+    while (b - a > 1) {
+        const int64_t mid = (a + b) >> 1;
+        if (ebegin[mid] <= r) a = mid; else b = mid;
+    }
+    return (uint32_t)a;
+}
+
+__global__ void __launch_bounds__(BT) k_build_sample_draw(const uint32_t *ebegin, int64_t Nd, int64_t N, int64_t S0, uint64_t seed,
+                                                          uint32_t *draw, uint32_t *keep)
+{
+    const int64_t s = (int64_t)blockIdx.x * BT + threadIdx.x;
+    if (s >= S0) return;
+    const uint32_t e = stratum_encoding(ebegin, Nd, N, S0, seed, (uint64_t)s);
+    draw[s] = e;
+    keep[s] = (s == 0 || stratum_encoding(ebegin, Nd, N, S0, seed, (uint64_t)s - 1) != e) ? 1u : 0u;
+}
+
+// The kept draws in scattered order: the j-th kept draw (kscan[s] - 1, in sorted order) goes to slot i with
+// j = (i * A + B) mod S, i.e. i = (j - B) * Ainv mod S, so that neighbouring slots hold encodings from all over the range.
+__global__ void __launch_bounds__(BT) k_build_sample_place(const uint32_t *draw, const uint32_t *keep, const uint32_t *kscan, int64_t S0,
+                                                           int64_t S, uint64_t Ainv, uint64_t B, const uint8_t *ecodes, int M,
+                                                           uint32_t *out_idx, uint8_t *out_rows)
+{
+    const int64_t s = (int64_t)blockIdx.x * BT + threadIdx.x;
+    if (s >= S0 || !keep[s]) return;
+    const uint64_t j = kscan[s] - 1u;
+    const uint64_t i = ((j + (uint64_t)S - B % (uint64_t)S) % (uint64_t)S) * Ainv % (uint64_t)S;  // S < 2^31: no overflow
+    const uint32_t e = draw[s];
+    out_idx[i] = e;
+    for (int m = 0; m < M; ++m) out_rows[i * M + m] = ecodes[(int64_t)e * M + m];
+}
+
 // multiplier of the slot -> stratum map: near S / golden ratio, coprime to S
+// a^-1 mod S for a coprime to S (extended Euclid), 0 for S = 1
+uint64_t inverse_mod(uint64_t a, int64_t S)
+{
+    if (S <= 1) return 0;
+    int64_t t = 0, nt = 1, r = S, nr = (int64_t)(a % (uint64_t)S);
+    while (nr != 0) {
+        const int64_t q = r / nr;
+        const int64_t t2 = t - q * nt, r2 = r - q * nr;
+        t = nt; nt = t2; r = nr; nr = r2;
+    }
+    return (uint64_t)(t < 0 ? t + S : t);
+}
+
 uint64_t spread_multiplier(int64_t S)
 {
     if (S <= 2) return 1;
@@ -456,12 +510,29 @@ int build_impl(etf_ctx *ctx, const uint8_t *codes, int64_t N, const int32_t *ids
     HIP_TRY(ctx, hipGetLastError());
     HIP_TRY(ctx, hipMemcpyAsync(&h_scal[1], scal + 1, 4, hipMemcpyDeviceToHost, st));  // read at the next synchronisation
 
-    // threshold samples (of the distinct encodings for the tree modes, of the input positions for the flat scan)
-    const int64_t S_enc = ix.n_sample_enc, S_pos = ix.n_sample_pos;
+    // threshold samples.  Tree modes: distinct encodings drawn through the vectors, repeats dropped (their number comes
+    // back to the host: the sample's arrays and everything behind them are placed once it is known).
     const uint64_t seed = 0x1509051860ull ^ (uint64_t)N;
-    hipLaunchKernelGGL(k_build_sample, dim3(blocks(S_enc)), dim3(BT), 0, st, d_ecodes, Nd, M, S_enc, spread_multiplier(S_enc),
-                       (uint64_t)(S_enc / 3), seed, (uint32_t *)(img + L.sample_enc), (uint8_t *)(img + L.sample_enc_codes));
-    HIP_TRY(ctx, hipGetLastError());
+    {
+        const int64_t S0 = ix.n_sample_enc;  // draws
+        uint32_t *draw = head, *keep = rank, *kscan = (uint32_t *)(ws + W.keys[0]);  // free between the scatter above and the trees
+        hipLaunchKernelGGL(k_build_sample_draw, dim3(blocks(S0)), dim3(BT), 0, st, d_ebegin, Nd, N, S0, seed, draw, keep);
+        HIP_TRY(ctx, hipGetLastError());
+        size_t tb = (size_t)W.temp_bytes;
+        HIP_TRY(ctx, rocprim::inclusive_scan(ws + W.temp, tb, keep, kscan, (size_t)S0, rocprim::plus<uint32_t>(), st));
+        HIP_TRY(ctx, hipMemcpyAsync(&h_scal[3], kscan + (S0 - 1), 4, hipMemcpyDeviceToHost, st));
+        HIP_TRY(ctx, hipStreamSynchronize(st));
+        const int64_t S_enc = h_scal[3];
+        if (S_enc < 1 || S_enc > S0) return fail(ctx, ETF_EHIP, "device build: %lld of %lld sample draws kept", (long long)S_enc, (long long)S0);
+        ix.n_sample_enc = S_enc;
+        compute_layout(ctx);
+        const uint64_t A = spread_multiplier(S_enc);
+        hipLaunchKernelGGL(k_build_sample_place, dim3(blocks(S0)), dim3(BT), 0, st, draw, keep, kscan, S0, S_enc, inverse_mod(A, S_enc),
+                           (uint64_t)(S_enc / 3), d_ecodes, M, (uint32_t *)(img + L.sample_enc), (uint8_t *)(img + L.sample_enc_codes));
+        HIP_TRY(ctx, hipGetLastError());
+    }
+    // flat scan: input positions, one from each of S_pos strata
+    const int64_t S_pos = ix.n_sample_pos;
     hipLaunchKernelGGL(k_build_sample, dim3(blocks(S_pos)), dim3(BT), 0, st, d_codes, N, M, S_pos, spread_multiplier(S_pos),
                        (uint64_t)(S_pos / 3), seed ^ 0x5DEECE66Dull, (uint32_t *)(img + L.sample_pos), (uint8_t *)(img + L.sample_pos_codes));
     HIP_TRY(ctx, hipGetLastError());

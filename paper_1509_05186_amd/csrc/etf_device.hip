@@ -230,7 +230,11 @@ int make_plan(const etf_ctx *ctx, int64_t Q, int k, int mode, bool search, Plan 
         P.ngroups = (P.S + P.gsize - 1) / P.gsize;
         int64_t C = ctx->opt.cand_cap;
         if (C == 0) {
-            const int64_t expect = (int64_t)(1.3 * (double)k * (double)P.items / (double)std::max<int64_t>(P.S, 1));
+            int64_t expect = (int64_t)(1.3 * (double)k * (double)P.items / (double)std::max<int64_t>(P.S, 1));
+            // The sample of the tree modes draws an encoding in proportion to the number of vectors that have it (the
+            // bound counts vectors).  A query whose neighbourhood holds encodings of single vectors then sees up to
+            // N / Nd times the candidates of one in a region of average duplication.
+            if (mode != ETF_MODE_FLAT && ix.Nd > 0) expect = (int64_t)((double)expect * std::min(8.0, (double)ix.N / (double)ix.Nd));
             // the flat scan lists every copy of an encoding at or below the bound
             const int64_t copies = mode == ETF_MODE_FLAT ? 2 * ix.max_dup : 0;
             C = 4096;

@@ -132,11 +132,18 @@ def test_device_build_sample_sizes_and_spread():
     c, img = dev_ctx(np.zeros((M, K, 1), dtype=np.float32), codes, None, T=2, sample_min=1000)
     st, lay, se, sp = check_image(c, img, codes, None)
     Nd = st["n_distinct"]
-    assert len(se) == int(120 * np.sqrt(Nd)) and len(sp) == int(120 * np.sqrt(N))   # the default sample_scale
-    # one draw from each of len(se) equal strata of the sorted encodings, in scattered order
-    srt, s = np.sort(se.astype(np.int64)), np.arange(len(se), dtype=np.int64)
-    assert np.all(srt >= s * Nd // len(se)) and np.all(srt < (s + 1) * Nd // len(se))
-    assert np.abs(np.diff(se.astype(np.int64))).min() > Nd // (4 * len(se))
+    draws = int(120 * np.sqrt(Nd))                                # the default sample_scale
+    assert 0.97 * draws <= len(se) <= draws and len(sp) == int(120 * np.sqrt(N))   # repeated draws of an encoding are dropped
+    # positions: one draw from each of len(sp) equal strata, in scattered order
+    srt, s = np.sort(sp.astype(np.int64)), np.arange(len(sp), dtype=np.int64)
+    assert np.all(srt >= s * N // len(sp)) and np.all(srt < (s + 1) * N // len(sp))
+    assert np.abs(np.diff(sp.astype(np.int64))).min() > N // (4 * len(sp))
+    # encodings: drawn through the vectors, so in proportion to their multiplicity: the mean multiplicity over the
+    # sample is the size-biased mean sum(m^2) / N, not the plain mean N / Nd (a few hundred pairs of equal vectors here)
+    enc_of_pos = arr(img, lay.enc_of_pos, N, np.uint32)
+    mult = np.bincount(enc_of_pos, minlength=Nd).astype(np.float64)
+    biased, plain, got = (mult ** 2).sum() / N, mult.mean(), mult[se].mean()
+    assert biased - plain > 1e-3 and abs(got - biased) < abs(got - plain), (biased, plain, got)
 
 
 @pytest.fixture(scope="module")
