@@ -180,6 +180,58 @@ __device__ __forceinline__ float ivf_distance(const float *tab, const uint8_t *_
     return fmaxf(fmaf(-2.f, s, bt), 0.f);
 }
 
+// The same distance from the code bytes packed into words (c[m] = byte m & 3 of word m >> 2): the entries' codes
+// are fetched with one 8- or 16-byte load where M allows it.  Same additions in the same order as ivf_distance.
+__device__ __forceinline__ void ivf_load_codes(const uint8_t *__restrict__ c, int M, uint32_t (&w)[4])
+{
+    w[0] = w[1] = w[2] = w[3] = 0u;
+    if (M == 8) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(c);
+        w[0] = v.x;
+        w[1] = v.y;
+    } else if (M == 16) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(c);
+        w[0] = v.x;
+        w[1] = v.y;
+        w[2] = v.z;
+        w[3] = v.w;
+    } else {
+        for (int m = 0; m < M; ++m) w[m >> 2] |= (uint32_t)c[m] << (8 * (m & 3));
+    }
+}
+__device__ __forceinline__ float ivf_distance_words(const float *tab, const uint32_t (&w)[4], int M, int K, float bt)
+{
+    float s = 0.f;
+    for (int m = 0; m < M; ++m) s += tab[m * K + ((w[m >> 2] >> (8 * (m & 3))) & 255u)];
+    return fmaxf(fmaf(-2.f, s, bt), 0.f);
+}
+
+// Every entry of the probed lists once: wave v of the workgroup takes lists v, v + 4, ..., its lanes the entries of a
+// list 128 at a time, two per lane, so that the loads of two entries (codes, stored term) are in flight together
+// and no position has to be looked up among the lists.  f(entry, distance) runs for every entry.
+template <class F>
+__device__ __forceinline__ void ivf_walk(const IvfScanArgs &a, const float *tab, const uint32_t *s_off, const uint32_t *s_lo,
+                                         const float *s_base, F f)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    for (int p = wave; p < a.w; p += nw) {
+        const uint32_t lo = s_lo[p], n = s_off[p + 1] - s_off[p];
+        const float base = s_base[p];
+        for (uint32_t i0 = lane; i0 < n; i0 += 128) {
+            const bool two = i0 + 64 < n;
+            const uint32_t e0 = lo + i0, e1 = two ? e0 + 64 : e0;
+            uint32_t w0[4], w1[4];
+            ivf_load_codes(a.ecodes + (int64_t)e0 * a.M, a.M, w0);
+            ivf_load_codes(a.ecodes + (int64_t)e1 * a.M, a.M, w1);
+            const float t0 = a.eterm[e0], t1 = a.eterm[e1];
+            const float d0 = ivf_distance_words(tab, w0, a.M, a.K, base + t0);
+            const float d1 = ivf_distance_words(tab, w1, a.M, a.K, base + t1);
+            f(e0, d0);
+            if (two) f(e1, d1);
+        }
+    }
+}
+
 // The w probed lists of a query as one sequence of entries: s_off[p] = entries before list p.  Thread i of a flat
 // position finds its list by bisection.
 struct IvfLists {
@@ -221,7 +273,7 @@ __device__ __forceinline__ void ivf_setup_lists(const IvfScanArgs &a, int64_t q,
 }
 
 // bytes of dynamic LDS of the two kernels below: tables, list bookkeeping, (scan only) the histogram
-constexpr int IVF_HIST_BITS = 13;  // sign-free float bits >> 18: exponent and five mantissa bits (bins 3 % wide)
+constexpr int IVF_HIST_BITS = 12;  // sign-free float bits >> 19: exponent and four mantissa bits (bins 6 % wide)
 __host__ __device__ inline size_t ivf_lds_bytes(int M, int K, int w, bool hist)
 {
     return (size_t)M * K * 4 + (size_t)(3 * w + 4) * 4 + (hist ? ((size_t)4 << IVF_HIST_BITS) : 0);
@@ -250,18 +302,9 @@ __global__ __launch_bounds__(256) void k_ivf_scan(IvfScanArgs a)
     for (int i = threadIdx.x; i < NB; i += 256) hist[i] = 0;
     if (threadIdx.x == 0) s_cnt = 0;
     ivf_setup_lists(a, q, s_off, s_lo, s_base);
-    const IvfLists L{s_off, s_lo, s_base, a.w};
-    const uint32_t total = s_off[a.w];
-    auto dist_of = [&](uint32_t i, uint32_t &e) -> float {
-        const int p = L.list_of(i);
-        e = s_lo[p] + (i - s_off[p]);
-        return ivf_distance(tab, a.ecodes + (int64_t)e * a.M, a.M, a.K, s_base[p] + a.eterm[e]);
-    };
-    for (uint32_t i = threadIdx.x; i < total; i += 256) {
-        uint32_t e;
-        const uint32_t bits = __float_as_uint(dist_of(i, e));
-        atomicAdd(&hist[bits >> SH], min(a.ebegin[e + 1] - a.ebegin[e], (uint32_t)a.k));
-    }
+    ivf_walk(a, tab, s_off, s_lo, s_base, [&](uint32_t e, float d) {
+        atomicAdd(&hist[__float_as_uint(d) >> SH], min(a.ebegin[e + 1] - a.ebegin[e], (uint32_t)a.k));
+    });
     __syncthreads();
     // the bin in which the running count of vectors reaches k (thread t owns bins [t * NB/256, (t+1) * NB/256))
     {
@@ -285,14 +328,13 @@ __global__ __launch_bounds__(256) void k_ivf_scan(IvfScanArgs a)
         __syncthreads();
     }
     const uint32_t tau = s_tau;
-    for (uint32_t i = threadIdx.x; i < total; i += 256) {
-        uint32_t e;
-        const uint32_t bits = __float_as_uint(dist_of(i, e));
+    ivf_walk(a, tab, s_off, s_lo, s_base, [&](uint32_t e, float d) {
+        const uint32_t bits = __float_as_uint(d);
         if (bits <= tau) {
             const uint32_t pos = atomicAdd(&s_cnt, 1u);
             if (pos < a.C) a.cand[q * a.C + pos] = ((uint64_t)bits << 32) | e;
         }
-    }
+    });
     __syncthreads();
     if (threadIdx.x == 0) a.cnt[q] = s_cnt;
 }
