@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256) void k_ivf_coarse(const float *__restrict__ x,
                                                     int Kc, float *__restrict__ dist, int32_t *__restrict__ best, int cslice)
 {
     constexpr int CT = 32, DJ = 32;
-    __shared__ float xs[DJ][256];
+    __shared__ float xs[DJ][257];  // rows one float longer than the block: the transposing stores below hit 32 banks, not 1
     __shared__ float cs[DJ][CT];
     const int t = threadIdx.x;
     const int64_t v0 = (int64_t)blockIdx.x * 256, v = v0 + t;
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void k_ivf_coarse(const float *__restrict__ x,
                 xs[j][vv] = (v0 + vv < n && j0 + j < d) ? x[(v0 + vv) * d + j0 + j] : 0.f;
             }
             for (int i = t; i < CT * DJ; i += 256) {
-                const int c = i / DJ, j = i % DJ;
+                const int c = i % CT, j = i / CT;  // consecutive lanes: consecutive words of a row of cs
                 cs[j][c] = (c0 + c < Kc && j0 + j < d) ? cent[(int64_t)(c0 + c) * d + j0 + j] : 0.f;
             }
             __syncthreads();
@@ -96,49 +96,41 @@ __global__ __launch_bounds__(256) void k_ivf_residual(const float *__restrict__ 
 
 // ------------------------------------------------------------------------------------------------
 // Probe selection: the w cells with the smallest (distance, index) of one query, ascending.  A radix select on the
-// 48-bit key (float bits of the distance, 16 bits of cell number) over the query's row of the distance matrix,
-// then the w keys at or below the w-th are collected and sorted.
+// float bits of the distances over the query's row of the distance matrix (and one on the cell numbers among exact
+// ties at the w-th, if they matter), then the w keys at or below the w-th are collected and sorted.
 //     grid (queries), block 256, dynamic LDS 8 * pow2(w) bytes; Kc <= 65536.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_ivf_probe(const float *__restrict__ dist, int Kc, int w, int32_t *__restrict__ probes)
 {
     extern __shared__ uint64_t pk[];
     __shared__ uint32_t hist[256];
-    __shared__ uint32_t s_digit, s_rank, s_n;
+    __shared__ uint32_t s_n;
     const int64_t q = blockIdx.x;
     const float *row = dist + q * Kc;
-    uint64_t prefix = 0;
-    uint32_t rank = (uint32_t)w;
-    for (int p = 0, shift = 40; p < 6; ++p, shift -= 8) {
-        hist[threadIdx.x] = 0;
-        __syncthreads();
-        for (int c = threadIdx.x; c < Kc; c += 256) {
-            const uint64_t key = ((uint64_t)__float_as_uint(row[c]) << 16) | (uint32_t)c;
-            if (p == 0 || (key >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(key >> shift) & 255], 1u);
-        }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            uint32_t below = 0;
-            int b = 0;
-            for (; b < 255; ++b) {
-                if (below + hist[b] >= rank) break;
-                below += hist[b];
-            }
-            s_digit = (uint32_t)b;
-            s_rank = rank - below;
-        }
-        __syncthreads();
-        prefix |= (uint64_t)s_digit << shift;
-        rank = s_rank;
-        __syncthreads();
+    // the w-th smallest distance, then, if more cells tie with it than are still needed, the largest cell number to take
+    __shared__ uint32_t sel_sh[8];
+    uint32_t vstar, rank_in_ties, n_ties, cstar = 0xFFFFFFFFu;
+    block_radix_select(
+        Kc, (uint32_t)min(w, Kc), [&](int c, uint32_t &v) { v = __float_as_uint(row[c]); return true; }, hist, sel_sh, vstar,
+        rank_in_ties, n_ties);
+    if (n_ties > rank_in_ties) {
+        uint32_t r2, n2;
+        block_radix_select(
+            Kc, rank_in_ties,
+            [&](int c, uint32_t &v) {
+                if (__float_as_uint(row[c]) != vstar) return false;
+                v = (uint32_t)c;
+                return true;
+            },
+            hist, sel_sh, cstar, r2, n2);
     }
     if (threadIdx.x == 0) s_n = 0;
     __syncthreads();
     for (int c = threadIdx.x; c < Kc; c += 256) {
-        const uint64_t key = ((uint64_t)__float_as_uint(row[c]) << 16) | (uint32_t)c;
-        if (key <= prefix) {
+        const uint32_t v = __float_as_uint(row[c]);
+        if (v < vstar || (v == vstar && (uint32_t)c <= cstar)) {
             const uint32_t pos = atomicAdd(&s_n, 1u);
-            if (pos < (uint32_t)w) pk[pos] = key;
+            if (pos < (uint32_t)w) pk[pos] = ((uint64_t)v << 16) | (uint32_t)c;
         }
     }
     __syncthreads();
@@ -202,17 +194,21 @@ __device__ __forceinline__ void ivf_load_codes(const uint8_t *__restrict__ c, in
 __device__ __forceinline__ float ivf_distance_words(const float *tab, const uint32_t (&w)[4], int M, int K, float bt)
 {
     float s = 0.f;
-    for (int m = 0; m < M; ++m) s += tab[m * K + ((w[m >> 2] >> (8 * (m & 3))) & 255u)];
+#pragma unroll
+    for (int m = 0; m < 16; ++m)
+        if (m < M) s += tab[m * K + ((w[m >> 2] >> (8 * (m & 3))) & 255u)];
     return fmaxf(fmaf(-2.f, s, bt), 0.f);
 }
 
 // Every entry of the probed lists once: wave v of the workgroup takes lists v, v + 4, ..., its lanes the entries of a
 // list 128 at a time, two per lane, so that the loads of two entries (codes, stored term) are in flight together
 // and no position has to be looked up among the lists.  f(entry, distance) runs for every entry.
-template <class F>
-__device__ __forceinline__ void ivf_walk(const IvfScanArgs &a, const float *tab, const uint32_t *s_off, const uint32_t *s_lo,
-                                         const float *s_base, F f)
+// CM, CK: M and K as constants (the common shape, loops unrolled and table offsets immediate), or 0: taken from a.
+template <int CM, int CK, class F>
+__device__ __forceinline__ void ivf_walk_shape(const IvfScanArgs &a, const float *tab, const uint32_t *s_off, const uint32_t *s_lo,
+                                               const float *s_base, F f)
 {
+    const int M = CM ? CM : a.M, K = CK ? CK : a.K;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     for (int p = wave; p < a.w; p += nw) {
         const uint32_t lo = s_lo[p], n = s_off[p + 1] - s_off[p];
@@ -221,15 +217,25 @@ __device__ __forceinline__ void ivf_walk(const IvfScanArgs &a, const float *tab,
             const bool two = i0 + 64 < n;
             const uint32_t e0 = lo + i0, e1 = two ? e0 + 64 : e0;
             uint32_t w0[4], w1[4];
-            ivf_load_codes(a.ecodes + (int64_t)e0 * a.M, a.M, w0);
-            ivf_load_codes(a.ecodes + (int64_t)e1 * a.M, a.M, w1);
+            ivf_load_codes(a.ecodes + (int64_t)e0 * M, M, w0);
+            ivf_load_codes(a.ecodes + (int64_t)e1 * M, M, w1);
             const float t0 = a.eterm[e0], t1 = a.eterm[e1];
-            const float d0 = ivf_distance_words(tab, w0, a.M, a.K, base + t0);
-            const float d1 = ivf_distance_words(tab, w1, a.M, a.K, base + t1);
+            const float d0 = ivf_distance_words(tab, w0, M, K, base + t0);
+            const float d1 = ivf_distance_words(tab, w1, M, K, base + t1);
             f(e0, d0);
             if (two) f(e1, d1);
         }
     }
+}
+
+template <class F>
+__device__ __forceinline__ void ivf_walk(const IvfScanArgs &a, const float *tab, const uint32_t *s_off, const uint32_t *s_lo,
+                                         const float *s_base, F f)
+{
+    if (a.M == 8 && a.K == 256)
+        ivf_walk_shape<8, 256>(a, tab, s_off, s_lo, s_base, f);
+    else
+        ivf_walk_shape<0, 0>(a, tab, s_off, s_lo, s_base, f);
 }
 
 // The w probed lists of a query as one sequence of entries: s_off[p] = entries before list p.  Thread i of a flat

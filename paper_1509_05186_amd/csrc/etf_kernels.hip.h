@@ -272,34 +272,54 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
     if (!IP)
         for (int k = threadIdx.x; k < K; k += blockDim.x) s_cc[k] = cbnorm[(int64_t)ms * K + k];
     __syncthreads();
+    // Small entries are queued with one reservation per wave: a first sweep over the 64 values of a lane only counts
+    // them (ballots, no memory), then one atomic reserves the wave's stretch of the queue and the second sweep hands
+    // out the slots in order (an atomic with return per value was a chain of 64 LDS round trips: 20 us for a
+    // workgroup of one wave).
+    auto value = [&](int rb, int r, int cb, int k, float &nn) -> float {
+        nn = qq[cb] + (IP ? 0.f : s_cc[k]);
+        return IP ? acc[rb][cb][r] : nn - 2.f * acc[rb][cb][r];
+    };
+    int wave_small = 0;
+    if (!IP) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int k = kbase + rb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) {
+                    float nn;
+                    const float v = value(rb, r, cb, min(k, K - 1), nn);
+                    wave_small += __popcll(__ballot(k < K && v < 0.25f * nn));
+                }
+            }
+    }
+    int slot = 0;
+    if (wave_small > 0) {
+        if (lane == 0) slot = atomicAdd(&nfix, wave_small);
+        slot = __builtin_amdgcn_readfirstlane(slot);
+    }
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int k = kbase + rb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-            if (k < K) {
-                const float cc = IP ? 0.f : s_cc[k];
 #pragma unroll
-                for (int cb = 0; cb < 2; ++cb) {
-                    const float nn = qq[cb] + cc;
-                    const float v = IP ? acc[rb][cb][r] : nn - 2.f * acc[rb][cb][r];
-                    const int ql = cb * 32 + col;
-                    const bool small = !IP && v < 0.25f * nn;   // scalar products: the contraction is the result
-                    // append the wave's small entries with one reservation (rank among them from the ballot)
-                    const uint64_t smask = __ballot(small);
-                    if (smask != 0ull) {
-                        int slot0 = 0;
-                        if (lane == __ffsll((unsigned long long)smask) - 1) slot0 = atomicAdd(&nfix, __popcll(smask));
-                        slot0 = __builtin_amdgcn_readlane(slot0, __ffsll((unsigned long long)smask) - 1);
-                        if (small)
-                            fix[slot0 + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(smask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)smask, 0u))] =
-                                (uint16_t)((ql << 8) | k);
-                    }
-                    if (!small) {
-                        if (lutT) lutT[(((int64_t)tile * M + m) * K + k) * QT + ql] = v;
-                        const int64_t q = q0 + (int64_t)tile * QT + ql;
-                        if (lut_public && q < Q) lut_public[(q * M + ms) * K + k] = v;
-                    }
+            for (int cb = 0; cb < 2; ++cb) {
+                float nn;
+                const float v = value(rb, r, cb, min(k, K - 1), nn);
+                const int ql = cb * 32 + col;
+                const bool small = !IP && k < K && v < 0.25f * nn;   // scalar products: the contraction is the result
+                const uint64_t smask = __ballot(small);
+                if (small)
+                    fix[slot + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(smask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)smask, 0u))] =
+                        (uint16_t)((ql << 8) | k);
+                slot += __popcll(smask);
+                if (!small && k < K) {
+                    if (lutT) lutT[(((int64_t)tile * M + m) * K + k) * QT + ql] = v;
+                    const int64_t q = q0 + (int64_t)tile * QT + ql;
+                    if (lut_public && q < Q) lut_public[(q * M + ms) * K + k] = v;
                 }
             }
         }
