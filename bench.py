@@ -844,6 +844,12 @@ def main():
             r = oracle.adc_all(queries[j:j + 1], cb, codes)[0]
             assert_topk_matches_identity(got_ids[j], got_dist[j], r, k, "bench q%d" % j)
         log("parity of the timed output against the oracle: ok on %d queries" % len(picks))
+        # the codes the search ran on are the device encoder's: a stretch of them against the oracle's float32 rule
+        from workload import GaussianMixture, SEED_DATABASE
+        x0 = next(iter(GaussianMixture.from_config(cfg).chunks(N, SEED_DATABASE)))[:20000]
+        assert np.array_equal(oracle.encode_f32(x0, cb), codes[:len(x0)]), "device-encoded codes differ from the oracle's"
+        cpu["codes_checked"] = "first %d database vectors: device encoder == oracle.encode_f32" % len(x0)
+        log("codes of the first %d database vectors equal the oracle's" % len(x0))
 
     # ---- the other configurations of the workload list, each end to end with its own roofline and parity check
     if not args.no_configs and cfg.name == "cfg2" and wl.valid:

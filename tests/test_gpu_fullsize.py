@@ -30,7 +30,12 @@ def build_inputs(cfg, N=None, Q=None):
     for chunk in gm.chunks(N, SEED_DATABASE):
         codes[done:done + len(chunk)] = host.pq_encode(chunk)
         done += len(chunk)
-    return host.pq_get_codebooks(), codes, gm.sample(Q, SEED_QUERIES)
+    # these codes come from the library's host encoder: a stretch of them against the oracle's rule, so that what the
+    # oracle is asked about below is what the oracle itself would have encoded
+    cb = host.pq_get_codebooks()
+    x0 = next(iter(gm.chunks(N, SEED_DATABASE)))[:5000]
+    assert np.array_equal(oracle.encode_f32(x0, cb), codes[:len(x0)])
+    return cb, codes, gm.sample(Q, SEED_QUERIES)
 
 
 def make_ctx(cb, codes, T, **opts):
@@ -251,3 +256,55 @@ def test_cfg5_forest_search_full_size():
     assert fallbacks == 0
     picks = [0, 255, 256, 640, cfg.Q - 1]                   # both sides of a call boundary, the ragged last call
     check_spread_queries(cb, codes, queries, ids.cpu().numpy(), dist.cpu().numpy(), cfg.topk, picks, "cfg5")
+
+
+def test_ivfadc_full_size():
+    """IVFADC in the configuration the paper's application experiment quotes (8192 cells, w = 64, residual PQ M = 8,
+    K = 256) on cfg2's vectors and all of its queries, as bench.py times it.  The database side (cells, residual codes)
+    comes from the device assignment; a stretch of it is held against the oracle's assignment first, then a spread of
+    queries against the oracle's distances to the reconstructions inside the oracle's probed lists."""
+    from oracle import ivfadc
+    cfg = get_config("cfg2")
+    cells_n, w, k = 8192, 64, 100
+    say("IVFADC at full size:", cfg.N, "vectors,", cells_n, "cells, w", w)
+    gm = GaussianMixture.from_config(cfg)
+    stream = torch.cuda.current_stream().cuda_stream
+    cent = gm.sample(cells_n, 77)
+    xt = gm.sample(cfg.n_train, SEED_TRAIN)
+    nt = 1200                                                                    # residual codebooks from the oracle's side
+    tc = ivfadc.coarse_assign(xt[:nt], cent)                                     # (its float32 rule takes 9 ms per vector here)
+    cb, _ = oracle.kmeans(xt[:nt] - cent[tc], cfg.M, cfg.K, 4, oracle.kmeans_init_rows(nt, cfg.M, cfg.K, 5))
+    c = etf.Context(device=0, stream=stream)
+    c.pq_set_codebooks(cb)
+    c.ivf_set_coarse(cent)
+    cells = np.empty(cfg.N, dtype=np.int32)
+    codes = np.empty((cfg.N, cfg.M), dtype=np.uint8)
+    done = 0
+    first = None
+    for chunk in gm.chunks(cfg.N, SEED_DATABASE):
+        first = chunk[:500] if first is None else first
+        ce, co = c.ivf_assign_device(torch.from_numpy(chunk).cuda())
+        cells[done:done + len(chunk)] = ce.cpu().numpy()
+        codes[done:done + len(chunk)] = co.cpu().numpy()
+        done += len(chunk)
+    say("  assigned and encoded; checking a stretch against the oracle")
+    oc, oe = ivfadc.build(first, cent, cb)
+    assert np.array_equal(oc, cells[:len(first)]) and np.array_equal(oe, codes[:len(first)])
+    c.ivf_build(cells, codes)
+    c.ivf_upload()
+    queries = gm.sample(cfg.Q, SEED_QUERIES)
+    ids, dist = c.ivf_search(torch.from_numpy(queries).cuda(), k, w)
+    torch.cuda.synchronize()
+    fallbacks = c.last_fallback_count()
+    ids, dist = ids.cpu().numpy(), dist.cpu().numpy()
+    xhat = ivfadc.reconstruct(cent, cb, cells, codes)
+    picks = [0, 1, 63, 64, 2500, 5000, 7777, cfg.Q - 1]
+    pr = ivfadc.probes(queries[picks], cent, w)
+    for jj, j in enumerate(picks):
+        inside = np.flatnonzero(np.isin(cells, pr[jj]))
+        diff = xhat[inside] - queries[j].astype(np.float64)
+        ref = np.einsum("ij,ij->i", diff, diff)
+        assert len(inside) >= k
+        assert_topk_matches(ids[j], dist[j], ref, inside, k, "ivf full size q%d" % j)
+    say("  %d queries checked; queries answered by the exact kernel: %d" % (len(picks), fallbacks))
+    assert fallbacks == 0
