@@ -361,6 +361,12 @@ class Workload:
         import oracle
         from parity import assert_topk_matches_identity
         ids, dist = self.out_ids.cpu().numpy(), self.out_dist.cpu().numpy()
+        if self.valid and not getattr(self, "codes_checked", False):
+            # the codes are the device encoder's: a stretch of them against the oracle's float32 rule, once
+            from workload import GaussianMixture, SEED_DATABASE
+            x0 = next(iter(GaussianMixture.from_config(self.cfg).chunks(self.N, SEED_DATABASE)))[:5000]
+            assert np.array_equal(oracle.encode_f32(x0, self.cb), self.codes[:len(x0)]), "device-encoded codes differ from the oracle's"
+            self.codes_checked = True
         for j in picks:
             ref = oracle.adc_all(self.queries[j:j + 1], self.cb, self.codes)[0]
             assert_topk_matches_identity(ids[j], dist[j], ref, self.k, "%s q%d" % (what, j))
@@ -487,6 +493,11 @@ def ivf_leg(etf, torch, args, steps, warmup):
         from parity import assert_topk_matches
         picks = [0, 63, 64, cfg.Q // 2, cfg.Q - 1]
         ids_h, dist_h = out_ids.cpu().numpy(), out_dist.cpu().numpy()
+        # the database side came from the device assignment: a stretch of it against the oracle's
+        x0 = next(iter(gm.chunks(cfg.N, SEED_DATABASE)))[:300]
+        oc, oe = ivfadc.build(x0, cent, cb)
+        assert np.array_equal(oc, cells[:len(x0)]) and np.array_equal(oe, codes[:len(x0)]), "device assignment differs from the oracle's"
+        leg["assignment_checked"] = "first %d vectors: cells and residual codes == oracle" % len(x0)
         xhat = ivfadc.reconstruct(cent, cb, cells, codes)
         pr = ivfadc.probes(queries[picks], cent, w)
         scanned = 0
