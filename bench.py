@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # Each figure carries the hash of the kernel sources it was measured on (kernel_source_hash below); a run on other
 # sources prints traffic: null.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", "lds16", "lds-resident"): (483.5e6, "b1d53425f643571c"),       # profiles/cfg2_forest_lds_resident.md
-    ("cfg2", "reduce", "register-context"): (9.344e9, "b1d53425f643571c"),  # profiles/cfg2_forest_register_context.md
-    ("cfg4", "lds16", "lds-resident"): (3.088e9, "b1d53425f643571c"),       # profiles/cfg4_forest_lds_resident.md
+    ("cfg2", "lds16", "lds-resident"): (483.5e6, "e67df71e1bac5489"),       # profiles/cfg2_forest_lds_resident.md
+    ("cfg2", "reduce", "register-context"): (9.344e9, "e67df71e1bac5489"),  # profiles/cfg2_forest_register_context.md
+    ("cfg4", "lds16", "lds-resident"): (3.107e9, "e67df71e1bac5489"),       # profiles/cfg4_forest_lds_resident.md
 }
 # LDS read bandwidth of the chip: 256 compute units x 256 bytes per clock x 2.4 GHz (a conflict-free 16-byte-per-lane
 # wave read, 1 KiB, occupies the LDS pipe for 4 clocks: SQ_LDS_IDX_ACTIVE minus SQ_LDS_BANK_CONFLICT per read)
@@ -81,7 +81,7 @@ def kernel_source_hash():
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_1509_05186_amd", "csrc")
     for name in sorted(os.listdir(csrc)):
-        if name.endswith((".hip", ".h", ".cpp")):
+        if name.endswith((".hip", ".h")):     # what the kernels are compiled from; host-only .cpp files do not move a profile
             h.update(open(os.path.join(csrc, name), "rb").read())
     return h.hexdigest()[:16]
 
@@ -743,6 +743,26 @@ def main():
                                  "kernels_ms_per_step": {n: v[0] / osteps for n, v in p5.items() if v[1]}}
         log("chunk order %s: lookups %d -> %d (sample), search %.2f ms/step" % (others["chunk_order"]["order"], lk_given, lk_order, d5 / osteps * 1e3))
         del oc, w5
+        # which chunks form a tree: the cut (and order) with the fewest lookups for T trees, and the search on that index
+        # (the register-context traversal, where a tree's leaves are what is evaluated, shows what the cut is worth)
+        pc = etf.Context(device=0, stream=stream)
+        pc.set_option("traversal", args.traversal)
+        pc.pq_set_codebooks(cb)
+        t0 = time.time()
+        pcb, porder, lk_equal, lk_best = pc.suggest_partition(codes, T=T)
+        t_part = time.time() - t0
+        pc.index_set_chunk_order(porder)
+        pc.index_build(codes, T=T, chunk_begin=pcb)
+        pc.index_upload()
+        w6 = pc.alloc_workspace(min(Q, cfg.query_batch or Q), k, mode)
+        d6, _ = time_search(pc, qd, k, mode, owarm, osteps, torch, w6, out_ids, out_dist, cfg.query_batch)
+        others["tree_partition"] = {"chunk_begin": [int(v) for v in pcb], "order": [int(v) for v in porder],
+                                    "lookups_equal_cut": lk_equal, "lookups_suggested_cut": lk_best,
+                                    "lookups_on": "at most 2^16 evenly spaced vectors", "suggest_s": t_part,
+                                    "ms_per_step": d6 / osteps * 1e3, "fallback_queries": pc.last_fallback_count()}
+        log("tree partition %s, order %s: lookups %d -> %d (sample), search %.2f ms/step"
+            % (others["tree_partition"]["chunk_begin"], others["tree_partition"]["order"], lk_equal, lk_best, d6 / osteps * 1e3))
+        del pc, w6
         if args.traversal == 2:
             # the same index built on the device from device-resident codes, and the same search on it
             db = etf.Context(device=0, stream=stream)

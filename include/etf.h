@@ -211,6 +211,14 @@ int etf_index_set_leaf_bytes(etf_ctx *ctx, const uint8_t *bytes, int64_t N, floa
  * lookups_order (either may be NULL) receive the table lookups of one traversal, L1 + L2 + sumP summed
  * over the trees, of those vectors' index in the given and in the suggested order. */
 int etf_index_set_chunk_order(etf_ctx *ctx, const int32_t *order);
+/* etf_suggest_partition: which chunks form a tree.  For T trees it tries the cuts of the M positions into T contiguous
+ * groups (all of them while there are at most 64, otherwise a descent from the equal cut, one boundary one position at a
+ * time), each with etf_suggest_chunk_order's greedy order for that cut, on at most 2^16 evenly spaced vectors of `codes`
+ * ([N][M] host), and returns the cut and order whose index needs the fewest table lookups per traversal:
+ * chunk_begin_out [T+1], order_out [M] (for etf_index_set_chunk_order and etf_index_build); lookups_equal /
+ * lookups_best (either may be NULL): the lookups on those vectors with the equal cut and with the returned one. */
+int etf_suggest_partition(const etf_ctx *ctx, const uint8_t *codes, int64_t N, int T, int32_t *chunk_begin_out,
+                          int32_t *order_out, int64_t *lookups_equal, int64_t *lookups_best);
 int etf_suggest_chunk_order(const etf_ctx *ctx, const uint8_t *codes, int64_t N, int T, const int32_t *chunk_begin,
                             int32_t *order_out, int64_t *lookups_given, int64_t *lookups_order);
 /* Bytes of device memory the built index needs. */

@@ -18,7 +18,7 @@ _lib = None
 EXPORTS = [
     "etf_create", "etf_destroy", "etf_set_stream", "etf_strerror", "etf_last_error", "etf_set_option",
     "etf_pq_train", "etf_pq_set_codebooks", "etf_pq_get_codebooks", "etf_pq_encode",
-    "etf_index_build", "etf_index_set_leaf_term", "etf_index_set_leaf_bytes", "etf_index_set_chunk_order", "etf_suggest_chunk_order", "etf_index_stats", "etf_index_device_bytes", "etf_index_upload",
+    "etf_index_build", "etf_index_set_leaf_term", "etf_index_set_leaf_bytes", "etf_index_set_chunk_order", "etf_suggest_chunk_order", "etf_suggest_partition", "etf_index_stats", "etf_index_device_bytes", "etf_index_upload",
     "etf_index_layout", "etf_index_export",
     "etf_encode_workspace_bytes", "etf_pq_encode_device",
     "etf_index_build_device_bytes", "etf_index_build_device",
@@ -138,6 +138,7 @@ def load_library():
         "etf_index_set_leaf_term": (I, [P, P, L]),
         "etf_index_set_leaf_bytes": (I, [P, P, L, ctypes.c_float, ctypes.c_float]),
         "etf_suggest_chunk_order": (I, [P, P, L, I, P, P, ctypes.POINTER(L), ctypes.POINTER(L)]),
+        "etf_suggest_partition": (I, [P, P, L, I, P, P, ctypes.POINTER(L), ctypes.POINTER(L)]),
         "etf_index_stats": (I, [P, ctypes.POINTER(EtfStats)]),
         "etf_index_device_bytes": (L, [P]),
         "etf_index_upload": (I, [P, P, L]),
@@ -292,6 +293,19 @@ class Context:
         self._ck(self._lib.etf_suggest_chunk_order(self._h, _host(codes), codes.shape[0], T, _host(cb), _host(order),
                                                    ctypes.byref(a), ctypes.byref(b)))
         return order, int(a.value), int(b.value)
+
+    def suggest_partition(self, codes: np.ndarray, T: int):
+        """(chunk_begin, order, lookups with the equal cut, lookups with the suggested cut) for host codes [N][M]."""
+        codes = np.ascontiguousarray(codes, dtype=np.uint8)
+        M = self._shape[1]
+        if codes.ndim != 2 or codes.shape[1] != M:
+            raise ValueError("expected [N][%d] codes" % M)
+        cb = np.zeros(T + 1, dtype=np.int32)
+        order = np.zeros(M, dtype=np.int32)
+        a, b = ctypes.c_int64(0), ctypes.c_int64(0)
+        self._ck(self._lib.etf_suggest_partition(self._h, _host(codes), codes.shape[0], T, _host(cb), _host(order),
+                                                 ctypes.byref(a), ctypes.byref(b)))
+        return cb, order, int(a.value), int(b.value)
 
     def index_stats(self) -> dict:
         st = EtfStats()

@@ -913,6 +913,91 @@ extern "C" int etf_suggest_chunk_order(const etf_ctx *ctx, const uint8_t *codes,
     return ETF_OK;
 }
 
+// Which chunks form a tree (paper, "Encoding Forests" and its remark on future work): for T trees, the cut of the M
+// positions into T contiguous groups, together with the greedy chunk order for that cut, whose index needs the fewest
+// table lookups per traversal.  All cuts are tried while there are at most 64 of them; otherwise a descent from the
+// equal cut that moves one boundary by one position as long as that saves lookups.
+extern "C" int etf_suggest_partition(const etf_ctx *ctx, const uint8_t *codes, int64_t N, int T, int32_t *chunk_begin_out,
+                                     int32_t *order_out, int64_t *lookups_equal, int64_t *lookups_best)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (ctx->codebooks.empty()) return fail(ctx, ETF_ESTATE, "no codebooks: M and K are unknown");
+    const int M = ctx->M;
+    if (!codes || N <= 0 || !order_out || !chunk_begin_out) return fail(ctx, ETF_EINVAL, "codes, chunk_begin_out or order_out is null, or N <= 0");
+    if (T < 1 || T > M) return fail(ctx, ETF_EINVAL, "need 1 <= T <= M (T=%d, M=%d)", T, M);
+    try {
+        // the trial indexes are built on at most 2^16 evenly spaced vectors (etf_suggest_chunk_order samples its input again)
+        const int64_t cap = (int64_t)1 << 16;
+        const int64_t step = (N + cap - 1) / cap, n = (N + step - 1) / step;
+        std::vector<uint8_t> rows((size_t)n * M);
+        for (int64_t i = 0; i < n; ++i) memcpy(rows.data() + (size_t)i * M, codes + (size_t)(i * step) * M, (size_t)M);
+        std::vector<int32_t> order(M);
+        auto cost_of = [&](const std::vector<int32_t> &cb, std::vector<int32_t> &ord, int64_t &cost) -> int {
+            int64_t given = 0;
+            return etf_suggest_chunk_order(ctx, rows.data(), n, T, cb.data(), ord.data(), &given, &cost);
+        };
+        // the (nearly) equal cut: the reference
+        std::vector<int32_t> best_cb(T + 1), best_order(M);
+        for (int t = 0; t <= T; ++t) best_cb[t] = (int32_t)((int64_t)t * M / T);
+        int64_t best = 0;
+        int rc = cost_of(best_cb, best_order, best);
+        if (rc) return rc;
+        const int64_t equal = best;
+        // number of cuts: C(M - 1, T - 1)
+        double ncuts = 1.0;
+        for (int i = 1; i <= T - 1; ++i) ncuts = ncuts * (M - T + i) / i;
+        if (ncuts <= 64.0) {
+            std::vector<int32_t> cb(T + 1);
+            cb[0] = 0;
+            cb[T] = M;
+            // boundaries 1 <= b_1 < ... < b_{T-1} <= M - 1, in lexicographic order
+            std::vector<int32_t> b(T - 1);
+            for (int i = 0; i < T - 1; ++i) b[i] = i + 1;
+            for (;;) {
+                for (int i = 0; i < T - 1; ++i) cb[i + 1] = b[i];
+                int64_t c = 0;
+                if ((rc = cost_of(cb, order, c))) return rc;
+                if (c < best) {
+                    best = c;
+                    best_cb = cb;
+                    best_order = order;
+                }
+                int i = T - 2;
+                while (i >= 0 && b[i] == M - (T - 1) + i) --i;
+                if (i < 0) break;
+                ++b[i];
+                for (int j = i + 1; j < T - 1; ++j) b[j] = b[j - 1] + 1;
+            }
+        } else {
+            bool moved = true;
+            while (moved) {
+                moved = false;
+                for (int i = 1; i < T; ++i)
+                    for (int dlt = -1; dlt <= 1; dlt += 2) {
+                        std::vector<int32_t> cb = best_cb;
+                        cb[i] += dlt;
+                        if (cb[i] <= cb[i - 1] || cb[i] >= cb[i + 1]) continue;
+                        int64_t c = 0;
+                        if ((rc = cost_of(cb, order, c))) return rc;
+                        if (c < best) {
+                            best = c;
+                            best_cb = cb;
+                            best_order = order;
+                            moved = true;
+                        }
+                    }
+            }
+        }
+        for (int t = 0; t <= T; ++t) chunk_begin_out[t] = best_cb[t];
+        for (int j = 0; j < M; ++j) order_out[j] = best_order[j];
+        if (lookups_equal) *lookups_equal = equal;
+        if (lookups_best) *lookups_best = best;
+    } catch (const std::bad_alloc &) {
+        return fail(ctx, ETF_ENOMEM, "out of host memory while choosing the partition");
+    }
+    return ETF_OK;
+}
+
 extern "C" int etf_index_stats(const etf_ctx *ctx, etf_stats *out)
 {
     if (!ctx) return ETF_EINVAL;

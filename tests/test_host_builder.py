@@ -344,3 +344,54 @@ def test_builder_with_leaf_payload(T, M, K, N):
     assert c2.index_layout().eterm == -1 and c2.index_stats()["n_distinct"] == len(np.unique(codes, axis=0))
     with pytest.raises(etf.EtfError):
         c2.index_set_leaf_term(-term - 1)
+
+
+def test_suggest_partition_finds_the_planted_cut():
+    """Six chunks: four of them are functions of one hidden variable with 40 values (any tree over them has at most 40
+    leaves), two are independent and uniform.  With two trees the cheap index keeps the four dependent chunks together;
+    the equal cut (3 + 3) mixes one of them with the independent ones and pays for thousands of distinct leaves."""
+    rng = np.random.default_rng(21)
+    N, M, K = 30000, 6, 16
+    hidden = rng.integers(0, 40, size=N)
+    table = rng.integers(0, K, size=(40, 4))
+    codes = np.empty((N, M), dtype=np.uint8)
+    codes[:, [0, 2, 3, 5]] = table[hidden]
+    codes[:, [1, 4]] = rng.integers(0, K, size=(N, 2))
+    c = host_ctx(np.zeros((M, K, 1), dtype=np.float32))
+    cb, order, equal, best = c.suggest_partition(codes, T=2)
+    assert sorted(order.tolist()) == list(range(M)) and cb[0] == 0 and cb[2] == M
+    groups = [sorted(order[cb[t]:cb[t + 1]].tolist()) for t in range(2)]
+    assert sorted(groups) == [[0, 2, 3, 5], [1, 4]], (cb, order)
+    assert best < equal
+    # the counts are the statistics of the indexes themselves (all 30000 vectors are within the 2^16 tried)
+    c.index_set_chunk_order(order)
+    c.index_build(codes, T=2, chunk_begin=cb)
+    assert sum(t["lookups"] for t in c.index_stats()["trees"]) == best
+    eq_order, _, eq_best = c.suggest_chunk_order(codes, T=2)
+    assert eq_best == equal
+    # one tree: nothing to cut; many cuts (M = 6, T = 3: 10) are all tried; T = M: the only cut
+    cb1, order1, e1, b1 = c.suggest_partition(codes, T=1)
+    assert cb1.tolist() == [0, M] and b1 == e1
+    cb3, order3, e3, b3 = c.suggest_partition(codes, T=3)
+    assert b3 <= e3 and cb3[0] == 0 and cb3[3] == M and np.all(np.diff(cb3) > 0)
+    cb6, order6, e6, b6 = c.suggest_partition(codes, T=6)
+    assert cb6.tolist() == list(range(M + 1)) and b6 == e6
+    with pytest.raises(etf.EtfError):
+        c.suggest_partition(codes, T=7)
+
+
+def test_suggest_partition_descends_when_there_are_many_cuts():
+    """M = 16, T = 4: 455 cuts, so the search moves boundaries from the equal cut.  Twelve chunks are copies of three
+    hidden variables, four are independent: every move that brings copies of one variable together saves lookups."""
+    rng = np.random.default_rng(22)
+    N, M, K = 8000, 16, 8
+    codes = rng.integers(0, K, size=(N, M)).astype(np.uint8)
+    for base in (0, 5, 10):
+        codes[:, base + 1:base + 4] = codes[:, base:base + 1]       # chunks base .. base+3 carry one value
+    c = host_ctx(np.zeros((M, K, 1), dtype=np.float32))
+    cb, order, equal, best = c.suggest_partition(codes, T=4)
+    assert sorted(order.tolist()) == list(range(M)) and np.all(np.diff(cb) > 0) and cb[0] == 0 and cb[4] == M
+    assert best <= equal
+    c.index_set_chunk_order(order)
+    c.index_build(codes, T=4, chunk_begin=cb)
+    assert sum(t["lookups"] for t in c.index_stats()["trees"]) == best
