@@ -169,6 +169,28 @@ int etf_pq_get_codebooks(const etf_ctx *ctx, float *cb_out);
  * sub-vector (lowest index on ties).  x [n][d] host, codes_out [n][M] host. */
 int etf_pq_encode(const etf_ctx *ctx, const float *x, int64_t n, uint8_t *codes_out);
 
+/* ---- rotation in front of the quantiser (paper, Related Work: Optimized Product Quantization is among the
+ *      quantisers whose codes the tree stores; a preprocessing step, not part of the distance computation) --------
+ * The quantiser then works on y = R x: train on, encode and query with rotated vectors; for an orthogonal R the
+ * distances are those of the original space.  Rotating is explicit: the library never rotates behind a call.
+ * etf_pq_set_rotation: R [d][d] host, row-major, finite (NULL clears; d need not match codebooks that are set until
+ *   vectors are rotated).  etf_pq_get_rotation: R_out [d][d].
+ * etf_rotate (host) / etf_rotate_device (device pointers, enqueued on the context's stream; ws: device, 256-byte
+ *   aligned, at least etf_rotate_workspace_bytes; not in place): out[i] = R x[i] for n vectors of d floats, every
+ *   component accumulated in double over the dimensions in ascending order and rounded to float once; host and
+ *   device return the same bits.
+ * etf_opq_train: the non-parametric alternation on x [n][d] (host): `rounds` times { rotate the training set,
+ *   etf_pq_train on it with `iters` Lloyd iterations, replace R by the orthogonal matrix nearest to
+ *   sum decode(encode(R x)) x^T }, then a last training on the rotated set; starts from the rotation that is set (the
+ *   identity if none, or if its size is not d) and leaves rotation and codebooks set.  rounds = 0 is etf_pq_train
+ *   behind the current rotation.  Cost per round: O(n d^2 + d^3 * tens) on the host. */
+int etf_pq_set_rotation(etf_ctx *ctx, const float *R, int d);
+int etf_pq_get_rotation(const etf_ctx *ctx, float *R_out);
+int etf_rotate(const etf_ctx *ctx, const float *x, int64_t n, float *out);
+int64_t etf_rotate_workspace_bytes(const etf_ctx *ctx);
+int etf_rotate_device(etf_ctx *ctx, const float *x, int64_t n, float *out, void *ws, int64_t ws_bytes);
+int etf_opq_train(etf_ctx *ctx, const float *x, int64_t n, int d, int M, int K, int iters, int rounds, uint64_t seed);
+
 /* ---- index build, host side (paper: Algorithm 1, Hierarchical Memory Structure) ---- */
 
 /* Sorts the encodings lexicographically and builds T encoding trees.

@@ -243,3 +243,20 @@ def search_term(q, codebooks, codes, term, k: int, ids: Optional[np.ndarray] = N
         order = np.lexsort((idv, d[j]))[:k]
         out_i[j], out_d[j] = idv[order], d[j][order]
     return out_i, out_d
+
+
+def rotate(x: np.ndarray, R: np.ndarray) -> np.ndarray:
+    """y = R x for every row of x ([n][d] float32, R [d][d] float32): the preprocessing step of Optimized Product
+    Quantization (the paper's Related Work lists it among the quantisers whose codes the tree stores).  Every
+    component is accumulated in float64 over the dimensions in ascending order, one rounded addition per dimension
+    (the product of two float32 values is exact in float64), and rounded to float32 once at the end: a plain
+    definition whose bits a float32 pipeline can reproduce.  Returns float32 [n][d]."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    R = np.ascontiguousarray(R, dtype=np.float32)
+    n, d = x.shape
+    assert R.shape == (d, d)
+    acc = np.zeros((n, d), dtype=np.float64)
+    Rt = R.T.astype(np.float64)                       # Rt[j] = column j of R: the factors of x[:, j]
+    for j in range(d):
+        acc = acc + x[:, j:j + 1].astype(np.float64) * Rt[j][None, :]
+    return acc.astype(np.float32)

@@ -18,6 +18,7 @@ _lib = None
 EXPORTS = [
     "etf_create", "etf_destroy", "etf_set_stream", "etf_strerror", "etf_last_error", "etf_set_option",
     "etf_pq_train", "etf_pq_set_codebooks", "etf_pq_get_codebooks", "etf_pq_encode",
+    "etf_pq_set_rotation", "etf_pq_get_rotation", "etf_rotate", "etf_rotate_workspace_bytes", "etf_rotate_device", "etf_opq_train",
     "etf_index_build", "etf_index_set_leaf_term", "etf_index_set_leaf_bytes", "etf_index_set_chunk_order", "etf_suggest_chunk_order", "etf_suggest_partition", "etf_index_stats", "etf_index_device_bytes", "etf_index_upload",
     "etf_index_layout", "etf_index_export",
     "etf_encode_workspace_bytes", "etf_pq_encode_device",
@@ -133,6 +134,12 @@ def load_library():
         "etf_pq_set_codebooks": (I, [P, P, I, I, I]),
         "etf_pq_get_codebooks": (I, [P, P]),
         "etf_pq_encode": (I, [P, P, L, P]),
+        "etf_pq_set_rotation": (I, [P, P, I]),
+        "etf_pq_get_rotation": (I, [P, P]),
+        "etf_rotate": (I, [P, P, L, P]),
+        "etf_rotate_workspace_bytes": (L, [P]),
+        "etf_rotate_device": (I, [P, P, L, P, P, L]),
+        "etf_opq_train": (I, [P, P, L, I, I, I, I, I, ctypes.c_uint64]),
         "etf_index_build": (I, [P, P, L, P, I, P]),
         "etf_index_set_chunk_order": (I, [P, P]),
         "etf_index_set_leaf_term": (I, [P, P, L]),
@@ -232,6 +239,57 @@ class Context:
         M, K, ds = cb.shape
         self._ck(self._lib.etf_pq_set_codebooks(self._h, _host(cb), M * ds, M, K))
         self._shape = (M * ds, M, K)
+
+    def pq_set_rotation(self, R: Optional[np.ndarray]):
+        """R: [d][d] float32 (the quantiser's space is y = R x), or None to clear."""
+        if R is None:
+            self._ck(self._lib.etf_pq_set_rotation(self._h, None, 0))
+            self._rot_d = 0
+            return
+        R = np.ascontiguousarray(R, dtype=np.float32)
+        if R.ndim != 2 or R.shape[0] != R.shape[1]:
+            raise ValueError("expected a square matrix")
+        self._ck(self._lib.etf_pq_set_rotation(self._h, _host(R), R.shape[0]))
+        self._rot_d = R.shape[0]
+
+    def pq_get_rotation(self) -> np.ndarray:
+        d = getattr(self, "_rot_d", 0)
+        R = np.zeros((d, d), dtype=np.float32)
+        self._ck(self._lib.etf_pq_get_rotation(self._h, _host(R) if d else None))
+        return R
+
+    def rotate(self, x: np.ndarray) -> np.ndarray:
+        """Host: [n][d] float32 -> R x, float32."""
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        out = np.empty_like(x)
+        if x.ndim != 2 or x.shape[1] != getattr(self, "_rot_d", 0):
+            raise ValueError("expected [n][%d] vectors" % getattr(self, "_rot_d", 0))
+        self._ck(self._lib.etf_rotate(self._h, _host(x) if len(x) else None, x.shape[0], _host(out) if len(x) else None))
+        return out
+
+    def rotate_workspace_bytes(self) -> int:
+        return self._ck(self._lib.etf_rotate_workspace_bytes(self._h))
+
+    def rotate_device(self, x, out=None, ws=None):
+        """x: float32 device tensor [n][d]; returns R x as a float32 device tensor."""
+        import torch
+        d = getattr(self, "_rot_d", 0)
+        if x.dim() != 2 or x.shape[1] != d or x.dtype != torch.float32 or not x.is_contiguous():
+            raise ValueError("expected a contiguous float32 tensor [n][%d]" % d)
+        n = x.shape[0]
+        if out is None:
+            out = torch.empty_like(x)
+        if ws is None:
+            ws = torch.empty(self.rotate_workspace_bytes() + 256, dtype=torch.uint8, device=x.device)
+        p, nb = self._ws(ws)
+        self._ck(self._lib.etf_rotate_device(self._h, _dev(x) if n else None, n, _dev(out) if n else None, p, nb))
+        return out
+
+    def opq_train(self, x: np.ndarray, M: int, K: int, iters: int, rounds: int, seed: int):
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        self._ck(self._lib.etf_opq_train(self._h, _host(x), x.shape[0], x.shape[1], M, K, iters, rounds, seed))
+        self._shape = (x.shape[1], M, K)
+        self._rot_d = x.shape[1]
 
     def pq_get_codebooks(self) -> np.ndarray:
         d, M, K = self._shape

@@ -962,6 +962,44 @@ extern "C" int etf_adc(etf_ctx *ctx, const float *queries, int64_t Q, int mode, 
 // =============================================================================================
 // device encoder
 // =============================================================================================
+extern "C" int64_t etf_rotate_workspace_bytes(const etf_ctx *ctx)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (ctx->rotation.empty()) return fail(ctx, ETF_ESTATE, "no rotation: call etf_pq_set_rotation or etf_opq_train first");
+    return (int64_t)((ctx->rotation.size() * sizeof(float) + 255) & ~(size_t)255);
+}
+
+extern "C" int etf_rotate_device(etf_ctx *ctx, const float *x, int64_t n, float *out, void *ws, int64_t ws_bytes)
+{
+    int rc = need_device(ctx);
+    if (rc) return rc;
+    if (ctx->rotation.empty()) return fail(ctx, ETF_ESTATE, "no rotation: call etf_pq_set_rotation or etf_opq_train first");
+    if (n < 0 || (n > 0 && (!x || !out))) return fail(ctx, ETF_EINVAL, "null input or output with n=%lld", (long long)n);
+    if (x == out && n > 0) return fail(ctx, ETF_EINVAL, "the rotation does not work in place");
+    if (!ws || ((uintptr_t)ws & 255) != 0) return fail(ctx, ETF_EINVAL, "workspace is null or not 256-byte aligned");
+    const int64_t need = etf_rotate_workspace_bytes(ctx);
+    if (ws_bytes < need) return fail(ctx, ETF_ENOMEM, "workspace too small: %lld < %lld", (long long)ws_bytes, (long long)need);
+    if (n == 0) return ETF_OK;
+    const int d = ctx->rot_d;
+    const int rows_per_block = std::max(1, std::min(8, 16384 / d));  // at most 64 KB of LDS
+    if ((n + rows_per_block - 1) / rows_per_block > 0x7FFFFFFF) return fail(ctx, ETF_EINVAL, "n too large for one launch");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    hipStream_t st = (hipStream_t)ctx->stream;
+    // the transposed rotation goes to the workspace (kept in the context so that the copy's source outlives the call)
+    try {
+        ctx->rotation_t.resize(ctx->rotation.size());
+    } catch (const std::bad_alloc &) {
+        return fail(ctx, ETF_ENOMEM, "out of host memory");
+    }
+    for (int r = 0; r < d; ++r)
+        for (int j = 0; j < d; ++j) ctx->rotation_t[(size_t)j * d + r] = ctx->rotation[(size_t)r * d + j];
+    HIP_TRY(ctx, hipMemcpyAsync(ws, ctx->rotation_t.data(), ctx->rotation_t.size() * sizeof(float), hipMemcpyHostToDevice, st));
+    hipLaunchKernelGGL(k_rotate, dim3((unsigned)((n + rows_per_block - 1) / rows_per_block)), dim3(256),
+                       (size_t)rows_per_block * d * sizeof(float), st, x, n, d, reinterpret_cast<const float *>(ws), out, rows_per_block);
+    LAUNCH_CHECK(ctx, "k_rotate");
+    return ETF_OK;
+}
+
 extern "C" int64_t etf_encode_workspace_bytes(const etf_ctx *ctx)
 {
     if (!ctx) return ETF_EINVAL;

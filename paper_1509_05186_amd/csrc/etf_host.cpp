@@ -538,6 +538,179 @@ extern "C" int etf_pq_train(etf_ctx *ctx, const float *x, int64_t n, int d, int 
     return ETF_OK;
 }
 
+// ---- rotation in front of the quantiser (paper, Related Work: Optimized Product Quantization rotates the space so
+//      that the dimension groups become less dependent; named in the survey of methods the tree applies to) --------
+// y = R x, every component accumulated in double over the dimensions in ascending order (a product of two floats is
+// exact in double, so fused or not makes no difference) and rounded to float once: the one rule host, device and
+// reference follow, so that codes of rotated vectors can be compared bit for bit.
+static void rotate_rows(const float *R, int d, const float *x, int64_t lo, int64_t hi, float *out)
+{
+    for (int64_t i = lo; i < hi; ++i) {
+        const float *xi = x + (size_t)i * d;
+        for (int r = 0; r < d; ++r) {
+            const float *Rr = R + (size_t)r * d;
+            double acc = 0.0;
+            for (int j = 0; j < d; ++j) acc += (double)Rr[j] * (double)xi[j];
+            out[(size_t)i * d + r] = (float)acc;
+        }
+    }
+}
+
+extern "C" int etf_pq_set_rotation(etf_ctx *ctx, const float *R, int d)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (!R) {
+        ctx->rotation.clear();
+        ctx->rot_d = 0;
+        return ETF_OK;
+    }
+    if (d < 1 || d > 4096) return fail(ctx, ETF_EINVAL, "rotation of %d dimensions", d);
+    for (size_t i = 0; i < (size_t)d * d; ++i)
+        if (!std::isfinite(R[i])) return fail(ctx, ETF_EINVAL, "the rotation has an entry that is not finite");
+    try {
+        ctx->rotation.assign(R, R + (size_t)d * d);
+    } catch (const std::bad_alloc &) {
+        return fail(ctx, ETF_ENOMEM, "out of host memory");
+    }
+    ctx->rot_d = d;
+    return ETF_OK;
+}
+
+extern "C" int etf_pq_get_rotation(const etf_ctx *ctx, float *R_out)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (!R_out) return fail(ctx, ETF_EINVAL, "output pointer is null");
+    if (ctx->rotation.empty()) return fail(ctx, ETF_ESTATE, "no rotation: call etf_pq_set_rotation or etf_opq_train first");
+    memcpy(R_out, ctx->rotation.data(), ctx->rotation.size() * sizeof(float));
+    return ETF_OK;
+}
+
+extern "C" int etf_rotate(const etf_ctx *ctx, const float *x, int64_t n, float *out)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (ctx->rotation.empty()) return fail(ctx, ETF_ESTATE, "no rotation: call etf_pq_set_rotation or etf_opq_train first");
+    if (n < 0 || (n > 0 && (!x || !out))) return fail(ctx, ETF_EINVAL, "null input or output with n=%lld", (long long)n);
+    const int d = ctx->rot_d;
+    const float *R = ctx->rotation.data();
+    parallel_slices(n, host_threads(), [&](int, int64_t lo, int64_t hi) { rotate_rows(R, d, x, lo, hi, out); });
+    return ETF_OK;
+}
+
+// inverse of a d x d matrix in place (Gauss-Jordan with partial pivoting); false if it is singular to working precision
+static bool invert(std::vector<double> &a, int d)
+{
+    std::vector<double> inv((size_t)d * d, 0.0);
+    for (int i = 0; i < d; ++i) inv[(size_t)i * d + i] = 1.0;
+    for (int c = 0; c < d; ++c) {
+        int p = c;
+        for (int r = c + 1; r < d; ++r)
+            if (std::fabs(a[(size_t)r * d + c]) > std::fabs(a[(size_t)p * d + c])) p = r;
+        if (std::fabs(a[(size_t)p * d + c]) < 1e-300) return false;
+        if (p != c)
+            for (int j = 0; j < d; ++j) {
+                std::swap(a[(size_t)p * d + j], a[(size_t)c * d + j]);
+                std::swap(inv[(size_t)p * d + j], inv[(size_t)c * d + j]);
+            }
+        const double piv = 1.0 / a[(size_t)c * d + c];
+        for (int j = 0; j < d; ++j) {
+            a[(size_t)c * d + j] *= piv;
+            inv[(size_t)c * d + j] *= piv;
+        }
+        parallel_slices(d, host_threads(), [&](int, int64_t lo, int64_t hi) {
+            for (int64_t r = lo; r < hi; ++r) {
+                if (r == c) continue;
+                const double f = a[(size_t)r * d + c];
+                if (f == 0.0) continue;
+                for (int j = 0; j < d; ++j) {
+                    a[(size_t)r * d + j] -= f * a[(size_t)c * d + j];
+                    inv[(size_t)r * d + j] -= f * inv[(size_t)c * d + j];
+                }
+            }
+        });
+    }
+    a.swap(inv);
+    return true;
+}
+
+// The orthogonal matrix nearest to c (its polar factor U V^T for c = U S V^T), by Newton's iteration
+// X <- (X + X^-T) / 2 from X = c scaled to unit Frobenius norm; false if c is singular.
+static bool polar_factor(std::vector<double> &c, int d)
+{
+    double fro = 0.0;
+    for (double v : c) fro += v * v;
+    fro = std::sqrt(fro);
+    if (!(fro > 0.0)) return false;
+    for (double &v : c) v *= std::sqrt((double)d) / fro;
+    for (int it = 0; it < 100; ++it) {
+        std::vector<double> inv(c);
+        if (!invert(inv, d)) return false;
+        double change = 0.0;
+        for (int i = 0; i < d; ++i)
+            for (int j = 0; j < d; ++j) {
+                const double nv = 0.5 * (c[(size_t)i * d + j] + inv[(size_t)j * d + i]);
+                change = std::max(change, std::fabs(nv - c[(size_t)i * d + j]));
+                c[(size_t)i * d + j] = nv;
+            }
+        if (change < 1e-13) break;
+    }
+    return true;
+}
+
+// Optimized product quantisation, the non-parametric alternation: with the rotation fixed, train the product
+// quantiser on the rotated training set; with the quantiser fixed, the orthogonal R that minimises
+// sum ||R x - decode(encode(R x))||^2 is the polar factor of sum yhat x^T.  The rotation starts from the one that is set
+// (the identity if none) and ends up set together with the codebooks of the last round.
+extern "C" int etf_opq_train(etf_ctx *ctx, const float *x, int64_t n, int d, int M, int K, int iters, int rounds, uint64_t seed)
+{
+    if (!ctx) return ETF_EINVAL;
+    if (!x || n <= 0) return fail(ctx, ETF_EINVAL, "training set is empty or null");
+    if (iters < 0 || rounds < 0) return fail(ctx, ETF_EINVAL, "iters and rounds must be >= 0");
+    int rc = check_pq_shape(ctx, d, M, K);
+    if (rc) return rc;
+    try {
+        if (ctx->rotation.empty() || ctx->rot_d != d) {
+            ctx->rotation.assign((size_t)d * d, 0.f);
+            for (int i = 0; i < d; ++i) ctx->rotation[(size_t)i * d + i] = 1.f;
+            ctx->rot_d = d;
+        }
+        std::vector<float> y((size_t)n * d);
+        std::vector<uint8_t> codes((size_t)n * M);
+        const int ds = d / M;
+        for (int round = 0;; ++round) {
+            if ((rc = etf_rotate(ctx, x, n, y.data()))) return rc;
+            if ((rc = etf_pq_train(ctx, y.data(), n, d, M, K, iters, seed))) return rc;
+            if (round == rounds) break;
+            if ((rc = etf_pq_encode(ctx, y.data(), n, codes.data()))) return rc;
+            // c = sum over the training set of yhat x^T, in double
+            const int threads = host_threads();
+            std::vector<std::vector<double>> part((size_t)threads, std::vector<double>((size_t)d * d, 0.0));
+            const float *cb = ctx->codebooks.data();
+            parallel_slices(n, threads, [&](int t, int64_t lo, int64_t hi) {
+                std::vector<double> &c = part[t];
+                std::vector<float> yh((size_t)d);
+                for (int64_t i = lo; i < hi; ++i) {
+                    for (int m = 0; m < M; ++m)
+                        memcpy(yh.data() + (size_t)m * ds, cb + ((size_t)m * K + codes[(size_t)i * M + m]) * ds, sizeof(float) * ds);
+                    const float *xi = x + (size_t)i * d;
+                    for (int r = 0; r < d; ++r) {
+                        const double yr = yh[r];
+                        double *cr = c.data() + (size_t)r * d;
+                        for (int j = 0; j < d; ++j) cr[j] += yr * (double)xi[j];
+                    }
+                }
+            });
+            std::vector<double> c((size_t)d * d, 0.0);
+            for (const auto &p : part)
+                for (size_t i = 0; i < c.size(); ++i) c[i] += p[i];
+            if (!polar_factor(c, d)) break;  // degenerate training set: keep the rotation of this round
+            for (size_t i = 0; i < c.size(); ++i) ctx->rotation[i] = (float)c[i];
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(ctx, ETF_ENOMEM, "out of host memory");
+    }
+    return ETF_OK;
+}
+
 extern "C" int etf_pq_encode(const etf_ctx *ctx, const float *x, int64_t n, uint8_t *codes_out)
 {
     if (!ctx) return ETF_EINVAL;

@@ -142,6 +142,9 @@ struct etf_ctx {
     // quantiser
     int d = 0, M = 0, K = 0, ds = 0;
     std::vector<float> codebooks;           // [M][K][ds]
+    std::vector<float> rotation;            // [d][d] row-major, or empty: the quantiser's space is y = rotation x (OPQ)
+    int rot_d = 0;
+    std::vector<float> rotation_t;          // the rotation transposed, staging for the device copy
     // for the matrix-core table build: codewords minus the group's mean codeword, rows padded to an even
     // length dsp; their squared norms; the means
     int dsp = 0;

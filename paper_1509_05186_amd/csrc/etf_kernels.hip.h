@@ -618,6 +618,31 @@ __global__ __launch_bounds__(256) void k_encode(const float *__restrict__ x, int
 }
 
 // ------------------------------------------------------------------------------------------------
+// Rotation in front of the quantiser (Optimized Product Quantization, named in the paper's Related Work among the
+//     quantisers the tree applies to): out[i] = R x[i], every component accumulated in double over the dimensions
+//     in ascending order and rounded to float once (a product of two floats is exact in double: the fused
+//     multiply-add changes nothing), the rule the host function and the reference follow bit for bit.
+//     Rt is the rotation transposed ([j][r] = R[r][j]: neighbouring threads read neighbouring words).
+//     grid (ceil(n / rows_per_block)), block 256, dynamic LDS rows_per_block * d * 4 bytes.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_rotate(const float *__restrict__ x, int64_t n, int d, const float *__restrict__ Rt,
+                                                float *__restrict__ out, int rows_per_block)
+{
+    extern __shared__ float rot_xs[];  // [rows_per_block][d]
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+    const int rows = (int)min<int64_t>(rows_per_block, n - r0);
+    for (int idx = threadIdx.x; idx < rows * d; idx += 256) rot_xs[idx] = x[r0 * d + idx];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < rows * d; idx += 256) {
+        const int row = idx / d, r = idx - row * d;
+        const float *xr = rot_xs + row * d;
+        double acc = 0.0;
+        for (int j = 0; j < d; ++j) acc += (double)Rt[(int64_t)j * d + r] * (double)xr[j];
+        out[(r0 + row) * d + r] = (float)acc;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // The same assignment with the distance evaluations on the matrix cores (the O(dKN) term of the paper's "Efficient
 //     Encoding Tree Construction").  For every (vector, group) the 256 values  ||c||^2 - 2 x.c  come from the dense
 //     contraction x.c (v_mfma_f32_32x32x2_f32, operands as in k_lut_mfma: A = codewords, B = vectors); they differ
