@@ -478,16 +478,13 @@ def ivf_leg(etf, torch, args, steps, warmup):
            "ms_per_step": ms, "queries_per_s": cfg.Q / (ms / 1e3), "steps": steps, "kernels": kernels,
            "fallback_queries": c.last_fallback_count(), "index": st, "assign_gpu_kernel_ms": assign_ms,
            "coarse_quantiser": "8192 vectors drawn from the mixture, not trained"}
-    # roofline of the dominant kernel.  Coarse distances: plain float32 vector arithmetic, 3 operations per (query,
-    # cell, dimension), nothing fused (the decisions must be reproducible).  Scan: 4-byte table entries gathered from LDS.
-    dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
-    if dom == "ivf_coarse":
-        ops = 3.0 * cfg.Q * cells_n * cfg.d
-        ach = ops / (kernels[dom]["ms_per_step"] / 1e3) / 1e12
-        meas = CEILINGS.get("valu_v_add_f32_Tlane_instr_per_s")
-        leg["roofline"] = {"bound": "alu", "kernel": dom, "achieved": ach, "peak": VALU_F32_PEAK_TOPS, "unit": "Top/s",
-                           "frac": ach / VALU_F32_PEAK_TOPS, "traffic": None, "note": VALU_PEAK_NOTE,
-                           "frac_of_measured_peak": ach / meas if meas else None}
+    # rooflines of the two large kernel classes.  Coarse: the query-centroid products are a dense float32 contraction
+    # on the matrix cores (2 Q K' d operations); the class also holds the probe selection, which re-evaluates the cells
+    # near the w-th by the sequential float32 rule.  Scan: 4-byte table entries gathered from LDS, M per entry.
+    if "ivf_coarse" in kernels:
+        ach = 2.0 * cfg.Q * cells_n * cfg.d / (kernels["ivf_coarse"]["ms_per_step"] / 1e3) / 1e12
+        leg["roofline_coarse"] = {"bound": "mfma", "kernel": "ivf_coarse (k_ivf_coarse_mfma and k_ivf_probe_mfma together)",
+                                  "dtype": "f32", "achieved": ach, "peak": 157.3, "unit": "TFLOP/s", "frac": ach / 157.3, "traffic": None}
     if not args.no_cpu:
         from oracle import ivfadc
         from parity import assert_topk_matches
@@ -509,6 +506,11 @@ def ivf_leg(etf, torch, args, steps, warmup):
             assert_topk_matches(ids_h[j], dist_h[j], ref, inside, k, "bench ivf q%d" % j)
         leg["parity_checked_queries"] = picks
         leg["vectors_in_probed_lists_per_query"] = scanned / len(picks)
+        if "ivf_scan" in kernels:
+            gbs = scanned / len(picks) * cfg.Q * cfg.M * 4.0 / (kernels["ivf_scan"]["ms_per_step"] / 1e3) / 1e9
+            leg["roofline_scan"] = {"bound": "alu", "resource": "LDS reads (on-chip): one gathered 4-byte table entry per chunk of every entry of the probed lists, counted once",
+                                    "kernel": "ivf_scan", "achieved": gbs, "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": gbs / LDS_PEAK_GBS, "traffic": None,
+                                    "note": "entries per query from the %d checked queries; the kernel evaluates the nearest lists a second time for its bound" % len(picks)}
         log("IVFADC: parity of the timed output against the oracle ok on queries %s" % picks)
     log("IVFADC (8192 cells, w=64) top-100: %.2f ms/step, %.3e queries/s; kernels %s"
         % (ms, leg["queries_per_s"], {n: round(v["ms_per_step"], 3) for n, v in kernels.items()}))

@@ -135,6 +135,16 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     where the smallest is not clearly below the second smallest (by twice a bound on the
  *                     rounding of either form) the float32 rule is evaluated for all K codewords.  1: the float32
  *                     rule for every codeword (needs d/M <= 128).  Both return the same codes, bit for bit
+ *   "ivf_coarse_kernel"  etf_ivf_search, distances between queries and centroids.  0 (default): all of them on the
+ *                     matrix cores as ||c||^2 - 2 q.c; the cells that can be among the w nearest, given a bound on
+ *                     the rounding of that form and of the float32 rule, are then evaluated by the rule, which
+ *                     decides.  1: the rule for every cell.  Both give the same probed cells, distances and order
+ *   "ivf_probe_cap"   most cells per query evaluated by the rule before the whole row is (0 = default: max(1024, 2 w);
+ *                     never below w), "ivf_probe_slack" a factor >= 1 on that rounding bound (default 1): both for tests
+ *   "ivf_bound_factor"  etf_ivf_search, scan of the probed lists: the bound on the k-th distance is taken from the
+ *                     nearest cells' lists that together hold this many times k entries (default 16), and from all
+ *                     probed lists if that bound lets more entries pass than the candidate list holds; 0: always
+ *                     from all lists.  The result does not depend on it
  *   "lds_filter"      the main pass of searches with traversal 2, which looks at every distinct encoding and only has
  *                     to decide which of them can be among the k nearest.
  *                     0: float32 sums of the table entries, compared with the query's bound (from the sample).
@@ -398,8 +408,8 @@ int etf_last_fallback_count(etf_ctx *ctx, int64_t *out);
  * per query, the ADC of every probed list on its Encoding Tree's leaf sequence: the entries of a cell sorted by
  * encoding, equal encodings merged into one entry with an id range.  A stored vector's distance
  *     || q - c - r ||^2  =  || q - c ||^2  +  ( ||r||^2 + 2 <c, r> )  -  2 <q, r>
- * (c its centroid, r its reconstructed residual) is evaluated as: the first term from the probe selection, the
- * second a float32 constant stored with the entry (the "extra information stored on the leaf node" of the paper's
+ * (c its centroid, r its reconstructed residual) is evaluated as: the first term from the probe selection (by the
+ * float32 rule below), the second a float32 constant stored with the entry (the "extra information stored on the leaf node" of the paper's
  * Experiments section), the third a sum of M entries of scalar-product tables that depend on the query only.
  * The terms cancel when q is close to the stored vector: a returned distance carries a rounding error of a few
  * 2^-24 of || q - c ||^2 + ||r||^2 + 2 |<q - c, r>| + 2 |<c, r>|, not of the distance itself.

@@ -386,6 +386,18 @@ extern "C" int etf_set_option(etf_ctx *ctx, const char *name, int64_t value)
     } else if (n == "lut_kernel") {
         if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "lut_kernel must be 0 (matrix cores) or 1 (plain sums)");
         ctx->opt.lut_kernel = value;
+    } else if (n == "ivf_coarse_kernel") {
+        if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "ivf_coarse_kernel must be 0 (matrix cores) or 1 (the float32 rule for every cell)");
+        ctx->opt.ivf_coarse_kernel = value;
+    } else if (n == "ivf_bound_factor") {
+        if (value < 0 || value > 1000000) return fail(ctx, ETF_EINVAL, "ivf_bound_factor must be in [0, 1e6]");
+        ctx->opt.ivf_bound_factor = value;
+    } else if (n == "ivf_probe_slack") {
+        if (value < 1 || value > 1000000000) return fail(ctx, ETF_EINVAL, "ivf_probe_slack must be in [1, 1e9]");
+        ctx->opt.ivf_probe_slack = value;
+    } else if (n == "ivf_probe_cap") {
+        if (value < 0 || value > 8192) return fail(ctx, ETF_EINVAL, "ivf_probe_cap must be in [0, 8192]");
+        ctx->opt.ivf_probe_cap = value;
     } else if (n == "lds16_context") {
         if (value < 0 || value > 1) return fail(ctx, ETF_EINVAL, "lds16_context is 0 or 1");
         ctx->opt.lds16_context = (int)value;

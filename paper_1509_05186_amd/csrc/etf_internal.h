@@ -102,6 +102,8 @@ struct IvfIndex {
     bool built = false;
     int Kc = 0;                         // cells
     std::vector<float> centroids;       // [Kc][d]
+    std::vector<float> cnorm;           // [Kc] ||centroid||^2
+    float cmax = 0.f;                   // largest ||centroid||, rounded up
     int64_t N = 0, Ne = 0;              // vectors, entries (distinct (cell, encoding) pairs)
     int64_t max_list = 0, max_dup = 0;  // most entries in one list, most vectors in one entry
     int64_t tree_lookups = 0;           // sum over the lists of the table lookups of the list's E-Tree (L1 + L2 + sumP)
@@ -110,7 +112,7 @@ struct IvfIndex {
     std::vector<float> eterm;           // [Ne] ||r||^2 + 2 <centroid, r>, r = the entry's reconstructed residual
     std::vector<uint32_t> ebegin;       // [Ne+1] range of ids_sorted of every entry
     std::vector<int32_t> ids_sorted;    // [N]
-    int64_t o_centroids = 0, o_codebooks = 0, o_lbegin = 0, o_ecodes = 0, o_eterm = 0, o_ebegin = 0, o_ids = 0, total = 0;
+    int64_t o_centroids = 0, o_cnorm = 0, o_codebooks = 0, o_lbegin = 0, o_ecodes = 0, o_eterm = 0, o_ebegin = 0, o_ids = 0, total = 0;
     char *dev_base = nullptr;           // caller-owned buffer holding the image
 };
 
@@ -126,6 +128,10 @@ struct Options {
     int64_t metric = 0;     // 0: squared Euclidean distance (smallest first), 1: scalar product (largest first)
     int64_t lds_filter = 2; // main pass of the LDS-resident search: 0 float32 sums, 1 / 2 candidate filter in 32 / 16-bit fixed point
     int64_t encode_kernel = 0; // device encoder: 0 distance evaluations on the matrix cores, near-ties by the float32 rule; 1 the rule for every codeword
+    int64_t ivf_coarse_kernel = 0; // IVFADC distances to the centroids: 0 matrix cores + the float32 rule near the w-th, 1 the rule for every cell
+    int64_t ivf_bound_factor = 16;  // IVFADC scan: the bound comes from the nearest lists that hold this many times k entries (0: from all lists)
+    int64_t ivf_probe_slack = 1;   // factor on the error bound of the matrix-core distances (tests: more cells, or all, go through the rule)
+    int64_t ivf_probe_cap = 0;     // cells the probe selection recomputes by the rule before it redoes the whole row (0: chosen by the library)
     int64_t lut_kernel = 0; // 0: matrix cores (expanded form on centred vectors, small entries recomputed), 1: plain (a-b)^2 sums
 };
 

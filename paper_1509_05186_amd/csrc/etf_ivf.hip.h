@@ -98,17 +98,13 @@ __global__ __launch_bounds__(256) void k_ivf_residual(const float *__restrict__ 
 // Probe selection: the w cells with the smallest (distance, index) of one query, ascending.  A radix select on the
 // float bits of the distances over the query's row of the distance matrix (and one on the cell numbers among exact
 // ties at the w-th, if they matter), then the w keys at or below the w-th are collected and sorted.
-//     grid (queries), block 256, dynamic LDS 8 * pow2(w) bytes; Kc <= 65536.
+//     row: the query's Kc distances (not negative); pk: LDS for pow2(w) keys; probes, base: the query's w cells and
+//     their distances.  Every thread of the workgroup of 256 calls it.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_ivf_probe(const float *__restrict__ dist, int Kc, int w, int32_t *__restrict__ probes)
+__device__ __forceinline__ void ivf_probe_row(const float *row, int Kc, int w, uint64_t *pk, uint32_t *hist, uint32_t *sel_sh, uint32_t *s_n,
+                                              int32_t *__restrict__ probes, float *__restrict__ base)
 {
-    extern __shared__ uint64_t pk[];
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t s_n;
-    const int64_t q = blockIdx.x;
-    const float *row = dist + q * Kc;
     // the w-th smallest distance, then, if more cells tie with it than are still needed, the largest cell number to take
-    __shared__ uint32_t sel_sh[8];
     uint32_t vstar, rank_in_ties, n_ties, cstar = 0xFFFFFFFFu;
     block_radix_select(
         Kc, (uint32_t)min(w, Kc), [&](int c, uint32_t &v) { v = __float_as_uint(row[c]); return true; }, hist, sel_sh, vstar,
@@ -124,12 +120,12 @@ __global__ __launch_bounds__(256) void k_ivf_probe(const float *__restrict__ dis
             },
             hist, sel_sh, cstar, r2, n2);
     }
-    if (threadIdx.x == 0) s_n = 0;
+    if (threadIdx.x == 0) *s_n = 0;
     __syncthreads();
     for (int c = threadIdx.x; c < Kc; c += 256) {
         const uint32_t v = __float_as_uint(row[c]);
         if (v < vstar || (v == vstar && (uint32_t)c <= cstar)) {
-            const uint32_t pos = atomicAdd(&s_n, 1u);
+            const uint32_t pos = atomicAdd(s_n, 1u);
             if (pos < (uint32_t)w) pk[pos] = ((uint64_t)v << 16) | (uint32_t)c;
         }
     }
@@ -138,7 +134,320 @@ __global__ __launch_bounds__(256) void k_ivf_probe(const float *__restrict__ dis
     for (int i = w + threadIdx.x; i < w2; i += 256) pk[i] = ~0ull;
     __syncthreads();
     bitonic_sort_u64(pk, w2);
-    for (int i = threadIdx.x; i < w; i += 256) probes[q * w + i] = (int32_t)(pk[i] & 0xFFFFu);
+    for (int i = threadIdx.x; i < w; i += 256) {
+        probes[i] = (int32_t)(pk[i] & 0xFFFFu);
+        base[i] = __uint_as_float((uint32_t)(pk[i] >> 16));
+    }
+}
+
+//     grid (queries), block 256, dynamic LDS 8 * pow2(w) bytes; Kc <= 65536.
+__global__ __launch_bounds__(256) void k_ivf_probe(const float *__restrict__ dist, int Kc, int w, int32_t *__restrict__ probes,
+                                                   float *__restrict__ base)
+{
+    extern __shared__ uint64_t pk[];
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_n;
+    __shared__ uint32_t sel_sh[8];
+    const int64_t q = blockIdx.x;
+    ivf_probe_row(dist + q * Kc, Kc, w, pk, hist, sel_sh, &s_n, probes + q * w, base + q * w);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The distance matrix of a batch of queries on the matrix cores, approximately, and without the query's own norm,
+// which is the same along its row:  a[q][c] = ||c||^2 - 2 <q, c>  (v_mfma_f32_32x32x2_f32, A = queries, B =
+// centroids, float32 in and out, operand layout as in k_lut_mfma: for a fixed accumulator register the lanes 0..31
+// hold 32 consecutive cells of one query, a 128-byte piece of a row of the matrix).  The probed cells are not decided
+// on these numbers: k_ivf_probe_mfma takes every cell that can be among the w nearest given the error of a[q][c] and
+// decides among them by the float32 rule.
+//     A wave owns 64 queries x 128 cells (2 x 4 accumulator blocks) and walks the dimensions 16 at a time (the two
+//     k-slots of the instruction take the lower and the upper 8, so a lane reads 8 consecutive floats of each of
+//     its six rows per block), the next block's operands in flight while the 64 instructions of this one run.
+//     grid (ceil(nq / 128), ceil(Kc / 256)), block 256 (wave w: queries 64 (w & 1).., cells 128 (w >> 1)..).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_ivf_coarse_mfma(const float *__restrict__ x, int64_t n, int d, const float *__restrict__ cent,
+                                                         const float *__restrict__ cnorm, int Kc, float *__restrict__ approx)
+{
+    const int lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6);
+    const int col = lane & 31, half = lane >> 5;
+    const int64_t qb = (int64_t)blockIdx.x * 128 + (w & 1) * 64;
+    const int cbase = (int)blockIdx.y * 256 + (w >> 1) * 128;
+    if (qb >= n || cbase >= Kc) return;  // the whole wave: there is no barrier below
+    const float *qrow[2], *crow[4];
+    bool qlive[2], clive[4];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        const int64_t q = qb + rb * 32 + col;
+        qlive[rb] = q < n;
+        qrow[rb] = x + (qlive[rb] ? q : 0) * d;
+    }
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+        const int c = cbase + cb * 32 + col;
+        clive[cb] = c < Kc;
+        crow[cb] = cent + (int64_t)(clive[cb] ? c : 0) * d;
+    }
+    const bool wide = (d & 3) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0 && (reinterpret_cast<uintptr_t>(cent) & 15) == 0;
+    auto load8 = [&](const float *row, bool live, int j, float (&o)[8]) {
+        if (wide && live && j + 8 <= d) {
+            const float4 lo = *reinterpret_cast<const float4 *>(row + j), hi = *reinterpret_cast<const float4 *>(row + j + 4);
+            o[0] = lo.x; o[1] = lo.y; o[2] = lo.z; o[3] = lo.w;
+            o[4] = hi.x; o[5] = hi.y; o[6] = hi.z; o[7] = hi.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] = (live && j + i < d) ? row[j + i] : 0.f;
+        }
+    };
+    auto load_block = [&](int j0, float (&a)[2][8], float (&b)[4][8]) {
+        const int j = j0 + 8 * half;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) load8(qrow[rb], qlive[rb], j, a[rb]);
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) load8(crow[cb], clive[cb], j, b[cb]);
+    };
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
+    auto multiply = [&](const float (&a)[2][8], const float (&b)[4][8]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb) acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rb][i], b[cb][i], acc[rb][cb], 0, 0, 0);
+    };
+    float a0[2][8], b0[4][8], a1[2][8], b1[4][8];
+    load_block(0, a0, b0);
+    for (int j0 = 0; j0 < d; j0 += 32) {
+        const bool second = j0 + 16 < d;
+        if (second) load_block(j0 + 16, a1, b1);
+        multiply(a0, b0);
+        if (second) {
+            if (j0 + 32 < d) load_block(j0 + 32, a0, b0);
+            multiply(a1, b1);
+        }
+    }
+    float cn[4];
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) cn[cb] = clive[cb] ? cnorm[cbase + cb * 32 + col] : 0.f;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t q = qb + rb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+            if (q >= n) continue;
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb)
+                if (clive[cb]) approx[q * Kc + cbase + cb * 32 + col] = fmaf(-2.f, acc[rb][cb][r], cn[cb]);
+        }
+}
+
+// One distance by the float32 rule (see k_ivf_coarse): q in LDS, c a centroid's row.
+__device__ __forceinline__ float ivf_rule_distance(const float *q, const float *__restrict__ c, int d)
+{
+    float acc = 0.f;
+    if ((d & 3) == 0 && (reinterpret_cast<uintptr_t>(c) & 15) == 0) {
+#pragma unroll 8
+        for (int j = 0; j < d; j += 4) {  // unrolled: the loads of eight steps are in flight together
+            const float4 cv = *reinterpret_cast<const float4 *>(c + j);
+            const float ce[4] = {cv.x, cv.y, cv.z, cv.w};
+            {
+#pragma clang fp contract(off)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float df = q[j + i] - ce[i];
+                    const float p = df * df;
+                    acc = acc + p;
+                }
+            }
+        }
+    } else {
+        for (int j = 0; j < d; ++j) {
+#pragma clang fp contract(off)
+            const float df = q[j] - c[j];
+            const float p = df * df;
+            acc = acc + p;
+        }
+    }
+    return acc;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Probe selection on the approximate matrix of k_ivf_coarse_mfma, with the result of the float32 rule.
+//     With a = ||c||^2 - 2 <q, c> as computed there and r the rule's distance, |a + ||q||^2 - r| <= E for
+//     E = (8 d + 16) 2^-24 (||q|| + max ||c||)^2: the centroid's norm, the contraction (d products, accumulated in
+//     float32, taken at twice the unit roundoff), the last operation and the rule's own d + 2 roundings are each at
+//     most their count times 2^-24 (||q|| + ||c||)^2, together (6 d + 7) of them.  So a cell among the w smallest
+//     by the rule has a <= a_w + 2 E, a_w the w-th smallest a of the row, and so a <= t + 2 E for any t with at
+//     least w cells at or below it (t: a bin edge of the row's range, see below).  Those cells are collected (a few
+//     more than w), their distances computed by the rule, and the w smallest (distance, cell) of them are the probes:
+//     the same cells, distances and order as k_ivf_coarse + k_ivf_probe give.  A row with more such cells than `cap`
+//     (or none: a row with a NaN or an infinity) is recomputed by the rule in full, in place, and handled like there.
+//     grid (queries), block 256, dynamic LDS ivf_probe_lds_bytes(w, cap, d); Kc <= 65536, cap >= w.
+// ------------------------------------------------------------------------------------------------
+__host__ __device__ inline int ivf_pow2(int n)
+{
+    int p = 1;
+    while (p < n) p <<= 1;
+    return p;
+}
+__host__ __device__ inline size_t ivf_probe_lds_bytes(int w, int cap, int d)
+{
+    (void)w;
+    return (size_t)ivf_pow2(cap) * 8 + (size_t)cap * 4 + (size_t)((d + 3) & ~3) * 4;
+}
+
+// f(c, row[c]) for every cell of a row, by the 256 threads of a workgroup: eight 16-byte loads in flight per thread
+// where the row allows them (a loop of single loads waits for the memory once per cell of the thread).
+template <class F>
+__device__ __forceinline__ void ivf_for_row(const float *__restrict__ row, int Kc, F f)
+{
+    if ((Kc & 3) == 0 && (reinterpret_cast<uintptr_t>(row) & 15) == 0) {
+        const float4 *row4 = reinterpret_cast<const float4 *>(row);
+        const int n4 = Kc >> 2;
+        for (int i0 = 0; i0 < n4; i0 += 256 * 8) {
+            float4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * 256 + (int)threadIdx.x;
+                v[u] = row4[min(i, n4 - 1)];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * 256 + (int)threadIdx.x;
+                if (i < n4) {
+                    f(4 * i, v[u].x);
+                    f(4 * i + 1, v[u].y);
+                    f(4 * i + 2, v[u].z);
+                    f(4 * i + 3, v[u].w);
+                }
+            }
+        }
+    } else {
+#pragma unroll 8
+        for (int c = threadIdx.x; c < Kc; c += 256) f(c, row[c]);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_ivf_probe_mfma(const float *__restrict__ x, int d, const float *__restrict__ cent, float cmax, float slack,
+                                                        float *__restrict__ approx, int Kc, int w, int cap,
+                                                        int32_t *__restrict__ probes, float *__restrict__ base)
+{
+    extern __shared__ uint64_t pk[];
+    __shared__ uint32_t hist[1024];
+    __shared__ uint32_t s_n;
+    __shared__ uint32_t sel_sh[8];
+    __shared__ float s_red[4], s_lo[4], s_hi[4];
+    const int cap2 = ivf_pow2(cap);
+    int32_t *s_cell = reinterpret_cast<int32_t *>(pk + cap2);
+    float *qs = reinterpret_cast<float *>(s_cell + cap);
+    const int64_t q = blockIdx.x;
+    float *row = approx + q * Kc;
+    float part = 0.f;
+    for (int j = threadIdx.x; j < d; j += 256) {
+        const float v = x[q * d + j];
+        qs[j] = v;
+        part = fmaf(v, v, part);
+    }
+#pragma unroll
+    for (int dlt = 32; dlt >= 1; dlt >>= 1) part += __shfl_xor(part, dlt);
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = part;
+    if (threadIdx.x == 0) s_n = 0;
+    __syncthreads();
+    const float qq = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+    const float S = sqrtf(qq) * 1.001f + cmax;
+    const float E2 = 2.f * (float)(8 * d + 16) * 5.9604645e-8f * 1.01f * S * S * slack;
+    // A bound at or above the w-th smallest a of the row, without sorting anything: the row's range in 1024 equal bins,
+    // the first bin at which the running count reaches w, its upper edge.  (A radix select on the float bits finds the
+    // w-th itself, but its first digits are the same for nearly all cells: every count lands on one LDS word.)
+    constexpr int NB = 1024;
+    float lo = 3.402823466e+38f, hi = -3.402823466e+38f;
+    ivf_for_row(row, Kc, [&](int, float v) {
+        lo = fminf(lo, v);
+        hi = fmaxf(hi, v);
+    });
+#pragma unroll
+    for (int dlt = 32; dlt >= 1; dlt >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, dlt));
+        hi = fmaxf(hi, __shfl_xor(hi, dlt));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        s_lo[threadIdx.x >> 6] = lo;
+        s_hi[threadIdx.x >> 6] = hi;
+    }
+    for (int i = threadIdx.x; i < NB; i += 256) hist[i] = 0u;
+    __syncthreads();
+    lo = fminf(fminf(s_lo[0], s_lo[1]), fminf(s_lo[2], s_lo[3]));
+    hi = fmaxf(fmaxf(s_hi[0], s_hi[1]), fmaxf(s_hi[2], s_hi[3]));
+    const float span = hi - lo;
+    const bool usable = span >= 0.f && span < 3.0e38f;  // false with a NaN or an infinity in the row
+    const float scale = span > 0.f ? (float)NB / span : 0.f;
+    auto bin_of = [&](float v) { return min(NB - 1, (int)((v - lo) * scale)); };
+    if (usable) ivf_for_row(row, Kc, [&](int, float v) { atomicAdd(&hist[bin_of(v)], 1u); });
+    __syncthreads();
+    {
+        // thread t owns bins 4t .. 4t+3; the running count before them by a scan over the threads
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        uint32_t h[4], own = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            h[i] = hist[4 * threadIdx.x + i];
+            own += h[i];
+        }
+        uint32_t inc = own;
+#pragma unroll
+        for (int dlt = 1; dlt < 64; dlt <<= 1) {
+            const uint32_t up = (uint32_t)__shfl_up((int)inc, dlt);
+            if (lane >= dlt) inc += up;
+        }
+        if (lane == 63) sel_sh[wave] = inc;
+        __syncthreads();
+        for (int w2 = 0; w2 < wave; ++w2) inc += sel_sh[w2];
+        uint32_t run = inc - own;
+        const uint32_t need = (uint32_t)min(w, Kc);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (run < need && need <= run + h[i]) sel_sh[4] = (uint32_t)(4 * threadIdx.x + i);
+            run += h[i];
+        }
+        if (threadIdx.x == 0 && !usable) sel_sh[4] = 0u;
+        __syncthreads();
+    }
+    const float thr = usable ? lo + (float)(sel_sh[4] + 1u) * (span / (float)NB) + E2 : -3.402823466e+38f;
+    if (usable)
+        ivf_for_row(row, Kc, [&](int c, float v) {
+            if (v <= thr) {
+                const uint32_t pos = atomicAdd(&s_n, 1u);
+                if (pos < (uint32_t)cap) s_cell[pos] = c;
+            }
+        });
+    __syncthreads();
+    const int ncand = (int)s_n;
+    __syncthreads();
+    if (ncand > cap || ncand < min(w, Kc)) {
+        for (int c = threadIdx.x; c < Kc; c += 256) row[c] = ivf_rule_distance(qs, cent + (int64_t)c * d, d);
+        __syncthreads();
+        ivf_probe_row(row, Kc, w, pk, hist, sel_sh, &s_n, probes + q * w, base + q * w);
+        return;
+    }
+    const int n2 = ivf_pow2(ncand);
+    for (int i = threadIdx.x; i < n2; i += 256) {
+        uint64_t key = ~0ull;
+        if (i < ncand) {
+            const int c = s_cell[i];
+            key = ((uint64_t)__float_as_uint(ivf_rule_distance(qs, cent + (int64_t)c * d, d)) << 16) | (uint32_t)c;
+        }
+        pk[i] = key;
+    }
+    __syncthreads();
+    bitonic_sort_u64(pk, n2);
+    for (int i = threadIdx.x; i < w; i += 256) {
+        probes[q * w + i] = (int32_t)(pk[i] & 0xFFFFu);
+        base[q * w + i] = __uint_as_float((uint32_t)(pk[i] >> 16));
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -146,7 +455,7 @@ __global__ __launch_bounds__(256) void k_ivf_probe(const float *__restrict__ dis
 // ------------------------------------------------------------------------------------------------
 struct IvfScanArgs {
     const float *lut;         // [nq][M][K] scalar products <q_m, codeword>
-    const float *coarse;      // [nq][Kc] squared distances to the centroids
+    const float *base;        // [nq][w] squared distances to the probed cells' centroids
     const int32_t *probes;    // [nq][w]
     int M, K, Kc, w, k;
     const uint32_t *lbegin;   // [Kc+1]
@@ -157,6 +466,7 @@ struct IvfScanArgs {
     uint32_t *cnt;            // [nq]
     uint64_t *cand;           // [nq][C]
     uint32_t C;
+    uint32_t bound_entries;   // scan: entries of the nearest lists that the bound is taken from (0: all lists)
     uint32_t *flag;           // [nq]
     uint32_t *nflag;          // running count of queries answered by the exact kernel
     int32_t *out_ids;         // [nq][k]   (exact kernel)
@@ -202,15 +512,16 @@ __device__ __forceinline__ float ivf_distance_words(const float *tab, const uint
 
 // Every entry of the probed lists once: wave v of the workgroup takes lists v, v + 4, ..., its lanes the entries of a
 // list 128 at a time, two per lane, so that the loads of two entries (codes, stored term) are in flight together
-// and no position has to be looked up among the lists.  f(entry, distance) runs for every entry.
+// and no position has to be looked up among the lists.  f(entry, distance) runs for every entry of the first nlists
+// lists.
 // CM, CK: M and K as constants (the common shape, loops unrolled and table offsets immediate), or 0: taken from a.
 template <int CM, int CK, class F>
 __device__ __forceinline__ void ivf_walk_shape(const IvfScanArgs &a, const float *tab, const uint32_t *s_off, const uint32_t *s_lo,
-                                               const float *s_base, F f)
+                                               const float *s_base, int nlists, F f)
 {
     const int M = CM ? CM : a.M, K = CK ? CK : a.K;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    for (int p = wave; p < a.w; p += nw) {
+    for (int p = wave; p < nlists; p += nw) {
         const uint32_t lo = s_lo[p], n = s_off[p + 1] - s_off[p];
         const float base = s_base[p];
         for (uint32_t i0 = lane; i0 < n; i0 += 128) {
@@ -230,12 +541,12 @@ __device__ __forceinline__ void ivf_walk_shape(const IvfScanArgs &a, const float
 
 template <class F>
 __device__ __forceinline__ void ivf_walk(const IvfScanArgs &a, const float *tab, const uint32_t *s_off, const uint32_t *s_lo,
-                                         const float *s_base, F f)
+                                         const float *s_base, int nlists, F f)
 {
     if (a.M == 8 && a.K == 256)
-        ivf_walk_shape<8, 256>(a, tab, s_off, s_lo, s_base, f);
+        ivf_walk_shape<8, 256>(a, tab, s_off, s_lo, s_base, nlists, f);
     else
-        ivf_walk_shape<0, 0>(a, tab, s_off, s_lo, s_base, f);
+        ivf_walk_shape<0, 0>(a, tab, s_off, s_lo, s_base, nlists, f);
 }
 
 // The w probed lists of a query as one sequence of entries: s_off[p] = entries before list p.  Thread i of a flat
@@ -264,7 +575,7 @@ __device__ __forceinline__ void ivf_setup_lists(const IvfScanArgs &a, int64_t q,
         const int cell = a.probes[q * a.w + p];
         s_lo[p] = a.lbegin[cell];
         s_off[p + 1] = a.lbegin[cell + 1] - a.lbegin[cell];
-        s_base[p] = a.coarse[q * a.Kc + cell];
+        s_base[p] = a.base[q * a.w + p];
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -287,9 +598,10 @@ __host__ __device__ inline size_t ivf_lds_bytes(int M, int K, int w, bool hist)
 
 // ------------------------------------------------------------------------------------------------
 // Scan of the probed lists of one query: every entry's distance from the query's tables in LDS (lane = entry).
-//     Pass 1 counts the vectors per distance bin (a histogram over the upper bits of the float) and finds the bin in
-//     which the running count reaches k: its upper edge bounds the k-th distance.  Pass 2 evaluates the entries again
-//     and appends those at or below the bound to the query's candidate list, which k_select orders and expands.
+//     Pass 1 counts the vectors per distance bin (a histogram over the upper bits of the float) over the nearest
+//     cells' lists, as many as together hold bound_entries entries, and finds the bin in which the running count
+//     reaches k: its upper edge bounds the k-th distance.  Pass 2 evaluates the entries of all lists and appends
+//     those at or below the bound to the query's candidate list, which k_select orders and expands.
 //     grid (queries), block 256, dynamic LDS ivf_lds_bytes(..., true).
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_ivf_scan(IvfScanArgs a)
@@ -308,39 +620,62 @@ __global__ __launch_bounds__(256) void k_ivf_scan(IvfScanArgs a)
     for (int i = threadIdx.x; i < NB; i += 256) hist[i] = 0;
     if (threadIdx.x == 0) s_cnt = 0;
     ivf_setup_lists(a, q, s_off, s_lo, s_base);
-    ivf_walk(a, tab, s_off, s_lo, s_base, [&](uint32_t e, float d) {
-        atomicAdd(&hist[__float_as_uint(d) >> SH], min(a.ebegin[e + 1] - a.ebegin[e], (uint32_t)a.k));
-    });
-    __syncthreads();
-    // the bin in which the running count of vectors reaches k (thread t owns bins [t * NB/256, (t+1) * NB/256))
-    {
-        constexpr int PER = NB / 256;
-        uint32_t part = 0;
-        for (int b = 0; b < PER; ++b) part += hist[threadIdx.x * PER + b];
-        s_part[threadIdx.x] = part;
-        if (threadIdx.x == 0) s_tau = 0x7F800000u;  // fewer than k vectors in the probed lists: everything passes
-        __syncthreads();
-        uint32_t below = 0;
-        for (int t2 = 0; t2 < (int)threadIdx.x; ++t2) below += s_part[t2];
-        if (below < (uint32_t)a.k && below + part >= (uint32_t)a.k) {
-            int b = 0;
-            for (; b < PER - 1; ++b) {
-                const uint32_t h = hist[threadIdx.x * PER + b];
-                if (below + h >= (uint32_t)a.k) break;
-                below += h;
-            }
-            s_tau = (((uint32_t)(threadIdx.x * PER + b) + 1u) << SH) - 1u;  // upper edge of that bin
+    // The bound comes from the nearest cells alone: the first lists that together hold bound_entries entries (all, if
+    // they do not).  The k-th smallest distance among part of the vectors is at or above the k-th among all.  Where
+    // that bound lets more entries pass than the candidate list holds (a query whose neighbours sit in a farther
+    // cell), the bound is taken again, from all lists.
+    int nbound = a.w;
+    if (a.bound_entries > 0) {
+        int lo = 1, hi = a.w;  // smallest p with s_off[p] >= bound_entries
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_off[mid] >= a.bound_entries) hi = mid;
+            else lo = mid + 1;
         }
+        nbound = lo;
+    }
+    for (;;) {
+        ivf_walk(a, tab, s_off, s_lo, s_base, nbound, [&](uint32_t e, float d) {
+            atomicAdd(&hist[__float_as_uint(d) >> SH], min(a.ebegin[e + 1] - a.ebegin[e], (uint32_t)a.k));
+        });
+        __syncthreads();
+        // the bin in which the running count of vectors reaches k (thread t owns bins [t * NB/256, (t+1) * NB/256))
+        {
+            constexpr int PER = NB / 256;
+            uint32_t part = 0;
+            for (int b = 0; b < PER; ++b) part += hist[threadIdx.x * PER + b];
+            s_part[threadIdx.x] = part;
+            if (threadIdx.x == 0) s_tau = 0x7F800000u;  // fewer than k vectors in the lists: everything passes
+            __syncthreads();
+            uint32_t below = 0;
+            for (int t2 = 0; t2 < (int)threadIdx.x; ++t2) below += s_part[t2];
+            if (below < (uint32_t)a.k && below + part >= (uint32_t)a.k) {
+                int b = 0;
+                for (; b < PER - 1; ++b) {
+                    const uint32_t h = hist[threadIdx.x * PER + b];
+                    if (below + h >= (uint32_t)a.k) break;
+                    below += h;
+                }
+                s_tau = (((uint32_t)(threadIdx.x * PER + b) + 1u) << SH) - 1u;  // upper edge of that bin
+            }
+            __syncthreads();
+        }
+        const uint32_t tau = s_tau;
+        ivf_walk(a, tab, s_off, s_lo, s_base, a.w, [&](uint32_t e, float d) {
+            const uint32_t bits = __float_as_uint(d);
+            if (bits <= tau) {
+                const uint32_t pos = atomicAdd(&s_cnt, 1u);
+                if (pos < a.C) a.cand[q * a.C + pos] = ((uint64_t)bits << 32) | e;
+            }
+        });
+        __syncthreads();
+        if (nbound == a.w || s_cnt <= a.C) break;
+        __syncthreads();
+        nbound = a.w;
+        for (int i = threadIdx.x; i < NB; i += 256) hist[i] = 0;
+        if (threadIdx.x == 0) s_cnt = 0;
         __syncthreads();
     }
-    const uint32_t tau = s_tau;
-    ivf_walk(a, tab, s_off, s_lo, s_base, [&](uint32_t e, float d) {
-        const uint32_t bits = __float_as_uint(d);
-        if (bits <= tau) {
-            const uint32_t pos = atomicAdd(&s_cnt, 1u);
-            if (pos < a.C) a.cand[q * a.C + pos] = ((uint64_t)bits << 32) | e;
-        }
-    });
     __syncthreads();
     if (threadIdx.x == 0) a.cnt[q] = s_cnt;
 }
@@ -476,6 +811,7 @@ void ivf_layout(etf_ctx *ctx)
         return o;
     };
     iv.o_centroids = take((int64_t)iv.Kc * ctx->d * 4);
+    iv.o_cnorm = take((int64_t)iv.Kc * 4);
     iv.o_codebooks = take((int64_t)ctx->codebooks.size() * 4);
     iv.o_lbegin = take(((int64_t)iv.Kc + 1) * 4);
     iv.o_ecodes = take(iv.Ne * ctx->M);
@@ -488,7 +824,8 @@ void ivf_layout(etf_ctx *ctx)
 struct IvfPlan {
     int64_t nqb = 0;  // queries per batch
     uint32_t C = 0;
-    int64_t o_counter = 0, o_coarse = 0, o_probes = 0, o_lut = 0, o_cnt = 0, o_flag = 0, o_cand = 0, total = 0;
+    int cap = 0;      // cells per query the probe selection recomputes by the float32 rule
+    int64_t o_counter = 0, o_coarse = 0, o_probes = 0, o_base = 0, o_lut = 0, o_cnt = 0, o_flag = 0, o_cand = 0, total = 0;
 };
 
 int ivf_plan(const etf_ctx *ctx, int64_t Q, int k, int w, IvfPlan &P)
@@ -504,7 +841,8 @@ int ivf_plan(const etf_ctx *ctx, int64_t Q, int k, int w, IvfPlan &P)
         while (C < 8 * (int64_t)k) C <<= 1;
     }
     P.C = (uint32_t)C;
-    const int64_t per_q = (int64_t)iv.Kc * 4 + (int64_t)w * 4 + (int64_t)ctx->M * ctx->K * 4 + 8 + C * 8;
+    P.cap = ctx->opt.ivf_probe_cap ? (int)std::max<int64_t>(ctx->opt.ivf_probe_cap, w) : std::max(1024, 2 * w);
+    const int64_t per_q = (int64_t)iv.Kc * 4 + (int64_t)w * 8 + (int64_t)ctx->M * ctx->K * 4 + 8 + C * 8;
     P.nqb = std::max<int64_t>(1, std::min<int64_t>(Q, ctx->opt.ws_cap_bytes / per_q));
     int64_t off = 0;
     auto take = [&](int64_t bytes) {
@@ -515,6 +853,7 @@ int ivf_plan(const etf_ctx *ctx, int64_t Q, int k, int w, IvfPlan &P)
     P.o_counter = take(256);
     P.o_coarse = take(P.nqb * iv.Kc * 4);
     P.o_probes = take(P.nqb * w * 4);
+    P.o_base = take(P.nqb * w * 4);
     P.o_lut = take(P.nqb * ctx->M * ctx->K * 4);
     P.o_cnt = take(P.nqb * 4);
     P.o_flag = take(P.nqb * 4);
@@ -534,6 +873,15 @@ extern "C" int etf_ivf_set_coarse(etf_ctx *ctx, const float *centroids, int Kc)
         ctx->ivf = IvfIndex();
         ctx->ivf.Kc = Kc;
         ctx->ivf.centroids.assign(centroids, centroids + (size_t)Kc * ctx->d);
+        ctx->ivf.cnorm.resize((size_t)Kc);
+        double big = 0.0;
+        for (int c = 0; c < Kc; ++c) {
+            double t = 0.0;
+            for (int j = 0; j < ctx->d; ++j) t += (double)centroids[(size_t)c * ctx->d + j] * (double)centroids[(size_t)c * ctx->d + j];
+            ctx->ivf.cnorm[c] = (float)t;
+            big = std::max(big, t);
+        }
+        ctx->ivf.cmax = (float)(std::sqrt(big) * 1.000001);
     } catch (const std::bad_alloc &) {
         return fail(ctx, ETF_ENOMEM, "out of host memory");
     }
@@ -670,6 +1018,7 @@ extern "C" int etf_ivf_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes)
     hipStream_t st = (hipStream_t)ctx->stream;
     char *base = (char *)dev_buf;
     HIP_TRY(ctx, hipMemcpyAsync(base + iv.o_centroids, iv.centroids.data(), iv.centroids.size() * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(ctx, hipMemcpyAsync(base + iv.o_cnorm, iv.cnorm.data(), iv.cnorm.size() * 4, hipMemcpyHostToDevice, st));
     HIP_TRY(ctx, hipMemcpyAsync(base + iv.o_codebooks, ctx->codebooks.data(), ctx->codebooks.size() * 4, hipMemcpyHostToDevice, st));
     HIP_TRY(ctx, hipMemcpyAsync(base + iv.o_lbegin, iv.lbegin.data(), iv.lbegin.size() * 4, hipMemcpyHostToDevice, st));
     HIP_TRY(ctx, hipMemcpyAsync(base + iv.o_ecodes, iv.ecodes.data(), iv.ecodes.size(), hipMemcpyHostToDevice, st));
@@ -682,12 +1031,21 @@ extern "C" int etf_ivf_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes)
 }
 
 // ---- database side on the device: cell, residual, residual encoding ------------------------------------------
+// vectors per batch of the coarse assignment: their distance matrix stays within 256 MiB
+static int64_t ivf_assign_batch(const etf_ctx *ctx, int64_t n)
+{
+    const int64_t by_bytes = ((int64_t)256 << 20) / ((int64_t)ctx->ivf.Kc * 4);
+    return std::max<int64_t>(1, std::min<int64_t>(n, std::max<int64_t>(256, by_bytes)));
+}
+
 extern "C" int64_t etf_ivf_assign_workspace_bytes(const etf_ctx *ctx, int64_t n)
 {
     if (!ctx) return ETF_EINVAL;
     if (ctx->codebooks.empty() || ctx->ivf.Kc == 0) return fail(ctx, ETF_ESTATE, "need codebooks and etf_ivf_set_coarse first");
     if (n < 0) return fail(ctx, ETF_EINVAL, "n is negative");
-    return ivf_al((int64_t)ctx->ivf.Kc * ctx->d * 4) + ivf_al(etf_encode_workspace_bytes(ctx)) + ivf_al(n * ctx->d * 4);
+    const int64_t nb = ivf_assign_batch(ctx, n);
+    return ivf_al((int64_t)ctx->ivf.Kc * ctx->d * 4) + ivf_al((int64_t)ctx->ivf.Kc * 4) + ivf_al(nb * ctx->ivf.Kc * 4) + ivf_al(nb * 4) +
+           ivf_al(etf_encode_workspace_bytes(ctx)) + ivf_al(n * ctx->d * 4);
 }
 
 extern "C" int etf_ivf_assign_device(etf_ctx *ctx, const float *x, int64_t n, int32_t *cells_out, uint8_t *codes_out, void *ws,
@@ -705,17 +1063,45 @@ extern "C" int etf_ivf_assign_device(etf_ctx *ctx, const float *x, int64_t n, in
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     hipStream_t st = (hipStream_t)ctx->stream;
     const IvfIndex &iv = ctx->ivf;
+    const int d = ctx->d;
+    const int64_t nb = ivf_assign_batch(ctx, n);
     char *w = (char *)ws;
     float *cent = (float *)w;
-    char *enc_ws = w + ivf_al((int64_t)iv.Kc * ctx->d * 4);
+    w += ivf_al((int64_t)iv.Kc * d * 4);
+    float *cnorm = (float *)w;
+    w += ivf_al((int64_t)iv.Kc * 4);
+    float *matrix = (float *)w;
+    w += ivf_al(nb * iv.Kc * 4);
+    float *nearest = (float *)w;
+    w += ivf_al(nb * 4);
+    char *enc_ws = w;
     const int64_t enc_bytes = ivf_al(etf_encode_workspace_bytes(ctx));
     float *res = (float *)(enc_ws + enc_bytes);
     HIP_TRY(ctx, hipMemcpyAsync(cent, iv.centroids.data(), iv.centroids.size() * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(ctx, hipMemcpyAsync(cnorm, iv.cnorm.data(), iv.cnorm.size() * 4, hipMemcpyHostToDevice, st));
     {
         ProfScope prof(ctx, ETF_K_ENCODE);
-        hipLaunchKernelGGL(k_ivf_coarse<true>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, x, n, ctx->d, cent, iv.Kc, nullptr, cells_out, iv.Kc);
-        LAUNCH_CHECK(ctx, "k_ivf_coarse");
-        hipLaunchKernelGGL(k_ivf_residual, dim3((unsigned)((n * ctx->d + 255) / 256)), dim3(256), 0, st, x, n, ctx->d, cent, cells_out, res);
+        if (ctx->opt.ivf_coarse_kernel == 0) {
+            // the cell of a vector is its one probed cell: smallest (distance, cell) by the float32 rule
+            const int cap = 1024;
+            const size_t lds_probe = ivf_probe_lds_bytes(1, cap, d);
+            if (lds_probe > 150 * 1024) return fail(ctx, ETF_EINVAL, "d=%d needs %zu bytes of LDS for the cell selection", d, lds_probe);
+            rc = set_lds(ctx, k_ivf_probe_mfma, lds_probe);
+            if (rc) return rc;
+            for (int64_t v0 = 0; v0 < n; v0 += nb) {
+                const int64_t nv = std::min<int64_t>(nb, n - v0);
+                hipLaunchKernelGGL(k_ivf_coarse_mfma, dim3((unsigned)((nv + 127) / 128), (unsigned)((iv.Kc + 255) / 256)), dim3(256), 0, st,
+                                   x + v0 * d, nv, d, cent, cnorm, iv.Kc, matrix);
+                LAUNCH_CHECK(ctx, "k_ivf_coarse_mfma");
+                hipLaunchKernelGGL(k_ivf_probe_mfma, dim3((unsigned)nv), dim3(256), lds_probe, st, x + v0 * d, d, cent, iv.cmax,
+                                   (float)ctx->opt.ivf_probe_slack, matrix, iv.Kc, 1, cap, cells_out + v0, nearest);
+                LAUNCH_CHECK(ctx, "k_ivf_probe_mfma");
+            }
+        } else {
+            hipLaunchKernelGGL(k_ivf_coarse<true>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, x, n, d, cent, iv.Kc, nullptr, cells_out, iv.Kc);
+            LAUNCH_CHECK(ctx, "k_ivf_coarse");
+        }
+        hipLaunchKernelGGL(k_ivf_residual, dim3((unsigned)((n * d + 255) / 256)), dim3(256), 0, st, x, n, d, cent, cells_out, res);
         LAUNCH_CHECK(ctx, "k_ivf_residual");
     }
     return etf_pq_encode_device(ctx, res, n, codes_out, enc_ws, enc_bytes);
@@ -760,6 +1146,10 @@ extern "C" int etf_ivf_search(etf_ctx *ctx, const float *queries, int64_t Q, int
     if (rc) return rc;
     rc = set_lds(ctx, k_ivf_exact, lds_exact);
     if (rc) return rc;
+    const size_t lds_probe = ivf_probe_lds_bytes(w, P.cap, d);
+    if (lds_probe > 150 * 1024) return fail(ctx, ETF_EINVAL, "w=%d with d=%d needs %zu bytes of LDS for the probe selection", w, d, lds_probe);
+    rc = set_lds(ctx, k_ivf_probe_mfma, lds_probe);
+    if (rc) return rc;
     const float *cent = reinterpret_cast<const float *>(img + iv.o_centroids);
     const float *cbd = reinterpret_cast<const float *>(img + iv.o_codebooks);
     ChunkOrder ord;
@@ -773,18 +1163,29 @@ extern "C" int etf_ivf_search(etf_ctx *ctx, const float *queries, int64_t Q, int
         uint32_t *cnt = reinterpret_cast<uint32_t *>(wsp + P.o_cnt);
         uint32_t *flag = reinterpret_cast<uint32_t *>(wsp + P.o_flag);
         uint64_t *cand = reinterpret_cast<uint64_t *>(wsp + P.o_cand);
+        float *pbase = reinterpret_cast<float *>(wsp + P.o_base);
         {
             ProfScope prof(ctx, ETF_K_IVF_COARSE);
-            // about 2048 workgroups: the centroids in slices of whole tiles of 32
-            const int64_t qblocks = (nq + 255) / 256;
-            int64_t slices = std::max<int64_t>(1, std::min<int64_t>((iv.Kc + 31) / 32, 2048 / qblocks));
-            const int cslice = (int)(((iv.Kc + slices - 1) / slices + 31) / 32 * 32);
-            slices = (iv.Kc + cslice - 1) / cslice;
-            hipLaunchKernelGGL(k_ivf_coarse<false>, dim3((unsigned)qblocks, (unsigned)slices), dim3(256), 0, st, qb, nq, d, cent, iv.Kc, coarse,
-                               nullptr, cslice);
-            LAUNCH_CHECK(ctx, "k_ivf_coarse");
-            hipLaunchKernelGGL(k_ivf_probe, dim3((unsigned)nq), dim3(256), (size_t)pow2_at_least_host(w) * 8, st, coarse, iv.Kc, w, probes);
-            LAUNCH_CHECK(ctx, "k_ivf_probe");
+            if (ctx->opt.ivf_coarse_kernel == 0) {
+                const float *cnorm = reinterpret_cast<const float *>(img + iv.o_cnorm);
+                hipLaunchKernelGGL(k_ivf_coarse_mfma, dim3((unsigned)((nq + 127) / 128), (unsigned)((iv.Kc + 255) / 256)), dim3(256), 0, st, qb, nq, d,
+                                   cent, cnorm, iv.Kc, coarse);
+                LAUNCH_CHECK(ctx, "k_ivf_coarse_mfma");
+                hipLaunchKernelGGL(k_ivf_probe_mfma, dim3((unsigned)nq), dim3(256), lds_probe, st, qb, d, cent, iv.cmax, (float)ctx->opt.ivf_probe_slack, coarse, iv.Kc, w, P.cap, probes,
+                                   pbase);
+                LAUNCH_CHECK(ctx, "k_ivf_probe_mfma");
+            } else {
+                // about 2048 workgroups: the centroids in slices of whole tiles of 32
+                const int64_t qblocks = (nq + 255) / 256;
+                int64_t slices = std::max<int64_t>(1, std::min<int64_t>((iv.Kc + 31) / 32, 2048 / qblocks));
+                const int cslice = (int)(((iv.Kc + slices - 1) / slices + 31) / 32 * 32);
+                slices = (iv.Kc + cslice - 1) / cslice;
+                hipLaunchKernelGGL(k_ivf_coarse<false>, dim3((unsigned)qblocks, (unsigned)slices), dim3(256), 0, st, qb, nq, d, cent, iv.Kc, coarse,
+                                   nullptr, cslice);
+                LAUNCH_CHECK(ctx, "k_ivf_coarse");
+                hipLaunchKernelGGL(k_ivf_probe, dim3((unsigned)nq), dim3(256), (size_t)pow2_at_least_host(w) * 8, st, coarse, iv.Kc, w, probes, pbase);
+                LAUNCH_CHECK(ctx, "k_ivf_probe");
+            }
         }
         {
             // tables of scalar products <q_m, codeword>, one set per query, shared by all cells
@@ -801,7 +1202,7 @@ extern "C" int etf_ivf_search(etf_ctx *ctx, const float *queries, int64_t Q, int
         IvfScanArgs a;
         memset(&a, 0, sizeof a);
         a.lut = lut;
-        a.coarse = coarse;
+        a.base = pbase;
         a.probes = probes;
         a.M = M;
         a.K = K;
@@ -816,6 +1217,7 @@ extern "C" int etf_ivf_search(etf_ctx *ctx, const float *queries, int64_t Q, int
         a.cnt = cnt;
         a.cand = cand;
         a.C = P.C;
+        a.bound_entries = (uint32_t)std::min<int64_t>((int64_t)ctx->opt.ivf_bound_factor * k, 0x7FFFFFFF);
         a.flag = flag;
         a.nflag = counter;
         a.out_ids = out_ids + q0 * k;

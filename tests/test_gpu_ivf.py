@@ -75,13 +75,16 @@ def prob():
 
 def test_ivf_assign_device_equals_oracle(prob):
     say("IVFADC: coarse assignment and residual encoding on the device")
-    c = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
-    c.pq_set_codebooks(prob.cb)
-    c.ivf_set_coarse(prob.cent)
-    cells, codes = c.ivf_assign_device(torch.from_numpy(prob.x).cuda())
-    torch.cuda.synchronize()
-    assert np.array_equal(cells.cpu().numpy(), prob.cells)
-    assert np.array_equal(codes.cpu().numpy(), prob.codes)
+    for opts in ({}, {"ivf_coarse_kernel": 1}, {"ivf_probe_slack": 10 ** 9}):   # matrix cores + rule; rule alone; every row redone
+        c = etf.Context(device=0, stream=torch.cuda.current_stream().cuda_stream)
+        for name, v in opts.items():
+            c.set_option(name, v)
+        c.pq_set_codebooks(prob.cb)
+        c.ivf_set_coarse(prob.cent)
+        cells, codes = c.ivf_assign_device(torch.from_numpy(prob.x).cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(cells.cpu().numpy(), prob.cells), opts
+        assert np.array_equal(codes.cpu().numpy(), prob.codes), opts
     cells0, codes0 = c.ivf_assign_device(torch.empty((0, 32), dtype=torch.float32, device="cuda"))
     assert cells0.shape == (0,) and codes0.shape == (0, 8)
 
@@ -132,6 +135,43 @@ def test_ivf_exact_kernel_ids_and_small_candidate_lists(prob):
         torch.cuda.synchronize()
         assert c.last_fallback_count() > 0
         assert torch.equal(got_i, want_i) and torch.equal(got_d, want_d)
+
+
+@pytest.mark.parametrize("w,k", [(1, 10), (64, 100), (1024, 50)])
+def test_ivf_probe_selection_variants_agree(prob, w, k):
+    say("IVFADC: probes from the matrix-core distances, from the rule alone, with a wide margin, with every row redone;",
+        "the scan's bound from all lists, from the nearest one, with a second attempt; w =", w)
+    qd = torch.from_numpy(prob.q).cuda()
+    want_i, want_d = prob.ctx(ivf_coarse_kernel=1).ivf_search(qd, k, w)
+    torch.cuda.synchronize()
+    prob.check(want_i.cpu().numpy(), want_d.cpu().numpy(), k, w, what="ivf rule w%d" % w)
+    for opts in ({}, {"ivf_probe_slack": 3000}, {"ivf_probe_slack": 10 ** 9}, {"ivf_probe_cap": 1},
+                 {"ivf_bound_factor": 0}, {"ivf_bound_factor": 1}, {"ivf_bound_factor": 1, "cand_cap": 128}):
+        c = prob.ctx(**opts)
+        got_i, got_d = c.ivf_search(qd, k, w)
+        torch.cuda.synchronize()
+        assert torch.equal(got_i, want_i) and torch.equal(got_d, want_d), opts
+
+
+def test_ivf_probe_selection_odd_shapes():
+    say("IVFADC: dimension not a multiple of 16 or 4, cells not a multiple of 32, far-off data (large norms, small distances)")
+    for d, M, cells, shift in ((20, 4, 77, 0.0), (18, 6, 300, 50.0), (128, 8, 520, 0.0)):
+        p = IvfProblem(d=d, M=M, K=16, cells=cells, N=5000, Q=130, seed=40 + d)
+        if shift:
+            p.x += np.float32(shift); p.q += np.float32(shift); p.cent += np.float32(shift)
+            p.cells, p.codes = ivfadc.build(p.x, p.cent, p.cb)
+            p.xhat = ivfadc.reconstruct(p.cent, p.cb, p.cells, p.codes)
+        k, w = 20, 9
+        qd = torch.from_numpy(p.q).cuda()
+        cells, codes = p.ctx().ivf_assign_device(torch.from_numpy(p.x).cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(cells.cpu().numpy(), p.cells) and np.array_equal(codes.cpu().numpy(), p.codes), (d, cells)
+        got_i, got_d = p.ctx().ivf_search(qd, k, w)
+        want_i, want_d = p.ctx(ivf_coarse_kernel=1).ivf_search(qd, k, w)
+        torch.cuda.synchronize()
+        assert torch.equal(got_i, want_i) and torch.equal(got_d, want_d), (d, cells)
+        if not shift:
+            p.check(got_i.cpu().numpy(), got_d.cpu().numpy(), k, w, what="ivf d%d" % d)
 
 
 def test_ivf_heavy_duplicates_and_query_batches():
