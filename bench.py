@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # Each figure carries the hash of the kernel sources it was measured on (kernel_source_hash below); a run on other
 # sources prints traffic: null.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", "lds16", "lds-resident"): (483.6e6, "73a148c36790066c"),       # profiles/cfg2_forest_lds_resident.md
-    ("cfg2", "reduce", "register-context"): (9.344e9, "73a148c36790066c"),  # profiles/cfg2_forest_register_context.md
-    ("cfg4", "lds16", "lds-resident"): (3.042e9, "73a148c36790066c"),       # profiles/cfg4_forest_lds_resident.md
+    ("cfg2", "lds16", "lds-resident"): (483.5e6, "60978b94dfcd4c35"),       # profiles/cfg2_forest_lds_resident.md
+    ("cfg2", "reduce", "register-context"): (9.343e9, "60978b94dfcd4c35"),  # profiles/cfg2_forest_register_context.md
+    ("cfg4", "lds16", "lds-resident"): (3.110e9, "60978b94dfcd4c35"),       # profiles/cfg4_forest_lds_resident.md
 }
 # LDS read bandwidth of the chip: 256 compute units x 256 bytes per clock x 2.4 GHz (a conflict-free 16-byte-per-lane
 # wave read, 1 KiB, occupies the LDS pipe for 4 clocks: SQ_LDS_IDX_ACTIVE minus SQ_LDS_BANK_CONFLICT per read)
@@ -483,8 +483,10 @@ def ivf_leg(etf, torch, args, steps, warmup):
     # near the w-th by the sequential float32 rule.  Scan: 4-byte table entries gathered from LDS, M per entry.
     if "ivf_coarse" in kernels:
         ach = 2.0 * cfg.Q * cells_n * cfg.d / (kernels["ivf_coarse"]["ms_per_step"] / 1e3) / 1e12
-        leg["roofline_coarse"] = {"bound": "mfma", "kernel": "ivf_coarse (k_ivf_coarse_mfma and k_ivf_probe_mfma together)",
-                                  "dtype": "f32", "achieved": ach, "peak": 157.3, "unit": "TFLOP/s", "frac": ach / 157.3, "traffic": None}
+        meas = CEILINGS.get("mfma_f32_32x32x2_TFLOPs")
+        leg["roofline_coarse"] = {"bound": "mfma", "kernel": "ivf_coarse (k_ivf_coarse_tc and k_ivf_probe_mfma together)",
+                                  "dtype": "f32", "achieved": ach, "peak": 157.3, "unit": "TFLOP/s", "frac": ach / 157.3, "traffic": None,
+                                  "frac_of_measured_peak": ach / meas if meas else None}
     if not args.no_cpu:
         from oracle import ivfadc
         from parity import assert_topk_matches
@@ -573,6 +575,17 @@ def measure_ceilings(etf, torch, stream):
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / 3
         out["%s_Tlane_instr_per_s" % kname] = nops / 1e12 / (ms / 1e3)
+    # the float32 matrix instruction of the table, encoder and coarse-quantiser kernels, nothing but that instruction
+    nflop = 2048 * 4 * 32 * 4096 * 2048
+    c.probe_bandwidth(etf.ETF_PROBE_MFMA_F32, b, b, nflop)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(3):
+        c.probe_bandwidth(etf.ETF_PROBE_MFMA_F32, b, b, nflop)
+    e1.record()
+    torch.cuda.synchronize()
+    out["mfma_f32_32x32x2_TFLOPs"] = nflop / 1e12 / (e0.elapsed_time(e1) / 3 / 1e3)
     log("ceilings (GB/s; T lane instructions/s): " + ", ".join("%s %.4g" % kv for kv in out.items()))
     return out
 

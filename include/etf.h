@@ -139,6 +139,8 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     matrix cores as ||c||^2 - 2 q.c; the cells that can be among the w nearest, given a bound on
  *                     the rounding of that form and of the float32 rule, are then evaluated by the rule, which
  *                     decides.  1: the rule for every cell.  Both give the same probed cells, distances and order
+ *   "ivf_coarse_tile" 1 (default): that contraction stages its operands through LDS where d is a multiple of 32 and the
+ *                     rows are 16-byte aligned; 0: every lane streams its own operand rows (the kernel for other d)
  *   "ivf_probe_cap"   most cells per query evaluated by the rule before the whole row is (0 = default: max(1024, 2 w);
  *                     never below w), "ivf_probe_slack" a factor >= 1 on that rounding bound (default 1): both for tests
  *   "ivf_bound_factor"  etf_ivf_search, scan of the probed lists: the bound on the k-th distance is taken from the
@@ -495,10 +497,13 @@ int etf_profile_read(etf_ctx *ctx, double *ms, int64_t *launches);
  *   ETF_PROBE_VALU_F32 / _ADD3 / _PK16  no memory traffic either: the rate at which the vector units issue one kind of
  *                    instruction (v_add_f32; v_add3_u32; v_pk_add_u16) from eight independent chains per lane; here
  *                    `bytes` is the number of lane instructions to execute in total, rounded down to a multiple of
- *                    2048 x 256 x 64 (a unused; b receives one word per workgroup, 8 KiB) */
+ *                    2048 x 256 x 64 (a unused; b receives one word per workgroup, 8 KiB)
+ *   ETF_PROBE_MFMA_F32  the rate of the float32 matrix instruction (v_mfma_f32_32x32x2_f32, eight independent
+ *                    accumulator blocks per wave, four waves per workgroup); `bytes` is the number of floating-point
+ *                    operations to execute in total, rounded down to a multiple of 2048 x 4 x 32 x 4096 (a unused; b as above) */
 enum {
     ETF_PROBE_READ = 0, ETF_PROBE_WRITE = 1, ETF_PROBE_COPY = 2, ETF_PROBE_ROWS = 3, ETF_PROBE_LDS = 4, ETF_PROBE_LDS_SCATTER = 5,
-    ETF_PROBE_VALU_F32 = 6, ETF_PROBE_VALU_ADD3 = 7, ETF_PROBE_VALU_PK16 = 8
+    ETF_PROBE_VALU_F32 = 6, ETF_PROBE_VALU_ADD3 = 7, ETF_PROBE_VALU_PK16 = 8, ETF_PROBE_MFMA_F32 = 9
 };
 int etf_probe_bandwidth(etf_ctx *ctx, int kind, void *a, void *b, int64_t bytes);
 

@@ -30,7 +30,7 @@ EXPORTS = [
     "etf_ivf_device_bytes", "etf_ivf_upload", "etf_ivf_workspace_bytes", "etf_ivf_search",
 ]
 ETF_PROBE_READ, ETF_PROBE_WRITE, ETF_PROBE_COPY, ETF_PROBE_ROWS, ETF_PROBE_LDS, ETF_PROBE_LDS_SCATTER = 0, 1, 2, 3, 4, 5
-ETF_PROBE_VALU_F32, ETF_PROBE_VALU_ADD3, ETF_PROBE_VALU_PK16 = 6, 7, 8
+ETF_PROBE_VALU_F32, ETF_PROBE_VALU_ADD3, ETF_PROBE_VALU_PK16, ETF_PROBE_MFMA_F32 = 6, 7, 8, 9
 KERNEL_CLASSES = ["lut", "level", "leaf", "flat", "reduce", "tau", "select", "exact", "sample", "lds", "encode",
                   "ivf_coarse", "ivf_scan", "lds16"]
 

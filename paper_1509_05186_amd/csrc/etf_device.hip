@@ -862,6 +862,12 @@ extern "C" int etf_probe_bandwidth(etf_ctx *ctx, int kind, void *a, void *b, int
             else hipLaunchKernelGGL(k_probe_valu<2>, dim3(2048), dim3(256), 0, st, iters, (uint32_t *)b);
             break;
         }
+        case ETF_PROBE_MFMA_F32: {
+            // `bytes` counts floating-point operations here: 2048 workgroups x 4 waves x 32 instructions of 4096 per iteration
+            const int iters = (int)std::max<int64_t>(1, std::min<int64_t>(bytes / ((int64_t)2048 * 4 * 32 * 4096), 1 << 24));
+            hipLaunchKernelGGL(k_probe_mfma, dim3(2048), dim3(256), 0, st, iters, (uint32_t *)b);
+            break;
+        }
         default: return fail(ctx, ETF_EINVAL, "unknown probe kind %d", kind);
     }
     LAUNCH_CHECK(ctx, "k_probe");

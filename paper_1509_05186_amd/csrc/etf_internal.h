@@ -129,6 +129,7 @@ struct Options {
     int64_t lds_filter = 2; // main pass of the LDS-resident search: 0 float32 sums, 1 / 2 candidate filter in 32 / 16-bit fixed point
     int64_t encode_kernel = 0; // device encoder: 0 distance evaluations on the matrix cores, near-ties by the float32 rule; 1 the rule for every codeword
     int64_t ivf_coarse_kernel = 0; // IVFADC distances to the centroids: 0 matrix cores + the float32 rule near the w-th, 1 the rule for every cell
+    int64_t ivf_coarse_tile = 1;   // the matrix-core distances with operands staged through LDS where the shape allows (1) or always streamed per lane (0)
     int64_t ivf_bound_factor = 16;  // IVFADC scan: the bound comes from the nearest lists that hold this many times k entries (0: from all lists)
     int64_t ivf_probe_slack = 1;   // factor on the error bound of the matrix-core distances (tests: more cells, or all, go through the rule)
     int64_t ivf_probe_cap = 0;     // cells the probe selection recomputes by the rule before it redoes the whole row (0: chosen by the library)

@@ -220,19 +220,156 @@ __global__ __launch_bounds__(256) void k_ivf_coarse_mfma(const float *__restrict
                 for (int cb = 0; cb < 4; ++cb) acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rb][i], b[cb][i], acc[rb][cb], 0, 0, 0);
     };
     float a0[2][8], b0[4][8], a1[2][8], b1[4][8];
-    load_block(0, a0, b0);
-    for (int j0 = 0; j0 < d; j0 += 32) {
-        const bool second = j0 + 16 < d;
-        if (second) load_block(j0 + 16, a1, b1);
-        multiply(a0, b0);
-        if (second) {
-            if (j0 + 32 < d) load_block(j0 + 32, a0, b0);
+    if (wide && (d & 15) == 0) {
+        // whole blocks of 16 dimensions, 16-byte loads: no branch between a load and its use, so that the wait before a
+        // block's instructions covers that block's loads only and the next block's stay in flight.  Rows beyond the
+        // batch or the cells read row 0 (their results are not stored); the block after the last is the last again.
+        auto fetch = [&](int j0, float (&a)[2][8], float (&b)[4][8]) {
+            const int j = min(j0, d - 16) + 8 * half;
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                const float4 lo = *reinterpret_cast<const float4 *>(qrow[rb] + j), hi = *reinterpret_cast<const float4 *>(qrow[rb] + j + 4);
+                a[rb][0] = lo.x; a[rb][1] = lo.y; a[rb][2] = lo.z; a[rb][3] = lo.w;
+                a[rb][4] = hi.x; a[rb][5] = hi.y; a[rb][6] = hi.z; a[rb][7] = hi.w;
+            }
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb) {
+                const float4 lo = *reinterpret_cast<const float4 *>(crow[cb] + j), hi = *reinterpret_cast<const float4 *>(crow[cb] + j + 4);
+                b[cb][0] = lo.x; b[cb][1] = lo.y; b[cb][2] = lo.z; b[cb][3] = lo.w;
+                b[cb][4] = hi.x; b[cb][5] = hi.y; b[cb][6] = hi.z; b[cb][7] = hi.w;
+            }
+        };
+        const int nblk = d >> 4;
+        fetch(0, a0, b0);
+        int blk = 0;
+        for (; blk + 2 <= nblk; blk += 2) {
+            fetch(16 * (blk + 1), a1, b1);
+            multiply(a0, b0);
+            fetch(16 * (blk + 2), a0, b0);
             multiply(a1, b1);
+        }
+        if (blk < nblk) multiply(a0, b0);
+    } else {
+        load_block(0, a0, b0);
+        for (int j0 = 0; j0 < d; j0 += 32) {
+            const bool second = j0 + 16 < d;
+            if (second) load_block(j0 + 16, a1, b1);
+            multiply(a0, b0);
+            if (second) {
+                if (j0 + 32 < d) load_block(j0 + 32, a0, b0);
+                multiply(a1, b1);
+            }
         }
     }
     float cn[4];
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb) cn[cb] = clive[cb] ? cnorm[cbase + cb * 32 + col] : 0.f;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t q = qb + rb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+            if (q >= n) continue;
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb)
+                if (clive[cb]) approx[q * Kc + cbase + cb * 32 + col] = fmaf(-2.f, acc[rb][cb][r], cn[cb]);
+        }
+}
+
+// ------------------------------------------------------------------------------------------------
+// The same matrix with both operands staged through LDS, for d a multiple of 32 and 16-byte aligned rows: a workgroup
+// owns 128 queries x 256 cells and walks the dimensions 32 at a time; the 384 rows of a stage (one 128-byte line each)
+// are fetched with coalesced 16-byte loads, eight threads per row, held in registers while the previous stage is
+// multiplied, and written to LDS rows of 36 floats (16 lanes reading one column of 16 rows hit 16 different bank
+// quartets).  Same tiles per wave, same operand order and so the same values as k_ivf_coarse_mfma, whose per-lane
+// loads of 16 bytes from 64 different lines keep the matrix cores waiting for the cache's tag look-ups.
+//     grid (ceil(nq / 128), ceil(Kc / 256)), block 256, static LDS 384 * 36 * 4 bytes.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 2) void k_ivf_coarse_tc(const float *__restrict__ x, int64_t n, int d, const float *__restrict__ cent,
+                                                       const float *__restrict__ cnorm, int Kc, float *__restrict__ approx)
+{
+    constexpr int RS = 36;  // floats per LDS row
+    __shared__ __attribute__((aligned(16))) float tile[384 * RS];
+    const int t = threadIdx.x, lane = t & 63, w = uniform(t >> 6);
+    const int col = lane & 31, half = lane >> 5;
+    const int64_t q0 = (int64_t)blockIdx.x * 128;
+    const int c0 = (int)blockIdx.y * 256;
+    // the rows this thread fetches: float4 number t + 256 i of the stage, i = 0..11, is piece t & 7 of row (t >> 3) +
+    // 32 i; rows 0..127 (i < 4) are queries, 128..383 cells; rows beyond the batch or the cells read the last one (their
+    // results are not stored)
+    const int r0 = t >> 3, c4 = t & 7;
+    // 32-bit offsets from the workgroup's first query and first cell (two workgroups share a compute unit if a wave
+    // stays within 256 registers, 128 of them accumulators)
+    const float *xq = x + q0 * d, *cc = cent + (int64_t)c0 * d;
+    const int qrows = (int)min<int64_t>(128, n - q0), crows = min(256, Kc - c0);
+    uint32_t off[12];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) off[i] = (uint32_t)(min(r0 + 32 * i, qrows - 1) * d + 4 * c4);
+#pragma unroll
+    for (int i = 4; i < 12; ++i) off[i] = (uint32_t)(min(r0 + 32 * (i - 4), crows - 1) * d + 4 * c4);
+    const int dst0 = r0 * RS + 4 * c4;  // LDS position of piece i: dst0 + 32 i RS
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
+    const int arow = (w & 1) * 64, brow = 128 + (w >> 1) * 128;  // first LDS row of this wave's queries and cells
+    typedef float vf4 __attribute__((ext_vector_type(4)));  // (an array of HIP's float4 structs stays in scratch memory here)
+    vf4 st[12];
+#pragma unroll
+    for (int i = 0; i < 12; ++i) st[i] = *reinterpret_cast<const vf4 *>((i < 4 ? xq : cc) + off[i]);
+    for (int j0 = 0; j0 < d; j0 += 32) {
+        __syncthreads();  // the previous stage has been read
+#pragma unroll
+        for (int i = 0; i < 12; ++i) *reinterpret_cast<vf4 *>(tile + dst0 + 32 * i * RS) = st[i];
+        __syncthreads();
+        {
+            const int jn = min(j0 + 32, d - 32);  // after the last stage: the last again (not used)
+#pragma unroll
+            for (int i = 0; i < 12; ++i) st[i] = *reinterpret_cast<const vf4 *>((i < 4 ? xq : cc) + off[i] + jn);
+        }
+        // the loads above are issued here, ahead of the stage's matrix instructions (left alone, the compiler sinks
+        // them below those to save registers, and every stage then waits for the memory)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            const int j = 16 * blk + 8 * half;
+            float a[2][8], b[4][8];
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                const float *p = tile + (arow + rb * 32 + col) * RS + j;
+                const float4 lo = *reinterpret_cast<const float4 *>(p), hi = *reinterpret_cast<const float4 *>(p + 4);
+                a[rb][0] = lo.x; a[rb][1] = lo.y; a[rb][2] = lo.z; a[rb][3] = lo.w;
+                a[rb][4] = hi.x; a[rb][5] = hi.y; a[rb][6] = hi.z; a[rb][7] = hi.w;
+            }
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb) {
+                const float *p = tile + (brow + cb * 32 + col) * RS + j;
+                const float4 lo = *reinterpret_cast<const float4 *>(p), hi = *reinterpret_cast<const float4 *>(p + 4);
+                b[cb][0] = lo.x; b[cb][1] = lo.y; b[cb][2] = lo.z; b[cb][3] = lo.w;
+                b[cb][4] = hi.x; b[cb][5] = hi.y; b[cb][6] = hi.z; b[cb][7] = hi.w;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb)
+                        acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rb][i], b[cb][i], acc[rb][cb], 0, 0, 0);
+        }
+    }
+    const int64_t qb = q0 + (w & 1) * 64;
+    const int cbase = c0 + (w >> 1) * 128;
+    float cn[4];
+    bool clive[4];
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+        clive[cb] = cbase + cb * 32 + col < Kc;
+        cn[cb] = clive[cb] ? cnorm[cbase + cb * 32 + col] : 0.f;
+    }
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -1031,6 +1168,18 @@ extern "C" int etf_ivf_upload(etf_ctx *ctx, void *dev_buf, int64_t bytes)
 }
 
 // ---- database side on the device: cell, residual, residual encoding ------------------------------------------
+// the approximate distance matrix of n vectors: operands through LDS where the rows allow it
+static void ivf_launch_coarse(etf_ctx *ctx, const float *x, int64_t n, const float *cent, const float *cnorm, float *matrix)
+{
+    const int d = ctx->d, Kc = ctx->ivf.Kc;
+    const dim3 grid((unsigned)((n + 127) / 128), (unsigned)((Kc + 255) / 256));
+    hipStream_t st = (hipStream_t)ctx->stream;
+    if ((d & 31) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0 && (reinterpret_cast<uintptr_t>(cent) & 15) == 0 && ctx->opt.ivf_coarse_tile != 0)
+        hipLaunchKernelGGL(k_ivf_coarse_tc, grid, dim3(256), 0, st, x, n, d, cent, cnorm, Kc, matrix);
+    else
+        hipLaunchKernelGGL(k_ivf_coarse_mfma, grid, dim3(256), 0, st, x, n, d, cent, cnorm, Kc, matrix);
+}
+
 // vectors per batch of the coarse assignment: their distance matrix stays within 256 MiB
 static int64_t ivf_assign_batch(const etf_ctx *ctx, int64_t n)
 {
@@ -1090,8 +1239,7 @@ extern "C" int etf_ivf_assign_device(etf_ctx *ctx, const float *x, int64_t n, in
             if (rc) return rc;
             for (int64_t v0 = 0; v0 < n; v0 += nb) {
                 const int64_t nv = std::min<int64_t>(nb, n - v0);
-                hipLaunchKernelGGL(k_ivf_coarse_mfma, dim3((unsigned)((nv + 127) / 128), (unsigned)((iv.Kc + 255) / 256)), dim3(256), 0, st,
-                                   x + v0 * d, nv, d, cent, cnorm, iv.Kc, matrix);
+                ivf_launch_coarse(ctx, x + v0 * d, nv, cent, cnorm, matrix);
                 LAUNCH_CHECK(ctx, "k_ivf_coarse_mfma");
                 hipLaunchKernelGGL(k_ivf_probe_mfma, dim3((unsigned)nv), dim3(256), lds_probe, st, x + v0 * d, d, cent, iv.cmax,
                                    (float)ctx->opt.ivf_probe_slack, matrix, iv.Kc, 1, cap, cells_out + v0, nearest);
@@ -1168,8 +1316,7 @@ extern "C" int etf_ivf_search(etf_ctx *ctx, const float *queries, int64_t Q, int
             ProfScope prof(ctx, ETF_K_IVF_COARSE);
             if (ctx->opt.ivf_coarse_kernel == 0) {
                 const float *cnorm = reinterpret_cast<const float *>(img + iv.o_cnorm);
-                hipLaunchKernelGGL(k_ivf_coarse_mfma, dim3((unsigned)((nq + 127) / 128), (unsigned)((iv.Kc + 255) / 256)), dim3(256), 0, st, qb, nq, d,
-                                   cent, cnorm, iv.Kc, coarse);
+                ivf_launch_coarse(ctx, qb, nq, cent, cnorm, coarse);
                 LAUNCH_CHECK(ctx, "k_ivf_coarse_mfma");
                 hipLaunchKernelGGL(k_ivf_probe_mfma, dim3((unsigned)nq), dim3(256), lds_probe, st, qb, d, cent, iv.cmax, (float)ctx->opt.ivf_probe_slack, coarse, iv.Kc, w, P.cap, probes,
                                    pbase);

@@ -2663,6 +2663,31 @@ __global__ __launch_bounds__(256) void k_probe_valu(int iters, uint32_t *__restr
     if (threadIdx.x == (x & 255u)) out[blockIdx.x] = x;
 }
 
+// The rate of the float32 matrix instruction the lookup-table, encoder and coarse-quantiser kernels are built on:
+// v_mfma_f32_32x32x2_f32 on eight independent accumulator blocks per wave, operands in registers, nothing else.
+// grid (2048), block 256; 32 instructions (131072 floating-point operations) per wave and iteration.
+__global__ __launch_bounds__(256) void k_probe_mfma(int iters, uint32_t *__restrict__ out)
+{
+    floatx16 acc[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[u][r] = 0.f;
+    const float a = (float)(threadIdx.x & 7) * 0.125f, b = (float)(blockIdx.x & 3) * 0.25f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int rep = 0; rep < 4; ++rep)
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[u], 0, 0, 0);
+    }
+    float x = 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) x += acc[u][r];
+    if (threadIdx.x == ((uint32_t)x & 255u)) out[blockIdx.x] = __float_as_uint(x);
+}
+
 // Plain: lane l of a wave reads piece l of a 1 KiB row (conflict-free: every quarter wave covers all 64 banks).
 // SCATTER: the four lanes of a group read the four pieces of one 64-byte row and the sixteen groups of a wave read
 // rows picked by a hash: the access pattern of the table lookups, bank conflicts as they fall.

@@ -146,7 +146,8 @@ def test_ivf_probe_selection_variants_agree(prob, w, k):
     torch.cuda.synchronize()
     prob.check(want_i.cpu().numpy(), want_d.cpu().numpy(), k, w, what="ivf rule w%d" % w)
     for opts in ({}, {"ivf_probe_slack": 3000}, {"ivf_probe_slack": 10 ** 9}, {"ivf_probe_cap": 1},
-                 {"ivf_bound_factor": 0}, {"ivf_bound_factor": 1}, {"ivf_bound_factor": 1, "cand_cap": 128}):
+                 {"ivf_bound_factor": 0}, {"ivf_bound_factor": 1}, {"ivf_bound_factor": 1, "cand_cap": 128},
+                 {"ivf_coarse_tile": 0}):
         c = prob.ctx(**opts)
         got_i, got_d = c.ivf_search(qd, k, w)
         torch.cuda.synchronize()

@@ -40,12 +40,12 @@ def test_streaming_probes_move_the_right_bytes(ctx, nbytes):
 
 
 def test_on_chip_probes_run_and_touch_nothing_else(ctx):
-    say("probe kernels: LDS reads and vector issue")
+    say("probe kernels: LDS reads, vector issue, matrix instruction")
     a = torch.full((1 << 16,), 5, dtype=torch.uint8, device="cuda")
     b = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
     for kind, amount in ((etf.ETF_PROBE_LDS, 1 << 30), (etf.ETF_PROBE_LDS_SCATTER, 1 << 30),
                          (etf.ETF_PROBE_VALU_F32, 2048 * 256 * 64 * 8), (etf.ETF_PROBE_VALU_ADD3, 2048 * 256 * 64 * 8),
-                         (etf.ETF_PROBE_VALU_PK16, 2048 * 256 * 64 * 8)):
+                         (etf.ETF_PROBE_VALU_PK16, 2048 * 256 * 64 * 8), (etf.ETF_PROBE_MFMA_F32, 2048 * 4 * 32 * 4096 * 4)):
         ctx.probe_bandwidth(kind, a, b, amount)
         torch.cuda.synchronize()
         assert int(a.min()) == 5 and int(a.max()) == 5                    # `a` is not used by these kinds
