@@ -128,12 +128,23 @@ def make_inputs(cfg, etf, torch, scale_n=None, scale_q=None):
     enc.pq_encode_device(torch.zeros((64, cfg.d), dtype=torch.float32, device="cuda"), ws=ws)
     enc.profile_read()
     done = 0
-    for chunk in gm.chunks_threaded(N, SEED_DATABASE, 12):
-        got = enc.pq_encode_device(torch.from_numpy(chunk).cuda(), ws=ws)
-        codes[done:done + len(chunk)] = got.cpu().numpy()
-        done += len(chunk)
-        if (done >> 17) % 64 == 0:
+    held, held_n = [], 0   # generated chunks already on the device, encoded a million vectors per call
+    def flush():
+        nonlocal done, held, held_n
+        if not held:
+            return
+        got = enc.pq_encode_device(held[0] if len(held) == 1 else torch.cat(held), ws=ws)
+        codes[done:done + held_n] = got.cpu().numpy()
+        done += held_n
+        held, held_n = [], 0
+        if (done >> 20) % 8 == 0:
             log("  generated + encoded %d of %d vectors, %.0f s" % (done, N, time.time() - t0))
+    for chunk in gm.chunks_threaded(N, SEED_DATABASE, 12):
+        held.append(torch.from_numpy(chunk).cuda())
+        held_n += len(chunk)
+        if held_n >= (1 << 20):
+            flush()
+    flush()
     ms, cnt = enc.profile_read()["encode"]
     # plain kernel: subtract, multiply, add per (vector, codeword, dimension), three unfused vector instructions;
     # matrix-core kernel: the contraction x.c, two operations per (vector, codeword, dimension)
