@@ -362,15 +362,19 @@ int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_
 {
     dim3 grid((unsigned)tiles, (unsigned)ctx->M);
     // few tiles: one wave per workgroup for the matrix-core kernel, so that the launch spreads over more compute units
-    const bool narrow = tiles * ctx->M < 128;
-    const dim3 mgrid((unsigned)tiles, (unsigned)ctx->M, narrow ? (unsigned)((ctx->K + 63) / 64) : 1u), mblock(narrow ? 64 : 256);
+    const bool narrow = tiles * ctx->M < 512;
+    const dim3 mgrid((unsigned)tiles, (unsigned)ctx->M, narrow ? (unsigned)((ctx->K + 31) / 32) : 1u), mblock(narrow ? 64 : 256);
     ChunkOrder ord;
     for (int j = 0; j < ETF_MAX_M; ++j) ord.src[j] = (uint8_t)((size_t)j < ctx->idx.order.size() ? ctx->idx.order[j] : j);
     ProfScope prof(ctx, ETF_K_LUT);
     if (ctx->opt.metric == 1 && ctx->opt.lut_kernel == 0) {
         const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
-        hipLaunchKernelGGL(k_lut_mfma<true>, mgrid, mblock, 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
-                           cb, nullptr, nullptr, nullptr, ctx->dsp, lutT, lut_public, ord);
+        if (narrow)
+            hipLaunchKernelGGL((k_lut_mfma<true, 1>), mgrid, mblock, 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
+                               cb, nullptr, nullptr, nullptr, ctx->dsp, lutT, lut_public, ord);
+        else
+            hipLaunchKernelGGL((k_lut_mfma<true, 2>), mgrid, mblock, 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
+                               cb, nullptr, nullptr, nullptr, ctx->dsp, lutT, lut_public, ord);
         LAUNCH_CHECK(ctx, "k_lut_mfma");
     } else if (ctx->opt.metric == 1) {
         const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
@@ -382,8 +386,12 @@ int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_
         const float *cbn = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_norm);
         const float *cbm = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.cb_mean);
         const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);
-        hipLaunchKernelGGL(k_lut_mfma<false>, mgrid, mblock, 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
-                           cb, cbc, cbn, cbm, ctx->dsp, lutT, lut_public, ord);
+        if (narrow)
+            hipLaunchKernelGGL((k_lut_mfma<false, 1>), mgrid, mblock, 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
+                               cb, cbc, cbn, cbm, ctx->dsp, lutT, lut_public, ord);
+        else
+            hipLaunchKernelGGL((k_lut_mfma<false, 2>), mgrid, mblock, 0, (hipStream_t)ctx->stream, queries, Q, q0, ctx->d, ctx->M, ctx->K,
+                               cb, cbc, cbn, cbm, ctx->dsp, lutT, lut_public, ord);
         LAUNCH_CHECK(ctx, "k_lut_mfma");
     } else {
         const float *cb = reinterpret_cast<const float *>(ctx->dev_base + ctx->lay.codebooks);

@@ -1338,7 +1338,7 @@ extern "C" int etf_ivf_search(etf_ctx *ctx, const float *queries, int64_t Q, int
             // tables of scalar products <q_m, codeword>, one set per query, shared by all cells
             ProfScope prof(ctx, ETF_K_LUT);
             const int64_t tiles = (nq + QT - 1) / QT;
-            hipLaunchKernelGGL(k_lut_mfma<true>, dim3((unsigned)tiles, (unsigned)M), dim3(256), 0, st, qb, nq, (int64_t)0, d, M, K, cbd, nullptr,
+            hipLaunchKernelGGL((k_lut_mfma<true, 2>), dim3((unsigned)tiles, (unsigned)M), dim3(256), 0, st, qb, nq, (int64_t)0, d, M, K, cbd, nullptr,
                                nullptr, nullptr, ctx->dsp, nullptr, lut, ord);
             LAUNCH_CHECK(ctx, "k_lut_mfma");
         }

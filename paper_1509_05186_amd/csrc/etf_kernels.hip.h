@@ -166,19 +166,20 @@ __global__ __launch_bounds__(64) void k_lut_shift_sum(const float *__restrict__ 
 //     between K codewords and 64 queries over ds dimensions:  ||q' - c'||^2 = ||q'||^2 + ||c'||^2 - 2 c'.q'
 //     with both sides shifted by the group's mean codeword.  The cross term is the dense contraction:
 //     v_mfma_f32_32x32x2_f32 with A = codewords (32 rows) and B = queries (32 columns), float32 in,
-//     float32 accumulate.  A wave owns 64 codewords x 64 queries = 2 x 2 accumulator blocks.
+//     float32 accumulate.  A wave owns 32 RB codewords x 64 queries = RB x 2 accumulator blocks.
 //     Operand layout of the instruction (lane l): A[i = l % 32][k = l / 32], B[k = l / 32][j = l % 32];
 //     accumulator register r of lane l is D[i = 8 * (r / 4) + 4 * (l / 32) + r % 4][j = l % 32], so for a
 //     fixed r the lanes 0..31 hold 32 consecutive queries of one codeword: a 128-byte piece of a table row.
 //     Entries that are small against the norms are recomputed exactly (see below).
 //     IP: the tables hold the scalar products q_m . c themselves: the contraction on the unshifted vectors.
-//     grid (tiles, M), block 256 (wave w: codewords 64w .. 64w+63); or, for batches of few tiles, grid (tiles, M,
-//     ceil(K / 64)), block 64 (one wave per workgroup, its 64 codewords given by blockIdx.z): four times the
-//     workgroups, each with a quarter of the entries to recompute.
+//     RB = 2: grid (tiles, M), block 256 (wave w: codewords 64w .. 64w+63).  RB = 1, for batches of few tiles: grid
+//     (tiles, M, ceil(K / 32)), block 64 (one wave per workgroup, its 32 codewords given by blockIdx.z): eight times
+//     the workgroups, each with an eighth of the entries to sweep and to recompute (a lone wave issues the sweeps'
+//     instructions one after the other: they, not the matrix instructions, are its time).
 // ------------------------------------------------------------------------------------------------
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-template <bool IP>
+template <bool IP, int RB>
 __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ queries, int64_t Q, int64_t q0, int d, int M,
                                                   int K, const float *__restrict__ cb, const float *__restrict__ cbc,
                                                   const float *__restrict__ cbnorm, const float *__restrict__ cbmean,
@@ -189,7 +190,7 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
     const int lane = threadIdx.x & 63, w = uniform(blockDim.x == 64 ? (int)blockIdx.z : (int)(threadIdx.x >> 6));
     const int ds = d / M;
     const int col = lane & 31, half = lane >> 5;
-    const int kbase = w * 64;
+    const int kbase = w * 32 * RB;
     // B operand: the two queries this lane feeds (columns col and col + 32 of the tile)
     const float *qrow[2];
     bool qlive[2];
@@ -200,18 +201,18 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
         qrow[cb] = queries + (qlive[cb] ? q : 0) * d + (int64_t)ms * ds;
     }
     // A operand: the two codewords this lane feeds (rows col and col + 32 of the wave's 64)
-    const float *crow[2];
-    bool clive[2];
+    const float *crow[RB];
+    bool clive[RB];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
+    for (int rb = 0; rb < RB; ++rb) {
         const int k = kbase + rb * 32 + col;
         clive[rb] = k < K;
         crow[rb] = IP ? cb + ((int64_t)ms * K + (clive[rb] ? k : 0)) * ds : cbc + ((int64_t)ms * K + (clive[rb] ? k : 0)) * dsp;
     }
     const float *mean = IP ? nullptr : cbmean + (int64_t)ms * ds;
-    floatx16 acc[2][2];
+    floatx16 acc[RB][2];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
@@ -236,9 +237,9 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
     };
     for (int j0 = 0; j0 < ds; j0 += 16) {
         const int j = j0 + 8 * half;
-        float a[2][8], b[2][8], mu[8];
+        float a[RB][8], b[2][8], mu[8];
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) load8(crow[rb], clive[rb], j, arow, a[rb]);
+        for (int rb = 0; rb < RB; ++rb) load8(crow[rb], clive[rb], j, arow, a[rb]);
         if (!IP) load8(mean, true, j, ds, mu);
 #pragma unroll
         for (int cb2 = 0; cb2 < 2; ++cb2) {
@@ -252,7 +253,7 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
 #pragma unroll
         for (int i = 0; i < 8; ++i)
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
+            for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                 for (int cb2 = 0; cb2 < 2; ++cb2)
                     acc[rb][cb2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rb][i], b[cb2][i], acc[rb][cb2], 0, 0, 0);
@@ -276,21 +277,28 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
     // them (ballots, no memory), then one atomic reserves the wave's stretch of the queue and the second sweep hands
     // out the slots in order (an atomic with return per value was a chain of 64 LDS round trips: 20 us for a
     // workgroup of one wave).
-    auto value = [&](int rb, int r, int cb, int k, float &nn) -> float {
-        nn = qq[cb] + (IP ? 0.f : s_cc[k]);
+    // (the norms of this lane's codewords once, in registers: a read inside the sweeps below is an LDS round trip per
+    // value, and a workgroup of one wave has nothing else to run meanwhile)
+    float ccv[RB][16];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ccv[rb][r] = IP ? 0.f : s_cc[min(kbase + rb * 32 + 8 * (r / 4) + 4 * half + (r % 4), K - 1)];
+    auto value = [&](int rb, int r, int cb, float &nn) -> float {
+        nn = qq[cb] + ccv[rb][r];
         return IP ? acc[rb][cb][r] : nn - 2.f * acc[rb][cb][r];
     };
     int wave_small = 0;
     if (!IP) {
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int k = kbase + rb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
 #pragma unroll
                 for (int cb = 0; cb < 2; ++cb) {
                     float nn;
-                    const float v = value(rb, r, cb, min(k, K - 1), nn);
+                    const float v = value(rb, r, cb, nn);
                     wave_small += __popcll(__ballot(k < K && v < 0.25f * nn));
                 }
             }
@@ -300,15 +308,19 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
         if (lane == 0) slot = atomicAdd(&nfix, wave_small);
         slot = __builtin_amdgcn_readfirstlane(slot);
     }
+    // this lane's entries of the transposed tables: row kbase + 4 half of the (tile, group), column col; every entry
+    // of the sweep is a constant number of rows and columns further
+    float *trow = lutT ? lutT + (((int64_t)tile * M + m) * K + kbase + 4 * half) * QT + col : nullptr;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int k = kbase + rb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+            const int krel = rb * 32 + 8 * (r / 4) + (r % 4);
+            const int k = kbase + 4 * half + krel;
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) {
                 float nn;
-                const float v = value(rb, r, cb, min(k, K - 1), nn);
+                const float v = value(rb, r, cb, nn);
                 const int ql = cb * 32 + col;
                 const bool small = !IP && k < K && v < 0.25f * nn;   // scalar products: the contraction is the result
                 const uint64_t smask = __ballot(small);
@@ -317,7 +329,7 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
                         (uint16_t)((ql << 8) | k);
                 slot += __popcll(smask);
                 if (!small && k < K) {
-                    if (lutT) lutT[(((int64_t)tile * M + m) * K + k) * QT + ql] = v;
+                    if (lutT) trow[krel * QT + cb * 32] = v;
                     const int64_t q = q0 + (int64_t)tile * QT + ql;
                     if (lut_public && q < Q) lut_public[(q * M + ms) * K + k] = v;
                 }
@@ -1313,6 +1325,7 @@ __global__ __launch_bounds__(1024) void k_lds(const uint32_t *__restrict__ rec, 
     const int w = uniform(threadIdx.x >> 6), nw = blockDim.x >> 6;
     static_assert(!FX || MODE == OUT_FILTER, "the fixed-point form is a candidate filter");
     static_assert(!TERM || (MODE == OUT_FILTER && !FX), "TERM selects the filter pass with a leaf payload; the other modes test o.term");
+    if (MODE == OUT_ALLPAIRS && (int64_t)tile * QT + sub * Qs >= o.nq) return;  // a sub-tile past the last query: nothing to write
     if (FILTER) wcount[w][lane] = 0u;
     stage_lines<G, FX>(lds, lutT, tile, sub, M, K, KP, FX ? o.tau : nullptr);
     const int lg = lane / LPI, lq = lane % LPI;
