@@ -135,6 +135,8 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     where the smallest is not clearly below the second smallest (by twice a bound on the
  *                     rounding of either form) the float32 rule is evaluated for all K codewords.  1: the float32
  *                     rule for every codeword (needs d/M <= 128).  Both return the same codes, bit for bit
+ *   "encode_wide"     1 (default): groups of more than 64 dimensions with aligned rows take the matrix-core kernel
+ *                     that stages both operands through LDS; 0: the general one (operands streamed per lane)
  *   "ivf_coarse_kernel"  etf_ivf_search, distances between queries and centroids.  0 (default): all of them on the
  *                     matrix cores as ||c||^2 - 2 q.c; the cells that can be among the w nearest, given a bound on
  *                     the rounding of that form and of the float32 rule, are then evaluated by the rule, which

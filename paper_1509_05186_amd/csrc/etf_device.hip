@@ -1066,6 +1066,14 @@ extern "C" int etf_pq_encode_device(etf_ctx *ctx, const float *x, int64_t n, uin
             LAUNCH_CHECK(ctx, "k_encode_tc");
             return ETF_OK;
         }
+        if (aligned && ds > 64 && K <= 256 && (int64_t)127 * d < ((int64_t)1 << 31) && ctx->opt.encode_wide != 0) {
+            // wide groups: both operands through LDS
+            float *cc2 = reinterpret_cast<float *>((char *)ws + ((ctx->codebooks.size() * sizeof(float) + 255) & ~(size_t)255));
+            hipLaunchKernelGGL(k_encode_norms, dim3((unsigned)M), dim3(256), 0, st, cb, ds, K, M, cc2);
+            hipLaunchKernelGGL(k_encode_wide, dim3((unsigned)((n + 127) / 128), (unsigned)M), dim3(256), 0, st, x, n, d, ds, K, M, cb, cc2, codes_out);
+            LAUNCH_CHECK(ctx, "k_encode_wide");
+            return ETF_OK;
+        }
         hipLaunchKernelGGL(k_encode_mfma, dim3((unsigned)((n + 255) / 256), (unsigned)M), dim3(256), 0, st, x, n, d, ds, K, M, cb, codes_out);
         LAUNCH_CHECK(ctx, "k_encode_mfma");
         return ETF_OK;

@@ -127,6 +127,7 @@ struct Options {
     int64_t lds_blocks = 0; // workgroups per sub-tile of queries in the LDS-resident search kernel (0: chosen by the library)
     int64_t metric = 0;     // 0: squared Euclidean distance (smallest first), 1: scalar product (largest first)
     int64_t lds_filter = 2; // main pass of the LDS-resident search: 0 float32 sums, 1 / 2 candidate filter in 32 / 16-bit fixed point
+    int64_t encode_wide = 1;   // matrix-core encoder for groups of more than 64 dimensions: operands through LDS (1) or streamed per lane (0)
     int64_t encode_kernel = 0; // device encoder: 0 distance evaluations on the matrix cores, near-ties by the float32 rule; 1 the rule for every codeword
     int64_t ivf_coarse_kernel = 0; // IVFADC distances to the centroids: 0 matrix cores + the float32 rule near the w-th, 1 the rule for every cell
     int64_t ivf_coarse_tile = 1;   // the matrix-core distances with operands staged through LDS where the shape allows (1) or always streamed per lane (0)

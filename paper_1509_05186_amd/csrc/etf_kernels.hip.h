@@ -654,6 +654,74 @@ __global__ __launch_bounds__(256) void k_rotate(const float *__restrict__ x, int
     }
 }
 
+// One term of the float32 rule: s + (x - c)^2 with every operation rounded on its own.
+__device__ __forceinline__ float encode_rule_term(float s, float x, float c)
+{
+#pragma clang fp contract(off)
+    const float t = x - c;
+    const float pr = t * t;
+    return s + pr;
+}
+
+// The float32 rule for one vector, evaluated by a whole wave (the near-ties of the matrix-core encoders): lane l takes
+// codewords l, l + 64, l + 128, l + 192 (K <= 256), each distance the sum of its terms in dimension order; returns
+// the codeword with the smallest (distance, index) in every lane.  xv: the vector's values of the group, cbm: the
+// group's codewords [K][ds].  rows16: ds is a multiple of 4 and both rows are 16-byte aligned; then the four sums
+// advance together on 16-byte loads, two steps in flight (one value per load and iteration is a memory latency per
+// dimension and codeword: 0.1 ms for a single vector with 120 dimensions per group).
+__device__ __forceinline__ int encode_rule_wave(const float *__restrict__ xv, const float *__restrict__ cbm, int ds, int K, int lane,
+                                                bool rows16)
+{
+    float bestd = 3.402823466e+38f;
+    int best = 0x7FFFFFFF;
+    if (rows16) {
+        float sacc[4] = {0.f, 0.f, 0.f, 0.f};
+        const float *c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) c[u] = cbm + (int64_t)min(lane + 64 * u, K - 1) * ds;
+#pragma unroll 2
+        for (int j = 0; j < ds; j += 4) {
+            const float4 xq = *reinterpret_cast<const float4 *>(xv + j);
+            float4 cq[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) cq[u] = *reinterpret_cast<const float4 *>(c[u] + j);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                sacc[u] = encode_rule_term(sacc[u], xq.x, cq[u].x);
+                sacc[u] = encode_rule_term(sacc[u], xq.y, cq[u].y);
+                sacc[u] = encode_rule_term(sacc[u], xq.z, cq[u].z);
+                sacc[u] = encode_rule_term(sacc[u], xq.w, cq[u].w);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (lane + 64 * u < K && sacc[u] < bestd) {  // ascending index inside a lane: the first minimum stays
+                bestd = sacc[u];
+                best = lane + 64 * u;
+            }
+    } else {
+        for (int k = lane; k < K; k += 64) {
+            const float *c = cbm + (int64_t)k * ds;
+            float sacc = 0.f;
+            for (int j = 0; j < ds; ++j) sacc = encode_rule_term(sacc, xv[j], c[j]);
+            if (sacc < bestd) {  // ascending k inside a lane: the first minimum stays
+                bestd = sacc;
+                best = k;
+            }
+        }
+    }
+#pragma unroll
+    for (int dlt = 32; dlt > 0; dlt >>= 1) {
+        const float od = __shfl_xor(bestd, dlt);
+        const int ob = __shfl_xor(best, dlt);
+        if (od < bestd || (od == bestd && ob < best)) {
+            bestd = od;
+            best = ob;
+        }
+    }
+    return best;
+}
+
 // ------------------------------------------------------------------------------------------------
 // The same assignment with the distance evaluations on the matrix cores (the O(dKN) term of the paper's "Efficient
 //     Encoding Tree Construction").  For every (vector, group) the 256 values  ||c||^2 - 2 x.c  come from the dense
@@ -801,34 +869,7 @@ __global__ __launch_bounds__(256, 2) void k_encode_mfma(const float *__restrict_
             const int src = __ffsll((unsigned long long)todo) - 1;
             todo &= todo - 1;
             const int64_t v = v0 + c2 * 32 + src;
-            const float *xv = x + v * d + (int64_t)m * ds;
-            float bestd = 3.402823466e+38f;
-            int best = 0x7FFFFFFF;
-            for (int k = lane; k < K; k += 64) {
-                const float *c = cbm + (int64_t)k * ds;
-                float sacc = 0.f;
-                {
-#pragma clang fp contract(off)
-                    for (int j = 0; j < ds; ++j) {
-                        const float t = xv[j] - c[j];
-                        const float pr = t * t;
-                        sacc = sacc + pr;
-                    }
-                }
-                if (sacc < bestd) {  // ascending k inside a lane: the first minimum stays
-                    bestd = sacc;
-                    best = k;
-                }
-            }
-#pragma unroll
-            for (int dlt = 32; dlt > 0; dlt >>= 1) {
-                const float od = __shfl_xor(bestd, dlt);
-                const int ob = __shfl_xor(best, dlt);
-                if (od < bestd || (od == bestd && ob < best)) {
-                    bestd = od;
-                    best = ob;
-                }
-            }
+            const int best = encode_rule_wave(x + v * d + (int64_t)m * ds, cbm, ds, K, lane, wide);
             if (lane == 0) codes[v * M + m] = (uint8_t)best;
         }
     }
@@ -976,34 +1017,179 @@ __global__ __launch_bounds__(256, 2) void k_encode_tc(const float *__restrict__ 
             const int src = __ffsll((unsigned long long)todo) - 1;
             todo &= todo - 1;
             const int64_t vh = v0 + src;
-            const float *xv = x + vh * d + (int64_t)m * ds;
-            float bestd = 3.402823466e+38f;
-            int best = 0x7FFFFFFF;
-            for (int k = lane; k < K; k += 64) {
-                const float *c = cbm + (int64_t)k * ds;
-                float sacc = 0.f;
-                {
-#pragma clang fp contract(off)
-                    for (int j = 0; j < ds; ++j) {
-                        const float t = xv[j] - c[j];
-                        const float pr = t * t;
-                        sacc = sacc + pr;
-                    }
-                }
-                if (sacc < bestd) {  // ascending k inside a lane: the first minimum stays
-                    bestd = sacc;
-                    best = k;
-                }
+            const int best = encode_rule_wave(x + vh * d + (int64_t)m * ds, cbm, ds, K, lane, true);
+            if (lane == 0) codes[vh * M + m] = (uint8_t)best;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// The matrix-core assignment for wide groups (more than 64 dimensions per group, aligned rows): both operands go
+//     through LDS 32 dimensions at a time, fetched with coalesced 16-byte loads (eight threads per row) into registers
+//     while the previous stage is multiplied, as in k_ivf_coarse_tc; k_encode_mfma's per-lane loads of 16 bytes from
+//     64 different rows keep the matrix cores waiting for the cache's tag look-ups.  A workgroup owns 128 vectors
+//     and the group's 256 codewords: wave (wk, wv) multiplies codewords 128 wk .. by vectors 64 wv .. (A = codewords,
+//     4 x 2 accumulator blocks that start at -||c||^2 / 2), keeps largest, second largest and index per vector as
+//     k_encode_tc does, the two waves of a vector set merge through LDS, and near-ties go through the float32 rule.
+//     The codes are k_encode's, bit for bit.
+//     cc2: from k_encode_norms.  grid (ceil(n / 128), M), block 256; ds and d multiples of 4, K <= 256.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 2) void k_encode_wide(const float *__restrict__ x, int64_t n, int d, int ds, int K, int M,
+                                                        const float *__restrict__ cb, const float *__restrict__ cc2, uint8_t *__restrict__ codes)
+{
+    constexpr int RS = 36;  // floats per LDS row: 16 lanes reading one column of 16 rows hit 16 different bank quartets
+    __shared__ __attribute__((aligned(16))) float tile[384 * RS];  // rows 0..127: vectors, 128..383: codewords
+    __shared__ __align__(16) float s_cc2[256];
+    __shared__ float s_v1[128], s_v2[128];
+    __shared__ int s_k1[128];
+    typedef float vf4 __attribute__((ext_vector_type(4)));
+    const int t = threadIdx.x, lane = t & 63, w = uniform(t >> 6);
+    const int col = lane & 31, half = lane >> 5;
+    const int wk = w & 1, wv = w >> 1;
+    const int m = blockIdx.y;
+    const int64_t v0 = (int64_t)blockIdx.x * 128;
+    const float *cbm = cb + (int64_t)m * K * ds;
+    const float *xw = x + v0 * d + (int64_t)m * ds;
+    const int vrows = (int)min<int64_t>(128, n - v0);
+    s_cc2[t] = cc2[m * 256 + t];
+    // float4 number t + 256 i of a stage, i = 0..11, is piece t & 7 of row (t >> 3) + 32 i; rows beyond the data or
+    // the codebook read the last one (their results are not used: -3e38 in cc2, no code written)
+    const int r0 = t >> 3, c4 = t & 7;
+    uint32_t off[12];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) off[i] = (uint32_t)(min(r0 + 32 * i, vrows - 1) * d + 4 * c4);
+#pragma unroll
+    for (int i = 4; i < 12; ++i) off[i] = (uint32_t)(min(r0 + 32 * (i - 4), K - 1) * ds + 4 * c4);
+    const int dst0 = r0 * RS + 4 * c4;
+    vf4 st[12];
+    auto fetch = [&](int j0) {
+        const bool in = j0 + 4 * c4 + 4 <= ds;  // the group's last stage may be shorter: zeros beyond it
+#pragma unroll
+        for (int i = 0; i < 12; ++i) {
+            vf4 v = 0.f;
+            if (in) v = *reinterpret_cast<const vf4 *>((i < 4 ? xw : cbm) + off[i] + j0);
+            st[i] = v;
+        }
+    };
+    fetch(0);
+    __syncthreads();  // s_cc2
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float4 c = *reinterpret_cast<const float4 *>(&s_cc2[wk * 128 + rb * 32 + 8 * g + 4 * half]);
+#pragma unroll
+            for (int cbk = 0; cbk < 2; ++cbk) {
+                acc[rb][cbk][4 * g + 0] = c.x;
+                acc[rb][cbk][4 * g + 1] = c.y;
+                acc[rb][cbk][4 * g + 2] = c.z;
+                acc[rb][cbk][4 * g + 3] = c.w;
+            }
+        }
+    const int arow = 128 + wk * 128, brow = wv * 64;  // first LDS row of this wave's codewords and vectors
+    float xx[2] = {0.f, 0.f};
+    for (int j0 = 0; j0 < ds; j0 += 32) {
+        __syncthreads();  // the previous stage has been read
+#pragma unroll
+        for (int i = 0; i < 12; ++i) *reinterpret_cast<vf4 *>(tile + dst0 + 32 * i * RS) = st[i];
+        __syncthreads();
+        fetch(min(j0 + 32, ((ds - 1) >> 5) << 5));  // after the last stage: the last again (not used)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);  // the loads stay ahead of the stage's matrix instructions
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            const int j = 16 * blk + 8 * half;
+            float a[4][8], b[2][8];
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) {
+                const float *p = tile + (arow + rb * 32 + col) * RS + j;
+                const float4 lo = *reinterpret_cast<const float4 *>(p), hi = *reinterpret_cast<const float4 *>(p + 4);
+                a[rb][0] = lo.x; a[rb][1] = lo.y; a[rb][2] = lo.z; a[rb][3] = lo.w;
+                a[rb][4] = hi.x; a[rb][5] = hi.y; a[rb][6] = hi.z; a[rb][7] = hi.w;
             }
 #pragma unroll
-            for (int dlt = 32; dlt > 0; dlt >>= 1) {
-                const float od = __shfl_xor(bestd, dlt);
-                const int ob = __shfl_xor(best, dlt);
-                if (od < bestd || (od == bestd && ob < best)) {
-                    bestd = od;
-                    best = ob;
-                }
+            for (int cbk = 0; cbk < 2; ++cbk) {
+                const float *p = tile + (brow + cbk * 32 + col) * RS + j;
+                const float4 lo = *reinterpret_cast<const float4 *>(p), hi = *reinterpret_cast<const float4 *>(p + 4);
+                b[cbk][0] = lo.x; b[cbk][1] = lo.y; b[cbk][2] = lo.z; b[cbk][3] = lo.w;
+                b[cbk][4] = hi.x; b[cbk][5] = hi.y; b[cbk][6] = hi.z; b[cbk][7] = hi.w;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) xx[cbk] = fmaf(b[cbk][i], b[cbk][i], xx[cbk]);
             }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                    for (int cbk = 0; cbk < 2; ++cbk)
+                        acc[rb][cbk] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rb][i], b[cbk][i], acc[rb][cbk], 0, 0, 0);
+        }
+    }
+    // accumulator register r of block rb, lane l: codeword 128 wk + 32 rb + 8 (r / 4) + 4 (l / 32) + r % 4, vector
+    // 64 wv + 32 cbk + l % 32.  Largest and second largest value and the first index of the largest, per vector.
+    const float inf = __uint_as_float(0x7F800000u);
+    float v1[2], v2[2];
+    int k1[2];
+#pragma unroll
+    for (int cbk = 0; cbk < 2; ++cbk) {
+        float a1 = -3.0e38f, a2 = -3.0e38f;
+        int kk = 0;
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float val = acc[rb][cbk][r];
+                kk = val > a1 ? rb * 32 + 8 * (r / 4) + (r % 4) : kk;
+                a2 = __builtin_amdgcn_fmed3f(val, a1, a2);
+                a1 = __builtin_amdgcn_fmed3f(val, a1, inf);
+            }
+        kk += wk * 128 + 4 * half;
+        // the two halves of the wave saw different codewords of the same vectors
+        const float o1 = __shfl_xor(a1, 32), o2 = __shfl_xor(a2, 32);
+        const int ok = __shfl_xor(kk, 32);
+        xx[cbk] += __shfl_xor(xx[cbk], 32);
+        const float lo = fminf(a1, o1);
+        if (o1 > a1 || (o1 == a1 && ok < kk)) kk = ok;
+        v1[cbk] = fmaxf(a1, o1);
+        v2[cbk] = fmaxf(lo, fmaxf(a2, o2));
+        k1[cbk] = kk;
+    }
+    // the wave with the upper 128 codewords hands its result to the one with the lower 128
+    if (wk == 1 && half == 0) {
+#pragma unroll
+        for (int cbk = 0; cbk < 2; ++cbk) {
+            const int vi = wv * 64 + cbk * 32 + col;
+            s_v1[vi] = v1[cbk];
+            s_v2[vi] = v2[cbk];
+            s_k1[vi] = k1[cbk];
+        }
+    }
+    __syncthreads();
+    if (wk == 1) return;
+    const float ccmax = cc2[M * 256 + m];
+    const float eps = 8.f * (float)(ds + 2) * 5.9604645e-8f;
+#pragma unroll
+    for (int cbk = 0; cbk < 2; ++cbk) {
+        const int vi = wv * 64 + cbk * 32 + col;
+        const float o1 = s_v1[vi], o2 = s_v2[vi];
+        const int ok = s_k1[vi];
+        const float lo = fminf(v1[cbk], o1);
+        int kk = k1[cbk];
+        if (o1 > v1[cbk] || (o1 == v1[cbk] && ok < kk)) kk = ok;
+        const float b1 = fmaxf(v1[cbk], o1), b2 = fmaxf(lo, fmaxf(v2[cbk], o2));
+        const int64_t v = v0 + vi;
+        const bool live = v < n;
+        const float E = eps * (xx[cbk] + ccmax);
+        const bool hard = live && !(b1 - b2 > E);
+        if (half == 0 && live && !hard) codes[v * M + m] = (uint8_t)kk;
+        // near-ties: the float32 rule itself for every codeword, the wave's lanes taking codewords lane, lane + 64, ...
+        uint64_t todo = __ballot(hard && half == 0);
+        while (todo != 0ull) {
+            const int src = __ffsll((unsigned long long)todo) - 1;
+            todo &= todo - 1;
+            const int64_t vh = v0 + wv * 64 + cbk * 32 + src;
+            const int best = encode_rule_wave(x + vh * d + (int64_t)m * ds, cbm, ds, K, lane, true);
             if (lane == 0) codes[vh * M + m] = (uint8_t)best;
         }
     }

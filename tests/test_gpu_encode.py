@@ -30,7 +30,8 @@ def make(d, M, K, ntrain, seed, iters=3, kernel=0):
 
 @pytest.mark.parametrize("d,M,K,n", [
     (128, 8, 256, 5000),     # 16 dimensions per group (the benchmark's shape), several blocks and a ragged tail
-    (240, 2, 256, 700),      # 120 dimensions per group: padded to 128, codewords staged in LDS in one piece
+    (240, 2, 256, 700),      # 120 dimensions per group: wide groups, both operands through LDS, last stage short
+    (200, 2, 100, 300),      # 100 per group, 100 codewords: rows of the codeword tile beyond the codebook
     (96, 8, 256, 1025),      # 12 per group: padded to 16
     (119, 7, 50, 513),       # 17 per group (odd: unaligned rows), K not a power of two
     (128, 16, 256, 300),     # 8 per group, 16 groups
@@ -53,6 +54,10 @@ def test_encode_device_wide_groups_on_the_matrix_cores():
     got = c.pq_encode_device(torch.from_numpy(x).cuda())
     torch.cuda.synchronize()
     assert np.array_equal(got.cpu().numpy(), oracle.encode_f32(x, cb))
+    c.set_option("encode_wide", 0)                       # the general matrix-core kernel on the same input
+    again = c.pq_encode_device(torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(again, got)
     c.set_option("encode_kernel", 1)
     with pytest.raises(etf.EtfError):
         c.pq_encode_device(torch.from_numpy(x).cuda())
