@@ -1197,7 +1197,8 @@ static int search_impl(etf_ctx *ctx, const float *queries, int64_t Q, int k, int
                 if (rc) return rc;
                 {
                     ProfScope prof(ctx, ETF_K_TAU);
-                    hipLaunchKernelGGL(k_tau, dim3((unsigned)tiles), dim3(1024), 0, st, o.gmin, P.ngroups, k, 4, nq, tau);
+                    // three digits: the bound is the top of a bucket 2^-16 of its value wide (the fourth pass bought nothing)
+                    hipLaunchKernelGGL(k_tau, dim3((unsigned)tiles), dim3(1024), 0, st, o.gmin, P.ngroups, k, 3, nq, tau);
                 }
                 LAUNCH_CHECK(ctx, "k_tau");
             } else {

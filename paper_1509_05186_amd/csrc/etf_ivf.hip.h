@@ -520,7 +520,9 @@ __global__ __launch_bounds__(256) void k_ivf_probe_mfma(const float *__restrict_
     lo = fminf(fminf(s_lo[0], s_lo[1]), fminf(s_lo[2], s_lo[3]));
     hi = fmaxf(fmaxf(s_hi[0], s_hi[1]), fmaxf(s_hi[2], s_hi[3]));
     const float span = hi - lo;
-    const bool usable = span >= 0.f && span < 3.0e38f;  // false with a NaN or an infinity in the row
+    // false with a NaN or an infinity in the row, and for data so small that products of two values are subnormal (the
+    // matrix instruction flushes those to zero, which the bound E does not cover): the rule then takes the whole row
+    const bool usable = span >= 0.f && span < 3.0e38f && S * S > 1.0e-30f;
     const float scale = span > 0.f ? (float)NB / span : 0.f;
     auto bin_of = [&](float v) { return min(NB - 1, (int)((v - lo) * scale)); };
     if (usable) ivf_for_row(row, Kc, [&](int, float v) { atomicAdd(&hist[bin_of(v)], 1u); });

@@ -858,7 +858,8 @@ __global__ __launch_bounds__(256, 2) void k_encode_mfma(const float *__restrict_
 #pragma unroll
     for (int c2 = 0; c2 < 2; ++c2) {
         const float E = eps * (xx[c2] + ccmax);
-        hard[c2] = xlive[c2] && !(v2[c2] - v1[c2] > 2.f * E);
+        // (values so small that products are subnormal: the matrix instruction flushes them, E does not cover that)
+        hard[c2] = xlive[c2] && (!(v2[c2] - v1[c2] > 2.f * E) || xx[c2] + ccmax < 1.0e-30f);
         if (half == 0 && xlive[c2] && !hard[c2]) codes[(v0 + c2 * 32 + col) * M + m] = (uint8_t)k1[c2];
     }
     // near-ties: the float32 rule itself for every codeword, the wave's lanes taking codewords lane, lane + 64, ...
@@ -1009,7 +1010,8 @@ __global__ __launch_bounds__(256, 2) void k_encode_tc(const float *__restrict__ 
             v2 = fmaxf(lo, fmaxf(v2, o2));
         }
         const float E = eps * (xx + ccmax);
-        const bool hard = live && !(v1 - v2 > E);
+        // (values so small that products are subnormal: the matrix instruction flushes them, E does not cover that)
+        const bool hard = live && (!(v1 - v2 > E) || xx + ccmax < 1.0e-30f);
         if (half == 0 && live && !hard) codes[v * M + m] = (uint8_t)k1;
         // near-ties: the float32 rule itself for every codeword, the wave's lanes taking codewords lane, lane + 64, ...
         uint64_t todo = __ballot(hard && half == 0);
@@ -1181,7 +1183,8 @@ __global__ __launch_bounds__(256, 2) void k_encode_wide(const float *__restrict_
         const int64_t v = v0 + vi;
         const bool live = v < n;
         const float E = eps * (xx[cbk] + ccmax);
-        const bool hard = live && !(b1 - b2 > E);
+        // (values so small that products are subnormal: the matrix instruction flushes them, E does not cover that)
+        const bool hard = live && (!(b1 - b2 > E) || xx[cbk] + ccmax < 1.0e-30f);
         if (half == 0 && live && !hard) codes[v * M + m] = (uint8_t)kk;
         // near-ties: the float32 rule itself for every codeword, the wave's lanes taking codewords lane, lane + 64, ...
         uint64_t todo = __ballot(hard && half == 0);
