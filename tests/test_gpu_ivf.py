@@ -175,6 +175,38 @@ def test_ivf_probe_selection_odd_shapes():
             p.check(got_i.cpu().numpy(), got_d.cpu().numpy(), k, w, what="ivf d%d" % d)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_ivf_random_shapes(seed):
+    """Random shapes: the default path (matrix-core distances to the centroids, bound from the nearest lists) against the
+    float32 rule for every cell with the bound from all lists, bit for bit, and against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    M = int(rng.choice([2, 4, 8]))
+    ds = int(rng.choice([1, 2, 4, 5, 8, 16]))
+    d = M * ds
+    K = int(rng.choice([4, 16, 64, 256]))
+    cells = int(rng.choice([5, 33, 64, 257, 1000]))
+    N = int(rng.integers(cells, 40 * cells + 200))
+    Q = int(rng.choice([1, 7, 64, 129]))
+    w = int(rng.integers(1, min(cells, 40) + 1))
+    k = int(rng.integers(1, 120))
+    say("IVFADC random shape: d", d, "M", M, "K", K, "cells", cells, "N", N, "Q", Q, "w", w, "k", k)
+    p = IvfProblem(d=d, M=M, K=K, cells=cells, N=N, Q=Q, seed=500 + seed, comps=6)
+    qd = torch.from_numpy(p.q).cuda()
+    c = p.ctx()
+    cells_d, codes_d = c.ivf_assign_device(torch.from_numpy(p.x).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(cells_d.cpu().numpy(), p.cells) and np.array_equal(codes_d.cpu().numpy(), p.codes)
+    got_i, got_d = c.ivf_search(qd, k, w)
+    want_i, want_d = p.ctx(ivf_coarse_kernel=1, ivf_bound_factor=0).ivf_search(qd, k, w)
+    torch.cuda.synchronize()
+    assert torch.equal(got_i, want_i) and torch.equal(got_d, want_d)
+    # against the oracle's float64 distances where the three-term form keeps its relative accuracy: with very fine
+    # quantisers (many codewords for one or two dimensions) a stored vector can sit so close to a query that the
+    # terms cancel, which the interface documents
+    if K ** (1.0 / ds) <= 16:
+        p.check(got_i.cpu().numpy(), got_d.cpu().numpy(), k, w, what="ivf random %d" % seed)
+
+
 def test_ivf_heavy_duplicates_and_query_batches():
     say("IVFADC: few codewords (many equal entries, exact ties), queries in several workspace batches")
     p = IvfProblem(d=16, M=4, K=4, cells=64, N=9000, Q=200, seed=33, dup=3)
