@@ -133,7 +133,7 @@ __device__ __forceinline__ void ivf_probe_row(const float *row, int Kc, int w, u
     const int w2 = pow2_at_least(w);
     for (int i = w + threadIdx.x; i < w2; i += 256) pk[i] = ~0ull;
     __syncthreads();
-    bitonic_sort_u64(pk, w2);
+    sort_u64(pk, w2);
     for (int i = threadIdx.x; i < w; i += 256) {
         probes[i] = (int32_t)(pk[i] & 0xFFFFu);
         base[i] = __uint_as_float((uint32_t)(pk[i] >> 16));
@@ -582,7 +582,7 @@ __global__ __launch_bounds__(256) void k_ivf_probe_mfma(const float *__restrict_
         pk[i] = key;
     }
     __syncthreads();
-    bitonic_sort_u64(pk, n2);
+    sort_u64(pk, n2);
     for (int i = threadIdx.x; i < w; i += 256) {
         probes[q * w + i] = (int32_t)(pk[i] & 0xFFFFu);
         base[q * w + i] = __uint_as_float((uint32_t)(pk[i] >> 16));

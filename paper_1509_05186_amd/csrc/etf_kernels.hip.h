@@ -2284,6 +2284,58 @@ __device__ __forceinline__ void bitonic_sort_u64(uint64_t *a, int n)
         }
 }
 
+// The same for lists of at most 256 keys (the usual case of the selection kernels: about k candidates): one wave holds
+// H = 2 or 4 keys per lane (key e in lane e % 64, slot e / 64) and exchanges them by lane shuffles, or inside the lane
+// where the partner is one of its own: 28 or 36 steps without a barrier or an LDS round trip each; the block-wide
+// network above spends most of its time in those.  n: a power of two (a[0..n) holds the keys, padded with ~0 by the
+// caller); every thread of the workgroup calls it, after a barrier.
+template <int H>
+__device__ __forceinline__ void wave_sort_u64(uint64_t *a, int n)
+{
+    const int lane = threadIdx.x;
+    uint64_t x[H];
+#pragma unroll
+    for (int h = 0; h < H; ++h) x[h] = lane + 64 * h < n ? a[lane + 64 * h] : ~0ull;
+#pragma unroll
+    for (int k = 2; k <= 64 * H; k <<= 1)
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const int e = lane + 64 * h;
+                const bool keep_min = ((e & j) == 0) == ((e & k) == 0);  // lower index of an ascending pair, upper of a descending one
+                if (j >= 64) {  // the partner is the lane's own key in slot h ^ (j / 64): handle the pair once
+                    const int hp = h ^ (j >> 6);
+                    if (hp > h) {
+                        const uint64_t mn = x[h] < x[hp] ? x[h] : x[hp], mx = x[h] < x[hp] ? x[hp] : x[h];
+                        x[h] = keep_min ? mn : mx;
+                        x[hp] = keep_min ? mx : mn;
+                    }
+                } else {
+                    const uint64_t y = (uint64_t)__shfl_xor((unsigned long long)x[h], j);
+                    const uint64_t mn = x[h] < y ? x[h] : y, mx = x[h] < y ? y : x[h];
+                    x[h] = keep_min ? mn : mx;
+                }
+            }
+        }
+#pragma unroll
+    for (int h = 0; h < H; ++h)
+        if (lane + 64 * h < n) a[lane + 64 * h] = x[h];
+}
+
+__device__ __forceinline__ void sort_u64(uint64_t *a, int n)
+{
+    if (n > 256) {
+        bitonic_sort_u64(a, n);
+        return;
+    }
+    if (threadIdx.x < 64) {
+        if (n <= 128) wave_sort_u64<2>(a, n);
+        else wave_sort_u64<4>(a, n);
+    }
+    __syncthreads();
+}
+
 // in-place inclusive scan of v[0..n) (n <= 256 * ipt), 256 threads, `tmp` has 4 entries
 __device__ __forceinline__ void block_inclusive_scan(uint32_t *v, int n, uint32_t *tmp)
 {
@@ -2566,7 +2618,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     const int nk2 = pow2_at_least(nk);
     for (int i = nk + threadIdx.x; i < nk2; i += 256) kept[i] = ~0ull;
     __syncthreads();
-    bitonic_sort_u64(kept, nk2);
+    sort_u64(kept, nk2);
     // 3. how many vectors each kept encoding holds (never more than k matter)
     for (int i = threadIdx.x; i < nk; i += 256) {
         const uint32_t e = (uint32_t)kept[i];
@@ -2589,7 +2641,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
             const int nx2s = pow2_at_least((int)total);
             for (int i = (int)total + threadIdx.x; i < nx2s; i += 256) xkeys[i] = ~0ull;
             __syncthreads();
-            bitonic_sort_u64(xkeys, nx2s);
+            sort_u64(xkeys, nx2s);
             for (int i = threadIdx.x; i < k; i += 256) {
                 const bool have = i < (int)total;
                 a.out_ids[ql * k + i] = have ? (int32_t)(uint32_t)xkeys[i] : -1;
@@ -2639,7 +2691,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a)
     const int nx2 = pow2_at_least((int)xtotal);
     for (int i = (int)xtotal + threadIdx.x; i < nx2; i += 256) xkeys[i] = ~0ull;
     __syncthreads();
-    bitonic_sort_u64(xkeys, nx2);
+    sort_u64(xkeys, nx2);
     for (int i = threadIdx.x; i < k; i += 256) {
         a.out_ids[ql * k + i] = (int32_t)(uint32_t)xkeys[i];
         const float v = __uint_as_float((uint32_t)(xkeys[i] >> 32));
