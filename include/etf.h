@@ -118,6 +118,9 @@ const char *etf_last_error(const etf_ctx *ctx);
  *                     on vectors shifted by the group's mean codeword; entries below a quarter of
  *                     ||q'||^2 + ||c'||^2, where that form cancels, are recomputed as plain sums.
  *                     1: every entry as a plain float32 sum of (q - c)^2
+ *   "lut_narrow_below"  the matrix-core table kernel runs as workgroups of one wave and 32 codewords when the batch
+ *                     has fewer (tile of 64 queries, group) pairs than this (default: always), else as workgroups
+ *                     of four waves and 256 codewords; same tables either way
  *   "traversal"       how trees are walked.
  *                     0: depth-first leaf order with the distance context in registers, per-tree
  *                     result tables in device memory for trees 1 .. T-1;

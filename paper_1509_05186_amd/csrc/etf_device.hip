@@ -361,8 +361,9 @@ int set_lds(const etf_ctx *ctx, F kernel, size_t bytes)
 int launch_lut(etf_ctx *ctx, const float *queries, int64_t Q, int64_t q0, int64_t tiles, float *lutT, float *lut_public)
 {
     dim3 grid((unsigned)tiles, (unsigned)ctx->M);
-    // few tiles: one wave per workgroup for the matrix-core kernel, so that the launch spreads over more compute units
-    const bool narrow = tiles * ctx->M < 512;
+    // one wave per workgroup and 32 codewords per wave for the matrix-core kernel (option lut_narrow_below: always, by
+    // default): the launch spreads over more compute units and more waves hide each other's sweeps and stores
+    const bool narrow = tiles * ctx->M < ctx->opt.lut_narrow_below;
     const dim3 mgrid((unsigned)tiles, (unsigned)ctx->M, narrow ? (unsigned)((ctx->K + 31) / 32) : 1u), mblock(narrow ? 64 : 256);
     ChunkOrder ord;
     for (int j = 0; j < ETF_MAX_M; ++j) ord.src[j] = (uint8_t)((size_t)j < ctx->idx.order.size() ? ctx->idx.order[j] : j);

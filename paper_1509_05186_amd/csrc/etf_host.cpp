@@ -389,6 +389,9 @@ extern "C" int etf_set_option(etf_ctx *ctx, const char *name, int64_t value)
     } else if (n == "ivf_coarse_kernel") {
         if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "ivf_coarse_kernel must be 0 (matrix cores) or 1 (the float32 rule for every cell)");
         ctx->opt.ivf_coarse_kernel = value;
+    } else if (n == "lut_narrow_below") {
+        if (value < 0) return fail(ctx, ETF_EINVAL, "lut_narrow_below must be >= 0");
+        ctx->opt.lut_narrow_below = value;
     } else if (n == "encode_wide") {
         if (value != 0 && value != 1) return fail(ctx, ETF_EINVAL, "encode_wide is 0 or 1");
         ctx->opt.encode_wide = value;

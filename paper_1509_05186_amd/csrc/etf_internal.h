@@ -134,6 +134,7 @@ struct Options {
     int64_t ivf_bound_factor = 16;  // IVFADC scan: the bound comes from the nearest lists that hold this many times k entries (0: from all lists)
     int64_t ivf_probe_slack = 1;   // factor on the error bound of the matrix-core distances (tests: more cells, or all, go through the rule)
     int64_t ivf_probe_cap = 0;     // cells the probe selection recomputes by the rule before it redoes the whole row (0: chosen by the library)
+    int64_t lut_narrow_below = (int64_t)1 << 40; // (tile, group) pairs below which the table kernel runs as single-wave workgroups of 32 codewords (default: always)
     int64_t lut_kernel = 0; // 0: matrix cores (expanded form on centred vectors, small entries recomputed), 1: plain (a-b)^2 sums
 };
 

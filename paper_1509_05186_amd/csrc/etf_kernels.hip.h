@@ -172,10 +172,11 @@ __global__ __launch_bounds__(64) void k_lut_shift_sum(const float *__restrict__ 
 //     fixed r the lanes 0..31 hold 32 consecutive queries of one codeword: a 128-byte piece of a table row.
 //     Entries that are small against the norms are recomputed exactly (see below).
 //     IP: the tables hold the scalar products q_m . c themselves: the contraction on the unshifted vectors.
-//     RB = 2: grid (tiles, M), block 256 (wave w: codewords 64w .. 64w+63).  RB = 1, for batches of few tiles: grid
+//     RB = 2: grid (tiles, M), block 256 (wave w: codewords 64w .. 64w+63).  RB = 1 (the default launch): grid
 //     (tiles, M, ceil(K / 32)), block 64 (one wave per workgroup, its 32 codewords given by blockIdx.z): eight times
-//     the workgroups, each with an eighth of the entries to sweep and to recompute (a lone wave issues the sweeps'
-//     instructions one after the other: they, not the matrix instructions, are its time).
+//     the workgroups, each with an eighth of the entries to sweep and to recompute and a queue of 4 KB instead of
+//     32 KB (a wave issues the sweeps' instructions one after the other: they, not the matrix instructions, are its
+//     time; small batches need the workgroups to fill the chip, large ones the waves per SIMD to hide them).
 // ------------------------------------------------------------------------------------------------
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -264,7 +265,7 @@ __global__ __launch_bounds__(256) void k_lut_mfma(const float *__restrict__ quer
     // The expanded form loses about 2^-23 (||q'||^2 + ||c'||^2) absolutely, which is too much for an entry
     // that is small against the norms (a codeword next to the query).  Such entries are not written here but
     // queued, and recomputed below as plain sums of (q - c)^2 by all threads of the workgroup.
-    __shared__ uint16_t fix[QT * 256];
+    __shared__ uint16_t fix[RB == 2 ? QT * 256 : QT * 32];  // every entry of the workgroup could be small: 256 or 32 codewords x 64 queries
     __shared__ int nfix;
     // the codewords' norms from LDS: a global load per entry inside the loop below, each followed by a ballot and
     // a branch, is a chain of 32 memory latencies per lane

@@ -63,11 +63,14 @@ def qdev(p):
     return torch.from_numpy(p.q).cuda()
 
 
-@pytest.mark.parametrize("lut_kernel", [0, 1])   # 0: matrix cores (+ exact recomputation of small entries), 1: plain sums
-def test_lut_build(small, lut_kernel):
-    say("lut_build small, kernel", lut_kernel)
-    c = small.ctx(lut_kernel=lut_kernel)
+# 0: matrix cores (+ exact recomputation of small entries), as workgroups of one wave (default) or of four; 1: plain sums
+@pytest.mark.parametrize("lut_kernel,opts", [(0, {}), (0, {"lut_narrow_below": 1}), (1, {})])
+def test_lut_build(small, lut_kernel, opts):
+    say("lut_build small, kernel", lut_kernel, opts)
+    c = small.ctx(lut_kernel=lut_kernel, **opts)
     lut = c.lut_build(qdev(small)).cpu().numpy()
+    if opts:   # the two launch shapes of the matrix-core kernel give the same tables, bit for bit
+        assert np.array_equal(lut, small.ctx(lut_kernel=lut_kernel).lut_build(qdev(small)).cpu().numpy())
     ref = np.stack([oracle.lut(q, small.cb) for q in small.q])
     assert lut.min() >= 0.0
     assert_distances_close(lut.reshape(small.Q, -1), ref.reshape(small.Q, -1), "lut kernel %d" % lut_kernel)
