@@ -322,11 +322,11 @@ int64_t blocks_for(int64_t n, int64_t min_items_per_block, int64_t other_dims)
 // different times while the LDS cannot be handed on (measured: 6 us, the time of about 5000 items at M = 8).
 // The cost of a choice is rounds * (5000 + nitems / bx), in items.  Few large workgroups win unless they leave
 // CUs idle.
-int64_t lds_blocks_for(int64_t W, int64_t nitems, int64_t min_bx)
+int64_t lds_blocks_for(int64_t W, int64_t nitems, int64_t min_bx, int64_t least_items = 4096)
 {
     const int64_t cus = 256, stage_items = 5000;
     int64_t best = min_bx, best_cost = -1;
-    const int64_t max_bx = std::max(min_bx, (nitems + 4095) / 4096);  // a workgroup of 16 waves wants a few thousand items
+    const int64_t max_bx = std::max(min_bx, (nitems + least_items - 1) / least_items);  // a workgroup of 16 waves wants a few thousand items
     for (int64_t bx = min_bx; bx <= max_bx && bx < min_bx + 256; ++bx) {
         const int64_t rounds = (W * bx + cus - 1) / cus;
         const int64_t cost = rounds * (stage_items + (nitems + bx - 1) / bx);
@@ -704,7 +704,15 @@ int launch_lds(etf_ctx *ctx, const Plan &P, char *ws, const uint32_t *rec, int64
         bx = blocks_for(o.ngroups, 2 * 16 * IPS, tiles * G);
     } else {
         // item numbers inside a workgroup's share travel in 26 bits
-        bx = lds_blocks_for(tiles * G, nitems, (nitems >> 25) + 1);
+        if (MODE == OUT_ALLPAIRS) {
+            // sub-tiles past the last query end at once: only the live ones share the compute units, and a small
+            // batch should fill them in one round
+            const int64_t Qs = WAVE / G, live = std::min<int64_t>(tiles * G, (o.nq + Qs - 1) / Qs);
+            const bool few = live * ((nitems + 4095) / 4096) < 256;  // would leave compute units idle
+            bx = lds_blocks_for(std::max<int64_t>(live, 1), nitems, (nitems >> 25) + 1, few ? 1024 : 4096);
+        } else {
+            bx = lds_blocks_for(tiles * G, nitems, (nitems >> 25) + 1);
+        }
         if (ctx->opt.lds_blocks > 0) bx = std::max<int64_t>(ctx->opt.lds_blocks, (nitems >> 25) + 1);
         per_block = (int)((nitems + bx - 1) / bx);
     }
