@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # Each figure carries the hash of the kernel sources it was measured on (kernel_source_hash below); a run on other
 # sources prints traffic: null.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", "lds16", "lds-resident"): (483.5e6, "8835f15118df8c0e"),       # profiles/cfg2_forest_lds_resident.md
-    ("cfg2", "reduce", "register-context"): (9.344e9, "8835f15118df8c0e"),  # profiles/cfg2_forest_register_context.md
-    ("cfg4", "lds16", "lds-resident"): (3.023e9, "8835f15118df8c0e"),       # profiles/cfg4_forest_lds_resident.md
+    ("cfg2", "lds16", "lds-resident"): (482.4e6, "4195ef506fb42311"),       # profiles/cfg2_forest_lds_resident.md
+    ("cfg2", "reduce", "register-context"): (9.343e9, "4195ef506fb42311"),  # profiles/cfg2_forest_register_context.md
+    ("cfg4", "lds16", "lds-resident"): (3.054e9, "4195ef506fb42311"),       # profiles/cfg4_forest_lds_resident.md
 }
 # LDS read bandwidth of the chip: 256 compute units x 256 bytes per clock x 2.4 GHz (a conflict-free 16-byte-per-lane
 # wave read, 1 KiB, occupies the LDS pipe for 4 clocks: SQ_LDS_IDX_ACTIVE minus SQ_LDS_BANK_CONFLICT per read)
